@@ -1,0 +1,146 @@
+/*
+ * kda.h -- C ABI of libkda: Kimi Delta Attention (KDA) forward on one MI355X.
+ *
+ * KDA is the gated delta rule of the paper's Section 3, Eq. (1):
+ *
+ *     S_t = (I - beta_t k_t k_t^T) Diag(alpha_t) S_{t-1} + beta_t k_t v_t^T,
+ *     o_t = scale * S_t^T q_t,          alpha_t = exp(log_alpha_t) in (0,1]^dk
+ *
+ * with one dk x dv state S per (sequence, head).  Two entry points compute it:
+ * kda_chunk_fwd with the chunkwise WY / UT-transform algorithm of Section 3.1
+ * (prefill), kda_recurrent_step with one literal step of Eq. (1) (decode,
+ * Section 6.3 "Inference strategy").
+ *
+ * Conventions shared by every call
+ *   - All tensor pointers are DEVICE pointers to contiguous row-major arrays,
+ *     16-byte aligned.  The caller owns every buffer, including the workspace;
+ *     the library allocates nothing, frees nothing and keeps no state between
+ *     calls.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = default stream); no host synchronisation happens inside.
+ *   - Element offsets are 64-bit; tensors with more than 2^31 elements are fine.
+ *   - Errors: a non-zero kda_status is returned and kda_last_error() holds a
+ *     thread-local description.  For KDA_ERR_INVALID_ARG, KDA_ERR_UNSUPPORTED
+ *     and KDA_ERR_WORKSPACE nothing has been launched.  No exception crosses
+ *     the ABI.
+ *   - log_alpha must be finite and <= 0 (alpha = 0 is not representable);
+ *     alpha = 1 (log_alpha = 0) is allowed.  Values are never clamped.
+ */
+#ifndef KDA_H_
+#define KDA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KDA_OK = 0,
+    KDA_ERR_INVALID_ARG = 1,   /* null pointer, negative size, bad combination   */
+    KDA_ERR_UNSUPPORTED = 2,   /* head dim / chunk / dtype outside the built set */
+    KDA_ERR_WORKSPACE = 3,     /* workspace missing, misaligned or too small     */
+    KDA_ERR_LAUNCH = 4         /* the HIP runtime refused a launch               */
+} kda_status;
+
+typedef enum { KDA_F32 = 0, KDA_BF16 = 1 } kda_dtype;
+
+/*
+ * Problem description.
+ *   Fixed-length batch : cu_seqlens == NULL, num_seqs == batch, every batch row
+ *                        is one sequence of `seqlen` tokens.
+ *   Packed batch       : cu_seqlens != NULL, batch == 1, `seqlen` is the total
+ *                        number of packed tokens, sequence n owns tokens
+ *                        [cu_seqlens[n], cu_seqlens[n+1]).
+ * Supported: dk == dv in {64, 128}, chunk == 64, in_dtype KDA_F32 (any of the
+ * two head dims) or KDA_BF16 (head dim 128), out_dtype KDA_F32.
+ */
+typedef struct {
+    int32_t   batch;       /* B                                                  */
+    int64_t   seqlen;      /* T per batch row, or total packed tokens            */
+    int32_t   heads;       /* H                                                  */
+    int32_t   dk, dv;      /* key / value head dimension                         */
+    int32_t   chunk;       /* C of Section 3.1; must be 64                       */
+    int32_t   num_seqs;    /* N                                                  */
+    kda_dtype in_dtype;    /* q, k, v, log_alpha, beta all share it              */
+    kda_dtype out_dtype;   /* dtype of o                                         */
+    float     scale;       /* multiplies o; 1.0f gives Eq. (1), dk^-0.5 gives    */
+                           /* the App. C listing                                 */
+    int64_t   max_seqlen;  /* packed batches only: upper bound on the longest    */
+                           /* sequence, 0 = unknown (seqlen is assumed)          */
+} kda_dims;
+
+/*
+ * Workspace, in bytes, with which kda_chunk_fwd runs `dims` in a single
+ * segment (fastest).  kda_chunk_fwd also accepts any workspace of at least
+ * kda_chunk_fwd_min_workspace_size(dims) bytes and then walks the time axis
+ * in several segments, carrying the state between them.  Both return 0 for an
+ * unsupported or malformed `dims`, and for problems that need no workspace.
+ */
+size_t kda_chunk_fwd_workspace_size(const kda_dims *dims);
+size_t kda_chunk_fwd_min_workspace_size(const kda_dims *dims);
+
+/*
+ * Chunkwise prefill (Section 3.1: chunk expansion, WY representation, UT
+ * transform, chunk state update, inter/intra-chunk output; the decay products
+ * follow the reading gamma^{i->r} = exp(G^r - G^i), G the inclusive running
+ * sum of log_alpha inside a chunk).  Each sequence is cut into chunks of 64
+ * tokens starting at its own first token; a shorter last chunk is legal.
+ *
+ *   q, k       [B,T,H,dk]      in_dtype
+ *   v          [B,T,H,dv]      in_dtype
+ *   log_alpha  [B,T,H,dk]      in_dtype, natural log of the per-channel decay
+ *   beta       [B,T,H]         in_dtype
+ *   h0         [N,H,dk,dv]     fp32 initial states, or NULL for zeros
+ *   cu_seqlens [N+1]           int32, device memory, non-decreasing, starts at
+ *                              0, last entry <= T; or NULL (fixed length)
+ *   o          [B,T,H,dv]      out_dtype; rows of tokens owned by no sequence
+ *                              are left untouched
+ *   hT         [N,H,dk,dv]     fp32 final states (state after the last token of
+ *                              each sequence; equals h0 for an empty sequence),
+ *                              or NULL if not wanted.  May alias h0.
+ *   workspace                  device scratch, 256-byte aligned (may be NULL
+ *                              when the required size is 0)
+ * o must not alias any input.  Arithmetic: KDA_F32 inputs are processed in fp32
+ * throughout; KDA_BF16 inputs use fp16 matrix-core operands with fp32
+ * accumulation, fp32 cumulative decay and an fp32 state.
+ */
+kda_status kda_chunk_fwd(const kda_dims *dims,
+                         const void *q, const void *k, const void *v,
+                         const void *log_alpha, const void *beta,
+                         const float *h0, const int32_t *cu_seqlens,
+                         void *o, float *hT,
+                         void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
+
+/*
+ * One decode step of Eq. (1) for N = dims->num_seqs sequences (Section 6.3):
+ *     S <- Diag(alpha) S;  r = v - S^T k;  S <- S + beta k r^T;  o = scale S^T q.
+ * dims->seqlen must be 1 and dims->batch == dims->num_seqs.
+ *
+ *   q, k, log_alpha [N,H,dk]   in_dtype
+ *   v               [N,H,dv]   in_dtype
+ *   beta            [N,H]      in_dtype
+ *   S               [N,H,dk,dv] fp32, read and written IN PLACE
+ *   o               [N,H,dv]   out_dtype
+ * All arithmetic is fp32.  No workspace.
+ */
+kda_status kda_recurrent_step(const kda_dims *dims,
+                              const void *q, const void *k, const void *v,
+                              const void *log_alpha, const void *beta,
+                              float *S, void *o, void *hip_stream);
+
+/* Static description of a status code (never NULL). */
+const char *kda_status_string(kda_status status);
+
+/* Detail of the last error raised on the calling thread ("" if none). */
+const char *kda_last_error(void);
+
+/* Library version string, e.g. "kda-gfx950 0.1". */
+const char *kda_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KDA_H_ */

@@ -1,0 +1,167 @@
+// C ABI of libkda: argument validation, error strings and dispatch to the
+// kernels.  Nothing here touches tensor data; every step of the path runs in
+// the kernels of kda_step.hip, kda_chunk_f32.hip and kda_chunk_mfma.hip.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "kda_common.h"
+
+namespace kda {
+
+static thread_local char g_last_error[512] = "";
+
+kda_status fail(kda_status code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_last_error, sizeof(g_last_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// Kernel-side entry points (one per source file).
+kda_status recurrent_step_dispatch(const kda_dims *, const void *, const void *, const void *,
+                                   const void *, const void *, float *, void *, hipStream_t);
+kda_status chunk_f32_dispatch(const kda_dims *, const void *, const void *, const void *,
+                              const void *, const void *, const float *, const int32_t *, void *,
+                              float *, hipStream_t);
+kda_status chunk_mfma_dispatch(const kda_dims *, const void *, const void *, const void *,
+                               const void *, const void *, const float *, const int32_t *, void *,
+                               float *, void *, size_t, hipStream_t);
+size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal);
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks shared by both entry points.  Returns KDA_OK or the failure code.
+static kda_status check_dims(const kda_dims *d, bool packed)
+{
+    if (!d) return fail(KDA_ERR_INVALID_ARG, "dims is NULL");
+    if (d->batch < 0 || d->seqlen < 0 || d->heads < 0 || d->num_seqs < 0)
+        return fail(KDA_ERR_INVALID_ARG, "negative size (batch %d, seqlen %lld, heads %d, num_seqs %d)",
+                    d->batch, (long long)d->seqlen, d->heads, d->num_seqs);
+    if (d->in_dtype != KDA_F32 && d->in_dtype != KDA_BF16)
+        return fail(KDA_ERR_INVALID_ARG, "in_dtype %d is not a kda_dtype", (int)d->in_dtype);
+    if (d->out_dtype != KDA_F32)
+        return fail(KDA_ERR_UNSUPPORTED, "out_dtype must be KDA_F32");
+    if (!(d->dk == d->dv && (d->dk == 64 || d->dk == 128)))
+        return fail(KDA_ERR_UNSUPPORTED, "head dims must satisfy dk == dv in {64,128}, got %d x %d",
+                    d->dk, d->dv);
+    if (d->heads > 65535) return fail(KDA_ERR_UNSUPPORTED, "heads > 65535");
+    if (packed) {
+        if (d->batch != 1) return fail(KDA_ERR_INVALID_ARG, "packed batches need batch == 1");
+        if (d->seqlen > 0x7fffffffLL)
+            return fail(KDA_ERR_INVALID_ARG, "packed token count exceeds the int32 range of cu_seqlens");
+        if (d->max_seqlen < 0) return fail(KDA_ERR_INVALID_ARG, "max_seqlen < 0");
+    } else if (d->num_seqs != d->batch) {
+        return fail(KDA_ERR_INVALID_ARG, "fixed-length batches need num_seqs == batch");
+    }
+    if (!(d->scale == d->scale)) return fail(KDA_ERR_INVALID_ARG, "scale is NaN");
+    return KDA_OK;
+}
+
+static bool mfma_path(const kda_dims *d)
+{
+    if (d->in_dtype != KDA_BF16) return false;
+    const char *force = getenv("KDA_CHUNK_IMPL");       // debugging switch: "f32" forces the
+    if (force && strcmp(force, "f32") == 0) return false;  // fp32 kernel for bf16 inputs too
+    return true;
+}
+
+}  // namespace kda
+
+using namespace kda;
+
+extern "C" {
+
+const char *kda_version(void) { return "kda-gfx950 0.1"; }
+
+const char *kda_last_error(void) { return g_last_error; }
+
+const char *kda_status_string(kda_status s)
+{
+    switch (s) {
+    case KDA_OK: return "ok";
+    case KDA_ERR_INVALID_ARG: return "invalid argument";
+    case KDA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case KDA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KDA_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+size_t kda_chunk_fwd_workspace_size(const kda_dims *d)
+{
+    if (!d || d->chunk != kChunk) return 0;
+    const char saved0 = g_last_error[0];
+    if (check_dims(d, d->num_seqs != d->batch) != KDA_OK) { g_last_error[0] = saved0; return 0; }
+    if (!mfma_path(d)) return 0;
+    return chunk_mfma_workspace_size(d, false);
+}
+
+size_t kda_chunk_fwd_min_workspace_size(const kda_dims *d)
+{
+    if (!d || d->chunk != kChunk) return 0;
+    const char saved0 = g_last_error[0];
+    if (check_dims(d, d->num_seqs != d->batch) != KDA_OK) { g_last_error[0] = saved0; return 0; }
+    if (!mfma_path(d)) return 0;
+    return chunk_mfma_workspace_size(d, true);
+}
+
+kda_status kda_chunk_fwd(const kda_dims *d, const void *q, const void *k, const void *v,
+                         const void *log_alpha, const void *beta, const float *h0,
+                         const int32_t *cu_seqlens, void *o, float *hT, void *workspace,
+                         size_t workspace_bytes, void *hip_stream)
+{
+    g_last_error[0] = 0;
+    kda_status st = check_dims(d, cu_seqlens != nullptr);
+    if (st != KDA_OK) return st;
+    if (d->chunk != kChunk) return fail(KDA_ERR_UNSUPPORTED, "chunk must be %d, got %d", kChunk, d->chunk);
+    const bool empty = d->seqlen == 0 || d->heads == 0 || d->batch == 0;
+    if (!empty && (!q || !k || !v || !log_alpha || !beta || !o))
+        return fail(KDA_ERR_INVALID_ARG, "q, k, v, log_alpha, beta and o must be non-NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(log_alpha) || !aligned16(beta) ||
+        !aligned16(o) || !aligned16(h0) || !aligned16(hT) || (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u))
+        return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (o == q || o == k || o == v || o == log_alpha || o == beta)
+        if (!empty) return fail(KDA_ERR_INVALID_ARG, "o must not alias an input");
+    if (d->num_seqs == 0 || d->heads == 0) return KDA_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    if (d->in_dtype == KDA_BF16 && d->dk != 128 && mfma_path(d))
+        return fail(KDA_ERR_UNSUPPORTED, "bf16 prefill is built for dk == dv == 128 only");
+    if (!mfma_path(d))
+        return chunk_f32_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, stream);
+
+    const size_t need = chunk_mfma_workspace_size(d, true);
+    if (need > 0) {
+        if (!workspace) return fail(KDA_ERR_WORKSPACE, "workspace is NULL, at least %zu bytes needed", need);
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u)
+            return fail(KDA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+        if (workspace_bytes < need)
+            return fail(KDA_ERR_WORKSPACE, "workspace has %zu bytes, at least %zu needed", workspace_bytes, need);
+    }
+    return chunk_mfma_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
+                               workspace_bytes, stream);
+}
+
+kda_status kda_recurrent_step(const kda_dims *d, const void *q, const void *k, const void *v,
+                              const void *log_alpha, const void *beta, float *S, void *o,
+                              void *hip_stream)
+{
+    g_last_error[0] = 0;
+    kda_status st = check_dims(d, false);
+    if (st != KDA_OK) return st;
+    if (d->seqlen != 1) return fail(KDA_ERR_INVALID_ARG, "recurrent step needs seqlen == 1, got %lld",
+                                    (long long)d->seqlen);
+    if (d->num_seqs == 0 || d->heads == 0) return KDA_OK;
+    if (!q || !k || !v || !log_alpha || !beta || !S || !o)
+        return fail(KDA_ERR_INVALID_ARG, "q, k, v, log_alpha, beta, S and o must be non-NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(log_alpha) || !aligned16(S) ||
+        !aligned16(o) || (reinterpret_cast<uintptr_t>(beta) & 1u))
+        return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    return recurrent_step_dispatch(d, q, k, v, log_alpha, beta, S, o, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,131 @@
+// Recurrent decode step of KDA (Section 3, Eq. (1); Section 6.3 "Inference
+// strategy"): one new token per (sequence, head), fp32 state updated in place.
+//
+//     S <- Diag(alpha) S;  r = v - S^T k;  S <- S + beta k r^T;  o = scale S^T q
+//
+// The step is pure streaming: each dk x dv fp32 state is read once and written
+// once (64 KiB each way at dk = dv = 128) for ~0.9 FLOP per byte, so the kernel
+// is laid out for HBM, not for the matrix cores.  Every column of S is an
+// independent recurrence, so a wavefront owns a 32-column slice of one state and
+// never talks to another wavefront: lanes are arranged 8 (row groups) x 8
+// (float4 column groups), each lane keeps dk/8 float4 of the slice in
+// registers, the two reductions over dk finish with three xor-shuffles, and the
+// slice is written back from the same registers.  A block is the dv/32
+// wavefronts of one (sequence, head), so a block streams one contiguous state.
+#include "kda_common.h"
+
+namespace kda {
+
+template <typename Tin, int DK, int DV>
+__global__ __launch_bounds__(DV * 2)
+void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
+                     const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
+                     const Tin *__restrict__ beta, float *__restrict__ S,
+                     float *__restrict__ o, float scale)
+{
+    constexpr int ROWS = DK / 8;             // state rows per lane
+    __shared__ float s_alpha[DK], s_k[DK], s_q[DK];
+
+    const int64_t pair = blockIdx.x;         // (sequence, head) index
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int cg = lane & 7;                 // float4 column group inside the slice
+    const int rg = lane >> 3;                // row group: rows rg, rg+8, ...
+    const int col = wave * 32 + cg * 4;
+
+    // Token vectors: decay, key and query are needed per row by every lane.
+    for (int i = tid; i < DK; i += DV * 2) {
+        const int64_t off = pair * DK + i;
+        s_alpha[i] = fast_exp2(load_as_float(log_alpha + off) * kLog2e);
+        s_k[i] = load_as_float(k + off);
+        s_q[i] = load_as_float(q + off);
+    }
+
+    // Stream the slice in: ROWS independent 16-byte loads per lane.
+    f32x4 *Sp = reinterpret_cast<f32x4 *>(S + pair * (int64_t)(DK * DV) + (int64_t)rg * DV + col);
+    f32x4 s[ROWS];
+#pragma unroll
+    for (int m = 0; m < ROWS; ++m) s[m] = __builtin_nontemporal_load(Sp + (int64_t)m * (8 * DV / 4));
+
+    float vv[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) vv[c] = load_as_float(v + pair * DV + col + c);
+    const float b = load_as_float(beta + pair);
+
+    __syncthreads();
+
+    // Decay, then the memory's prediction S^T k for this lane's columns.
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+    for (int m = 0; m < ROWS; ++m) {
+        const float a = s_alpha[rg + 8 * m];
+        const float kk = s_k[rg + 8 * m];
+        s[m].x *= a; s[m].y *= a; s[m].z *= a; s[m].w *= a;
+        p0 = fmaf(kk, s[m].x, p0); p1 = fmaf(kk, s[m].y, p1);
+        p2 = fmaf(kk, s[m].z, p2); p3 = fmaf(kk, s[m].w, p3);
+    }
+#pragma unroll
+    for (int d = 8; d < 64; d <<= 1) {
+        p0 += __shfl_xor(p0, d); p1 += __shfl_xor(p1, d);
+        p2 += __shfl_xor(p2, d); p3 += __shfl_xor(p3, d);
+    }
+    // w = beta * (v - S^T k): the delta-rule correction written along k.
+    const float w0 = b * (vv[0] - p0), w1 = b * (vv[1] - p1);
+    const float w2 = b * (vv[2] - p2), w3 = b * (vv[3] - p3);
+
+    float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+#pragma unroll
+    for (int m = 0; m < ROWS; ++m) {
+        const float kk = s_k[rg + 8 * m];
+        const float qq = s_q[rg + 8 * m];
+        s[m].x = fmaf(kk, w0, s[m].x); s[m].y = fmaf(kk, w1, s[m].y);
+        s[m].z = fmaf(kk, w2, s[m].z); s[m].w = fmaf(kk, w3, s[m].w);
+        o0 = fmaf(qq, s[m].x, o0); o1 = fmaf(qq, s[m].y, o1);
+        o2 = fmaf(qq, s[m].z, o2); o3 = fmaf(qq, s[m].w, o3);
+        __builtin_nontemporal_store(s[m], Sp + (int64_t)m * (8 * DV / 4));
+    }
+#pragma unroll
+    for (int d = 8; d < 64; d <<= 1) {
+        o0 += __shfl_xor(o0, d); o1 += __shfl_xor(o1, d);
+        o2 += __shfl_xor(o2, d); o3 += __shfl_xor(o3, d);
+    }
+    if (rg == 0) {
+        f32x4 out = {o0 * scale, o1 * scale, o2 * scale, o3 * scale};
+        *reinterpret_cast<f32x4 *>(o + pair * DV + col) = out;
+    }
+}
+
+template <typename Tin, int DK, int DV>
+static kda_status launch_step(const kda_dims *d, const void *q, const void *k, const void *v,
+                              const void *log_alpha, const void *beta, float *S, void *o,
+                              hipStream_t stream)
+{
+    const int64_t pairs = (int64_t)d->num_seqs * d->heads;
+    if (pairs == 0) return KDA_OK;
+    if (pairs > 0x7fffffffLL) return fail(KDA_ERR_INVALID_ARG, "num_seqs*heads exceeds 2^31-1");
+    hipLaunchKernelGGL((kda_step_kernel<Tin, DK, DV>), dim3((unsigned)pairs), dim3(DV * 2), 0, stream,
+                       static_cast<const Tin *>(q), static_cast<const Tin *>(k),
+                       static_cast<const Tin *>(v), static_cast<const Tin *>(log_alpha),
+                       static_cast<const Tin *>(beta), S, static_cast<float *>(o), d->scale);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_step_kernel: %s", hipGetErrorString(e));
+    return KDA_OK;
+}
+
+kda_status recurrent_step_dispatch(const kda_dims *d, const void *q, const void *k, const void *v,
+                                   const void *log_alpha, const void *beta, float *S, void *o,
+                                   hipStream_t stream)
+{
+    const bool bf = d->in_dtype == KDA_BF16;
+    if (d->dk == 128 && d->dv == 128)
+        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, q, k, v, log_alpha, beta, S, o, stream)
+                  : launch_step<float, 128, 128>(d, q, k, v, log_alpha, beta, S, o, stream);
+    if (d->dk == 64 && d->dv == 64)
+        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, q, k, v, log_alpha, beta, S, o, stream)
+                  : launch_step<float, 64, 64>(d, q, k, v, log_alpha, beta, S, o, stream);
+    return fail(KDA_ERR_UNSUPPORTED, "recurrent step supports dk == dv in {64,128}, got %d x %d",
+                d->dk, d->dv);
+}
+
+}  // namespace kda

@@ -1,0 +1,177 @@
+"""ctypes binding for libkda.so (see include/kda.h for the contract).
+
+Argument marshalling only.  Tensors are torch tensors used as device-memory
+handles (``data_ptr()``), the stream is torch's current HIP stream.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libkda.so")
+_lib = None
+
+KDA_F32, KDA_BF16 = 0, 1
+_DTYPE_CODE = {torch.float32: KDA_F32, torch.bfloat16: KDA_BF16}
+
+
+class KdaError(RuntimeError):
+    """A libkda entry point returned a non-zero status."""
+
+    def __init__(self, status, detail):
+        super().__init__("libkda status %d (%s): %s" % (status, kda_status_string(status), detail))
+        self.status = status
+        self.detail = detail
+
+
+class KdaDims(ctypes.Structure):
+    """Mirror of ``kda_dims``."""
+    _fields_ = [("batch", ctypes.c_int32), ("seqlen", ctypes.c_int64), ("heads", ctypes.c_int32),
+                ("dk", ctypes.c_int32), ("dv", ctypes.c_int32), ("chunk", ctypes.c_int32),
+                ("num_seqs", ctypes.c_int32), ("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int),
+                ("scale", ctypes.c_float), ("max_seqlen", ctypes.c_int64)]
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libkda.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("libkda.so is not built: run `python -m paper_2510_26692_amd.build` "
+                           "(there is no CPU or PyTorch fallback for the KDA kernels)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    dp = ctypes.POINTER(KdaDims)
+    lib.kda_version.restype = ctypes.c_char_p
+    lib.kda_last_error.restype = ctypes.c_char_p
+    lib.kda_status_string.restype = ctypes.c_char_p
+    lib.kda_status_string.argtypes = [ctypes.c_int]
+    lib.kda_chunk_fwd_workspace_size.restype = sz
+    lib.kda_chunk_fwd_workspace_size.argtypes = [dp]
+    lib.kda_chunk_fwd_min_workspace_size.restype = sz
+    lib.kda_chunk_fwd_min_workspace_size.argtypes = [dp]
+    lib.kda_chunk_fwd.restype = ctypes.c_int
+    lib.kda_chunk_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kda_recurrent_step.restype = ctypes.c_int
+    lib.kda_recurrent_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def kda_version():
+    return load_library().kda_version().decode()
+
+
+def kda_last_error():
+    return load_library().kda_last_error().decode()
+
+
+def kda_status_string(status):
+    return load_library().kda_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _check_dev(*tensors):
+    dev = None
+    for t in tensors:
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise ValueError("libkda takes device tensors only")
+        if not t.is_contiguous():
+            raise ValueError("libkda takes contiguous tensors only")
+        dev = dev or t.device
+        if t.device != dev:
+            raise ValueError("all tensors must live on one device")
+    return dev
+
+
+def _stream_ptr(dev):
+    return ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+
+
+def make_chunk_dims(q, v, cu_seqlens=None, scale=1.0, max_seqlen=0):
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    N = B if cu_seqlens is None else cu_seqlens.numel() - 1
+    return KdaDims(batch=B, seqlen=T, heads=H, dk=dk, dv=dv, chunk=64, num_seqs=N,
+                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale),
+                   max_seqlen=int(max_seqlen))
+
+
+def kda_chunk_fwd_workspace_size(dims):
+    return int(load_library().kda_chunk_fwd_workspace_size(ctypes.byref(dims)))
+
+
+def kda_chunk_fwd_min_workspace_size(dims):
+    return int(load_library().kda_chunk_fwd_min_workspace_size(ctypes.byref(dims)))
+
+
+def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0, o=None,
+                  hT=None, want_hT=True, workspace=None, max_seqlen=0):
+    """Chunkwise prefill.  q,k,log_alpha [B,T,H,dk]; v [B,T,H,dv]; beta [B,T,H];
+    h0 [N,H,dk,dv] fp32 or None; cu_seqlens int32 [N+1] on device or None.
+    Returns (o fp32 [B,T,H,dv], hT fp32 [N,H,dk,dv] or None).  `o`, `hT` and
+    `workspace` (a uint8 device tensor) may be passed in to avoid allocation."""
+    lib = load_library()
+    dev = _check_dev(q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace)
+    if not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype):
+        raise ValueError("q, k, v, log_alpha, beta must share one dtype")
+    if q.dtype not in _DTYPE_CODE:
+        raise ValueError("unsupported input dtype %s" % q.dtype)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    if k.shape != q.shape or log_alpha.shape != q.shape or v.shape != (B, T, H, dv) \
+            or beta.shape != (B, T, H):
+        raise ValueError("inconsistent input shapes")
+    dims = make_chunk_dims(q, v, cu_seqlens, scale, max_seqlen)
+    N = dims.num_seqs
+    if h0 is not None and (h0.dtype != torch.float32 or h0.shape != (N, H, dk, dv)):
+        raise ValueError("h0 must be fp32 [N,H,dk,dv]")
+    if cu_seqlens is not None and cu_seqlens.dtype != torch.int32:
+        raise ValueError("cu_seqlens must be int32")
+    if o is None:
+        o = torch.zeros(B, T, H, dv, dtype=torch.float32, device=dev)
+    if hT is None and want_hT:
+        hT = torch.empty(N, H, dk, dv, dtype=torch.float32, device=dev)
+    if workspace is None:
+        need = kda_chunk_fwd_workspace_size(dims)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev) if need else None
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.kda_chunk_fwd(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha),
+                           _ptr(beta), _ptr(h0), _ptr(cu_seqlens), _ptr(o), _ptr(hT),
+                           _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(dev))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return o, hT
+
+
+def kda_recurrent_step(q, k, v, log_alpha, beta, S, scale=1.0, o=None):
+    """One decode step.  q,k,log_alpha [N,H,dk]; v [N,H,dv]; beta [N,H];
+    S fp32 [N,H,dk,dv], updated in place.  Returns o fp32 [N,H,dv]."""
+    lib = load_library()
+    dev = _check_dev(q, k, v, log_alpha, beta, S, o)
+    N, H, dk = q.shape
+    dv = v.shape[-1]
+    if S.dtype != torch.float32 or S.shape != (N, H, dk, dv):
+        raise ValueError("S must be fp32 [N,H,dk,dv]")
+    if q.dtype not in _DTYPE_CODE or not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype):
+        raise ValueError("q, k, v, log_alpha, beta must share a supported dtype")
+    if o is None:
+        o = torch.empty(N, H, dv, dtype=torch.float32, device=dev)
+    dims = KdaDims(batch=N, seqlen=1, heads=H, dk=dk, dv=dv, chunk=64, num_seqs=N,
+                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale), max_seqlen=0)
+    st = lib.kda_recurrent_step(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha),
+                                _ptr(beta), _ptr(S), _ptr(o), _stream_ptr(dev))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return o

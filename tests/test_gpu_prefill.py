@@ -1,0 +1,56 @@
+"""GPU parity of kda_chunk_fwd against the fp64 oracle on seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from helpers import check_prefill
+
+pytestmark = pytest.mark.gpu
+
+# fp32 path: fp32 products/accumulation over <= 128-term dot products and a 64-step
+# substitution, hardware exp2 (1 ulp): errors sit near 1e-6; gate as stated for fp32.
+TOL_F32 = 1e-5
+# bf16 inputs: fp16 matrix-core operands (unit roundoff 2^-11) with fp32 accumulation;
+# emulation of the operand roundings puts the error near 6e-4; gate as stated for bf16.
+TOL_BF16 = 2e-3
+
+
+def test_config0_tiny_fp32():
+    c = si.CONFIGS["cfg0_tiny_fp32"]
+    d = si.make_prefill(c["B"], c["T"], c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"],
+                        c["h0_std"])
+    eo, eh = check_prefill(d, TOL_F32)
+    print("config 0: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+@pytest.mark.parametrize("T", [1, 63, 64, 65, 200])
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp32_ragged_lengths_and_h0(T, d):
+    x = si.make_prefill(2, T, 3, d, d, "f32", -1.0, 5 + T, 0.05)
+    eo, eh = check_prefill(x, TOL_F32, scale=d ** -0.5)
+    print("fp32 T=%d d=%d: err_o %.2e err_hT %.2e" % (T, d, eo, eh))
+
+
+def test_fp32_packed_with_empty_sequence():
+    lens = [70, 0, 5, 129]
+    x = si.make_varlen(lens, 2, 64, 64, "f32", -1.0, 9, 0.05)
+    eo, eh = check_prefill(x, TOL_F32)
+    print("fp32 packed: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+def test_fp32_strong_decay():
+    """log alpha down to about -20 per token: the pairwise log-domain products must
+    neither overflow nor lose the surviving terms."""
+    x = si.make_prefill(1, 130, 2, 64, 64, "f32", 0.0, 21, 0.05)
+    x["log_alpha"] = (x["log_alpha"] * 6.0).contiguous()
+    assert float(x["log_alpha"].min()) < -15.0
+    eo, eh = check_prefill(x, TOL_F32)
+    print("fp32 strong decay: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+@pytest.mark.parametrize("T", [64, 200, 1024])
+def test_bf16_small(T):
+    x = si.make_prefill(2, T, 4, 128, 128, "bf16", -2.0, 31 + T, 0.02)
+    eo, eh = check_prefill(x, TOL_BF16)
+    print("bf16 T=%d: err_o %.2e err_hT %.2e" % (T, eo, eh))
