@@ -1,21 +1,780 @@
-// Placeholder: the matrix-core prefill path is under construction; bf16 inputs
-// run through the fp32 kernel until it lands.
+// Chunkwise KDA prefill on the matrix cores (Section 3.1) for bf16 inputs,
+// d_k = d_v = 128, C = 64.
+//
+// Two kernels per time segment:
+//
+//  kda_intra  one workgroup per (chunk, head), all chunks in parallel.  It forms the
+//             running log-decay G, the two intra-chunk matrices A_kk and A_qk, the
+//             UT-transform M = (I + StrictTril(Diag(beta) A_kk))^-1 Diag(beta) by
+//             forward substitution, W = M (Gamma.K), U = M V and the decay-scaled
+//             operands Gamma.Q and Gamma^{i->C}.K, and leaves them in the workspace
+//             in MFMA register order (kda_mfma_layout.h).
+//  kda_scan   one workgroup per (sequence, head), sequential over that sequence's
+//             chunks: V_new = U - W S, O = (Gamma.Q) S + Tril(A_qk) V_new,
+//             S <- Diag(gamma^C) S + (Gamma^{i->C}.K)^T V_new, with the fp32 state
+//             held in accumulator registers for the whole sequence.
+//
+// Matrix-core operands are fp16 (unit roundoff 2^-11), accumulation is fp32.  The
+// raw bf16 inputs convert to fp16 exactly; only derived operands are rounded.
+//
+// Decay handling ("secondary chunking"): the chunk is cut into four 16-token
+// sub-chunks.  For a pair of tokens in different sub-chunks the decay
+// 2^(G_r - G_i) is split at the boundary in front of the row's sub-chunk, so both
+// factors are <= 1 and go straight into the operands.  Inside a sub-chunk it is
+// split at the sub-chunk's start, which makes the column factor 2^(-G_i) >= 1; a
+// channel whose decay across the sub-chunk exceeds 2^-kStrongLog2 is taken out of
+// those operands and added back exactly, pair by pair, in fp32.
 #include "kda_common.h"
+#include "kda_mfma_layout.h"
 
 namespace kda {
+namespace mfma {
 
-kda_status chunk_f32_dispatch(const kda_dims *, const void *, const void *, const void *,
-                              const void *, const void *, const float *, const int32_t *, void *,
-                              float *, hipStream_t);
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-size_t chunk_mfma_workspace_size(const kda_dims *, bool) { return 0; }
+constexpr float kStrongLog2 = 11.0f;   // sub-chunk decay below 2^-11 leaves the fast operands
+constexpr float kRowScale = 16.0f;     // keeps small row operands out of the fp16 subnormals
+
+// ----------------------------------------------------------------------------------
+// LDS map of kda_intra (bytes).  Two phases share the space.
+// ----------------------------------------------------------------------------------
+constexpr int kLdH = 136;                               // halfs per row of a [*][128] fp16 tile
+constexpr int kTileH = 64 * kLdH * 2;                   // 17408 B
+// phase A: operands of the A-matrix products
+constexpr int kRowK = 0;
+constexpr int kRowQ = kRowK + kTileH;
+constexpr int kColKd = kRowQ + kTileH;
+constexpr int kColK = kColKd + kTileH;                  // [6][16][136] halfs
+constexpr int kColKBytes = 6 * 16 * kLdH * 2;           // 26112
+// phase A, only when a strong channel exists: exact data for the pairwise fix-up
+constexpr int kLdG = 132;                               // floats per row of the fp32 G tile
+constexpr int kGl = kColK + kColKBytes;                 // fp32 [64][132]
+constexpr int kKraw = kGl + 64 * kLdG * 4;              // bf16 [64][136]
+constexpr int kQraw = kKraw + kTileH;
+constexpr int kSmall = kQraw + kTileH;
+// phase B (aliases phase A)
+constexpr int kLdF = 68;                                // floats per row of a [64][64] fp32 tile
+constexpr int kTileF = 64 * kLdF * 4;                   // 17408 B
+constexpr int kL = 0;                                   // fp32 L = StrictTril(Diag(beta) A_kk)
+constexpr int kAq = kL + kTileF;                        // fp32 Tril(A_qk)
+constexpr int kX = kAq + kTileF;                        // fp32 (I + L)^-1
+constexpr int kLdM = 72;                                // halfs per row of the fp16 M tile
+constexpr int kM = kX + kTileF;                         // fp16 [64][72]
+constexpr int kV = kM + 64 * kLdM * 2;                  // fp16 [64][136]
+constexpr int kGK = kV + kTileH;
+constexpr int kQp = kGK + kTileH;
+constexpr int kKp = kQp + kTileH;
+static_assert(kKp + kTileH <= kSmall, "phase B tiles must not reach the small region");
+// small region (lives through both phases)
+constexpr int kTot = kSmall;                            // fp32 [4][128] sub-chunk log2-decay totals
+constexpr int kBeta = kTot + 4 * 128 * 4;               // fp32 [64]
+constexpr int kStrong = kBeta + 64 * 4;                 // u64 [4][2] strong-channel masks
+constexpr int kIntraLds = kStrong + 64;
+static_assert(kIntraLds <= 160 * 1024, "kda_intra exceeds the 160 KiB of LDS");
+
+__device__ __forceinline__ uint32_t pack_h2(float a, float b)
+{
+    h2 v = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// ----------------------------------------------------------------------------------
+// kda_intra
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256)
+void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
+                      const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
+                      const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
+                      uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
+                      int64_t seg_index)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+
+    const int h = (int)(blockIdx.x % (unsigned)H);
+    const int64_t slot = blockIdx.x / (unsigned)H;
+    const int n = (int)(slot / seg_chunks);
+    const int64_t ci = seg_index * seg_chunks + slot % seg_chunks;
+    int64_t tok_base, len;
+    if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
+    else            { tok_base = (int64_t)n * T; len = T; }
+    if (ci * kChunk >= len) return;                      // uniform for the workgroup
+    const int nv = (int)((len - ci * kChunk < kChunk) ? (len - ci * kChunk) : kChunk);
+    const int64_t tok0 = tok_base + ci * kChunk;
+    uint8_t *out = ws + (slot * H + h) * (int64_t)kSlotBytes;
+
+    float *sTot = reinterpret_cast<float *>(lds + kTot);
+    float *sBeta = reinterpret_cast<float *>(lds + kBeta);
+    uint64_t *sStrong = reinterpret_cast<uint64_t *>(lds + kStrong);
+
+    // ---- loads.  Thread (c = lane, R = wave) owns channels 2c, 2c+1 of sub-chunk R. ----
+    const int R = wave, c = lane;
+    uint32_t k2[16], q2[16];
+    float G0[16], G1[16];
+    {
+        float run0 = 0.f, run1 = 0.f;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int tok = 16 * R + t;
+            uint32_t kk = 0, qq = 0, gg = 0;
+            if (tok < nv) {
+                const int64_t off = ((tok0 + tok) * H + h) * (int64_t)D + 2 * c;
+                kk = *reinterpret_cast<const uint32_t *>(k + off);
+                qq = *reinterpret_cast<const uint32_t *>(q + off);
+                gg = *reinterpret_cast<const uint32_t *>(log_alpha + off);
+            }
+            k2[t] = kk; q2[t] = qq;
+            float g0, g1;
+            unpack_bf16x2(gg, g0, g1);
+            run0 = fmaf(g0, kLog2e, run0); run1 = fmaf(g1, kLog2e, run1);
+            G0[t] = run0; G1[t] = run1;                  // inclusive, local to the sub-chunk, log2 units
+        }
+    }
+    const float tot0 = G0[15], tot1 = G1[15];
+    u32x4 vraw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+        u32x4 x = {0, 0, 0, 0};
+        if (tokv < nv)
+            x = *reinterpret_cast<const u32x4 *>(v + ((tok0 + tokv) * H + h) * (int64_t)D + 8 * cg);
+        vraw[i] = x;
+    }
+    *reinterpret_cast<float2 *>(sTot + R * 128 + 2 * c) = make_float2(tot0, tot1);
+    const bool strong0 = tot0 < -kStrongLog2, strong1 = tot1 < -kStrongLog2;
+    {
+        const uint64_t b0 = __ballot(strong0), b1 = __ballot(strong1);
+        if (lane == 0) { sStrong[R * 2 + 0] = b0; sStrong[R * 2 + 1] = b1; }
+    }
+    if (tid < kChunk)
+        sBeta[tid] = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
+    __syncthreads();                                                               // B1
+
+    // ---- phase A operands ----
+    float tt0[4], tt1[4];
+#pragma unroll
+    for (int J = 0; J < 4; ++J) {
+        const float2 x = *reinterpret_cast<const float2 *>(sTot + J * 128 + 2 * c);
+        tt0[J] = x.x; tt1[J] = x.y;
+    }
+    float pre0 = 0.f, pre1 = 0.f, post0 = 0.f, post1 = 0.f;
+#pragma unroll
+    for (int J = 0; J < 4; ++J) {
+        if (J < R) { pre0 += tt0[J]; pre1 += tt1[J]; }
+        if (J > R) { post0 += tt0[J]; post1 += tt1[J]; }
+    }
+    bool strong_any = false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) strong_any |= (sStrong[i] != 0);
+    // decay between the end of sub-chunk R and the start of sub-chunk R+2 / R+3
+    const float interA0 = (R + 1 < 4) ? fast_exp2(tt0[(R + 1) & 3]) : 0.f;
+    const float interA1 = (R + 1 < 4) ? fast_exp2(tt1[(R + 1) & 3]) : 0.f;
+    const float interB0 = (R + 2 < 4) ? fast_exp2(tt0[(R + 1) & 3] + tt0[(R + 2) & 3]) : 0.f;
+    const float interB1 = (R + 2 < 4) ? fast_exp2(tt1[(R + 1) & 3] + tt1[(R + 2) & 3]) : 0.f;
+
+    float RF0[16], RF1[16], SF0[16], SF1[16];            // kept for phase B
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int tok = 16 * R + t;
+        float k0, k1, q0, q1;
+        unpack_bf16x2(k2[t], k0, k1);
+        unpack_bf16x2(q2[t], q0, q1);
+        const float rf0 = fast_exp2(G0[t]), rf1 = fast_exp2(G1[t]);          // 2^(G_r - G_ref(R))
+        const float sf0 = fast_exp2(tot0 - G0[t]), sf1 = fast_exp2(tot1 - G1[t]);  // to the end of R
+        const float in0 = strong0 ? 0.f : fast_exp2(-G0[t]);
+        const float in1 = strong1 ? 0.f : fast_exp2(-G1[t]);
+        RF0[t] = rf0; RF1[t] = rf1; SF0[t] = sf0; SF1[t] = sf1;
+        const int at = (tok * kLdH + 2 * c) * 2;
+        *reinterpret_cast<uint32_t *>(lds + kRowK + at) = pack_h2(k0 * rf0 * kRowScale, k1 * rf1 * kRowScale);
+        *reinterpret_cast<uint32_t *>(lds + kRowQ + at) = pack_h2(q0 * rf0 * kRowScale, q1 * rf1 * kRowScale);
+        *reinterpret_cast<uint32_t *>(lds + kColKd + at) = pack_h2(k0 * in0, k1 * in1);
+        const float ks0 = k0 * sf0, ks1 = k1 * sf1;
+        // column operand of tile (Rp, R), Rp > R: reference in front of sub-chunk Rp
+        if (R + 1 < 4) {
+            const int pid = (R + 1) * R / 2 + R;
+            *reinterpret_cast<uint32_t *>(lds + kColK + ((pid * 16 + t) * kLdH + 2 * c) * 2) = pack_h2(ks0, ks1);
+        }
+        if (R + 2 < 4) {
+            const int pid = (R + 2) * (R + 1) / 2 + R;
+            *reinterpret_cast<uint32_t *>(lds + kColK + ((pid * 16 + t) * kLdH + 2 * c) * 2) =
+                pack_h2(ks0 * interA0, ks1 * interA1);
+        }
+        if (R + 3 < 4) {
+            const int pid = (R + 3) * (R + 2) / 2 + R;
+            *reinterpret_cast<uint32_t *>(lds + kColK + ((pid * 16 + t) * kLdH + 2 * c) * 2) =
+                pack_h2(ks0 * interB0, ks1 * interB1);
+        }
+        if (strong_any) {
+            *reinterpret_cast<float2 *>(lds + kGl + (tok * kLdG + 2 * c) * 4) = make_float2(G0[t], G1[t]);
+            *reinterpret_cast<uint32_t *>(lds + kKraw + at) = k2[t];
+            *reinterpret_cast<uint32_t *>(lds + kQraw + at) = q2[t];
+        }
+    }
+    if (R == 0) {   // gamma^C: decay of the whole chunk
+        float2 gc = make_float2(fast_exp2(tt0[0] + tt0[1] + tt0[2] + tt0[3]),
+                                fast_exp2(tt1[0] + tt1[1] + tt1[2] + tt1[3]));
+        *reinterpret_cast<float2 *>(out + kOffGc + 2 * c * 4) = gc;
+    }
+    __syncthreads();                                                               // B2
+
+    // ---- A_kk, A_qk tiles (16x16, K = 128) on the matrix cores ----
+    // tiles per wave: w0 (3,0)(3,1)(0,0)  w1 (3,2)(3,3)  w2 (2,0)(2,1)(2,2)  w3 (1,0)(1,1)
+    const int nt = (wave & 1) ? 2 : 3;
+    const int tR[3] = {wave == 3 ? 1 : (wave == 2 ? 2 : 3), wave == 3 ? 1 : (wave == 2 ? 2 : 3),
+                       wave == 0 ? 0 : 2};
+    const int tI[3] = {wave == 1 ? 2 : 0, wave == 1 ? 3 : 1, wave == 0 ? 0 : 2};
+    f32x4 res_kk[3], res_qk[3];
+    {
+        const int m = lane & 15, g = lane >> 4;
+#pragma unroll
+        for (int ti = 0; ti < 3; ++ti) {
+            f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
+            if (ti < nt) {
+                const int Rr = tR[ti], Ii = tI[ti];
+                const int rowoff = ((16 * Rr + m) * kLdH + 8 * g) * 2;
+                const int coloff = (Ii == Rr) ? kColKd + rowoff
+                                              : kColK + (((Rr * (Rr - 1) / 2 + Ii) * 16 + m) * kLdH + 8 * g) * 2;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const h8 ak = *reinterpret_cast<const h8 *>(lds + kRowK + rowoff + ks * 64);
+                    const h8 aq = *reinterpret_cast<const h8 *>(lds + kRowQ + rowoff + ks * 64);
+                    const h8 b = *reinterpret_cast<const h8 *>(lds + coloff + ks * 64);
+                    akk = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, b, akk, 0, 0, 0);
+                    aqk = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, b, aqk, 0, 0, 0);
+                }
+                akk *= (1.0f / kRowScale);
+                aqk *= (1.0f / kRowScale);
+                if (Ii == Rr && strong_any) {
+                    // exact pairwise terms of the channels that were left out of colKd
+                    const float *sG = reinterpret_cast<const float *>(lds + kGl);
+                    const uint16_t *sKr = reinterpret_cast<const uint16_t *>(lds + kKraw);
+                    const uint16_t *sQr = reinterpret_cast<const uint16_t *>(lds + kQraw);
+                    for (int half = 0; half < 2; ++half) {
+                        uint64_t mask = sStrong[Rr * 2 + half];
+                        while (mask) {
+                            const int bit = __builtin_ctzll(mask);
+                            mask &= mask - 1;
+                            const int ch = 2 * bit + half;
+                            const int ic = 16 * Rr + m;                      // column token
+                            const float Gi = sG[ic * kLdG + ch];
+                            const float ki = bf16_bits_to_float(sKr[ic * kLdH + ch]);
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int rr = 4 * g + j;
+                                if (rr >= m) {
+                                    const int ir = 16 * Rr + rr;
+                                    const float e = fast_exp2(sG[ir * kLdG + ch] - Gi);
+                                    const float t = ki * e;
+                                    akk[j] = fmaf(bf16_bits_to_float(sKr[ir * kLdH + ch]), t, akk[j]);
+                                    aqk[j] = fmaf(bf16_bits_to_float(sQr[ir * kLdH + ch]), t, aqk[j]);
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+            res_kk[ti] = akk; res_qk[ti] = aqk;
+        }
+    }
+    __syncthreads();                                                               // B3
+
+    // ---- phase B tiles: L, Tril(A_qk), Gamma.K, Gamma.Q, Gamma^{i->C}.K, V ----
+    {
+        float *sL = reinterpret_cast<float *>(lds + kL);
+        float *sAq = reinterpret_cast<float *>(lds + kAq);
+        const int m = lane & 15, g = lane >> 4;
+#pragma unroll
+        for (int ti = 0; ti < 3; ++ti) {
+            if (ti < nt) {
+                const int i = 16 * tI[ti] + m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 16 * tR[ti] + 4 * g + j;
+                    sL[r * kLdF + i] = (i < r) ? sBeta[r] * res_kk[ti][j] : 0.f;
+                    sAq[r * kLdF + i] = (i <= r) ? res_qk[ti][j] : 0.f;
+                }
+            }
+        }
+        const float P0 = fast_exp2(pre0), P1 = fast_exp2(pre1);      // Gamma at the start of sub-chunk R
+        const float E0 = fast_exp2(post0), E1 = fast_exp2(post1);    // decay from its end to the chunk end
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            float k0, k1, q0, q1;
+            unpack_bf16x2(k2[t], k0, k1);
+            unpack_bf16x2(q2[t], q0, q1);
+            const float gam0 = RF0[t] * P0, gam1 = RF1[t] * P1;
+            const int at = ((16 * R + t) * kLdH + 2 * c) * 2;
+            *reinterpret_cast<uint32_t *>(lds + kGK + at) = pack_h2(k0 * gam0, k1 * gam1);
+            *reinterpret_cast<uint32_t *>(lds + kQp + at) = pack_h2(q0 * gam0, q1 * gam1);
+            *reinterpret_cast<uint32_t *>(lds + kKp + at) = pack_h2(k0 * SF0[t] * E0, k1 * SF1[t] * E1);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+            u32x4 x;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float a, b;
+                unpack_bf16x2(vraw[i][w], a, b);
+                x[w] = pack_h2(a, b);
+            }
+            *reinterpret_cast<u32x4 *>(lds + kV + (tokv * kLdH + 8 * cg) * 2) = x;
+        }
+    }
+    __syncthreads();                                                               // B4
+
+    // ---- UT transform, diagonal 16x16 blocks: column j of (I + L_ww)^-1 per lane ----
+    {
+        const float *sL = reinterpret_cast<const float *>(lds + kL);
+        float *sX = reinterpret_cast<float *>(lds + kX);
+        const int j = lane & 15, w = wave;
+        float x[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float s = (r == j) ? 1.f : 0.f;
+            const float *row = sL + (16 * w + r) * kLdF + 16 * w;
+#pragma unroll
+            for (int i = 0; i < r; ++i) s = fmaf(-row[i], x[i], s);
+            x[r] = (r < j) ? 0.f : s;
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sX[(16 * w + r) * kLdF + 16 * w + j] = x[r];
+        }
+    }
+    // ---- copy Gamma.Q and (Gamma^{i->C}.K)^T out in MFMA register order ----
+    {
+        const int x = lane & 31, hh = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int f = wave * 4 + i;
+            {   // Qp frag f = (rho*4 + tau)*2 + s
+                const int rho = f >> 3, tau = (f >> 1) & 3, s = f & 1;
+                const int at = ((32 * rho + x) * kLdH + 32 * tau + 16 * s + 4 * hh) * 2;
+                const u32x2 a = *reinterpret_cast<const u32x2 *>(lds + kQp + at);
+                const u32x2 b = *reinterpret_cast<const u32x2 *>(lds + kQp + at + 16);
+                u32x4 o4 = {a[0], a[1], b[0], b[1]};
+                *reinterpret_cast<u32x4 *>(out + kOffQp + f * kFragBytes + lane * 16) = o4;
+            }
+            {   // Kt frag f = (tau*2 + rho)*2 + s
+                const int tau = f >> 2, rho = (f >> 1) & 1, s = f & 1;
+                const uint16_t *sKp = reinterpret_cast<const uint16_t *>(lds + kKp);
+                uint32_t w4[4];
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const int t0 = 32 * rho + kidx(s, hh, e), t1 = 32 * rho + kidx(s, hh, e + 1);
+                    w4[e >> 1] = (uint32_t)sKp[t0 * kLdH + 32 * tau + x] |
+                                 ((uint32_t)sKp[t1 * kLdH + 32 * tau + x] << 16);
+                }
+                u32x4 o4 = {w4[0], w4[1], w4[2], w4[3]};
+                *reinterpret_cast<u32x4 *>(out + kOffKt + f * kFragBytes + lane * 16) = o4;
+            }
+        }
+    }
+    __syncthreads();                                                               // B5
+
+    // ---- UT transform, off-diagonal blocks: X_RI = -X_RR sum_{I<=J<R} L_RJ X_JI (fp32 MFMA) ----
+    {
+        const float *sL = reinterpret_cast<const float *>(lds + kL);
+        float *sX = reinterpret_cast<float *>(lds + kX);
+        const int m = lane & 15, g = lane >> 4;
+        for (int Rr = 1; Rr < 4; ++Rr) {
+            if (wave < Rr) {
+                const int Ii = wave;
+                f32x4 t = {0.f, 0.f, 0.f, 0.f};
+                for (int J = Ii; J < Rr; ++J) {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        const float a = sL[(16 * Rr + m) * kLdF + 16 * J + 4 * ks + g];
+                        const float b = sX[(16 * J + 4 * ks + g) * kLdF + 16 * Ii + m];
+                        t = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, t, 0, 0, 0);
+                    }
+                }
+                // second product with contraction slot (ks, g) standing for index 4 g + ks, so
+                // that register ks of the accumulator t is the B operand as it stands
+                f32x4 r = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const float a = sX[(16 * Rr + m) * kLdF + 16 * Rr + 4 * g + ks];
+                    r = __builtin_amdgcn_mfma_f32_16x16x4f32(a, t[ks], r, 0, 0, 0);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sX[(16 * Rr + 4 * g + j) * kLdF + 16 * Ii + m] = -r[j];
+            }
+            __syncthreads();                                                       // B6
+        }
+    }
+
+    // ---- M = X Diag(beta) as fp16; Tril(A_qk) out in MFMA register order ----
+    {
+        const float *sX = reinterpret_cast<const float *>(lds + kX);
+        _Float16 *sM = reinterpret_cast<_Float16 *>(lds + kM);
+        for (int idx = tid; idx < 64 * 64; idx += 256) {
+            const int r = idx >> 6, j = idx & 63;
+            float val = 0.f;
+            if (j < r) val = sX[r * kLdF + j] * sBeta[j];
+            else if (j == r) val = sBeta[j];
+            sM[r * kLdM + j] = (_Float16)val;
+        }
+        const float *sAq = reinterpret_cast<const float *>(lds + kAq);
+        const int x = lane & 31, hh = lane >> 5;
+        for (int idx = wave; idx < 6; idx += 4) {
+            const int p = idx >> 1, s = idx & 1;
+            const int rr = (p == 0) ? 0 : 1, ri = (p == 2) ? 1 : 0;
+            const int r = 32 * rr + x;
+            const int i0 = 32 * ri + 16 * s + 4 * hh;
+            const f32x4 a = *reinterpret_cast<const f32x4 *>(sAq + r * kLdF + i0);
+            const f32x4 b = *reinterpret_cast<const f32x4 *>(sAq + r * kLdF + i0 + 8);
+            float e[8];
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                e[z] = (i0 + z <= r) ? a[z] : 0.f;
+                e[4 + z] = (i0 + 8 + z <= r) ? b[z] : 0.f;
+            }
+            u32x4 o4 = {pack_h2(e[0], e[1]), pack_h2(e[2], e[3]), pack_h2(e[4], e[5]), pack_h2(e[6], e[7])};
+            *reinterpret_cast<u32x4 *>(out + kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16) = o4;
+        }
+    }
+    __syncthreads();                                                               // B7
+
+    // ---- W^T = (Gamma.K)^T M^T (wave = d_k tile) and U = M V (wave = d_v tile) ----
+    {
+        const int x = lane & 31, hh = lane >> 5;
+        const uint16_t *sGK = reinterpret_cast<const uint16_t *>(lds + kGK);
+        const uint16_t *sV = reinterpret_cast<const uint16_t *>(lds + kV);
+        h8 mf[2][4], gk[4], vv[4];
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+            for (int rho = 0; rho < 2; ++rho)
+                mf[rho][s4] = *reinterpret_cast<const h8 *>(lds + kM + ((32 * rho + x) * kLdM + 16 * s4 + 8 * hh) * 2);
+            uint32_t wg[4], wv[4];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const int t0 = 16 * s4 + 8 * hh + e;
+                wg[e >> 1] = (uint32_t)sGK[t0 * kLdH + 32 * wave + x] | ((uint32_t)sGK[(t0 + 1) * kLdH + 32 * wave + x] << 16);
+                wv[e >> 1] = (uint32_t)sV[t0 * kLdH + 32 * wave + x] | ((uint32_t)sV[(t0 + 1) * kLdH + 32 * wave + x] << 16);
+            }
+            u32x4 pg = {wg[0], wg[1], wg[2], wg[3]}, pv = {wv[0], wv[1], wv[2], wv[3]};
+            gk[s4] = __builtin_bit_cast(h8, pg);
+            vv[s4] = __builtin_bit_cast(h8, pv);
+        }
+#pragma unroll
+        for (int rho = 0; rho < 2; ++rho) {
+            f32x16 wt = {0.f}, u = {0.f};
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                if (s4 < 2 * (rho + 1)) {            // M is lower triangular: tokens j <= r only
+                    wt = __builtin_amdgcn_mfma_f32_32x32x16_f16(gk[s4], mf[rho][s4], wt, 0, 0, 0);
+                    u = __builtin_amdgcn_mfma_f32_32x32x16_f16(mf[rho][s4], vv[s4], u, 0, 0, 0);
+                }
+            }
+            // -W: registers 8s..8s+7 of a lane are its 8 contraction slots of K-step s
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                u32x4 o4;
+#pragma unroll
+                for (int z = 0; z < 4; ++z) o4[z] = pack_h2(-wt[8 * s + 2 * z], -wt[8 * s + 2 * z + 1]);
+                *reinterpret_cast<u32x4 *>(out + kOffWn + frag_rts(rho, wave, s) * kFragBytes + lane * 16) = o4;
+            }
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4) {
+                f32x4 o4 = {u[4 * j4], u[4 * j4 + 1], u[4 * j4 + 2], u[4 * j4 + 3]};
+                *reinterpret_cast<f32x4 *>(out + kOffU + (((rho * 4 + wave) * 4 + j4) * 64 + lane) * 16) = o4;
+            }
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// kda_scan
+// ----------------------------------------------------------------------------------
+template <int NW>
+__global__ __launch_bounds__(NW * 64)
+void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, float *state_out,
+                     const int32_t *__restrict__ cu_seqlens, float *__restrict__ o, int64_t T, int H,
+                     int64_t seg_chunks, int64_t seg_index, float scale)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int NT = NW * 64;
+    constexpr int UNITS = kLdsBlockBytes / 16;
+    constexpr int NPRE = (UNITS + NT - 1) / NT;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int x = lane & 31, hh = lane >> 5;
+    const int n = blockIdx.x, h = blockIdx.y;
+    const int ct = blockIdx.z * NW + wave;               // this wave's 32-column slice of S
+
+    int64_t tok_base, len;
+    if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
+    else            { tok_base = (int64_t)n * T; len = T; }
+    const int64_t nchunks = (len + kChunk - 1) / kChunk;
+    const int64_t c_begin = seg_index * seg_chunks;
+    const int64_t c_end = (nchunks < c_begin + seg_chunks) ? nchunks : c_begin + seg_chunks;
+
+    // state slice in accumulator order: S[tau][j] = S(dk = 32 tau + acc_row(j, hh), dv = 32 ct + x)
+    const int64_t st_base = ((int64_t)n * H + h) * (int64_t)(D * D) + 32 * ct + x;
+    f32x16 S[4];
+#pragma unroll
+    for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            S[tau][j] = state_in ? state_in[st_base + (int64_t)(32 * tau + acc_row(j, hh)) * D] : 0.f;
+
+    if (c_begin < c_end) {
+        const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks) * H + h) * (int64_t)kSlotBytes;
+        const int64_t slot_stride = (int64_t)H * kSlotBytes;
+
+        // prologue: stage the first chunk, fetch its U tiles
+        f32x16 un[2];
+        {
+            const uint8_t *src = slot0;
+            for (int u = tid; u < UNITS; u += NT)
+                *reinterpret_cast<u32x4 *>(lds + u * 16) = *reinterpret_cast<const u32x4 *>(src + u * 16);
+#pragma unroll
+            for (int rho = 0; rho < 2; ++rho)
+#pragma unroll
+                for (int j4 = 0; j4 < 4; ++j4) {
+                    const f32x4 t = *reinterpret_cast<const f32x4 *>(src + kOffU + (((rho * 4 + ct) * 4 + j4) * 64 + lane) * 16);
+                    un[rho][4 * j4] = t[0]; un[rho][4 * j4 + 1] = t[1];
+                    un[rho][4 * j4 + 2] = t[2]; un[rho][4 * j4 + 3] = t[3];
+                }
+        }
+        __syncthreads();
+
+        for (int64_t ci = c_begin; ci < c_end; ++ci) {
+            const int stage = (int)((ci - c_begin) & 1);
+            const uint8_t *cur = lds + stage * kLdsBlockBytes;
+            const bool more = ci + 1 < c_end;
+            const uint8_t *nxt = slot0 + (ci + 1 - c_begin) * slot_stride;
+
+            // prefetch the next chunk while this one computes
+            u32x4 pre[NPRE];
+            f32x16 av[2] = {un[0], un[1]};
+            if (more) {
+#pragma unroll
+                for (int i = 0; i < NPRE; ++i) {
+                    const int u = tid + i * NT;
+                    if (u < UNITS) pre[i] = *reinterpret_cast<const u32x4 *>(nxt + u * 16);
+                }
+#pragma unroll
+                for (int rho = 0; rho < 2; ++rho)
+#pragma unroll
+                    for (int j4 = 0; j4 < 4; ++j4) {
+                        const f32x4 t = *reinterpret_cast<const f32x4 *>(nxt + kOffU + (((rho * 4 + ct) * 4 + j4) * 64 + lane) * 16);
+                        un[rho][4 * j4] = t[0]; un[rho][4 * j4 + 1] = t[1];
+                        un[rho][4 * j4 + 2] = t[2]; un[rho][4 * j4 + 3] = t[3];
+                    }
+            }
+
+            // S as B operand: registers 8s..8s+7 of tile tau are the slots of K-step (tau, s)
+            h8 Sb[4][2];
+#pragma unroll
+            for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) Sb[tau][s][e] = (_Float16)S[tau][8 * s + e];
+
+            // V_new = U + (-W) S   and   O = (Gamma.Q) S
+            f32x16 ao[2] = {{0.f}, {0.f}};
+#pragma unroll
+            for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int rho = 0; rho < 2; ++rho) {
+                        const h8 aw = *reinterpret_cast<const h8 *>(cur + kOffWn + frag_rts(rho, tau, s) * kFragBytes + lane * 16);
+                        const h8 aq = *reinterpret_cast<const h8 *>(cur + kOffQp + frag_rts(rho, tau, s) * kFragBytes + lane * 16);
+                        av[rho] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aw, Sb[tau][s], av[rho], 0, 0, 0);
+                        ao[rho] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq, Sb[tau][s], ao[rho], 0, 0, 0);
+                    }
+
+            // V_new as B operand
+            h8 Vb[2][2];
+#pragma unroll
+            for (int rho = 0; rho < 2; ++rho)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) Vb[rho][s][e] = (_Float16)av[rho][8 * s + e];
+
+            // O += Tril(A_qk) V_new   (token tile (0,1) of A_qk is zero)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const h8 a00 = *reinterpret_cast<const h8 *>(cur + kOffAqk + frag_aqk(0, 0, s) * kFragBytes + lane * 16);
+                const h8 a10 = *reinterpret_cast<const h8 *>(cur + kOffAqk + frag_aqk(1, 0, s) * kFragBytes + lane * 16);
+                const h8 a11 = *reinterpret_cast<const h8 *>(cur + kOffAqk + frag_aqk(1, 1, s) * kFragBytes + lane * 16);
+                ao[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a00, Vb[0][s], ao[0], 0, 0, 0);
+                ao[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a10, Vb[0][s], ao[1], 0, 0, 0);
+                ao[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a11, Vb[1][s], ao[1], 0, 0, 0);
+            }
+
+            // S <- Diag(gamma^C) S + (Gamma^{i->C}.K)^T V_new
+            {
+                const float *gc = reinterpret_cast<const float *>(cur + kOffGc);
+#pragma unroll
+                for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const f32x4 gv = *reinterpret_cast<const f32x4 *>(gc + 32 * tau + 8 * q4 + 4 * hh);
+#pragma unroll
+                        for (int z = 0; z < 4; ++z) S[tau][4 * q4 + z] *= gv[z];
+                    }
+            }
+#pragma unroll
+            for (int rho = 0; rho < 2; ++rho)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int tau = 0; tau < 4; ++tau) {
+                        const h8 ak = *reinterpret_cast<const h8 *>(cur + kOffKt + frag_trs(tau, rho, s) * kFragBytes + lane * 16);
+                        S[tau] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak, Vb[rho][s], S[tau], 0, 0, 0);
+                    }
+
+            // write O
+            {
+                const int64_t t0 = ci * kChunk;
+#pragma unroll
+                for (int rho = 0; rho < 2; ++rho)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int64_t t = t0 + 32 * rho + acc_row(j, hh);
+                        if (t < len)
+                            o[((tok_base + t) * H + h) * (int64_t)D + 32 * ct + x] = ao[rho][j] * scale;
+                    }
+            }
+
+            // publish the prefetched chunk for the next iteration
+            if (more) {
+                uint8_t *dst = lds + (stage ^ 1) * kLdsBlockBytes;
+#pragma unroll
+                for (int i = 0; i < NPRE; ++i) {
+                    const int u = tid + i * NT;
+                    if (u < UNITS) *reinterpret_cast<u32x4 *>(dst + u * 16) = pre[i];
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    if (state_out && (state_out != state_in || c_begin < c_end)) {
+#pragma unroll
+        for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                state_out[st_base + (int64_t)(32 * tau + acc_row(j, hh)) * D] = S[tau][j];
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// host side
+// ----------------------------------------------------------------------------------
+static int64_t max_chunks_per_seq(const kda_dims *d)
+{
+    int64_t longest = d->seqlen;
+    if (d->num_seqs != d->batch || d->batch == 1) {           // packed (or a single row)
+        if (d->max_seqlen > 0 && d->max_seqlen < longest) longest = d->max_seqlen;
+    }
+    return (longest + kChunk - 1) / kChunk;
+}
+
+static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full)
+{
+    SegPlan p;
+    const int64_t maxc = max_chunks_per_seq(d);
+    const size_t carry = (size_t)d->num_seqs * d->heads * D * D * sizeof(float);
+    const size_t per_chunk_index = (size_t)d->num_seqs * d->heads * kSlotBytes;
+    int64_t sc = maxc;
+    if (!full && per_chunk_index > 0) {
+        const size_t avail = workspace_bytes > carry ? workspace_bytes - carry : 0;
+        const int64_t fit = (int64_t)(avail / per_chunk_index);
+        if (fit < sc) sc = fit;
+    }
+    if (sc < 1) sc = 1;
+    p.seg_chunks = sc;
+    p.num_segments = (maxc + sc - 1) / sc;
+    p.carry_offset = (size_t)sc * per_chunk_index;
+    p.total_bytes = p.carry_offset + carry;
+    return p;
+}
+
+}  // namespace mfma
+
+size_t chunk_mfma_workspace_size(const kda_dims *d, bool minimal)
+{
+    if (d->num_seqs == 0 || d->heads == 0 || d->seqlen == 0) return 0;
+    if (minimal) {
+        // four chunk indices per segment keep the launches from being pure overhead
+        const int64_t maxc = mfma::max_chunks_per_seq(d);
+        const int64_t sc = maxc < 4 ? maxc : 4;
+        return (size_t)sc * d->num_seqs * d->heads * mfma::kSlotBytes +
+               (size_t)d->num_seqs * d->heads * mfma::D * mfma::D * sizeof(float);
+    }
+    return mfma::make_plan(d, 0, true).total_bytes;
+}
 
 kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, const void *v,
                                const void *log_alpha, const void *beta, const float *h0,
-                               const int32_t *cu, void *o, float *hT, void *, size_t,
-                               hipStream_t stream)
+                               const int32_t *cu, void *o, float *hT, void *workspace,
+                               size_t workspace_bytes, hipStream_t stream)
 {
-    return chunk_f32_dispatch(d, q, k, v, log_alpha, beta, h0, cu, o, hT, stream);
+    using namespace mfma;
+    constexpr int NW = 4;
+    if (d->seqlen == 0) {
+        // nothing to scan: the final state is the initial one
+        if (hT && hT != h0) {
+            const size_t bytes = (size_t)d->num_seqs * d->heads * D * D * sizeof(float);
+            hipError_t e = h0 ? hipMemcpyAsync(hT, h0, bytes, hipMemcpyDeviceToDevice, stream)
+                              : hipMemsetAsync(hT, 0, bytes, stream);
+            if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "state copy: %s", hipGetErrorString(e));
+        }
+        return KDA_OK;
+    }
+    const SegPlan plan = make_plan(d, workspace_bytes, false);
+    if (plan.total_bytes > workspace_bytes)
+        return fail(KDA_ERR_WORKSPACE, "workspace has %zu bytes, segment plan needs %zu", workspace_bytes,
+                    plan.total_bytes);
+    const int64_t slots = (int64_t)d->num_seqs * plan.seg_chunks;
+    if (slots * d->heads > 0x7fffffffLL)
+        return fail(KDA_ERR_UNSUPPORTED, "too many (chunk, head) pairs per segment for one launch: %lld",
+                    (long long)(slots * d->heads));
+
+    static bool attr_done = false;
+    const size_t scan_lds = 2 * (size_t)kLdsBlockBytes;
+    if (!attr_done) {
+        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
+        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<NW>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
+        if (e1 != hipSuccess || e2 != hipSuccess)
+            return fail(KDA_ERR_LAUNCH, "cannot reserve LDS for the prefill kernels (%d, %d bytes)", kIntraLds,
+                        (int)scan_lds);
+        attr_done = true;
+    }
+
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    float *carry = hT ? hT : reinterpret_cast<float *>(ws + plan.carry_offset);
+    const uint16_t *q16 = static_cast<const uint16_t *>(q), *k16 = static_cast<const uint16_t *>(k),
+                   *v16 = static_cast<const uint16_t *>(v), *g16 = static_cast<const uint16_t *>(log_alpha),
+                   *b16 = static_cast<const uint16_t *>(beta);
+    for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
+        hipLaunchKernelGGL(kda_intra_kernel, dim3((unsigned)(slots * d->heads)), dim3(256), kIntraLds, stream,
+                           q16, k16, v16, g16, b16, cu, ws, (int64_t)d->seqlen, (int)d->heads,
+                           plan.seg_chunks, seg);
+        const float *sin = (seg == 0) ? h0 : carry;
+        float *sout = (plan.num_segments > 1 || hT) ? carry : nullptr;
+        hipLaunchKernelGGL(kda_scan_kernel<NW>, dim3((unsigned)d->num_seqs, (unsigned)d->heads, 4 / NW),
+                           dim3(NW * 64), scan_lds, stream, ws, sin, sout, cu, static_cast<float *>(o),
+                           (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));
+    return KDA_OK;
 }
 
 }  // namespace kda

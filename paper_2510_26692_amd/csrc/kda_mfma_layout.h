@@ -1,0 +1,67 @@
+// Workspace layout shared by the two kernels of the matrix-core prefill path.
+//
+// kda_intra (parallel over chunks) leaves, for every (chunk, head) "slot", the
+// operands that the sequential kda_scan needs, already arranged in the register
+// order of the 32x32x16 f16 MFMA so that kda_scan moves them with straight
+// 16-byte copies and never transposes anything:
+//
+//   Wn   -W            A operand [token r][dk]      frags [rho][tau][s]      fp16
+//   Qp   Gamma.Q       A operand [token r][dk]      frags [rho][tau][s]      fp16
+//   Kt   (Gamma^{i->C}.K)^T  A operand [dk][token]  frags [tau][rho][s]      fp16
+//   Aqk  Tril(A_qk)    A operand [token r][token i] frags [rho_r][rho_i][s]  fp16
+//   gC   gamma^C       [dk]                                                  fp32
+//   U                  C/D tiles [rho][ct] in accumulator order              fp32
+//
+// rho: 32-token tile, tau: 32-channel d_k tile, ct: 32-column d_v tile, s: one
+// K-step of 16.  A "frag" is 64 lanes x 8 halfs (1 KiB); lane L = (x = L % 32,
+// hh = L / 32) holds row x of the tile and the 8 contraction slots e = 0..7 of
+// K-step s, where slot (hh, e) stands for contraction index
+//
+//       kidx(s, hh, e) = 16 s + 8 (e / 4) + 4 hh + (e % 4)          (0..31)
+//
+// inside the 32-wide tile.  This is the order in which a 32x32 accumulator tile
+// (register j of lane (x, hh) holds row 8 (j/4) + 4 hh + j%4, column x) turns
+// into a B operand with no data movement: registers 8 s .. 8 s + 7 of a lane are
+// exactly its 8 slots of K-step s.  The state S and the pseudo-value V_new live
+// in accumulators and are fed back as B operands that way.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace kda {
+namespace mfma {
+
+constexpr int D = 128;                        // d_k = d_v of this path
+constexpr int kFragBytes = 1024;
+
+constexpr int kOffWn = 0;                     // 16 frags
+constexpr int kOffQp = kOffWn + 16 * kFragBytes;
+constexpr int kOffKt = kOffQp + 16 * kFragBytes;
+constexpr int kOffAqk = kOffKt + 16 * kFragBytes;   // 8 frag positions, (rho_r=0,rho_i=1) unused
+constexpr int kOffGc = kOffAqk + 8 * kFragBytes;
+constexpr int kLdsBlockBytes = kOffGc + D * 4;      // what kda_scan stages through LDS
+constexpr int kOffU = kLdsBlockBytes;               // 8 tiles x 4 KiB
+constexpr int kSlotBytes = kOffU + 8 * 4096;        // 90624
+
+static_assert(kLdsBlockBytes % 16 == 0, "LDS block must be a whole number of 16-byte units");
+static_assert(kSlotBytes % 256 == 0, "slots must stay 256-byte aligned");
+
+// Contraction index inside a 32-wide tile for K-step s, lane half hh, slot e.
+__host__ __device__ constexpr int kidx(int s, int hh, int e) { return 16 * s + 8 * (e >> 2) + 4 * hh + (e & 3); }
+// Row inside a 32x32 accumulator tile held by register j of a lane in half hh.
+__host__ __device__ constexpr int acc_row(int j, int hh) { return 8 * (j >> 2) + 4 * hh + (j & 3); }
+
+constexpr int frag_rts(int r, int t, int s) { return (r * 4 + t) * 2 + s; }   // Wn, Qp: [rho][tau][s]
+constexpr int frag_trs(int t, int r, int s) { return (t * 2 + r) * 2 + s; }   // Kt: [tau][rho][s]
+constexpr int frag_aqk(int rr, int ri, int s) { return (rr * 2 + ri) * 2 + s; }
+
+// Geometry of one launch pair: `seg_chunks` chunk indices of every sequence.
+struct SegPlan {
+    int64_t seg_chunks;      // chunks per sequence held in the workspace at once
+    int64_t num_segments;    // passes over the time axis
+    size_t carry_offset;     // byte offset of the state carry buffer in the workspace
+    size_t total_bytes;
+};
+
+}  // namespace mfma
+}  // namespace kda

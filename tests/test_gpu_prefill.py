@@ -54,3 +54,58 @@ def test_bf16_small(T):
     x = si.make_prefill(2, T, 4, 128, 128, "bf16", -2.0, 31 + T, 0.02)
     eo, eh = check_prefill(x, TOL_BF16)
     print("bf16 T=%d: err_o %.2e err_hT %.2e" % (T, eo, eh))
+
+
+def test_bf16_single_chunk_tail():
+    x = si.make_prefill(1, 37, 2, 128, 128, "bf16", -2.0, 77, 0.02)
+    eo, eh = check_prefill(x, TOL_BF16)
+    print("bf16 T=37: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+def test_bf16_packed_with_empty_sequence():
+    lens = [70, 0, 5, 129, 64, 300]
+    x = si.make_varlen(lens, 3, 128, 128, "bf16", -2.0, 9, 0.05)
+    eo, eh = check_prefill(x, TOL_BF16)
+    print("bf16 packed: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+def test_bf16_strong_decay_takes_the_exact_subchunk_path():
+    """Gates far stronger than the fast operands allow (sub-chunk decay below 2^-11 on
+    most channels, log alpha down to about -20 per token)."""
+    x = si.make_prefill(1, 200, 2, 128, 128, "bf16", 0.0, 21, 0.05)
+    x["log_alpha"] = (x["log_alpha"].float() * 6.0).to(torch.bfloat16).contiguous()
+    assert float(x["log_alpha"].float().min()) < -15.0
+    eo, eh = check_prefill(x, TOL_BF16)
+    print("bf16 strong decay: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+def test_bf16_mixed_decay_mu0():
+    """mu = 0 gate (mean log alpha about -0.8): some channels strong, most not."""
+    x = si.make_prefill(1, 512, 4, 128, 128, "bf16", 0.0, 5, 0.02)
+    eo, eh = check_prefill(x, TOL_BF16)
+    print("bf16 mu=0: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+def test_bf16_segmented_workspace_matches_single_segment():
+    """A workspace of the minimum size forces several time segments with the state
+    carried between them; results must equal the single-segment run bit for bit."""
+    import paper_2510_26692_amd as kda
+    x = si.make_prefill(2, 1000, 2, 128, 128, "bf16", -2.0, 13, 0.02)
+    dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+    dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
+    full = kda.kda_chunk_fwd_workspace_size(dims)
+    small = kda.kda_chunk_fwd_min_workspace_size(dims)
+    assert 0 < small < full
+    o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"])
+    ws = torch.empty(small, dtype=torch.uint8, device="cuda")
+    o2, h2 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                               workspace=ws)
+    # and without hT, so the carry lives in the workspace
+    o3, _ = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                              workspace=ws, want_hT=False)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(h1, h2) and torch.equal(o1, o3)
+    with pytest.raises(kda.KdaError) as ei:
+        kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"],
+                          workspace=torch.empty(small - 256, dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == 3
