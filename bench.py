@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the KDA hot path on one MI355X.
+
+A "step" is one pass of the hot path over one batch of synthetic input: the
+chunkwise prefill (kda_chunk_fwd) on the bf16 prefill workload, and one decode
+step (kda_recurrent_step) over the decode workload's state pool.  The two are
+timed in separate regions of K steps each, inputs resident in HBM, bracketed
+by device synchronisation and measured with HIP events on the launch stream.
+`value` is prefill tokens/s; the decode figures are in the `decode` object.
+
+Prints ONE JSON line.  Runs on one GPU only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# Published MI355X peaks used for the roofline fractions.
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0          # dense fp16/bf16 matrix cores
+
+# Algorithmic work per (token, head) at d_k = d_v = 128, C = 64.
+FLOP_PER_TOKHEAD = 6 * 128 * 128 + 3 * 64 * 128 + 64 * 64        # paper's FLOPs model: 126976
+BYTES_PER_TOKHEAD = (3 * 128 + 128) * 2 + 2 + 128 * 4            # q,k,log_alpha,v,beta bf16 + o fp32: 1538
+
+
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def _time_region(torch, fn, steps):
+    """Time `steps` calls of fn() with HIP events on the current stream; returns ms per call."""
+    torch.cuda.synchronize()
+    a, b = _events(torch)
+    a.record()
+    for _ in range(steps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="cfg1_prefill_bf16",
+                    help="prefill workload: cfg1_prefill_bf16 (default), cfg2_varlen_bf16, cfg3_long_bf16")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth_inputs as si
+    import paper_2510_26692_amd as kda
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    # ------------------------------------------------------------------ prefill workload
+    name = args.workload
+    c = si.CONFIGS[name]
+    if name == "cfg1_prefill_bf16":
+        host = si.make_prefill(c["B"], c["T"], c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"],
+                               c["h0_std"])
+        x = {k_: (v_.to(dev) if isinstance(v_, torch.Tensor) else v_) for k_, v_ in host.items()}
+        tokens = c["B"] * c["T"]
+        desc = {"workload": name, "B": c["B"], "T": c["T"], "H": c["H"], "dk": c["dk"], "dv": c["dv"],
+                "chunk": 64}
+    elif name == "cfg2_varlen_bf16":
+        lens = si.varlen_lengths(c["N"], c["len_lo"], c["len_hi"], c["seed"])
+        host = si.make_varlen(lens, c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"], c["h0_std"])
+        x = {k_: (v_.to(dev) if isinstance(v_, torch.Tensor) else v_) for k_, v_ in host.items()}
+        tokens = int(lens.sum())
+        desc = {"workload": name, "num_seqs": c["N"], "total_tokens": tokens, "H": c["H"], "dk": c["dk"],
+                "dv": c["dv"], "chunk": 64}
+    elif name == "cfg3_long_bf16":
+        host = None
+        x = si.make_long_on_device(c["T"], c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"], dev)
+        x["h0"] = None
+        x["cu_seqlens"] = None
+        tokens = c["T"]
+        desc = {"workload": name, "B": 1, "T": c["T"], "H": c["H"], "dk": c["dk"], "dv": c["dv"], "chunk": 64}
+    else:
+        raise SystemExit("unknown workload " + name)
+    H = c["H"]
+    tokheads = tokens * H
+
+    max_len = int(lens.max()) if name == "cfg2_varlen_bf16" else 0
+    dims = kda.kda.make_chunk_dims(x["q"], x["v"], x["cu_seqlens"], 1.0, max_len)
+    ws_bytes = kda.kda_chunk_fwd_workspace_size(dims)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    o = torch.empty(x["q"].shape[0], x["q"].shape[1], H, c["dv"], dtype=torch.float32, device=dev)
+    hT = torch.empty(dims.num_seqs, H, c["dk"], c["dv"], dtype=torch.float32, device=dev)
+
+    def prefill():
+        kda.kda_chunk_fwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], h0=x["h0"],
+                          cu_seqlens=x["cu_seqlens"], o=o, hT=hT, workspace=ws, max_seqlen=max_len)
+
+    for _ in range(args.warmup):
+        prefill()
+    ms_prefill = _time_region(torch, prefill, args.steps)
+    # per-kernel durations: the same call with one of its two kernels switched off
+    kda.kda_debug_set_phase_mask(1)
+    ms_intra = _time_region(torch, prefill, args.steps)
+    kda.kda_debug_set_phase_mask(2)
+    ms_scan = _time_region(torch, prefill, args.steps)
+    kda.kda_debug_set_phase_mask(3)
+    prefill()
+    torch.cuda.synchronize()
+
+    tok_per_s = tokens / (ms_prefill * 1e-3)
+    dom_name, dom_ms = ("kda_scan_kernel", ms_scan) if ms_scan >= ms_intra else ("kda_intra_kernel", ms_intra)
+    alg_bytes = tokheads * BYTES_PER_TOKHEAD + 2 * dims.num_seqs * H * 128 * 128 * 4
+    roofline = {
+        "kernel": dom_name, "bound": "hbm",
+        "achieved": alg_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": alg_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": None,
+        "ms_kernel": dom_ms,
+        "kernels_ms": {"kda_intra_kernel": ms_intra, "kda_scan_kernel": ms_scan},
+        "whole_call": {
+            "hbm_frac": alg_bytes / (ms_prefill * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "mfma_frac_model_flops": tokheads * FLOP_PER_TOKHEAD / (ms_prefill * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+            "model_tflops": tokheads * FLOP_PER_TOKHEAD / (ms_prefill * 1e-3) / 1e12,
+        },
+    }
+
+    # ------------------------------------------------------------------ decode workload
+    d4 = si.CONFIGS["cfg4_decode_bf16"]
+    N4, H4, dk4, dv4 = d4["N"], d4["H"], d4["dk"], d4["dv"]
+    del ws
+    S = si.make_state(N4, H4, dk4, dv4, d4["state_std"], d4["seed"]).to(dev)
+    tok_host = si.make_decode_tokens(N4, H4, dk4, dv4, d4["dtype"], d4["mu"], d4["seed"], 0)
+    tk = {k_: v_.to(dev) for k_, v_ in tok_host.items()}
+    o4 = torch.empty(N4, H4, dv4, dtype=torch.float32, device=dev)
+
+    def decode():
+        kda.kda_recurrent_step(tk["q"], tk["k"], tk["v"], tk["log_alpha"], tk["beta"], S, o=o4)
+
+    for _ in range(args.warmup):
+        decode()
+    ms_decode = _time_region(torch, decode, args.steps)
+    dec_bytes = 2 * N4 * H4 * dk4 * dv4 * 4 + N4 * H4 * ((3 * dk4 + dv4) * 2 + 2) + N4 * H4 * dv4 * 4
+    decode_obj = {
+        "metric": "decode-step state GB/s", "value": dec_bytes / (ms_decode * 1e-3) / 1e9, "unit": "GB/s",
+        "ms_per_step": ms_decode, "steps": args.steps,
+        "config": {"workload": "cfg4_decode_bf16", "num_seqs": N4, "H": H4, "dk": dk4, "dv": dv4,
+                   "state_bytes": N4 * H4 * dk4 * dv4 * 4},
+        "roofline": {"kernel": "kda_step_kernel", "bound": "hbm",
+                     "achieved": dec_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dec_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None},
+    }
+
+    # ------------------------------------------------------------------ CPU baseline (oracle)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        if host is not None and name == "cfg1_prefill_bf16":
+            a = {k_: si.to_np32(host[k_]) for k_ in ("q", "k", "v", "log_alpha", "beta")}
+            h0 = host["h0"].numpy().astype(np.float64)
+            t0 = time.perf_counter()
+            oracle.kda_forward(a["q"], a["k"], a["v"], a["log_alpha"], a["beta"], h0=h0)
+            dt = time.perf_counter() - t0
+            sample_tokens = tokens
+            sample = "whole %s workload (%d tokens x %d heads), fp64 per-token recurrence" % (name, tokens, H)
+        else:
+            # bounded sample: the first 4096 tokens of every head
+            n_s = min(4096, tokens)
+            a = {k_: si.to_np32(x[k_][:, :n_s]) for k_ in ("q", "k", "v", "log_alpha", "beta")}
+            t0 = time.perf_counter()
+            oracle.kda_forward(a["q"], a["k"], a["v"], a["log_alpha"], a["beta"])
+            dt = time.perf_counter() - t0
+            sample_tokens = n_s
+            sample = "first %d tokens of %s x %d heads, fp64 per-token recurrence" % (n_s, name, H)
+        cpu = {"value": sample_tokens / dt, "unit": "tokens/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": sample, "seconds": dt}
+        Sh = S.cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        oracle.kda_step(si.to_np32(tok_host["q"]), si.to_np32(tok_host["k"]), si.to_np32(tok_host["v"]),
+                        si.to_np32(tok_host["log_alpha"]), si.to_np32(tok_host["beta"]), Sh)
+        dt4 = time.perf_counter() - t0
+        decode_obj["cpu_baseline"] = {"value": dec_bytes / dt4 / 1e9, "unit": "GB/s",
+                                      "cores": oracle.num_threads(), "kind": "oracle",
+                                      "sample": "one decode step over the whole cfg4 state pool, fp64",
+                                      "seconds": dt4}
+
+    out = {
+        "metric": "KDA prefill tokens/s", "value": tok_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_prefill,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 matrix-core operands (bf16 inputs), f32 accumulate/state",
+        "data": "synthetic",
+        "config": desc,
+        "tokheads_per_s": tokheads / (ms_prefill * 1e-3),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "decode": decode_obj,
+        "error_metric": "max|x-ref|/max|ref| per (sequence, head); parity is gated in tests/",
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -137,6 +137,14 @@ const char *kda_status_string(kda_status status);
 /* Detail of the last error raised on the calling thread ("" if none). */
 const char *kda_last_error(void);
 
+/*
+ * Diagnostics for per-kernel timing only: selects which kernels of the
+ * matrix-core prefill run on later kda_chunk_fwd calls (bit 0: the per-chunk
+ * kernel, bit 1: the sequential scan; default 3).  With a bit cleared the
+ * outputs of that call are incomplete.  Process-wide, not thread-safe.
+ */
+void kda_debug_set_phase_mask(int mask);
+
 /* Library version string, e.g. "kda-gfx950 0.1". */
 const char *kda_version(void);
 

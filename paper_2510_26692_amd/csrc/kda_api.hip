@@ -32,6 +32,9 @@ kda_status chunk_mfma_dispatch(const kda_dims *, const void *, const void *, con
                                float *, void *, size_t, hipStream_t);
 size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal);
 
+// Diagnostics: which kernels of the matrix-core prefill run (bit 0 kda_intra, bit 1 kda_scan).
+int g_phase_mask = 3;
+
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Checks shared by both entry points.  Returns KDA_OK or the failure code.
@@ -76,6 +79,8 @@ using namespace kda;
 extern "C" {
 
 const char *kda_version(void) { return "kda-gfx950 0.1"; }
+
+void kda_debug_set_phase_mask(int mask) { g_phase_mask = mask & 3; }
 
 const char *kda_last_error(void) { return g_last_error; }
 

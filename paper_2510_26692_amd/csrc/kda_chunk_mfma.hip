@@ -28,6 +28,9 @@
 #include "kda_mfma_layout.h"
 
 namespace kda {
+
+extern int g_phase_mask;   // diagnostics switch owned by kda_api.hip
+
 namespace mfma {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -744,9 +747,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
         return fail(KDA_ERR_UNSUPPORTED, "too many (chunk, head) pairs per segment for one launch: %lld",
                     (long long)(slots * d->heads));
 
-    static bool attr_done = false;
     const size_t scan_lds = 2 * (size_t)kLdsBlockBytes;
-    if (!attr_done) {
+    {
         hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
         hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<NW>),
@@ -754,7 +756,6 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
         if (e1 != hipSuccess || e2 != hipSuccess)
             return fail(KDA_ERR_LAUNCH, "cannot reserve LDS for the prefill kernels (%d, %d bytes)", kIntraLds,
                         (int)scan_lds);
-        attr_done = true;
     }
 
     uint8_t *ws = static_cast<uint8_t *>(workspace);
@@ -763,14 +764,16 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
                    *v16 = static_cast<const uint16_t *>(v), *g16 = static_cast<const uint16_t *>(log_alpha),
                    *b16 = static_cast<const uint16_t *>(beta);
     for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
-        hipLaunchKernelGGL(kda_intra_kernel, dim3((unsigned)(slots * d->heads)), dim3(256), kIntraLds, stream,
-                           q16, k16, v16, g16, b16, cu, ws, (int64_t)d->seqlen, (int)d->heads,
-                           plan.seg_chunks, seg);
+        if (g_phase_mask & 1)
+            hipLaunchKernelGGL(kda_intra_kernel, dim3((unsigned)(slots * d->heads)), dim3(256), kIntraLds,
+                               stream, q16, k16, v16, g16, b16, cu, ws, (int64_t)d->seqlen, (int)d->heads,
+                               plan.seg_chunks, seg);
         const float *sin = (seg == 0) ? h0 : carry;
         float *sout = (plan.num_segments > 1 || hT) ? carry : nullptr;
-        hipLaunchKernelGGL(kda_scan_kernel<NW>, dim3((unsigned)d->num_seqs, (unsigned)d->heads, 4 / NW),
-                           dim3(NW * 64), scan_lds, stream, ws, sin, sout, cu, static_cast<float *>(o),
-                           (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale);
+        if (g_phase_mask & 2)
+            hipLaunchKernelGGL(kda_scan_kernel<NW>, dim3((unsigned)d->num_seqs, (unsigned)d->heads, 4 / NW),
+                               dim3(NW * 64), scan_lds, stream, ws, sin, sout, cu, static_cast<float *>(o),
+                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));

@@ -58,6 +58,8 @@ def load_library():
     lib.kda_chunk_fwd_min_workspace_size.argtypes = [dp]
     lib.kda_chunk_fwd.restype = ctypes.c_int
     lib.kda_chunk_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kda_debug_set_phase_mask.restype = None
+    lib.kda_debug_set_phase_mask.argtypes = [ctypes.c_int]
     lib.kda_recurrent_step.restype = ctypes.c_int
     lib.kda_recurrent_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
@@ -70,6 +72,10 @@ def kda_version():
 
 def kda_last_error():
     return load_library().kda_last_error().decode()
+
+
+def kda_debug_set_phase_mask(mask):
+    load_library().kda_debug_set_phase_mask(int(mask))
 
 
 def kda_status_string(status):
