@@ -44,41 +44,33 @@ constexpr float kStrongLog2 = 11.0f;   // sub-chunk decay below 2^-11 leaves the
 constexpr float kRowScale = 16.0f;     // keeps small row operands out of the fp16 subnormals
 
 // ----------------------------------------------------------------------------------
-// LDS map of kda_intra (bytes).  Two phases share the space.
+// LDS map of kda_intra (bytes).  Regions are reused as the phases advance; the whole
+// map stays under 80 KiB so that two workgroups share a compute unit.
 // ----------------------------------------------------------------------------------
-constexpr int kLdH = 136;                               // halfs per row of a [*][128] fp16 tile
+constexpr int kLdH = 136;                               // halfs per row of a [64][128] fp16 tile
 constexpr int kTileH = 64 * kLdH * 2;                   // 17408 B
-// phase A: operands of the A-matrix products
-constexpr int kRowK = 0;
-constexpr int kRowQ = kRowK + kTileH;
-constexpr int kColKd = kRowQ + kTileH;
-constexpr int kColK = kColKd + kTileH;                  // [6][16][136] halfs
-constexpr int kColKBytes = 6 * 16 * kLdH * 2;           // 26112
-// phase A, only when a strong channel exists: exact data for the pairwise fix-up
-constexpr int kLdG = 132;                               // floats per row of the fp32 G tile
-constexpr int kGl = kColK + kColKBytes;                 // fp32 [64][132]
-constexpr int kKraw = kGl + 64 * kLdG * 4;              // bf16 [64][136]
-constexpr int kQraw = kKraw + kTileH;
-constexpr int kSmall = kQraw + kTileH;
-// phase B (aliases phase A)
 constexpr int kLdF = 68;                                // floats per row of a [64][64] fp32 tile
 constexpr int kTileF = 64 * kLdF * 4;                   // 17408 B
-constexpr int kL = 0;                                   // fp32 L = StrictTril(Diag(beta) A_kk)
-constexpr int kAq = kL + kTileF;                        // fp32 Tril(A_qk)
-constexpr int kX = kAq + kTileF;                        // fp32 (I + L)^-1
-constexpr int kLdM = 72;                                // halfs per row of the fp16 M tile
-constexpr int kM = kX + kTileF;                         // fp16 [64][72]
-constexpr int kV = kM + 64 * kLdM * 2;                  // fp16 [64][136]
-constexpr int kGK = kV + kTileH;
-constexpr int kQp = kGK + kTileH;
-constexpr int kKp = kQp + kTileH;
-static_assert(kKp + kTileH <= kSmall, "phase B tiles must not reach the small region");
-// small region (lives through both phases)
-constexpr int kTot = kSmall;                            // fp32 [4][128] sub-chunk log2-decay totals
+constexpr int kLdM = 72;                                // halfs per row of a [64][64] fp16 tile
+constexpr int kTileM = 64 * kLdM * 2;                   // 9216 B
+
+constexpr int kX = 0;                                   // fp32 (I + L)^-1
+constexpr int kTab = kX;                                //   early alias: per-channel constants, 5 x [4][128] fp32
+constexpr int kFix = kTab + 5 * 2048;                   //   early alias: scratch of the strong-channel fix-up
+constexpr int kL = kX + kTileF;                         // fp32 L = StrictTril(Diag(beta) A_kk)
+constexpr int kAq = kL + kTileF;                        // fp16 Tril(A_qk)
+constexpr int kColS = kL;                               //   early alias: column operands [6 tiles][4][64] x 16 B
+constexpr int kV = kL;                                  //   late alias: fp16 V tile
+constexpr int kGK = kAq + kTileM;                       // fp16 Gamma.K
+constexpr int kKp = kGK + kTileH;                       // fp16 Gamma^{i->C}.K
+constexpr int kM = kKp;                                 //   late alias: fp16 M
+constexpr int kTot = kKp + kTileH;                      // fp32 [4][128] sub-chunk log2-decay totals
 constexpr int kBeta = kTot + 4 * 128 * 4;               // fp32 [64]
-constexpr int kStrong = kBeta + 64 * 4;                 // u64 [4][2] strong-channel masks
+constexpr int kStrong = kBeta + 64 * 4;                 // u32 [4][4] strong-channel masks per (sub-chunk, g)
 constexpr int kIntraLds = kStrong + 64;
-static_assert(kIntraLds <= 160 * 1024, "kda_intra exceeds the 160 KiB of LDS");
+static_assert(kFix + 4 * 4 * 16 * 3 * 4 <= kL, "early aliases must fit under X");
+static_assert(kColS + 6 * 4 * 64 * 16 <= kGK, "early aliases must fit under L and A_qk");
+static_assert(kIntraLds <= 80 * 1024, "kda_intra must leave room for two workgroups per CU");
 
 __device__ __forceinline__ uint32_t pack_h2(float a, float b)
 {
@@ -86,10 +78,19 @@ __device__ __forceinline__ uint32_t pack_h2(float a, float b)
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// lane i of each row of 16 lanes receives the value of lane i - N (0 when there is none)
+template <int N> __device__ __forceinline__ float row_shr(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x110 + N, 0xf, 0xf, true));
+}
+
 // ----------------------------------------------------------------------------------
 // kda_intra
 // ----------------------------------------------------------------------------------
-__global__ __launch_bounds__(256)
+// Lane (m = lane % 16, g = lane / 16) of wave R owns token 16 R + m and the 32 channels
+// 32 ks + 8 g + e (ks = 0..3, e = 0..7): exactly its A/B operand slots of the 16x16x32 MFMA,
+// so the decay-scaled operands of the A-matrix products are built in registers.
+__global__ __launch_bounds__(256, 2)
 void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
                       const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
                       const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
@@ -113,32 +114,280 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     float *sTot = reinterpret_cast<float *>(lds + kTot);
     float *sBeta = reinterpret_cast<float *>(lds + kBeta);
-    uint64_t *sStrong = reinterpret_cast<uint64_t *>(lds + kStrong);
+    uint32_t *sStrong = reinterpret_cast<uint32_t *>(lds + kStrong);
+    float *sTab = reinterpret_cast<float *>(lds + kTab);     // [5][4][128]: P, E, Tinv, iA, iB
 
-    // ---- loads.  Thread (c = lane, R = wave) owns channels 2c, 2c+1 of sub-chunk R. ----
-    const int R = wave, c = lane;
-    uint32_t k2[16], q2[16];
-    float G0[16], G1[16];
-    {
-        float run0 = 0.f, run1 = 0.f;
+    const int R = wave, m = lane & 15, g = lane >> 4;
+    const int tok = 16 * R + m;
+
+    // ---- loads: 16 bytes (8 channels) per ks and tensor ----
+    u32x4 kraw[4], qraw[4], graw[4];
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const int tok = 16 * R + t;
-            uint32_t kk = 0, qq = 0, gg = 0;
-            if (tok < nv) {
-                const int64_t off = ((tok0 + tok) * H + h) * (int64_t)D + 2 * c;
-                kk = *reinterpret_cast<const uint32_t *>(k + off);
-                qq = *reinterpret_cast<const uint32_t *>(q + off);
-                gg = *reinterpret_cast<const uint32_t *>(log_alpha + off);
-            }
-            k2[t] = kk; q2[t] = qq;
-            float g0, g1;
-            unpack_bf16x2(gg, g0, g1);
-            run0 = fmaf(g0, kLog2e, run0); run1 = fmaf(g1, kLog2e, run1);
-            G0[t] = run0; G1[t] = run1;                  // inclusive, local to the sub-chunk, log2 units
+    for (int ks = 0; ks < 4; ++ks) {
+        u32x4 z = {0, 0, 0, 0};
+        kraw[ks] = z; qraw[ks] = z; graw[ks] = z;
+        if (tok < nv) {
+            const int64_t off = ((tok0 + tok) * H + h) * (int64_t)D + 32 * ks + 8 * g;
+            kraw[ks] = *reinterpret_cast<const u32x4 *>(k + off);
+            qraw[ks] = *reinterpret_cast<const u32x4 *>(q + off);
+            graw[ks] = *reinterpret_cast<const u32x4 *>(log_alpha + off);
         }
     }
-    const float tot0 = G0[15], tot1 = G1[15];
+    if (tid < kChunk)
+        sBeta[tid] = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
+
+    // ---- G: running sum of log2(alpha) over the 16 tokens of the sub-chunk (lanes of a row) ----
+    float G[32];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            float a, b;
+            unpack_bf16x2(graw[ks][w], a, b);
+            a *= kLog2e; b *= kLog2e;
+            a += row_shr<1>(a); b += row_shr<1>(b);
+            a += row_shr<2>(a); b += row_shr<2>(b);
+            a += row_shr<4>(a); b += row_shr<4>(b);
+            a += row_shr<8>(a); b += row_shr<8>(b);
+            G[ks * 8 + 2 * w] = a; G[ks * 8 + 2 * w + 1] = b;
+        }
+    if (m == 15) {          // the last token of the sub-chunk holds its totals
+        uint32_t smask = 0;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            f32x4 t0 = {G[ks * 8 + 0], G[ks * 8 + 1], G[ks * 8 + 2], G[ks * 8 + 3]};
+            f32x4 t1 = {G[ks * 8 + 4], G[ks * 8 + 5], G[ks * 8 + 6], G[ks * 8 + 7]};
+            *reinterpret_cast<f32x4 *>(sTot + R * 128 + 32 * ks + 8 * g) = t0;
+            *reinterpret_cast<f32x4 *>(sTot + R * 128 + 32 * ks + 8 * g + 4) = t1;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (G[ks * 8 + e] < -kStrongLog2) smask |= 1u << (ks * 8 + e);
+        }
+        sStrong[R * 4 + g] = smask;
+    }
+    __syncthreads();                                                               // B1
+
+    // ---- per-channel constants of sub-chunk R, two channels per lane ----
+    {
+        const int c2 = 2 * lane;
+        float t0[4], t1[4];
+#pragma unroll
+        for (int J = 0; J < 4; ++J) {
+            const float2 x = *reinterpret_cast<const float2 *>(sTot + J * 128 + c2);
+            t0[J] = x.x; t1[J] = x.y;
+        }
+        float pre0 = 0.f, pre1 = 0.f, post0 = 0.f, post1 = 0.f;
+#pragma unroll
+        for (int J = 0; J < 4; ++J) {
+            if (J < R) { pre0 += t0[J]; pre1 += t1[J]; }
+            if (J > R) { post0 += t0[J]; post1 += t1[J]; }
+        }
+        const int r1 = (R + 1) & 3, r2 = (R + 2) & 3;        // R+1, R+2 (only used when they exist)
+        float *tb = sTab + R * 128 + c2;
+        *reinterpret_cast<float2 *>(tb + 0 * 512) = make_float2(fast_exp2(pre0), fast_exp2(pre1));
+        *reinterpret_cast<float2 *>(tb + 1 * 512) = make_float2(fast_exp2(post0), fast_exp2(post1));
+        *reinterpret_cast<float2 *>(tb + 2 * 512) = make_float2(fast_exp2(-t0[R]), fast_exp2(-t1[R]));
+        *reinterpret_cast<float2 *>(tb + 3 * 512) = make_float2(fast_exp2(t0[r1]), fast_exp2(t1[r1]));
+        *reinterpret_cast<float2 *>(tb + 4 * 512) = make_float2(fast_exp2(t0[r1] + t0[r2]), fast_exp2(t1[r1] + t1[r2]));
+        if (R == 0) {   // gamma^C: decay of the whole chunk
+            float2 gc = make_float2(fast_exp2(t0[0] + t0[1] + t0[2] + t0[3]), fast_exp2(t1[0] + t1[1] + t1[2] + t1[3]));
+            *reinterpret_cast<float2 *>(out + kOffGc + c2 * 4) = gc;
+        }
+    }
+    uint32_t strong_all = 0;        // union over g of this sub-chunk's strong-channel slots
+    {
+        const uint32_t s0 = sStrong[R * 4 + 0], s1 = sStrong[R * 4 + 1], s2 = sStrong[R * 4 + 2],
+                       s3 = sStrong[R * 4 + 3];
+        strong_all = s0 | s1 | s2 | s3;
+    }
+    const uint32_t strong_mine = sStrong[R * 4 + g];
+    __syncthreads();                                                               // B2
+
+    // ---- operands, built in registers ----
+    h8 rowK[4], rowQ[4], colKd[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        float kf[8], qf[8];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            unpack_bf16x2(kraw[ks][w], kf[2 * w], kf[2 * w + 1]);
+            unpack_bf16x2(qraw[ks][w], qf[2 * w], qf[2 * w + 1]);
+        }
+        const int cb = R * 128 + 32 * ks + 8 * g;
+        float tot[8], P[8], E[8], Ti[8], iA[8], iB[8];
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            const f32x4 a = *reinterpret_cast<const f32x4 *>(sTot + cb + 4 * hf);
+            const f32x4 b = *reinterpret_cast<const f32x4 *>(sTab + 0 * 512 + cb + 4 * hf);
+            const f32x4 c = *reinterpret_cast<const f32x4 *>(sTab + 1 * 512 + cb + 4 * hf);
+            const f32x4 d = *reinterpret_cast<const f32x4 *>(sTab + 2 * 512 + cb + 4 * hf);
+#pragma unroll
+            for (int z = 0; z < 4; ++z) { tot[4 * hf + z] = a[z]; P[4 * hf + z] = b[z]; E[4 * hf + z] = c[z]; Ti[4 * hf + z] = d[z]; }
+            if (R <= 1) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(sTab + 3 * 512 + cb + 4 * hf);
+#pragma unroll
+                for (int z = 0; z < 4; ++z) iA[4 * hf + z] = x[z];
+            }
+            if (R == 0) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(sTab + 4 * 512 + cb + 4 * hf);
+#pragma unroll
+                for (int z = 0; z < 4; ++z) iB[4 * hf + z] = x[z];
+            }
+        }
+        float rk[8], rq[8], cs[8], cd[8], gk[8], qp[8], kp[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float Ge = G[ks * 8 + e];
+            const float rf = fast_exp2(Ge);                       // 2^(G_r - G_ref(R)), <= 1
+            const float sf = fast_exp2(tot[e] - Ge);              // decay from this token to the end of R
+            const bool strong = (strong_mine >> (ks * 8 + e)) & 1u;
+            rk[e] = kf[e] * rf * kRowScale;
+            rq[e] = qf[e] * rf * kRowScale;
+            cs[e] = kf[e] * sf;
+            cd[e] = strong ? 0.f : cs[e] * Ti[e];                 // k 2^(-G_i)
+            gk[e] = kf[e] * rf * P[e];                            // Gamma . K
+            qp[e] = qf[e] * rf * P[e];                            // Gamma . Q
+            kp[e] = cs[e] * E[e];                                 // Gamma^{i->C} . K
+        }
+        u32x4 t;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) t[w] = pack_h2(rk[2 * w], rk[2 * w + 1]);
+        rowK[ks] = __builtin_bit_cast(h8, t);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) t[w] = pack_h2(rq[2 * w], rq[2 * w + 1]);
+        rowQ[ks] = __builtin_bit_cast(h8, t);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) t[w] = pack_h2(cd[2 * w], cd[2 * w + 1]);
+        colKd[ks] = __builtin_bit_cast(h8, t);
+        // column operands for the sub-chunks below: tile (Rp, R) splits the decay at the boundary in
+        // front of sub-chunk Rp, so the part across the sub-chunks in between rides on the columns
+        if (R < 3) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) t[w] = pack_h2(cs[2 * w], cs[2 * w + 1]);
+            *reinterpret_cast<u32x4 *>(lds + kColS + ((((R + 1) * R / 2 + R) * 4 + ks) * 64 + lane) * 16) = t;
+        }
+        if (R < 2) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) t[w] = pack_h2(cs[2 * w] * iA[2 * w], cs[2 * w + 1] * iA[2 * w + 1]);
+            *reinterpret_cast<u32x4 *>(lds + kColS + ((((R + 2) * (R + 1) / 2 + R) * 4 + ks) * 64 + lane) * 16) = t;
+        }
+        if (R < 1) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) t[w] = pack_h2(cs[2 * w] * iB[2 * w], cs[2 * w + 1] * iB[2 * w + 1]);
+            *reinterpret_cast<u32x4 *>(lds + kColS + ((((R + 3) * (R + 2) / 2 + R) * 4 + ks) * 64 + lane) * 16) = t;
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) t[w] = pack_h2(gk[2 * w], gk[2 * w + 1]);
+        *reinterpret_cast<u32x4 *>(lds + kGK + (tok * kLdH + 32 * ks + 8 * g) * 2) = t;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) t[w] = pack_h2(kp[2 * w], kp[2 * w + 1]);
+        *reinterpret_cast<u32x4 *>(lds + kKp + (tok * kLdH + 32 * ks + 8 * g) * 2) = t;
+        // Gamma.Q goes straight to the workspace in MFMA register order: lanes g and g^1 swap one
+        // 4-channel piece each so that every lane ends up with a complete 16-byte slot
+        {
+            const uint32_t a0 = pack_h2(qp[0], qp[1]), a1 = pack_h2(qp[2], qp[3]);
+            const uint32_t b0 = pack_h2(qp[4], qp[5]), b1 = pack_h2(qp[6], qp[7]);
+            const bool odd = g & 1;
+            const uint32_t r0 = __shfl_xor(odd ? a0 : b0, 16), r1 = __shfl_xor(odd ? a1 : b1, 16);
+            u32x4 o4;
+            if (odd) { o4[0] = r0; o4[1] = r1; o4[2] = b0; o4[3] = b1; }
+            else     { o4[0] = a0; o4[1] = a1; o4[2] = r0; o4[3] = r1; }
+            *reinterpret_cast<u32x4 *>(out + kOffQp + frag_rts(tok >> 5, ks, g >> 1) * kFragBytes +
+                                       ((tok & 31) + 32 * (g & 1)) * 16) = o4;
+        }
+    }
+
+    // ---- A_kk, A_qk tiles of sub-chunk row R on the matrix cores (16x16, K = 128) ----
+    f32x4 res_kk[4], res_qk[4];              // index I = 0..R
+    {
+        f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            akk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowK[ks], colKd[ks], akk, 0, 0, 0);
+            aqk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowQ[ks], colKd[ks], aqk, 0, 0, 0);
+        }
+        akk *= (1.0f / kRowScale);
+        aqk *= (1.0f / kRowScale);
+        if (strong_all) {
+            // channels left out of colKd: exact pairwise terms 2^(G_r - G_i) in fp32.  For each
+            // register slot with a strong channel the 64 lanes drop (G, k, q) of that slot into a
+            // small scratch indexed [g][token]; every lane then reads column m and its four rows.
+            float *fix = reinterpret_cast<float *>(lds + kFix) + wave * (4 * 16 * 3);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if ((strong_all >> (ks * 8 + e)) & 1u) {
+                        const uint32_t kw = kraw[ks][e >> 1], qw = qraw[ks][e >> 1];
+                        const float kfe = (e & 1) ? __uint_as_float(kw & 0xffff0000u) : __uint_as_float(kw << 16);
+                        const float qfe = (e & 1) ? __uint_as_float(qw & 0xffff0000u) : __uint_as_float(qw << 16);
+                        __builtin_amdgcn_wave_barrier();
+                        fix[(g * 16 + m) * 3 + 0] = G[ks * 8 + e];
+                        fix[(g * 16 + m) * 3 + 1] = kfe;
+                        fix[(g * 16 + m) * 3 + 2] = qfe;
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                        for (int gg = 0; gg < 4; ++gg) {
+                            if ((sStrong[R * 4 + gg] >> (ks * 8 + e)) & 1u) {
+                                const float Gi = fix[(gg * 16 + m) * 3 + 0], ki = fix[(gg * 16 + m) * 3 + 1];
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    const int rr = 4 * g + j;
+                                    if (rr >= m) {
+                                        const float t = ki * fast_exp2(fix[(gg * 16 + rr) * 3 + 0] - Gi);
+                                        akk[j] = fmaf(fix[(gg * 16 + rr) * 3 + 1], t, akk[j]);
+                                        aqk[j] = fmaf(fix[(gg * 16 + rr) * 3 + 2], t, aqk[j]);
+                                    }
+                                }
+                            }
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    }
+                }
+        }
+        res_kk[R] = akk; res_qk[R] = aqk;
+    }
+    __syncthreads();                                                               // B3 (colS visible)
+#pragma unroll
+    for (int I = 0; I < 3; ++I) {
+        if (I < R) {
+            f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const h8 b = *reinterpret_cast<const h8 *>(lds + kColS + (((R * (R - 1) / 2 + I) * 4 + ks) * 64 + lane) * 16);
+                akk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowK[ks], b, akk, 0, 0, 0);
+                aqk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowQ[ks], b, aqk, 0, 0, 0);
+            }
+            res_kk[I] = akk * (1.0f / kRowScale);
+            res_qk[I] = aqk * (1.0f / kRowScale);
+        }
+    }
+    __syncthreads();                                                               // B4 (early aliases dead)
+
+    // ---- L and Tril(A_qk) tiles of row R; fp16 V tile ----
+    {
+        float *sL = reinterpret_cast<float *>(lds + kL);
+        _Float16 *sAq = reinterpret_cast<_Float16 *>(lds + kAq);
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            const int i = 16 * I + m;                       // column token of this lane
+            if (I <= R) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 16 * R + 4 * g + j;
+                    sL[r * kLdF + i] = (i < r) ? sBeta[r] * res_kk[I][j] : 0.f;
+                    sAq[r * kLdM + i] = (_Float16)((i <= r) ? res_qk[I][j] : 0.f);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sAq[(16 * R + 4 * g + j) * kLdM + i] = (_Float16)0.f;
+            }
+        }
+    }
+    __syncthreads();                                                               // B5
+
+    // V is fetched now; its latency hides behind the UT transform
     u32x4 vraw[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -148,188 +397,6 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             x = *reinterpret_cast<const u32x4 *>(v + ((tok0 + tokv) * H + h) * (int64_t)D + 8 * cg);
         vraw[i] = x;
     }
-    *reinterpret_cast<float2 *>(sTot + R * 128 + 2 * c) = make_float2(tot0, tot1);
-    const bool strong0 = tot0 < -kStrongLog2, strong1 = tot1 < -kStrongLog2;
-    {
-        const uint64_t b0 = __ballot(strong0), b1 = __ballot(strong1);
-        if (lane == 0) { sStrong[R * 2 + 0] = b0; sStrong[R * 2 + 1] = b1; }
-    }
-    if (tid < kChunk)
-        sBeta[tid] = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
-    __syncthreads();                                                               // B1
-
-    // ---- phase A operands ----
-    float tt0[4], tt1[4];
-#pragma unroll
-    for (int J = 0; J < 4; ++J) {
-        const float2 x = *reinterpret_cast<const float2 *>(sTot + J * 128 + 2 * c);
-        tt0[J] = x.x; tt1[J] = x.y;
-    }
-    float pre0 = 0.f, pre1 = 0.f, post0 = 0.f, post1 = 0.f;
-#pragma unroll
-    for (int J = 0; J < 4; ++J) {
-        if (J < R) { pre0 += tt0[J]; pre1 += tt1[J]; }
-        if (J > R) { post0 += tt0[J]; post1 += tt1[J]; }
-    }
-    bool strong_any = false;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) strong_any |= (sStrong[i] != 0);
-    // decay between the end of sub-chunk R and the start of sub-chunk R+2 / R+3
-    const float interA0 = (R + 1 < 4) ? fast_exp2(tt0[(R + 1) & 3]) : 0.f;
-    const float interA1 = (R + 1 < 4) ? fast_exp2(tt1[(R + 1) & 3]) : 0.f;
-    const float interB0 = (R + 2 < 4) ? fast_exp2(tt0[(R + 1) & 3] + tt0[(R + 2) & 3]) : 0.f;
-    const float interB1 = (R + 2 < 4) ? fast_exp2(tt1[(R + 1) & 3] + tt1[(R + 2) & 3]) : 0.f;
-
-    float RF0[16], RF1[16], SF0[16], SF1[16];            // kept for phase B
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {
-        const int tok = 16 * R + t;
-        float k0, k1, q0, q1;
-        unpack_bf16x2(k2[t], k0, k1);
-        unpack_bf16x2(q2[t], q0, q1);
-        const float rf0 = fast_exp2(G0[t]), rf1 = fast_exp2(G1[t]);          // 2^(G_r - G_ref(R))
-        const float sf0 = fast_exp2(tot0 - G0[t]), sf1 = fast_exp2(tot1 - G1[t]);  // to the end of R
-        const float in0 = strong0 ? 0.f : fast_exp2(-G0[t]);
-        const float in1 = strong1 ? 0.f : fast_exp2(-G1[t]);
-        RF0[t] = rf0; RF1[t] = rf1; SF0[t] = sf0; SF1[t] = sf1;
-        const int at = (tok * kLdH + 2 * c) * 2;
-        *reinterpret_cast<uint32_t *>(lds + kRowK + at) = pack_h2(k0 * rf0 * kRowScale, k1 * rf1 * kRowScale);
-        *reinterpret_cast<uint32_t *>(lds + kRowQ + at) = pack_h2(q0 * rf0 * kRowScale, q1 * rf1 * kRowScale);
-        *reinterpret_cast<uint32_t *>(lds + kColKd + at) = pack_h2(k0 * in0, k1 * in1);
-        const float ks0 = k0 * sf0, ks1 = k1 * sf1;
-        // column operand of tile (Rp, R), Rp > R: reference in front of sub-chunk Rp
-        if (R + 1 < 4) {
-            const int pid = (R + 1) * R / 2 + R;
-            *reinterpret_cast<uint32_t *>(lds + kColK + ((pid * 16 + t) * kLdH + 2 * c) * 2) = pack_h2(ks0, ks1);
-        }
-        if (R + 2 < 4) {
-            const int pid = (R + 2) * (R + 1) / 2 + R;
-            *reinterpret_cast<uint32_t *>(lds + kColK + ((pid * 16 + t) * kLdH + 2 * c) * 2) =
-                pack_h2(ks0 * interA0, ks1 * interA1);
-        }
-        if (R + 3 < 4) {
-            const int pid = (R + 3) * (R + 2) / 2 + R;
-            *reinterpret_cast<uint32_t *>(lds + kColK + ((pid * 16 + t) * kLdH + 2 * c) * 2) =
-                pack_h2(ks0 * interB0, ks1 * interB1);
-        }
-        if (strong_any) {
-            *reinterpret_cast<float2 *>(lds + kGl + (tok * kLdG + 2 * c) * 4) = make_float2(G0[t], G1[t]);
-            *reinterpret_cast<uint32_t *>(lds + kKraw + at) = k2[t];
-            *reinterpret_cast<uint32_t *>(lds + kQraw + at) = q2[t];
-        }
-    }
-    if (R == 0) {   // gamma^C: decay of the whole chunk
-        float2 gc = make_float2(fast_exp2(tt0[0] + tt0[1] + tt0[2] + tt0[3]),
-                                fast_exp2(tt1[0] + tt1[1] + tt1[2] + tt1[3]));
-        *reinterpret_cast<float2 *>(out + kOffGc + 2 * c * 4) = gc;
-    }
-    __syncthreads();                                                               // B2
-
-    // ---- A_kk, A_qk tiles (16x16, K = 128) on the matrix cores ----
-    // tiles per wave: w0 (3,0)(3,1)(0,0)  w1 (3,2)(3,3)  w2 (2,0)(2,1)(2,2)  w3 (1,0)(1,1)
-    const int nt = (wave & 1) ? 2 : 3;
-    const int tR[3] = {wave == 3 ? 1 : (wave == 2 ? 2 : 3), wave == 3 ? 1 : (wave == 2 ? 2 : 3),
-                       wave == 0 ? 0 : 2};
-    const int tI[3] = {wave == 1 ? 2 : 0, wave == 1 ? 3 : 1, wave == 0 ? 0 : 2};
-    f32x4 res_kk[3], res_qk[3];
-    {
-        const int m = lane & 15, g = lane >> 4;
-#pragma unroll
-        for (int ti = 0; ti < 3; ++ti) {
-            f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
-            if (ti < nt) {
-                const int Rr = tR[ti], Ii = tI[ti];
-                const int rowoff = ((16 * Rr + m) * kLdH + 8 * g) * 2;
-                const int coloff = (Ii == Rr) ? kColKd + rowoff
-                                              : kColK + (((Rr * (Rr - 1) / 2 + Ii) * 16 + m) * kLdH + 8 * g) * 2;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const h8 ak = *reinterpret_cast<const h8 *>(lds + kRowK + rowoff + ks * 64);
-                    const h8 aq = *reinterpret_cast<const h8 *>(lds + kRowQ + rowoff + ks * 64);
-                    const h8 b = *reinterpret_cast<const h8 *>(lds + coloff + ks * 64);
-                    akk = __builtin_amdgcn_mfma_f32_16x16x32_f16(ak, b, akk, 0, 0, 0);
-                    aqk = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, b, aqk, 0, 0, 0);
-                }
-                akk *= (1.0f / kRowScale);
-                aqk *= (1.0f / kRowScale);
-                if (Ii == Rr && strong_any) {
-                    // exact pairwise terms of the channels that were left out of colKd
-                    const float *sG = reinterpret_cast<const float *>(lds + kGl);
-                    const uint16_t *sKr = reinterpret_cast<const uint16_t *>(lds + kKraw);
-                    const uint16_t *sQr = reinterpret_cast<const uint16_t *>(lds + kQraw);
-                    for (int half = 0; half < 2; ++half) {
-                        uint64_t mask = sStrong[Rr * 2 + half];
-                        while (mask) {
-                            const int bit = __builtin_ctzll(mask);
-                            mask &= mask - 1;
-                            const int ch = 2 * bit + half;
-                            const int ic = 16 * Rr + m;                      // column token
-                            const float Gi = sG[ic * kLdG + ch];
-                            const float ki = bf16_bits_to_float(sKr[ic * kLdH + ch]);
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const int rr = 4 * g + j;
-                                if (rr >= m) {
-                                    const int ir = 16 * Rr + rr;
-                                    const float e = fast_exp2(sG[ir * kLdG + ch] - Gi);
-                                    const float t = ki * e;
-                                    akk[j] = fmaf(bf16_bits_to_float(sKr[ir * kLdH + ch]), t, akk[j]);
-                                    aqk[j] = fmaf(bf16_bits_to_float(sQr[ir * kLdH + ch]), t, aqk[j]);
-                                }
-                            }
-                        }
-                    }
-                }
-            }
-            res_kk[ti] = akk; res_qk[ti] = aqk;
-        }
-    }
-    __syncthreads();                                                               // B3
-
-    // ---- phase B tiles: L, Tril(A_qk), Gamma.K, Gamma.Q, Gamma^{i->C}.K, V ----
-    {
-        float *sL = reinterpret_cast<float *>(lds + kL);
-        float *sAq = reinterpret_cast<float *>(lds + kAq);
-        const int m = lane & 15, g = lane >> 4;
-#pragma unroll
-        for (int ti = 0; ti < 3; ++ti) {
-            if (ti < nt) {
-                const int i = 16 * tI[ti] + m;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int r = 16 * tR[ti] + 4 * g + j;
-                    sL[r * kLdF + i] = (i < r) ? sBeta[r] * res_kk[ti][j] : 0.f;
-                    sAq[r * kLdF + i] = (i <= r) ? res_qk[ti][j] : 0.f;
-                }
-            }
-        }
-        const float P0 = fast_exp2(pre0), P1 = fast_exp2(pre1);      // Gamma at the start of sub-chunk R
-        const float E0 = fast_exp2(post0), E1 = fast_exp2(post1);    // decay from its end to the chunk end
-#pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            float k0, k1, q0, q1;
-            unpack_bf16x2(k2[t], k0, k1);
-            unpack_bf16x2(q2[t], q0, q1);
-            const float gam0 = RF0[t] * P0, gam1 = RF1[t] * P1;
-            const int at = ((16 * R + t) * kLdH + 2 * c) * 2;
-            *reinterpret_cast<uint32_t *>(lds + kGK + at) = pack_h2(k0 * gam0, k1 * gam1);
-            *reinterpret_cast<uint32_t *>(lds + kQp + at) = pack_h2(q0 * gam0, q1 * gam1);
-            *reinterpret_cast<uint32_t *>(lds + kKp + at) = pack_h2(k0 * SF0[t] * E0, k1 * SF1[t] * E1);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
-            u32x4 x;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                float a, b;
-                unpack_bf16x2(vraw[i][w], a, b);
-                x[w] = pack_h2(a, b);
-            }
-            *reinterpret_cast<u32x4 *>(lds + kV + (tokv * kLdH + 8 * cg) * 2) = x;
-        }
-    }
-    __syncthreads();                                                               // B4
 
     // ---- UT transform, diagonal 16x16 blocks: column j of (I + L_ww)^-1 per lane ----
     {
@@ -350,42 +417,31 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             for (int r = 0; r < 16; ++r) sX[(16 * w + r) * kLdF + 16 * w + j] = x[r];
         }
     }
-    // ---- copy Gamma.Q and (Gamma^{i->C}.K)^T out in MFMA register order ----
+    // ---- copy (Gamma^{i->C}.K)^T out in MFMA register order ----
     {
         const int x = lane & 31, hh = lane >> 5;
+        const uint16_t *sKp = reinterpret_cast<const uint16_t *>(lds + kKp);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int f = wave * 4 + i;
-            {   // Qp frag f = (rho*4 + tau)*2 + s
-                const int rho = f >> 3, tau = (f >> 1) & 3, s = f & 1;
-                const int at = ((32 * rho + x) * kLdH + 32 * tau + 16 * s + 4 * hh) * 2;
-                const u32x2 a = *reinterpret_cast<const u32x2 *>(lds + kQp + at);
-                const u32x2 b = *reinterpret_cast<const u32x2 *>(lds + kQp + at + 16);
-                u32x4 o4 = {a[0], a[1], b[0], b[1]};
-                *reinterpret_cast<u32x4 *>(out + kOffQp + f * kFragBytes + lane * 16) = o4;
-            }
-            {   // Kt frag f = (tau*2 + rho)*2 + s
-                const int tau = f >> 2, rho = (f >> 1) & 1, s = f & 1;
-                const uint16_t *sKp = reinterpret_cast<const uint16_t *>(lds + kKp);
-                uint32_t w4[4];
+            const int f = wave * 4 + i;                     // Kt frag f = (tau*2 + rho)*2 + s
+            const int tau = f >> 2, rho = (f >> 1) & 1, s = f & 1;
+            uint32_t w4[4];
 #pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const int t0 = 32 * rho + kidx(s, hh, e), t1 = 32 * rho + kidx(s, hh, e + 1);
-                    w4[e >> 1] = (uint32_t)sKp[t0 * kLdH + 32 * tau + x] |
-                                 ((uint32_t)sKp[t1 * kLdH + 32 * tau + x] << 16);
-                }
-                u32x4 o4 = {w4[0], w4[1], w4[2], w4[3]};
-                *reinterpret_cast<u32x4 *>(out + kOffKt + f * kFragBytes + lane * 16) = o4;
+            for (int e = 0; e < 8; e += 2) {
+                const int t0 = 32 * rho + kidx(s, hh, e), t1 = 32 * rho + kidx(s, hh, e + 1);
+                w4[e >> 1] = (uint32_t)sKp[t0 * kLdH + 32 * tau + x] |
+                             ((uint32_t)sKp[t1 * kLdH + 32 * tau + x] << 16);
             }
+            u32x4 o4 = {w4[0], w4[1], w4[2], w4[3]};
+            *reinterpret_cast<u32x4 *>(out + kOffKt + f * kFragBytes + lane * 16) = o4;
         }
     }
-    __syncthreads();                                                               // B5
+    __syncthreads();                                                               // B6
 
     // ---- UT transform, off-diagonal blocks: X_RI = -X_RR sum_{I<=J<R} L_RJ X_JI (fp32 MFMA) ----
     {
         const float *sL = reinterpret_cast<const float *>(lds + kL);
         float *sX = reinterpret_cast<float *>(lds + kX);
-        const int m = lane & 15, g = lane >> 4;
         for (int Rr = 1; Rr < 4; ++Rr) {
             if (wave < Rr) {
                 const int Ii = wave;
@@ -409,11 +465,11 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 #pragma unroll
                 for (int j = 0; j < 4; ++j) sX[(16 * Rr + 4 * g + j) * kLdF + 16 * Ii + m] = -r[j];
             }
-            __syncthreads();                                                       // B6
+            __syncthreads();                                                       // B7
         }
     }
 
-    // ---- M = X Diag(beta) as fp16; Tril(A_qk) out in MFMA register order ----
+    // ---- M = X Diag(beta) as fp16 (over the dead K' tile); Tril(A_qk) out; V tile (over L) ----
     {
         const float *sX = reinterpret_cast<const float *>(lds + kX);
         _Float16 *sM = reinterpret_cast<_Float16 *>(lds + kM);
@@ -424,26 +480,30 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             else if (j == r) val = sBeta[j];
             sM[r * kLdM + j] = (_Float16)val;
         }
-        const float *sAq = reinterpret_cast<const float *>(lds + kAq);
         const int x = lane & 31, hh = lane >> 5;
         for (int idx = wave; idx < 6; idx += 4) {
             const int p = idx >> 1, s = idx & 1;
             const int rr = (p == 0) ? 0 : 1, ri = (p == 2) ? 1 : 0;
-            const int r = 32 * rr + x;
-            const int i0 = 32 * ri + 16 * s + 4 * hh;
-            const f32x4 a = *reinterpret_cast<const f32x4 *>(sAq + r * kLdF + i0);
-            const f32x4 b = *reinterpret_cast<const f32x4 *>(sAq + r * kLdF + i0 + 8);
-            float e[8];
-#pragma unroll
-            for (int z = 0; z < 4; ++z) {
-                e[z] = (i0 + z <= r) ? a[z] : 0.f;
-                e[4 + z] = (i0 + 8 + z <= r) ? b[z] : 0.f;
-            }
-            u32x4 o4 = {pack_h2(e[0], e[1]), pack_h2(e[2], e[3]), pack_h2(e[4], e[5]), pack_h2(e[6], e[7])};
+            const int at = ((32 * rr + x) * kLdM + 32 * ri + 16 * s + 4 * hh) * 2;
+            const u32x2 a = *reinterpret_cast<const u32x2 *>(lds + kAq + at);
+            const u32x2 b = *reinterpret_cast<const u32x2 *>(lds + kAq + at + 16);
+            u32x4 o4 = {a[0], a[1], b[0], b[1]};
             *reinterpret_cast<u32x4 *>(out + kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16) = o4;
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+            u32x4 y;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float a, b;
+                unpack_bf16x2(vraw[i][w], a, b);
+                y[w] = pack_h2(a, b);
+            }
+            *reinterpret_cast<u32x4 *>(lds + kV + (tokv * kLdH + 8 * cg) * 2) = y;
+        }
     }
-    __syncthreads();                                                               // B7
+    __syncthreads();                                                               // B8
 
     // ---- W^T = (Gamma.K)^T M^T (wave = d_k tile) and U = M V (wave = d_v tile) ----
     {

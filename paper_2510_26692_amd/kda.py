@@ -9,7 +9,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libkda.so")
+# KDA_LIBRARY_PATH lets a developer point the binding at another build of the same library.
+_LIB_PATH = os.environ.get("KDA_LIBRARY_PATH") or os.path.join(_HERE, "libkda.so")
 _lib = None
 
 KDA_F32, KDA_BF16 = 0, 1
