@@ -24,6 +24,9 @@
 // split at the sub-chunk's start, which makes the column factor 2^(-G_i) >= 1; a
 // channel whose decay across the sub-chunk exceeds 2^-kStrongLog2 is taken out of
 // those operands and added back exactly, pair by pair, in fp32.
+#include <stdlib.h>
+#include <type_traits>
+
 #include "kda_common.h"
 #include "kda_mfma_layout.h"
 
@@ -95,7 +98,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
                       const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
                       uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
-                      int64_t seg_index)
+                      int64_t seg_index, float scale)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -246,7 +249,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             cs[e] = kf[e] * sf;
             cd[e] = strong ? 0.f : cs[e] * Ti[e];                 // k 2^(-G_i)
             gk[e] = kf[e] * rf * P[e];                            // Gamma . K
-            qp[e] = qf[e] * rf * P[e];                            // Gamma . Q
+            qp[e] = qf[e] * rf * (P[e] * scale);                  // scale * Gamma . Q
             kp[e] = cs[e] * E[e];                                 // Gamma^{i->C} . K
         }
         u32x4 t;
@@ -377,7 +380,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 for (int j = 0; j < 4; ++j) {
                     const int r = 16 * R + 4 * g + j;
                     sL[r * kLdF + i] = (i < r) ? sBeta[r] * res_kk[I][j] : 0.f;
-                    sAq[r * kLdM + i] = (_Float16)((i <= r) ? res_qk[I][j] : 0.f);
+                    sAq[r * kLdM + i] = (_Float16)((i <= r) ? res_qk[I][j] * scale : 0.f);
                 }
             } else {
 #pragma unroll
@@ -557,16 +560,59 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 // ----------------------------------------------------------------------------------
 // kda_scan
 // ----------------------------------------------------------------------------------
+// One wave owns a 32-column slice of S for a whole sequence.  Per chunk it issues 54 MFMAs
+// (32x32x16) whose LDS-resident operands (W, Gamma.Q, A_qk, decayed K) are read a few MFMAs
+// ahead of their use through a small register ring; S and V_new are converted in registers
+// into the other operand.  The two O products are issued with the operands swapped, so the
+// accumulator holds O^T and a lane owns 4 consecutive columns of a token's output row.  The
+// next chunk's operand block goes from the workspace to LDS with LDS-direct loads while the
+// current chunk computes.  With one wave per SIMD every instruction issues from the same
+// wave, so the loop is written to keep the instruction count per chunk low.
+#define KDA_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+namespace scan {
+// compile-time loop: f(integral_constant<int, I>) for I in [0, N)
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// MFMA slots of one chunk, in issue order.
+//   0..31  stage B: group tau = i / 8; within a group s = (i % 8) / 4, then W rho0, W rho1, Q rho0, Q rho1
+//   32..37 stage C: A_qk (0,0,s0) (1,0,s0) (0,0,s1) (1,0,s1) (1,1,s0) (1,1,s1)
+//   38..53 stage D: rho = (i - 38) / 8, s = ((i - 38) % 8) / 4, tau = (i - 38) % 4
+constexpr int kSlots = 54;
+constexpr int slot_lds_offset(int i)
+{
+    if (i < 32) {
+        const int tau = i / 8, s = (i % 8) / 4, k = i % 4, rho = k & 1;
+        return ((k < 2) ? kOffWn : kOffQp) + frag_rts(rho, tau, s) * kFragBytes;
+    }
+    if (i < 38) {
+        const int j = i - 32;
+        const int rr = (j == 0 || j == 2) ? 0 : 1, ri = (j >= 4) ? 1 : 0, s = (j < 4) ? (j / 2) : (j - 4);
+        return kOffAqk + frag_aqk(rr, ri, s) * kFragBytes;
+    }
+    const int j = i - 38, rho = j / 8, s = (j % 8) / 4, tau = j % 4;
+    return kOffKt + frag_trs(tau, rho, s) * kFragBytes;
+}
+}  // namespace scan
+
 template <int NW>
 __global__ __launch_bounds__(NW * 64)
 void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, float *state_out,
                      const int32_t *__restrict__ cu_seqlens, float *__restrict__ o, int64_t T, int H,
-                     int64_t seg_chunks, int64_t seg_index, float scale)
+                     int64_t seg_chunks, int64_t seg_index)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    constexpr int NT = NW * 64;
-    constexpr int UNITS = kLdsBlockBytes / 16;
-    constexpr int NPRE = (UNITS + NT - 1) / NT;
+    constexpr int UNITS = kLdsBlockBytes / 16;           // 16-byte units per staged block
+    constexpr int NCOPY = (UNITS + 63) / 64;             // wave-wide copy instructions per block
+    constexpr int LA = 8, RING = 10;                     // operand look-ahead (MFMA slots) and ring size
+    constexpr int STAGE = kLdsBlockBytes + NW * 8192;    // shared operand block + one 8 KiB U slice per wave
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int x = lane & 31, hh = lane >> 5;
     const int n = blockIdx.x, h = blockIdx.y;
@@ -582,145 +628,145 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
     // state slice in accumulator order: S[tau][j] = S(dk = 32 tau + acc_row(j, hh), dv = 32 ct + x)
     const int64_t st_base = ((int64_t)n * H + h) * (int64_t)(D * D) + 32 * ct + x;
     f32x16 S[4];
+    if (state_in) {
 #pragma unroll
-    for (int tau = 0; tau < 4; ++tau)
+        for (int tau = 0; tau < 4; ++tau)
 #pragma unroll
-        for (int j = 0; j < 16; ++j)
-            S[tau][j] = state_in ? state_in[st_base + (int64_t)(32 * tau + acc_row(j, hh)) * D] : 0.f;
+            for (int j = 0; j < 16; ++j)
+                S[tau][j] = state_in[st_base + (int64_t)(32 * tau + acc_row(j, hh)) * D];
+    } else {
+#pragma unroll
+        for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) S[tau][j] = 0.f;
+    }
 
     if (c_begin < c_end) {
         const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks) * H + h) * (int64_t)kSlotBytes;
         const int64_t slot_stride = (int64_t)H * kSlotBytes;
+        const uint32_t lane16 = (uint32_t)lane * 16;
+        const uint32_t u_src = (uint32_t)(kOffU + ct * 4096);           // U tile (0, ct) inside a slot
+        const uint32_t u_lds = (uint32_t)(kLdsBlockBytes + wave * 8192);   // this wave's U slice inside a stage
 
-        // prologue: stage the first chunk, fetch its U tiles
-        f32x16 un[2];
-        {
-            const uint8_t *src = slot0;
-            for (int u = tid; u < UNITS; u += NT)
-                *reinterpret_cast<u32x4 *>(lds + u * 16) = *reinterpret_cast<const u32x4 *>(src + u * 16);
+        // workspace block -> LDS stage, 1 KiB per wave instruction, instructions dealt round robin
+        auto stage_in = [&](const uint8_t *src, int stage) {
 #pragma unroll
-            for (int rho = 0; rho < 2; ++rho)
+            for (int i = 0; i < (NCOPY + NW - 1) / NW; ++i) {
+                const int c = wave + i * NW;
+                if (c < NCOPY && c * 64 + lane < UNITS)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(src + c * 1024 + lane16),
+                        (__attribute__((address_space(3))) void *)(lds + stage * STAGE + c * 1024),
+                        16, 0, 0);
+            }
+            // this wave's two U tiles (rho = 0, 1), 4 KiB each
 #pragma unroll
-                for (int j4 = 0; j4 < 4; ++j4) {
-                    const f32x4 t = *reinterpret_cast<const f32x4 *>(src + kOffU + (((rho * 4 + ct) * 4 + j4) * 64 + lane) * 16);
-                    un[rho][4 * j4] = t[0]; un[rho][4 * j4 + 1] = t[1];
-                    un[rho][4 * j4 + 2] = t[2]; un[rho][4 * j4 + 3] = t[3];
-                }
-        }
+            for (int i = 0; i < 8; ++i)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(src + u_src + (i >> 2) * 16384 + (i & 3) * 1024 + lane16),
+                    (__attribute__((address_space(3))) void *)(lds + stage * STAGE + u_lds + i * 1024), 16, 0, 0);
+        };
+
+        stage_in(slot0, 0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): the LDS-direct loads have landed
         __syncthreads();
+
+        const uint32_t o_rstride = (uint32_t)H * D * 4;      // bytes between consecutive tokens of o
+        // O^T accumulator: lane (token 32 rho + x, hh), registers 4q..4q+3 = columns 32 ct + 8 q + 4 hh + 0..3
+        const uint32_t o_lane = (uint32_t)x * o_rstride + (uint32_t)(32 * ct + 4 * hh) * 4;
 
         for (int64_t ci = c_begin; ci < c_end; ++ci) {
             const int stage = (int)((ci - c_begin) & 1);
-            const uint8_t *cur = lds + stage * kLdsBlockBytes;
+            const uint8_t *cur = lds + stage * STAGE + lane16;
+            const float *gc = reinterpret_cast<const float *>(lds + stage * STAGE + kOffGc) + 4 * hh;
             const bool more = ci + 1 < c_end;
             const uint8_t *nxt = slot0 + (ci + 1 - c_begin) * slot_stride;
 
-            // prefetch the next chunk while this one computes
-            u32x4 pre[NPRE];
-            f32x16 av[2] = {un[0], un[1]};
-            if (more) {
+            if (more) stage_in(nxt, stage ^ 1);
+
+            // accumulators of V_new start from U
+            f32x16 av[2], ao[2] = {{0.f}, {0.f}};
 #pragma unroll
-                for (int i = 0; i < NPRE; ++i) {
-                    const int u = tid + i * NT;
-                    if (u < UNITS) pre[i] = *reinterpret_cast<const u32x4 *>(nxt + u * 16);
+            for (int i = 0; i < 8; ++i) {
+                const f32x4 t = *reinterpret_cast<const f32x4 *>(cur + u_lds + i * 1024);
+#pragma unroll
+                for (int z = 0; z < 4; ++z) av[i >> 2][4 * (i & 3) + z] = t[z];
+            }
+
+            h8 ring[RING];
+            h8 Sb[4][2], Vb[2][2];
+#pragma unroll
+            for (int i = 0; i < LA; ++i)
+                ring[i % RING] = *reinterpret_cast<const h8 *>(cur + scan::slot_lds_offset(i));
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) Sb[0][s][e] = (_Float16)S[0][8 * s + e];
+
+            scan::static_for<0, scan::kSlots>([&](auto ic) __attribute__((always_inline)) {
+                constexpr int i = decltype(ic)::value;
+                if constexpr (i + LA < scan::kSlots)
+                    ring[(i + LA) % RING] = *reinterpret_cast<const h8 *>(cur + scan::slot_lds_offset(i + LA));
+                const h8 a = ring[i % RING];
+                if constexpr (i < 32) {
+                    // V_new = U + (-W) S ; O^T = S^T (Gamma.Q)^T
+                    constexpr int tau = i / 8, s = (i % 8) / 4, k = i % 4, rho = k & 1;
+                    if constexpr (k < 2) av[rho] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Sb[tau][s], av[rho], 0, 0, 0);
+                    else       ao[rho] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Sb[tau][s], a, ao[rho], 0, 0, 0);
+                    if constexpr (i % 8 == 1 && tau < 3) {
+                        // fp16 copy of the next d_k tile of S, in the shadow of this group's MFMAs
+#pragma unroll
+                        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) Sb[tau + 1][s2][e] = (_Float16)S[tau + 1][8 * s2 + e];
+                    }
+                    if constexpr (i % 8 == 5) {
+                        // S <- Diag(gamma^C) S for the tile whose fp16 copy is already taken
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const f32x4 gv = *reinterpret_cast<const f32x4 *>(gc + 32 * tau + 8 * q4);
+#pragma unroll
+                            for (int z = 0; z < 4; ++z) S[tau][4 * q4 + z] *= gv[z];
+                        }
+                    }
+                    if constexpr (i == 31) {
+#pragma unroll
+                        for (int rho2 = 0; rho2 < 2; ++rho2)
+#pragma unroll
+                            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) Vb[rho2][s2][e] = (_Float16)av[rho2][8 * s2 + e];
+                    }
+                } else if constexpr (i < 38) {
+                    // O^T += V_new^T Tril(A_qk)^T
+                    constexpr int j = i - 32;
+                    constexpr int rr = (j == 0 || j == 2) ? 0 : 1, ri = (j >= 4) ? 1 : 0, s = (j < 4) ? (j / 2) : (j - 4);
+                    ao[rr] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Vb[ri][s], a, ao[rr], 0, 0, 0);
+                } else {
+                    // S += (Gamma^{i->C}.K)^T V_new
+                    constexpr int j = i - 38, rho = j / 8, s = (j % 8) / 4, tau = j % 4;
+                    S[tau] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Vb[rho][s], S[tau], 0, 0, 0);
                 }
-#pragma unroll
-                for (int rho = 0; rho < 2; ++rho)
-#pragma unroll
-                    for (int j4 = 0; j4 < 4; ++j4) {
-                        const f32x4 t = *reinterpret_cast<const f32x4 *>(nxt + kOffU + (((rho * 4 + ct) * 4 + j4) * 64 + lane) * 16);
-                        un[rho][4 * j4] = t[0]; un[rho][4 * j4 + 1] = t[1];
-                        un[rho][4 * j4 + 2] = t[2]; un[rho][4 * j4 + 3] = t[3];
-                    }
-            }
+                KDA_FENCE();   // keeps each operand read LA slots ahead of its MFMA
+            });
 
-            // S as B operand: registers 8s..8s+7 of tile tau are the slots of K-step (tau, s)
-            h8 Sb[4][2];
-#pragma unroll
-            for (int tau = 0; tau < 4; ++tau)
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) Sb[tau][s][e] = (_Float16)S[tau][8 * s + e];
-
-            // V_new = U + (-W) S   and   O = (Gamma.Q) S
-            f32x16 ao[2] = {{0.f}, {0.f}};
-#pragma unroll
-            for (int tau = 0; tau < 4; ++tau)
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int rho = 0; rho < 2; ++rho) {
-                        const h8 aw = *reinterpret_cast<const h8 *>(cur + kOffWn + frag_rts(rho, tau, s) * kFragBytes + lane * 16);
-                        const h8 aq = *reinterpret_cast<const h8 *>(cur + kOffQp + frag_rts(rho, tau, s) * kFragBytes + lane * 16);
-                        av[rho] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aw, Sb[tau][s], av[rho], 0, 0, 0);
-                        ao[rho] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aq, Sb[tau][s], ao[rho], 0, 0, 0);
-                    }
-
-            // V_new as B operand
-            h8 Vb[2][2];
-#pragma unroll
-            for (int rho = 0; rho < 2; ++rho)
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) Vb[rho][s][e] = (_Float16)av[rho][8 * s + e];
-
-            // O += Tril(A_qk) V_new   (token tile (0,1) of A_qk is zero)
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const h8 a00 = *reinterpret_cast<const h8 *>(cur + kOffAqk + frag_aqk(0, 0, s) * kFragBytes + lane * 16);
-                const h8 a10 = *reinterpret_cast<const h8 *>(cur + kOffAqk + frag_aqk(1, 0, s) * kFragBytes + lane * 16);
-                const h8 a11 = *reinterpret_cast<const h8 *>(cur + kOffAqk + frag_aqk(1, 1, s) * kFragBytes + lane * 16);
-                ao[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a00, Vb[0][s], ao[0], 0, 0, 0);
-                ao[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a10, Vb[0][s], ao[1], 0, 0, 0);
-                ao[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a11, Vb[1][s], ao[1], 0, 0, 0);
-            }
-
-            // S <- Diag(gamma^C) S + (Gamma^{i->C}.K)^T V_new
-            {
-                const float *gc = reinterpret_cast<const float *>(cur + kOffGc);
-#pragma unroll
-                for (int tau = 0; tau < 4; ++tau)
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const f32x4 gv = *reinterpret_cast<const f32x4 *>(gc + 32 * tau + 8 * q4 + 4 * hh);
-#pragma unroll
-                        for (int z = 0; z < 4; ++z) S[tau][4 * q4 + z] *= gv[z];
-                    }
-            }
-#pragma unroll
-            for (int rho = 0; rho < 2; ++rho)
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int tau = 0; tau < 4; ++tau) {
-                        const h8 ak = *reinterpret_cast<const h8 *>(cur + kOffKt + frag_trs(tau, rho, s) * kFragBytes + lane * 16);
-                        S[tau] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak, Vb[rho][s], S[tau], 0, 0, 0);
-                    }
-
-            // write O
+            // write O (fp32, already scaled): 16 bytes per store
             {
                 const int64_t t0 = ci * kChunk;
+                uint8_t *obase = reinterpret_cast<uint8_t *>(o + ((tok_base + t0) * H + h) * (int64_t)D);
 #pragma unroll
-                for (int rho = 0; rho < 2; ++rho)
+                for (int rho = 0; rho < 2; ++rho) {
+                    if (t0 + 32 * rho + x < len) {
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const int64_t t = t0 + 32 * rho + acc_row(j, hh);
-                        if (t < len)
-                            o[((tok_base + t) * H + h) * (int64_t)D + 32 * ct + x] = ao[rho][j] * scale;
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            f32x4 val = {ao[rho][4 * q4], ao[rho][4 * q4 + 1], ao[rho][4 * q4 + 2], ao[rho][4 * q4 + 3]};
+                            *reinterpret_cast<f32x4 *>(obase + (o_lane + (uint32_t)(32 * rho) * o_rstride + 32 * q4)) = val;
+                        }
                     }
-            }
-
-            // publish the prefetched chunk for the next iteration
-            if (more) {
-                uint8_t *dst = lds + (stage ^ 1) * kLdsBlockBytes;
-#pragma unroll
-                for (int i = 0; i < NPRE; ++i) {
-                    const int u = tid + i * NT;
-                    if (u < UNITS) *reinterpret_cast<u32x4 *>(dst + u * 16) = pre[i];
                 }
             }
+            KDA_FENCE();
+            __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): next block is in LDS (this wave's part)
             __syncthreads();
         }
     }
@@ -787,7 +833,6 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
                                size_t workspace_bytes, hipStream_t stream)
 {
     using namespace mfma;
-    constexpr int NW = 4;
     if (d->seqlen == 0) {
         // nothing to scan: the final state is the initial one
         if (hT && hT != h0) {
@@ -807,12 +852,20 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
         return fail(KDA_ERR_UNSUPPORTED, "too many (chunk, head) pairs per segment for one launch: %lld",
                     (long long)(slots * d->heads));
 
-    const size_t scan_lds = 2 * (size_t)kLdsBlockBytes;
+    // wavefronts per scan workgroup (each owns a 32-column slice of S); KDA_SCAN_NW overrides for tuning
+    int nw = 2;
+    if (const char *env = getenv("KDA_SCAN_NW")) {
+        const int v = atoi(env);
+        if (v == 1 || v == 2) nw = v;
+    }
+    const size_t scan_lds = 2 * ((size_t)kLdsBlockBytes + (size_t)nw * 8192);
     {
         hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
-        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<NW>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
+        hipError_t e2 = (nw == 2) ? hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<2>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds)
+                                  : hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<1>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
         if (e1 != hipSuccess || e2 != hipSuccess)
             return fail(KDA_ERR_LAUNCH, "cannot reserve LDS for the prefill kernels (%d, %d bytes)", kIntraLds,
                         (int)scan_lds);
@@ -827,13 +880,19 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
         if (g_phase_mask & 1)
             hipLaunchKernelGGL(kda_intra_kernel, dim3((unsigned)(slots * d->heads)), dim3(256), kIntraLds,
                                stream, q16, k16, v16, g16, b16, cu, ws, (int64_t)d->seqlen, (int)d->heads,
-                               plan.seg_chunks, seg);
+                               plan.seg_chunks, seg, d->scale);
         const float *sin = (seg == 0) ? h0 : carry;
         float *sout = (plan.num_segments > 1 || hT) ? carry : nullptr;
-        if (g_phase_mask & 2)
-            hipLaunchKernelGGL(kda_scan_kernel<NW>, dim3((unsigned)d->num_seqs, (unsigned)d->heads, 4 / NW),
-                               dim3(NW * 64), scan_lds, stream, ws, sin, sout, cu, static_cast<float *>(o),
-                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale);
+        if (g_phase_mask & 2) {
+            const dim3 grid((unsigned)d->num_seqs, (unsigned)d->heads, (unsigned)(4 / nw));
+            float *op = static_cast<float *>(o);
+            if (nw == 2)
+                hipLaunchKernelGGL(kda_scan_kernel<2>, grid, dim3(128), scan_lds, stream, ws, sin, sout, cu, op,
+                                   (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg);
+            else
+                hipLaunchKernelGGL(kda_scan_kernel<1>, grid, dim3(64), scan_lds, stream, ws, sin, sout, cu, op,
+                                   (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg);
+        }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));
