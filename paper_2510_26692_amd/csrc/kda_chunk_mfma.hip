@@ -648,23 +648,28 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
         const uint32_t u_src = (uint32_t)(kOffU + ct * 4096);           // U tile (0, ct) inside a slot
         const uint32_t u_lds = (uint32_t)(kLdsBlockBytes + wave * 8192);   // this wave's U slice inside a stage
 
-        // workspace block -> LDS stage, 1 KiB per wave instruction, instructions dealt round robin
-        auto stage_in = [&](const uint8_t *src, int stage) {
-#pragma unroll
-            for (int i = 0; i < (NCOPY + NW - 1) / NW; ++i) {
-                const int c = wave + i * NW;
+        // workspace block -> LDS stage with LDS-direct loads of 1 KiB per wave instruction.  A wave owns
+        // the block pieces wave, wave + NW, ... and its own two U tiles: kCopies instructions in all.
+        // Issued in one burst they would stall the wave on the address FIFO, so inside the chunk loop
+        // they are spread over the MFMA slots.
+        constexpr int kBlkCopies = (NCOPY + NW - 1) / NW, kCopies = kBlkCopies + 8;
+        auto stage_copy = [&](const uint8_t *src, int stage, int idx) __attribute__((always_inline)) {
+            if (idx < kBlkCopies) {
+                const int c = wave + idx * NW;
                 if (c < NCOPY && c * 64 + lane < UNITS)
                     __builtin_amdgcn_global_load_lds(
                         (const __attribute__((address_space(1))) void *)(src + c * 1024 + lane16),
-                        (__attribute__((address_space(3))) void *)(lds + stage * STAGE + c * 1024),
-                        16, 0, 0);
-            }
-            // this wave's two U tiles (rho = 0, 1), 4 KiB each
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
+                        (__attribute__((address_space(3))) void *)(lds + stage * STAGE + c * 1024), 16, 0, 0);
+            } else {
+                const int i = idx - kBlkCopies;              // U tile rho = i / 4, quarter i % 4
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void *)(src + u_src + (i >> 2) * 16384 + (i & 3) * 1024 + lane16),
                     (__attribute__((address_space(3))) void *)(lds + stage * STAGE + u_lds + i * 1024), 16, 0, 0);
+            }
+        };
+        auto stage_in = [&](const uint8_t *src, int stage) {
+#pragma unroll
+            for (int idx = 0; idx < kCopies; ++idx) stage_copy(src, stage, idx);
         };
 
         stage_in(slot0, 0);
@@ -681,8 +686,6 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
             const float *gc = reinterpret_cast<const float *>(lds + stage * STAGE + kOffGc) + 4 * hh;
             const bool more = ci + 1 < c_end;
             const uint8_t *nxt = slot0 + (ci + 1 - c_begin) * slot_stride;
-
-            if (more) stage_in(nxt, stage ^ 1);
 
             // accumulators of V_new start from U
             f32x16 av[2], ao[2] = {{0.f}, {0.f}};
@@ -705,6 +708,13 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
 
             scan::static_for<0, scan::kSlots>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value;
+                // next chunk's block: a few LDS-direct loads per slot, all issued by slot 40
+                constexpr int kPer = (kCopies + 39) / 40;
+                static_assert(kPer <= 2, "at most two copies per slot are written out below");
+                if (more) {
+                    if constexpr (i * kPer < kCopies) stage_copy(nxt, stage ^ 1, i * kPer);
+                    if constexpr (kPer > 1 && i * kPer + 1 < kCopies) stage_copy(nxt, stage ^ 1, i * kPer + 1);
+                }
                 if constexpr (i + LA < scan::kSlots)
                     ring[(i + LA) % RING] = *reinterpret_cast<const h8 *>(cur + scan::slot_lds_offset(i + LA));
                 const h8 a = ring[i % RING];
