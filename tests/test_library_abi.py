@@ -1,0 +1,121 @@
+"""CPU-side checks: the C-ABI library loads, exports what include/kda.h declares, and
+rejects malformed calls without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lib():
+    import paper_2510_26692_amd as kda
+    if not os.path.exists(kda.library_path()):
+        from paper_2510_26692_amd import build
+        build.build(verbose=False)
+    return kda, kda.load_library()
+
+
+def test_every_declared_symbol_is_exported():
+    kda, lib = _lib()
+    header = open(os.path.join(ROOT, "include", "kda.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(kda_[a-z_0-9]+)\s*\(", header))
+    assert {"kda_chunk_fwd", "kda_recurrent_step", "kda_chunk_fwd_workspace_size",
+            "kda_chunk_fwd_min_workspace_size", "kda_status_string", "kda_last_error",
+            "kda_version", "kda_debug_set_phase_mask"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_dims_struct_layout_matches_header():
+    kda, _ = _lib()
+    # int32, pad, int64, 4 x int32, int32, 2 x enum, float, pad, int64 -> 56 bytes on LP64
+    assert ctypes.sizeof(kda.KdaDims) == 56
+    assert kda.KdaDims.seqlen.offset == 8 and kda.KdaDims.max_seqlen.offset == 48
+
+
+def _dims(kda, **kw):
+    base = dict(batch=1, seqlen=128, heads=2, dk=128, dv=128, chunk=64, num_seqs=1, in_dtype=1,
+                out_dtype=0, scale=1.0, max_seqlen=0)
+    base.update(kw)
+    return kda.KdaDims(**base)
+
+
+def test_workspace_sizes_are_consistent():
+    kda, lib = _lib()
+    d = _dims(kda, batch=4, num_seqs=4, seqlen=4096, heads=16)
+    full = kda.kda_chunk_fwd_workspace_size(d)
+    small = kda.kda_chunk_fwd_min_workspace_size(d)
+    assert full > small > 0 and full % 256 == 0
+    per_chunk = (full - 4 * 16 * 128 * 128 * 4) // (4096 // 64)
+    assert per_chunk == 4 * 16 * 90624
+    assert kda.kda_chunk_fwd_workspace_size(_dims(kda, in_dtype=0)) == 0          # fp32 path
+    assert kda.kda_chunk_fwd_workspace_size(_dims(kda, dk=96, dv=96)) == 0        # unsupported
+    assert kda.kda_chunk_fwd_workspace_size(_dims(kda, seqlen=0)) == 0
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(dk=96, dv=96), 2), (dict(chunk=32), 2), (dict(out_dtype=1), 2), (dict(seqlen=-1), 1),
+    (dict(num_seqs=3), 1), (dict(in_dtype=7), 1),
+])
+def test_chunk_fwd_rejects_bad_dims_without_launching(kw, status):
+    kda, lib = _lib()
+    d = _dims(kda, **kw)
+    fake = ctypes.c_void_p(0x1000)
+    st = lib.kda_chunk_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, None, None,
+                           ctypes.c_void_p(0x2000), None, None, 0, None)
+    assert st == status, kda.kda_last_error()
+    assert kda.kda_last_error() != ""
+    assert kda.kda_status_string(st) not in ("ok", "unknown status")
+
+
+def test_chunk_fwd_rejects_null_misaligned_and_missing_workspace():
+    kda, lib = _lib()
+    d = _dims(kda)
+    fake = ctypes.c_void_p(0x1000)
+    out = ctypes.c_void_p(0x2000)
+    assert lib.kda_chunk_fwd(ctypes.byref(d), None, fake, fake, fake, fake, None, None, out, None,
+                             None, 0, None) == 1
+    assert lib.kda_chunk_fwd(ctypes.byref(d), ctypes.c_void_p(0x1008), fake, fake, fake, fake, None,
+                             None, out, None, None, 0, None) == 1
+    assert lib.kda_chunk_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, None, None, fake, None,
+                             None, 0, None) == 1                                   # o aliases q
+    assert lib.kda_chunk_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, None, None, out, None,
+                             None, 0, None) == 3                                   # no workspace
+    assert lib.kda_chunk_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, None, None, out, None,
+                             ctypes.c_void_p(0x3010), 1 << 30, None) == 3          # misaligned
+    assert lib.kda_chunk_fwd(ctypes.byref(d), fake, fake, fake, fake, fake, None, None, out, None,
+                             ctypes.c_void_p(0x3000), 1024, None) == 3             # too small
+    packed = _dims(kda, batch=2, num_seqs=3)
+    assert lib.kda_chunk_fwd(ctypes.byref(packed), fake, fake, fake, fake, fake, None, fake, out,
+                             None, None, 0, None) == 1                             # packed needs B == 1
+
+
+def test_recurrent_step_rejects_bad_calls():
+    kda, lib = _lib()
+    d = _dims(kda, seqlen=2)
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.kda_recurrent_step(ctypes.byref(d), fake, fake, fake, fake, fake, fake, fake, None) == 1
+    d = _dims(kda, seqlen=1)
+    assert lib.kda_recurrent_step(ctypes.byref(d), fake, fake, fake, fake, fake, None, fake, None) == 1
+    d = _dims(kda, seqlen=1, dk=256, dv=256)
+    assert lib.kda_recurrent_step(ctypes.byref(d), fake, fake, fake, fake, fake, fake, fake, None) == 2
+
+
+def test_empty_problems_are_ok_and_launch_nothing():
+    kda, lib = _lib()
+    d = _dims(kda, heads=0)
+    assert lib.kda_chunk_fwd(ctypes.byref(d), None, None, None, None, None, None, None, None, None,
+                             None, 0, None) == 0
+    d = _dims(kda, seqlen=1, batch=0, num_seqs=0)
+    assert lib.kda_recurrent_step(ctypes.byref(d), None, None, None, None, None, None, None, None) == 0
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    import paper_2510_26692_amd.kda as binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libkda.so")
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        binding.load_library()
