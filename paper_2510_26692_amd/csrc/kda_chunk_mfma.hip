@@ -560,14 +560,14 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 // ----------------------------------------------------------------------------------
 // kda_scan
 // ----------------------------------------------------------------------------------
-// One wave owns a 32-column slice of S for a whole sequence.  Per chunk it issues 54 MFMAs
-// (32x32x16) whose LDS-resident operands (W, Gamma.Q, A_qk, decayed K) are read a few MFMAs
-// ahead of their use through a small register ring; S and V_new are converted in registers
-// into the other operand.  The two O products are issued with the operands swapped, so the
-// accumulator holds O^T and a lane owns 4 consecutive columns of a token's output row.  The
-// next chunk's operand block goes from the workspace to LDS with LDS-direct loads while the
-// current chunk computes.  With one wave per SIMD every instruction issues from the same
-// wave, so the loop is written to keep the instruction count per chunk low.
+// One workgroup of eight waves walks the chunks of one (sequence, head).  Wave (c, p) owns the
+// 32-column slice c of the state for the two d_k tiles 2p, 2p+1, and the token tile p of V_new and
+// O.  A chunk therefore costs each wave 26-28 MFMAs (32x32x16) instead of 54, at the price of two
+// exchanges through LDS per chunk: the fp16 copies of S (every wave needs all four d_k tiles as
+// an operand) and of V_new (both token tiles).  All other operands stream from the LDS copy of the
+// workspace slot, which the eight waves refill for the next chunk with LDS-direct loads while
+// the current chunk computes.  O is accumulated transposed (operands swapped), so a lane owns four
+// consecutive output columns and stores 16 bytes at a time.
 #define KDA_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 namespace scan {
@@ -581,181 +581,170 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-// MFMA slots of one chunk, in issue order.
-//   0..31  stage B: group tau = i / 8; within a group s = (i % 8) / 4, then W rho0, W rho1, Q rho0, Q rho1
-//   32..37 stage C: A_qk (0,0,s0) (1,0,s0) (0,0,s1) (1,0,s1) (1,1,s0) (1,1,s1)
-//   38..53 stage D: rho = (i - 38) / 8, s = ((i - 38) % 8) / 4, tau = (i - 38) % 4
-constexpr int kSlots = 54;
-constexpr int slot_lds_offset(int i)
+constexpr int kWaves = 8;
+constexpr int kUnits = kLdsBlockBytes / 16;                  // 16-byte units per staged block
+constexpr int kCopies = (kUnits + 63) / 64;                  // wave-wide LDS-direct loads per block
+constexpr int kXS = 2 * kLdsBlockBytes;                      // fp16 S exchange: [c][tau][s] frags
+constexpr int kXV = kXS + 4 * 4 * 2 * kFragBytes;            // fp16 V_new exchange: [c][rho][s] frags
+constexpr int kLds = kXV + 4 * 2 * 2 * kFragBytes;
+static_assert(kLds <= 160 * 1024, "kda_scan exceeds the 160 KiB of LDS");
+
+// MFMA slots of wave half P, in issue order:
+//   0..7   V_new tile P:  W(P, tau, s),  tau = i / 2, s = i % 2
+//   8..15  O^T tile P:    Gamma.Q(P, tau, s)
+//   16..23 state tiles 2P, 2P+1: decayed K^T (tau, rho, s): tau = 2P + (j / 4), rho = (j % 4) / 2, s = j % 2
+//   24..   O^T tile P += A_qk(P, rho_i, s): rho_i = 0 (and 1 when P = 1)
+template <int P> constexpr int num_slots() { return 24 + 2 * (P + 1); }
+template <int P> constexpr int slot_lds_offset(int i)
 {
-    if (i < 32) {
-        const int tau = i / 8, s = (i % 8) / 4, k = i % 4, rho = k & 1;
-        return ((k < 2) ? kOffWn : kOffQp) + frag_rts(rho, tau, s) * kFragBytes;
+    if (i < 8) return kOffWn + frag_rts(P, i / 2, i % 2) * kFragBytes;
+    if (i < 16) return kOffQp + frag_rts(P, (i - 8) / 2, (i - 8) % 2) * kFragBytes;
+    if (i < 24) {
+        const int j = i - 16;
+        return kOffKt + frag_trs(2 * P + j / 4, (j % 4) / 2, j % 2) * kFragBytes;
     }
-    if (i < 38) {
-        const int j = i - 32;
-        const int rr = (j == 0 || j == 2) ? 0 : 1, ri = (j >= 4) ? 1 : 0, s = (j < 4) ? (j / 2) : (j - 4);
-        return kOffAqk + frag_aqk(rr, ri, s) * kFragBytes;
-    }
-    const int j = i - 38, rho = j / 8, s = (j % 8) / 4, tau = j % 4;
-    return kOffKt + frag_trs(tau, rho, s) * kFragBytes;
+    const int j = i - 24;
+    return kOffAqk + frag_aqk(P, j / 2, j % 2) * kFragBytes;
 }
 }  // namespace scan
 
-template <int NW>
-__global__ __launch_bounds__(NW * 64)
-void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, float *state_out,
-                     const int32_t *__restrict__ cu_seqlens, float *__restrict__ o, int64_t T, int H,
-                     int64_t seg_chunks, int64_t seg_index)
+template <int P>
+__device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
+                                              const float *state_in, float *state_out, float *o,
+                                              int64_t st_base, int64_t tok_base, int64_t len, int H,
+                                              int64_t c_begin, int64_t c_end, int h)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    constexpr int UNITS = kLdsBlockBytes / 16;           // 16-byte units per staged block
-    constexpr int NCOPY = (UNITS + 63) / 64;             // wave-wide copy instructions per block
-    constexpr int LA = 8, RING = 10;                     // operand look-ahead (MFMA slots) and ring size
-    constexpr int STAGE = kLdsBlockBytes + NW * 8192;    // shared operand block + one 8 KiB U slice per wave
+    using namespace scan;
+    constexpr int LA = 6, RING = 8;
+    constexpr int NS = num_slots<P>();
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int x = lane & 31, hh = lane >> 5;
-    const int n = blockIdx.x, h = blockIdx.y;
-    const int ct = blockIdx.z * NW + wave;               // this wave's 32-column slice of S
+    const int c = wave & 3;                                  // column slice of S, V_new, O
+    const uint32_t lane16 = (uint32_t)lane * 16;
 
-    int64_t tok_base, len;
-    if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
-    else            { tok_base = (int64_t)n * T; len = T; }
-    const int64_t nchunks = (len + kChunk - 1) / kChunk;
-    const int64_t c_begin = seg_index * seg_chunks;
-    const int64_t c_end = (nchunks < c_begin + seg_chunks) ? nchunks : c_begin + seg_chunks;
-
-    // state slice in accumulator order: S[tau][j] = S(dk = 32 tau + acc_row(j, hh), dv = 32 ct + x)
-    const int64_t st_base = ((int64_t)n * H + h) * (int64_t)(D * D) + 32 * ct + x;
-    f32x16 S[4];
-    if (state_in) {
+    // own state tiles in accumulator order: S[t][j] = S(dk = 32 (2P + t) + acc_row(j, hh), dv = 32 c + x)
+    f32x16 S[2];
 #pragma unroll
-        for (int tau = 0; tau < 4; ++tau)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
-                S[tau][j] = state_in[st_base + (int64_t)(32 * tau + acc_row(j, hh)) * D];
-    } else {
-#pragma unroll
-        for (int tau = 0; tau < 4; ++tau)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) S[tau][j] = 0.f;
-    }
+        for (int j = 0; j < 16; ++j)
+            S[t][j] = state_in ? state_in[st_base + (int64_t)(32 * (2 * P + t) + acc_row(j, hh)) * D] : 0.f;
 
     if (c_begin < c_end) {
-        const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks) * H + h) * (int64_t)kSlotBytes;
-        const int64_t slot_stride = (int64_t)H * kSlotBytes;
-        const uint32_t lane16 = (uint32_t)lane * 16;
-        const uint32_t u_src = (uint32_t)(kOffU + ct * 4096);           // U tile (0, ct) inside a slot
-        const uint32_t u_lds = (uint32_t)(kLdsBlockBytes + wave * 8192);   // this wave's U slice inside a stage
-
-        // workspace block -> LDS stage with LDS-direct loads of 1 KiB per wave instruction.  A wave owns
-        // the block pieces wave, wave + NW, ... and its own two U tiles: kCopies instructions in all.
-        // Issued in one burst they would stall the wave on the address FIFO, so inside the chunk loop
-        // they are spread over the MFMA slots.
-        constexpr int kBlkCopies = (NCOPY + NW - 1) / NW, kCopies = kBlkCopies + 8;
+        // workspace block -> LDS stage: this wave issues copies wave, wave + 8, ...
         auto stage_copy = [&](const uint8_t *src, int stage, int idx) __attribute__((always_inline)) {
-            if (idx < kBlkCopies) {
-                const int c = wave + idx * NW;
-                if (c < NCOPY && c * 64 + lane < UNITS)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void *)(src + c * 1024 + lane16),
-                        (__attribute__((address_space(3))) void *)(lds + stage * STAGE + c * 1024), 16, 0, 0);
-            } else {
-                const int i = idx - kBlkCopies;              // U tile rho = i / 4, quarter i % 4
+            const int cc = wave + idx * kWaves;
+            if (cc < kCopies && cc * 64 + lane < kUnits)
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(src + u_src + (i >> 2) * 16384 + (i & 3) * 1024 + lane16),
-                    (__attribute__((address_space(3))) void *)(lds + stage * STAGE + u_lds + i * 1024), 16, 0, 0);
-            }
+                    (const __attribute__((address_space(1))) void *)(src + cc * 1024 + lane16),
+                    (__attribute__((address_space(3))) void *)(lds + stage * kLdsBlockBytes + cc * 1024), 16, 0, 0);
         };
-        auto stage_in = [&](const uint8_t *src, int stage) {
+        constexpr int kMyCopies = (kCopies + kWaves - 1) / kWaves;
+        const uint32_t u_src = (uint32_t)(kOffU + (P * 4 + c) * 4096) + lane16;   // U tile (P, c): 4 x 1 KiB
+        f32x4 un[4];
 #pragma unroll
-            for (int idx = 0; idx < kCopies; ++idx) stage_copy(src, stage, idx);
-        };
-
-        stage_in(slot0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): the LDS-direct loads have landed
-        __syncthreads();
+        for (int i = 0; i < kMyCopies; ++i) stage_copy(slot0, 0, i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) un[i] = *reinterpret_cast<const f32x4 *>(slot0 + u_src + i * 1024);
 
         const uint32_t o_rstride = (uint32_t)H * D * 4;      // bytes between consecutive tokens of o
-        // O^T accumulator: lane (token 32 rho + x, hh), registers 4q..4q+3 = columns 32 ct + 8 q + 4 hh + 0..3
-        const uint32_t o_lane = (uint32_t)x * o_rstride + (uint32_t)(32 * ct + 4 * hh) * 4;
+        // O^T accumulator: lane (token 32 P + x, hh), registers 4q..4q+3 = columns 32 c + 8 q + 4 hh + 0..3
+        const uint32_t o_lane = (uint32_t)(32 * P + x) * o_rstride + (uint32_t)(32 * c + 4 * hh) * 4;
+        uint8_t *xs = lds + kXS + c * (4 * 2 * kFragBytes) + lane16;    // + (tau * 2 + s) * kFragBytes
+        uint8_t *xv = lds + kXV + c * (2 * 2 * kFragBytes) + lane16;    // + (rho * 2 + s) * kFragBytes
+        bool stores_pending = false;
 
         for (int64_t ci = c_begin; ci < c_end; ++ci) {
             const int stage = (int)((ci - c_begin) & 1);
-            const uint8_t *cur = lds + stage * STAGE + lane16;
-            const float *gc = reinterpret_cast<const float *>(lds + stage * STAGE + kOffGc) + 4 * hh;
+            const uint8_t *cur = lds + stage * kLdsBlockBytes + lane16;
+            const float *gc = reinterpret_cast<const float *>(lds + stage * kLdsBlockBytes + kOffGc) + 4 * hh;
             const bool more = ci + 1 < c_end;
             const uint8_t *nxt = slot0 + (ci + 1 - c_begin) * slot_stride;
 
-            // accumulators of V_new start from U
-            f32x16 av[2], ao[2] = {{0.f}, {0.f}};
+            // ---- publish the fp16 copy of the own state tiles ----
+            h8 Sb[4][2];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const f32x4 t = *reinterpret_cast<const f32x4 *>(cur + u_lds + i * 1024);
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int z = 0; z < 4; ++z) av[i >> 2][4 * (i & 3) + z] = t[z];
+                for (int s = 0; s < 2; ++s) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) Sb[2 * P + t][s][e] = (_Float16)S[t][8 * s + e];
+                    *reinterpret_cast<h8 *>(xs + ((2 * P + t) * 2 + s) * kFragBytes) = Sb[2 * P + t][s];
+                }
+            // this chunk's block must have landed (the stores of the previous chunk may still be in flight)
+            if (stores_pending) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);      // vmcnt(4)
+            else __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
+            __syncthreads();                                                 // B1
+
+            f32x16 av, ao = {0.f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int z = 0; z < 4; ++z) av[4 * i + z] = un[i][z];
+            if (more) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) un[i] = *reinterpret_cast<const f32x4 *>(nxt + u_src + i * 1024);
             }
+            // the partner's two d_k tiles of S
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+                    Sb[2 * (1 - P) + t][s] = *reinterpret_cast<const h8 *>(xs + ((2 * (1 - P) + t) * 2 + s) * kFragBytes);
 
             h8 ring[RING];
-            h8 Sb[4][2], Vb[2][2];
+            h8 Vb[2][2];
 #pragma unroll
             for (int i = 0; i < LA; ++i)
-                ring[i % RING] = *reinterpret_cast<const h8 *>(cur + scan::slot_lds_offset(i));
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) Sb[0][s][e] = (_Float16)S[0][8 * s + e];
+                ring[i % RING] = *reinterpret_cast<const h8 *>(cur + slot_lds_offset<P>(i));
 
-            scan::static_for<0, scan::kSlots>([&](auto ic) __attribute__((always_inline)) {
+            static_for<0, NS>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value;
-                // next chunk's block: a few LDS-direct loads per slot, all issued by slot 40
-                constexpr int kPer = (kCopies + 39) / 40;
-                static_assert(kPer <= 2, "at most two copies per slot are written out below");
                 if (more) {
-                    if constexpr (i * kPer < kCopies) stage_copy(nxt, stage ^ 1, i * kPer);
-                    if constexpr (kPer > 1 && i * kPer + 1 < kCopies) stage_copy(nxt, stage ^ 1, i * kPer + 1);
+                    if constexpr (i < kMyCopies) stage_copy(nxt, stage ^ 1, i);
                 }
-                if constexpr (i + LA < scan::kSlots)
-                    ring[(i + LA) % RING] = *reinterpret_cast<const h8 *>(cur + scan::slot_lds_offset(i + LA));
+                if constexpr (i + LA < NS)
+                    ring[(i + LA) % RING] = *reinterpret_cast<const h8 *>(cur + slot_lds_offset<P>(i + LA));
                 const h8 a = ring[i % RING];
-                if constexpr (i < 32) {
-                    // V_new = U + (-W) S ; O^T = S^T (Gamma.Q)^T
-                    constexpr int tau = i / 8, s = (i % 8) / 4, k = i % 4, rho = k & 1;
-                    if constexpr (k < 2) av[rho] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Sb[tau][s], av[rho], 0, 0, 0);
-                    else       ao[rho] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Sb[tau][s], a, ao[rho], 0, 0, 0);
-                    if constexpr (i % 8 == 1 && tau < 3) {
-                        // fp16 copy of the next d_k tile of S, in the shadow of this group's MFMAs
+                if constexpr (i < 8) {
+                    // V_new = U + (-W) S
+                    av = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Sb[i / 2][i % 2], av, 0, 0, 0);
+                    if constexpr (i == 7) {
+                        // publish the fp16 copy of the own token tile of V_new
 #pragma unroll
-                        for (int s2 = 0; s2 < 2; ++s2)
+                        for (int s = 0; s < 2; ++s) {
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) Sb[tau + 1][s2][e] = (_Float16)S[tau + 1][8 * s2 + e];
-                    }
-                    if constexpr (i % 8 == 5) {
-                        // S <- Diag(gamma^C) S for the tile whose fp16 copy is already taken
-#pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4) {
-                            const f32x4 gv = *reinterpret_cast<const f32x4 *>(gc + 32 * tau + 8 * q4);
-#pragma unroll
-                            for (int z = 0; z < 4; ++z) S[tau][4 * q4 + z] *= gv[z];
+                            for (int e = 0; e < 8; ++e) Vb[P][s][e] = (_Float16)av[8 * s + e];
+                            *reinterpret_cast<h8 *>(xv + (P * 2 + s) * kFragBytes) = Vb[P][s];
                         }
                     }
-                    if constexpr (i == 31) {
+                } else if constexpr (i < 16) {
+                    // O^T = S^T (Gamma.Q)^T
+                    ao = __builtin_amdgcn_mfma_f32_32x32x16_f16(Sb[(i - 8) / 2][(i - 8) % 2], a, ao, 0, 0, 0);
+                    if constexpr (i == 10 || i == 12) {
+                        // S <- Diag(gamma^C) S on the own tiles (their fp16 copies are taken)
+                        constexpr int t = (i - 10) / 2;
 #pragma unroll
-                        for (int rho2 = 0; rho2 < 2; ++rho2)
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const f32x4 gv = *reinterpret_cast<const f32x4 *>(gc + 32 * (2 * P + t) + 8 * q4);
 #pragma unroll
-                            for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-                                for (int e = 0; e < 8; ++e) Vb[rho2][s2][e] = (_Float16)av[rho2][8 * s2 + e];
+                            for (int z = 0; z < 4; ++z) S[t][4 * q4 + z] *= gv[z];
+                        }
                     }
-                } else if constexpr (i < 38) {
-                    // O^T += V_new^T Tril(A_qk)^T
-                    constexpr int j = i - 32;
-                    constexpr int rr = (j == 0 || j == 2) ? 0 : 1, ri = (j >= 4) ? 1 : 0, s = (j < 4) ? (j / 2) : (j - 4);
-                    ao[rr] = __builtin_amdgcn_mfma_f32_32x32x16_f16(Vb[ri][s], a, ao[rr], 0, 0, 0);
+                    if constexpr (i == 15) {
+                        __syncthreads();                                         // B2: V_new exchange complete
+#pragma unroll
+                        for (int s = 0; s < 2; ++s)
+                            Vb[1 - P][s] = *reinterpret_cast<const h8 *>(xv + ((1 - P) * 2 + s) * kFragBytes);
+                    }
+                } else if constexpr (i < 24) {
+                    // S += (Gamma^{i->C}.K)^T V_new on the own d_k tiles
+                    constexpr int j = i - 16;
+                    S[j / 4] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Vb[(j % 4) / 2][j % 2], S[j / 4], 0, 0, 0);
                 } else {
-                    // S += (Gamma^{i->C}.K)^T V_new
-                    constexpr int j = i - 38, rho = j / 8, s = (j % 8) / 4, tau = j % 4;
-                    S[tau] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Vb[rho][s], S[tau], 0, 0, 0);
+                    // O^T += V_new^T Tril(A_qk)^T
+                    constexpr int j = i - 24;
+                    ao = __builtin_amdgcn_mfma_f32_32x32x16_f16(Vb[j / 2][j % 2], a, ao, 0, 0, 0);
                 }
                 KDA_FENCE();   // keeps each operand read LA slots ahead of its MFMA
             });
@@ -764,30 +753,51 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
             {
                 const int64_t t0 = ci * kChunk;
                 uint8_t *obase = reinterpret_cast<uint8_t *>(o + ((tok_base + t0) * H + h) * (int64_t)D);
+                stores_pending = (t0 + kChunk <= len);       // uniform: all four stores are issued
+                if (t0 + 32 * P + x < len) {
 #pragma unroll
-                for (int rho = 0; rho < 2; ++rho) {
-                    if (t0 + 32 * rho + x < len) {
-#pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4) {
-                            f32x4 val = {ao[rho][4 * q4], ao[rho][4 * q4 + 1], ao[rho][4 * q4 + 2], ao[rho][4 * q4 + 3]};
-                            *reinterpret_cast<f32x4 *>(obase + (o_lane + (uint32_t)(32 * rho) * o_rstride + 32 * q4)) = val;
-                        }
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        f32x4 val = {ao[4 * q4], ao[4 * q4 + 1], ao[4 * q4 + 2], ao[4 * q4 + 3]};
+                        *reinterpret_cast<f32x4 *>(obase + (o_lane + 32 * q4)) = val;
                     }
                 }
             }
             KDA_FENCE();
-            __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): next block is in LDS (this wave's part)
-            __syncthreads();
         }
     }
 
     if (state_out && (state_out != state_in || c_begin < c_end)) {
 #pragma unroll
-        for (int tau = 0; tau < 4; ++tau)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                state_out[st_base + (int64_t)(32 * tau + acc_row(j, hh)) * D] = S[tau][j];
+                state_out[st_base + (int64_t)(32 * (2 * P + t) + acc_row(j, hh)) * D] = S[t][j];
     }
+}
+
+__global__ __launch_bounds__(512)
+void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, float *state_out,
+                     const int32_t *__restrict__ cu_seqlens, float *__restrict__ o, int64_t T, int H,
+                     int64_t seg_chunks, int64_t seg_index)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = blockIdx.x / H, h = blockIdx.x % H;
+
+    int64_t tok_base, len;
+    if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
+    else            { tok_base = (int64_t)n * T; len = T; }
+    const int64_t nchunks = (len + kChunk - 1) / kChunk;
+    const int64_t c_begin = seg_index * seg_chunks;
+    const int64_t c_end = (nchunks < c_begin + seg_chunks) ? nchunks : c_begin + seg_chunks;
+    const int64_t st_base = ((int64_t)n * H + h) * (int64_t)(D * D) + 32 * (wave & 3) + (lane & 31);
+    const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks) * H + h) * (int64_t)kSlotBytes;
+    const int64_t slot_stride = (int64_t)H * kSlotBytes;
+
+    if (wave < 4)
+        kda_scan_body<0>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h);
+    else
+        kda_scan_body<1>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h);
 }
 
 // ----------------------------------------------------------------------------------
@@ -862,20 +872,12 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
         return fail(KDA_ERR_UNSUPPORTED, "too many (chunk, head) pairs per segment for one launch: %lld",
                     (long long)(slots * d->heads));
 
-    // wavefronts per scan workgroup (each owns a 32-column slice of S); KDA_SCAN_NW overrides for tuning
-    int nw = 2;
-    if (const char *env = getenv("KDA_SCAN_NW")) {
-        const int v = atoi(env);
-        if (v == 1 || v == 2) nw = v;
-    }
-    const size_t scan_lds = 2 * ((size_t)kLdsBlockBytes + (size_t)nw * 8192);
+    const size_t scan_lds = (size_t)scan::kLds;
     {
         hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
-        hipError_t e2 = (nw == 2) ? hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<2>),
-                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds)
-                                  : hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<1>),
-                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
+        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
         if (e1 != hipSuccess || e2 != hipSuccess)
             return fail(KDA_ERR_LAUNCH, "cannot reserve LDS for the prefill kernels (%d, %d bytes)", kIntraLds,
                         (int)scan_lds);
@@ -893,16 +895,10 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
                                plan.seg_chunks, seg, d->scale);
         const float *sin = (seg == 0) ? h0 : carry;
         float *sout = (plan.num_segments > 1 || hT) ? carry : nullptr;
-        if (g_phase_mask & 2) {
-            const dim3 grid((unsigned)d->num_seqs, (unsigned)d->heads, (unsigned)(4 / nw));
-            float *op = static_cast<float *>(o);
-            if (nw == 2)
-                hipLaunchKernelGGL(kda_scan_kernel<2>, grid, dim3(128), scan_lds, stream, ws, sin, sout, cu, op,
-                                   (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg);
-            else
-                hipLaunchKernelGGL(kda_scan_kernel<1>, grid, dim3(64), scan_lds, stream, ws, sin, sout, cu, op,
-                                   (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg);
-        }
+        if (g_phase_mask & 2)
+            hipLaunchKernelGGL(kda_scan_kernel, dim3((unsigned)(d->num_seqs * d->heads)), dim3(512), scan_lds, stream,
+                               ws, sin, sout, cu, static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads,
+                               plan.seg_chunks, seg);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));

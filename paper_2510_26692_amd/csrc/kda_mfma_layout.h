@@ -8,7 +8,7 @@
 //   Wn   -W            A operand [token r][dk]      frags [rho][tau][s]      fp16
 //   Qp   Gamma.Q       A operand [token r][dk]      frags [rho][tau][s]      fp16
 //   Kt   (Gamma^{i->C}.K)^T  A operand [dk][token]  frags [tau][rho][s]      fp16
-//   Aqk  Tril(A_qk)    A operand [token r][token i] frags [rho_r][rho_i][s]  fp16
+//   Aqk  Tril(A_qk)    A operand [token r][token i] frags (0,0,s) (1,0,s) (1,1,s) fp16
 //   gC   gamma^C       [dk]                                                  fp32
 //   U                  C/D tiles [rho][ct] in accumulator order              fp32
 //
@@ -37,11 +37,11 @@ constexpr int kFragBytes = 1024;
 constexpr int kOffWn = 0;                     // 16 frags
 constexpr int kOffQp = kOffWn + 16 * kFragBytes;
 constexpr int kOffKt = kOffQp + 16 * kFragBytes;
-constexpr int kOffAqk = kOffKt + 16 * kFragBytes;   // 8 frag positions, (rho_r=0,rho_i=1) unused
-constexpr int kOffGc = kOffAqk + 8 * kFragBytes;
+constexpr int kOffAqk = kOffKt + 16 * kFragBytes;   // 6 frags: token tile (0,1) of Tril(A_qk) is zero
+constexpr int kOffGc = kOffAqk + 6 * kFragBytes;
 constexpr int kLdsBlockBytes = kOffGc + D * 4;      // what kda_scan stages through LDS
 constexpr int kOffU = kLdsBlockBytes;               // 8 tiles x 4 KiB
-constexpr int kSlotBytes = kOffU + 8 * 4096;        // 90624
+constexpr int kSlotBytes = kOffU + 8 * 4096;        // 88576
 
 static_assert(kLdsBlockBytes % 16 == 0, "LDS block must be a whole number of 16-byte units");
 static_assert(kSlotBytes % 256 == 0, "slots must stay 256-byte aligned");
@@ -53,7 +53,7 @@ __host__ __device__ constexpr int acc_row(int j, int hh) { return 8 * (j >> 2) +
 
 constexpr int frag_rts(int r, int t, int s) { return (r * 4 + t) * 2 + s; }   // Wn, Qp: [rho][tau][s]
 constexpr int frag_trs(int t, int r, int s) { return (t * 2 + r) * 2 + s; }   // Kt: [tau][rho][s]
-constexpr int frag_aqk(int rr, int ri, int s) { return (rr * 2 + ri) * 2 + s; }
+constexpr int frag_aqk(int rr, int ri, int s) { return (rr + ri) * 2 + s; }   // (0,0) (1,0) (1,1)
 
 // Geometry of one launch pair: `seg_chunks` chunk indices of every sequence.
 struct SegPlan {

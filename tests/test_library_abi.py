@@ -50,7 +50,7 @@ def test_workspace_sizes_are_consistent():
     small = kda.kda_chunk_fwd_min_workspace_size(d)
     assert full > small > 0 and full % 256 == 0
     per_chunk = (full - 4 * 16 * 128 * 128 * 4) // (4096 // 64)
-    assert per_chunk == 4 * 16 * 90624
+    assert per_chunk == 4 * 16 * 88576
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, in_dtype=0)) == 0          # fp32 path
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, dk=96, dv=96)) == 0        # unsupported
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, seqlen=0)) == 0
