@@ -631,35 +631,46 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
             S[t][j] = state_in ? state_in[st_base + (int64_t)(32 * (2 * P + t) + acc_row(j, hh)) * D] : 0.f;
 
     if (c_begin < c_end) {
-        // workspace block -> LDS stage: this wave issues copies wave, wave + 8, ...
-        auto stage_copy = [&](const uint8_t *src, int stage, int idx) __attribute__((always_inline)) {
-            const int cc = wave + idx * kWaves;
-            if (cc < kCopies && cc * 64 + lane < kUnits)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(src + cc * 1024 + lane16),
-                    (__attribute__((address_space(3))) void *)(lds + stage * kLdsBlockBytes + cc * 1024), 16, 0, 0);
-        };
-        constexpr int kMyCopies = (kCopies + kWaves - 1) / kWaves;
+        // Workspace slot -> LDS: the block of chunk ci is fetched into registers two steps ahead
+        // (register set ci % 2), written to LDS stage ci % 2 at the end of step ci - 1 and read in
+        // step ci, so that a fetch has two full steps to complete.  Thread tid moves the 16-byte
+        // units tid, tid + 512, ...; the wave's U tile (P, c) travels the same way.
+        constexpr int kMyUnits = (kUnits + 511) / 512;
         const uint32_t u_src = (uint32_t)(kOffU + (P * 4 + c) * 4096) + lane16;   // U tile (P, c): 4 x 1 KiB
-        f32x4 un[4];
+        u32x4 pre[2][kMyUnits];
+        f32x4 un[2][4];
+        auto fetch = [&](const uint8_t *src, u32x4 *blk, f32x4 *u) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < kMyCopies; ++i) stage_copy(slot0, 0, i);
+            for (int i = 0; i < kMyUnits; ++i) {
+                const int unit = tid + i * 512;
+                if (unit < kUnits) blk[i] = *reinterpret_cast<const u32x4 *>(src + (uint32_t)unit * 16);
+            }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) un[i] = *reinterpret_cast<const f32x4 *>(slot0 + u_src + i * 1024);
+            for (int i = 0; i < 4; ++i) u[i] = *reinterpret_cast<const f32x4 *>(src + u_src + i * 1024);
+        };
+        auto publish = [&](const u32x4 *blk, int stage) __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < kMyUnits; ++i) {
+                const int unit = tid + i * 512;
+                if (unit < kUnits) *reinterpret_cast<u32x4 *>(lds + stage * kLdsBlockBytes + unit * 16) = blk[i];
+            }
+        };
+        fetch(slot0, pre[0], un[0]);
+        if (c_begin + 1 < c_end) fetch(slot0 + slot_stride, pre[1], un[1]);
+        publish(pre[0], 0);
 
         const uint32_t o_rstride = (uint32_t)H * D * 4;      // bytes between consecutive tokens of o
         // O^T accumulator: lane (token 32 P + x, hh), registers 4q..4q+3 = columns 32 c + 8 q + 4 hh + 0..3
         const uint32_t o_lane = (uint32_t)(32 * P + x) * o_rstride + (uint32_t)(32 * c + 4 * hh) * 4;
         uint8_t *xs = lds + kXS + c * (4 * 2 * kFragBytes) + lane16;    // + (tau * 2 + s) * kFragBytes
         uint8_t *xv = lds + kXV + c * (2 * 2 * kFragBytes) + lane16;    // + (rho * 2 + s) * kFragBytes
-        bool stores_pending = false;
 
-        for (int64_t ci = c_begin; ci < c_end; ++ci) {
-            const int stage = (int)((ci - c_begin) & 1);
+        // one chunk; `stage` (compile-time parity) is its LDS stage and register set
+        auto chunk_step = [&](const int64_t ci, auto stage_c) __attribute__((always_inline)) {
+            constexpr int stage = decltype(stage_c)::value;
             const uint8_t *cur = lds + stage * kLdsBlockBytes + lane16;
             const float *gc = reinterpret_cast<const float *>(lds + stage * kLdsBlockBytes + kOffGc) + 4 * hh;
             const bool more = ci + 1 < c_end;
-            const uint8_t *nxt = slot0 + (ci + 1 - c_begin) * slot_stride;
 
             // ---- publish the fp16 copy of the own state tiles ----
             h8 Sb[4][2];
@@ -671,20 +682,15 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                     for (int e = 0; e < 8; ++e) Sb[2 * P + t][s][e] = (_Float16)S[t][8 * s + e];
                     *reinterpret_cast<h8 *>(xs + ((2 * P + t) * 2 + s) * kFragBytes) = Sb[2 * P + t][s];
                 }
-            // this chunk's block must have landed (the stores of the previous chunk may still be in flight)
-            if (stores_pending) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);      // vmcnt(4)
-            else __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
-            __syncthreads();                                                 // B1
+            __syncthreads();                                                 // B1: S exchange and LDS stage ready
 
             f32x16 av, ao = {0.f};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int z = 0; z < 4; ++z) av[4 * i + z] = un[i][z];
-            if (more) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) un[i] = *reinterpret_cast<const f32x4 *>(nxt + u_src + i * 1024);
-            }
+                for (int z = 0; z < 4; ++z) av[4 * i + z] = un[stage][i][z];
+            // this register set is free now: start fetching chunk ci + 2 into it
+            if (ci + 2 < c_end) fetch(slot0 + (ci + 2 - c_begin) * slot_stride, pre[stage], un[stage]);
             // the partner's two d_k tiles of S
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -700,9 +706,6 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
 
             static_for<0, NS>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value;
-                if (more) {
-                    if constexpr (i < kMyCopies) stage_copy(nxt, stage ^ 1, i);
-                }
                 if constexpr (i + LA < NS)
                     ring[(i + LA) % RING] = *reinterpret_cast<const h8 *>(cur + slot_lds_offset<P>(i + LA));
                 const h8 a = ring[i % RING];
@@ -753,7 +756,6 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
             {
                 const int64_t t0 = ci * kChunk;
                 uint8_t *obase = reinterpret_cast<uint8_t *>(o + ((tok_base + t0) * H + h) * (int64_t)D);
-                stores_pending = (t0 + kChunk <= len);       // uniform: all four stores are issued
                 if (t0 + 32 * P + x < len) {
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4) {
@@ -763,6 +765,12 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 }
             }
             KDA_FENCE();
+            // the next chunk's block (fetched one step ago) goes to the other LDS stage
+            if (more) publish(pre[stage ^ 1], stage ^ 1);
+        };
+        for (int64_t ci = c_begin; ci < c_end; ci += 2) {
+            chunk_step(ci, std::integral_constant<int, 0>{});
+            if (ci + 1 < c_end) chunk_step(ci + 1, std::integral_constant<int, 1>{});
         }
     }
 
