@@ -14,10 +14,15 @@
  * Conventions shared by every call
  *   - All tensor pointers are DEVICE pointers to contiguous row-major arrays,
  *     16-byte aligned.  The caller owns every buffer, including the workspace;
- *     the library allocates nothing, frees nothing and keeps no state between
- *     calls.
+ *     the library allocates no device memory and frees none.  The only state
+ *     it keeps is a helper stream with two events per device and host thread,
+ *     created by the first bf16 kda_chunk_fwd call that uses them.
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
- *     NULL = default stream); no host synchronisation happens inside.
+ *     NULL = default stream); no host synchronisation happens inside.  Work
+ *     that a call puts on the helper stream is ordered after everything queued
+ *     on `hip_stream` before the call, and `hip_stream` waits for it before
+ *     the call's work counts as complete: to the caller the call behaves as if
+ *     everything ran on `hip_stream`.
  *   - Element offsets are 64-bit; tensors with more than 2^31 elements are fine.
  *   - Errors: a non-zero kda_status is returned and kda_last_error() holds a
  *     thread-local description.  For KDA_ERR_INVALID_ARG, KDA_ERR_UNSUPPORTED
@@ -115,6 +120,18 @@ kda_status kda_chunk_fwd(const kda_dims *dims,
                          void *hip_stream);
 
 /*
+ * Optional check after a bf16 kda_chunk_fwd: waits for `hip_stream` and reads
+ * the status word that the call left in `workspace` (same dims, workspace and
+ * size as that call).  The sequential kernel of the prefill may run next to
+ * the per-chunk kernel and then waits, for a bounded time, for each workspace
+ * slot; if such a wait ever ran out, the outputs of the call are invalid and
+ * this returns KDA_ERR_LAUNCH.  KDA_OK otherwise (also for calls that keep no
+ * status word).
+ */
+kda_status kda_chunk_fwd_check(const kda_dims *dims, const void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
+/*
  * One decode step of Eq. (1) for N = dims->num_seqs sequences (Section 6.3):
  *     S <- Diag(alpha) S;  r = v - S^T k;  S <- S + beta k r^T;  o = scale S^T q.
  * dims->seqlen must be 1 and dims->batch == dims->num_seqs.
@@ -141,9 +158,18 @@ const char *kda_last_error(void);
  * Diagnostics for per-kernel timing only: selects which kernels of the
  * matrix-core prefill run on later kda_chunk_fwd calls (bit 0: the per-chunk
  * kernel, bit 1: the sequential scan; default 3).  With a bit cleared the
- * outputs of that call are incomplete.  Process-wide, not thread-safe.
+ * outputs of that call are incomplete and the two kernels never overlap.
+ * Process-wide, not thread-safe.
  */
 void kda_debug_set_phase_mask(int mask);
+
+/*
+ * Diagnostics: 0 makes the matrix-core prefill run its two kernels strictly one
+ * after the other on `hip_stream`; 1 (default) lets them overlap when there are
+ * few enough (sequence, head) pairs.  Results are identical either way.
+ * Process-wide, not thread-safe.
+ */
+void kda_debug_set_overlap(int enabled);
 
 /* Library version string, e.g. "kda-gfx950 0.1". */
 const char *kda_version(void);

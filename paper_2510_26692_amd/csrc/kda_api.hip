@@ -31,9 +31,12 @@ kda_status chunk_mfma_dispatch(const kda_dims *, const void *, const void *, con
                                const void *, const void *, const float *, const int32_t *, void *,
                                float *, void *, size_t, hipStream_t);
 size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal);
+size_t chunk_mfma_status_offset(const kda_dims *, size_t workspace_bytes);
 
 // Diagnostics: which kernels of the matrix-core prefill run (bit 0 kda_intra, bit 1 kda_scan).
 int g_phase_mask = 3;
+// Diagnostics: 0 keeps kda_intra and kda_scan strictly one after the other.
+int g_overlap = 1;
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -81,6 +84,8 @@ extern "C" {
 const char *kda_version(void) { return "kda-gfx950 0.1"; }
 
 void kda_debug_set_phase_mask(int mask) { g_phase_mask = mask & 3; }
+
+void kda_debug_set_overlap(int enabled) { g_overlap = enabled ? 1 : 0; }
 
 const char *kda_last_error(void) { return g_last_error; }
 
@@ -149,6 +154,27 @@ kda_status kda_chunk_fwd(const kda_dims *d, const void *q, const void *k, const 
     }
     return chunk_mfma_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
                                workspace_bytes, stream);
+}
+
+kda_status kda_chunk_fwd_check(const kda_dims *d, const void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    g_last_error[0] = 0;
+    if (!d) return fail(KDA_ERR_INVALID_ARG, "dims is NULL");
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "stream: %s", hipGetErrorString(e));
+    if (d->chunk != kChunk || check_dims(d, d->num_seqs != d->batch) != KDA_OK) return KDA_ERR_INVALID_ARG;
+    if (!mfma_path(d) || !workspace || chunk_mfma_workspace_size(d, true) == 0 ||
+        workspace_bytes < chunk_mfma_workspace_size(d, true))
+        return KDA_OK;                                       // this path leaves no status word
+    uint32_t word = 0;
+    e = hipMemcpy(&word, static_cast<const uint8_t *>(workspace) + chunk_mfma_status_offset(d, workspace_bytes),
+                  sizeof(word), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "status read: %s", hipGetErrorString(e));
+    if (word != 0)
+        return fail(KDA_ERR_LAUNCH, "kda_scan gave up waiting for a workspace slot (status %u): outputs are invalid",
+                    word);
+    return KDA_OK;
 }
 
 kda_status kda_recurrent_step(const kda_dims *d, const void *q, const void *k, const void *v,

@@ -32,7 +32,8 @@
 
 namespace kda {
 
-extern int g_phase_mask;   // diagnostics switch owned by kda_api.hip
+extern int g_phase_mask;   // diagnostics switches owned by kda_api.hip
+extern int g_overlap;
 
 namespace mfma {
 
@@ -87,6 +88,31 @@ template <int N> __device__ __forceinline__ float row_shr(float x)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x110 + N, 0xf, 0xf, true));
 }
 
+// Workspace slots are written and read through buffer instructions with the device-scope cache
+// policy (sc1): the stores write through the L2 of the writing XCD and the loads do not trust
+// the L2 of the reading XCD, so a slot produced by one workgroup can be consumed by another one
+// of a kernel that runs at the same time, with no cache write-back or invalidate in between.
+// The descriptor covers exactly one slot; offsets beyond it are dropped by the hardware.
+constexpr int kCacheDevice = 16;                            // sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t slot_resource(const uint8_t *slot)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(slot), 0, kSlotBytes, 0x00020000);
+}
+template <typename V> __device__ __forceinline__ void slot_store16(__amdgpu_buffer_rsrc_t rs, int off, V val)
+{
+    static_assert(sizeof(V) == 16, "16-byte store");
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), rs, off, 0, kCacheDevice);
+}
+template <typename V> __device__ __forceinline__ void slot_store8(__amdgpu_buffer_rsrc_t rs, int off, V val)
+{
+    static_assert(sizeof(V) == 8, "8-byte store");
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, val), rs, off, 0, kCacheDevice);
+}
+template <int kPolicy> __device__ __forceinline__ u32x4 slot_load16(__amdgpu_buffer_rsrc_t rs, int off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, kPolicy);
+}
+
 // ----------------------------------------------------------------------------------
 // kda_intra
 // ----------------------------------------------------------------------------------
@@ -98,22 +124,27 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
                       const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
                       uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
-                      int64_t seg_index, float scale)
+                      int64_t seg_index, float scale, int num_seqs, uint32_t *ready, uint32_t epoch)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
+    // Workgroup -> (sequence n, chunk, head h).  With `ready` set the grid is ordered by chunk
+    // index first, so that the slots a concurrently running kda_scan needs next are produced
+    // first; otherwise sequence-major (consecutive workgroups write consecutive slots).
     const int h = (int)(blockIdx.x % (unsigned)H);
-    const int64_t slot = blockIdx.x / (unsigned)H;
-    const int n = (int)(slot / seg_chunks);
-    const int64_t ci = seg_index * seg_chunks + slot % seg_chunks;
+    const int64_t bq = blockIdx.x / (unsigned)H;
+    const int n = ready ? (int)(bq % num_seqs) : (int)(bq / seg_chunks);
+    const int64_t cl = ready ? bq / num_seqs : bq % seg_chunks;
+    const int64_t slot = n * seg_chunks + cl;
+    const int64_t ci = seg_index * seg_chunks + cl;
     int64_t tok_base, len;
     if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
     else            { tok_base = (int64_t)n * T; len = T; }
     if (ci * kChunk >= len) return;                      // uniform for the workgroup
     const int nv = (int)((len - ci * kChunk < kChunk) ? (len - ci * kChunk) : kChunk);
     const int64_t tok0 = tok_base + ci * kChunk;
-    uint8_t *out = ws + (slot * H + h) * (int64_t)kSlotBytes;
+    const __amdgpu_buffer_rsrc_t out = slot_resource(ws + (slot * H + h) * (int64_t)kSlotBytes);
 
     float *sTot = reinterpret_cast<float *>(lds + kTot);
     float *sBeta = reinterpret_cast<float *>(lds + kBeta);
@@ -194,7 +225,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         *reinterpret_cast<float2 *>(tb + 4 * 512) = make_float2(fast_exp2(t0[r1] + t0[r2]), fast_exp2(t1[r1] + t1[r2]));
         if (R == 0) {   // gamma^C: decay of the whole chunk
             float2 gc = make_float2(fast_exp2(t0[0] + t0[1] + t0[2] + t0[3]), fast_exp2(t1[0] + t1[1] + t1[2] + t1[3]));
-            *reinterpret_cast<float2 *>(out + kOffGc + c2 * 4) = gc;
+            slot_store8(out, kOffGc + c2 * 4, gc);
         }
     }
     uint32_t strong_all = 0;        // union over g of this sub-chunk's strong-channel slots
@@ -295,8 +326,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             u32x4 o4;
             if (odd) { o4[0] = r0; o4[1] = r1; o4[2] = b0; o4[3] = b1; }
             else     { o4[0] = a0; o4[1] = a1; o4[2] = r0; o4[3] = r1; }
-            *reinterpret_cast<u32x4 *>(out + kOffQp + frag_rts(tok >> 5, ks, g >> 1) * kFragBytes +
-                                       ((tok & 31) + 32 * (g & 1)) * 16) = o4;
+            slot_store16(out, kOffQp + frag_rts(tok >> 5, ks, g >> 1) * kFragBytes + ((tok & 31) + 32 * (g & 1)) * 16, o4);
         }
     }
 
@@ -436,7 +466,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                              ((uint32_t)sKp[t1 * kLdH + 32 * tau + x] << 16);
             }
             u32x4 o4 = {w4[0], w4[1], w4[2], w4[3]};
-            *reinterpret_cast<u32x4 *>(out + kOffKt + f * kFragBytes + lane * 16) = o4;
+            slot_store16(out, kOffKt + f * kFragBytes + lane * 16, o4);
         }
     }
     __syncthreads();                                                               // B6
@@ -491,7 +521,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             const u32x2 a = *reinterpret_cast<const u32x2 *>(lds + kAq + at);
             const u32x2 b = *reinterpret_cast<const u32x2 *>(lds + kAq + at + 16);
             u32x4 o4 = {a[0], a[1], b[0], b[1]};
-            *reinterpret_cast<u32x4 *>(out + kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16) = o4;
+            slot_store16(out, kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16, o4);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -546,14 +576,23 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 u32x4 o4;
 #pragma unroll
                 for (int z = 0; z < 4; ++z) o4[z] = pack_h2(-wt[8 * s + 2 * z], -wt[8 * s + 2 * z + 1]);
-                *reinterpret_cast<u32x4 *>(out + kOffWn + frag_rts(rho, wave, s) * kFragBytes + lane * 16) = o4;
+                slot_store16(out, kOffWn + frag_rts(rho, wave, s) * kFragBytes + lane * 16, o4);
             }
 #pragma unroll
             for (int j4 = 0; j4 < 4; ++j4) {
                 f32x4 o4 = {u[4 * j4], u[4 * j4 + 1], u[4 * j4 + 2], u[4 * j4 + 3]};
-                *reinterpret_cast<f32x4 *>(out + kOffU + (((rho * 4 + wave) * 4 + j4) * 64 + lane) * 16) = o4;
+                slot_store16(out, kOffU + (((rho * 4 + wave) * 4 + j4) * 64 + lane) * 16, o4);
             }
         }
+    }
+    if (ready) {
+        // Hand the finished slot to kda_scan.  Every store to the slot is a write-through store;
+        // the barrier's release makes each wave wait until all of its stores have completed, so
+        // the slot is in place, device-wide, before one lane raises its flag.
+        __syncthreads();
+        if (tid == 0)
+            __hip_atomic_store(ready + ((int64_t)n * H + h) * seg_chunks + cl, epoch, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -608,11 +647,29 @@ template <int P> constexpr int slot_lds_offset(int i)
 }
 }  // namespace scan
 
+// Waits (one lane) until the producer has raised `*flag` to `epoch`.  The wait is bounded: after
+// about two seconds the lane records the failure in *status and the kernel runs on with whatever
+// the slot holds, so that every wave still reaches the end of the grid.
+__device__ __noinline__ void wait_ready(const uint32_t *flag, uint32_t epoch, uint32_t *status, bool &gave_up)
+{
+    if (gave_up) return;
+    const uint64_t t0 = wall_clock64();                     // 100 MHz
+    while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+        __builtin_amdgcn_s_sleep(8);
+        if (wall_clock64() - t0 > 200000000ull) {
+            gave_up = true;
+            __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+    }
+}
+
 template <int P>
 __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
                                               const float *state_in, float *state_out, float *o,
                                               int64_t st_base, int64_t tok_base, int64_t len, int H,
-                                              int64_t c_begin, int64_t c_end, int h)
+                                              int64_t c_begin, int64_t c_end, int h,
+                                              const uint32_t *ready, uint32_t epoch, uint32_t *status)
 {
     using namespace scan;
     constexpr int LA = 6, RING = 8;
@@ -640,13 +697,25 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
         u32x4 pre[2][kMyUnits];
         f32x4 un[2][4];
         auto fetch = [&](const uint8_t *src, u32x4 *blk, f32x4 *u) __attribute__((always_inline)) {
+            const __amdgpu_buffer_rsrc_t rs = slot_resource(src);
+            if (ready) {     // the slot was written while this kernel runs: device-scope loads
 #pragma unroll
-            for (int i = 0; i < kMyUnits; ++i) {
-                const int unit = tid + i * 512;
-                if (unit < kUnits) blk[i] = *reinterpret_cast<const u32x4 *>(src + (uint32_t)unit * 16);
+                for (int i = 0; i < kMyUnits; ++i) {
+                    const int unit = tid + i * 512;
+                    if (unit < kUnits) blk[i] = slot_load16<kCacheDevice>(rs, unit * 16);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    u[i] = __builtin_bit_cast(f32x4, slot_load16<kCacheDevice>(rs, (int)u_src + i * 1024));
+            } else {
+#pragma unroll
+                for (int i = 0; i < kMyUnits; ++i) {
+                    const int unit = tid + i * 512;
+                    if (unit < kUnits) blk[i] = slot_load16<0>(rs, unit * 16);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) u[i] = __builtin_bit_cast(f32x4, slot_load16<0>(rs, (int)u_src + i * 1024));
             }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) u[i] = *reinterpret_cast<const f32x4 *>(src + u_src + i * 1024);
         };
         auto publish = [&](const u32x4 *blk, int stage) __attribute__((always_inline)) {
 #pragma unroll
@@ -655,8 +724,23 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 if (unit < kUnits) *reinterpret_cast<u32x4 *>(lds + stage * kLdsBlockBytes + unit * 16) = blk[i];
             }
         };
+        // With `ready` set the slots are produced while this kernel runs: lane 0 of the workgroup
+        // checks the flag of chunk ci + 2 before the barrier that precedes its fetch; the flag is
+        // read one step early (`seen`), so the check normally costs nothing.
+        const bool poll = (P == 0) && tid == 0 && ready != nullptr;
+        bool gave_up = false;
+        uint32_t seen = epoch;
+        if (ready) {
+            if (poll) {
+                wait_ready(ready, epoch, status, gave_up);
+                if (c_begin + 1 < c_end) wait_ready(ready + 1, epoch, status, gave_up);
+            }
+            __syncthreads();
+        }
         fetch(slot0, pre[0], un[0]);
         if (c_begin + 1 < c_end) fetch(slot0 + slot_stride, pre[1], un[1]);
+        if (poll && c_begin + 2 < c_end)
+            seen = __hip_atomic_load(ready + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         publish(pre[0], 0);
 
         const uint32_t o_rstride = (uint32_t)H * D * 4;      // bytes between consecutive tokens of o
@@ -682,6 +766,8 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                     for (int e = 0; e < 8; ++e) Sb[2 * P + t][s][e] = (_Float16)S[t][8 * s + e];
                     *reinterpret_cast<h8 *>(xs + ((2 * P + t) * 2 + s) * kFragBytes) = Sb[2 * P + t][s];
                 }
+            if (poll && ci + 2 < c_end && seen != epoch)
+                wait_ready(ready + (ci + 2 - c_begin), epoch, status, gave_up);
             __syncthreads();                                                 // B1: S exchange and LDS stage ready
 
             f32x16 av, ao = {0.f};
@@ -691,6 +777,8 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 for (int z = 0; z < 4; ++z) av[4 * i + z] = un[stage][i][z];
             // this register set is free now: start fetching chunk ci + 2 into it
             if (ci + 2 < c_end) fetch(slot0 + (ci + 2 - c_begin) * slot_stride, pre[stage], un[stage]);
+            if (poll && ci + 3 < c_end)
+                seen = __hip_atomic_load(ready + (ci + 3 - c_begin), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             // the partner's two d_k tiles of S
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -786,7 +874,8 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
 __global__ __launch_bounds__(512)
 void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, float *state_out,
                      const int32_t *__restrict__ cu_seqlens, float *__restrict__ o, int64_t T, int H,
-                     int64_t seg_chunks, int64_t seg_index)
+                     int64_t seg_chunks, int64_t seg_index, const uint32_t *ready, uint32_t epoch,
+                     uint32_t *status)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -802,10 +891,21 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
     const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks) * H + h) * (int64_t)kSlotBytes;
     const int64_t slot_stride = (int64_t)H * kSlotBytes;
 
+    const uint32_t *flag0 = ready ? ready + (int64_t)blockIdx.x * seg_chunks : nullptr;
+
     if (wave < 4)
-        kda_scan_body<0>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h);
+        kda_scan_body<0>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
+                         flag0, epoch, status);
     else
-        kda_scan_body<1>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h);
+        kda_scan_body<1>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
+                         flag0, epoch, status);
+}
+
+// flags and status word of the overlapped mode start every call at zero
+__global__ void kda_fill_u32_kernel(uint32_t *p, int64_t n, uint32_t value)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
 }
 
 // ----------------------------------------------------------------------------------
@@ -820,24 +920,69 @@ static int64_t max_chunks_per_seq(const kda_dims *d)
     return (longest + kChunk - 1) / kChunk;
 }
 
-static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full)
+static size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workspace: [slots of one segment][state carry][ready flags, one per slot][status word]
+static SegPlan plan_with(const kda_dims *d, int64_t sc)
 {
     SegPlan p;
     const int64_t maxc = max_chunks_per_seq(d);
-    const size_t carry = (size_t)d->num_seqs * d->heads * D * D * sizeof(float);
-    const size_t per_chunk_index = (size_t)d->num_seqs * d->heads * kSlotBytes;
-    int64_t sc = maxc;
-    if (!full && per_chunk_index > 0) {
-        const size_t avail = workspace_bytes > carry ? workspace_bytes - carry : 0;
-        const int64_t fit = (int64_t)(avail / per_chunk_index);
-        if (fit < sc) sc = fit;
-    }
-    if (sc < 1) sc = 1;
+    const size_t streams = (size_t)d->num_seqs * d->heads;
+    const size_t carry = streams * D * D * sizeof(float);
     p.seg_chunks = sc;
     p.num_segments = (maxc + sc - 1) / sc;
-    p.carry_offset = (size_t)sc * per_chunk_index;
-    p.total_bytes = p.carry_offset + carry;
+    p.carry_offset = (size_t)sc * streams * kSlotBytes;
+    p.flags_offset = p.carry_offset + carry;
+    p.status_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
+    p.total_bytes = p.status_offset + 256;
     return p;
+}
+
+// The plan with the most chunk indices per segment that fits `workspace_bytes` (full: no limit).
+static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full)
+{
+    const int64_t maxc = max_chunks_per_seq(d);
+    int64_t sc = maxc < 1 ? 1 : maxc;
+    if (!full) {
+        const size_t streams = (size_t)d->num_seqs * d->heads;
+        const size_t per_chunk_index = streams * (kSlotBytes + sizeof(uint32_t));
+        const size_t fixed = plan_with(d, 1).total_bytes - per_chunk_index;
+        const size_t avail = workspace_bytes > fixed ? workspace_bytes - fixed : 0;
+        const int64_t fit = per_chunk_index ? (int64_t)(avail / per_chunk_index) : sc;
+        if (fit < sc) sc = fit;
+        if (sc < 1) sc = 1;
+        while (sc > 1 && plan_with(d, sc).total_bytes > workspace_bytes) --sc;   // rounding of the flag area
+    }
+    return plan_with(d, sc);
+}
+
+// Helper stream and events of the overlapped mode, created on first use, one set per device
+// and host thread, never destroyed.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    int compute_units = 0;
+    bool tried = false, ok = false;
+};
+
+static SideStream *side_stream()
+{
+    constexpr int kMaxDevices = 64;
+    static thread_local SideStream table[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    SideStream *s = &table[dev];
+    if (!s->tried) {
+        s->tried = true;
+        hipDeviceProp_t prop;
+        s->ok = hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+                hipStreamCreateWithFlags(&s->stream, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&s->fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&s->join, hipEventDisableTiming) == hipSuccess;
+        if (s->ok) s->compute_units = prop.multiProcessorCount;
+        (void)hipGetLastError();
+    }
+    return s->ok ? s : nullptr;
 }
 
 }  // namespace mfma
@@ -848,11 +993,14 @@ size_t chunk_mfma_workspace_size(const kda_dims *d, bool minimal)
     if (minimal) {
         // four chunk indices per segment keep the launches from being pure overhead
         const int64_t maxc = mfma::max_chunks_per_seq(d);
-        const int64_t sc = maxc < 4 ? maxc : 4;
-        return (size_t)sc * d->num_seqs * d->heads * mfma::kSlotBytes +
-               (size_t)d->num_seqs * d->heads * mfma::D * mfma::D * sizeof(float);
+        return mfma::plan_with(d, maxc < 4 ? maxc : 4).total_bytes;
     }
     return mfma::make_plan(d, 0, true).total_bytes;
+}
+
+size_t chunk_mfma_status_offset(const kda_dims *d, size_t workspace_bytes)
+{
+    return mfma::make_plan(d, workspace_bytes, false).status_offset;
 }
 
 kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, const void *v,
@@ -893,20 +1041,58 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
 
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     float *carry = hT ? hT : reinterpret_cast<float *>(ws + plan.carry_offset);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(ws + plan.flags_offset);
+    uint32_t *status = reinterpret_cast<uint32_t *>(ws + plan.status_offset);
     const uint16_t *q16 = static_cast<const uint16_t *>(q), *k16 = static_cast<const uint16_t *>(k),
                    *v16 = static_cast<const uint16_t *>(v), *g16 = static_cast<const uint16_t *>(log_alpha),
                    *b16 = static_cast<const uint16_t *>(beta);
+    const unsigned streams = (unsigned)(d->num_seqs * d->heads);
+    const dim3 intra_grid((unsigned)(slots * d->heads));
+
+    // Overlapped mode: kda_intra runs on a helper stream while kda_scan, on the caller's stream,
+    // consumes each slot as soon as its flag is up.  kda_scan keeps one compute unit per
+    // (sequence, head) busy, so this needs enough units left over for kda_intra to make progress
+    // (it never waits for anything, which is what rules out a deadlock).
+    SideStream *side = nullptr;
+    if (g_phase_mask == 3 && g_overlap) {
+        side = side_stream();
+        if (side && (int64_t)streams * 4 > (int64_t)side->compute_units * 3) side = nullptr;
+    }
+
+    if (side) {
+        const int64_t nflags = (int64_t)(plan.status_offset - plan.flags_offset) / 4 + 1;   // flags + status
+        hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream,
+                           flags, nflags, 0u);
+    }
     for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
-        if (g_phase_mask & 1)
-            hipLaunchKernelGGL(kda_intra_kernel, dim3((unsigned)(slots * d->heads)), dim3(256), kIntraLds,
-                               stream, q16, k16, v16, g16, b16, cu, ws, (int64_t)d->seqlen, (int)d->heads,
-                               plan.seg_chunks, seg, d->scale);
         const float *sin = (seg == 0) ? h0 : carry;
         float *sout = (plan.num_segments > 1 || hT) ? carry : nullptr;
-        if (g_phase_mask & 2)
-            hipLaunchKernelGGL(kda_scan_kernel, dim3((unsigned)(d->num_seqs * d->heads)), dim3(512), scan_lds, stream,
-                               ws, sin, sout, cu, static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads,
-                               plan.seg_chunks, seg);
+        if (side) {
+            // kda_intra of this segment may start once everything queued so far on the caller's
+            // stream (the inputs' producers, the flag reset, the previous segment's scan) is done
+            const uint32_t epoch = (uint32_t)(seg + 1);
+            if (hipEventRecord(side->fork, stream) != hipSuccess ||
+                hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+                return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
+            hipLaunchKernelGGL(kda_scan_kernel, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
+                               static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
+                               flags, epoch, status);
+            hipLaunchKernelGGL(kda_intra_kernel, intra_grid, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16,
+                               b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
+                               (int)d->num_seqs, flags, epoch);
+            if (hipEventRecord(side->join, side->stream) != hipSuccess ||
+                hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
+                return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
+        } else {
+            if (g_phase_mask & 1)
+                hipLaunchKernelGGL(kda_intra_kernel, intra_grid, dim3(256), kIntraLds, stream, q16, k16, v16, g16,
+                                   b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
+                                   (int)d->num_seqs, (uint32_t *)nullptr, 0u);
+            if (g_phase_mask & 2)
+                hipLaunchKernelGGL(kda_scan_kernel, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
+                                   static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
+                                   (const uint32_t *)nullptr, 0u, (uint32_t *)nullptr);
+        }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));

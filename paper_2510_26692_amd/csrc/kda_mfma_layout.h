@@ -60,6 +60,8 @@ struct SegPlan {
     int64_t seg_chunks;      // chunks per sequence held in the workspace at once
     int64_t num_segments;    // passes over the time axis
     size_t carry_offset;     // byte offset of the state carry buffer in the workspace
+    size_t flags_offset;     // one u32 "slot ready" flag per (sequence, head, chunk of the segment)
+    size_t status_offset;    // u32 set by kda_scan when a bounded wait for a flag ran out
     size_t total_bytes;
 };
 

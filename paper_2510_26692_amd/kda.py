@@ -59,8 +59,12 @@ def load_library():
     lib.kda_chunk_fwd_min_workspace_size.argtypes = [dp]
     lib.kda_chunk_fwd.restype = ctypes.c_int
     lib.kda_chunk_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kda_chunk_fwd_check.restype = ctypes.c_int
+    lib.kda_chunk_fwd_check.argtypes = [dp, vp, sz, vp]
     lib.kda_debug_set_phase_mask.restype = None
     lib.kda_debug_set_phase_mask.argtypes = [ctypes.c_int]
+    lib.kda_debug_set_overlap.restype = None
+    lib.kda_debug_set_overlap.argtypes = [ctypes.c_int]
     lib.kda_recurrent_step.restype = ctypes.c_int
     lib.kda_recurrent_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
@@ -77,6 +81,10 @@ def kda_last_error():
 
 def kda_debug_set_phase_mask(mask):
     load_library().kda_debug_set_phase_mask(int(mask))
+
+
+def kda_debug_set_overlap(enabled):
+    load_library().kda_debug_set_overlap(int(bool(enabled)))
 
 
 def kda_status_string(status):
@@ -123,12 +131,25 @@ def kda_chunk_fwd_min_workspace_size(dims):
     return int(load_library().kda_chunk_fwd_min_workspace_size(ctypes.byref(dims)))
 
 
+def kda_chunk_fwd_check(dims, workspace):
+    """Waits for the current stream and raises KdaError if the kda_chunk_fwd call that used
+    `workspace` with `dims` reported a failed wait (see kda_chunk_fwd_check in kda.h)."""
+    if workspace is None:
+        return
+    st = load_library().kda_chunk_fwd_check(ctypes.byref(dims), _ptr(workspace),
+                                            ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                            _stream_ptr(workspace.device))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+
+
 def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0, o=None,
-                  hT=None, want_hT=True, workspace=None, max_seqlen=0):
+                  hT=None, want_hT=True, workspace=None, max_seqlen=0, check=False):
     """Chunkwise prefill.  q,k,log_alpha [B,T,H,dk]; v [B,T,H,dv]; beta [B,T,H];
     h0 [N,H,dk,dv] fp32 or None; cu_seqlens int32 [N+1] on device or None.
     Returns (o fp32 [B,T,H,dv], hT fp32 [N,H,dk,dv] or None).  `o`, `hT` and
-    `workspace` (a uint8 device tensor) may be passed in to avoid allocation."""
+    `workspace` (a uint8 device tensor) may be passed in to avoid allocation.
+    check=True synchronises and runs kda_chunk_fwd_check before returning."""
     lib = load_library()
     dev = _check_dev(q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace)
     if not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype):
@@ -159,6 +180,8 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
                            _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(dev))
     if st != 0:
         raise KdaError(st, kda_last_error())
+    if check:
+        kda_chunk_fwd_check(dims, workspace)
     return o, hT
 
 

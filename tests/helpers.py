@@ -55,7 +55,7 @@ def check_prefill(d, tol, scale=1.0, **kw):
     import paper_2510_26692_amd as kda
     dd = to_device(d)
     o, hT = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"],
-                              h0=dd.get("h0"), cu_seqlens=dd.get("cu_seqlens"), scale=scale, **kw)
+                              h0=dd.get("h0"), cu_seqlens=dd.get("cu_seqlens"), scale=scale, check=True, **kw)
     torch.cuda.synchronize()
     o_ref, hT_ref = oracle_prefill(d, scale)
     B, T, H, _ = d["q"].shape

@@ -109,3 +109,31 @@ def test_bf16_segmented_workspace_matches_single_segment():
         kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"],
                           workspace=torch.empty(small - 256, dtype=torch.uint8, device="cuda"))
     assert ei.value.status == 3
+
+
+def test_bf16_overlapped_kernels_match_the_serial_order():
+    """With few (sequence, head) pairs the sequential kernel runs next to the per-chunk kernel and
+    picks up each workspace slot when its flag goes up.  The arithmetic is the same, so the
+    results must equal, bit for bit, those of the strictly serial order, also when the workspace
+    still holds the slots and flags of an earlier call with other inputs, or garbage."""
+    import paper_2510_26692_amd as kda
+    ws = None
+    try:
+        for seed, fill in ((21, 0xFF), (22, None), (23, 0x01)):
+            x = si.make_prefill(3, 1500, 4, 128, 128, "bf16", -2.0, seed, 0.02)
+            dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+            dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
+            if ws is None:
+                ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
+            if fill is not None:
+                ws.fill_(fill)
+            kda.kda_debug_set_overlap(1)
+            o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                                       workspace=ws, check=True)
+            o1, h1 = o1.clone(), h1.clone()
+            kda.kda_debug_set_overlap(0)
+            o2, h2 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                                       workspace=ws, check=True)
+            assert torch.equal(o1, o2) and torch.equal(h1, h2), seed
+    finally:
+        kda.kda_debug_set_overlap(1)
