@@ -124,18 +124,18 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
                       const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
                       uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
-                      int64_t seg_index, float scale, int num_seqs, uint32_t *ready, uint32_t epoch)
+                      int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
-    // Workgroup -> (sequence n, chunk, head h).  With `ready` set the grid is ordered by chunk
-    // index first, so that the slots a concurrently running kda_scan needs next are produced
-    // first; otherwise sequence-major (consecutive workgroups write consecutive slots).
-    const int h = (int)(blockIdx.x % (unsigned)H);
-    const int64_t bq = blockIdx.x / (unsigned)H;
-    const int n = ready ? (int)(bq % num_seqs) : (int)(bq / seg_chunks);
-    const int64_t cl = ready ? bq / num_seqs : bq % seg_chunks;
+    // Workgroup -> (head, sequence, chunk) straight from the 3-D grid (no divisions).  x = head;
+    // with `ready` set y = sequence and z = chunk, so that workgroups are dispatched by chunk index
+    // first and the slots a concurrently running kda_scan needs next are produced first;
+    // otherwise y = chunk and z = sequence (consecutive workgroups write consecutive slots).
+    const int h = (int)blockIdx.x;
+    const int n = (int)(ready ? blockIdx.y : blockIdx.z);
+    const int64_t cl = ready ? blockIdx.z : blockIdx.y;
     const int64_t slot = n * seg_chunks + cl;
     const int64_t ci = seg_index * seg_chunks + cl;
     int64_t tok_base, len;
@@ -155,17 +155,17 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int tok = 16 * R + m;
 
     // ---- loads: 16 bytes (8 channels) per ks and tensor ----
+    // (log_alpha first: the running sum below waits for it, k and q are not needed before B2)
     u32x4 kraw[4], qraw[4], graw[4];
+    {
+        const u32x4 z = {0, 0, 0, 0};
+        const int64_t off = ((tok0 + tok) * H + h) * (int64_t)D + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        u32x4 z = {0, 0, 0, 0};
-        kraw[ks] = z; qraw[ks] = z; graw[ks] = z;
-        if (tok < nv) {
-            const int64_t off = ((tok0 + tok) * H + h) * (int64_t)D + 32 * ks + 8 * g;
-            kraw[ks] = *reinterpret_cast<const u32x4 *>(k + off);
-            qraw[ks] = *reinterpret_cast<const u32x4 *>(q + off);
-            graw[ks] = *reinterpret_cast<const u32x4 *>(log_alpha + off);
-        }
+        for (int ks = 0; ks < 4; ++ks) graw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(log_alpha + off + 32 * ks) : z;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) kraw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(k + off + 32 * ks) : z;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) qraw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(q + off + 32 * ks) : z;
     }
     if (tid < kChunk)
         sBeta[tid] = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
@@ -943,6 +943,7 @@ static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full)
 {
     const int64_t maxc = max_chunks_per_seq(d);
     int64_t sc = maxc < 1 ? 1 : maxc;
+    if (sc > 65535) sc = 65535;                               // grid dimension limit of kda_intra
     if (!full) {
         const size_t streams = (size_t)d->num_seqs * d->heads;
         const size_t per_chunk_index = streams * (kSlotBytes + sizeof(uint32_t));
@@ -1023,10 +1024,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
     if (plan.total_bytes > workspace_bytes)
         return fail(KDA_ERR_WORKSPACE, "workspace has %zu bytes, segment plan needs %zu", workspace_bytes,
                     plan.total_bytes);
-    const int64_t slots = (int64_t)d->num_seqs * plan.seg_chunks;
-    if (slots * d->heads > 0x7fffffffLL)
-        return fail(KDA_ERR_UNSUPPORTED, "too many (chunk, head) pairs per segment for one launch: %lld",
-                    (long long)(slots * d->heads));
+    if (d->num_seqs > 65535)
+        return fail(KDA_ERR_UNSUPPORTED, "more than 65535 sequences in one call: %d", d->num_seqs);
 
     const size_t scan_lds = (size_t)scan::kLds;
     {
@@ -1047,7 +1046,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
                    *v16 = static_cast<const uint16_t *>(v), *g16 = static_cast<const uint16_t *>(log_alpha),
                    *b16 = static_cast<const uint16_t *>(beta);
     const unsigned streams = (unsigned)(d->num_seqs * d->heads);
-    const dim3 intra_grid((unsigned)(slots * d->heads));
+    const dim3 intra_grid_serial((unsigned)d->heads, (unsigned)plan.seg_chunks, (unsigned)d->num_seqs);
+    const dim3 intra_grid_overlap((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)plan.seg_chunks);
 
     // Overlapped mode: kda_intra runs on a helper stream while kda_scan, on the caller's stream,
     // consumes each slot as soon as its flag is up.  kda_scan keeps one compute unit per
@@ -1077,17 +1077,17 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
             hipLaunchKernelGGL(kda_scan_kernel, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                flags, epoch, status);
-            hipLaunchKernelGGL(kda_intra_kernel, intra_grid, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16,
+            hipLaunchKernelGGL(kda_intra_kernel, intra_grid_overlap, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16,
                                b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
-                               (int)d->num_seqs, flags, epoch);
+                               flags, epoch);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
         } else {
             if (g_phase_mask & 1)
-                hipLaunchKernelGGL(kda_intra_kernel, intra_grid, dim3(256), kIntraLds, stream, q16, k16, v16, g16,
+                hipLaunchKernelGGL(kda_intra_kernel, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16,
                                    b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
-                                   (int)d->num_seqs, (uint32_t *)nullptr, 0u);
+                                   (uint32_t *)nullptr, 0u);
             if (g_phase_mask & 2)
                 hipLaunchKernelGGL(kda_scan_kernel, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                    static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
