@@ -98,15 +98,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slot_resource(const uint8_t *s
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(slot), 0, kSlotBytes, 0x00020000);
 }
-template <typename V> __device__ __forceinline__ void slot_store16(__amdgpu_buffer_rsrc_t rs, int off, V val)
+template <int kPolicy, typename V> __device__ __forceinline__ void slot_store16(__amdgpu_buffer_rsrc_t rs, int off, V val)
 {
     static_assert(sizeof(V) == 16, "16-byte store");
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), rs, off, 0, kCacheDevice);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), rs, off, 0, kPolicy);
 }
-template <typename V> __device__ __forceinline__ void slot_store8(__amdgpu_buffer_rsrc_t rs, int off, V val)
+template <int kPolicy, typename V> __device__ __forceinline__ void slot_store8(__amdgpu_buffer_rsrc_t rs, int off, V val)
 {
     static_assert(sizeof(V) == 8, "8-byte store");
-    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, val), rs, off, 0, kCacheDevice);
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, val), rs, off, 0, kPolicy);
 }
 template <int kPolicy> __device__ __forceinline__ u32x4 slot_load16(__amdgpu_buffer_rsrc_t rs, int off)
 {
@@ -119,6 +119,9 @@ template <int kPolicy> __device__ __forceinline__ u32x4 slot_load16(__amdgpu_buf
 // Lane (m = lane % 16, g = lane / 16) of wave R owns token 16 R + m and the 32 channels
 // 32 ks + 8 g + e (ks = 0..3, e = 0..7): exactly its A/B operand slots of the 16x16x32 MFMA,
 // so the decay-scaled operands of the A-matrix products are built in registers.
+// kHandoff: the slot is handed to a kda_scan that runs at the same time (write-through stores and a
+// ready flag); otherwise the stores are ordinary ones and the kernel boundary publishes them.
+template <bool kHandoff>
 __global__ __launch_bounds__(256, 2)
 void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
                       const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
@@ -128,14 +131,15 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    constexpr int kPolicy = kHandoff ? kCacheDevice : 0;
 
     // Workgroup -> (head, sequence, chunk) straight from the 3-D grid (no divisions).  x = head;
-    // with `ready` set y = sequence and z = chunk, so that workgroups are dispatched by chunk index
+    // with kHandoff y = sequence and z = chunk, so that workgroups are dispatched by chunk index
     // first and the slots a concurrently running kda_scan needs next are produced first;
     // otherwise y = chunk and z = sequence (consecutive workgroups write consecutive slots).
     const int h = (int)blockIdx.x;
-    const int n = (int)(ready ? blockIdx.y : blockIdx.z);
-    const int64_t cl = ready ? blockIdx.z : blockIdx.y;
+    const int n = (int)(kHandoff ? blockIdx.y : blockIdx.z);
+    const int64_t cl = kHandoff ? blockIdx.z : blockIdx.y;
     const int64_t slot = n * seg_chunks + cl;
     const int64_t ci = seg_index * seg_chunks + cl;
     int64_t tok_base, len;
@@ -225,7 +229,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         *reinterpret_cast<float2 *>(tb + 4 * 512) = make_float2(fast_exp2(t0[r1] + t0[r2]), fast_exp2(t1[r1] + t1[r2]));
         if (R == 0) {   // gamma^C: decay of the whole chunk
             float2 gc = make_float2(fast_exp2(t0[0] + t0[1] + t0[2] + t0[3]), fast_exp2(t1[0] + t1[1] + t1[2] + t1[3]));
-            slot_store8(out, kOffGc + c2 * 4, gc);
+            slot_store8<kPolicy>(out, kOffGc + c2 * 4, gc);
         }
     }
     uint32_t strong_all = 0;        // union over g of this sub-chunk's strong-channel slots
@@ -326,7 +330,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             u32x4 o4;
             if (odd) { o4[0] = r0; o4[1] = r1; o4[2] = b0; o4[3] = b1; }
             else     { o4[0] = a0; o4[1] = a1; o4[2] = r0; o4[3] = r1; }
-            slot_store16(out, kOffQp + frag_rts(tok >> 5, ks, g >> 1) * kFragBytes + ((tok & 31) + 32 * (g & 1)) * 16, o4);
+            slot_store16<kPolicy>(out, kOffQp + frag_rts(tok >> 5, ks, g >> 1) * kFragBytes + ((tok & 31) + 32 * (g & 1)) * 16, o4);
         }
     }
 
@@ -466,7 +470,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                              ((uint32_t)sKp[t1 * kLdH + 32 * tau + x] << 16);
             }
             u32x4 o4 = {w4[0], w4[1], w4[2], w4[3]};
-            slot_store16(out, kOffKt + f * kFragBytes + lane * 16, o4);
+            slot_store16<kPolicy>(out, kOffKt + f * kFragBytes + lane * 16, o4);
         }
     }
     __syncthreads();                                                               // B6
@@ -521,7 +525,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             const u32x2 a = *reinterpret_cast<const u32x2 *>(lds + kAq + at);
             const u32x2 b = *reinterpret_cast<const u32x2 *>(lds + kAq + at + 16);
             u32x4 o4 = {a[0], a[1], b[0], b[1]};
-            slot_store16(out, kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16, o4);
+            slot_store16<kPolicy>(out, kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16, o4);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -576,16 +580,16 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 u32x4 o4;
 #pragma unroll
                 for (int z = 0; z < 4; ++z) o4[z] = pack_h2(-wt[8 * s + 2 * z], -wt[8 * s + 2 * z + 1]);
-                slot_store16(out, kOffWn + frag_rts(rho, wave, s) * kFragBytes + lane * 16, o4);
+                slot_store16<kPolicy>(out, kOffWn + frag_rts(rho, wave, s) * kFragBytes + lane * 16, o4);
             }
 #pragma unroll
             for (int j4 = 0; j4 < 4; ++j4) {
                 f32x4 o4 = {u[4 * j4], u[4 * j4 + 1], u[4 * j4 + 2], u[4 * j4 + 3]};
-                slot_store16(out, kOffU + (((rho * 4 + wave) * 4 + j4) * 64 + lane) * 16, o4);
+                slot_store16<kPolicy>(out, kOffU + (((rho * 4 + wave) * 4 + j4) * 64 + lane) * 16, o4);
             }
         }
     }
-    if (ready) {
+    if (kHandoff) {
         // Hand the finished slot to kda_scan.  Every store to the slot is a write-through store;
         // the barrier's release makes each wave wait until all of its stores have completed, so
         // the slot is in place, device-wide, before one lane raises its flag.
@@ -620,9 +624,7 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-constexpr int kWaves = 8;
 constexpr int kUnits = kLdsBlockBytes / 16;                  // 16-byte units per staged block
-constexpr int kCopies = (kUnits + 63) / 64;                  // wave-wide LDS-direct loads per block
 constexpr int kXS = 2 * kLdsBlockBytes;                      // fp16 S exchange: [c][tau][s] frags
 constexpr int kXV = kXS + 4 * 4 * 2 * kFragBytes;            // fp16 V_new exchange: [c][rho][s] frags
 constexpr int kLds = kXV + 4 * 2 * 2 * kFragBytes;
@@ -1029,8 +1031,11 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
 
     const size_t scan_lds = (size_t)scan::kLds;
     {
-        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel),
+        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<false>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
+        if (e1 == hipSuccess)
+            e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
         hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
         if (e1 != hipSuccess || e2 != hipSuccess)
@@ -1077,7 +1082,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
             hipLaunchKernelGGL(kda_scan_kernel, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                flags, epoch, status);
-            hipLaunchKernelGGL(kda_intra_kernel, intra_grid_overlap, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16,
+            hipLaunchKernelGGL(kda_intra_kernel<true>, intra_grid_overlap, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16,
                                b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
                                flags, epoch);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
@@ -1085,7 +1090,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
         } else {
             if (g_phase_mask & 1)
-                hipLaunchKernelGGL(kda_intra_kernel, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16,
+                hipLaunchKernelGGL(kda_intra_kernel<false>, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16,
                                    b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
                                    (uint32_t *)nullptr, 0u);
             if (g_phase_mask & 2)
