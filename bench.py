@@ -23,6 +23,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0          # dense fp16/bf16 matrix cores
 
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/pmc_traffic_bench_cfg1_cfg4.txt),
+# scaled by what the same counters read for a 1 GiB copy.  Counter collection serialises kernels, so the
+# prefill figure is that of the two kernels run one after the other (both summed).
+MEASURED_TRAFFIC_BYTES = {"cfg1_prefill_bf16": 1203.1e6, "cfg4_decode_bf16": 1086.7e6}
+
 # Algorithmic work per (token, head) at d_k = d_v = 128, C = 64.
 FLOP_PER_TOKHEAD = 6 * 128 * 128 + 3 * 64 * 128 + 64 * 64        # paper's FLOPs model: 126976
 BYTES_PER_TOKHEAD = (3 * 128 + 128) * 2 + 2 + 128 * 4            # q,k,log_alpha,v,beta bf16 + o fp32: 1538
@@ -53,6 +58,12 @@ def main():
     ap.add_argument("--no-breakdown", action="store_true",
                     help="skip the extra serial / single-kernel timing passes (keeps a profile of this "
                          "run down to the launches of the timed configuration)")
+    ap.add_argument("--serial", action="store_true",
+                    help="run the two prefill kernels one after the other (needed under tools that serialise "
+                         "kernels, e.g. rocprofv3 --pmc); implies --no-breakdown")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="first run a plain 1 GiB device copy three times, so that a byte counter collected over "
+                         "this run can be scaled by what it reads for a transfer of known size")
     ap.add_argument("--workload", default="cfg1_prefill_bf16",
                     help="prefill workload: cfg1_prefill_bf16 (default), cfg2_varlen_bf16, cfg3_long_bf16")
     args = ap.parse_args()
@@ -70,6 +81,16 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.serial:
+        args.no_breakdown = True
+        kda.kda_debug_set_overlap(0)
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ prefill workload
     name = args.workload
@@ -134,7 +155,8 @@ def main():
     alg_bytes = tokheads * BYTES_PER_TOKHEAD + 2 * dims.num_seqs * H * 128 * 128 * 4
     streams = dims.num_seqs * H
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    overlapped = 4 * streams <= 3 * cus          # the library's own rule for running the kernels side by side
+    # the library's own rule for running the kernels side by side
+    overlapped = 4 * streams <= 3 * cus and not args.serial
     if overlapped or ms_scan is None:
         # kda_scan is launched first and retires last: its duration is the call's, up to the flag
         # reset (a few microseconds) and the launch gaps, which the event pair also brackets
@@ -145,7 +167,7 @@ def main():
         "kernel": dom_name, "bound": "hbm",
         "achieved": alg_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": alg_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(name),
         "ms_kernel": dom_ms,
         "algorithmic_bytes": alg_bytes,
         "kernels_ms_alone": {"kda_intra_kernel": ms_intra, "kda_scan_kernel": ms_scan, "both_serial": ms_serial},
@@ -180,7 +202,8 @@ def main():
         "roofline": {"kernel": "kda_step_kernel", "bound": "hbm",
                      "achieved": dec_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dec_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get("cfg4_decode_bf16"),
+                     "algorithmic_bytes": dec_bytes},
     }
 
     # ------------------------------------------------------------------ CPU baseline (oracle)

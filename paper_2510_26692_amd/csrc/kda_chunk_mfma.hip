@@ -894,6 +894,8 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
     const int64_t slot_stride = (int64_t)H * kSlotBytes;
 
     const uint32_t *flag0 = ready ? ready + (int64_t)blockIdx.x * seg_chunks : nullptr;
+    // nothing is waited for without flags: leave a clean status word for kda_chunk_fwd_check
+    if (!ready && status && blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
 
     if (wave < 4)
         kda_scan_body<0>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
@@ -1096,7 +1098,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
             if (g_phase_mask & 2)
                 hipLaunchKernelGGL(kda_scan_kernel, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                    static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
-                                   (const uint32_t *)nullptr, 0u, (uint32_t *)nullptr);
+                                   (const uint32_t *)nullptr, 0u, status);
         }
     }
     hipError_t e = hipGetLastError();
