@@ -591,8 +591,10 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     }
     if (kHandoff) {
         // Hand the finished slot to kda_scan.  Every store to the slot is a write-through store;
-        // the barrier's release makes each wave wait until all of its stores have completed, so
-        // the slot is in place, device-wide, before one lane raises its flag.
+        // each wave waits until all of its stores have completed (vmcnt(0): a workgroup barrier
+        // alone does not wait for global stores), so after the barrier the slot is in place,
+        // device-wide, and one lane raises its flag.
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
         __syncthreads();
         if (tid == 0)
             __hip_atomic_store(ready + ((int64_t)n * H + h) * seg_chunks + cl, epoch, __ATOMIC_RELAXED,
