@@ -668,7 +668,7 @@ __device__ __noinline__ void wait_ready(const uint32_t *flag, uint32_t epoch, ui
     }
 }
 
-template <int P>
+template <int P, bool kFlags>
 __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
                                               const float *state_in, float *state_out, float *o,
                                               int64_t st_base, int64_t tok_base, int64_t len, int H,
@@ -702,7 +702,7 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
         f32x4 un[2][4];
         auto fetch = [&](const uint8_t *src, u32x4 *blk, f32x4 *u) __attribute__((always_inline)) {
             const __amdgpu_buffer_rsrc_t rs = slot_resource(src);
-            if (ready) {     // the slot was written while this kernel runs: device-scope loads
+            if (kFlags) {    // the slot was written while this kernel runs: device-scope loads
 #pragma unroll
                 for (int i = 0; i < kMyUnits; ++i) {
                     const int unit = tid + i * 512;
@@ -728,23 +728,25 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 if (unit < kUnits) *reinterpret_cast<u32x4 *>(lds + stage * kLdsBlockBytes + unit * 16) = blk[i];
             }
         };
-        // With `ready` set the slots are produced while this kernel runs: lane 0 of the workgroup
+        // With kFlags the slots are produced while this kernel runs: lane 0 of the workgroup
         // checks the flag of chunk ci + 2 before the barrier that precedes its fetch; the flag is
         // read one step early (`seen`), so the check normally costs nothing.
-        const bool poll = (P == 0) && tid == 0 && ready != nullptr;
+        const bool poll = kFlags && (P == 0) && tid == 0;
         bool gave_up = false;
         uint32_t seen = epoch;
-        if (ready) {
+        if (kFlags) {
             if (poll) {
                 wait_ready(ready, epoch, status, gave_up);
                 if (c_begin + 1 < c_end) wait_ready(ready + 1, epoch, status, gave_up);
             }
             __syncthreads();
         }
-        fetch(slot0, pre[0], un[0]);
-        if (c_begin + 1 < c_end) fetch(slot0 + slot_stride, pre[1], un[1]);
+        // (the flag load goes out before the slot loads: loads return in order, so the check of
+        // `seen` one step later must not have to wait for a whole slot fetch that was issued first)
         if (poll && c_begin + 2 < c_end)
             seen = __hip_atomic_load(ready + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        fetch(slot0, pre[0], un[0]);
+        if (c_begin + 1 < c_end) fetch(slot0 + slot_stride, pre[1], un[1]);
         publish(pre[0], 0);
 
         const uint32_t o_rstride = (uint32_t)H * D * 4;      // bytes between consecutive tokens of o
@@ -780,9 +782,9 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
 #pragma unroll
                 for (int z = 0; z < 4; ++z) av[4 * i + z] = un[stage][i][z];
             // this register set is free now: start fetching chunk ci + 2 into it
-            if (ci + 2 < c_end) fetch(slot0 + (ci + 2 - c_begin) * slot_stride, pre[stage], un[stage]);
             if (poll && ci + 3 < c_end)
                 seen = __hip_atomic_load(ready + (ci + 3 - c_begin), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (ci + 2 < c_end) fetch(slot0 + (ci + 2 - c_begin) * slot_stride, pre[stage], un[stage]);
             // the partner's two d_k tiles of S
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -875,6 +877,8 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
     }
 }
 
+// kFlags: the slots are produced by a kda_intra that runs at the same time (per-slot ready flags).
+template <bool kFlags>
 __global__ __launch_bounds__(512)
 void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, float *state_out,
                      const int32_t *__restrict__ cu_seqlens, float *__restrict__ o, int64_t T, int H,
@@ -895,15 +899,15 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
     const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks) * H + h) * (int64_t)kSlotBytes;
     const int64_t slot_stride = (int64_t)H * kSlotBytes;
 
-    const uint32_t *flag0 = ready ? ready + (int64_t)blockIdx.x * seg_chunks : nullptr;
+    const uint32_t *flag0 = kFlags ? ready + (int64_t)blockIdx.x * seg_chunks : nullptr;
     // nothing is waited for without flags: leave a clean status word for kda_chunk_fwd_check
-    if (!ready && status && blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
+    if (!kFlags && status && blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
 
     if (wave < 4)
-        kda_scan_body<0>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
+        kda_scan_body<0, kFlags>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
                          flag0, epoch, status);
     else
-        kda_scan_body<1>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
+        kda_scan_body<1, kFlags>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
                          flag0, epoch, status);
 }
 
@@ -1040,8 +1044,11 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
         if (e1 == hipSuccess)
             e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
-        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel),
+        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
+        if (e2 == hipSuccess)
+            e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
         if (e1 != hipSuccess || e2 != hipSuccess)
             return fail(KDA_ERR_LAUNCH, "cannot reserve LDS for the prefill kernels (%d, %d bytes)", kIntraLds,
                         (int)scan_lds);
@@ -1083,7 +1090,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
             if (hipEventRecord(side->fork, stream) != hipSuccess ||
                 hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
-            hipLaunchKernelGGL(kda_scan_kernel, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
+            hipLaunchKernelGGL(kda_scan_kernel<true>, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                flags, epoch, status);
             hipLaunchKernelGGL(kda_intra_kernel<true>, intra_grid_overlap, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16,
@@ -1098,7 +1105,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
                                    b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
                                    (uint32_t *)nullptr, 0u);
             if (g_phase_mask & 2)
-                hipLaunchKernelGGL(kda_scan_kernel, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
+                hipLaunchKernelGGL(kda_scan_kernel<false>, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                    static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                    (const uint32_t *)nullptr, 0u, status);
         }
