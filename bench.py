@@ -206,6 +206,29 @@ def main():
                      "algorithmic_bytes": dec_bytes},
     }
 
+    # pooled multi-token decode: the same 256 x 32 states addressed through a permuted index array,
+    # four tokens per sequence and call (state traffic is paid once per call, not once per token)
+    Tq = 4
+    perm = torch.randperm(N4, generator=torch.Generator().manual_seed(d4["seed"])).to(torch.int32).to(dev)
+    mt_host = [si.make_decode_tokens(N4, H4, dk4, dv4, d4["dtype"], d4["mu"], d4["seed"], 1 + t) for t in range(Tq)]
+    mt = {k_: torch.stack([t_[k_] for t_ in mt_host], dim=1).contiguous().to(dev) for k_ in mt_host[0]}
+    o4m = torch.empty(N4, Tq, H4, dv4, dtype=torch.float32, device=dev)
+
+    def decode_pooled():
+        kda.kda_recurrent_steps_pooled(mt["q"], mt["k"], mt["v"], mt["log_alpha"], mt["beta"], S, perm, o=o4m)
+
+    for _ in range(args.warmup):
+        decode_pooled()
+    ms_pooled = _time_region(torch, decode_pooled, args.steps)
+    pooled_bytes = 2 * N4 * H4 * dk4 * dv4 * 4 + Tq * (N4 * H4 * ((3 * dk4 + dv4) * 2 + 2) + N4 * H4 * dv4 * 4)
+    decode_obj["pooled_multi_token"] = {
+        "tokens_per_call": Tq, "ms_per_call": ms_pooled,
+        "decode_tokens_per_s": N4 * Tq / (ms_pooled * 1e-3),
+        "single_token_decode_tokens_per_s": N4 / (ms_decode * 1e-3),
+        "achieved_GBps": pooled_bytes / (ms_pooled * 1e-3) / 1e9,
+        "hbm_frac": pooled_bytes / (ms_pooled * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    }
+
     # ------------------------------------------------------------------ CPU baseline (oracle)
     cpu = None
     if not args.no_cpu_baseline:

@@ -148,6 +148,32 @@ kda_status kda_recurrent_step(const kda_dims *dims,
                               const void *log_alpha, const void *beta,
                               float *S, void *o, void *hip_stream);
 
+/*
+ * Decode over a state pool (serving-shaped variant of kda_recurrent_step, same
+ * Eq. (1) and Section 6.3): sequence n works on the state S_pool[state_indices[n]]
+ * and takes Tq = dims->seqlen new tokens (1 <= Tq <= 8) through it in order, e.g.
+ * the draft tokens of a speculative-decoding verification step.  The state is read
+ * once and written once per call, whatever Tq is.  dims->batch == dims->num_seqs = N.
+ *
+ *   q, k, log_alpha [N,Tq,H,dk]   in_dtype
+ *   v               [N,Tq,H,dv]   in_dtype
+ *   beta            [N,Tq,H]      in_dtype
+ *   S_pool          [P,H,dk,dv]   fp32 pool of P states; only the addressed ones are
+ *                                 read and written, in place
+ *   state_indices   [N]           int32, device memory; entry n in [0,P) names the state
+ *                                 of sequence n, a negative entry skips the sequence
+ *                                 (its rows of o are left untouched); NULL = 0,1,..,N-1.
+ *                                 Entries are not range-checked against P, and two
+ *                                 sequences naming the same state race.
+ *   o               [N,Tq,H,dv]   out_dtype; o of token t reads the state after token t
+ * All arithmetic is fp32.  No workspace.
+ */
+kda_status kda_recurrent_steps_pooled(const kda_dims *dims,
+                                      const void *q, const void *k, const void *v,
+                                      const void *log_alpha, const void *beta,
+                                      float *S_pool, const int32_t *state_indices,
+                                      void *o, void *hip_stream);
+
 /* Static description of a status code (never NULL). */
 const char *kda_status_string(kda_status status);
 

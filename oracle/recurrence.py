@@ -116,3 +116,26 @@ def kda_step(q, k, v, log_alpha, beta, S, scale=1.0):
                            np.asarray(v)[:, None], np.asarray(log_alpha)[:, None],
                            np.asarray(beta)[:, None], h0=S, scale=scale)
     return o[:, 0], S_new
+
+
+def kda_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=None, scale=1.0):
+    """Decode over a state pool (Section 6.3, Eq. (1) applied Tq times per sequence).
+
+    q, k, log_alpha: [N,Tq,H,dk]; v: [N,Tq,H,dv]; beta: [N,Tq,H]; S_pool: [P,H,dk,dv];
+    state_indices: int [N] (negative = sequence skipped) or None for 0..N-1.
+    Returns (o [N,Tq,H,dv], S_pool_new [P,H,dk,dv]) in float64; rows of o that belong to
+    skipped sequences are NaN, so a test notices if it compares them.  S_pool is not modified.
+    """
+    q = np.asarray(q)
+    N, Tq, H, dk = q.shape
+    dv = np.asarray(v).shape[-1]
+    idx = np.arange(N) if state_indices is None else np.asarray(state_indices).astype(np.int64)
+    pool = np.array(S_pool, dtype=np.float64, copy=True)
+    o = np.full((N, Tq, H, dv), np.nan)
+    act = np.nonzero(idx >= 0)[0]
+    if act.size:
+        o_a, S_a = kda_forward(q[act], np.asarray(k)[act], np.asarray(v)[act], np.asarray(log_alpha)[act],
+                               np.asarray(beta)[act], h0=pool[idx[act]], scale=scale)
+        o[act] = o_a
+        pool[idx[act]] = S_a
+    return o, pool

@@ -23,7 +23,9 @@ kda_status fail(kda_status code, const char *fmt, ...)
 
 // Kernel-side entry points (one per source file).
 kda_status recurrent_step_dispatch(const kda_dims *, const void *, const void *, const void *,
-                                   const void *, const void *, float *, void *, hipStream_t);
+                                   const void *, const void *, float *, void *, const int32_t *,
+                                   hipStream_t);
+int recurrent_max_steps();
 kda_status chunk_f32_dispatch(const kda_dims *, const void *, const void *, const void *,
                               const void *, const void *, const float *, const int32_t *, void *,
                               float *, hipStream_t);
@@ -192,7 +194,29 @@ kda_status kda_recurrent_step(const kda_dims *d, const void *q, const void *k, c
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(log_alpha) || !aligned16(S) ||
         !aligned16(o) || (reinterpret_cast<uintptr_t>(beta) & 1u))
         return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    return recurrent_step_dispatch(d, q, k, v, log_alpha, beta, S, o, static_cast<hipStream_t>(hip_stream));
+    return recurrent_step_dispatch(d, q, k, v, log_alpha, beta, S, o, nullptr,
+                                   static_cast<hipStream_t>(hip_stream));
+}
+
+kda_status kda_recurrent_steps_pooled(const kda_dims *d, const void *q, const void *k, const void *v,
+                                      const void *log_alpha, const void *beta, float *S_pool,
+                                      const int32_t *state_indices, void *o, void *hip_stream)
+{
+    g_last_error[0] = 0;
+    kda_status st = check_dims(d, false);
+    if (st != KDA_OK) return st;
+    if (d->seqlen < 1 || d->seqlen > recurrent_max_steps())
+        return fail(KDA_ERR_INVALID_ARG, "pooled decode takes 1..%d tokens per sequence, got %lld",
+                    recurrent_max_steps(), (long long)d->seqlen);
+    if (d->num_seqs == 0 || d->heads == 0) return KDA_OK;
+    if (!q || !k || !v || !log_alpha || !beta || !S_pool || !o)
+        return fail(KDA_ERR_INVALID_ARG, "q, k, v, log_alpha, beta, S_pool and o must be non-NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(log_alpha) || !aligned16(S_pool) ||
+        !aligned16(o) || (reinterpret_cast<uintptr_t>(beta) & 1u) ||
+        (reinterpret_cast<uintptr_t>(state_indices) & 3u))
+        return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned (state_indices: 4)");
+    return recurrent_step_dispatch(d, q, k, v, log_alpha, beta, S_pool, o, state_indices,
+                                   static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

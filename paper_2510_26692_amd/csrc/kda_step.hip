@@ -16,15 +16,23 @@
 
 namespace kda {
 
+// steps:   tokens per sequence handled by one launch (1 = plain decode; up to kMaxSteps for
+//          multi-token steps such as speculative verification): the state is read once, taken
+//          through the tokens in order in registers, and written once.
+// indices: NULL, or one state-pool slot per sequence (sequence n works on state indices[n];
+//          a negative entry skips the sequence).
+constexpr int kMaxSteps = 8;
+
 template <typename Tin, int DK, int DV>
 __global__ __launch_bounds__(DV * 2)
 void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                      const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
                      const Tin *__restrict__ beta, float *__restrict__ S,
-                     float *__restrict__ o, float scale)
+                     float *__restrict__ o, float scale, int H, int steps,
+                     const int32_t *__restrict__ indices)
 {
     constexpr int ROWS = DK / 8;             // state rows per lane
-    __shared__ float s_alpha[DK], s_k[DK], s_q[DK];
+    __shared__ float s_alpha[kMaxSteps][DK], s_k[kMaxSteps][DK], s_q[kMaxSteps][DK];
 
     const int64_t pair = blockIdx.x;         // (sequence, head) index
     const int tid = threadIdx.x;
@@ -34,72 +42,88 @@ void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     const int rg = lane >> 3;                // row group: rows rg, rg+8, ...
     const int col = wave * 32 + cg * 4;
 
+    const int64_t n = pair / H;
+    const int h = (int)(pair - n * H);
+    int64_t state = pair;                    // which dk x dv state this block works on
+    if (indices) {
+        const int32_t slot = indices[n];
+        if (slot < 0) return;                // uniform for the block
+        state = (int64_t)slot * H + h;
+    }
+    // token t of this pair: element offset (n * steps + t) * H + h in units of one head row
+    const int64_t row0 = n * steps * H + h;
+
     // Token vectors: decay, key and query are needed per row by every lane.
-    for (int i = tid; i < DK; i += DV * 2) {
-        const int64_t off = pair * DK + i;
-        s_alpha[i] = fast_exp2(load_as_float(log_alpha + off) * kLog2e);
-        s_k[i] = load_as_float(k + off);
-        s_q[i] = load_as_float(q + off);
+    for (int i = tid; i < steps * DK; i += DV * 2) {
+        const int t = i / DK, c = i - t * DK;
+        const int64_t off = (row0 + (int64_t)t * H) * DK + c;
+        s_alpha[t][c] = fast_exp2(load_as_float(log_alpha + off) * kLog2e);
+        s_k[t][c] = load_as_float(k + off);
+        s_q[t][c] = load_as_float(q + off);
     }
 
     // Stream the slice in: ROWS independent 16-byte loads per lane.
-    f32x4 *Sp = reinterpret_cast<f32x4 *>(S + pair * (int64_t)(DK * DV) + (int64_t)rg * DV + col);
+    f32x4 *Sp = reinterpret_cast<f32x4 *>(S + state * (int64_t)(DK * DV) + (int64_t)rg * DV + col);
     f32x4 s[ROWS];
 #pragma unroll
     for (int m = 0; m < ROWS; ++m) s[m] = __builtin_nontemporal_load(Sp + (int64_t)m * (8 * DV / 4));
 
-    float vv[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) vv[c] = load_as_float(v + pair * DV + col + c);
-    const float b = load_as_float(beta + pair);
-
     __syncthreads();
 
-    // Decay, then the memory's prediction S^T k for this lane's columns.
-    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+    for (int t = 0; t < steps; ++t) {
+        const int64_t row = row0 + (int64_t)t * H;
+        float vv[4];
 #pragma unroll
-    for (int m = 0; m < ROWS; ++m) {
-        const float a = s_alpha[rg + 8 * m];
-        const float kk = s_k[rg + 8 * m];
-        s[m].x *= a; s[m].y *= a; s[m].z *= a; s[m].w *= a;
-        p0 = fmaf(kk, s[m].x, p0); p1 = fmaf(kk, s[m].y, p1);
-        p2 = fmaf(kk, s[m].z, p2); p3 = fmaf(kk, s[m].w, p3);
-    }
-#pragma unroll
-    for (int d = 8; d < 64; d <<= 1) {
-        p0 += __shfl_xor(p0, d); p1 += __shfl_xor(p1, d);
-        p2 += __shfl_xor(p2, d); p3 += __shfl_xor(p3, d);
-    }
-    // w = beta * (v - S^T k): the delta-rule correction written along k.
-    const float w0 = b * (vv[0] - p0), w1 = b * (vv[1] - p1);
-    const float w2 = b * (vv[2] - p2), w3 = b * (vv[3] - p3);
+        for (int c = 0; c < 4; ++c) vv[c] = load_as_float(v + row * DV + col + c);
+        const float b = load_as_float(beta + row);
+        const bool last = t + 1 == steps;
 
-    float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+        // Decay, then the memory's prediction S^T k for this lane's columns.
+        float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
 #pragma unroll
-    for (int m = 0; m < ROWS; ++m) {
-        const float kk = s_k[rg + 8 * m];
-        const float qq = s_q[rg + 8 * m];
-        s[m].x = fmaf(kk, w0, s[m].x); s[m].y = fmaf(kk, w1, s[m].y);
-        s[m].z = fmaf(kk, w2, s[m].z); s[m].w = fmaf(kk, w3, s[m].w);
-        o0 = fmaf(qq, s[m].x, o0); o1 = fmaf(qq, s[m].y, o1);
-        o2 = fmaf(qq, s[m].z, o2); o3 = fmaf(qq, s[m].w, o3);
-        __builtin_nontemporal_store(s[m], Sp + (int64_t)m * (8 * DV / 4));
-    }
+        for (int m = 0; m < ROWS; ++m) {
+            const float a = s_alpha[t][rg + 8 * m];
+            const float kk = s_k[t][rg + 8 * m];
+            s[m].x *= a; s[m].y *= a; s[m].z *= a; s[m].w *= a;
+            p0 = fmaf(kk, s[m].x, p0); p1 = fmaf(kk, s[m].y, p1);
+            p2 = fmaf(kk, s[m].z, p2); p3 = fmaf(kk, s[m].w, p3);
+        }
 #pragma unroll
-    for (int d = 8; d < 64; d <<= 1) {
-        o0 += __shfl_xor(o0, d); o1 += __shfl_xor(o1, d);
-        o2 += __shfl_xor(o2, d); o3 += __shfl_xor(o3, d);
-    }
-    if (rg == 0) {
-        f32x4 out = {o0 * scale, o1 * scale, o2 * scale, o3 * scale};
-        *reinterpret_cast<f32x4 *>(o + pair * DV + col) = out;
+        for (int d = 8; d < 64; d <<= 1) {
+            p0 += __shfl_xor(p0, d); p1 += __shfl_xor(p1, d);
+            p2 += __shfl_xor(p2, d); p3 += __shfl_xor(p3, d);
+        }
+        // w = beta * (v - S^T k): the delta-rule correction written along k.
+        const float w0 = b * (vv[0] - p0), w1 = b * (vv[1] - p1);
+        const float w2 = b * (vv[2] - p2), w3 = b * (vv[3] - p3);
+
+        float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+#pragma unroll
+        for (int m = 0; m < ROWS; ++m) {
+            const float kk = s_k[t][rg + 8 * m];
+            const float qq = s_q[t][rg + 8 * m];
+            s[m].x = fmaf(kk, w0, s[m].x); s[m].y = fmaf(kk, w1, s[m].y);
+            s[m].z = fmaf(kk, w2, s[m].z); s[m].w = fmaf(kk, w3, s[m].w);
+            o0 = fmaf(qq, s[m].x, o0); o1 = fmaf(qq, s[m].y, o1);
+            o2 = fmaf(qq, s[m].z, o2); o3 = fmaf(qq, s[m].w, o3);
+            if (last) __builtin_nontemporal_store(s[m], Sp + (int64_t)m * (8 * DV / 4));
+        }
+#pragma unroll
+        for (int d = 8; d < 64; d <<= 1) {
+            o0 += __shfl_xor(o0, d); o1 += __shfl_xor(o1, d);
+            o2 += __shfl_xor(o2, d); o3 += __shfl_xor(o3, d);
+        }
+        if (rg == 0) {
+            f32x4 out = {o0 * scale, o1 * scale, o2 * scale, o3 * scale};
+            *reinterpret_cast<f32x4 *>(o + row * DV + col) = out;
+        }
     }
 }
 
 template <typename Tin, int DK, int DV>
 static kda_status launch_step(const kda_dims *d, const void *q, const void *k, const void *v,
                               const void *log_alpha, const void *beta, float *S, void *o,
-                              hipStream_t stream)
+                              const int32_t *indices, hipStream_t stream)
 {
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
     if (pairs == 0) return KDA_OK;
@@ -107,23 +131,26 @@ static kda_status launch_step(const kda_dims *d, const void *q, const void *k, c
     hipLaunchKernelGGL((kda_step_kernel<Tin, DK, DV>), dim3((unsigned)pairs), dim3(DV * 2), 0, stream,
                        static_cast<const Tin *>(q), static_cast<const Tin *>(k),
                        static_cast<const Tin *>(v), static_cast<const Tin *>(log_alpha),
-                       static_cast<const Tin *>(beta), S, static_cast<float *>(o), d->scale);
+                       static_cast<const Tin *>(beta), S, static_cast<float *>(o), d->scale,
+                       (int)d->heads, (int)d->seqlen, indices);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_step_kernel: %s", hipGetErrorString(e));
     return KDA_OK;
 }
 
+int recurrent_max_steps() { return kMaxSteps; }
+
 kda_status recurrent_step_dispatch(const kda_dims *d, const void *q, const void *k, const void *v,
                                    const void *log_alpha, const void *beta, float *S, void *o,
-                                   hipStream_t stream)
+                                   const int32_t *indices, hipStream_t stream)
 {
     const bool bf = d->in_dtype == KDA_BF16;
     if (d->dk == 128 && d->dv == 128)
-        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, q, k, v, log_alpha, beta, S, o, stream)
-                  : launch_step<float, 128, 128>(d, q, k, v, log_alpha, beta, S, o, stream);
+        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, q, k, v, log_alpha, beta, S, o, indices, stream)
+                  : launch_step<float, 128, 128>(d, q, k, v, log_alpha, beta, S, o, indices, stream);
     if (d->dk == 64 && d->dv == 64)
-        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, q, k, v, log_alpha, beta, S, o, stream)
-                  : launch_step<float, 64, 64>(d, q, k, v, log_alpha, beta, S, o, stream);
+        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, q, k, v, log_alpha, beta, S, o, indices, stream)
+                  : launch_step<float, 64, 64>(d, q, k, v, log_alpha, beta, S, o, indices, stream);
     return fail(KDA_ERR_UNSUPPORTED, "recurrent step supports dk == dv in {64,128}, got %d x %d",
                 d->dk, d->dv);
 }

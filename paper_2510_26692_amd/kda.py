@@ -67,6 +67,8 @@ def load_library():
     lib.kda_debug_set_overlap.argtypes = [ctypes.c_int]
     lib.kda_recurrent_step.restype = ctypes.c_int
     lib.kda_recurrent_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.kda_recurrent_steps_pooled.restype = ctypes.c_int
+    lib.kda_recurrent_steps_pooled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -202,6 +204,37 @@ def kda_recurrent_step(q, k, v, log_alpha, beta, S, scale=1.0, o=None):
                    in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale), max_seqlen=0)
     st = lib.kda_recurrent_step(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha),
                                 _ptr(beta), _ptr(S), _ptr(o), _stream_ptr(dev))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return o
+
+
+def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=None, scale=1.0, o=None):
+    """Decode over a state pool.  q,k,log_alpha [N,Tq,H,dk]; v [N,Tq,H,dv]; beta [N,Tq,H];
+    S_pool fp32 [P,H,dk,dv], the addressed states updated in place; state_indices int32 [N] on the
+    device (negative = skip) or None for 0..N-1.  Returns o fp32 [N,Tq,H,dv]."""
+    lib = load_library()
+    dev = _check_dev(q, k, v, log_alpha, beta, S_pool, state_indices, o)
+    N, Tq, H, dk = q.shape
+    dv = v.shape[-1]
+    if S_pool.dtype != torch.float32 or S_pool.dim() != 4 or S_pool.shape[1:] != (H, dk, dv):
+        raise ValueError("S_pool must be fp32 [P,H,dk,dv]")
+    if q.dtype not in _DTYPE_CODE or not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype):
+        raise ValueError("q, k, v, log_alpha, beta must share a supported dtype")
+    if k.shape != q.shape or log_alpha.shape != q.shape or v.shape != (N, Tq, H, dv) or beta.shape != (N, Tq, H):
+        raise ValueError("inconsistent input shapes")
+    if state_indices is None:
+        if S_pool.shape[0] < N:
+            raise ValueError("S_pool holds fewer states than there are sequences")
+    elif state_indices.dtype != torch.int32 or state_indices.shape != (N,):
+        raise ValueError("state_indices must be int32 [N]")
+    if o is None:
+        o = torch.zeros(N, Tq, H, dv, dtype=torch.float32, device=dev)
+    dims = KdaDims(batch=N, seqlen=Tq, heads=H, dk=dk, dv=dv, chunk=64, num_seqs=N,
+                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale), max_seqlen=0)
+    st = lib.kda_recurrent_steps_pooled(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha),
+                                        _ptr(beta), _ptr(S_pool), _ptr(state_indices), _ptr(o),
+                                        _stream_ptr(dev))
     if st != 0:
         raise KdaError(st, kda_last_error())
     return o

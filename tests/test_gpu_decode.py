@@ -77,3 +77,59 @@ def test_decode_rejects_bad_arguments():
     with pytest.raises(kda.KdaError) as ei:
         kda.kda_recurrent_step(q96, q96, q96, q96, b, S96)
     assert ei.value.status == 2
+
+
+def _stack_tokens(N, H, d, dtype, Tq, seed):
+    toks = [si.make_decode_tokens(N, H, d, d, dtype, -2.0, seed, t) for t in range(Tq)]
+    return {k_: torch.stack([t_[k_] for t_ in toks], dim=1).contiguous() for k_ in toks[0]}
+
+
+@pytest.mark.parametrize("Tq", [1, 3, 8])
+@pytest.mark.parametrize("dtype,tol,d", [("f32", TOL_F32, 64), ("bf16", TOL_BF16, 128)])
+def test_pooled_multi_token_decode(Tq, dtype, tol, d):
+    """Sequences name states of a larger pool through a permuted index array with skipped entries;
+    each takes Tq tokens through its state in one call.  Checked against the oracle: o, the named
+    states, and that every other state of the pool is bit-for-bit untouched."""
+    import paper_2510_26692_amd as kda
+    N, H, P = 6, 4, 11
+    pool0 = si.make_state(P, H, d, d, 0.02, 31)
+    idx = torch.tensor([7, 2, -1, 10, 0, 5], dtype=torch.int32)
+    tok = _stack_tokens(N, H, d, dtype, Tq, 31)
+    g = {k_: v_.cuda() for k_, v_ in tok.items()}
+    pool = pool0.cuda().clone()
+    o_init = torch.full((N, Tq, H, d), 7.0, device="cuda")
+    o = kda.kda_recurrent_steps_pooled(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], pool, idx.cuda(),
+                                       scale=0.9, o=o_init)
+    torch.cuda.synchronize()
+    o_ref, pool_ref = oracle.kda_steps_pooled(si.to_np32(tok["q"]), si.to_np32(tok["k"]), si.to_np32(tok["v"]),
+                                              si.to_np32(tok["log_alpha"]), si.to_np32(tok["beta"]),
+                                              pool0.numpy().astype(np.float64), idx.numpy(), scale=0.9)
+    o_np, pool_np = o.cpu().numpy(), pool.cpu().numpy()
+    act = [n for n in range(N) if idx[n] >= 0]
+    eo = max(rel_err(o_np[n, :, h], o_ref[n, :, h]) for n in act for h in range(H))
+    eS = max(rel_err(pool_np[int(idx[n]), h], pool_ref[int(idx[n]), h]) for n in act for h in range(H))
+    print("pooled decode Tq=%d %s: err_o %.2e err_S %.2e" % (Tq, dtype, eo, eS))
+    assert eo <= tol and eS <= tol
+    assert (o_np[2] == 7.0).all()                                   # skipped sequence: o untouched
+    unused = [p_ for p_ in range(P) if p_ not in idx.tolist()]
+    assert torch.equal(pool.cpu()[unused], pool0[unused])            # states nobody named
+
+
+def test_pooled_decode_without_indices_equals_the_plain_step_and_rejects_bad_sizes():
+    import paper_2510_26692_amd as kda
+    N, H, d = 3, 2, 128
+    S0 = si.make_state(N, H, d, d, 0.02, 41)
+    tok = si.make_decode_tokens(N, H, d, d, "bf16", -2.0, 41, 0)
+    g = {k_: v_.cuda() for k_, v_ in tok.items()}
+    S1, S2 = S0.cuda().clone(), S0.cuda().clone()
+    o1 = kda.kda_recurrent_step(g["q"], g["k"], g["v"], g["log_alpha"], g["beta"], S1)
+    o2 = kda.kda_recurrent_steps_pooled(g["q"][:, None].contiguous(), g["k"][:, None].contiguous(),
+                                        g["v"][:, None].contiguous(), g["log_alpha"][:, None].contiguous(),
+                                        g["beta"][:, None].contiguous(), S2)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2[:, 0]) and torch.equal(S1, S2)
+    big = _stack_tokens(N, H, d, "bf16", 9, 41)
+    gb = {k_: v_.cuda() for k_, v_ in big.items()}
+    with pytest.raises(kda.KdaError) as ei:
+        kda.kda_recurrent_steps_pooled(gb["q"], gb["k"], gb["v"], gb["log_alpha"], gb["beta"], S2)
+    assert ei.value.status == 1

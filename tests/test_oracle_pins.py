@@ -298,3 +298,35 @@ def test_planted_mistakes_are_caught():
 
     for variant in ("decay_after", "decayed_write", "old_state_output"):
         assert np.max(np.abs(run(variant) - o[0, :, 0])) > 1e-3
+
+
+def test_pooled_multi_token_decode_is_successive_single_steps_on_the_named_states():
+    """Section 6.3: a multi-token decode over a state pool is Eq. (1) applied token by token to
+    the state each sequence names; states nobody names stay as they were, skipped sequences
+    produce no output."""
+    rng = np.random.default_rng(5)
+    N, Tq, H, dk, dv, P = 4, 3, 2, 8, 6, 7
+    q = rng.standard_normal((N, Tq, H, dk)); k = rng.standard_normal((N, Tq, H, dk))
+    k /= np.linalg.norm(k, axis=-1, keepdims=True)
+    v = rng.standard_normal((N, Tq, H, dv))
+    g = -np.log1p(np.exp(rng.standard_normal((N, Tq, H, dk))))
+    b = 1.0 / (1.0 + np.exp(-rng.standard_normal((N, Tq, H))))
+    pool = rng.standard_normal((P, H, dk, dv))
+    idx = np.array([5, -1, 0, 3])
+    f = lambda x: x.astype(np.float32)
+    o, new = oracle.kda_steps_pooled(f(q), f(k), f(v), f(g), f(b), pool, idx, scale=0.5)
+    # by hand: explicit transition matrices of Eq. (1), token by token
+    for n in range(N):
+        if idx[n] < 0:
+            assert np.isnan(o[n]).all()
+            continue
+        for h in range(H):
+            S = pool[idx[n], h].copy()
+            for t in range(Tq):
+                kk = f(k)[n, t, h].astype(np.float64); a = np.exp(f(g)[n, t, h].astype(np.float64))
+                bb = float(f(b)[n, t, h])
+                S = (np.eye(dk) - bb * np.outer(kk, kk)) @ (a[:, None] * S) + bb * np.outer(kk, f(v)[n, t, h].astype(np.float64))
+                np.testing.assert_allclose(o[n, t, h], 0.5 * S.T @ f(q)[n, t, h].astype(np.float64), rtol=1e-11, atol=1e-12)
+            np.testing.assert_allclose(new[idx[n], h], S, rtol=1e-11, atol=1e-12)
+    untouched = [p_ for p_ in range(P) if p_ not in idx]
+    assert np.array_equal(new[untouched], pool[untouched])
