@@ -193,6 +193,11 @@ void kda_debug_set_phase_mask(int mask);
  * Diagnostics: 0 makes the matrix-core prefill run its two kernels strictly one
  * after the other on `hip_stream`; 1 (default) lets them overlap when there are
  * few enough (sequence, head) pairs.  Results are identical either way.
+ * KDA_PREFILL_OVERLAP=0 in the environment sets the default to 0.  Use 0 under
+ * tools that run kernels strictly one at a time (hardware-counter collection):
+ * there the sequential kernel would wait for slots that cannot be produced
+ * until it has given up (bounded, about two seconds; see kda_chunk_fwd_check).
+ * Calls made while `hip_stream` is being captured into a graph never overlap.
  * Process-wide, not thread-safe.
  */
 void kda_debug_set_overlap(int enabled);

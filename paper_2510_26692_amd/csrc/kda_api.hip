@@ -37,8 +37,14 @@ size_t chunk_mfma_status_offset(const kda_dims *, size_t workspace_bytes);
 
 // Diagnostics: which kernels of the matrix-core prefill run (bit 0 kda_intra, bit 1 kda_scan).
 int g_phase_mask = 3;
-// Diagnostics: 0 keeps kda_intra and kda_scan strictly one after the other.
-int g_overlap = 1;
+// 0 keeps kda_intra and kda_scan strictly one after the other (kda_debug_set_overlap, or
+// KDA_PREFILL_OVERLAP=0 in the environment when the library is loaded).
+static int overlap_default()
+{
+    const char *e = getenv("KDA_PREFILL_OVERLAP");
+    return (e && e[0] == '0' && e[1] == 0) ? 0 : 1;
+}
+int g_overlap = overlap_default();
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

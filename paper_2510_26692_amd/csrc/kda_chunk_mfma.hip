@@ -967,6 +967,29 @@ static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full)
     return plan_with(d, sc);
 }
 
+// Raises the dynamic-LDS limit of the four prefill kernels, once per device.
+static bool reserve_lds()
+{
+    constexpr int kMaxDevices = 64;
+    static bool done[kMaxDevices];                          // same outcome from every thread
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+    if (done[dev]) return true;
+    const int scan_lds = scan::kLds;
+    const bool ok =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
+    done[dev] = ok;
+    return ok;
+}
+
 // Helper stream and events of the overlapped mode, created on first use, one set per device
 // and host thread, never destroyed.
 struct SideStream {
@@ -1038,21 +1061,9 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
         return fail(KDA_ERR_UNSUPPORTED, "more than 65535 sequences in one call: %d", d->num_seqs);
 
     const size_t scan_lds = (size_t)scan::kLds;
-    {
-        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<false>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
-        if (e1 == hipSuccess)
-            e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds);
-        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
-        if (e2 == hipSuccess)
-            e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds);
-        if (e1 != hipSuccess || e2 != hipSuccess)
-            return fail(KDA_ERR_LAUNCH, "cannot reserve LDS for the prefill kernels (%d, %d bytes)", kIntraLds,
-                        (int)scan_lds);
-    }
+    if (!reserve_lds())
+        return fail(KDA_ERR_LAUNCH, "cannot reserve LDS for the prefill kernels (%d, %d bytes)", kIntraLds,
+                    (int)scan_lds);
 
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     float *carry = hT ? hT : reinterpret_cast<float *>(ws + plan.carry_offset);
@@ -1069,8 +1080,12 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
     // consumes each slot as soon as its flag is up.  kda_scan keeps one compute unit per
     // (sequence, head) busy, so this needs enough units left over for kda_intra to make progress
     // (it never waits for anything, which is what rules out a deadlock).
+    // Not while the caller's stream is being captured into a graph: a captured kda_scan could be
+    // replayed by a runtime that does not start the other branch at the same time.
     SideStream *side = nullptr;
-    if (g_phase_mask == 3 && g_overlap) {
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) != hipSuccess) { capture = hipStreamCaptureStatusNone; (void)hipGetLastError(); }
+    if (g_phase_mask == 3 && g_overlap && capture == hipStreamCaptureStatusNone) {
         side = side_stream();
         if (side && (int64_t)streams * 4 > (int64_t)side->compute_units * 3) side = nullptr;
     }

@@ -137,3 +137,31 @@ def test_bf16_overlapped_kernels_match_the_serial_order():
             assert torch.equal(o1, o2) and torch.equal(h1, h2), seed
     finally:
         kda.kda_debug_set_overlap(1)
+
+
+def test_bf16_prefill_inside_a_captured_graph_replays_correctly():
+    """A caller may capture kda_chunk_fwd into a graph.  The call then keeps its two kernels on
+    the captured stream, one after the other (no helper stream, no waiting on flags).  Every
+    replay, with eager work in between, must reproduce the eager result bit for bit."""
+    import paper_2510_26692_amd as kda
+    x = si.make_prefill(2, 700, 4, 128, 128, "bf16", -2.0, 51, 0.02)
+    dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+    dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
+    ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
+    o = torch.empty(2, 700, 4, 128, device="cuda")
+    hT = torch.empty(2, 4, 128, 128, device="cuda")
+    o_ref, h_ref = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], check=True)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], o=o, hT=hT,
+                          workspace=ws)
+    for rep in range(3):
+        o.fill_(float("nan")); hT.fill_(float("nan")); ws.fill_(rep)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, o_ref) and torch.equal(hT, h_ref), rep
+        # eager work between the replays
+        o2, _ = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"])
+        assert torch.equal(o2, o_ref)
