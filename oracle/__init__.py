@@ -6,6 +6,16 @@ this package.  It never imports the HIP package and shares no code with it.
 `kda_forward` / `kda_step` / `kda_steps_pooled` call the plain C recurrence in ``kda_oracle.c``
 (paper Section 3, Eq. (1)); `chunkwise_ref.kda_chunkwise` is a second, numpy
 fp64 statement of the same function written from the chunkwise equations of
-Section 3.1, used to pin the recurrence (chunk-size invariance).
+Section 3.1, used to pin the recurrence (chunk-size invariance).  `prologue` states the
+input parameterisation of Section 4 (L2Norm, Sigmoid, the decay function) in float64.
 """
+from . import prologue  # noqa: F401
 from .recurrence import build, kda_forward, kda_step, kda_steps_pooled, num_threads  # noqa: F401
+
+
+def kda_forward_raw(q_raw, k_raw, v, gate, beta_logit, eps=1e-6, a_scale=None, dt_bias=None, **kw):
+    """The recurrence behind the input parameterisation of Section 4: prologue.apply in float64,
+    then kda_forward (which takes its inputs as float32: the one rounding, 6e-8 relative, that
+    this adds is far below every tolerance it is compared under)."""
+    q, k, log_alpha, beta = prologue.apply(q_raw, k_raw, gate, beta_logit, eps, a_scale, dt_bias)
+    return kda_forward(q, k, v, log_alpha, beta, **kw)

@@ -330,3 +330,47 @@ def test_pooled_multi_token_decode_is_successive_single_steps_on_the_named_state
             np.testing.assert_allclose(new[idx[n], h], S, rtol=1e-11, atol=1e-12)
     untouched = [p_ for p_ in range(P) if p_ not in idx]
     assert np.array_equal(new[untouched], pool[untouched])
+
+
+def test_prologue_closed_forms():
+    """Input parameterisation (Section 4): each piece against a formula written differently."""
+    from oracle import prologue as pro
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((3, 5, 2, 16)) * 3
+    y = pro.l2norm(x, 0.0)
+    np.testing.assert_allclose(np.linalg.norm(y, axis=-1), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(pro.l2norm(7.5 * x, 0.0), y, rtol=1e-13)           # scale invariant
+    np.testing.assert_allclose(pro.l2norm(x, 0.25), x / np.sqrt((x ** 2).sum(-1, keepdims=True) + 0.25), rtol=1e-14)
+    z = rng.standard_normal(1000) * 6
+    assert pro.sigmoid(0.0) == 0.5
+    np.testing.assert_allclose(pro.sigmoid(z) + pro.sigmoid(-z), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(pro.sigmoid(z), np.exp(z) / (1 + np.exp(z)), rtol=1e-12)
+    np.testing.assert_allclose(pro.softplus(z) - pro.softplus(-z), z, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(pro.softplus(0.0), np.log(2.0), rtol=1e-15)
+    np.testing.assert_allclose(pro.softplus(50.0), 50.0, rtol=1e-15)
+    np.testing.assert_allclose(pro.softplus(-40.0), np.exp(-40.0), rtol=1e-12)
+    # alpha = sigmoid(-(gate + bias)) ** a_scale, per head and channel
+    gate = rng.standard_normal((2, 7, 3, 16)) * 2
+    a = np.array([0.5, 1.0, 3.0]); bias = rng.standard_normal((3, 16))
+    la = pro.log_alpha_from_gate(gate, a, bias)
+    np.testing.assert_allclose(np.exp(la), pro.sigmoid(-(gate + bias)) ** a[:, None], rtol=1e-12)
+    assert (la < 0).all()
+    # the baseline workloads draw log alpha = -softplus(logit): a_scale = 1, bias = 0
+    np.testing.assert_allclose(pro.log_alpha_from_gate(gate), -np.log1p(np.exp(gate)), rtol=1e-12)
+
+
+def test_forward_raw_composes_prologue_and_recurrence():
+    rng = np.random.default_rng(10)
+    B, T, H, dk, dv = 1, 9, 2, 8, 4
+    qr, kr = rng.standard_normal((2, B, T, H, dk)) * 2
+    v = rng.standard_normal((B, T, H, dv)); gate = rng.standard_normal((B, T, H, dk)); bl = rng.standard_normal((B, T, H))
+    o, hT = oracle.kda_forward_raw(qr, kr, v, gate, bl, eps=0.0)
+    # by hand, with explicit transition matrices of Eq. (1)
+    for h in range(H):
+        S = np.zeros((dk, dv))
+        for t in range(T):
+            kk = kr[0, t, h] / np.linalg.norm(kr[0, t, h]); qq = qr[0, t, h] / np.linalg.norm(qr[0, t, h])
+            al = 1.0 / (1.0 + np.exp(gate[0, t, h])); be = 1.0 / (1.0 + np.exp(-bl[0, t, h]))
+            S = (np.eye(dk) - be * np.outer(kk, kk)) @ (al[:, None] * S) + be * np.outer(kk, v[0, t, h])
+            np.testing.assert_allclose(o[0, t, h], S.T @ qq, rtol=2e-6, atol=2e-7)
+        np.testing.assert_allclose(hT[0, h], S, rtol=2e-6, atol=2e-7)
