@@ -120,6 +120,36 @@ kda_status kda_chunk_fwd(const kda_dims *dims,
                          void *hip_stream);
 
 /*
+ * Fused input prologue (Section 4, "Neural Parameterization").  With a kda_prologue the kernels
+ * take the raw projections and apply, in fp32 and before anything else,
+ *     q <- q / sqrt(sum_c q_c^2 + l2norm_eps),   k likewise            (L2Norm over dk)
+ *     beta <- 1 / (1 + exp(-beta))                                       (Sigmoid)
+ *     log_alpha[c] <- -a_scale[h] * log(1 + exp(gate[c] + dt_bias[h][c]))
+ * The paper does not print its decay function f; this is the softplus form of the two models
+ * it names as its pattern, with the constants exposed (a_scale = NULL means 1, dt_bias = NULL
+ * means 0, which gives log_alpha = -softplus(gate)).  The short convolution, Swish and the
+ * projections themselves stay with the caller.
+ */
+typedef struct {
+    float        l2norm_eps;   /* >= 0                                            */
+    const float *a_scale;      /* [H]     fp32, device memory, or NULL            */
+    const float *dt_bias;      /* [H,dk]  fp32, device memory, or NULL            */
+} kda_prologue;
+
+/*
+ * kda_chunk_fwd on raw projections: q, k, beta and the gate logits (in the place of log_alpha)
+ * go through `prologue` inside the per-chunk kernel; everything else is as for kda_chunk_fwd.
+ * Built for KDA_BF16 inputs with dk == dv == 128.
+ */
+kda_status kda_chunk_fwd_fused(const kda_dims *dims, const kda_prologue *prologue,
+                               const void *q_raw, const void *k_raw, const void *v,
+                               const void *gate, const void *beta_logit,
+                               const float *h0, const int32_t *cu_seqlens,
+                               void *o, float *hT,
+                               void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
+/*
  * Optional check after a bf16 kda_chunk_fwd: waits for `hip_stream` and reads
  * the status word that the call left in `workspace` (same dims, workspace and
  * size as that call).  The sequential kernel of the prefill may run next to
@@ -173,6 +203,16 @@ kda_status kda_recurrent_steps_pooled(const kda_dims *dims,
                                       const void *log_alpha, const void *beta,
                                       float *S_pool, const int32_t *state_indices,
                                       void *o, void *hip_stream);
+
+/*
+ * kda_recurrent_steps_pooled on raw projections (see kda_prologue); q_raw, k_raw, gate
+ * [N,Tq,H,dk], beta_logit [N,Tq,H].
+ */
+kda_status kda_recurrent_steps_fused(const kda_dims *dims, const kda_prologue *prologue,
+                                     const void *q_raw, const void *k_raw, const void *v,
+                                     const void *gate, const void *beta_logit,
+                                     float *S_pool, const int32_t *state_indices,
+                                     void *o, void *hip_stream);
 
 /* Static description of a status code (never NULL). */
 const char *kda_status_string(kda_status status);

@@ -121,13 +121,30 @@ template <int kPolicy> __device__ __forceinline__ u32x4 slot_load16(__amdgpu_buf
 // so the decay-scaled operands of the A-matrix products are built in registers.
 // kHandoff: the slot is handed to a kda_scan that runs at the same time (write-through stores and a
 // ready flag); otherwise the stores are ordinary ones and the kernel boundary publishes them.
-template <bool kHandoff>
+// kRaw: q, k, log_alpha and beta arrive as the raw projections of Section 4 ("Neural
+// Parameterization") and the kernel applies L2Norm to q and k, Sigmoid to beta and the decay
+// function log alpha = -a_scale[h] softplus(gate + dt_bias[h][c]) itself, in fp32.
+struct RawParams {
+    const float *a_scale;    // [H] or NULL (= 1)
+    const float *dt_bias;    // [H][128] or NULL (= 0)
+    float eps;               // L2Norm: x / sqrt(sum x^2 + eps)
+};
+
+// log2(alpha) of one channel from its gate logit x (bias already added): -a * log2(1 + e^x)
+__device__ __forceinline__ float log2_alpha_from_gate(float x, float a)
+{
+    const float t = x * kLog2e;
+    const float sp = (t > 30.f) ? t : __log2f(1.f + fast_exp2(t));
+    return -a * sp;
+}
+
+template <bool kHandoff, bool kRaw>
 __global__ __launch_bounds__(256, 2)
 void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
                       const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
                       const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
                       uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
-                      int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch)
+                      int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch, RawParams raw)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -171,18 +188,54 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qraw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(q + off + 32 * ks) : z;
     }
-    if (tid < kChunk)
-        sBeta[tid] = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
+    if (tid < kChunk) {
+        float b = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
+        if (kRaw) b = (tid < nv) ? __builtin_amdgcn_rcpf(1.f + fast_exp2(-b * kLog2e)) : 0.f;   // Sigmoid
+        sBeta[tid] = b;
+    }
+    // kRaw: 1 / |q|, 1 / |k| of this lane's token (the four lanes g = 0..3 of a token hold 32 channels each)
+    float invq = 1.f, invk = 1.f;
+    if (kRaw) {
+        float sq = 0.f, sk = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float a, b;
+                unpack_bf16x2(kraw[ks][w], a, b); sk = fmaf(a, a, fmaf(b, b, sk));
+                unpack_bf16x2(qraw[ks][w], a, b); sq = fmaf(a, a, fmaf(b, b, sq));
+            }
+        sq += __shfl_xor(sq, 16); sk += __shfl_xor(sk, 16);
+        sq += __shfl_xor(sq, 32); sk += __shfl_xor(sk, 32);
+        invq = (tok < nv) ? __builtin_amdgcn_rsqf(sq + raw.eps) : 0.f;
+        invk = (tok < nv) ? __builtin_amdgcn_rsqf(sk + raw.eps) : 0.f;
+    }
 
     // ---- G: running sum of log2(alpha) over the 16 tokens of the sub-chunk (lanes of a row) ----
     float G[32];
+    f32x4 bias[8];                                           // kRaw: dt_bias of this lane's 32 channels
+    float a_scale = 1.f;
+    if (kRaw) {
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            bias[i] = raw.dt_bias ? *reinterpret_cast<const f32x4 *>(raw.dt_bias + h * D + 32 * (i >> 1) + 8 * g + 4 * (i & 1)) : z;
+        if (raw.a_scale) a_scale = raw.a_scale[h];
+    }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             float a, b;
             unpack_bf16x2(graw[ks][w], a, b);
-            a *= kLog2e; b *= kLog2e;
+            if (kRaw) {
+                // padding tokens must stay identity transitions: log alpha = 0
+                const float b0 = bias[2 * ks + (w >> 1)][2 * (w & 1)], b1 = bias[2 * ks + (w >> 1)][2 * (w & 1) + 1];
+                a = (tok < nv) ? log2_alpha_from_gate(a + b0, a_scale) : 0.f;
+                b = (tok < nv) ? log2_alpha_from_gate(b + b1, a_scale) : 0.f;
+            } else {
+                a *= kLog2e; b *= kLog2e;
+            }
             a += row_shr<1>(a); b += row_shr<1>(b);
             a += row_shr<2>(a); b += row_shr<2>(b);
             a += row_shr<4>(a); b += row_shr<4>(b);
@@ -250,6 +303,10 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         for (int w = 0; w < 4; ++w) {
             unpack_bf16x2(kraw[ks][w], kf[2 * w], kf[2 * w + 1]);
             unpack_bf16x2(qraw[ks][w], qf[2 * w], qf[2 * w + 1]);
+        }
+        if (kRaw) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { kf[e] *= invk; qf[e] *= invq; }
         }
         const int cb = R * 128 + 32 * ks + 8 * g;
         float tot[8], P[8], E[8], Ti[8], iA[8], iB[8];
@@ -356,8 +413,8 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 for (int e = 0; e < 8; ++e) {
                     if ((strong_all >> (ks * 8 + e)) & 1u) {
                         const uint32_t kw = kraw[ks][e >> 1], qw = qraw[ks][e >> 1];
-                        const float kfe = (e & 1) ? __uint_as_float(kw & 0xffff0000u) : __uint_as_float(kw << 16);
-                        const float qfe = (e & 1) ? __uint_as_float(qw & 0xffff0000u) : __uint_as_float(qw << 16);
+                        const float kfe = invk * ((e & 1) ? __uint_as_float(kw & 0xffff0000u) : __uint_as_float(kw << 16));
+                        const float qfe = invq * ((e & 1) ? __uint_as_float(qw & 0xffff0000u) : __uint_as_float(qw << 16));
                         __builtin_amdgcn_wave_barrier();
                         fix[(g * 16 + m) * 3 + 0] = G[ks * 8 + e];
                         fix[(g * 16 + m) * 3 + 1] = kfe;
@@ -967,7 +1024,7 @@ static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full)
     return plan_with(d, sc);
 }
 
-// Raises the dynamic-LDS limit of the four prefill kernels, once per device.
+// Raises the dynamic-LDS limit of the prefill kernels, once per device.
 static bool reserve_lds()
 {
     constexpr int kMaxDevices = 64;
@@ -977,9 +1034,13 @@ static bool reserve_lds()
     if (done[dev]) return true;
     const int scan_lds = scan::kLds;
     const bool ok =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<false>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<false, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<false, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
@@ -1037,12 +1098,14 @@ size_t chunk_mfma_status_offset(const kda_dims *d, size_t workspace_bytes)
     return mfma::make_plan(d, workspace_bytes, false).status_offset;
 }
 
-kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, const void *v,
-                               const void *log_alpha, const void *beta, const float *h0,
+kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const void *q, const void *k,
+                               const void *v, const void *log_alpha, const void *beta, const float *h0,
                                const int32_t *cu, void *o, float *hT, void *workspace,
                                size_t workspace_bytes, hipStream_t stream)
 {
     using namespace mfma;
+    RawParams raw = {nullptr, nullptr, 0.f};
+    if (pro) { raw.a_scale = pro->a_scale; raw.dt_bias = pro->dt_bias; raw.eps = pro->l2norm_eps; }
     if (d->seqlen == 0) {
         // nothing to scan: the final state is the initial one
         if (hT && hT != h0) {
@@ -1108,17 +1171,19 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const void *q, const void *k, 
             hipLaunchKernelGGL(kda_scan_kernel<true>, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                flags, epoch, status);
-            hipLaunchKernelGGL(kda_intra_kernel<true>, intra_grid_overlap, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16,
-                               b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
-                               flags, epoch);
+            auto intra = pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>;
+            hipLaunchKernelGGL(intra, intra_grid_overlap,
+                               dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
+                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
         } else {
+            auto intra = pro ? kda_intra_kernel<false, true> : kda_intra_kernel<false, false>;
             if (g_phase_mask & 1)
-                hipLaunchKernelGGL(kda_intra_kernel<false>, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16,
-                                   b16, cu, ws, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
-                                   (uint32_t *)nullptr, 0u);
+                hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
+                                   (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
+                                   (uint32_t *)nullptr, 0u, raw);
             if (g_phase_mask & 2)
                 hipLaunchKernelGGL(kda_scan_kernel<false>, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                    static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,

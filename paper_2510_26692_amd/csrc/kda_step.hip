@@ -23,13 +23,16 @@ namespace kda {
 //          a negative entry skips the sequence).
 constexpr int kMaxSteps = 8;
 
-template <typename Tin, int DK, int DV>
+// kRaw:    q, k, log_alpha, beta are the raw projections of Section 4; the kernel applies L2Norm,
+//          Sigmoid and log alpha = -a_scale[h] softplus(gate + dt_bias[h][c]) while it stages them.
+template <typename Tin, int DK, int DV, bool kRaw>
 __global__ __launch_bounds__(DV * 2)
 void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                      const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
                      const Tin *__restrict__ beta, float *__restrict__ S,
                      float *__restrict__ o, float scale, int H, int steps,
-                     const int32_t *__restrict__ indices)
+                     const int32_t *__restrict__ indices, const float *__restrict__ a_scale,
+                     const float *__restrict__ dt_bias, float l2_eps)
 {
     constexpr int ROWS = DK / 8;             // state rows per lane
     __shared__ float s_alpha[kMaxSteps][DK], s_k[kMaxSteps][DK], s_q[kMaxSteps][DK];
@@ -54,12 +57,39 @@ void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     const int64_t row0 = n * steps * H + h;
 
     // Token vectors: decay, key and query are needed per row by every lane.
-    for (int i = tid; i < steps * DK; i += DV * 2) {
-        const int t = i / DK, c = i - t * DK;
-        const int64_t off = (row0 + (int64_t)t * H) * DK + c;
-        s_alpha[t][c] = fast_exp2(load_as_float(log_alpha + off) * kLog2e);
-        s_k[t][c] = load_as_float(k + off);
-        s_q[t][c] = load_as_float(q + off);
+    if (!kRaw) {
+        for (int i = tid; i < steps * DK; i += DV * 2) {
+            const int t = i / DK, c = i - t * DK;
+            const int64_t off = (row0 + (int64_t)t * H) * DK + c;
+            s_alpha[t][c] = fast_exp2(load_as_float(log_alpha + off) * kLog2e);
+            s_k[t][c] = load_as_float(k + off);
+            s_q[t][c] = load_as_float(q + off);
+        }
+    } else {
+        // one wave per token: a lane holds channels lane, lane + 64, ...; the norms are wave sums
+        const float as = a_scale ? a_scale[h] : 1.f;
+        for (int t = wave; t < steps; t += DV / 32) {
+            const int64_t off = (row0 + (int64_t)t * H) * DK;
+            float qv[DK / 64], kv[DK / 64], sq = 0.f, sk = 0.f;
+#pragma unroll
+            for (int j = 0; j < DK / 64; ++j) {
+                const int c = lane + 64 * j;
+                qv[j] = load_as_float(q + off + c); kv[j] = load_as_float(k + off + c);
+                sq = fmaf(qv[j], qv[j], sq); sk = fmaf(kv[j], kv[j], sk);
+                const float x = load_as_float(log_alpha + off + c) + (dt_bias ? dt_bias[h * DK + c] : 0.f);
+                const float tt = x * kLog2e;
+                const float sp = (tt > 30.f) ? tt : __log2f(1.f + fast_exp2(tt));   // log2(1 + e^x)
+                s_alpha[t][c] = fast_exp2(-as * sp);
+            }
+#pragma unroll
+            for (int dd = 1; dd < 64; dd <<= 1) { sq += __shfl_xor(sq, dd); sk += __shfl_xor(sk, dd); }
+            const float iq = __builtin_amdgcn_rsqf(sq + l2_eps), ik = __builtin_amdgcn_rsqf(sk + l2_eps);
+#pragma unroll
+            for (int j = 0; j < DK / 64; ++j) {
+                s_q[t][lane + 64 * j] = qv[j] * iq;
+                s_k[t][lane + 64 * j] = kv[j] * ik;
+            }
+        }
     }
 
     // Stream the slice in: ROWS independent 16-byte loads per lane.
@@ -75,7 +105,8 @@ void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
         float vv[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) vv[c] = load_as_float(v + row * DV + col + c);
-        const float b = load_as_float(beta + row);
+        float b = load_as_float(beta + row);
+        if (kRaw) b = __builtin_amdgcn_rcpf(1.f + fast_exp2(-b * kLog2e));          // Sigmoid
         const bool last = t + 1 == steps;
 
         // Decay, then the memory's prediction S^T k for this lane's columns.
@@ -121,18 +152,20 @@ void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
 }
 
 template <typename Tin, int DK, int DV>
-static kda_status launch_step(const kda_dims *d, const void *q, const void *k, const void *v,
-                              const void *log_alpha, const void *beta, float *S, void *o,
+static kda_status launch_step(const kda_dims *d, const kda_prologue *pro, const void *q, const void *k,
+                              const void *v, const void *log_alpha, const void *beta, float *S, void *o,
                               const int32_t *indices, hipStream_t stream)
 {
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
     if (pairs == 0) return KDA_OK;
     if (pairs > 0x7fffffffLL) return fail(KDA_ERR_INVALID_ARG, "num_seqs*heads exceeds 2^31-1");
-    hipLaunchKernelGGL((kda_step_kernel<Tin, DK, DV>), dim3((unsigned)pairs), dim3(DV * 2), 0, stream,
+    auto step = pro ? kda_step_kernel<Tin, DK, DV, true> : kda_step_kernel<Tin, DK, DV, false>;
+    hipLaunchKernelGGL(step, dim3((unsigned)pairs), dim3(DV * 2), 0, stream,
                        static_cast<const Tin *>(q), static_cast<const Tin *>(k),
                        static_cast<const Tin *>(v), static_cast<const Tin *>(log_alpha),
                        static_cast<const Tin *>(beta), S, static_cast<float *>(o), d->scale,
-                       (int)d->heads, (int)d->seqlen, indices);
+                       (int)d->heads, (int)d->seqlen, indices, pro ? pro->a_scale : nullptr,
+                       pro ? pro->dt_bias : nullptr, pro ? pro->l2norm_eps : 0.f);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_step_kernel: %s", hipGetErrorString(e));
     return KDA_OK;
@@ -140,17 +173,17 @@ static kda_status launch_step(const kda_dims *d, const void *q, const void *k, c
 
 int recurrent_max_steps() { return kMaxSteps; }
 
-kda_status recurrent_step_dispatch(const kda_dims *d, const void *q, const void *k, const void *v,
-                                   const void *log_alpha, const void *beta, float *S, void *o,
+kda_status recurrent_step_dispatch(const kda_dims *d, const kda_prologue *pro, const void *q, const void *k,
+                                   const void *v, const void *log_alpha, const void *beta, float *S, void *o,
                                    const int32_t *indices, hipStream_t stream)
 {
     const bool bf = d->in_dtype == KDA_BF16;
     if (d->dk == 128 && d->dv == 128)
-        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, q, k, v, log_alpha, beta, S, o, indices, stream)
-                  : launch_step<float, 128, 128>(d, q, k, v, log_alpha, beta, S, o, indices, stream);
+        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, pro, q, k, v, log_alpha, beta, S, o, indices, stream)
+                  : launch_step<float, 128, 128>(d, pro, q, k, v, log_alpha, beta, S, o, indices, stream);
     if (d->dk == 64 && d->dv == 64)
-        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, q, k, v, log_alpha, beta, S, o, indices, stream)
-                  : launch_step<float, 64, 64>(d, q, k, v, log_alpha, beta, S, o, indices, stream);
+        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, pro, q, k, v, log_alpha, beta, S, o, indices, stream)
+                  : launch_step<float, 64, 64>(d, pro, q, k, v, log_alpha, beta, S, o, indices, stream);
     return fail(KDA_ERR_UNSUPPORTED, "recurrent step supports dk == dv in {64,128}, got %d x %d",
                 d->dk, d->dv);
 }

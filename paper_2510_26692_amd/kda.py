@@ -34,6 +34,11 @@ class KdaDims(ctypes.Structure):
                 ("scale", ctypes.c_float), ("max_seqlen", ctypes.c_int64)]
 
 
+class KdaPrologue(ctypes.Structure):
+    """Mirror of ``kda_prologue``."""
+    _fields_ = [("l2norm_eps", ctypes.c_float), ("a_scale", ctypes.c_void_p), ("dt_bias", ctypes.c_void_p)]
+
+
 def library_path():
     return _LIB_PATH
 
@@ -69,6 +74,11 @@ def load_library():
     lib.kda_recurrent_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kda_recurrent_steps_pooled.restype = ctypes.c_int
     lib.kda_recurrent_steps_pooled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    pp = ctypes.POINTER(KdaPrologue)
+    lib.kda_chunk_fwd_fused.restype = ctypes.c_int
+    lib.kda_chunk_fwd_fused.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kda_recurrent_steps_fused.restype = ctypes.c_int
+    lib.kda_recurrent_steps_fused.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -145,8 +155,28 @@ def kda_chunk_fwd_check(dims, workspace):
         raise KdaError(st, kda_last_error())
 
 
+def _make_prologue(H, dk, l2norm_eps, a_scale, dt_bias):
+    for t, shape, name in ((a_scale, (H,), "a_scale"), (dt_bias, (H, dk), "dt_bias")):
+        if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_cuda
+                              or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous fp32 device tensor of shape %r" % (name, shape))
+    return KdaPrologue(l2norm_eps=float(l2norm_eps),
+                       a_scale=None if a_scale is None else a_scale.data_ptr(),
+                       dt_bias=None if dt_bias is None else dt_bias.data_ptr())
+
+
+def kda_chunk_fwd_fused(q_raw, k_raw, v, gate, beta_logit, l2norm_eps=1e-6, a_scale=None, dt_bias=None,
+                        **kw):
+    """kda_chunk_fwd on raw projections: L2Norm of q and k, Sigmoid of beta and the decay function
+    log_alpha = -a_scale[h] softplus(gate + dt_bias[h]) run inside the kernel (see kda_prologue in
+    kda.h).  a_scale fp32 [H] and dt_bias fp32 [H,dk] on the device, or None.  Other arguments and
+    the result as for kda_chunk_fwd."""
+    pro = _make_prologue(q_raw.shape[2], q_raw.shape[3], l2norm_eps, a_scale, dt_bias)
+    return kda_chunk_fwd(q_raw, k_raw, v, gate, beta_logit, _prologue=pro, **kw)
+
+
 def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0, o=None,
-                  hT=None, want_hT=True, workspace=None, max_seqlen=0, check=False):
+                  hT=None, want_hT=True, workspace=None, max_seqlen=0, check=False, _prologue=None):
     """Chunkwise prefill.  q,k,log_alpha [B,T,H,dk]; v [B,T,H,dv]; beta [B,T,H];
     h0 [N,H,dk,dv] fp32 or None; cu_seqlens int32 [N+1] on device or None.
     Returns (o fp32 [B,T,H,dv], hT fp32 [N,H,dk,dv] or None).  `o`, `hT` and
@@ -177,9 +207,12 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
         need = kda_chunk_fwd_workspace_size(dims)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev) if need else None
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    st = lib.kda_chunk_fwd(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha),
-                           _ptr(beta), _ptr(h0), _ptr(cu_seqlens), _ptr(o), _ptr(hT),
-                           _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(dev))
+    tail = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(h0), _ptr(cu_seqlens), _ptr(o),
+            _ptr(hT), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(dev))
+    if _prologue is None:
+        st = lib.kda_chunk_fwd(ctypes.byref(dims), *tail)
+    else:
+        st = lib.kda_chunk_fwd_fused(ctypes.byref(dims), ctypes.byref(_prologue), *tail)
     if st != 0:
         raise KdaError(st, kda_last_error())
     if check:
@@ -209,7 +242,15 @@ def kda_recurrent_step(q, k, v, log_alpha, beta, S, scale=1.0, o=None):
     return o
 
 
-def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=None, scale=1.0, o=None):
+def kda_recurrent_steps_fused(q_raw, k_raw, v, gate, beta_logit, S_pool, state_indices=None, l2norm_eps=1e-6,
+                              a_scale=None, dt_bias=None, **kw):
+    """kda_recurrent_steps_pooled on raw projections (see kda_chunk_fwd_fused)."""
+    pro = _make_prologue(q_raw.shape[2], q_raw.shape[3], l2norm_eps, a_scale, dt_bias)
+    return kda_recurrent_steps_pooled(q_raw, k_raw, v, gate, beta_logit, S_pool, state_indices, _prologue=pro, **kw)
+
+
+def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=None, scale=1.0, o=None,
+                               _prologue=None):
     """Decode over a state pool.  q,k,log_alpha [N,Tq,H,dk]; v [N,Tq,H,dv]; beta [N,Tq,H];
     S_pool fp32 [P,H,dk,dv], the addressed states updated in place; state_indices int32 [N] on the
     device (negative = skip) or None for 0..N-1.  Returns o fp32 [N,Tq,H,dv]."""
@@ -232,9 +273,12 @@ def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=N
         o = torch.zeros(N, Tq, H, dv, dtype=torch.float32, device=dev)
     dims = KdaDims(batch=N, seqlen=Tq, heads=H, dk=dk, dv=dv, chunk=64, num_seqs=N,
                    in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale), max_seqlen=0)
-    st = lib.kda_recurrent_steps_pooled(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha),
-                                        _ptr(beta), _ptr(S_pool), _ptr(state_indices), _ptr(o),
-                                        _stream_ptr(dev))
+    tail = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S_pool), _ptr(state_indices), _ptr(o),
+            _stream_ptr(dev))
+    if _prologue is None:
+        st = lib.kda_recurrent_steps_pooled(ctypes.byref(dims), *tail)
+    else:
+        st = lib.kda_recurrent_steps_fused(ctypes.byref(dims), ctypes.byref(_prologue), *tail)
     if st != 0:
         raise KdaError(st, kda_last_error())
     return o

@@ -59,6 +59,25 @@ def make_tokens(B, T, H, dk, dv, dtype="bf16", mu=-2.0, seed=0, device="cpu"):
                 beta=beta.to(dt))
 
 
+def make_raw_tokens(B, T, H, dk, dv, dtype="bf16", mu=-2.0, seed=0, device="cpu"):
+    """Raw projections for the fused-prologue entry points, [B,T,H,*]: un-normalised q and k
+    (N(0, 2^2)), v, gate logits N(mu, 1), beta logits N(0, 1), plus the decay-function constants
+    a_scale [H] in [0.5, 2) and dt_bias [H,dk] ~ N(0, 0.5^2) in fp32.  No arithmetic of the method
+    is applied here."""
+    gen = _gen(seed + 104729, device)
+    dt = _TORCH_DTYPE[dtype]
+
+    def randn(*shape):
+        return torch.randn(*shape, generator=gen, device=device, dtype=torch.float32)
+
+    d = dict(q_raw=(2.0 * randn(B, T, H, dk)).to(dt), k_raw=(2.0 * randn(B, T, H, dk)).to(dt),
+             v=randn(B, T, H, dv).to(dt), gate=(randn(B, T, H, dk) + mu).to(dt),
+             beta_logit=randn(B, T, H).to(dt))
+    d["a_scale"] = 0.5 + 1.5 * torch.rand(H, generator=gen, device=device, dtype=torch.float32)
+    d["dt_bias"] = 0.5 * randn(H, dk)
+    return d
+
+
 def make_state(N, H, dk, dv, std, seed, device="cpu"):
     """fp32 state tensor [N,H,dk,dv] ~ N(0, std^2) (zeros if std == 0)."""
     if std == 0.0:

@@ -1,0 +1,101 @@
+"""GPU parity of the fused input prologue (Section 4: L2Norm of q and k, Sigmoid of beta, decay
+function on the gate logits) against the fp64 oracle, for the prefill and the pooled decode."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from helpers import o_slices, rel_err, state_slices, worst_slice_err
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-3   # stated tolerance for bf16 inputs
+TOL_F32 = 1e-5
+
+
+def _np(d, *names):
+    return [si.to_np32(d[n_]) for n_ in names]
+
+
+@pytest.mark.parametrize("with_consts", [False, True])
+@pytest.mark.parametrize("T", [130, 1000])
+def test_prefill_fused_prologue(T, with_consts):
+    import paper_2510_26692_amd as kda
+    B, H, d = 2, 4, 128
+    x = si.make_raw_tokens(B, T, H, d, d, "bf16", -2.0, 61 + T)
+    h0 = si.make_state(B, H, d, d, 0.02, 61)
+    a_scale, dt_bias = (x["a_scale"], x["dt_bias"]) if with_consts else (None, None)
+    g = {k_: v_.cuda() for k_, v_ in x.items()}
+    o, hT = kda.kda_chunk_fwd_fused(g["q_raw"], g["k_raw"], g["v"], g["gate"], g["beta_logit"], l2norm_eps=1e-6,
+                                    a_scale=g["a_scale"] if with_consts else None,
+                                    dt_bias=g["dt_bias"] if with_consts else None, h0=h0.cuda(), scale=0.8,
+                                    check=True)
+    torch.cuda.synchronize()
+    o_ref, h_ref = oracle.kda_forward_raw(*_np(x, "q_raw", "k_raw", "v", "gate", "beta_logit"), eps=1e-6,
+                                          a_scale=None if a_scale is None else a_scale.numpy(),
+                                          dt_bias=None if dt_bias is None else dt_bias.numpy(),
+                                          h0=h0.numpy().astype(np.float64), scale=0.8)
+    eo = worst_slice_err(o.cpu().numpy(), o_ref, o_slices(B, H))
+    eh = worst_slice_err(hT.cpu().numpy(), h_ref, state_slices(B, H))
+    print("fused prologue prefill T=%d consts=%s: err_o %.2e err_hT %.2e" % (T, with_consts, eo, eh))
+    assert eo <= TOL_BF16 and eh <= TOL_BF16
+
+
+def test_prefill_fused_prologue_packed_with_short_tail():
+    """Packed sequences whose last chunks are short: padding tokens must stay identity
+    transitions although a zero gate logit alone would mean alpha = 1/2."""
+    import paper_2510_26692_amd as kda
+    lens = np.array([70, 0, 129, 5])
+    H, d = 2, 128
+    T = int(lens.sum())
+    x = si.make_raw_tokens(1, T, H, d, d, "bf16", -1.0, 67)
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32)
+    g = {k_: v_.cuda() for k_, v_ in x.items()}
+    o, hT = kda.kda_chunk_fwd_fused(g["q_raw"], g["k_raw"], g["v"], g["gate"], g["beta_logit"],
+                                    a_scale=g["a_scale"], dt_bias=g["dt_bias"], cu_seqlens=cu.cuda(), check=True)
+    torch.cuda.synchronize()
+    o_ref, h_ref = oracle.kda_forward_raw(*_np(x, "q_raw", "k_raw", "v", "gate", "beta_logit"),
+                                          a_scale=x["a_scale"].numpy(), dt_bias=x["dt_bias"].numpy(),
+                                          cu_seqlens=cu.numpy().astype(np.int64))
+    eo = worst_slice_err(o.cpu().numpy(), o_ref, o_slices(1, H, cu.numpy()))
+    eh = worst_slice_err(hT.cpu().numpy(), h_ref, state_slices(len(lens), H))
+    print("fused prologue packed: err_o %.2e err_hT %.2e" % (eo, eh))
+    assert eo <= TOL_BF16 and eh <= TOL_BF16
+    assert (hT[1] == 0).all()                                       # empty sequence, zero initial state
+
+
+@pytest.mark.parametrize("dtype,tol,d", [("f32", TOL_F32, 64), ("bf16", TOL_BF16, 128)])
+def test_decode_fused_prologue(dtype, tol, d):
+    import paper_2510_26692_amd as kda
+    N, Tq, H, P = 5, 3, 4, 8
+    x = si.make_raw_tokens(N, Tq, H, d, d, dtype, -2.0, 71)
+    pool0 = si.make_state(P, H, d, d, 0.02, 71)
+    idx = torch.tensor([6, 1, -1, 0, 3], dtype=torch.int32)
+    g = {k_: v_.cuda() for k_, v_ in x.items()}
+    pool = pool0.cuda().clone()
+    o = kda.kda_recurrent_steps_fused(g["q_raw"], g["k_raw"], g["v"], g["gate"], g["beta_logit"], pool, idx.cuda(),
+                                      l2norm_eps=1e-6, a_scale=g["a_scale"], dt_bias=g["dt_bias"], scale=1.1)
+    torch.cuda.synchronize()
+    q, k, la, b = oracle.prologue.apply(*_np(x, "q_raw", "k_raw", "gate", "beta_logit"), eps=1e-6,
+                                        a_scale=x["a_scale"].numpy(), dt_bias=x["dt_bias"].numpy())
+    o_ref, pool_ref = oracle.kda_steps_pooled(q, k, si.to_np32(x["v"]), la, b, pool0.numpy().astype(np.float64),
+                                              idx.numpy(), scale=1.1)
+    act = [n for n in range(N) if idx[n] >= 0]
+    o_np, pool_np = o.cpu().numpy(), pool.cpu().numpy()
+    eo = max(rel_err(o_np[n, :, h], o_ref[n, :, h]) for n in act for h in range(H))
+    eS = max(rel_err(pool_np[int(idx[n]), h], pool_ref[int(idx[n]), h]) for n in act for h in range(H))
+    print("fused prologue decode %s: err_o %.2e err_S %.2e" % (dtype, eo, eS))
+    assert eo <= tol and eS <= tol
+
+
+def test_fused_prologue_rejects_what_it_is_not_built_for():
+    import paper_2510_26692_amd as kda
+    x = si.make_raw_tokens(1, 64, 2, 64, 64, "f32", -2.0, 73)
+    g = {k_: v_.cuda() for k_, v_ in x.items()}
+    with pytest.raises(kda.KdaError) as ei:
+        kda.kda_chunk_fwd_fused(g["q_raw"], g["k_raw"], g["v"], g["gate"], g["beta_logit"])
+    assert ei.value.status == 2
+    with pytest.raises(kda.KdaError) as ei:
+        kda.kda_chunk_fwd_fused(g["q_raw"], g["k_raw"], g["v"], g["gate"], g["beta_logit"], l2norm_eps=-1.0)
+    assert ei.value.status == 1

@@ -25,7 +25,8 @@ def test_every_declared_symbol_is_exported():
     assert {"kda_chunk_fwd", "kda_recurrent_step", "kda_chunk_fwd_workspace_size",
             "kda_chunk_fwd_min_workspace_size", "kda_status_string", "kda_last_error",
             "kda_version", "kda_debug_set_phase_mask", "kda_debug_set_overlap",
-            "kda_chunk_fwd_check", "kda_recurrent_steps_pooled"} <= names
+            "kda_chunk_fwd_check", "kda_recurrent_steps_pooled", "kda_chunk_fwd_fused",
+            "kda_recurrent_steps_fused"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
