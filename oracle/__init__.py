@@ -7,9 +7,10 @@ this package.  It never imports the HIP package and shares no code with it.
 (paper Section 3, Eq. (1)); `chunkwise_ref.kda_chunkwise` is a second, numpy
 fp64 statement of the same function written from the chunkwise equations of
 Section 3.1, used to pin the recurrence (chunk-size invariance).  `prologue` states the
-input parameterisation of Section 4 (L2Norm, Sigmoid, the decay function) in float64.
+input parameterisation of Section 4 (L2Norm, Sigmoid, the decay function) and `epilogue`
+the output gate of the same section (head-wise RMSNorm times a sigmoid gate), in float64.
 """
-from . import prologue  # noqa: F401
+from . import epilogue, prologue  # noqa: F401
 from .recurrence import build, kda_forward, kda_step, kda_steps_pooled, num_threads  # noqa: F401
 
 

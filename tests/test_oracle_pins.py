@@ -374,3 +374,23 @@ def test_forward_raw_composes_prologue_and_recurrence():
             S = (np.eye(dk) - be * np.outer(kk, kk)) @ (al[:, None] * S) + be * np.outer(kk, v[0, t, h])
             np.testing.assert_allclose(o[0, t, h], S.T @ qq, rtol=2e-6, atol=2e-7)
         np.testing.assert_allclose(hT[0, h], S, rtol=2e-6, atol=2e-7)
+
+
+def test_epilogue_closed_forms():
+    """Output gate (Section 4): head-wise RMSNorm times Sigmoid(gate), against other formulas."""
+    from oracle import epilogue as epi
+    rng = np.random.default_rng(12)
+    o = rng.standard_normal((2, 5, 3, 16)) * 4
+    y = epi.rmsnorm(o, None, 0.0)
+    np.testing.assert_allclose(np.mean(y * y, axis=-1), 1.0, rtol=1e-13)          # unit mean square
+    np.testing.assert_allclose(epi.rmsnorm(-3.0 * o, None, 0.0), -y, rtol=1e-13)  # scale invariant, odd
+    np.testing.assert_allclose(y, o * np.sqrt(16) / np.linalg.norm(o, axis=-1, keepdims=True), rtol=1e-13)
+    w = rng.standard_normal(16)
+    np.testing.assert_allclose(epi.rmsnorm(o, w, 0.5), o / np.sqrt((o ** 2).mean(-1, keepdims=True) + 0.5) * w,
+                               rtol=1e-14)
+    g = rng.standard_normal(o.shape) * 3
+    out = epi.apply(o, g, w, 0.5)
+    np.testing.assert_allclose(out, epi.rmsnorm(o, w, 0.5) * np.exp(g) / (1 + np.exp(g)), rtol=1e-12)
+    np.testing.assert_allclose(epi.apply(o, np.zeros_like(o), w, 0.5), 0.5 * epi.rmsnorm(o, w, 0.5), rtol=1e-15)
+    big = epi.apply(o, np.full_like(o, 40.0), None, 0.0)
+    np.testing.assert_allclose(big, y, rtol=1e-12)                                  # open gate
