@@ -137,11 +137,26 @@ typedef struct {
 } kda_prologue;
 
 /*
- * kda_chunk_fwd on raw projections: q, k, beta and the gate logits (in the place of log_alpha)
- * go through `prologue` inside the per-chunk kernel; everything else is as for kda_chunk_fwd.
- * Built for KDA_BF16 inputs with dk == dv == 128.
+ * Fused output gate (Section 4): with a kda_epilogue the kernels replace each o (one vector of
+ * dv values per token and head) by
+ *     o <- Sigmoid(gate) * o / sqrt(mean_j o_j^2 + rms_eps) * norm_weight
+ * in fp32 before they store it (`scale` is applied to o first).  The paper gives neither the
+ * epsilon nor the shape of the learned RMSNorm weight: one vector of dv values shared by all
+ * heads is taken (NULL = ones).  The gate's and the output's projections stay with the caller.
+ */
+typedef struct {
+    float        rms_eps;      /* >= 0                                                       */
+    const void  *gate;         /* gate logits, same shape and dtype as v ([..,H,dv]), device  */
+    const float *norm_weight;  /* [dv] fp32, device memory, or NULL                           */
+} kda_epilogue;
+
+/*
+ * kda_chunk_fwd with the fused stages: `prologue` (or NULL: q, k, gate = log_alpha and beta are
+ * taken as kda_chunk_fwd takes them) and `epilogue` (or NULL: o is stored as it is).  Everything
+ * else is as for kda_chunk_fwd.  Built for KDA_BF16 inputs with dk == dv == 128.
  */
 kda_status kda_chunk_fwd_fused(const kda_dims *dims, const kda_prologue *prologue,
+                               const kda_epilogue *epilogue,
                                const void *q_raw, const void *k_raw, const void *v,
                                const void *gate, const void *beta_logit,
                                const float *h0, const int32_t *cu_seqlens,
@@ -205,10 +220,11 @@ kda_status kda_recurrent_steps_pooled(const kda_dims *dims,
                                       void *o, void *hip_stream);
 
 /*
- * kda_recurrent_steps_pooled on raw projections (see kda_prologue); q_raw, k_raw, gate
- * [N,Tq,H,dk], beta_logit [N,Tq,H].
+ * kda_recurrent_steps_pooled with the fused stages (either may be NULL; see kda_prologue and
+ * kda_epilogue); q_raw, k_raw, gate [N,Tq,H,dk], beta_logit [N,Tq,H], epilogue->gate [N,Tq,H,dv].
  */
 kda_status kda_recurrent_steps_fused(const kda_dims *dims, const kda_prologue *prologue,
+                                     const kda_epilogue *epilogue,
                                      const void *q_raw, const void *k_raw, const void *v,
                                      const void *gate, const void *beta_logit,
                                      float *S_pool, const int32_t *state_indices,

@@ -22,14 +22,14 @@ kda_status fail(kda_status code, const char *fmt, ...)
 }
 
 // Kernel-side entry points (one per source file).
-kda_status recurrent_step_dispatch(const kda_dims *, const kda_prologue *, const void *, const void *,
+kda_status recurrent_step_dispatch(const kda_dims *, const kda_prologue *, const kda_epilogue *, const void *, const void *,
                                    const void *, const void *, const void *, float *, void *,
                                    const int32_t *, hipStream_t);
 int recurrent_max_steps();
 kda_status chunk_f32_dispatch(const kda_dims *, const void *, const void *, const void *,
                               const void *, const void *, const float *, const int32_t *, void *,
                               float *, hipStream_t);
-kda_status chunk_mfma_dispatch(const kda_dims *, const kda_prologue *, const void *, const void *, const void *,
+kda_status chunk_mfma_dispatch(const kda_dims *, const kda_prologue *, const kda_epilogue *, const void *, const void *, const void *,
                                const void *, const void *, const float *, const int32_t *, void *,
                                float *, void *, size_t, hipStream_t);
 size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal);
@@ -127,24 +127,35 @@ size_t kda_chunk_fwd_min_workspace_size(const kda_dims *d)
     return chunk_mfma_workspace_size(d, true);
 }
 
+static kda_status check_epilogue(const kda_epilogue *epi)
+{
+    if (!epi) return KDA_OK;
+    if (!(epi->rms_eps >= 0.f)) return fail(KDA_ERR_INVALID_ARG, "rms_eps must be >= 0");
+    if (!epi->gate || !aligned16(epi->gate) || (reinterpret_cast<uintptr_t>(epi->norm_weight) & 15u))
+        return fail(KDA_ERR_INVALID_ARG, "epilogue gate must be non-NULL; gate and norm_weight 16-byte aligned");
+    return KDA_OK;
+}
+
 static kda_status check_prologue(const kda_prologue *pro)
 {
-    if (!pro) return fail(KDA_ERR_INVALID_ARG, "prologue is NULL");
+    if (!pro) return KDA_OK;
     if (!(pro->l2norm_eps >= 0.f)) return fail(KDA_ERR_INVALID_ARG, "l2norm_eps must be >= 0");
     if ((reinterpret_cast<uintptr_t>(pro->a_scale) & 3u) || (reinterpret_cast<uintptr_t>(pro->dt_bias) & 3u))
         return fail(KDA_ERR_INVALID_ARG, "a_scale and dt_bias must be 4-byte aligned");
     return KDA_OK;
 }
 
-static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, const void *q, const void *k,
+static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
+                                 const void *q, const void *k,
                                  const void *v, const void *log_alpha, const void *beta, const float *h0,
                                  const int32_t *cu_seqlens, void *o, float *hT, void *workspace,
                                  size_t workspace_bytes, void *hip_stream)
 {
     kda_status st = check_dims(d, cu_seqlens != nullptr);
     if (st != KDA_OK) return st;
-    if (pro && !(d->in_dtype == KDA_BF16 && d->dk == 128 && d->dv == 128))
-        return fail(KDA_ERR_UNSUPPORTED, "the fused prologue is built for bf16 inputs with dk == dv == 128");
+    if ((pro || epi) && !(d->in_dtype == KDA_BF16 && d->dk == 128 && d->dv == 128))
+        return fail(KDA_ERR_UNSUPPORTED, "the fused stages are built for bf16 inputs with dk == dv == 128");
+    if (epi && (o == epi->gate)) return fail(KDA_ERR_INVALID_ARG, "o must not alias the output gate");
     if (d->chunk != kChunk) return fail(KDA_ERR_UNSUPPORTED, "chunk must be %d, got %d", kChunk, d->chunk);
     const bool empty = d->seqlen == 0 || d->heads == 0 || d->batch == 0;
     if (!empty && (!q || !k || !v || !log_alpha || !beta || !o))
@@ -160,7 +171,7 @@ static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, con
     if (d->in_dtype == KDA_BF16 && d->dk != 128 && mfma_path(d))
         return fail(KDA_ERR_UNSUPPORTED, "bf16 prefill is built for dk == dv == 128 only");
     if (!mfma_path(d)) {
-        if (pro) return fail(KDA_ERR_UNSUPPORTED, "the fused prologue needs the matrix-core prefill");
+        if (pro || epi) return fail(KDA_ERR_UNSUPPORTED, "the fused stages need the matrix-core prefill");
         return chunk_f32_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, stream);
     }
 
@@ -172,7 +183,7 @@ static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, con
         if (workspace_bytes < need)
             return fail(KDA_ERR_WORKSPACE, "workspace has %zu bytes, at least %zu needed", workspace_bytes, need);
     }
-    return chunk_mfma_dispatch(d, pro, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
+    return chunk_mfma_dispatch(d, pro, epi, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
                                workspace_bytes, stream);
 }
 
@@ -182,19 +193,20 @@ kda_status kda_chunk_fwd(const kda_dims *d, const void *q, const void *k, const 
                          size_t workspace_bytes, void *hip_stream)
 {
     g_last_error[0] = 0;
-    return chunk_fwd_impl(d, nullptr, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
+    return chunk_fwd_impl(d, nullptr, nullptr, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
                           workspace_bytes, hip_stream);
 }
 
-kda_status kda_chunk_fwd_fused(const kda_dims *d, const kda_prologue *pro, const void *q_raw,
-                               const void *k_raw, const void *v, const void *gate, const void *beta_logit,
+kda_status kda_chunk_fwd_fused(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
+                               const void *q_raw, const void *k_raw, const void *v, const void *gate, const void *beta_logit,
                                const float *h0, const int32_t *cu_seqlens, void *o, float *hT,
                                void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     g_last_error[0] = 0;
     kda_status st = check_prologue(pro);
+    if (st == KDA_OK) st = check_epilogue(epi);
     if (st != KDA_OK) return st;
-    return chunk_fwd_impl(d, pro, q_raw, k_raw, v, gate, beta_logit, h0, cu_seqlens, o, hT, workspace,
+    return chunk_fwd_impl(d, pro, epi, q_raw, k_raw, v, gate, beta_logit, h0, cu_seqlens, o, hT, workspace,
                           workspace_bytes, hip_stream);
 }
 
@@ -234,11 +246,12 @@ kda_status kda_recurrent_step(const kda_dims *d, const void *q, const void *k, c
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(log_alpha) || !aligned16(S) ||
         !aligned16(o) || (reinterpret_cast<uintptr_t>(beta) & 1u))
         return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    return recurrent_step_dispatch(d, nullptr, q, k, v, log_alpha, beta, S, o, nullptr,
+    return recurrent_step_dispatch(d, nullptr, nullptr, q, k, v, log_alpha, beta, S, o, nullptr,
                                    static_cast<hipStream_t>(hip_stream));
 }
 
-static kda_status steps_pooled_impl(const kda_dims *d, const kda_prologue *pro, const void *q, const void *k,
+static kda_status steps_pooled_impl(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
+                                    const void *q, const void *k,
                                     const void *v, const void *log_alpha, const void *beta, float *S_pool,
                                     const int32_t *state_indices, void *o, void *hip_stream)
 {
@@ -254,7 +267,7 @@ static kda_status steps_pooled_impl(const kda_dims *d, const kda_prologue *pro, 
         !aligned16(o) || (reinterpret_cast<uintptr_t>(beta) & 1u) ||
         (reinterpret_cast<uintptr_t>(state_indices) & 3u))
         return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned (state_indices: 4)");
-    return recurrent_step_dispatch(d, pro, q, k, v, log_alpha, beta, S_pool, o, state_indices,
+    return recurrent_step_dispatch(d, pro, epi, q, k, v, log_alpha, beta, S_pool, o, state_indices,
                                    static_cast<hipStream_t>(hip_stream));
 }
 
@@ -263,18 +276,19 @@ kda_status kda_recurrent_steps_pooled(const kda_dims *d, const void *q, const vo
                                       const int32_t *state_indices, void *o, void *hip_stream)
 {
     g_last_error[0] = 0;
-    return steps_pooled_impl(d, nullptr, q, k, v, log_alpha, beta, S_pool, state_indices, o, hip_stream);
+    return steps_pooled_impl(d, nullptr, nullptr, q, k, v, log_alpha, beta, S_pool, state_indices, o, hip_stream);
 }
 
-kda_status kda_recurrent_steps_fused(const kda_dims *d, const kda_prologue *pro, const void *q_raw,
-                                     const void *k_raw, const void *v, const void *gate,
+kda_status kda_recurrent_steps_fused(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
+                                     const void *q_raw, const void *k_raw, const void *v, const void *gate,
                                      const void *beta_logit, float *S_pool, const int32_t *state_indices,
                                      void *o, void *hip_stream)
 {
     g_last_error[0] = 0;
     kda_status st = check_prologue(pro);
+    if (st == KDA_OK) st = check_epilogue(epi);
     if (st != KDA_OK) return st;
-    return steps_pooled_impl(d, pro, q_raw, k_raw, v, gate, beta_logit, S_pool, state_indices, o, hip_stream);
+    return steps_pooled_impl(d, pro, epi, q_raw, k_raw, v, gate, beta_logit, S_pool, state_indices, o, hip_stream);
 }
 
 }  // extern "C"

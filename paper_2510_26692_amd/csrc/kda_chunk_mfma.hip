@@ -686,7 +686,9 @@ __device__ __forceinline__ void static_for(F &&f)
 constexpr int kUnits = kLdsBlockBytes / 16;                  // 16-byte units per staged block
 constexpr int kXS = 2 * kLdsBlockBytes;                      // fp16 S exchange: [c][tau][s] frags
 constexpr int kXV = kXS + 4 * 4 * 2 * kFragBytes;            // fp16 V_new exchange: [c][rho][s] frags
-constexpr int kLds = kXV + 4 * 2 * 2 * kFragBytes;
+constexpr int kRed = kXV + 4 * 2 * 2 * kFragBytes;          // fp32 [2][4][32] sums of squares (output gate)
+constexpr int kNormW = kRed + 2 * 4 * 32 * 4;                // fp32 [128] RMSNorm weight (output gate)
+constexpr int kLds = kNormW + D * 4;
 static_assert(kLds <= 160 * 1024, "kda_scan exceeds the 160 KiB of LDS");
 
 // MFMA slots of wave half P, in issue order:
@@ -725,12 +727,21 @@ __device__ __noinline__ void wait_ready(const uint32_t *flag, uint32_t epoch, ui
     }
 }
 
-template <int P, bool kFlags>
+// Output gate of Section 4, applied to O before it is stored (kEpi): gate logits [B,T,H,dv] in the
+// input dtype, RMSNorm weight [dv] (NULL = ones) and epsilon.
+struct EpiParams {
+    const uint16_t *gate;
+    const float *norm_w;
+    float eps;
+};
+
+template <int P, bool kFlags, bool kEpi>
 __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
                                               const float *state_in, float *state_out, float *o,
                                               int64_t st_base, int64_t tok_base, int64_t len, int H,
                                               int64_t c_begin, int64_t c_end, int h,
-                                              const uint32_t *ready, uint32_t epoch, uint32_t *status)
+                                              const uint32_t *ready, uint32_t epoch, uint32_t *status,
+                                              const EpiParams epi)
 {
     using namespace scan;
     constexpr int LA = 6, RING = 8;
@@ -839,9 +850,27 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
 #pragma unroll
                 for (int z = 0; z < 4; ++z) av[4 * i + z] = un[stage][i][z];
             // this register set is free now: start fetching chunk ci + 2 into it
+            // kEpi: gate logits of this lane's 16 outputs (token 32 P + x, columns 32 c + 8 q + 4 hh + 0..3).
+            // They go out before the slot loads of chunk ci + 2: loads return in order, and these are
+            // needed within this step
+            u32x2 gate_raw[4];
+            if (kEpi) {
+                const int64_t trow = ci * kChunk + 32 * P + x;
+                const uint16_t *gp = epi.gate + ((tok_base + trow) * H + h) * (int64_t)D + 32 * c + 4 * hh;
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const u32x2 z2 = {0u, 0u};
+                    gate_raw[q4] = (trow < len) ? *reinterpret_cast<const u32x2 *>(gp + 8 * q4) : z2;
+                }
+            }
             if (poll && ci + 3 < c_end)
                 seen = __hip_atomic_load(ready + (ci + 3 - c_begin), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (ci + 2 < c_end) fetch(slot0 + (ci + 2 - c_begin) * slot_stride, pre[stage], un[stage]);
+            // (issued unconditionally, past the end the last slot is simply fetched again: with a
+            // fixed number of loads in flight behind them, earlier loads can be waited for one by one)
+            {
+                const int64_t cf = (ci + 2 < c_end) ? ci + 2 : c_end - 1;
+                fetch(slot0 + (cf - c_begin) * slot_stride, pre[stage], un[stage]);
+            }
             // the partner's two d_k tiles of S
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -855,8 +884,18 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
             for (int i = 0; i < LA; ++i)
                 ring[i % RING] = *reinterpret_cast<const h8 *>(cur + slot_lds_offset<P>(i));
 
+            float sg[16];                                    // kEpi: Sigmoid(gate) * norm weight per output
             static_for<0, NS>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value;
+                if constexpr (kEpi && i >= 16 && i < 24) {
+                    // two gate factors per MFMA slot: the transcendentals run under the matrix cores
+                    constexpr int j = i - 16, q4 = j / 2, w = j % 2;
+                    float g0, g1;
+                    unpack_bf16x2(gate_raw[q4][w], g0, g1);
+                    const float2 nw = *reinterpret_cast<const float2 *>(lds + kNormW + (32 * c + 4 * hh + 8 * q4 + 2 * w) * 4);
+                    sg[4 * q4 + 2 * w] = nw.x * __builtin_amdgcn_rcpf(1.f + fast_exp2(-g0 * kLog2e));
+                    sg[4 * q4 + 2 * w + 1] = nw.y * __builtin_amdgcn_rcpf(1.f + fast_exp2(-g1 * kLog2e));
+                }
                 if constexpr (i + LA < NS)
                     ring[(i + LA) % RING] = *reinterpret_cast<const h8 *>(cur + slot_lds_offset<P>(i + LA));
                 const h8 a = ring[i % RING];
@@ -903,6 +942,25 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 KDA_FENCE();   // keeps each operand read LA slots ahead of its MFMA
             });
 
+            if (kEpi) {
+                // O <- Sigmoid(gate) * RMSNorm(O) * w.  A token's 128 outputs sit in the four waves
+                // of this token tile: lane-local sum of squares, the two lane halves by a swap,
+                // the four waves through LDS.
+                float ssq = 0.f;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) ssq = fmaf(ao[j], ao[j], ssq);
+                ssq += __shfl_xor(ssq, 32);
+                float *red = reinterpret_cast<float *>(lds + kRed);
+                if (hh == 0) red[(P * 4 + c) * 32 + x] = ssq;
+                // the next chunk's block goes to the other LDS stage while the partial sums gather
+                if (more) publish(pre[stage ^ 1], stage ^ 1);
+                __syncthreads();                                             // B3 (kEpi only)
+                const float tot = red[(P * 4 + 0) * 32 + x] + red[(P * 4 + 1) * 32 + x] +
+                                  red[(P * 4 + 2) * 32 + x] + red[(P * 4 + 3) * 32 + x];
+                const float rstd = __builtin_amdgcn_rsqf(tot * (1.0f / D) + epi.eps);
+#pragma unroll
+                for (int j = 0; j < 16; ++j) ao[j] *= rstd * sg[j];
+            }
             // write O (fp32, already scaled): 16 bytes per store
             {
                 const int64_t t0 = ci * kChunk;
@@ -917,7 +975,7 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
             }
             KDA_FENCE();
             // the next chunk's block (fetched one step ago) goes to the other LDS stage
-            if (more) publish(pre[stage ^ 1], stage ^ 1);
+            if (!kEpi && more) publish(pre[stage ^ 1], stage ^ 1);
         };
         for (int64_t ci = c_begin; ci < c_end; ci += 2) {
             chunk_step(ci, std::integral_constant<int, 0>{});
@@ -935,12 +993,12 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
 }
 
 // kFlags: the slots are produced by a kda_intra that runs at the same time (per-slot ready flags).
-template <bool kFlags>
+template <bool kFlags, bool kEpi>
 __global__ __launch_bounds__(512)
 void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, float *state_out,
                      const int32_t *__restrict__ cu_seqlens, float *__restrict__ o, int64_t T, int H,
                      int64_t seg_chunks, int64_t seg_index, const uint32_t *ready, uint32_t epoch,
-                     uint32_t *status)
+                     uint32_t *status, EpiParams epi)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -956,16 +1014,18 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
     const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks) * H + h) * (int64_t)kSlotBytes;
     const int64_t slot_stride = (int64_t)H * kSlotBytes;
 
+    if (kEpi && threadIdx.x < D)     // RMSNorm weights: read by every step after its first barrier
+        reinterpret_cast<float *>(lds + scan::kNormW)[threadIdx.x] = epi.norm_w ? epi.norm_w[threadIdx.x] : 1.f;
     const uint32_t *flag0 = kFlags ? ready + (int64_t)blockIdx.x * seg_chunks : nullptr;
     // nothing is waited for without flags: leave a clean status word for kda_chunk_fwd_check
     if (!kFlags && status && blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
 
     if (wave < 4)
-        kda_scan_body<0, kFlags>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
-                         flag0, epoch, status);
+        kda_scan_body<0, kFlags, kEpi>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H,
+                                       c_begin, c_end, h, flag0, epoch, status, epi);
     else
-        kda_scan_body<1, kFlags>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H, c_begin, c_end, h,
-                         flag0, epoch, status);
+        kda_scan_body<1, kFlags, kEpi>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H,
+                                       c_begin, c_end, h, flag0, epoch, status, epi);
 }
 
 // flags and status word of the overlapped mode start every call at zero
@@ -1042,9 +1102,13 @@ static bool reserve_lds()
                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess;
     if (!ok) (void)hipGetLastError();
     done[dev] = ok;
@@ -1098,7 +1162,8 @@ size_t chunk_mfma_status_offset(const kda_dims *d, size_t workspace_bytes)
     return mfma::make_plan(d, workspace_bytes, false).status_offset;
 }
 
-kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const void *q, const void *k,
+kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
+                               const void *q, const void *k,
                                const void *v, const void *log_alpha, const void *beta, const float *h0,
                                const int32_t *cu, void *o, float *hT, void *workspace,
                                size_t workspace_bytes, hipStream_t stream)
@@ -1106,6 +1171,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     using namespace mfma;
     RawParams raw = {nullptr, nullptr, 0.f};
     if (pro) { raw.a_scale = pro->a_scale; raw.dt_bias = pro->dt_bias; raw.eps = pro->l2norm_eps; }
+    EpiParams ep = {nullptr, nullptr, 0.f};
+    if (epi) { ep.gate = static_cast<const uint16_t *>(epi->gate); ep.norm_w = epi->norm_weight; ep.eps = epi->rms_eps; }
     if (d->seqlen == 0) {
         // nothing to scan: the final state is the initial one
         if (hT && hT != h0) {
@@ -1168,9 +1235,10 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             if (hipEventRecord(side->fork, stream) != hipSuccess ||
                 hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
-            hipLaunchKernelGGL(kda_scan_kernel<true>, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
+            auto scan_k = epi ? kda_scan_kernel<true, true> : kda_scan_kernel<true, false>;
+            hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
-                               flags, epoch, status);
+                               flags, epoch, status, ep);
             auto intra = pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>;
             hipLaunchKernelGGL(intra, intra_grid_overlap,
                                dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
@@ -1184,10 +1252,11 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                 hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
                                    (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
                                    (uint32_t *)nullptr, 0u, raw);
+            auto scan_k = epi ? kda_scan_kernel<false, true> : kda_scan_kernel<false, false>;
             if (g_phase_mask & 2)
-                hipLaunchKernelGGL(kda_scan_kernel<false>, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
+                hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                    static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
-                                   (const uint32_t *)nullptr, 0u, status);
+                                   (const uint32_t *)nullptr, 0u, status, ep);
         }
     }
     hipError_t e = hipGetLastError();

@@ -25,17 +25,21 @@ constexpr int kMaxSteps = 8;
 
 // kRaw:    q, k, log_alpha, beta are the raw projections of Section 4; the kernel applies L2Norm,
 //          Sigmoid and log alpha = -a_scale[h] softplus(gate + dt_bias[h][c]) while it stages them.
-template <typename Tin, int DK, int DV, bool kRaw>
+// kEpi:    o leaves as Sigmoid(out_gate) * RMSNorm(o) * norm_w (Section 4, output gate); the mean
+//          square runs over the DV values of the (token, head), i.e. over the block's waves.
+template <typename Tin, int DK, int DV, bool kRaw, bool kEpi>
 __global__ __launch_bounds__(DV * 2)
 void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                      const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
                      const Tin *__restrict__ beta, float *__restrict__ S,
                      float *__restrict__ o, float scale, int H, int steps,
                      const int32_t *__restrict__ indices, const float *__restrict__ a_scale,
-                     const float *__restrict__ dt_bias, float l2_eps)
+                     const float *__restrict__ dt_bias, float l2_eps, const Tin *__restrict__ out_gate,
+                     const float *__restrict__ norm_w, float rms_eps)
 {
     constexpr int ROWS = DK / 8;             // state rows per lane
     __shared__ float s_alpha[kMaxSteps][DK], s_k[kMaxSteps][DK], s_q[kMaxSteps][DK];
+    __shared__ float s_ssq[kMaxSteps][DV / 32];
 
     const int64_t pair = blockIdx.x;         // (sequence, head) index
     const int tid = threadIdx.x;
@@ -144,28 +148,54 @@ void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             o0 += __shfl_xor(o0, d); o1 += __shfl_xor(o1, d);
             o2 += __shfl_xor(o2, d); o3 += __shfl_xor(o3, d);
         }
+        o0 *= scale; o1 *= scale; o2 *= scale; o3 *= scale;
+        if (kEpi) {
+            // every lane holds the four outputs of its column group: sum the squares over the
+            // wave's eight groups, then over the block's waves through LDS
+            float ssq = o0 * o0 + o1 * o1 + o2 * o2 + o3 * o3;
+            ssq += __shfl_xor(ssq, 1); ssq += __shfl_xor(ssq, 2); ssq += __shfl_xor(ssq, 4);
+            if (lane == 0) s_ssq[t][wave] = ssq;
+            __syncthreads();
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < DV / 32; ++w) tot += s_ssq[t][w];
+            const float rstd = __builtin_amdgcn_rsqf(tot * (1.0f / DV) + rms_eps);
+            float gv[4], wv[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                gv[c] = load_as_float(out_gate + row * DV + col + c);
+                wv[c] = norm_w ? norm_w[col + c] : 1.f;
+            }
+            o0 *= rstd * wv[0] * __builtin_amdgcn_rcpf(1.f + fast_exp2(-gv[0] * kLog2e));
+            o1 *= rstd * wv[1] * __builtin_amdgcn_rcpf(1.f + fast_exp2(-gv[1] * kLog2e));
+            o2 *= rstd * wv[2] * __builtin_amdgcn_rcpf(1.f + fast_exp2(-gv[2] * kLog2e));
+            o3 *= rstd * wv[3] * __builtin_amdgcn_rcpf(1.f + fast_exp2(-gv[3] * kLog2e));
+        }
         if (rg == 0) {
-            f32x4 out = {o0 * scale, o1 * scale, o2 * scale, o3 * scale};
+            f32x4 out = {o0, o1, o2, o3};
             *reinterpret_cast<f32x4 *>(o + row * DV + col) = out;
         }
     }
 }
 
 template <typename Tin, int DK, int DV>
-static kda_status launch_step(const kda_dims *d, const kda_prologue *pro, const void *q, const void *k,
-                              const void *v, const void *log_alpha, const void *beta, float *S, void *o,
-                              const int32_t *indices, hipStream_t stream)
+static kda_status launch_step(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
+                              const void *q, const void *k, const void *v, const void *log_alpha,
+                              const void *beta, float *S, void *o, const int32_t *indices, hipStream_t stream)
 {
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
     if (pairs == 0) return KDA_OK;
     if (pairs > 0x7fffffffLL) return fail(KDA_ERR_INVALID_ARG, "num_seqs*heads exceeds 2^31-1");
-    auto step = pro ? kda_step_kernel<Tin, DK, DV, true> : kda_step_kernel<Tin, DK, DV, false>;
+    auto step = pro ? (epi ? kda_step_kernel<Tin, DK, DV, true, true> : kda_step_kernel<Tin, DK, DV, true, false>)
+                    : (epi ? kda_step_kernel<Tin, DK, DV, false, true> : kda_step_kernel<Tin, DK, DV, false, false>);
     hipLaunchKernelGGL(step, dim3((unsigned)pairs), dim3(DV * 2), 0, stream,
                        static_cast<const Tin *>(q), static_cast<const Tin *>(k),
                        static_cast<const Tin *>(v), static_cast<const Tin *>(log_alpha),
                        static_cast<const Tin *>(beta), S, static_cast<float *>(o), d->scale,
                        (int)d->heads, (int)d->seqlen, indices, pro ? pro->a_scale : nullptr,
-                       pro ? pro->dt_bias : nullptr, pro ? pro->l2norm_eps : 0.f);
+                       pro ? pro->dt_bias : nullptr, pro ? pro->l2norm_eps : 0.f,
+                       static_cast<const Tin *>(epi ? epi->gate : nullptr), epi ? epi->norm_weight : nullptr,
+                       epi ? epi->rms_eps : 0.f);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_step_kernel: %s", hipGetErrorString(e));
     return KDA_OK;
@@ -173,17 +203,18 @@ static kda_status launch_step(const kda_dims *d, const kda_prologue *pro, const 
 
 int recurrent_max_steps() { return kMaxSteps; }
 
-kda_status recurrent_step_dispatch(const kda_dims *d, const kda_prologue *pro, const void *q, const void *k,
-                                   const void *v, const void *log_alpha, const void *beta, float *S, void *o,
-                                   const int32_t *indices, hipStream_t stream)
+kda_status recurrent_step_dispatch(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
+                                   const void *q, const void *k, const void *v, const void *log_alpha,
+                                   const void *beta, float *S, void *o, const int32_t *indices,
+                                   hipStream_t stream)
 {
     const bool bf = d->in_dtype == KDA_BF16;
     if (d->dk == 128 && d->dv == 128)
-        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, pro, q, k, v, log_alpha, beta, S, o, indices, stream)
-                  : launch_step<float, 128, 128>(d, pro, q, k, v, log_alpha, beta, S, o, indices, stream);
+        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, stream)
+                  : launch_step<float, 128, 128>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, stream);
     if (d->dk == 64 && d->dv == 64)
-        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, pro, q, k, v, log_alpha, beta, S, o, indices, stream)
-                  : launch_step<float, 64, 64>(d, pro, q, k, v, log_alpha, beta, S, o, indices, stream);
+        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, stream)
+                  : launch_step<float, 64, 64>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, stream);
     return fail(KDA_ERR_UNSUPPORTED, "recurrent step supports dk == dv in {64,128}, got %d x %d",
                 d->dk, d->dv);
 }

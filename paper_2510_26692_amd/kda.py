@@ -39,6 +39,11 @@ class KdaPrologue(ctypes.Structure):
     _fields_ = [("l2norm_eps", ctypes.c_float), ("a_scale", ctypes.c_void_p), ("dt_bias", ctypes.c_void_p)]
 
 
+class KdaEpilogue(ctypes.Structure):
+    """Mirror of ``kda_epilogue``."""
+    _fields_ = [("rms_eps", ctypes.c_float), ("gate", ctypes.c_void_p), ("norm_weight", ctypes.c_void_p)]
+
+
 def library_path():
     return _LIB_PATH
 
@@ -74,11 +79,11 @@ def load_library():
     lib.kda_recurrent_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kda_recurrent_steps_pooled.restype = ctypes.c_int
     lib.kda_recurrent_steps_pooled.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
-    pp = ctypes.POINTER(KdaPrologue)
+    pp, ep = ctypes.POINTER(KdaPrologue), ctypes.POINTER(KdaEpilogue)
     lib.kda_chunk_fwd_fused.restype = ctypes.c_int
-    lib.kda_chunk_fwd_fused.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kda_chunk_fwd_fused.argtypes = [dp, pp, ep, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kda_recurrent_steps_fused.restype = ctypes.c_int
-    lib.kda_recurrent_steps_fused.argtypes = [dp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.kda_recurrent_steps_fused.argtypes = [dp, pp, ep, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -165,18 +170,32 @@ def _make_prologue(H, dk, l2norm_eps, a_scale, dt_bias):
                        dt_bias=None if dt_bias is None else dt_bias.data_ptr())
 
 
-def kda_chunk_fwd_fused(q_raw, k_raw, v, gate, beta_logit, l2norm_eps=1e-6, a_scale=None, dt_bias=None,
-                        **kw):
-    """kda_chunk_fwd on raw projections: L2Norm of q and k, Sigmoid of beta and the decay function
-    log_alpha = -a_scale[h] softplus(gate + dt_bias[h]) run inside the kernel (see kda_prologue in
-    kda.h).  a_scale fp32 [H] and dt_bias fp32 [H,dk] on the device, or None.  Other arguments and
-    the result as for kda_chunk_fwd."""
-    pro = _make_prologue(q_raw.shape[2], q_raw.shape[3], l2norm_eps, a_scale, dt_bias)
-    return kda_chunk_fwd(q_raw, k_raw, v, gate, beta_logit, _prologue=pro, **kw)
+def _make_epilogue(v, out_gate, norm_weight, rms_eps):
+    if out_gate is None:
+        return None
+    if out_gate.shape != v.shape or out_gate.dtype != v.dtype or not out_gate.is_cuda or not out_gate.is_contiguous():
+        raise ValueError("out_gate must be a contiguous device tensor with the shape and dtype of v")
+    if norm_weight is not None and (norm_weight.dtype != torch.float32 or tuple(norm_weight.shape) != (v.shape[-1],)
+                                    or not norm_weight.is_cuda or not norm_weight.is_contiguous()):
+        raise ValueError("norm_weight must be a contiguous fp32 device tensor of shape (dv,)")
+    return KdaEpilogue(rms_eps=float(rms_eps), gate=out_gate.data_ptr(),
+                       norm_weight=None if norm_weight is None else norm_weight.data_ptr())
+
+
+def kda_chunk_fwd_fused(q, k, v, gate, beta, prologue=True, l2norm_eps=1e-6, a_scale=None, dt_bias=None,
+                        out_gate=None, norm_weight=None, rms_eps=1e-6, **kw):
+    """kda_chunk_fwd with the fused stages of kda.h.  prologue=True: q, k, beta and gate are raw
+    projections (L2Norm, Sigmoid and log_alpha = -a_scale[h] softplus(gate + dt_bias[h]) run inside
+    the kernel; a_scale fp32 [H], dt_bias fp32 [H,dk] on the device, or None); prologue=False: they
+    are taken as kda_chunk_fwd takes them (gate = log_alpha).  out_gate (shape and dtype of v) turns
+    on the output gate o <- Sigmoid(out_gate) * RMSNorm(o) * norm_weight (fp32 [dv] or None).
+    Other arguments and the result as for kda_chunk_fwd."""
+    pro = _make_prologue(q.shape[2], q.shape[3], l2norm_eps, a_scale, dt_bias) if prologue else None
+    return kda_chunk_fwd(q, k, v, gate, beta, _fused=(pro, _make_epilogue(v, out_gate, norm_weight, rms_eps)), **kw)
 
 
 def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0, o=None,
-                  hT=None, want_hT=True, workspace=None, max_seqlen=0, check=False, _prologue=None):
+                  hT=None, want_hT=True, workspace=None, max_seqlen=0, check=False, _fused=None):
     """Chunkwise prefill.  q,k,log_alpha [B,T,H,dk]; v [B,T,H,dv]; beta [B,T,H];
     h0 [N,H,dk,dv] fp32 or None; cu_seqlens int32 [N+1] on device or None.
     Returns (o fp32 [B,T,H,dv], hT fp32 [N,H,dk,dv] or None).  `o`, `hT` and
@@ -209,10 +228,11 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     tail = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(h0), _ptr(cu_seqlens), _ptr(o),
             _ptr(hT), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(dev))
-    if _prologue is None:
+    if _fused is None:
         st = lib.kda_chunk_fwd(ctypes.byref(dims), *tail)
     else:
-        st = lib.kda_chunk_fwd_fused(ctypes.byref(dims), ctypes.byref(_prologue), *tail)
+        st = lib.kda_chunk_fwd_fused(ctypes.byref(dims), *[None if f is None else ctypes.byref(f) for f in _fused],
+                                     *tail)
     if st != 0:
         raise KdaError(st, kda_last_error())
     if check:
@@ -242,15 +262,16 @@ def kda_recurrent_step(q, k, v, log_alpha, beta, S, scale=1.0, o=None):
     return o
 
 
-def kda_recurrent_steps_fused(q_raw, k_raw, v, gate, beta_logit, S_pool, state_indices=None, l2norm_eps=1e-6,
-                              a_scale=None, dt_bias=None, **kw):
-    """kda_recurrent_steps_pooled on raw projections (see kda_chunk_fwd_fused)."""
-    pro = _make_prologue(q_raw.shape[2], q_raw.shape[3], l2norm_eps, a_scale, dt_bias)
-    return kda_recurrent_steps_pooled(q_raw, k_raw, v, gate, beta_logit, S_pool, state_indices, _prologue=pro, **kw)
+def kda_recurrent_steps_fused(q, k, v, gate, beta, S_pool, state_indices=None, prologue=True, l2norm_eps=1e-6,
+                              a_scale=None, dt_bias=None, out_gate=None, norm_weight=None, rms_eps=1e-6, **kw):
+    """kda_recurrent_steps_pooled with the fused stages (see kda_chunk_fwd_fused)."""
+    pro = _make_prologue(q.shape[2], q.shape[3], l2norm_eps, a_scale, dt_bias) if prologue else None
+    return kda_recurrent_steps_pooled(q, k, v, gate, beta, S_pool, state_indices,
+                                      _fused=(pro, _make_epilogue(v, out_gate, norm_weight, rms_eps)), **kw)
 
 
 def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=None, scale=1.0, o=None,
-                               _prologue=None):
+                               _fused=None):
     """Decode over a state pool.  q,k,log_alpha [N,Tq,H,dk]; v [N,Tq,H,dv]; beta [N,Tq,H];
     S_pool fp32 [P,H,dk,dv], the addressed states updated in place; state_indices int32 [N] on the
     device (negative = skip) or None for 0..N-1.  Returns o fp32 [N,Tq,H,dv]."""
@@ -275,10 +296,11 @@ def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=N
                    in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale), max_seqlen=0)
     tail = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S_pool), _ptr(state_indices), _ptr(o),
             _stream_ptr(dev))
-    if _prologue is None:
+    if _fused is None:
         st = lib.kda_recurrent_steps_pooled(ctypes.byref(dims), *tail)
     else:
-        st = lib.kda_recurrent_steps_fused(ctypes.byref(dims), ctypes.byref(_prologue), *tail)
+        st = lib.kda_recurrent_steps_fused(ctypes.byref(dims),
+                                           *[None if f is None else ctypes.byref(f) for f in _fused], *tail)
     if st != 0:
         raise KdaError(st, kda_last_error())
     return o
