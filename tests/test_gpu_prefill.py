@@ -165,3 +165,27 @@ def test_bf16_prefill_inside_a_captured_graph_replays_correctly():
         # eager work between the replays
         o2, _ = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"])
         assert torch.equal(o2, o_ref)
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_bf16_random_shapes_and_layouts(seed):
+    """Seeded sweep over small problems: batch or packed layout (with empty and one-token sequences),
+    any number of heads, ragged lengths, with or without initial state, slow to fast decay."""
+    rng = np.random.default_rng(1000 + seed)
+    H = int(rng.integers(1, 6))
+    mu = float(rng.choice([-3.0, -1.0, 0.5]))
+    h0_std = float(rng.choice([0.0, 0.05]))
+    scale = float(rng.choice([1.0, 128 ** -0.5]))
+    if rng.random() < 0.5:
+        B, T = int(rng.integers(1, 4)), int(rng.integers(1, 700))
+        x = si.make_prefill(B, T, H, 128, 128, "bf16", mu, 2000 + seed, h0_std)
+        desc = "batch B=%d T=%d" % (B, T)
+    else:
+        lens = rng.integers(0, 400, int(rng.integers(1, 6)))
+        lens[rng.integers(0, len(lens))] = int(rng.choice([0, 1, 64, 65]))
+        if lens.sum() == 0:
+            lens[0] = 3
+        x = si.make_varlen(lens, H, 128, 128, "bf16", mu, 2000 + seed, h0_std)
+        desc = "packed lens=%s" % lens.tolist()
+    eo, eh = check_prefill(x, TOL_BF16, scale=scale)
+    print("random %d: %s H=%d mu=%.1f h0=%.2f scale=%.3f: err_o %.2e err_hT %.2e" % (seed, desc, H, mu, h0_std, scale, eo, eh))
