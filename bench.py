@@ -261,6 +261,16 @@ def main():
         "hbm_frac": pooled_bytes / (ms_pooled * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
 
+    # what a plain device-to-device copy reaches on this GPU (bytes read + written per second)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ms_copy = _time_region(torch, lambda: dst.copy_(src), 10)
+    copy_gbs = 2 * src.numel() / (ms_copy * 1e-3) / 1e9
+    del src, dst
+    decode_obj["roofline"]["measured_copy_GBps"] = copy_gbs
+    decode_obj["roofline"]["frac_of_measured_copy"] = decode_obj["value"] / copy_gbs
+
     # ------------------------------------------------------------------ CPU baseline (oracle)
     cpu = None
     if not args.no_cpu_baseline:
