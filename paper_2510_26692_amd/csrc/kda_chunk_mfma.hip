@@ -21,9 +21,13 @@
 // sub-chunks.  For a pair of tokens in different sub-chunks the decay
 // 2^(G_r - G_i) is split at the boundary in front of the row's sub-chunk, so both
 // factors are <= 1 and go straight into the operands.  Inside a sub-chunk it is
-// split at the sub-chunk's start, which makes the column factor 2^(-G_i) >= 1; a
-// channel whose decay across the sub-chunk exceeds 2^-kStrongLog2 is taken out of
-// those operands and added back exactly, pair by pair, in fp32.
+// split at the point where half of the sub-chunk's decay D (in log2 units) has been
+// spent: row factor 2^(G_r + D/2), column factor 2^(-G_i - D/2), both within
+// 2^(+-D/2), so fp16 holds them for D up to kStrongLog2 (the row operands of all
+// tiles carry the 2^(D/2) and the column operands of the tiles below undo it).  A
+// channel whose decay across the sub-chunk exceeds 2^-kStrongLog2 keeps the split at
+// the sub-chunk's start, is taken out of the diagonal tile's column operand and is
+// added back exactly, pair by pair, in fp32.
 #include <stdlib.h>
 #include <type_traits>
 
@@ -44,7 +48,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr float kStrongLog2 = 11.0f;   // sub-chunk decay below 2^-11 leaves the fast operands
+constexpr float kStrongLog2 = 18.0f;   // sub-chunk decay below 2^-18 leaves the fast operands
 constexpr float kRowScale = 16.0f;     // keeps small row operands out of the fp16 subnormals
 
 // ----------------------------------------------------------------------------------
@@ -59,8 +63,8 @@ constexpr int kLdM = 72;                                // halfs per row of a [6
 constexpr int kTileM = 64 * kLdM * 2;                   // 9216 B
 
 constexpr int kX = 0;                                   // fp32 (I + L)^-1
-constexpr int kTab = kX;                                //   early alias: per-channel constants, 5 x [4][128] fp32
-constexpr int kFix = kTab + 5 * 2048;                   //   early alias: scratch of the strong-channel fix-up
+constexpr int kTab = kX;                                //   early alias: per-channel constants, 7 x [4][128] fp32
+constexpr int kFix = kTab + 7 * 2048;                   //   early alias: scratch of the strong-channel fix-up
 constexpr int kL = kX + kTileF;                         // fp32 L = StrictTril(Diag(beta) A_kk)
 constexpr int kAq = kL + kTileF;                        // fp16 Tril(A_qk)
 constexpr int kColS = kL;                               //   early alias: column operands [6 tiles][4][64] x 16 B
@@ -75,6 +79,9 @@ constexpr int kIntraLds = kStrong + 64;
 static_assert(kFix + 4 * 4 * 16 * 3 * 4 <= kL, "early aliases must fit under X");
 static_assert(kColS + 6 * 4 * 64 * 16 <= kGK, "early aliases must fit under L and A_qk");
 static_assert(kIntraLds <= 80 * 1024, "kda_intra must leave room for two workgroups per CU");
+
+// Half of a sub-chunk's log2 decay `tot` (<= 0), as a non-negative shift; 0 for a strong channel.
+__device__ __forceinline__ float half_shift(float tot) { return (tot < -kStrongLog2) ? 0.f : -0.5f * tot; }
 
 __device__ __forceinline__ uint32_t pack_h2(float a, float b)
 {
@@ -170,7 +177,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     float *sTot = reinterpret_cast<float *>(lds + kTot);
     float *sBeta = reinterpret_cast<float *>(lds + kBeta);
     uint32_t *sStrong = reinterpret_cast<uint32_t *>(lds + kStrong);
-    float *sTab = reinterpret_cast<float *>(lds + kTab);     // [5][4][128]: P, E, Tinv, iA, iB
+    float *sTab = reinterpret_cast<float *>(lds + kTab);     // [7][4][128]: P, E, Tinv, iA, iB, shifted total, row shift
 
     const int R = wave, m = lane & 15, g = lane >> 4;
     const int tok = 16 * R + m;
@@ -273,13 +280,22 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             if (J < R) { pre0 += t0[J]; pre1 += t1[J]; }
             if (J > R) { post0 += t0[J]; post1 += t1[J]; }
         }
-        const int r1 = (R + 1) & 3, r2 = (R + 2) & 3;        // R+1, R+2 (only used when they exist)
+        // r1..r3 = R+1..R+3 (only used when they exist).  sh: the half-decay shift carried by the row
+        // operands of sub-chunk R; the column operands of a tile (Rp, R) undo the shift of Rp.  The
+        // column base value already undoes the shift of R+1 (n1), so the other constants put it back.
+        const int r1 = (R + 1) & 3, r2 = (R + 2) & 3, r3 = (R + 3) & 3;
+        const float sh0 = half_shift(t0[R]), sh1 = half_shift(t1[R]);
+        const float n10 = (R < 3) ? half_shift(t0[r1]) : 0.f, n11 = (R < 3) ? half_shift(t1[r1]) : 0.f;
         float *tb = sTab + R * 128 + c2;
-        *reinterpret_cast<float2 *>(tb + 0 * 512) = make_float2(fast_exp2(pre0), fast_exp2(pre1));
-        *reinterpret_cast<float2 *>(tb + 1 * 512) = make_float2(fast_exp2(post0), fast_exp2(post1));
-        *reinterpret_cast<float2 *>(tb + 2 * 512) = make_float2(fast_exp2(-t0[R]), fast_exp2(-t1[R]));
-        *reinterpret_cast<float2 *>(tb + 3 * 512) = make_float2(fast_exp2(t0[r1]), fast_exp2(t1[r1]));
-        *reinterpret_cast<float2 *>(tb + 4 * 512) = make_float2(fast_exp2(t0[r1] + t0[r2]), fast_exp2(t1[r1] + t1[r2]));
+        *reinterpret_cast<float2 *>(tb + 0 * 512) = make_float2(fast_exp2(pre0 - sh0), fast_exp2(pre1 - sh1));
+        *reinterpret_cast<float2 *>(tb + 1 * 512) = make_float2(fast_exp2(post0 + n10), fast_exp2(post1 + n11));
+        *reinterpret_cast<float2 *>(tb + 2 * 512) = make_float2(fast_exp2(-t0[R] - sh0 + n10), fast_exp2(-t1[R] - sh1 + n11));
+        *reinterpret_cast<float2 *>(tb + 3 * 512) = make_float2(fast_exp2(t0[r1] - half_shift(t0[r2]) + n10),
+                                                                fast_exp2(t1[r1] - half_shift(t1[r2]) + n11));
+        *reinterpret_cast<float2 *>(tb + 4 * 512) = make_float2(fast_exp2(t0[r1] + t0[r2] - half_shift(t0[r3]) + n10),
+                                                                fast_exp2(t1[r1] + t1[r2] - half_shift(t1[r3]) + n11));
+        *reinterpret_cast<float2 *>(tb + 5 * 512) = make_float2(t0[R] + sh0 - n10, t1[R] + sh1 - n11);
+        *reinterpret_cast<float2 *>(tb + 6 * 512) = make_float2(sh0, sh1);
         if (R == 0) {   // gamma^C: decay of the whole chunk
             float2 gc = make_float2(fast_exp2(t0[0] + t0[1] + t0[2] + t0[3]), fast_exp2(t1[0] + t1[1] + t1[2] + t1[3]));
             slot_store8<kPolicy>(out, kOffGc + c2 * 4, gc);
@@ -293,6 +309,15 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     }
     const uint32_t strong_mine = sStrong[R * 4 + g];
     __syncthreads();                                                               // B2
+
+    // the row shift goes into G once (a strong channel's shift is 0, so the fix-up below still sees
+    // its plain running sums)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const f32x4 x = *reinterpret_cast<const f32x4 *>(sTab + 6 * 512 + R * 128 + 32 * (i >> 1) + 8 * g + 4 * (i & 1));
+#pragma unroll
+        for (int z = 0; z < 4; ++z) G[4 * i + z] += x[z];
+    }
 
     // ---- operands, built in registers ----
     h8 rowK[4], rowQ[4], colKd[4];
@@ -312,12 +337,13 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         float tot[8], P[8], E[8], Ti[8], iA[8], iB[8];
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
-            const f32x4 a = *reinterpret_cast<const f32x4 *>(sTot + cb + 4 * hf);
+            const f32x4 a = *reinterpret_cast<const f32x4 *>(sTab + 5 * 512 + cb + 4 * hf);
             const f32x4 b = *reinterpret_cast<const f32x4 *>(sTab + 0 * 512 + cb + 4 * hf);
             const f32x4 c = *reinterpret_cast<const f32x4 *>(sTab + 1 * 512 + cb + 4 * hf);
             const f32x4 d = *reinterpret_cast<const f32x4 *>(sTab + 2 * 512 + cb + 4 * hf);
 #pragma unroll
             for (int z = 0; z < 4; ++z) { tot[4 * hf + z] = a[z]; P[4 * hf + z] = b[z]; E[4 * hf + z] = c[z]; Ti[4 * hf + z] = d[z]; }
+
             if (R <= 1) {
                 const f32x4 x = *reinterpret_cast<const f32x4 *>(sTab + 3 * 512 + cb + 4 * hf);
 #pragma unroll
@@ -333,13 +359,13 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float Ge = G[ks * 8 + e];
-            const float rf = fast_exp2(Ge);                       // 2^(G_r - G_ref(R)), <= 1
-            const float sf = fast_exp2(tot[e] - Ge);              // decay from this token to the end of R
+            const float rf = fast_exp2(Ge);                       // 2^(G_r + D/2): within 2^(+-D/2)
+            const float sf = fast_exp2(tot[e] - Ge);              // decay from this token to the end of R, less the shift of R+1
             const bool strong = (strong_mine >> (ks * 8 + e)) & 1u;
             rk[e] = kf[e] * rf * kRowScale;
             rq[e] = qf[e] * rf * kRowScale;
             cs[e] = kf[e] * sf;
-            cd[e] = strong ? 0.f : cs[e] * Ti[e];                 // k 2^(-G_i)
+            cd[e] = strong ? 0.f : cs[e] * Ti[e];                 // k 2^(-G_i - D/2)
             gk[e] = kf[e] * rf * P[e];                            // Gamma . K
             qp[e] = qf[e] * rf * (P[e] * scale);                  // scale * Gamma . Q
             kp[e] = cs[e] * E[e];                                 // Gamma^{i->C} . K
