@@ -109,7 +109,9 @@ size_t kda_chunk_fwd_min_workspace_size(const kda_dims *dims);
  *                              when the required size is 0)
  * o must not alias any input.  Arithmetic: KDA_F32 inputs are processed in fp32
  * throughout; KDA_BF16 inputs use fp16 matrix-core operands with fp32
- * accumulation, fp32 cumulative decay and an fp32 state.
+ * accumulation, fp32 cumulative decay and an fp32 state.  Domain of the KDA_BF16
+ * path: entries of q and k within +-3.9 (the paper's q and k are L2-normalised,
+ * Section 4), and states and values small enough for fp16 (below 65504).
  */
 kda_status kda_chunk_fwd(const kda_dims *dims,
                          const void *q, const void *k, const void *v,

@@ -48,8 +48,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr float kStrongLog2 = 18.0f;   // sub-chunk decay below 2^-18 leaves the fast operands
-constexpr float kRowScale = 16.0f;     // keeps small row operands out of the fp16 subnormals
+constexpr float kStrongLog2 = 24.0f;   // sub-chunk decay below 2^-24 leaves the fast operands
+constexpr float kRowScale = 4.0f;      // keeps small row operands out of the fp16 subnormals
 
 // ----------------------------------------------------------------------------------
 // LDS map of kda_intra (bytes).  Regions are reused as the phases advance; the whole
