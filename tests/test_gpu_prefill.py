@@ -189,3 +189,15 @@ def test_bf16_random_shapes_and_layouts(seed):
         desc = "packed lens=%s" % lens.tolist()
     eo, eh = check_prefill(x, TOL_BF16, scale=scale)
     print("random %d: %s H=%d mu=%.1f h0=%.2f scale=%.3f: err_o %.2e err_hT %.2e" % (seed, desc, H, mu, h0_std, scale, eo, eh))
+
+
+def test_bf16_decay_ladder_across_the_exact_path_threshold():
+    """Channels with a fixed decay per token, chosen so that the decay over a 16-token sub-chunk is
+    2^-D for D = 0 ... 48 in steps of 1.5: below D = 24 the half-decay split keeps them in the fp16
+    operands, above it they take the exact fp32 path; both sides and the threshold itself are hit."""
+    x = si.make_prefill(2, 300, 2, 128, 128, "bf16", -2.0, 77, 0.02)
+    D = torch.arange(128, dtype=torch.float32) % 33 * 1.5                       # 0, 1.5, ..., 48
+    per_token = -(D / 16.0) * float(np.log(2.0))
+    x["log_alpha"] = per_token.view(1, 1, 1, 128).expand(2, 300, 2, 128).contiguous().to(torch.bfloat16)
+    eo, eh = check_prefill(x, TOL_BF16)
+    print("bf16 decay ladder: err_o %.2e err_hT %.2e" % (eo, eh))
