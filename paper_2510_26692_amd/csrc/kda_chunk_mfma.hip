@@ -693,9 +693,12 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 // O.  A chunk therefore costs each wave 26-28 MFMAs (32x32x16) instead of 54, at the price of two
 // exchanges through LDS per chunk: the fp16 copies of S (every wave needs all four d_k tiles as
 // an operand) and of V_new (both token tiles).  All other operands stream from the LDS copy of the
-// workspace slot, which the eight waves refill for the next chunk with LDS-direct loads while
-// the current chunk computes.  O is accumulated transposed (operands swapped), so a lane owns four
-// consecutive output columns and stores 16 bytes at a time.
+// workspace slot.  The slot of chunk c + 2 is fetched into registers while chunk c computes and
+// written to the other LDS stage at the end of chunk c + 1, so a fetch has two full steps to
+// arrive.  O is accumulated transposed (operands swapped), so a lane owns four consecutive output
+// columns and stores 16 bytes at a time.  Two optional features are compiled in per template
+// flag: slots produced by a kda_intra that runs at the same time (kFlags) and the output gate
+// (kEpi).
 #define KDA_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 namespace scan {
