@@ -666,9 +666,11 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 slot_store16<kPolicy>(out, kOffWn + frag_rts(rho, wave, s) * kFragBytes + lane * 16, o4);
             }
 #pragma unroll
-            for (int j4 = 0; j4 < 4; ++j4) {
-                f32x4 o4 = {u[4 * j4], u[4 * j4 + 1], u[4 * j4 + 2], u[4 * j4 + 3]};
-                slot_store16<kPolicy>(out, kOffU + (((rho * 4 + wave) * 4 + j4) * 64 + lane) * 16, o4);
+            for (int j2 = 0; j2 < 2; ++j2) {            // U as fp16: kda_scan rounds V_new = U - W S to fp16 anyway
+                u32x4 o4;
+#pragma unroll
+                for (int z = 0; z < 4; ++z) o4[z] = pack_h2(u[8 * j2 + 2 * z], u[8 * j2 + 2 * z + 1]);
+                slot_store16<kPolicy>(out, kOffU + (rho * 4 + wave) * kUTileBytes + (j2 * 64 + lane) * 16, o4);
             }
         }
     }
@@ -794,10 +796,10 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
         // step ci, so that a fetch has two full steps to complete.  Thread tid moves the 16-byte
         // units tid, tid + 512, ...; the wave's U tile (P, c) travels the same way.
         constexpr int kMyUnits = (kUnits + 511) / 512;
-        const uint32_t u_src = (uint32_t)(kOffU + (P * 4 + c) * 4096) + lane16;   // U tile (P, c): 4 x 1 KiB
+        const uint32_t u_src = (uint32_t)(kOffU + (P * 4 + c) * kUTileBytes) + lane16;   // U tile (P, c): 2 x 1 KiB
         u32x4 pre[2][kMyUnits];
-        f32x4 un[2][4];
-        auto fetch = [&](const uint8_t *src, u32x4 *blk, f32x4 *u) __attribute__((always_inline)) {
+        u32x4 un[2][2];
+        auto fetch = [&](const uint8_t *src, u32x4 *blk, u32x4 *u) __attribute__((always_inline)) {
             const __amdgpu_buffer_rsrc_t rs = slot_resource(src);
             if (kFlags) {    // the slot was written while this kernel runs: device-scope loads
 #pragma unroll
@@ -806,8 +808,7 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                     if (unit < kUnits) blk[i] = slot_load16<kCacheDevice>(rs, unit * 16);
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    u[i] = __builtin_bit_cast(f32x4, slot_load16<kCacheDevice>(rs, (int)u_src + i * 1024));
+                for (int i = 0; i < 2; ++i) u[i] = slot_load16<kCacheDevice>(rs, (int)u_src + i * 1024);
             } else {
 #pragma unroll
                 for (int i = 0; i < kMyUnits; ++i) {
@@ -815,7 +816,7 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                     if (unit < kUnits) blk[i] = slot_load16<0>(rs, unit * 16);
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) u[i] = __builtin_bit_cast(f32x4, slot_load16<0>(rs, (int)u_src + i * 1024));
+                for (int i = 0; i < 2; ++i) u[i] = slot_load16<0>(rs, (int)u_src + i * 1024);
             }
         };
         auto publish = [&](const u32x4 *blk, int stage) __attribute__((always_inline)) {
@@ -875,9 +876,14 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
 
             f32x16 av, ao = {0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int z = 0; z < 4; ++z) av[4 * i + z] = un[stage][i][z];
+                for (int z = 0; z < 4; ++z) {
+                    const uint32_t w2 = un[stage][i][z];     // (a copy first: bit_cast straight from a vector element misreads it)
+                    const h2 pr = __builtin_bit_cast(h2, w2);
+                    av[8 * i + 2 * z] = (float)pr[0];
+                    av[8 * i + 2 * z + 1] = (float)pr[1];
+                }
             // this register set is free now: start fetching chunk ci + 2 into it
             // kEpi: gate logits of this lane's 16 outputs (token 32 P + x, columns 32 c + 8 q + 4 hh + 0..3).
             // They go out before the slot loads of chunk ci + 2: loads return in order, and these are

@@ -10,7 +10,7 @@
 //   Kt   (Gamma^{i->C}.K)^T  A operand [dk][token]  frags [tau][rho][s]      fp16
 //   Aqk  Tril(A_qk)    A operand [token r][token i] frags (0,0,s) (1,0,s) (1,1,s) fp16
 //   gC   gamma^C       [dk]                                                  fp32
-//   U                  C/D tiles [rho][ct] in accumulator order              fp32
+//   U                  C/D tiles [rho][ct] in accumulator order              fp16
 //
 // rho: 32-token tile, tau: 32-channel d_k tile, ct: 32-column d_v tile, s: one
 // K-step of 16.  A "frag" is 64 lanes x 8 halfs (1 KiB); lane L = (x = L % 32,
@@ -40,8 +40,9 @@ constexpr int kOffKt = kOffQp + 16 * kFragBytes;
 constexpr int kOffAqk = kOffKt + 16 * kFragBytes;   // 6 frags: token tile (0,1) of Tril(A_qk) is zero
 constexpr int kOffGc = kOffAqk + 6 * kFragBytes;
 constexpr int kLdsBlockBytes = kOffGc + D * 4;      // what kda_scan stages through LDS
-constexpr int kOffU = kLdsBlockBytes;               // 8 tiles x 4 KiB
-constexpr int kSlotBytes = kOffU + 8 * 4096;        // 88576
+constexpr int kUTileBytes = 64 * 16 * 2;            // one 32x32 tile of U: 16 halfs per lane, two 16-byte units
+constexpr int kOffU = kLdsBlockBytes;               // 8 tiles x 2 KiB
+constexpr int kSlotBytes = kOffU + 8 * kUTileBytes; // 72192
 
 static_assert(kLdsBlockBytes % 16 == 0, "LDS block must be a whole number of 16-byte units");
 static_assert(kSlotBytes % 256 == 0, "slots must stay 256-byte aligned");

@@ -53,7 +53,7 @@ def test_workspace_sizes_are_consistent():
     assert full > small > 0 and full % 256 == 0
     # slots + one ready flag per slot, the fp32 state carry, the status word (with alignment slack)
     slots = 4 * 16 * (4096 // 64)
-    fixed = full - slots * (88576 + 4) - 4 * 16 * 128 * 128 * 4
+    fixed = full - slots * (72192 + 4) - 4 * 16 * 128 * 128 * 4
     assert 256 <= fixed <= 512
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, in_dtype=0)) == 0          # fp32 path
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, dk=96, dv=96)) == 0        # unsupported
