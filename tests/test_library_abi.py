@@ -123,3 +123,18 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libkda.so")
     with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
         binding.load_library()
+
+
+def test_bench_flop_model_matches_the_papers_formula():
+    """bench.py's FLOP-per-token constant against the hand-evaluated values of the paper's
+    formula (Section 6.3, "Training flops") stored in tests/golden/flops_model.txt."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_mod", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    rows = [tuple(int(x) for x in ln.split()) for ln in open(os.path.join(ROOT, "tests", "golden", "flops_model.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    assert rows
+    for T, C, d, flops in rows:
+        assert 6 * T * d * d + 3 * T * C * d + T * C * C == flops
+    assert (1, 64, 128, bench.FLOP_PER_TOKHEAD) in rows
