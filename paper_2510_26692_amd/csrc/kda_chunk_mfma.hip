@@ -593,12 +593,20 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     {
         const float *sX = reinterpret_cast<const float *>(lds + kX);
         _Float16 *sM = reinterpret_cast<_Float16 *>(lds + kM);
-        for (int idx = tid; idx < 64 * 64; idx += 256) {
-            const int r = idx >> 6, j = idx & 63;
-            float val = 0.f;
-            if (j < r) val = sX[r * kLdF + j] * sBeta[j];
-            else if (j == r) val = sBeta[j];
-            sM[r * kLdM + j] = (_Float16)val;
+        // four consecutive columns per thread and pass: 16-byte reads, 8-byte writes
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int idx = tid + 256 * pass, r = idx >> 4, j0 = 4 * (idx & 15);
+            const f32x4 xr = *reinterpret_cast<const f32x4 *>(sX + r * kLdF + j0);
+            const f32x4 br = *reinterpret_cast<const f32x4 *>(sBeta + j0);
+            float val[4];
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const int j = j0 + z;
+                val[z] = (j < r) ? xr[z] * br[z] : ((j == r) ? br[z] : 0.f);
+            }
+            u32x2 w2 = {pack_h2(val[0], val[1]), pack_h2(val[2], val[3])};
+            *reinterpret_cast<u32x2 *>(sM + r * kLdM + j0) = w2;
         }
         const int x = lane & 31, hh = lane >> 5;
         for (int idx = wave; idx < 6; idx += 4) {
