@@ -45,6 +45,14 @@ static int overlap_default()
     return (e && e[0] == '0' && e[1] == 0) ? 0 : 1;
 }
 int g_overlap = overlap_default();
+// 0 keeps the sequential kernel to one workgroup per (sequence, head) whatever the shape
+// (kda_debug_set_time_split, or KDA_PREFILL_TIME_SPLIT=0 in the environment).
+static int split_default()
+{
+    const char *e = getenv("KDA_PREFILL_TIME_SPLIT");
+    return (e && e[0] == '0' && e[1] == 0) ? 0 : 1;
+}
+int g_split = split_default();
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -94,6 +102,8 @@ const char *kda_version(void) { return "kda-gfx950 0.1"; }
 void kda_debug_set_phase_mask(int mask) { g_phase_mask = mask & 3; }
 
 void kda_debug_set_overlap(int enabled) { g_overlap = enabled ? 1 : 0; }
+
+void kda_debug_set_time_split(int enabled) { g_split = enabled ? 1 : 0; }
 
 const char *kda_last_error(void) { return g_last_error; }
 

@@ -38,6 +38,7 @@ namespace kda {
 
 extern int g_phase_mask;   // diagnostics switches owned by kda_api.hip
 extern int g_overlap;
+extern int g_split;
 
 namespace mfma {
 
@@ -151,7 +152,8 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
                       const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
                       uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
-                      int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch, RawParams raw)
+                      int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch, RawParams raw,
+                      int parts, int part_len)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -163,7 +165,15 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // otherwise y = chunk and z = sequence (consecutive workgroups write consecutive slots).
     const int h = (int)blockIdx.x;
     const int n = (int)(kHandoff ? blockIdx.y : blockIdx.z);
-    const int64_t cl = kHandoff ? blockIdx.z : blockIdx.y;
+    // (when the scan is time-split into `parts` ranges of `part_len` chunks, its first pass walks
+    // all ranges but the last side by side, so the chunk order interleaves those and lets the last
+    // range follow)
+    int64_t cl = kHandoff ? blockIdx.z : blockIdx.y;
+    if (kHandoff && parts > 1) {
+        const unsigned first = (unsigned)(parts - 1), z = blockIdx.z;
+        if (z < first * (unsigned)part_len) cl = (int64_t)(z % first) * part_len + z / first;
+    }
+    if (cl >= seg_chunks) return;
     const int64_t slot = n * seg_chunks + cl;
     const int64_t ci = seg_index * seg_chunks + cl;
     int64_t tok_base, len;
@@ -774,7 +784,14 @@ struct EpiParams {
     float eps;
 };
 
-template <int P, bool kFlags, bool kEpi>
+// kRole selects what one pass over a range of chunks computes (the time-split scan below):
+//   kRoleFull   the scan itself: state from state_in (zero if NULL), outputs written
+//   kRoleT      the d_k x d_k transition of the range: starts from the identity, drops U (the
+//               recurrence is affine in the state: S_out = T S_in + B), writes no output
+//   kRoleB      the offset of the range: starts from zero, keeps U, writes no output
+constexpr int kRoleFull = 0, kRoleT = 1, kRoleB = 2;
+
+template <int P, bool kFlags, bool kEpi, int kRole = kRoleFull>
 __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
                                               const float *state_in, float *state_out, float *o,
                                               int64_t st_base, int64_t tok_base, int64_t len, int H,
@@ -796,7 +813,12 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int j = 0; j < 16; ++j)
-            S[t][j] = state_in ? state_in[st_base + (int64_t)(32 * (2 * P + t) + acc_row(j, hh)) * D] : 0.f;
+        {
+            const int row = 32 * (2 * P + t) + acc_row(j, hh);
+            if (kRole == kRoleT)      S[t][j] = (row == 32 * (wave & 3) + (lane & 31)) ? 1.f : 0.f;
+            else if (kRole == kRoleB) S[t][j] = 0.f;
+            else                      S[t][j] = state_in ? state_in[st_base + (int64_t)row * D] : 0.f;
+        }
 
     if (c_begin < c_end) {
         // Workspace slot -> LDS: the block of chunk ci is fetched into registers two steps ahead
@@ -849,8 +871,10 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
         }
         // (the flag load goes out before the slot loads: loads return in order, so the check of
         // `seen` one step later must not have to wait for a whole slot fetch that was issued first)
-        if (poll && c_begin + 2 < c_end)
-            seen = __hip_atomic_load(ready + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (kFlags) {
+            const int64_t cf = (c_begin + 2 < c_end) ? 2 : c_end - 1 - c_begin;
+            seen = __hip_atomic_load(ready + cf, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         fetch(slot0, pre[0], un[0]);
         if (c_begin + 1 < c_end) fetch(slot0 + slot_stride, pre[1], un[1]);
         publish(pre[0], 0);
@@ -889,8 +913,8 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 for (int z = 0; z < 4; ++z) {
                     const uint32_t w2 = un[stage][i][z];     // (a copy first: bit_cast straight from a vector element misreads it)
                     const h2 pr = __builtin_bit_cast(h2, w2);
-                    av[8 * i + 2 * z] = (float)pr[0];
-                    av[8 * i + 2 * z + 1] = (float)pr[1];
+                    av[8 * i + 2 * z] = (kRole == kRoleT) ? 0.f : (float)pr[0];
+                    av[8 * i + 2 * z + 1] = (kRole == kRoleT) ? 0.f : (float)pr[1];
                 }
             // this register set is free now: start fetching chunk ci + 2 into it
             // kEpi: gate logits of this lane's 16 outputs (token 32 P + x, columns 32 c + 8 q + 4 hh + 0..3).
@@ -906,8 +930,12 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                     gate_raw[q4] = (trow < len) ? *reinterpret_cast<const u32x2 *>(gp + 8 * q4) : z2;
                 }
             }
-            if (poll && ci + 3 < c_end)
-                seen = __hip_atomic_load(ready + (ci + 3 - c_begin), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // (every lane loads the flag, unconditionally and past the end clamped to the last chunk:
+            // a fixed number of loads in flight lets the check wait for exactly this one)
+            if (kFlags) {
+                const int64_t cf = (ci + 3 < c_end) ? ci + 3 : c_end - 1;
+                seen = __hip_atomic_load(ready + (cf - c_begin), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
             // (issued unconditionally, past the end the last slot is simply fetched again: with a
             // fixed number of loads in flight behind them, earlier loads can be waited for one by one)
             {
@@ -956,7 +984,8 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                     }
                 } else if constexpr (i < 16) {
                     // O^T = S^T (Gamma.Q)^T
-                    ao = __builtin_amdgcn_mfma_f32_32x32x16_f16(Sb[(i - 8) / 2][(i - 8) % 2], a, ao, 0, 0, 0);
+                    if constexpr (kRole == kRoleFull)
+                        ao = __builtin_amdgcn_mfma_f32_32x32x16_f16(Sb[(i - 8) / 2][(i - 8) % 2], a, ao, 0, 0, 0);
                     if constexpr (i == 10 || i == 12) {
                         // S <- Diag(gamma^C) S on the own tiles (their fp16 copies are taken)
                         constexpr int t = (i - 10) / 2;
@@ -980,7 +1009,8 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 } else {
                     // O^T += V_new^T Tril(A_qk)^T
                     constexpr int j = i - 24;
-                    ao = __builtin_amdgcn_mfma_f32_32x32x16_f16(Vb[j / 2][j % 2], a, ao, 0, 0, 0);
+                    if constexpr (kRole == kRoleFull)
+                        ao = __builtin_amdgcn_mfma_f32_32x32x16_f16(Vb[j / 2][j % 2], a, ao, 0, 0, 0);
                 }
                 KDA_FENCE();   // keeps each operand read LA slots ahead of its MFMA
             });
@@ -1005,7 +1035,7 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 for (int j = 0; j < 16; ++j) ao[j] *= rstd * sg[j];
             }
             // write O (fp32, already scaled): 16 bytes per store
-            {
+            if (kRole == kRoleFull) {
                 const int64_t t0 = ci * kChunk;
                 uint8_t *obase = reinterpret_cast<uint8_t *>(o + ((tok_base + t0) * H + h) * (int64_t)D);
                 if (t0 + 32 * P + x < len) {
@@ -1071,6 +1101,114 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
                                        c_begin, c_end, h, flag0, epoch, status, epi);
 }
 
+// Time-split scan for few (sequence, head) pairs: the chunk axis is cut into `parts` ranges of
+// `part_len` chunk indices, and several workgroups work on one pair at a time.
+//   pass 0: blockIdx.y = 0 scans range 0 from h0 (outputs and all) and leaves its final state in
+//           E[0]; blockIdx.y = 1 + 2 (p - 1) + r computes, for range p = 1 .. parts - 2, the
+//           transition T_p (r = 0) or the offset B_p (r = 1) of that range.
+//   (kda_combine_kernel then forms E[p] = T_p E[p-1] + B_p, the state at the end of range p.)
+//   pass 1: blockIdx.y = p - 1 scans range p = 1 .. parts - 1 from E[p-1]; the last range also
+//           delivers the final state.
+// E, Tm, Bm: arrays of [pairs][128][128] fp32 states, one per range.
+template <bool kFlags>
+__global__ __launch_bounds__(512)
+void kda_scan_part_kernel(const uint8_t *__restrict__ ws, const float *h0, float *E, float *Tm, float *Bm,
+                          float *state_final, const int32_t *__restrict__ cu_seqlens, float *__restrict__ o,
+                          int64_t T, int H, int64_t seg_chunks, int64_t part_len, int parts, int pass,
+                          const uint32_t *ready, uint32_t epoch, uint32_t *status)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = blockIdx.x / H, h = blockIdx.x % H;
+    const int64_t pair_states = (int64_t)gridDim.x * (D * D);
+
+    int64_t tok_base, len;
+    if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
+    else            { tok_base = (int64_t)n * T; len = T; }
+    const int64_t nchunks = (len + kChunk - 1) / kChunk;
+
+    int part, role;
+    const float *state_in = nullptr;
+    float *state_out = nullptr;
+    if (pass == 0) {
+        if (blockIdx.y == 0) { part = 0; role = kRoleFull; state_in = h0; state_out = E; }
+        else {
+            part = 1 + ((int)blockIdx.y - 1) / 2;
+            role = (((int)blockIdx.y - 1) & 1) ? kRoleB : kRoleT;
+            state_out = (role == kRoleT ? Tm : Bm) + part * pair_states;
+        }
+    } else {
+        part = (int)blockIdx.y + 1; role = kRoleFull;
+        state_in = E + (part - 1) * pair_states;
+        state_out = (part == parts - 1) ? state_final : nullptr;
+    }
+    int64_t c_begin = part * part_len, c_end = c_begin + part_len;
+    if (c_begin > nchunks) c_begin = nchunks;
+    if (c_end > nchunks) c_end = nchunks;
+
+    const int64_t st_base = ((int64_t)n * H + h) * (int64_t)(D * D) + 32 * (wave & 3) + (lane & 31);
+    const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kSlotBytes;
+    const int64_t slot_stride = (int64_t)H * kSlotBytes;
+    const uint32_t *flag0 = kFlags ? ready + (int64_t)blockIdx.x * seg_chunks + c_begin : nullptr;
+    if (!kFlags && status && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *status = 0;
+    const EpiParams no_epi = {nullptr, nullptr, 0.f};
+
+#define KDA_SCAN_PART(ROLE)                                                                                       \
+    if (wave < 4)                                                                                                 \
+        kda_scan_body<0, kFlags, false, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,  \
+                                              len, H, c_begin, c_end, h, flag0, epoch, status, no_epi);           \
+    else                                                                                                          \
+        kda_scan_body<1, kFlags, false, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,  \
+                                              len, H, c_begin, c_end, h, flag0, epoch, status, no_epi)
+    if (role == kRoleFull) { KDA_SCAN_PART(kRoleFull); }
+    else if (role == kRoleT) { KDA_SCAN_PART(kRoleT); }
+    else { KDA_SCAN_PART(kRoleB); }
+#undef KDA_SCAN_PART
+}
+
+// E[p] = T_p E[p-1] + B_p for p = 1 .. parts - 2, in fp32.  One workgroup per (pair, 32-column
+// tile of the state); thread (ty, tx) owns rows 4 ty .. 4 ty + 3 and columns 4 tx .. 4 tx + 3 of the
+// tile, the current E tile sits in LDS.
+__global__ __launch_bounds__(256)
+void kda_combine_kernel(float *E, const float *__restrict__ Tm, const float *__restrict__ Bm, int parts)
+{
+    __shared__ float sE[D][32];
+    const int tid = threadIdx.x, ty = tid >> 3, tx = tid & 7;
+    const int64_t pair_states = (int64_t)gridDim.x * (D * D);
+    const int64_t base = (int64_t)blockIdx.x * (D * D) + 32 * blockIdx.y;
+    for (int i = tid; i < D * 8; i += 256)
+        *reinterpret_cast<f32x4 *>(&sE[i >> 3][4 * (i & 7)]) =
+            *reinterpret_cast<const f32x4 *>(E + base + (int64_t)(i >> 3) * D + 4 * (i & 7));
+    __syncthreads();
+    for (int p = 1; p <= parts - 2; ++p) {
+        const float *Tp = Tm + p * pair_states + (int64_t)blockIdx.x * (D * D);
+        const float *Bp = Bm + p * pair_states + base;
+        f32x4 acc[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = *reinterpret_cast<const f32x4 *>(Bp + (int64_t)(4 * ty + i) * D + 4 * tx);
+        for (int k4 = 0; k4 < D / 4; ++k4) {
+            f32x4 a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const f32x4 *>(Tp + (int64_t)(4 * ty + i) * D + 4 * k4);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) b[kk] = *reinterpret_cast<const f32x4 *>(&sE[4 * k4 + kk][4 * tx]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                    for (int z = 0; z < 4; ++z) acc[i][z] = fmaf(a[i][kk], b[kk][z], acc[i][z]);
+        }
+        __syncthreads();                                     // every thread is done reading the old tile
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<f32x4 *>(&sE[4 * ty + i][4 * tx]) = acc[i];
+            *reinterpret_cast<f32x4 *>(E + p * pair_states + base + (int64_t)(4 * ty + i) * D + 4 * tx) = acc[i];
+        }
+        __syncthreads();
+    }
+}
+
 // flags and status word of the overlapped mode start every call at zero
 __global__ void kda_fill_u32_kernel(uint32_t *p, int64_t n, uint32_t value)
 {
@@ -1104,8 +1242,25 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc)
     p.carry_offset = (size_t)sc * streams * kSlotBytes;
     p.flags_offset = p.carry_offset + carry;
     p.status_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
-    p.total_bytes = p.status_offset + 256;
+    p.split_offset = p.status_offset + 256;
+    // the states of the time-split scan, when the call qualifies for it (single segment only)
+    const bool split = sc == maxc && streams <= (size_t)kSplitMaxPairs && maxc >= kSplitMinChunks;
+    p.total_bytes = p.split_offset + (split ? 3 * (size_t)kSplitMaxParts * carry : 0);
     return p;
+}
+
+// Number of ranges for the time-split scan (1 = plain scan).  Pass 0 keeps 2 parts - 3 compute
+// units per pair busy; at most half of the device is given to it, so that kda_intra, which runs
+// beside it, keeps the other half.
+static int split_parts(const SegPlan &plan, const kda_dims *d, int cus)
+{
+    const int64_t maxc = max_chunks_per_seq(d);
+    const int64_t pairs = (int64_t)d->num_seqs * d->heads;
+    if (plan.num_segments != 1 || pairs > kSplitMaxPairs || maxc < kSplitMinChunks) return 1;
+    int parts = 1;
+    for (int p = 3; p <= kSplitMaxParts; ++p)
+        if (pairs * (2 * p - 3) * 2 <= cus && (maxc + p - 1) / p >= 16) parts = p;
+    return parts;
 }
 
 // The plan with the most chunk indices per segment that fits `workspace_bytes` (full: no limit).
@@ -1152,6 +1307,10 @@ static bool reserve_lds()
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_part_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_part_kernel<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess;
     if (!ok) (void)hipGetLastError();
     done[dev] = ok;
@@ -1163,9 +1322,23 @@ static bool reserve_lds()
 struct SideStream {
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
-    int compute_units = 0;
     bool tried = false, ok = false;
 };
+
+// Compute units of the current device (cached per device), 0 on failure.
+static int compute_units()
+{
+    constexpr int kMaxDevices = 64;
+    static int table[kMaxDevices];                          // 0 = not asked yet; same value from every thread
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    if (table[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { n = 0; (void)hipGetLastError(); }
+        table[dev] = n;
+    }
+    return table[dev];
+}
 
 static SideStream *side_stream()
 {
@@ -1176,12 +1349,9 @@ static SideStream *side_stream()
     SideStream *s = &table[dev];
     if (!s->tried) {
         s->tried = true;
-        hipDeviceProp_t prop;
-        s->ok = hipGetDeviceProperties(&prop, dev) == hipSuccess &&
-                hipStreamCreateWithFlags(&s->stream, hipStreamNonBlocking) == hipSuccess &&
+        s->ok = hipStreamCreateWithFlags(&s->stream, hipStreamNonBlocking) == hipSuccess &&
                 hipEventCreateWithFlags(&s->fork, hipEventDisableTiming) == hipSuccess &&
                 hipEventCreateWithFlags(&s->join, hipEventDisableTiming) == hipSuccess;
-        if (s->ok) s->compute_units = prop.multiProcessorCount;
         (void)hipGetLastError();
     }
     return s->ok ? s : nullptr;
@@ -1258,15 +1428,56 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     SideStream *side = nullptr;
     hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(stream, &capture) != hipSuccess) { capture = hipStreamCaptureStatusNone; (void)hipGetLastError(); }
+    const int cus = compute_units();
+    if (cus <= 0) return fail(KDA_ERR_LAUNCH, "cannot query the device");
     if (g_phase_mask == 3 && g_overlap && capture == hipStreamCaptureStatusNone) {
         side = side_stream();
-        if (side && (int64_t)streams * 4 > (int64_t)side->compute_units * 3) side = nullptr;
+        if (side && (int64_t)streams * 4 > (int64_t)cus * 3) side = nullptr;
     }
+    const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus) : 1;
 
     if (side) {
         const int64_t nflags = (int64_t)(plan.status_offset - plan.flags_offset) / 4 + 1;   // flags + status
         hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream,
                            flags, nflags, 0u);
+    }
+    if (parts > 1) {
+        // Time-split scan (single segment): pass 0 and kda_intra side by side, the fold of the
+        // per-range transitions, pass 1.
+        const int64_t part_len = (plan.seg_chunks + parts - 1) / parts;
+        const size_t pair_states = (size_t)streams * D * D;
+        float *E = reinterpret_cast<float *>(ws + plan.split_offset);
+        float *Tm = E + kSplitMaxParts * pair_states, *Bm = Tm + kSplitMaxParts * pair_states;
+        auto intra = side ? (pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>)
+                          : (pro ? kda_intra_kernel<false, true> : kda_intra_kernel<false, false>);
+        auto part_k = side ? kda_scan_part_kernel<true> : kda_scan_part_kernel<false>;
+        const dim3 intra_grid_split((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)(parts * part_len));
+        if (side) {
+            if (hipEventRecord(side->fork, stream) != hipSuccess ||
+                hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+                return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
+        } else {
+            hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
+                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale,
+                               (uint32_t *)nullptr, 0u, raw, 1, 0);
+        }
+        hipLaunchKernelGGL(part_k, dim3(streams, (unsigned)(1 + 2 * (parts - 2))), dim3(512), scan_lds, stream, ws, h0, E,
+                           Tm, Bm, (float *)nullptr, cu, static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads,
+                           plan.seg_chunks, part_len, parts, 0, flags, 1u, status);
+        if (side)
+            hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
+                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale, flags, 1u, raw,
+                               parts, (int)part_len);
+        hipLaunchKernelGGL(kda_combine_kernel, dim3(streams, 4), dim3(256), 0, stream, E, Tm, Bm, parts);
+        hipLaunchKernelGGL(part_k, dim3(streams, (unsigned)(parts - 1)), dim3(512), scan_lds, stream, ws, h0, E, Tm, Bm,
+                           hT, cu, static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, part_len,
+                           parts, 1, flags, 1u, status);
+        if (side && (hipEventRecord(side->join, side->stream) != hipSuccess ||
+                     hipStreamWaitEvent(stream, side->join, 0) != hipSuccess))
+            return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));
+        return KDA_OK;
     }
     for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
         const float *sin = (seg == 0) ? h0 : carry;
@@ -1285,7 +1496,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             auto intra = pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>;
             hipLaunchKernelGGL(intra, intra_grid_overlap,
                                dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
-                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw);
+                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw, 1, 0);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
@@ -1294,7 +1505,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             if (g_phase_mask & 1)
                 hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
                                    (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
-                                   (uint32_t *)nullptr, 0u, raw);
+                                   (uint32_t *)nullptr, 0u, raw, 1, 0);
             auto scan_k = epi ? kda_scan_kernel<false, true> : kda_scan_kernel<false, false>;
             if (g_phase_mask & 2)
                 hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,

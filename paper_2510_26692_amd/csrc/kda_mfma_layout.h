@@ -56,6 +56,12 @@ constexpr int frag_rts(int r, int t, int s) { return (r * 4 + t) * 2 + s; }   //
 constexpr int frag_trs(int t, int r, int s) { return (t * 2 + r) * 2 + s; }   // Kt: [tau][rho][s]
 constexpr int frag_aqk(int rr, int ri, int s) { return (rr + ri) * 2 + s; }   // (0,0) (1,0) (1,1)
 
+// Time-split scan: at most this many ranges per sequence, offered to calls with at most this many
+// (sequence, head) pairs whose longest sequence has at least kSplitMinChunks chunks.
+constexpr int kSplitMaxParts = 8;
+constexpr int kSplitMaxPairs = 42;
+constexpr int kSplitMinChunks = 48;
+
 // Geometry of one launch pair: `seg_chunks` chunk indices of every sequence.
 struct SegPlan {
     int64_t seg_chunks;      // chunks per sequence held in the workspace at once
@@ -63,6 +69,7 @@ struct SegPlan {
     size_t carry_offset;     // byte offset of the state carry buffer in the workspace
     size_t flags_offset;     // one u32 "slot ready" flag per (sequence, head, chunk of the segment)
     size_t status_offset;    // u32 set by kda_scan when a bounded wait for a flag ran out
+    size_t split_offset;     // states of the time-split scan: E, T, B, each [kSplitMaxParts][pairs][128][128] fp32
     size_t total_bytes;
 };
 

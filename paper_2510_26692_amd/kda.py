@@ -75,6 +75,8 @@ def load_library():
     lib.kda_debug_set_phase_mask.argtypes = [ctypes.c_int]
     lib.kda_debug_set_overlap.restype = None
     lib.kda_debug_set_overlap.argtypes = [ctypes.c_int]
+    lib.kda_debug_set_time_split.restype = None
+    lib.kda_debug_set_time_split.argtypes = [ctypes.c_int]
     lib.kda_recurrent_step.restype = ctypes.c_int
     lib.kda_recurrent_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kda_recurrent_steps_pooled.restype = ctypes.c_int
@@ -102,6 +104,10 @@ def kda_debug_set_phase_mask(mask):
 
 def kda_debug_set_overlap(enabled):
     load_library().kda_debug_set_overlap(int(bool(enabled)))
+
+
+def kda_debug_set_time_split(enabled):
+    load_library().kda_debug_set_time_split(int(bool(enabled)))
 
 
 def kda_status_string(status):

@@ -201,3 +201,41 @@ def test_bf16_decay_ladder_across_the_exact_path_threshold():
     x["log_alpha"] = per_token.view(1, 1, 1, 128).expand(2, 300, 2, 128).contiguous().to(torch.bfloat16)
     eo, eh = check_prefill(x, TOL_BF16)
     print("bf16 decay ladder: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+@pytest.mark.parametrize("overlap", [1, 0])
+@pytest.mark.parametrize("case", ["three_ranges", "eight_ranges", "packed_ragged"])
+def test_bf16_time_split_scan(case, overlap):
+    """Few (sequence, head) pairs and long sequences: the sequential kernel cuts the chunk axis into
+    ranges that several workgroups walk side by side (transition and offset of a range first, the
+    true states after a fold).  Checked against the oracle, and against the plain scan, with which
+    it must agree to rounding."""
+    import paper_2510_26692_amd as kda
+    # mu = -6: log alpha around -0.0025 per token, so a range's transition matrix is far from zero
+    # and the fold of the ranges matters; mu = -2: the state is forgotten within a range
+    if case == "three_ranges":
+        x = si.make_prefill(1, 64 * 60 - 11, 2, 128, 128, "bf16", -6.0, 301, 0.05)
+    elif case == "eight_ranges":
+        x = si.make_prefill(2, 64 * 130 + 5, 1, 128, 128, "bf16", -6.0, 302, 0.05)
+    else:
+        x = si.make_varlen(np.array([64 * 130, 3001, 100, 0]), 1, 128, 128, "bf16", -2.0, 303, 0.05)
+    try:
+        kda.kda_debug_set_overlap(overlap)
+        kda.kda_debug_set_time_split(1)
+        eo, eh = check_prefill(x, TOL_BF16)
+        dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+        o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                                   cu_seqlens=dd["cu_seqlens"], check=True)
+        kda.kda_debug_set_time_split(0)
+        o2, h2 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                                   cu_seqlens=dd["cu_seqlens"], check=True)
+        torch.cuda.synchronize()
+        d_o = (o1 - o2).abs().max().item() / o2.abs().max().item()
+        d_h = (h1 - h2).abs().max().item() / h2.abs().max().item()
+        print("time split %s overlap=%d: err_o %.2e err_hT %.2e; vs plain scan %.2e / %.2e" % (case, overlap, eo, eh, d_o, d_h))
+        assert d_o <= TOL_BF16 and d_h <= TOL_BF16
+        if case != "packed_ragged":
+            assert not torch.equal(h1, h2)                    # the split path really ran: same result, other rounding
+    finally:
+        kda.kda_debug_set_overlap(1)
+        kda.kda_debug_set_time_split(1)
