@@ -1102,55 +1102,122 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
 }
 
 // Time-split scan for few (sequence, head) pairs: the chunk axis is cut into `parts` ranges of
-// `part_len` chunk indices, and several workgroups work on one pair at a time.
-//   pass 0: blockIdx.y = 0 scans range 0 from h0 (outputs and all) and leaves its final state in
-//           E[0]; blockIdx.y = 1 + 2 (p - 1) + r computes, for range p = 1 .. parts - 2, the
-//           transition T_p (r = 0) or the offset B_p (r = 1) of that range.
-//   (kda_combine_kernel then forms E[p] = T_p E[p-1] + B_p, the state at the end of range p.)
-//   pass 1: blockIdx.y = p - 1 scans range p = 1 .. parts - 1 from E[p-1]; the last range also
-//           delivers the final state.
-// E, Tm, Bm: arrays of [pairs][128][128] fp32 states, one per range.
+// `part_len` chunk indices, and 2 parts - 3 workgroups work on one pair side by side, in one launch.
+//   blockIdx.y = 0              scans range 0 from h0 (outputs and all) and leaves its final state
+//                               in E[0]; later it scans the last range from E[parts - 2] and
+//                               delivers the final state.
+//   blockIdx.y = 2 p - 1        computes the transition T_p of range p = 1 .. parts - 2; later it
+//                               scans range p from E[p - 1].
+//   blockIdx.y = 2 p            computes the offset B_p of range p.
+// Between the phases, workgroups blockIdx.y = 1 .. workers form E[p] = T_p E[p-1] + B_p for
+// p = 1 .. parts - 2, each on its own slice of the d_v columns (the columns do not interact).
+// Results travel through the workspace (E, Tm, Bm: arrays of [pairs][128][128] fp32 states, one
+// per range) under per-pair counters: pf[p] = slices of E[p] that are complete (E[0]: set to
+// `workers` at once), pf[8 + p] / pf[16 + p] = T_p / B_p complete.  Every producer makes its stores
+// visible with a device-scope release before it raises the counter, every consumer follows its
+// (bounded) wait with a device-scope acquire.  No first-phase work waits for anything and a
+// launch has at most one workgroup per two compute units, so every wait ends.
+constexpr int kSplitFlagsPerPair = 24;
+
+// E[p][:, col0 .. col0 + 16 CW) for p = 1 .. parts - 2, in fp32, by one 512-thread workgroup.
+// Thread (ty, tx) owns rows 4 ty .. 4 ty + 3 and columns col0 + CW tx .. + CW - 1; the current
+// slice of E sits in LDS.  All T_p and B_p are awaited first (they finish before E[0] does) and
+// pulled into this die's L2; after that the chain crosses no fence: E[0] is read and E[p] written
+// with device-scope accesses.
+template <int CW>
+__device__ __forceinline__ void kda_fold_slices(float *sE, float *E, const float *Tm, const float *Bm,
+                                                int64_t pair_states, int64_t pair_base, int col0, int parts,
+                                                int workers, uint32_t *pf, uint32_t *status, bool &gave_up)
+{
+    constexpr int NC = 16 * CW;
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    if (tid == 0)
+        for (int p = 1; p <= parts - 2; ++p) {
+            wait_ready(pf + 8 + p, 1u, status, gave_up);
+            wait_ready(pf + 16 + p, 1u, status, gave_up);
+        }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    {
+        f32x4 touch = {0.f, 0.f, 0.f, 0.f};
+        for (int p = 1; p <= parts - 2; ++p)
+            for (int i = tid; i < D * D / 4; i += 512)
+                touch += *reinterpret_cast<const f32x4 *>(Tm + p * pair_states + pair_base + 4 * i);
+        asm volatile("" ::"v"(touch));
+    }
+    if (tid == 0) wait_ready(pf, (uint32_t)workers, status, gave_up);
+    __syncthreads();
+    for (int i = tid; i < D * NC; i += 512)
+        sE[i] = __hip_atomic_load(E + pair_base + (int64_t)(i / NC) * D + col0 + (i % NC), __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    for (int p = 1; p <= parts - 2; ++p) {
+        const float *Tp = Tm + p * pair_states + pair_base;
+        const float *Bp = Bm + p * pair_states + pair_base + col0 + CW * tx;
+        float acc[4][CW];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int z = 0; z < CW; ++z) acc[i][z] = Bp[(int64_t)(4 * ty + i) * D + z];
+        for (int k4 = 0; k4 < D / 4; ++k4) {
+            f32x4 a[4];
+            float b[4][CW];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const f32x4 *>(Tp + (int64_t)(4 * ty + i) * D + 4 * k4);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int z = 0; z < CW; ++z) b[kk][z] = sE[(4 * k4 + kk) * NC + CW * tx + z];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                    for (int z = 0; z < CW; ++z) acc[i][z] = fmaf(a[i][kk], b[kk][z], acc[i][z]);
+        }
+        __syncthreads();                                     // every thread is done reading the old slice
+        float *Ep = E + p * pair_states + pair_base + col0 + CW * tx;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int z = 0; z < CW; ++z) {
+                sE[(4 * ty + i) * NC + CW * tx + z] = acc[i][z];
+                __hip_atomic_store(Ep + (int64_t)(4 * ty + i) * D + z, acc[i][z], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): the write-through stores have landed
+        __syncthreads();
+        if (tid == 0) __hip_atomic_fetch_add(pf + p, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 template <bool kFlags>
 __global__ __launch_bounds__(512)
-void kda_scan_part_kernel(const uint8_t *__restrict__ ws, const float *h0, float *E, float *Tm, float *Bm,
-                          float *state_final, const int32_t *__restrict__ cu_seqlens, float *__restrict__ o,
-                          int64_t T, int H, int64_t seg_chunks, int64_t part_len, int parts, int pass,
-                          const uint32_t *ready, uint32_t epoch, uint32_t *status)
+void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, float *E, float *Tm, float *Bm,
+                           float *state_final, const int32_t *__restrict__ cu_seqlens, float *__restrict__ o,
+                           int64_t T, int H, int64_t seg_chunks, int64_t part_len, int parts,
+                           const uint32_t *ready, uint32_t epoch, uint32_t *status, uint32_t *split_flags)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int n = blockIdx.x / H, h = blockIdx.x % H;
     const int64_t pair_states = (int64_t)gridDim.x * (D * D);
+    const int64_t pair_base = (int64_t)blockIdx.x * (D * D);
 
     int64_t tok_base, len;
     if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
     else            { tok_base = (int64_t)n * T; len = T; }
     const int64_t nchunks = (len + kChunk - 1) / kChunk;
 
-    int part, role;
-    const float *state_in = nullptr;
-    float *state_out = nullptr;
-    if (pass == 0) {
-        if (blockIdx.y == 0) { part = 0; role = kRoleFull; state_in = h0; state_out = E; }
-        else {
-            part = 1 + ((int)blockIdx.y - 1) / 2;
-            role = (((int)blockIdx.y - 1) & 1) ? kRoleB : kRoleT;
-            state_out = (role == kRoleT ? Tm : Bm) + part * pair_states;
-        }
-    } else {
-        part = (int)blockIdx.y + 1; role = kRoleFull;
-        state_in = E + (part - 1) * pair_states;
-        state_out = (part == parts - 1) ? state_final : nullptr;
-    }
-    int64_t c_begin = part * part_len, c_end = c_begin + part_len;
-    if (c_begin > nchunks) c_begin = nchunks;
-    if (c_end > nchunks) c_end = nchunks;
+    const int y = (int)blockIdx.y;
+    const int kind = (y == 0) ? kRoleFull : ((y & 1) ? kRoleT : kRoleB);
+    const int mid = (y + 1) / 2;                              // the range of the first phase
+    const int workers = (parts - 2 >= 4) ? 8 : (parts - 2 >= 2) ? 4 : 2;   // among the 2 parts - 4 others
+    uint32_t *pf = split_flags + (int64_t)blockIdx.x * kSplitFlagsPerPair;
+    bool gave_up = false;
 
-    const int64_t st_base = ((int64_t)n * H + h) * (int64_t)(D * D) + 32 * (wave & 3) + (lane & 31);
-    const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kSlotBytes;
+    const int64_t st_base = pair_base + 32 * (wave & 3) + (lane & 31);
     const int64_t slot_stride = (int64_t)H * kSlotBytes;
-    const uint32_t *flag0 = kFlags ? ready + (int64_t)blockIdx.x * seg_chunks + c_begin : nullptr;
-    if (!kFlags && status && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *status = 0;
     const EpiParams no_epi = {nullptr, nullptr, 0.f};
 
 #define KDA_SCAN_PART(ROLE)                                                                                       \
@@ -1160,53 +1227,48 @@ void kda_scan_part_kernel(const uint8_t *__restrict__ ws, const float *h0, float
     else                                                                                                          \
         kda_scan_body<1, kFlags, false, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,  \
                                               len, H, c_begin, c_end, h, flag0, epoch, status, no_epi)
-    if (role == kRoleFull) { KDA_SCAN_PART(kRoleFull); }
-    else if (role == kRoleT) { KDA_SCAN_PART(kRoleT); }
-    else { KDA_SCAN_PART(kRoleB); }
-#undef KDA_SCAN_PART
-}
-
-// E[p] = T_p E[p-1] + B_p for p = 1 .. parts - 2, in fp32.  One workgroup per (pair, 32-column
-// tile of the state); thread (ty, tx) owns rows 4 ty .. 4 ty + 3 and columns 4 tx .. 4 tx + 3 of the
-// tile, the current E tile sits in LDS.
-__global__ __launch_bounds__(256)
-void kda_combine_kernel(float *E, const float *__restrict__ Tm, const float *__restrict__ Bm, int parts)
-{
-    __shared__ float sE[D][32];
-    const int tid = threadIdx.x, ty = tid >> 3, tx = tid & 7;
-    const int64_t pair_states = (int64_t)gridDim.x * (D * D);
-    const int64_t base = (int64_t)blockIdx.x * (D * D) + 32 * blockIdx.y;
-    for (int i = tid; i < D * 8; i += 256)
-        *reinterpret_cast<f32x4 *>(&sE[i >> 3][4 * (i & 7)]) =
-            *reinterpret_cast<const f32x4 *>(E + base + (int64_t)(i >> 3) * D + 4 * (i & 7));
-    __syncthreads();
-    for (int p = 1; p <= parts - 2; ++p) {
-        const float *Tp = Tm + p * pair_states + (int64_t)blockIdx.x * (D * D);
-        const float *Bp = Bm + p * pair_states + base;
-        f32x4 acc[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = *reinterpret_cast<const f32x4 *>(Bp + (int64_t)(4 * ty + i) * D + 4 * tx);
-        for (int k4 = 0; k4 < D / 4; ++k4) {
-            f32x4 a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const f32x4 *>(Tp + (int64_t)(4 * ty + i) * D + 4 * k4);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) b[kk] = *reinterpret_cast<const f32x4 *>(&sE[4 * k4 + kk][4 * tx]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                    for (int z = 0; z < 4; ++z) acc[i][z] = fmaf(a[i][kk], b[kk][z], acc[i][z]);
-        }
-        __syncthreads();                                     // every thread is done reading the old tile
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<f32x4 *>(&sE[4 * ty + i][4 * tx]) = acc[i];
-            *reinterpret_cast<f32x4 *>(E + p * pair_states + base + (int64_t)(4 * ty + i) * D + 4 * tx) = acc[i];
-        }
+    {   // first phase: the own range, from h0 / the identity / zero
+        const float *state_in = (y == 0) ? h0 : nullptr;
+        float *state_out = (y == 0) ? E : (kind == kRoleT ? Tm : Bm) + mid * pair_states;
+        int64_t c_begin = mid * part_len, c_end = c_begin + part_len;
+        if (c_begin > nchunks) c_begin = nchunks;
+        if (c_end > nchunks) c_end = nchunks;
+        const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kSlotBytes;
+        const uint32_t *flag0 = kFlags ? ready + (int64_t)blockIdx.x * seg_chunks + c_begin : nullptr;
+        if (kind == kRoleFull) { KDA_SCAN_PART(kRoleFull); }
+        else if (kind == kRoleT) { KDA_SCAN_PART(kRoleT); }
+        else { KDA_SCAN_PART(kRoleB); }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t *f = (kind == kRoleFull) ? pf : (kind == kRoleT) ? pf + 8 + mid : pf + 16 + mid;
+            __hip_atomic_store(f, (kind == kRoleFull) ? (uint32_t)workers : 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
+    if (y >= 1 && y <= workers) {
+        float *sE = reinterpret_cast<float *>(lds);
+        const int w = y - 1;
+        if (workers == 8)      kda_fold_slices<1>(sE, E, Tm, Bm, pair_states, pair_base, 16 * w, parts, workers, pf, status, gave_up);
+        else if (workers == 4) kda_fold_slices<2>(sE, E, Tm, Bm, pair_states, pair_base, 32 * w, parts, workers, pf, status, gave_up);
+        else                   kda_fold_slices<4>(sE, E, Tm, Bm, pair_states, pair_base, 64 * w, parts, workers, pf, status, gave_up);
+    }
+    if (kind == kRoleB) return;
+    {   // second phase: the scan of a range whose initial state is now known
+        const int part = (y == 0) ? parts - 1 : mid;
+        const float *state_in = E + (part - 1) * pair_states;
+        float *state_out = (y == 0) ? state_final : nullptr;
+        if (threadIdx.x == 0) wait_ready(pf + part - 1, (uint32_t)workers, status, gave_up);
+        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        int64_t c_begin = part * part_len, c_end = c_begin + part_len;
+        if (c_begin > nchunks) c_begin = nchunks;
+        if (c_end > nchunks) c_end = nchunks;
+        const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kSlotBytes;
+        const uint32_t *flag0 = kFlags ? ready + (int64_t)blockIdx.x * seg_chunks + c_begin : nullptr;
+        KDA_SCAN_PART(kRoleFull);
+    }
+#undef KDA_SCAN_PART
 }
 
 // flags and status word of the overlapped mode start every call at zero
@@ -1243,9 +1305,9 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc)
     p.flags_offset = p.carry_offset + carry;
     p.status_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
     p.split_offset = p.status_offset + 256;
-    // the states of the time-split scan, when the call qualifies for it (single segment only)
+    // counters and states of the time-split scan, when the call qualifies for it (single segment only)
     const bool split = sc == maxc && streams <= (size_t)kSplitMaxPairs && maxc >= kSplitMinChunks;
-    p.total_bytes = p.split_offset + (split ? 3 * (size_t)kSplitMaxParts * carry : 0);
+    p.total_bytes = p.split_offset + (split ? kSplitFlagBytes + 3 * (size_t)kSplitMaxParts * carry : 0);
     return p;
 }
 
@@ -1308,9 +1370,9 @@ static bool reserve_lds()
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_part_kernel<false>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_split_kernel<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_part_kernel<true>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_split_kernel<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess;
     if (!ok) (void)hipGetLastError();
     done[dev] = ok;
@@ -1436,21 +1498,24 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     }
     const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus) : 1;
 
-    if (side) {
-        const int64_t nflags = (int64_t)(plan.status_offset - plan.flags_offset) / 4 + 1;   // flags + status
-        hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream,
-                           flags, nflags, 0u);
+    if (side || parts > 1) {
+        // the slot flags (overlapped mode), the status word, the counters of the time-split scan
+        uint32_t *first = side ? flags : status;
+        const uint8_t *end = ws + (parts > 1 ? plan.split_offset + kSplitFlagBytes : plan.status_offset + 4);
+        const int64_t nfill = (int64_t)(end - reinterpret_cast<const uint8_t *>(first)) / 4;
+        hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)((nfill + 255) / 256)), dim3(256), 0, stream,
+                           first, nfill, 0u);
     }
     if (parts > 1) {
-        // Time-split scan (single segment): pass 0 and kda_intra side by side, the fold of the
-        // per-range transitions, pass 1.
+        // Time-split scan (single segment): one launch, kda_intra beside it in the overlapped mode.
         const int64_t part_len = (plan.seg_chunks + parts - 1) / parts;
         const size_t pair_states = (size_t)streams * D * D;
-        float *E = reinterpret_cast<float *>(ws + plan.split_offset);
+        uint32_t *split_flags = reinterpret_cast<uint32_t *>(ws + plan.split_offset);
+        float *E = reinterpret_cast<float *>(ws + plan.split_offset + kSplitFlagBytes);
         float *Tm = E + kSplitMaxParts * pair_states, *Bm = Tm + kSplitMaxParts * pair_states;
         auto intra = side ? (pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>)
                           : (pro ? kda_intra_kernel<false, true> : kda_intra_kernel<false, false>);
-        auto part_k = side ? kda_scan_part_kernel<true> : kda_scan_part_kernel<false>;
+        auto split_k = side ? kda_scan_split_kernel<true> : kda_scan_split_kernel<false>;
         const dim3 intra_grid_split((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)(parts * part_len));
         if (side) {
             if (hipEventRecord(side->fork, stream) != hipSuccess ||
@@ -1461,20 +1526,17 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale,
                                (uint32_t *)nullptr, 0u, raw, 1, 0);
         }
-        hipLaunchKernelGGL(part_k, dim3(streams, (unsigned)(1 + 2 * (parts - 2))), dim3(512), scan_lds, stream, ws, h0, E,
-                           Tm, Bm, (float *)nullptr, cu, static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads,
-                           plan.seg_chunks, part_len, parts, 0, flags, 1u, status);
-        if (side)
+        hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, stream, ws, h0, E,
+                           Tm, Bm, hT, cu, static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads,
+                           plan.seg_chunks, part_len, parts, flags, 1u, status, split_flags);
+        if (side) {
             hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale, flags, 1u, raw,
                                parts, (int)part_len);
-        hipLaunchKernelGGL(kda_combine_kernel, dim3(streams, 4), dim3(256), 0, stream, E, Tm, Bm, parts);
-        hipLaunchKernelGGL(part_k, dim3(streams, (unsigned)(parts - 1)), dim3(512), scan_lds, stream, ws, h0, E, Tm, Bm,
-                           hT, cu, static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, part_len,
-                           parts, 1, flags, 1u, status);
-        if (side && (hipEventRecord(side->join, side->stream) != hipSuccess ||
-                     hipStreamWaitEvent(stream, side->join, 0) != hipSuccess))
-            return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
+            if (hipEventRecord(side->join, side->stream) != hipSuccess ||
+                hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
+                return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));
         return KDA_OK;

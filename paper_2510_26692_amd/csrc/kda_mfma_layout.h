@@ -61,6 +61,7 @@ constexpr int frag_aqk(int rr, int ri, int s) { return (rr + ri) * 2 + s; }   //
 constexpr int kSplitMaxParts = 8;
 constexpr int kSplitMaxPairs = 42;
 constexpr int kSplitMinChunks = 48;
+constexpr size_t kSplitFlagBytes = 4096;     // 24 u32 counters per pair, ahead of the states
 
 // Geometry of one launch pair: `seg_chunks` chunk indices of every sequence.
 struct SegPlan {
@@ -69,7 +70,7 @@ struct SegPlan {
     size_t carry_offset;     // byte offset of the state carry buffer in the workspace
     size_t flags_offset;     // one u32 "slot ready" flag per (sequence, head, chunk of the segment)
     size_t status_offset;    // u32 set by kda_scan when a bounded wait for a flag ran out
-    size_t split_offset;     // states of the time-split scan: E, T, B, each [kSplitMaxParts][pairs][128][128] fp32
+    size_t split_offset;     // time-split scan: kSplitFlagBytes of counters, then E, T, B, each [kSplitMaxParts][pairs][128][128] fp32
     size_t total_bytes;
 };
 
