@@ -443,38 +443,50 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             // register slot with a strong channel the 64 lanes drop (G, k, q) of that slot into a
             // small scratch indexed [g][token]; every lane then reads column m and its four rows.
             float *fix = reinterpret_cast<float *>(lds + kFix) + wave * (4 * 16 * 3);
+            // (a run-time loop over the register slots that hold a strong channel: the slot's values
+            // are picked by compare-and-select, so the rare path stays a few hundred instructions)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
+            for (int ks = 0; ks < 4; ++ks) {
+                uint32_t bits = __builtin_amdgcn_readfirstlane((strong_all >> (ks * 8)) & 0xffu);
+                while (bits) {
+                    const int e = __builtin_ctz(bits);
+                    bits &= bits - 1;
+                    float Ge = G[ks * 8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    if ((strong_all >> (ks * 8 + e)) & 1u) {
-                        const uint32_t kw = kraw[ks][e >> 1], qw = qraw[ks][e >> 1];
-                        const float kfe = invk * ((e & 1) ? __uint_as_float(kw & 0xffff0000u) : __uint_as_float(kw << 16));
-                        const float qfe = invq * ((e & 1) ? __uint_as_float(qw & 0xffff0000u) : __uint_as_float(qw << 16));
-                        __builtin_amdgcn_wave_barrier();
-                        fix[(g * 16 + m) * 3 + 0] = G[ks * 8 + e];
-                        fix[(g * 16 + m) * 3 + 1] = kfe;
-                        fix[(g * 16 + m) * 3 + 2] = qfe;
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
+                    for (int z = 1; z < 8; ++z) Ge = (e == z) ? G[ks * 8 + z] : Ge;
+                    uint32_t kw = kraw[ks][0], qw = qraw[ks][0];
 #pragma unroll
-                        for (int gg = 0; gg < 4; ++gg) {
-                            if ((sStrong[R * 4 + gg] >> (ks * 8 + e)) & 1u) {
-                                const float Gi = fix[(gg * 16 + m) * 3 + 0], ki = fix[(gg * 16 + m) * 3 + 1];
+                    for (int z = 1; z < 4; ++z) {
+                        kw = ((e >> 1) == z) ? kraw[ks][z] : kw;
+                        qw = ((e >> 1) == z) ? qraw[ks][z] : qw;
+                    }
+                    const float kfe = invk * ((e & 1) ? __uint_as_float(kw & 0xffff0000u) : __uint_as_float(kw << 16));
+                    const float qfe = invq * ((e & 1) ? __uint_as_float(qw & 0xffff0000u) : __uint_as_float(qw << 16));
+                    const int sl = ks * 8 + e;
+                    __builtin_amdgcn_wave_barrier();
+                    fix[(g * 16 + m) * 3 + 0] = Ge;
+                    fix[(g * 16 + m) * 3 + 1] = kfe;
+                    fix[(g * 16 + m) * 3 + 2] = qfe;
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) {
-                                    const int rr = 4 * g + j;
-                                    if (rr >= m) {
-                                        const float t = ki * fast_exp2(fix[(gg * 16 + rr) * 3 + 0] - Gi);
-                                        akk[j] = fmaf(fix[(gg * 16 + rr) * 3 + 1], t, akk[j]);
-                                        aqk[j] = fmaf(fix[(gg * 16 + rr) * 3 + 2], t, aqk[j]);
-                                    }
+                    for (int gg = 0; gg < 4; ++gg) {
+                        if ((sStrong[R * 4 + gg] >> sl) & 1u) {
+                            const float Gi = fix[(gg * 16 + m) * 3 + 0], ki = fix[(gg * 16 + m) * 3 + 1];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int rr = 4 * g + j;
+                                if (rr >= m) {
+                                    const float t = ki * fast_exp2(fix[(gg * 16 + rr) * 3 + 0] - Gi);
+                                    akk[j] = fmaf(fix[(gg * 16 + rr) * 3 + 1], t, akk[j]);
+                                    aqk[j] = fmaf(fix[(gg * 16 + rr) * 3 + 2], t, aqk[j]);
                                 }
                             }
                         }
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                     }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 }
+            }
         }
         res_kk[R] = akk; res_qk[R] = aqk;
     }
