@@ -51,6 +51,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kStrongLog2 = 24.0f;   // sub-chunk decay below 2^-24 leaves the fast operands
 constexpr float kRowScale = 4.0f;      // keeps small row operands out of the fp16 subnormals
+constexpr float kRowShift = 2.0f;      // log2(kRowScale)
 
 // ----------------------------------------------------------------------------------
 // LDS map of kda_intra (bytes).  Regions are reused as the phases advance; the whole
@@ -297,15 +298,18 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         const float sh0 = half_shift(t0[R]), sh1 = half_shift(t1[R]);
         const float n10 = (R < 3) ? half_shift(t0[r1]) : 0.f, n11 = (R < 3) ? half_shift(t1[r1]) : 0.f;
         float *tb = sTab + R * 128 + c2;
-        *reinterpret_cast<float2 *>(tb + 0 * 512) = make_float2(fast_exp2(pre0 - sh0), fast_exp2(pre1 - sh1));
+        // (the row operands carry kRowScale as +kRowShift in their exponent: tables 0, 5 and 6 account
+        // for it; a strong channel is kept out of the diagonal tile's column operand by Tinv = 0)
+        *reinterpret_cast<float2 *>(tb + 0 * 512) = make_float2(fast_exp2(pre0 - sh0 - kRowShift), fast_exp2(pre1 - sh1 - kRowShift));
         *reinterpret_cast<float2 *>(tb + 1 * 512) = make_float2(fast_exp2(post0 + n10), fast_exp2(post1 + n11));
-        *reinterpret_cast<float2 *>(tb + 2 * 512) = make_float2(fast_exp2(-t0[R] - sh0 + n10), fast_exp2(-t1[R] - sh1 + n11));
+        *reinterpret_cast<float2 *>(tb + 2 * 512) = make_float2((t0[R] < -kStrongLog2) ? 0.f : fast_exp2(-t0[R] - sh0 + n10),
+                                                                (t1[R] < -kStrongLog2) ? 0.f : fast_exp2(-t1[R] - sh1 + n11));
         *reinterpret_cast<float2 *>(tb + 3 * 512) = make_float2(fast_exp2(t0[r1] - half_shift(t0[r2]) + n10),
                                                                 fast_exp2(t1[r1] - half_shift(t1[r2]) + n11));
         *reinterpret_cast<float2 *>(tb + 4 * 512) = make_float2(fast_exp2(t0[r1] + t0[r2] - half_shift(t0[r3]) + n10),
                                                                 fast_exp2(t1[r1] + t1[r2] - half_shift(t1[r3]) + n11));
-        *reinterpret_cast<float2 *>(tb + 5 * 512) = make_float2(t0[R] + sh0 - n10, t1[R] + sh1 - n11);
-        *reinterpret_cast<float2 *>(tb + 6 * 512) = make_float2(sh0, sh1);
+        *reinterpret_cast<float2 *>(tb + 5 * 512) = make_float2(t0[R] + sh0 - n10 + kRowShift, t1[R] + sh1 - n11 + kRowShift);
+        *reinterpret_cast<float2 *>(tb + 6 * 512) = make_float2(sh0 + kRowShift, sh1 + kRowShift);
         if (R == 0) {   // gamma^C: decay of the whole chunk
             float2 gc = make_float2(fast_exp2(t0[0] + t0[1] + t0[2] + t0[3]), fast_exp2(t1[0] + t1[1] + t1[2] + t1[3]));
             slot_store8<kPolicy>(out, kOffGc + c2 * 4, gc);
@@ -317,11 +321,10 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                        s3 = sStrong[R * 4 + 3];
         strong_all = s0 | s1 | s2 | s3;
     }
-    const uint32_t strong_mine = sStrong[R * 4 + g];
     __syncthreads();                                                               // B2
 
-    // the row shift goes into G once (a strong channel's shift is 0, so the fix-up below still sees
-    // its plain running sums)
+    // the row shift goes into G once (a strong channel's shift is the constant kRowShift alone, so
+    // the fix-up below, which uses differences of G, still sees its plain running sums)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const f32x4 x = *reinterpret_cast<const f32x4 *>(sTab + 6 * 512 + R * 128 + 32 * (i >> 1) + 8 * g + 4 * (i & 1));
@@ -369,15 +372,14 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float Ge = G[ks * 8 + e];
-            const float rf = fast_exp2(Ge);                       // 2^(G_r + D/2): within 2^(+-D/2)
+            const float rf = fast_exp2(Ge);                       // kRowScale 2^(G_r + D/2): within kRowScale 2^(+-D/2)
             const float sf = fast_exp2(tot[e] - Ge);              // decay from this token to the end of R, less the shift of R+1
-            const bool strong = (strong_mine >> (ks * 8 + e)) & 1u;
-            rk[e] = kf[e] * rf * kRowScale;
-            rq[e] = qf[e] * rf * kRowScale;
+            rk[e] = kf[e] * rf;
+            rq[e] = qf[e] * rf;
             cs[e] = kf[e] * sf;
-            cd[e] = strong ? 0.f : cs[e] * Ti[e];                 // k 2^(-G_i - D/2)
-            gk[e] = kf[e] * rf * P[e];                            // Gamma . K
-            qp[e] = qf[e] * rf * (P[e] * scale);                  // scale * Gamma . Q
+            cd[e] = cs[e] * Ti[e];                                // k 2^(-G_i - D/2); 0 for a strong channel
+            gk[e] = rk[e] * P[e];                                 // Gamma . K
+            qp[e] = rq[e] * (P[e] * scale);                       // scale * Gamma . Q
             kp[e] = cs[e] * E[e];                                 // Gamma^{i->C} . K
         }
         u32x4 t;
