@@ -178,6 +178,22 @@ def main():
         },
     }
 
+    # the same prefill with o stored as bf16 (the headline keeps fp32 o, which parity is stated on)
+    bf16_out_obj = None
+    if not args.no_breakdown:
+        o16 = torch.empty(o.shape, dtype=torch.bfloat16, device=dev)
+
+        def prefill_bf16_out():
+            kda.kda_chunk_fwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], h0=x["h0"],
+                              cu_seqlens=x["cu_seqlens"], o=o16, hT=hT, workspace=ws, max_seqlen=max_len)
+        for _ in range(args.warmup):
+            prefill_bf16_out()
+        ms_o16 = _time_region(torch, prefill_bf16_out, args.steps)
+        kda.kda_chunk_fwd_check(dims, ws)
+        bf16_out_obj = {"what": "same workload, out_dtype bf16 (o rounded once at the store)",
+                        "ms_per_step": ms_o16, "tokens_per_s": tokens / (ms_o16 * 1e-3)}
+        del o16
+
     # the same prefill on raw projections (fused input prologue), cfg1 shape only
     fused_obj = None
     if name == "cfg1_prefill_bf16" and not args.no_breakdown:
@@ -315,6 +331,7 @@ def main():
         "tokheads_per_s": tokheads / (ms_prefill * 1e-3),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "prefill_bf16_out": bf16_out_obj,
         "prefill_fused_stages": fused_obj,
         "decode": decode_obj,
         "error_metric": "max|x-ref|/max|ref| per (sequence, head); parity is gated in tests/",

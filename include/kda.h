@@ -59,7 +59,9 @@ typedef enum { KDA_F32 = 0, KDA_BF16 = 1 } kda_dtype;
  *                        number of packed tokens, sequence n owns tokens
  *                        [cu_seqlens[n], cu_seqlens[n+1]).
  * Supported: dk == dv in {64, 128}, chunk == 64, in_dtype KDA_F32 (any of the
- * two head dims) or KDA_BF16 (head dim 128), out_dtype KDA_F32.
+ * two head dims) or KDA_BF16 (head dim 128).  out_dtype KDA_F32 always;
+ * KDA_BF16 with in_dtype KDA_BF16 (o is computed in fp32 and rounded to
+ * nearest even once, when it is stored; states stay fp32).
  */
 typedef struct {
     int32_t   batch;       /* B                                                  */

@@ -65,8 +65,10 @@ static kda_status check_dims(const kda_dims *d, bool packed)
                     d->batch, (long long)d->seqlen, d->heads, d->num_seqs);
     if (d->in_dtype != KDA_F32 && d->in_dtype != KDA_BF16)
         return fail(KDA_ERR_INVALID_ARG, "in_dtype %d is not a kda_dtype", (int)d->in_dtype);
-    if (d->out_dtype != KDA_F32)
-        return fail(KDA_ERR_UNSUPPORTED, "out_dtype must be KDA_F32");
+    if (d->out_dtype != KDA_F32 && d->out_dtype != KDA_BF16)
+        return fail(KDA_ERR_INVALID_ARG, "out_dtype %d is not a kda_dtype", (int)d->out_dtype);
+    if (d->out_dtype == KDA_BF16 && d->in_dtype != KDA_BF16)
+        return fail(KDA_ERR_UNSUPPORTED, "out_dtype KDA_BF16 needs in_dtype KDA_BF16");
     if (!(d->dk == d->dv && (d->dk == 64 || d->dk == 128)))
         return fail(KDA_ERR_UNSUPPORTED, "head dims must satisfy dk == dv in {64,128}, got %d x %d",
                     d->dk, d->dv);
@@ -182,6 +184,7 @@ static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, con
         return fail(KDA_ERR_UNSUPPORTED, "bf16 prefill is built for dk == dv == 128 only");
     if (!mfma_path(d)) {
         if (pro || epi) return fail(KDA_ERR_UNSUPPORTED, "the fused stages need the matrix-core prefill");
+        if (d->out_dtype != KDA_F32) return fail(KDA_ERR_UNSUPPORTED, "the fp32 prefill kernel writes fp32 outputs only");
         return chunk_f32_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, stream);
     }
 

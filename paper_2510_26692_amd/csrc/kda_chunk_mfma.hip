@@ -791,11 +791,12 @@ __device__ __noinline__ void wait_ready(const uint32_t *flag, uint32_t epoch, ui
 }
 
 // Output gate of Section 4, applied to O before it is stored (kEpi): gate logits [B,T,H,dv] in the
-// input dtype, RMSNorm weight [dv] (NULL = ones) and epsilon.
+// input dtype, RMSNorm weight [dv] (NULL = ones) and epsilon.  out_bf16 applies with or without the gate.
 struct EpiParams {
     const uint16_t *gate;
     const float *norm_w;
     float eps;
+    int out_bf16;            // o is stored as bf16 (round to nearest even) instead of fp32
 };
 
 // kRole selects what one pass over a range of chunks computes (the time-split scan below):
@@ -807,7 +808,7 @@ constexpr int kRoleFull = 0, kRoleT = 1, kRoleB = 2;
 
 template <int P, bool kFlags, bool kEpi, int kRole = kRoleFull>
 __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
-                                              const float *state_in, float *state_out, float *o,
+                                              const float *state_in, float *state_out, void *o,
                                               int64_t st_base, int64_t tok_base, int64_t len, int H,
                                               int64_t c_begin, int64_t c_end, int h,
                                               const uint32_t *ready, uint32_t epoch, uint32_t *status,
@@ -1048,15 +1049,42 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
 #pragma unroll
                 for (int j = 0; j < 16; ++j) ao[j] *= rstd * sg[j];
             }
-            // write O (fp32, already scaled): 16 bytes per store
+            // write O (already scaled): 16 bytes per store
             if (kRole == kRoleFull) {
                 const int64_t t0 = ci * kChunk;
-                uint8_t *obase = reinterpret_cast<uint8_t *>(o + ((tok_base + t0) * H + h) * (int64_t)D);
-                if (t0 + 32 * P + x < len) {
+                if (!epi.out_bf16) {
+                    uint8_t *obase = static_cast<uint8_t *>(o) + ((tok_base + t0) * H + h) * (int64_t)(D * 4);
+                    if (t0 + 32 * P + x < len) {
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            f32x4 val = {ao[4 * q4], ao[4 * q4 + 1], ao[4 * q4 + 2], ao[4 * q4 + 3]};
+                            *reinterpret_cast<f32x4 *>(obase + (o_lane + 32 * q4)) = val;
+                        }
+                    }
+                } else {
+                    // bf16: w[2 q4 + z] = columns 8 q4 + 4 hh + 2 z, + 1.  The two lanes of a token
+                    // trade halves (lanes 0-31 hand over q4 = 2, 3 and receive the partner's q4 = 0, 1),
+                    // so each lane ends up with two runs of eight consecutive columns: two stores
+                    // instead of four.
+                    uint32_t w[8];
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4) {
-                        f32x4 val = {ao[4 * q4], ao[4 * q4 + 1], ao[4 * q4 + 2], ao[4 * q4 + 3]};
-                        *reinterpret_cast<f32x4 *>(obase + (o_lane + 32 * q4)) = val;
+                        w[2 * q4] = pack_bf16x2(ao[4 * q4], ao[4 * q4 + 1]);
+                        w[2 * q4 + 1] = pack_bf16x2(ao[4 * q4 + 2], ao[4 * q4 + 3]);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(w[i], w[4 + i], false, false);
+                        w[i] = sw[0]; w[4 + i] = sw[1];
+                    }
+                    uint8_t *obase = static_cast<uint8_t *>(o) + ((tok_base + t0) * H + h) * (int64_t)(D * 2);
+                    if (t0 + 32 * P + x < len) {
+#pragma unroll
+                        for (int qq = 0; qq < 2; ++qq) {
+                            u32x4 val = {w[2 * qq], w[2 * qq + 1], w[4 + 2 * qq], w[4 + 2 * qq + 1]};
+                            *reinterpret_cast<u32x4 *>(obase + (uint32_t)(32 * P + x) * (o_rstride / 2) +
+                                                       (uint32_t)(32 * c + 8 * (qq + 2 * hh)) * 2) = val;
+                        }
                     }
                 }
             }
@@ -1083,7 +1111,7 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
 template <bool kFlags, bool kEpi>
 __global__ __launch_bounds__(512)
 void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, float *state_out,
-                     const int32_t *__restrict__ cu_seqlens, float *__restrict__ o, int64_t T, int H,
+                     const int32_t *__restrict__ cu_seqlens, void *__restrict__ o, int64_t T, int H,
                      int64_t seg_chunks, int64_t seg_index, const uint32_t *ready, uint32_t epoch,
                      uint32_t *status, EpiParams epi)
 {
@@ -1208,9 +1236,10 @@ __device__ __forceinline__ void kda_fold_slices(float *sE, float *E, const float
 template <bool kFlags>
 __global__ __launch_bounds__(512)
 void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, float *E, float *Tm, float *Bm,
-                           float *state_final, const int32_t *__restrict__ cu_seqlens, float *__restrict__ o,
+                           float *state_final, const int32_t *__restrict__ cu_seqlens, void *__restrict__ o,
                            int64_t T, int H, int64_t seg_chunks, int64_t part_len, int parts,
-                           const uint32_t *ready, uint32_t epoch, uint32_t *status, uint32_t *split_flags)
+                           const uint32_t *ready, uint32_t epoch, uint32_t *status, uint32_t *split_flags,
+                           int out_bf16)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1232,7 +1261,7 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
 
     const int64_t st_base = pair_base + 32 * (wave & 3) + (lane & 31);
     const int64_t slot_stride = (int64_t)H * kSlotBytes;
-    const EpiParams no_epi = {nullptr, nullptr, 0.f};
+    const EpiParams no_epi = {nullptr, nullptr, 0.f, out_bf16};
 
 #define KDA_SCAN_PART(ROLE)                                                                                       \
     if (wave < 4)                                                                                                 \
@@ -1460,7 +1489,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     using namespace mfma;
     RawParams raw = {nullptr, nullptr, 0.f};
     if (pro) { raw.a_scale = pro->a_scale; raw.dt_bias = pro->dt_bias; raw.eps = pro->l2norm_eps; }
-    EpiParams ep = {nullptr, nullptr, 0.f};
+    const int out_bf16 = d->out_dtype == KDA_BF16;
+    EpiParams ep = {nullptr, nullptr, 0.f, out_bf16};
     if (epi) { ep.gate = static_cast<const uint16_t *>(epi->gate); ep.norm_w = epi->norm_weight; ep.eps = epi->rms_eps; }
     if (d->seqlen == 0) {
         // nothing to scan: the final state is the initial one
@@ -1541,8 +1571,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                                (uint32_t *)nullptr, 0u, raw, 1, 0);
         }
         hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, stream, ws, h0, E,
-                           Tm, Bm, hT, cu, static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads,
-                           plan.seg_chunks, part_len, parts, flags, 1u, status, split_flags);
+                           Tm, Bm, hT, cu, o, (int64_t)d->seqlen, (int)d->heads,
+                           plan.seg_chunks, part_len, parts, flags, 1u, status, split_flags, out_bf16);
         if (side) {
             hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale, flags, 1u, raw,
@@ -1567,7 +1597,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                 return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
             auto scan_k = epi ? kda_scan_kernel<true, true> : kda_scan_kernel<true, false>;
             hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
-                               static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
+                               o, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                flags, epoch, status, ep);
             auto intra = pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>;
             hipLaunchKernelGGL(intra, intra_grid_overlap,
@@ -1585,7 +1615,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             auto scan_k = epi ? kda_scan_kernel<false, true> : kda_scan_kernel<false, false>;
             if (g_phase_mask & 2)
                 hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
-                                   static_cast<float *>(o), (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
+                                   o, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                    (const uint32_t *)nullptr, 0u, status, ep);
         }
     }

@@ -29,6 +29,15 @@ __device__ __forceinline__ void unpack_bf16x2(uint32_t w, float &lo, float &hi)
     hi = __uint_as_float(w & 0xffff0000u);
 }
 
+// Two floats -> two packed bf16, round to nearest even (element 0 in the low half).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 // Scalar element loads, widened to fp32, for the two supported input dtypes.
 template <typename T> __device__ __forceinline__ float load_as_float(const T *p);
 template <> __device__ __forceinline__ float load_as_float<float>(const float *p) { return *p; }

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(DV * 2)
 void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                      const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
                      const Tin *__restrict__ beta, float *__restrict__ S,
-                     float *__restrict__ o, float scale, int H, int steps,
+                     void *__restrict__ o, int o_bf16, float scale, int H, int steps,
                      const int32_t *__restrict__ indices, const float *__restrict__ a_scale,
                      const float *__restrict__ dt_bias, float l2_eps, const Tin *__restrict__ out_gate,
                      const float *__restrict__ norm_w, float rms_eps)
@@ -172,8 +172,14 @@ void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             o3 *= rstd * wv[3] * __builtin_amdgcn_rcpf(1.f + fast_exp2(-gv[3] * kLog2e));
         }
         if (rg == 0) {
-            f32x4 out = {o0, o1, o2, o3};
-            *reinterpret_cast<f32x4 *>(o + row * DV + col) = out;
+            if (o_bf16) {
+                const uint32_t lo = pack_bf16x2(o0, o1), hi = pack_bf16x2(o2, o3);
+                uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<uint16_t *>(o) + row * DV + col);
+                dst[0] = lo; dst[1] = hi;
+            } else {
+                f32x4 out = {o0, o1, o2, o3};
+                *reinterpret_cast<f32x4 *>(static_cast<float *>(o) + row * DV + col) = out;
+            }
         }
     }
 }
@@ -191,7 +197,7 @@ static kda_status launch_step(const kda_dims *d, const kda_prologue *pro, const 
     hipLaunchKernelGGL(step, dim3((unsigned)pairs), dim3(DV * 2), 0, stream,
                        static_cast<const Tin *>(q), static_cast<const Tin *>(k),
                        static_cast<const Tin *>(v), static_cast<const Tin *>(log_alpha),
-                       static_cast<const Tin *>(beta), S, static_cast<float *>(o), d->scale,
+                       static_cast<const Tin *>(beta), S, o, (int)(d->out_dtype == KDA_BF16), d->scale,
                        (int)d->heads, (int)d->seqlen, indices, pro ? pro->a_scale : nullptr,
                        pro ? pro->dt_bias : nullptr, pro ? pro->l2norm_eps : 0.f,
                        static_cast<const Tin *>(epi ? epi->gate : nullptr), epi ? epi->norm_weight : nullptr,

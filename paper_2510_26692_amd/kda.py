@@ -137,12 +137,22 @@ def _stream_ptr(dev):
     return ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
 
 
-def make_chunk_dims(q, v, cu_seqlens=None, scale=1.0, max_seqlen=0):
+def _out_dtype(o, out_dtype):
+    """torch dtype of o: that of a tensor passed in, else `out_dtype`, else fp32."""
+    dt = o.dtype if o is not None else (out_dtype or torch.float32)
+    if out_dtype is not None and dt != out_dtype:
+        raise ValueError("o has dtype %s but out_dtype is %s" % (dt, out_dtype))
+    if dt not in _DTYPE_CODE:
+        raise ValueError("unsupported output dtype %s" % dt)
+    return dt
+
+
+def make_chunk_dims(q, v, cu_seqlens=None, scale=1.0, max_seqlen=0, out_dtype=torch.float32):
     B, T, H, dk = q.shape
     dv = v.shape[-1]
     N = B if cu_seqlens is None else cu_seqlens.numel() - 1
     return KdaDims(batch=B, seqlen=T, heads=H, dk=dk, dv=dv, chunk=64, num_seqs=N,
-                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale),
+                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=_DTYPE_CODE[out_dtype], scale=float(scale),
                    max_seqlen=int(max_seqlen))
 
 
@@ -201,10 +211,12 @@ def kda_chunk_fwd_fused(q, k, v, gate, beta, prologue=True, l2norm_eps=1e-6, a_s
 
 
 def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0, o=None,
-                  hT=None, want_hT=True, workspace=None, max_seqlen=0, check=False, _fused=None):
+                  hT=None, want_hT=True, workspace=None, max_seqlen=0, check=False, out_dtype=None,
+                  _fused=None):
     """Chunkwise prefill.  q,k,log_alpha [B,T,H,dk]; v [B,T,H,dv]; beta [B,T,H];
     h0 [N,H,dk,dv] fp32 or None; cu_seqlens int32 [N+1] on device or None.
-    Returns (o fp32 [B,T,H,dv], hT fp32 [N,H,dk,dv] or None).  `o`, `hT` and
+    Returns (o [B,T,H,dv], hT fp32 [N,H,dk,dv] or None); o is fp32 unless out_dtype (or the `o`
+    passed in) is torch.bfloat16, which bf16 inputs allow.  `o`, `hT` and
     `workspace` (a uint8 device tensor) may be passed in to avoid allocation.
     check=True synchronises and runs kda_chunk_fwd_check before returning."""
     lib = load_library()
@@ -218,14 +230,17 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
     if k.shape != q.shape or log_alpha.shape != q.shape or v.shape != (B, T, H, dv) \
             or beta.shape != (B, T, H):
         raise ValueError("inconsistent input shapes")
-    dims = make_chunk_dims(q, v, cu_seqlens, scale, max_seqlen)
+    odt = _out_dtype(o, out_dtype)
+    dims = make_chunk_dims(q, v, cu_seqlens, scale, max_seqlen, odt)
     N = dims.num_seqs
+    if o is not None and o.shape != (B, T, H, dv):
+        raise ValueError("o must have shape [B,T,H,dv]")
     if h0 is not None and (h0.dtype != torch.float32 or h0.shape != (N, H, dk, dv)):
         raise ValueError("h0 must be fp32 [N,H,dk,dv]")
     if cu_seqlens is not None and cu_seqlens.dtype != torch.int32:
         raise ValueError("cu_seqlens must be int32")
     if o is None:
-        o = torch.zeros(B, T, H, dv, dtype=torch.float32, device=dev)
+        o = torch.zeros(B, T, H, dv, dtype=odt, device=dev)
     if hT is None and want_hT:
         hT = torch.empty(N, H, dk, dv, dtype=torch.float32, device=dev)
     if workspace is None:
@@ -246,9 +261,10 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
     return o, hT
 
 
-def kda_recurrent_step(q, k, v, log_alpha, beta, S, scale=1.0, o=None):
+def kda_recurrent_step(q, k, v, log_alpha, beta, S, scale=1.0, o=None, out_dtype=None):
     """One decode step.  q,k,log_alpha [N,H,dk]; v [N,H,dv]; beta [N,H];
-    S fp32 [N,H,dk,dv], updated in place.  Returns o fp32 [N,H,dv]."""
+    S fp32 [N,H,dk,dv], updated in place.  Returns o [N,H,dv] (fp32, or bf16 on request as in
+    kda_chunk_fwd)."""
     lib = load_library()
     dev = _check_dev(q, k, v, log_alpha, beta, S, o)
     N, H, dk = q.shape
@@ -257,10 +273,13 @@ def kda_recurrent_step(q, k, v, log_alpha, beta, S, scale=1.0, o=None):
         raise ValueError("S must be fp32 [N,H,dk,dv]")
     if q.dtype not in _DTYPE_CODE or not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype):
         raise ValueError("q, k, v, log_alpha, beta must share a supported dtype")
+    odt = _out_dtype(o, out_dtype)
     if o is None:
-        o = torch.empty(N, H, dv, dtype=torch.float32, device=dev)
+        o = torch.empty(N, H, dv, dtype=odt, device=dev)
+    elif o.shape != (N, H, dv):
+        raise ValueError("o must have shape [N,H,dv]")
     dims = KdaDims(batch=N, seqlen=1, heads=H, dk=dk, dv=dv, chunk=64, num_seqs=N,
-                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale), max_seqlen=0)
+                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=_DTYPE_CODE[odt], scale=float(scale), max_seqlen=0)
     st = lib.kda_recurrent_step(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha),
                                 _ptr(beta), _ptr(S), _ptr(o), _stream_ptr(dev))
     if st != 0:
@@ -277,10 +296,11 @@ def kda_recurrent_steps_fused(q, k, v, gate, beta, S_pool, state_indices=None, p
 
 
 def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=None, scale=1.0, o=None,
-                               _fused=None):
+                               out_dtype=None, _fused=None):
     """Decode over a state pool.  q,k,log_alpha [N,Tq,H,dk]; v [N,Tq,H,dv]; beta [N,Tq,H];
     S_pool fp32 [P,H,dk,dv], the addressed states updated in place; state_indices int32 [N] on the
-    device (negative = skip) or None for 0..N-1.  Returns o fp32 [N,Tq,H,dv]."""
+    device (negative = skip) or None for 0..N-1.  Returns o [N,Tq,H,dv] (fp32, or bf16 on request as in
+    kda_chunk_fwd)."""
     lib = load_library()
     dev = _check_dev(q, k, v, log_alpha, beta, S_pool, state_indices, o)
     N, Tq, H, dk = q.shape
@@ -296,10 +316,13 @@ def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=N
             raise ValueError("S_pool holds fewer states than there are sequences")
     elif state_indices.dtype != torch.int32 or state_indices.shape != (N,):
         raise ValueError("state_indices must be int32 [N]")
+    odt = _out_dtype(o, out_dtype)
     if o is None:
-        o = torch.zeros(N, Tq, H, dv, dtype=torch.float32, device=dev)
+        o = torch.zeros(N, Tq, H, dv, dtype=odt, device=dev)
+    elif o.shape != (N, Tq, H, dv):
+        raise ValueError("o must have shape [N,Tq,H,dv]")
     dims = KdaDims(batch=N, seqlen=Tq, heads=H, dk=dk, dv=dv, chunk=64, num_seqs=N,
-                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=KDA_F32, scale=float(scale), max_seqlen=0)
+                   in_dtype=_DTYPE_CODE[q.dtype], out_dtype=_DTYPE_CODE[odt], scale=float(scale), max_seqlen=0)
     tail = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S_pool), _ptr(state_indices), _ptr(o),
             _stream_ptr(dev))
     if _fused is None:

@@ -1,0 +1,115 @@
+"""bf16 outputs (out_dtype KDA_BF16): o is computed in fp32 and rounded to nearest even once, at
+the store.  Two checks per case: the bf16 output is bit for bit the rounded fp32 output of the same
+call (same kernels, same order of operations, only the store differs), and it meets the oracle
+within the bf16 tolerance plus one bf16 rounding."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from helpers import o_slices, oracle_prefill, to_device, worst_slice_err
+
+pytestmark = pytest.mark.gpu
+
+# 2e-3 (bf16 inputs, fp32 outputs) plus the unit roundoff of bf16: 8 significant bits, so rounding
+# to nearest moves a value in [2^e, 2^(e+1)) by at most 2^(e-8), i.e. by at most 2^-8 max|ref| for
+# values no larger than max|ref|.
+TOL_BF16_OUT = 2e-3 + 2.0 ** -8
+
+
+def _prefill_both(x, **kw):
+    import paper_2510_26692_amd as kda
+    dd = to_device(x)
+    args = (dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"])
+    common = dict(h0=dd.get("h0"), cu_seqlens=dd.get("cu_seqlens"), check=True, **kw)
+    o16, h16 = kda.kda_chunk_fwd(*args, out_dtype=torch.bfloat16, **common)
+    o32, h32 = kda.kda_chunk_fwd(*args, **common)
+    torch.cuda.synchronize()
+    assert o16.dtype == torch.bfloat16 and o32.dtype == torch.float32
+    return o16, h16, o32, h32
+
+
+@pytest.mark.parametrize("case", ["ragged", "packed", "time_split", "serial_kernels"])
+def test_prefill_bf16_output_is_the_rounded_fp32_output(case):
+    import paper_2510_26692_amd as kda
+    if case == "ragged":
+        x = si.make_prefill(2, 200 + 37, 4, 128, 128, "bf16", -2.0, 401, 0.02)
+    elif case == "packed":
+        x = si.make_varlen([70, 0, 5, 129, 64, 300], 3, 128, 128, "bf16", -2.0, 402, 0.05)
+    elif case == "time_split":
+        x = si.make_prefill(1, 64 * 60 - 11, 2, 128, 128, "bf16", -6.0, 403, 0.05)
+    else:
+        x = si.make_prefill(3, 500, 2, 128, 128, "bf16", -2.0, 404, 0.02)
+    try:
+        if case == "serial_kernels":
+            kda.kda_debug_set_overlap(0)
+        o16, h16, o32, h32 = _prefill_both(x)
+    finally:
+        kda.kda_debug_set_overlap(1)
+    assert torch.equal(o16, o32.to(torch.bfloat16))
+    assert torch.equal(h16, h32)
+    o_ref, _ = oracle_prefill(x)
+    B, T, H, _ = x["q"].shape
+    cu = None if x.get("cu_seqlens") is None else x["cu_seqlens"].cpu().numpy()
+    eo = worst_slice_err(o16.float().cpu().numpy(), o_ref, o_slices(B, H, cu))
+    print("bf16 output %s: err_o %.2e" % (case, eo))
+    assert eo <= TOL_BF16_OUT
+
+
+def test_prefill_bf16_output_with_the_output_gate():
+    import paper_2510_26692_amd as kda
+    H, d, T = 3, 128, 341
+    cu = torch.tensor([0, 200, 277, 341], dtype=torch.int32)
+    gen = torch.Generator().manual_seed(405)
+    og = (torch.randn(1, T, H, d, generator=gen) * 1.5).to(torch.bfloat16)
+    w = 1.0 + 0.3 * torch.randn(d, generator=gen)
+    x = si.make_raw_tokens(1, T, H, d, d, "bf16", -2.0, 406)
+    g = {k_: v_.cuda() for k_, v_ in x.items() if isinstance(v_, torch.Tensor)}
+    args = [g[n_] for n_ in ("q_raw", "k_raw", "v", "gate", "beta_logit")]
+    common = dict(prologue=True, out_gate=og.cuda(), norm_weight=w.cuda(), rms_eps=1e-5, cu_seqlens=cu.cuda(),
+                  scale=0.5, check=True)
+    o16, h16 = kda.kda_chunk_fwd_fused(*args, out_dtype=torch.bfloat16, **common)
+    o32, h32 = kda.kda_chunk_fwd_fused(*args, **common)
+    torch.cuda.synchronize()
+    assert torch.equal(o16, o32.to(torch.bfloat16)) and torch.equal(h16, h32)
+
+
+@pytest.mark.parametrize("Tq", [1, 4])
+def test_decode_bf16_output_is_the_rounded_fp32_output(Tq):
+    import paper_2510_26692_amd as kda
+    N, H, d = 5, 4, 128
+    S0 = si.make_state(N, H, d, d, 0.02, 407)
+    toks = [si.make_decode_tokens(N, H, d, d, "bf16", -2.0, 407, t) for t in range(Tq)]
+    tok = {k_: torch.stack([t_[k_] for t_ in toks], dim=1).contiguous().cuda() for k_ in toks[0]}
+    outs = []
+    for odt in (torch.bfloat16, torch.float32):
+        S = S0.cuda().clone()
+        if Tq == 1:
+            o = kda.kda_recurrent_step(*[tok[n_][:, 0].contiguous() for n_ in ("q", "k", "v", "log_alpha", "beta")],
+                                       S, scale=0.9, out_dtype=odt)
+        else:
+            o = kda.kda_recurrent_steps_pooled(tok["q"], tok["k"], tok["v"], tok["log_alpha"], tok["beta"], S,
+                                               scale=0.9, out_dtype=odt)
+        torch.cuda.synchronize()
+        assert o.dtype == odt
+        outs.append((o, S))
+    assert torch.equal(outs[0][0], outs[1][0].to(torch.bfloat16))
+    assert torch.equal(outs[0][1], outs[1][1])
+    # and against the oracle
+    names = ("q", "k", "v", "log_alpha", "beta")
+    o_ref, _ = oracle.kda_steps_pooled(*[si.to_np32(tok[n_].cpu()) for n_ in names],
+                                       S0.numpy().astype(np.float64), np.arange(N), scale=0.9)
+    o_np = outs[0][0].float().cpu().numpy().reshape(N, Tq, H, d)
+    err = max(np.max(np.abs(o_np[n, :, h] - o_ref[n, :, h])) / np.max(np.abs(o_ref[n, :, h]))
+              for n in range(N) for h in range(H))
+    print("bf16 decode output Tq=%d: err_o %.2e" % (Tq, err))
+    assert err <= TOL_BF16_OUT
+
+
+def test_bf16_output_needs_bf16_inputs():
+    import paper_2510_26692_amd as kda
+    x = to_device(si.make_prefill(1, 64, 1, 64, 64, "f32", -2.0, 408, 0.0))
+    with pytest.raises(kda.KdaError) as e:
+        kda.kda_chunk_fwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], out_dtype=torch.bfloat16)
+    assert e.value.status == 2

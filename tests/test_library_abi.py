@@ -61,7 +61,8 @@ def test_workspace_sizes_are_consistent():
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(dk=96, dv=96), 2), (dict(chunk=32), 2), (dict(out_dtype=1), 2), (dict(seqlen=-1), 1),
+    (dict(dk=96, dv=96), 2), (dict(chunk=32), 2), (dict(out_dtype=1, in_dtype=0), 2), (dict(out_dtype=5), 1),
+    (dict(seqlen=-1), 1),
     (dict(num_seqs=3), 1), (dict(in_dtype=7), 1),
 ])
 def test_chunk_fwd_rejects_bad_dims_without_launching(kw, status):
