@@ -105,7 +105,7 @@ void kda_debug_set_phase_mask(int mask) { g_phase_mask = mask & 3; }
 
 void kda_debug_set_overlap(int enabled) { g_overlap = enabled ? 1 : 0; }
 
-void kda_debug_set_time_split(int enabled) { g_split = enabled ? 1 : 0; }
+void kda_debug_set_time_split(int mode) { g_split = mode < 0 ? 0 : mode; }
 
 const char *kda_last_error(void) { return g_last_error; }
 

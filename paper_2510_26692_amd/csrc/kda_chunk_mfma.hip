@@ -1158,7 +1158,7 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
 // `workers` at once), pf[8 + p] / pf[16 + p] = T_p / B_p complete.  Every producer makes its stores
 // visible with a device-scope release before it raises the counter, every consumer follows its
 // (bounded) wait with a device-scope acquire.  No first-phase work waits for anything and a
-// launch has at most one workgroup per two compute units, so every wait ends.
+// launch has fewer workgroups than half the compute units, so every wait ends.
 constexpr int kSplitFlagsPerPair = 24;
 
 // E[p][:, col0 .. col0 + 16 CW) for p = 1 .. parts - 2, in fp32, by one 512-thread workgroup.
@@ -1354,17 +1354,19 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc)
     return p;
 }
 
-// Number of ranges for the time-split scan (1 = plain scan).  Pass 0 keeps 2 parts - 3 compute
-// units per pair busy; at most half of the device is given to it, so that kda_intra, which runs
-// beside it, keeps the other half.
-static int split_parts(const SegPlan &plan, const kda_dims *d, int cus)
+// Number of ranges for the time-split scan (1 = plain scan).  The launch keeps 2 parts - 3 compute
+// units per pair busy; it gets at most three eighths of the device, so that kda_intra, which runs
+// beside it and is the larger half of the work, keeps the rest (measured on 2 to 40 pairs: the
+// best number of ranges is the largest one under that limit, and beyond it the plain scan wins).
+static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forced)
 {
     const int64_t maxc = max_chunks_per_seq(d);
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
     if (plan.num_segments != 1 || pairs > kSplitMaxPairs || maxc < kSplitMinChunks) return 1;
     int parts = 1;
     for (int p = 3; p <= kSplitMaxParts; ++p)
-        if (pairs * (2 * p - 3) * 2 <= cus && (maxc + p - 1) / p >= 16) parts = p;
+        if (pairs * (2 * p - 3) * 8 <= (int64_t)cus * 3 && (maxc + p - 1) / p >= 16 && (forced < 3 || p <= forced))
+            parts = p;
     return parts;
 }
 
@@ -1540,7 +1542,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         side = side_stream();
         if (side && (int64_t)streams * 4 > (int64_t)cus * 3) side = nullptr;
     }
-    const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus) : 1;
+    const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus, g_split) : 1;
 
     if (side || parts > 1) {
         // the slot flags (overlapped mode), the status word, the counters of the time-split scan

@@ -106,8 +106,9 @@ def kda_debug_set_overlap(enabled):
     load_library().kda_debug_set_overlap(int(bool(enabled)))
 
 
-def kda_debug_set_time_split(enabled):
-    load_library().kda_debug_set_time_split(int(bool(enabled)))
+def kda_debug_set_time_split(mode):
+    """0 = off, 1 = on (the library picks the number of ranges), 3..8 = at most that many ranges."""
+    load_library().kda_debug_set_time_split(int(mode))
 
 
 def kda_status_string(status):
