@@ -26,7 +26,7 @@ MFMA_PEAK_TFLOPS = 2500.0          # dense fp16/bf16 matrix cores
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/pmc_traffic_bench_cfg1_cfg4.txt),
 # scaled by what the same counters read for a 1 GiB copy.  Counter collection serialises kernels, so the
 # prefill figure is that of the two kernels run one after the other (both summed).
-MEASURED_TRAFFIC_BYTES = {"cfg1_prefill_bf16": 1084.5e6, "cfg4_decode_bf16": 1086.6e6}
+MEASURED_TRAFFIC_BYTES = {"cfg1_prefill_bf16": 1007.3e6, "cfg4_decode_bf16": 1086.6e6}
 
 # Algorithmic work per (token, head) at d_k = d_v = 128, C = 64.
 FLOP_PER_TOKHEAD = 6 * 128 * 128 + 3 * 64 * 128 + 64 * 64        # paper's FLOPs model: 126976
