@@ -211,13 +211,17 @@ def main():
         og = torch.randn(c["B"], c["T"], H, c["dv"], generator=torch.Generator().manual_seed(c["seed"])).to(torch.bfloat16).to(dev)
         nw = torch.ones(c["dv"], dtype=torch.float32, device=dev)
 
+        # (with the output gate the workspace also holds the re-laid gate logits)
+        ws_g = torch.empty(kda.kda_chunk_fwd_workspace_size(dims, output_gate=True), dtype=torch.uint8, device=dev)
+
         def prefill_fused_both():
             kda.kda_chunk_fwd_fused(rx["q_raw"], rx["k_raw"], rx["v"], rx["gate"], rx["beta_logit"],
-                                    out_gate=og, norm_weight=nw, h0=x["h0"], o=o, hT=hT, workspace=ws)
+                                    out_gate=og, norm_weight=nw, h0=x["h0"], o=o, hT=hT, workspace=ws_g)
         for _ in range(args.warmup):
             prefill_fused_both()
         ms_both = _time_region(torch, prefill_fused_both, args.steps)
-        kda.kda_chunk_fwd_check(dims, ws)
+        kda.kda_chunk_fwd_check(dims, ws_g)
+        del ws_g
         fused_obj = {"what": "kda_chunk_fwd_fused on the cfg1 shape: (a) input prologue (L2Norm(q), L2Norm(k), "
                              "Sigmoid(beta), decay function) inside the per-chunk kernel; (b) plus the output gate "
                              "Sigmoid(g) * RMSNorm(o) inside the sequential kernel",

@@ -23,6 +23,15 @@
  *     on `hip_stream` before the call, and `hip_stream` waits for it before
  *     the call's work counts as complete: to the caller the call behaves as if
  *     everything ran on `hip_stream`.
+ *   - Concurrency: calls may be issued from several host threads and on several
+ *     streams at once, each with its own workspace (a workspace belongs to one call
+ *     until that call has completed).  A bf16 kda_chunk_fwd keeps one compute unit per
+ *     (sequence, head) waiting on its producer kernel (up to three eighths of the
+ *     device with few pairs), so calls in flight together whose pairs add up to more
+ *     than the device has compute units can starve their producers: the waits give up
+ *     after about two seconds and kda_chunk_fwd_check reports it.  Run such workloads
+ *     with kda_debug_set_overlap(0) (or KDA_PREFILL_OVERLAP=0), which keeps every call
+ *     free of waits.
  *   - Element offsets are 64-bit; tensors with more than 2^31 elements are fine.
  *   - Errors: a non-zero kda_status is returned and kda_last_error() holds a
  *     thread-local description.  For KDA_ERR_INVALID_ARG, KDA_ERR_UNSUPPORTED
@@ -153,6 +162,16 @@ typedef struct {
     const void  *gate;         /* gate logits, same shape and dtype as v ([..,H,dv]), device  */
     const float *norm_weight;  /* [dv] fp32, device memory, or NULL                           */
 } kda_epilogue;
+
+/*
+ * Workspace sizes for kda_chunk_fwd_fused: as kda_chunk_fwd_workspace_size and
+ * kda_chunk_fwd_min_workspace_size, plus, when `epilogue` is not NULL, room for the gate logits that
+ * the per-chunk kernel re-lays for the sequential kernel (16 KiB per chunk and head held at once).
+ * With epilogue == NULL they equal the plain functions.  A fused call whose workspace is smaller
+ * than the first figure still runs, in more segments.
+ */
+size_t kda_chunk_fwd_fused_workspace_size(const kda_dims *dims, const kda_epilogue *epilogue);
+size_t kda_chunk_fwd_fused_min_workspace_size(const kda_dims *dims, const kda_epilogue *epilogue);
 
 /*
  * kda_chunk_fwd with the fused stages: `prologue` (or NULL: q, k, gate = log_alpha and beta are

@@ -32,7 +32,7 @@ kda_status chunk_f32_dispatch(const kda_dims *, const void *, const void *, cons
 kda_status chunk_mfma_dispatch(const kda_dims *, const kda_prologue *, const kda_epilogue *, const void *, const void *, const void *,
                                const void *, const void *, const float *, const int32_t *, void *,
                                float *, void *, size_t, hipStream_t);
-size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal);
+size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal, bool output_gate);
 size_t chunk_mfma_status_offset(const kda_dims *, size_t workspace_bytes);
 
 // Diagnostics: which kernels of the matrix-core prefill run (bit 0 kda_intra, bit 1 kda_scan).
@@ -121,22 +121,24 @@ const char *kda_status_string(kda_status s)
     return "unknown status";
 }
 
-size_t kda_chunk_fwd_workspace_size(const kda_dims *d)
+static size_t workspace_size(const kda_dims *d, bool minimal, bool output_gate)
 {
     if (!d || d->chunk != kChunk) return 0;
     const char saved0 = g_last_error[0];
     if (check_dims(d, d->num_seqs != d->batch) != KDA_OK) { g_last_error[0] = saved0; return 0; }
     if (!mfma_path(d)) return 0;
-    return chunk_mfma_workspace_size(d, false);
+    return chunk_mfma_workspace_size(d, minimal, output_gate);
 }
 
-size_t kda_chunk_fwd_min_workspace_size(const kda_dims *d)
+size_t kda_chunk_fwd_workspace_size(const kda_dims *d) { return workspace_size(d, false, false); }
+size_t kda_chunk_fwd_min_workspace_size(const kda_dims *d) { return workspace_size(d, true, false); }
+size_t kda_chunk_fwd_fused_workspace_size(const kda_dims *d, const kda_epilogue *epi)
 {
-    if (!d || d->chunk != kChunk) return 0;
-    const char saved0 = g_last_error[0];
-    if (check_dims(d, d->num_seqs != d->batch) != KDA_OK) { g_last_error[0] = saved0; return 0; }
-    if (!mfma_path(d)) return 0;
-    return chunk_mfma_workspace_size(d, true);
+    return workspace_size(d, false, epi != nullptr);
+}
+size_t kda_chunk_fwd_fused_min_workspace_size(const kda_dims *d, const kda_epilogue *epi)
+{
+    return workspace_size(d, true, epi != nullptr);
 }
 
 static kda_status check_epilogue(const kda_epilogue *epi)
@@ -188,7 +190,7 @@ static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, con
         return chunk_f32_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, stream);
     }
 
-    const size_t need = chunk_mfma_workspace_size(d, true);
+    const size_t need = chunk_mfma_workspace_size(d, true, epi != nullptr);
     if (need > 0) {
         if (!workspace) return fail(KDA_ERR_WORKSPACE, "workspace is NULL, at least %zu bytes needed", need);
         if (reinterpret_cast<uintptr_t>(workspace) & 255u)
@@ -231,8 +233,8 @@ kda_status kda_chunk_fwd_check(const kda_dims *d, const void *workspace, size_t 
     hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "stream: %s", hipGetErrorString(e));
     if (d->chunk != kChunk || check_dims(d, d->num_seqs != d->batch) != KDA_OK) return KDA_ERR_INVALID_ARG;
-    if (!mfma_path(d) || !workspace || chunk_mfma_workspace_size(d, true) == 0 ||
-        workspace_bytes < chunk_mfma_workspace_size(d, true))
+    if (!mfma_path(d) || !workspace || chunk_mfma_workspace_size(d, true, false) == 0 ||
+        workspace_bytes < chunk_mfma_workspace_size(d, true, false))
         return KDA_OK;                                       // this path leaves no status word
     uint32_t word = 0;
     e = hipMemcpy(&word, static_cast<const uint8_t *>(workspace) + chunk_mfma_status_offset(d, workspace_bytes),

@@ -154,7 +154,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
                       uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
                       int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch, RawParams raw,
-                      int parts, int part_len)
+                      int parts, int part_len, const uint16_t *__restrict__ out_gate, uint8_t *__restrict__ gate_ws)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -193,6 +193,21 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     const int R = wave, m = lane & 15, g = lane >> 4;
     const int tok = 16 * R + m;
 
+    // ---- output gate (fused epilogue): the chunk's gate logits are re-laid into the accumulator
+    // order of the sequential kernel, which reads them like any other part of the slot.  The loads
+    // go out first and the stores follow the kernel's own loads, so the copy hides in their latency.
+    u32x4 ograw[4];
+    if (out_gate) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+            u32x4 x = {0, 0, 0, 0};
+            if (tokv < nv)
+                x = *reinterpret_cast<const u32x4 *>(out_gate + ((tok0 + tokv) * H + h) * (int64_t)D + 8 * cg);
+            ograw[i] = x;
+        }
+    }
+
     // ---- loads: 16 bytes (8 channels) per ks and tensor ----
     // (log_alpha first: the running sum below waits for it, k and q are not needed before B2)
     u32x4 kraw[4], qraw[4], graw[4];
@@ -210,6 +225,21 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         float b = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
         if (kRaw) b = (tid < nv) ? __builtin_amdgcn_rcpf(1.f + fast_exp2(-b * kLog2e)) : 0.f;   // Sigmoid
         sBeta[tid] = b;
+    }
+    if (out_gate) {
+        // piece (token, 8 columns 8 cg ..) = column group q = cg % 4 of tile (token / 32, cg / 4): its
+        // first four columns belong to lane (token % 32, hh = 0), the other four to lane (.., hh = 1)
+        const __amdgpu_buffer_rsrc_t gout = __builtin_amdgcn_make_buffer_rsrc(
+            gate_ws + (slot * H + h) * (int64_t)kGateSlotBytes, 0, kGateSlotBytes, 0x00020000);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+            const int base = ((tokv >> 5) * 4 + (cg >> 2)) * kGateTileBytes + ((cg & 3) >> 1) * 1024 + (tokv & 31) * 16 +
+                             (cg & 1) * 8;
+            const u32x2 lo = {ograw[i][0], ograw[i][1]}, hi = {ograw[i][2], ograw[i][3]};
+            slot_store8<kPolicy>(gout, base, lo);
+            slot_store8<kPolicy>(gout, base + 32 * 16, hi);
+        }
     }
     // kRaw: 1 / |q|, 1 / |k| of this lane's token (the four lanes g = 0..3 of a token hold 32 channels each)
     float invq = 1.f, invk = 1.f;
@@ -793,10 +823,11 @@ __device__ __noinline__ void wait_ready(const uint32_t *flag, uint32_t epoch, ui
 // Output gate of Section 4, applied to O before it is stored (kEpi): gate logits [B,T,H,dv] in the
 // input dtype, RMSNorm weight [dv] (NULL = ones) and epsilon.  out_bf16 applies with or without the gate.
 struct EpiParams {
-    const uint16_t *gate;
+    const uint16_t *gate;    // caller's gate logits (read by kda_intra, which stages them)
     const float *norm_w;
     float eps;
     int out_bf16;            // o is stored as bf16 (round to nearest even) instead of fp32
+    const uint8_t *gate_ws;  // staged gate logits: kGateSlotBytes per slot, same order as the slots
 };
 
 // kRole selects what one pass over a range of chunks computes (the time-split scan below):
@@ -844,8 +875,19 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
         const uint32_t u_src = (uint32_t)(kOffU + (P * 4 + c) * kUTileBytes) + lane16;   // U tile (P, c): 2 x 1 KiB
         u32x4 pre[2][kMyUnits];
         u32x4 un[2][2];
-        auto fetch = [&](const uint8_t *src, u32x4 *blk, u32x4 *u) __attribute__((always_inline)) {
+        u32x4 gt[2][2];                                      // kEpi: the wave's tile of staged gate logits
+        const int64_t gate_stride = (int64_t)H * kGateSlotBytes;
+        auto fetch = [&](const int64_t rel, u32x4 *blk, u32x4 *u, u32x4 *g) __attribute__((always_inline)) {
+            const uint8_t *src = slot0 + rel * slot_stride;
             const __amdgpu_buffer_rsrc_t rs = slot_resource(src);
+            if (kEpi) {
+                const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<uint8_t *>(epi.gate_ws + rel * gate_stride), 0, kGateSlotBytes, 0x00020000);
+                const int goff = (P * 4 + c) * kGateTileBytes + (int)lane16;
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    g[i] = kFlags ? slot_load16<kCacheDevice>(rg, goff + i * 1024) : slot_load16<0>(rg, goff + i * 1024);
+            }
             if (kFlags) {    // the slot was written while this kernel runs: device-scope loads
 #pragma unroll
                 for (int i = 0; i < kMyUnits; ++i) {
@@ -890,8 +932,8 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
             const int64_t cf = (c_begin + 2 < c_end) ? 2 : c_end - 1 - c_begin;
             seen = __hip_atomic_load(ready + cf, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        fetch(slot0, pre[0], un[0]);
-        if (c_begin + 1 < c_end) fetch(slot0 + slot_stride, pre[1], un[1]);
+        fetch(0, pre[0], un[0], gt[0]);
+        if (c_begin + 1 < c_end) fetch(1, pre[1], un[1], gt[1]);
         publish(pre[0], 0);
 
         const uint32_t o_rstride = (uint32_t)H * D * 4;      // bytes between consecutive tokens of o
@@ -932,18 +974,14 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                     av[8 * i + 2 * z + 1] = (kRole == kRoleT) ? 0.f : (float)pr[1];
                 }
             // this register set is free now: start fetching chunk ci + 2 into it
-            // kEpi: gate logits of this lane's 16 outputs (token 32 P + x, columns 32 c + 8 q + 4 hh + 0..3).
-            // They go out before the slot loads of chunk ci + 2: loads return in order, and these are
-            // needed within this step
-            u32x2 gate_raw[4];
+            // kEpi: this chunk's gate logits leave their register set before it is refilled;
+            // gate_raw[q4][w] = columns 8 q4 + 4 hh + 2 w, + 1
+            uint32_t gate_raw[4][2];
             if (kEpi) {
-                const int64_t trow = ci * kChunk + 32 * P + x;
-                const uint16_t *gp = epi.gate + ((tok_base + trow) * H + h) * (int64_t)D + 32 * c + 4 * hh;
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const u32x2 z2 = {0u, 0u};
-                    gate_raw[q4] = (trow < len) ? *reinterpret_cast<const u32x2 *>(gp + 8 * q4) : z2;
-                }
+                for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                    for (int w = 0; w < 2; ++w) gate_raw[q4][w] = gt[stage][q4 / 2][(q4 % 2) * 2 + w];
             }
             // (every lane loads the flag, unconditionally and past the end clamped to the last chunk:
             // a fixed number of loads in flight lets the check wait for exactly this one)
@@ -955,7 +993,7 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
             // fixed number of loads in flight behind them, earlier loads can be waited for one by one)
             {
                 const int64_t cf = (ci + 2 < c_end) ? ci + 2 : c_end - 1;
-                fetch(slot0 + (cf - c_begin) * slot_stride, pre[stage], un[stage]);
+                fetch(cf - c_begin, pre[stage], un[stage], gt[stage]);
             }
             // the partner's two d_k tiles of S
 #pragma unroll
@@ -1135,6 +1173,7 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
     // nothing is waited for without flags: leave a clean status word for kda_chunk_fwd_check
     if (!kFlags && status && blockIdx.x == 0 && threadIdx.x == 0) *status = 0;
 
+    if (kEpi) epi.gate_ws += (((int64_t)n * seg_chunks) * H + h) * (int64_t)kGateSlotBytes;   // this pair's first slot
     if (wave < 4)
         kda_scan_body<0, kFlags, kEpi>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base, len, H,
                                        c_begin, c_end, h, flag0, epoch, status, epi);
@@ -1261,7 +1300,7 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
 
     const int64_t st_base = pair_base + 32 * (wave & 3) + (lane & 31);
     const int64_t slot_stride = (int64_t)H * kSlotBytes;
-    const EpiParams no_epi = {nullptr, nullptr, 0.f, out_bf16};
+    const EpiParams no_epi = {nullptr, nullptr, 0.f, out_bf16, nullptr};
 
 #define KDA_SCAN_PART(ROLE)                                                                                       \
     if (wave < 4)                                                                                                 \
@@ -1315,10 +1354,11 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
 }
 
 // flags and status word of the overlapped mode start every call at zero
-__global__ void kda_fill_u32_kernel(uint32_t *p, int64_t n, uint32_t value)
+__global__ void kda_fill_u32_kernel(uint32_t *p, int64_t n, uint32_t value, uint32_t *one_more)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = value;
+    if (i == 0) *one_more = value;
 }
 
 // ----------------------------------------------------------------------------------
@@ -1335,8 +1375,9 @@ static int64_t max_chunks_per_seq(const kda_dims *d)
 
 static size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Workspace: [slots of one segment][state carry][ready flags, one per slot][status word]
-static SegPlan plan_with(const kda_dims *d, int64_t sc)
+// Workspace: [status word, 256 B][slots of one segment][state carry][ready flags, one per slot]
+// [time-split counters and states][staged gate logits]; the last two only when the call can use them.
+static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
 {
     SegPlan p;
     const int64_t maxc = max_chunks_per_seq(d);
@@ -1344,13 +1385,19 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc)
     const size_t carry = streams * D * D * sizeof(float);
     p.seg_chunks = sc;
     p.num_segments = (maxc + sc - 1) / sc;
-    p.carry_offset = (size_t)sc * streams * kSlotBytes;
+    p.status_offset = 0;                                  // the same place whatever the segment size
+    p.slots_offset = 256;
+    p.carry_offset = p.slots_offset + (size_t)sc * streams * kSlotBytes;
     p.flags_offset = p.carry_offset + carry;
-    p.status_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
-    p.split_offset = p.status_offset + 256;
+    p.split_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
     // counters and states of the time-split scan, when the call qualifies for it (single segment only)
     const bool split = sc == maxc && streams <= (size_t)kSplitMaxPairs && maxc >= kSplitMinChunks;
     p.total_bytes = p.split_offset + (split ? kSplitFlagBytes + 3 * (size_t)kSplitMaxParts * carry : 0);
+    p.gate_offset = 0;
+    if (gate) {
+        p.gate_offset = round_up(p.total_bytes, 256);
+        p.total_bytes = p.gate_offset + (size_t)sc * streams * kGateSlotBytes;
+    }
     return p;
 }
 
@@ -1371,22 +1418,22 @@ static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forc
 }
 
 // The plan with the most chunk indices per segment that fits `workspace_bytes` (full: no limit).
-static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full)
+static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full, bool gate)
 {
     const int64_t maxc = max_chunks_per_seq(d);
     int64_t sc = maxc < 1 ? 1 : maxc;
     if (sc > 65535) sc = 65535;                               // grid dimension limit of kda_intra
     if (!full) {
         const size_t streams = (size_t)d->num_seqs * d->heads;
-        const size_t per_chunk_index = streams * (kSlotBytes + sizeof(uint32_t));
-        const size_t fixed = plan_with(d, 1).total_bytes - per_chunk_index;
+        const size_t per_chunk_index = streams * (kSlotBytes + sizeof(uint32_t) + (gate ? kGateSlotBytes : 0));
+        const size_t fixed = plan_with(d, 1, gate).total_bytes - per_chunk_index;
         const size_t avail = workspace_bytes > fixed ? workspace_bytes - fixed : 0;
         const int64_t fit = per_chunk_index ? (int64_t)(avail / per_chunk_index) : sc;
         if (fit < sc) sc = fit;
         if (sc < 1) sc = 1;
-        while (sc > 1 && plan_with(d, sc).total_bytes > workspace_bytes) --sc;   // rounding of the flag area
+        while (sc > 1 && plan_with(d, sc, gate).total_bytes > workspace_bytes) --sc;   // rounding of the flag area
     }
-    return plan_with(d, sc);
+    return plan_with(d, sc, gate);
 }
 
 // Raises the dynamic-LDS limit of the prefill kernels, once per device.
@@ -1466,20 +1513,20 @@ static SideStream *side_stream()
 
 }  // namespace mfma
 
-size_t chunk_mfma_workspace_size(const kda_dims *d, bool minimal)
+size_t chunk_mfma_workspace_size(const kda_dims *d, bool minimal, bool gate)
 {
     if (d->num_seqs == 0 || d->heads == 0 || d->seqlen == 0) return 0;
     if (minimal) {
         // four chunk indices per segment keep the launches from being pure overhead
         const int64_t maxc = mfma::max_chunks_per_seq(d);
-        return mfma::plan_with(d, maxc < 4 ? maxc : 4).total_bytes;
+        return mfma::plan_with(d, maxc < 4 ? maxc : 4, gate).total_bytes;
     }
-    return mfma::make_plan(d, 0, true).total_bytes;
+    return mfma::make_plan(d, 0, true, gate).total_bytes;
 }
 
 size_t chunk_mfma_status_offset(const kda_dims *d, size_t workspace_bytes)
 {
-    return mfma::make_plan(d, workspace_bytes, false).status_offset;
+    return mfma::make_plan(d, workspace_bytes, false, false).status_offset;
 }
 
 kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
@@ -1492,7 +1539,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     RawParams raw = {nullptr, nullptr, 0.f};
     if (pro) { raw.a_scale = pro->a_scale; raw.dt_bias = pro->dt_bias; raw.eps = pro->l2norm_eps; }
     const int out_bf16 = d->out_dtype == KDA_BF16;
-    EpiParams ep = {nullptr, nullptr, 0.f, out_bf16};
+    EpiParams ep = {nullptr, nullptr, 0.f, out_bf16, nullptr};
     if (epi) { ep.gate = static_cast<const uint16_t *>(epi->gate); ep.norm_w = epi->norm_weight; ep.eps = epi->rms_eps; }
     if (d->seqlen == 0) {
         // nothing to scan: the final state is the initial one
@@ -1504,7 +1551,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         }
         return KDA_OK;
     }
-    const SegPlan plan = make_plan(d, workspace_bytes, false);
+    const SegPlan plan = make_plan(d, workspace_bytes, false, epi != nullptr);
     if (plan.total_bytes > workspace_bytes)
         return fail(KDA_ERR_WORKSPACE, "workspace has %zu bytes, segment plan needs %zu", workspace_bytes,
                     plan.total_bytes);
@@ -1516,10 +1563,13 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         return fail(KDA_ERR_LAUNCH, "cannot reserve LDS for the prefill kernels (%d, %d bytes)", kIntraLds,
                     (int)scan_lds);
 
-    uint8_t *ws = static_cast<uint8_t *>(workspace);
-    float *carry = hT ? hT : reinterpret_cast<float *>(ws + plan.carry_offset);
-    uint32_t *flags = reinterpret_cast<uint32_t *>(ws + plan.flags_offset);
-    uint32_t *status = reinterpret_cast<uint32_t *>(ws + plan.status_offset);
+    uint8_t *base = static_cast<uint8_t *>(workspace);
+    uint8_t *ws = base + plan.slots_offset;
+    float *carry = hT ? hT : reinterpret_cast<float *>(base + plan.carry_offset);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(base + plan.flags_offset);
+    uint32_t *status = reinterpret_cast<uint32_t *>(base + plan.status_offset);
+    uint8_t *gate_ws = epi ? base + plan.gate_offset : nullptr;
+    ep.gate_ws = gate_ws;
     const uint16_t *q16 = static_cast<const uint16_t *>(q), *k16 = static_cast<const uint16_t *>(k),
                    *v16 = static_cast<const uint16_t *>(v), *g16 = static_cast<const uint16_t *>(log_alpha),
                    *b16 = static_cast<const uint16_t *>(beta);
@@ -1545,19 +1595,20 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus, g_split) : 1;
 
     if (side || parts > 1) {
-        // the slot flags (overlapped mode), the status word, the counters of the time-split scan
-        uint32_t *first = side ? flags : status;
-        const uint8_t *end = ws + (parts > 1 ? plan.split_offset + kSplitFlagBytes : plan.status_offset + 4);
-        const int64_t nfill = (int64_t)(end - reinterpret_cast<const uint8_t *>(first)) / 4;
-        hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)((nfill + 255) / 256)), dim3(256), 0, stream,
-                           first, nfill, 0u);
+        // the slot flags (overlapped mode), the counters of the time-split scan (they follow the
+        // flags), the status word
+        uint8_t *first = base + (side ? plan.flags_offset : plan.split_offset);
+        const uint8_t *end = base + (parts > 1 ? plan.split_offset + kSplitFlagBytes : plan.split_offset);
+        const int64_t nfill = (int64_t)(end - first) / 4;
+        hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)((nfill + 255) / 256 + 1)), dim3(256), 0, stream,
+                           reinterpret_cast<uint32_t *>(first), nfill, 0u, status);
     }
     if (parts > 1) {
         // Time-split scan (single segment): one launch, kda_intra beside it in the overlapped mode.
         const int64_t part_len = (plan.seg_chunks + parts - 1) / parts;
         const size_t pair_states = (size_t)streams * D * D;
-        uint32_t *split_flags = reinterpret_cast<uint32_t *>(ws + plan.split_offset);
-        float *E = reinterpret_cast<float *>(ws + plan.split_offset + kSplitFlagBytes);
+        uint32_t *split_flags = reinterpret_cast<uint32_t *>(base + plan.split_offset);
+        float *E = reinterpret_cast<float *>(base + plan.split_offset + kSplitFlagBytes);
         float *Tm = E + kSplitMaxParts * pair_states, *Bm = Tm + kSplitMaxParts * pair_states;
         auto intra = side ? (pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>)
                           : (pro ? kda_intra_kernel<false, true> : kda_intra_kernel<false, false>);
@@ -1570,7 +1621,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         } else {
             hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale,
-                               (uint32_t *)nullptr, 0u, raw, 1, 0);
+                               (uint32_t *)nullptr, 0u, raw, 1, 0, ep.gate, gate_ws);
         }
         hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, stream, ws, h0, E,
                            Tm, Bm, hT, cu, o, (int64_t)d->seqlen, (int)d->heads,
@@ -1578,7 +1629,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         if (side) {
             hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale, flags, 1u, raw,
-                               parts, (int)part_len);
+                               parts, (int)part_len, (const uint16_t *)nullptr, (uint8_t *)nullptr);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
@@ -1604,7 +1655,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             auto intra = pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>;
             hipLaunchKernelGGL(intra, intra_grid_overlap,
                                dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
-                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw, 1, 0);
+                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw, 1, 0, ep.gate, gate_ws);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
@@ -1613,7 +1664,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             if (g_phase_mask & 1)
                 hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
                                    (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
-                                   (uint32_t *)nullptr, 0u, raw, 1, 0);
+                                   (uint32_t *)nullptr, 0u, raw, 1, 0, ep.gate, gate_ws);
             auto scan_k = epi ? kda_scan_kernel<false, true> : kda_scan_kernel<false, false>;
             if (g_phase_mask & 2)
                 hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,

@@ -43,6 +43,11 @@ constexpr int kLdsBlockBytes = kOffGc + D * 4;      // what kda_scan stages thro
 constexpr int kUTileBytes = 64 * 16 * 2;            // one 32x32 tile of U: 16 halfs per lane, two 16-byte units
 constexpr int kOffU = kLdsBlockBytes;               // 8 tiles x 2 KiB
 constexpr int kSlotBytes = kOffU + 8 * kUTileBytes; // 72192
+// Output gate (fused epilogue): the gate logits of a chunk, bf16, in the accumulator order of the
+// sequential kernel's O tiles: tile (rho, ct) = [2 units][64 lanes][16 B], lane (x, hh) holds the
+// columns 32 ct + 8 q + 4 hh + 0..3 of token 32 rho + x, q = 0..3 (unit q / 2, bytes 8 (q % 2) ..).
+constexpr int kGateTileBytes = 64 * 16 * 2;
+constexpr int kGateSlotBytes = 8 * kGateTileBytes;  // 16384, one per workspace slot when the gate is on
 
 static_assert(kLdsBlockBytes % 16 == 0, "LDS block must be a whole number of 16-byte units");
 static_assert(kSlotBytes % 256 == 0, "slots must stay 256-byte aligned");
@@ -67,9 +72,11 @@ constexpr size_t kSplitFlagBytes = 4096;     // 24 u32 counters per pair, ahead 
 struct SegPlan {
     int64_t seg_chunks;      // chunks per sequence held in the workspace at once
     int64_t num_segments;    // passes over the time axis
+    size_t slots_offset;     // first slot (the status word sits in front of it)
     size_t carry_offset;     // byte offset of the state carry buffer in the workspace
     size_t flags_offset;     // one u32 "slot ready" flag per (sequence, head, chunk of the segment)
     size_t status_offset;    // u32 set by kda_scan when a bounded wait for a flag ran out
+    size_t gate_offset;      // staged gate logits, kGateSlotBytes per slot (0: no output gate)
     size_t split_offset;     // time-split scan: kSplitFlagBytes of counters, then E, T, B, each [kSplitMaxParts][pairs][128][128] fp32
     size_t total_bytes;
 };

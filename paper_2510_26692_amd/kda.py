@@ -84,6 +84,10 @@ def load_library():
     pp, ep = ctypes.POINTER(KdaPrologue), ctypes.POINTER(KdaEpilogue)
     lib.kda_chunk_fwd_fused.restype = ctypes.c_int
     lib.kda_chunk_fwd_fused.argtypes = [dp, pp, ep, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kda_chunk_fwd_fused_workspace_size.restype = sz
+    lib.kda_chunk_fwd_fused_workspace_size.argtypes = [dp, ep]
+    lib.kda_chunk_fwd_fused_min_workspace_size.restype = sz
+    lib.kda_chunk_fwd_fused_min_workspace_size.argtypes = [dp, ep]
     lib.kda_recurrent_steps_fused.restype = ctypes.c_int
     lib.kda_recurrent_steps_fused.argtypes = [dp, pp, ep, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
@@ -157,12 +161,17 @@ def make_chunk_dims(q, v, cu_seqlens=None, scale=1.0, max_seqlen=0, out_dtype=to
                    max_seqlen=int(max_seqlen))
 
 
-def kda_chunk_fwd_workspace_size(dims):
-    return int(load_library().kda_chunk_fwd_workspace_size(ctypes.byref(dims)))
+def kda_chunk_fwd_workspace_size(dims, output_gate=False):
+    """Bytes for a single-segment call; output_gate=True: for kda_chunk_fwd_fused with an output gate."""
+    if not output_gate:
+        return int(load_library().kda_chunk_fwd_workspace_size(ctypes.byref(dims)))
+    return int(load_library().kda_chunk_fwd_fused_workspace_size(ctypes.byref(dims), ctypes.byref(KdaEpilogue())))
 
 
-def kda_chunk_fwd_min_workspace_size(dims):
-    return int(load_library().kda_chunk_fwd_min_workspace_size(ctypes.byref(dims)))
+def kda_chunk_fwd_min_workspace_size(dims, output_gate=False):
+    if not output_gate:
+        return int(load_library().kda_chunk_fwd_min_workspace_size(ctypes.byref(dims)))
+    return int(load_library().kda_chunk_fwd_fused_min_workspace_size(ctypes.byref(dims), ctypes.byref(KdaEpilogue())))
 
 
 def kda_chunk_fwd_check(dims, workspace):
@@ -245,7 +254,7 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
     if hT is None and want_hT:
         hT = torch.empty(N, H, dk, dv, dtype=torch.float32, device=dev)
     if workspace is None:
-        need = kda_chunk_fwd_workspace_size(dims)
+        need = kda_chunk_fwd_workspace_size(dims, output_gate=_fused is not None and _fused[1] is not None)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev) if need else None
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     tail = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(h0), _ptr(cu_seqlens), _ptr(o),

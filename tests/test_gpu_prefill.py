@@ -239,3 +239,41 @@ def test_bf16_time_split_scan(case, overlap):
     finally:
         kda.kda_debug_set_overlap(1)
         kda.kda_debug_set_time_split(1)
+
+
+def test_bf16_two_host_threads_on_their_own_streams():
+    """Two host threads, each with its own stream, workspace and inputs, call the prefill at the
+    same time (the library keeps one helper stream per host thread and device).  Each result must
+    equal, bit for bit, what the same inputs give when the thread runs alone."""
+    import threading
+    import paper_2510_26692_amd as kda
+    xs = [si.make_prefill(2, 64 * 24 + 13, 4, 128, 128, "bf16", -2.0, 501 + i, 0.02) for i in range(2)]
+    dev = [{k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()} for x in xs]
+
+    def run(d, reps):
+        out = None
+        for _ in range(reps):
+            out = kda.kda_chunk_fwd(d["q"], d["k"], d["v"], d["log_alpha"], d["beta"], h0=d["h0"], check=True)
+        return out
+
+    alone = [run(d, 1) for d in dev]
+    torch.cuda.synchronize()
+    results, errors = [None, None], []
+
+    def worker(i):
+        try:
+            with torch.cuda.stream(torch.cuda.Stream()):
+                results[i] = run(dev[i], 20)
+                torch.cuda.current_stream().synchronize()
+        except Exception as e:                                   # surfaced below, in the test's thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(2):
+        assert torch.equal(results[i][0], alone[i][0]) and torch.equal(results[i][1], alone[i][1])

@@ -26,7 +26,8 @@ def test_every_declared_symbol_is_exported():
             "kda_chunk_fwd_min_workspace_size", "kda_status_string", "kda_last_error",
             "kda_version", "kda_debug_set_phase_mask", "kda_debug_set_overlap",
             "kda_chunk_fwd_check", "kda_recurrent_steps_pooled", "kda_chunk_fwd_fused",
-            "kda_recurrent_steps_fused"} <= names
+            "kda_recurrent_steps_fused", "kda_chunk_fwd_fused_workspace_size",
+            "kda_chunk_fwd_fused_min_workspace_size", "kda_debug_set_time_split"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
@@ -55,6 +56,11 @@ def test_workspace_sizes_are_consistent():
     slots = 4 * 16 * (4096 // 64)
     fixed = full - slots * (72192 + 4) - 4 * 16 * 128 * 128 * 4
     assert 256 <= fixed <= 512
+    # with the output gate: 16 KiB of staged gate logits per slot on top
+    gated = kda.kda_chunk_fwd_workspace_size(d, output_gate=True)
+    assert 0 <= gated - full - slots * 16384 < 256
+    assert kda.kda_chunk_fwd_min_workspace_size(d, output_gate=True) > small
+    assert lib.kda_chunk_fwd_fused_workspace_size(ctypes.byref(d), None) == full
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, in_dtype=0)) == 0          # fp32 path
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, dk=96, dv=96)) == 0        # unsupported
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, seqlen=0)) == 0
