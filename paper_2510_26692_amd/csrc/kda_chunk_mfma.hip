@@ -1579,8 +1579,11 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
 
     // Overlapped mode: kda_intra runs on a helper stream while kda_scan, on the caller's stream,
     // consumes each slot as soon as its flag is up.  kda_scan keeps one compute unit per
-    // (sequence, head) busy, so this needs enough units left over for kda_intra to make progress
-    // (it never waits for anything, which is what rules out a deadlock).
+    // (sequence, head) busy for the whole call, and kda_intra, the larger half of the work, has
+    // to live on the rest (it never waits for anything, which is what rules out a deadlock):
+    // measured on 64 to 192 pairs, running side by side wins up to a third of the compute units
+    // (80 pairs of 256: 0.38 against 0.40 ms) and loses beyond (96: 0.45 against 0.44 ms; 192:
+    // 1.54 against 0.69 ms), where the kernels run one after the other.
     // Not while the caller's stream is being captured into a graph: a captured kda_scan could be
     // replayed by a runtime that does not start the other branch at the same time.
     SideStream *side = nullptr;
@@ -1590,7 +1593,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     if (cus <= 0) return fail(KDA_ERR_LAUNCH, "cannot query the device");
     if (g_phase_mask == 3 && g_overlap && capture == hipStreamCaptureStatusNone) {
         side = side_stream();
-        if (side && (int64_t)streams * 4 > (int64_t)cus * 3) side = nullptr;
+        if (side && (int64_t)streams * 3 > (int64_t)cus) side = nullptr;
     }
     const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus, g_split) : 1;
 
