@@ -1545,8 +1545,17 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         // nothing to scan: the final state is the initial one
         if (hT && hT != h0) {
             const size_t bytes = (size_t)d->num_seqs * d->heads * D * D * sizeof(float);
-            hipError_t e = h0 ? hipMemcpyAsync(hT, h0, bytes, hipMemcpyDeviceToDevice, stream)
-                              : hipMemsetAsync(hT, 0, bytes, stream);
+            hipError_t e = hipSuccess;
+            if (h0) {
+                e = hipMemcpyAsync(hT, h0, bytes, hipMemcpyDeviceToDevice, stream);
+            } else {
+                // (a fill kernel rather than a memset: the call may be captured into a graph)
+                const int64_t words = (int64_t)(bytes / 4);
+                uint32_t *dst = reinterpret_cast<uint32_t *>(hT);
+                hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, dst,
+                                   words, 0u, dst);
+                e = hipGetLastError();
+            }
             if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "state copy: %s", hipGetErrorString(e));
         }
         return KDA_OK;

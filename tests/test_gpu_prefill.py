@@ -277,3 +277,16 @@ def test_bf16_two_host_threads_on_their_own_streams():
     assert not errors, errors
     for i in range(2):
         assert torch.equal(results[i][0], alone[i][0]) and torch.equal(results[i][1], alone[i][1])
+
+
+@pytest.mark.parametrize("with_h0", [True, False])
+def test_bf16_zero_tokens_returns_the_initial_state(with_h0):
+    import paper_2510_26692_amd as kda
+    B, H, d = 2, 3, 128
+    z = lambda *shape: torch.empty(*shape, dtype=torch.bfloat16, device="cuda")
+    h0 = si.make_state(B, H, d, d, 0.5, 601).cuda() if with_h0 else None
+    hT = torch.full((B, H, d, d), 7.0, device="cuda")
+    o, hT = kda.kda_chunk_fwd(z(B, 0, H, d), z(B, 0, H, d), z(B, 0, H, d), z(B, 0, H, d), z(B, 0, H), h0=h0, hT=hT)
+    torch.cuda.synchronize()
+    assert o.numel() == 0
+    assert torch.equal(hT, h0 if with_h0 else torch.zeros_like(hT))
