@@ -286,7 +286,10 @@ void kda_debug_set_overlap(int enabled);
  * (sequence, head); 1 (default) lets calls with few pairs and long sequences cut the chunk axis into
  * ranges that several workgroups walk at the same time (the chunk recurrence is affine in the state,
  * S_out = T S_in + B, so a range's T and B can be formed before its initial state is known).  Results
- * agree within rounding, not bit for bit.  A value of 3..8 asks for that many ranges where the
+ * agree within rounding, not bit for bit.  The workgroups of such a launch wait for one another
+ * (first the ranges' transitions, then the folded states), again for a bounded time that
+ * kda_chunk_fwd_check reports; they all fit the device at once, so every wait ends, also under
+ * tools that run one kernel at a time.  A value of 3..8 asks for that many ranges where the
  * library would have chosen the number itself (it is still lowered to what the device and the
  * sequence length allow).  KDA_PREFILL_TIME_SPLIT=0 in the environment sets the default to 0.
  * Process-wide, not thread-safe.
