@@ -1566,6 +1566,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                     plan.total_bytes);
     if (d->num_seqs > 65535)
         return fail(KDA_ERR_UNSUPPORTED, "more than 65535 sequences in one call: %d", d->num_seqs);
+    if ((int64_t)d->num_seqs * d->heads > 0x7fffffffLL)
+        return fail(KDA_ERR_UNSUPPORTED, "num_seqs * heads exceeds 2^31 - 1");
 
     const size_t scan_lds = (size_t)scan::kLds;
     if (!reserve_lds())
@@ -1582,7 +1584,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     const uint16_t *q16 = static_cast<const uint16_t *>(q), *k16 = static_cast<const uint16_t *>(k),
                    *v16 = static_cast<const uint16_t *>(v), *g16 = static_cast<const uint16_t *>(log_alpha),
                    *b16 = static_cast<const uint16_t *>(beta);
-    const unsigned streams = (unsigned)(d->num_seqs * d->heads);
+    const unsigned streams = (unsigned)((int64_t)d->num_seqs * d->heads);
     const dim3 intra_grid_serial((unsigned)d->heads, (unsigned)plan.seg_chunks, (unsigned)d->num_seqs);
     const dim3 intra_grid_overlap((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)plan.seg_chunks);
 
