@@ -289,9 +289,10 @@ void kda_debug_set_overlap(int enabled);
  * agree within rounding, not bit for bit.  The workgroups of such a launch wait for one another
  * (first the ranges' transitions, then the folded states), again for a bounded time that
  * kda_chunk_fwd_check reports; they all fit the device at once, so every wait ends, also under
- * tools that run one kernel at a time.  A value of 3..8 asks for that many ranges where the
- * library would have chosen the number itself (it is still lowered to what the device and the
- * sequence length allow).  KDA_PREFILL_TIME_SPLIT=0 in the environment sets the default to 0.
+ * tools that run one kernel at a time.  With 1 the library estimates whether, and into how many
+ * ranges, a call is worth splitting; a value of 3..8 takes that many ranges whatever the estimate
+ * says (still lowered to what the device and the sequence length allow; calls with fewer than 24
+ * chunks are never split).  KDA_PREFILL_TIME_SPLIT=0 in the environment sets the default to 0.
  * Process-wide, not thread-safe.
  */
 void kda_debug_set_time_split(int mode);

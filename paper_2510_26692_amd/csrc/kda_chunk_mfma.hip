@@ -1403,17 +1403,38 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
 
 // Number of ranges for the time-split scan (1 = plain scan).  The launch keeps 2 parts - 3 compute
 // units per pair busy; it gets at most three eighths of the device, so that kda_intra, which runs
-// beside it and is the larger half of the work, keeps the rest (measured on 2 to 40 pairs: the
-// best number of ranges is the largest one under that limit, and beyond it the plain scan wins).
+// beside it and is the larger half of the work, keeps the rest (measured on 2 to 40 pairs: beyond
+// that limit the plain scan wins).  Among the admissible numbers the one with the smallest
+// estimated duration is taken, the plain scan included.  The estimate (microseconds; constants
+// measured on MI355X): a step of the scan 2.85, a chunk of kda_intra 9.5 on one compute unit, the
+// fold and the extra start-up of a split launch 60 + 12 per middle range.  The first phase needs
+// the first parts - 1 ranges produced, the last range one more phase after everything before it.
+// forced = 3..8: the largest admissible number up to `forced`, whatever the estimate says.
 static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forced)
 {
     const int64_t maxc = max_chunks_per_seq(d);
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
-    if (plan.num_segments != 1 || pairs > kSplitMaxPairs || maxc < kSplitMinChunks) return 1;
+    if (plan.num_segments != 1 || pairs > kSplitMaxPairs || maxc < kSplitMinChunks || pairs >= cus) return 1;
+    const double step = 2.85, item = 9.5;
+    const double items = (double)pairs * (double)maxc;
+    const double t_scan = (double)maxc * step, t_intra1 = items * item / (double)(cus - pairs);
+    double best = t_scan > t_intra1 ? t_scan : t_intra1;
     int parts = 1;
-    for (int p = 3; p <= kSplitMaxParts; ++p)
-        if (pairs * (2 * p - 3) * 8 <= (int64_t)cus * 3 && (maxc + p - 1) / p >= 16 && (forced < 3 || p <= forced))
-            parts = p;
+    for (int p = 3; p <= kSplitMaxParts; ++p) {
+        const int64_t len = (maxc + p - 1) / p;
+        if (pairs * (2 * p - 3) * 8 > (int64_t)cus * 3 || len < 8) continue;
+        if (forced >= 3) {
+            if (p <= forced) parts = p;
+            continue;
+        }
+        const double phase = (double)len * step;
+        const double t_intra = items * item / (double)(cus - pairs * (2 * p - 3));
+        const double fed = t_intra * (double)(p - 1) / (double)p;
+        const double t1 = phase > fed ? phase : fed;
+        double t = t1 + 60.0 + 12.0 * (p - 2) + phase;
+        if (t_intra + 2 * step > t) t = t_intra + 2 * step;
+        if (t < best) { best = t; parts = p; }
+    }
     return parts;
 }
 

@@ -65,7 +65,7 @@ constexpr int frag_aqk(int rr, int ri, int s) { return (rr + ri) * 2 + s; }   //
 // (sequence, head) pairs whose longest sequence has at least kSplitMinChunks chunks.
 constexpr int kSplitMaxParts = 8;
 constexpr int kSplitMaxPairs = 42;
-constexpr int kSplitMinChunks = 48;
+constexpr int kSplitMinChunks = 24;
 constexpr size_t kSplitFlagBytes = 4096;     // 24 u32 counters per pair, ahead of the states
 
 // Geometry of one launch pair: `seg_chunks` chunk indices of every sequence.

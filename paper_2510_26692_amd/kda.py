@@ -111,7 +111,8 @@ def kda_debug_set_overlap(enabled):
 
 
 def kda_debug_set_time_split(mode):
-    """0 = off, 1 = on (the library picks the number of ranges), 3..8 = at most that many ranges."""
+    """0 = off, 1 = on (the library estimates whether and how far to split), 3..8 = that many ranges
+    (at most) whatever the estimate says."""
     load_library().kda_debug_set_time_split(int(mode))
 
 

@@ -44,9 +44,12 @@ def test_prefill_bf16_output_is_the_rounded_fp32_output(case):
     try:
         if case == "serial_kernels":
             kda.kda_debug_set_overlap(0)
+        if case == "time_split":
+            kda.kda_debug_set_time_split(8)                  # split for sure
         o16, h16, o32, h32 = _prefill_both(x)
     finally:
         kda.kda_debug_set_overlap(1)
+        kda.kda_debug_set_time_split(1)
     assert torch.equal(o16, o32.to(torch.bfloat16))
     assert torch.equal(h16, h32)
     o_ref, _ = oracle_prefill(x)

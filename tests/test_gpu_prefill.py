@@ -221,7 +221,7 @@ def test_bf16_time_split_scan(case, overlap):
         x = si.make_varlen(np.array([64 * 130, 3001, 100, 0]), 1, 128, 128, "bf16", -2.0, 303, 0.05)
     try:
         kda.kda_debug_set_overlap(overlap)
-        kda.kda_debug_set_time_split(1)
+        kda.kda_debug_set_time_split(8)                      # split for sure, into as many ranges as fit
         eo, eh = check_prefill(x, TOL_BF16)
         dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
         o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
