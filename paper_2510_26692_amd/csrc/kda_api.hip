@@ -53,6 +53,15 @@ static int split_default()
     return (e && e[0] == '0' && e[1] == 0) ? 0 : 1;
 }
 int g_split = split_default();
+// development switch: length of the first range of the time-split scan relative to the others
+// (0 = chosen per call)
+static double split_ratio_default()
+{
+    const char *e = getenv("KDA_PREFILL_SPLIT_RATIO");
+    const double r = e ? atof(e) : 0.0;
+    return (r >= 0.2 && r <= 1.0) ? r : 0.0;
+}
+double g_split_ratio = split_ratio_default();
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -39,6 +39,7 @@ namespace kda {
 extern int g_phase_mask;   // diagnostics switches owned by kda_api.hip
 extern int g_overlap;
 extern int g_split;
+extern double g_split_ratio;
 
 namespace mfma {
 
@@ -154,7 +155,8 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
                       uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
                       int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch, RawParams raw,
-                      int parts, int part_len, const uint16_t *__restrict__ out_gate, uint8_t *__restrict__ gate_ws)
+                      int parts, int part_len, int part0_len, const uint16_t *__restrict__ out_gate,
+                      uint8_t *__restrict__ gate_ws)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -166,13 +168,19 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     // otherwise y = chunk and z = sequence (consecutive workgroups write consecutive slots).
     const int h = (int)blockIdx.x;
     const int n = (int)(kHandoff ? blockIdx.y : blockIdx.z);
-    // (when the scan is time-split into `parts` ranges of `part_len` chunks, its first pass walks
-    // all ranges but the last side by side, so the chunk order interleaves those and lets the last
-    // range follow)
+    // (when the scan is time-split into `parts` ranges -- the first of `part0_len` chunks, the others
+    // of `part_len` -- its first phase walks all ranges but the last side by side, so the chunk
+    // order interleaves those and lets the last range follow)
     int64_t cl = kHandoff ? blockIdx.z : blockIdx.y;
     if (kHandoff && parts > 1) {
         const unsigned first = (unsigned)(parts - 1), z = blockIdx.z;
-        if (z < first * (unsigned)part_len) cl = (int64_t)(z % first) * part_len + z / first;
+        if (z < first * (unsigned)part_len) {
+            const unsigned r = z % first, j = z / first;
+            if (r == 0 && j >= (unsigned)part0_len) return;  // the first range is the shorter one
+            cl = (r == 0) ? (int64_t)j : (int64_t)part0_len + (int64_t)(r - 1) * part_len + j;
+        } else {
+            cl = (int64_t)part0_len + (int64_t)(first - 1) * part_len + (z - first * (unsigned)part_len);
+        }
     }
     if (cl >= seg_chunks) return;
     const int64_t slot = n * seg_chunks + cl;
@@ -877,6 +885,13 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
         u32x4 un[2][2];
         u32x4 gt[2][2];                                      // kEpi: the wave's tile of staged gate logits
         const int64_t gate_stride = (int64_t)H * kGateSlotBytes;
+        // The transition and offset passes of the time-split scan write no output: they leave
+        // Gamma.Q (units 1024 .. 2047: i = 2, 3) and A_qk (the units of i = 6 below gamma^C) where
+        // they are, and the transition pass U as well.
+        static_assert(kOffQp == 2 * 512 * 16 && kOffKt == 4 * 512 * 16 && kOffAqk == 6 * 512 * 16, "unit ranges of the skipped operands");
+        auto wanted = [&](const int i, const int unit) __attribute__((always_inline)) {
+            return kRole == kRoleFull || !(i == 2 || i == 3 || (i == 6 && unit * 16 < kOffGc));
+        };
         auto fetch = [&](const int64_t rel, u32x4 *blk, u32x4 *u, u32x4 *g) __attribute__((always_inline)) {
             const uint8_t *src = slot0 + rel * slot_stride;
             const __amdgpu_buffer_rsrc_t rs = slot_resource(src);
@@ -888,29 +903,24 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                 for (int i = 0; i < 2; ++i)
                     g[i] = kFlags ? slot_load16<kCacheDevice>(rg, goff + i * 1024) : slot_load16<0>(rg, goff + i * 1024);
             }
-            if (kFlags) {    // the slot was written while this kernel runs: device-scope loads
+            // (kFlags: the slot was written while this kernel runs, hence device-scope loads)
+            constexpr int kPol = kFlags ? kCacheDevice : 0;
 #pragma unroll
-                for (int i = 0; i < kMyUnits; ++i) {
-                    const int unit = tid + i * 512;
-                    if (unit < kUnits) blk[i] = slot_load16<kCacheDevice>(rs, unit * 16);
-                }
+            for (int i = 0; i < kMyUnits; ++i) {
+                const int unit = tid + i * 512;
+                if (unit < kUnits && wanted(i, unit)) blk[i] = slot_load16<kPol>(rs, unit * 16);
+            }
+            if (kRole != kRoleT) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i) u[i] = slot_load16<kCacheDevice>(rs, (int)u_src + i * 1024);
-            } else {
-#pragma unroll
-                for (int i = 0; i < kMyUnits; ++i) {
-                    const int unit = tid + i * 512;
-                    if (unit < kUnits) blk[i] = slot_load16<0>(rs, unit * 16);
-                }
-#pragma unroll
-                for (int i = 0; i < 2; ++i) u[i] = slot_load16<0>(rs, (int)u_src + i * 1024);
+                for (int i = 0; i < 2; ++i) u[i] = slot_load16<kPol>(rs, (int)u_src + i * 1024);
             }
         };
         auto publish = [&](const u32x4 *blk, int stage) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < kMyUnits; ++i) {
                 const int unit = tid + i * 512;
-                if (unit < kUnits) *reinterpret_cast<u32x4 *>(lds + stage * kLdsBlockBytes + unit * 16) = blk[i];
+                if (unit < kUnits && wanted(i, unit))
+                    *reinterpret_cast<u32x4 *>(lds + stage * kLdsBlockBytes + unit * 16) = blk[i];
             }
         };
         // With kFlags the slots are produced while this kernel runs: lane 0 of the workgroup
@@ -1020,7 +1030,7 @@ __device__ __forceinline__ void kda_scan_body(uint8_t *lds, const uint8_t *slot0
                     sg[4 * q4 + 2 * w] = nw.x * __builtin_amdgcn_rcpf(1.f + fast_exp2(-g0 * kLog2e));
                     sg[4 * q4 + 2 * w + 1] = nw.y * __builtin_amdgcn_rcpf(1.f + fast_exp2(-g1 * kLog2e));
                 }
-                if constexpr (i + LA < NS)
+                if constexpr (i + LA < NS && (kRole == kRoleFull || !((i + LA >= 8 && i + LA < 16) || i + LA >= 24)))
                     ring[(i + LA) % RING] = *reinterpret_cast<const h8 *>(cur + slot_lds_offset<P>(i + LA));
                 const h8 a = ring[i % RING];
                 if constexpr (i < 8) {
@@ -1182,8 +1192,10 @@ void kda_scan_kernel(const uint8_t *__restrict__ ws, const float *state_in, floa
                                        c_begin, c_end, h, flag0, epoch, status, epi);
 }
 
-// Time-split scan for few (sequence, head) pairs: the chunk axis is cut into `parts` ranges of
-// `part_len` chunk indices, and 2 parts - 3 workgroups work on one pair side by side, in one launch.
+// Time-split scan for few (sequence, head) pairs: the chunk axis is cut into `parts` ranges, the
+// first of `part0_len` chunk indices and the others of `part_len` (the first range is walked by the
+// full scan, which is slower per step than the transition and offset passes of the other ranges,
+// so it is made shorter), and 2 parts - 3 workgroups work on one pair side by side, in one launch.
 //   blockIdx.y = 0              scans range 0 from h0 (outputs and all) and leaves its final state
 //                               in E[0]; later it scans the last range from E[parts - 2] and
 //                               delivers the final state.
@@ -1276,7 +1288,7 @@ template <bool kFlags>
 __global__ __launch_bounds__(512)
 void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, float *E, float *Tm, float *Bm,
                            float *state_final, const int32_t *__restrict__ cu_seqlens, void *__restrict__ o,
-                           int64_t T, int H, int64_t seg_chunks, int64_t part_len, int parts,
+                           int64_t T, int H, int64_t seg_chunks, int64_t part_len, int64_t part0_len, int parts,
                            const uint32_t *ready, uint32_t epoch, uint32_t *status, uint32_t *split_flags,
                            int out_bf16)
 {
@@ -1312,7 +1324,8 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
     {   // first phase: the own range, from h0 / the identity / zero
         const float *state_in = (y == 0) ? h0 : nullptr;
         float *state_out = (y == 0) ? E : (kind == kRoleT ? Tm : Bm) + mid * pair_states;
-        int64_t c_begin = mid * part_len, c_end = c_begin + part_len;
+        int64_t c_begin = (mid == 0) ? 0 : part0_len + (mid - 1) * part_len;
+        int64_t c_end = c_begin + ((mid == 0) ? part0_len : part_len);
         if (c_begin > nchunks) c_begin = nchunks;
         if (c_end > nchunks) c_end = nchunks;
         const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kSlotBytes;
@@ -1343,7 +1356,7 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
         if (threadIdx.x == 0) wait_ready(pf + part - 1, (uint32_t)workers, status, gave_up);
         __syncthreads();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        int64_t c_begin = part * part_len, c_end = c_begin + part_len;
+        int64_t c_begin = part0_len + (part - 1) * part_len, c_end = c_begin + part_len;   // part >= 1 here
         if (c_begin > nchunks) c_begin = nchunks;
         if (c_end > nchunks) c_end = nchunks;
         const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kSlotBytes;
@@ -1410,8 +1423,9 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
 // fold and the extra start-up of a split launch 60 + 12 per middle range.  The first phase needs
 // the first parts - 1 ranges produced, the last range one more phase after everything before it.
 // forced = 3..8: the largest admissible number up to `forced`, whatever the estimate says.
-static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forced)
+static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forced, double *first_ratio)
 {
+    *first_ratio = 1.0;
     const int64_t maxc = max_chunks_per_seq(d);
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
     if (plan.num_segments != 1 || pairs > kSplitMaxPairs || maxc < kSplitMinChunks || pairs >= cus) return 1;
@@ -1423,17 +1437,22 @@ static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forc
     for (int p = 3; p <= kSplitMaxParts; ++p) {
         const int64_t len = (maxc + p - 1) / p;
         if (pairs * (2 * p - 3) * 8 > (int64_t)cus * 3 || len < 8) continue;
-        if (forced >= 3) {
-            if (p <= forced) parts = p;
-            continue;
-        }
         const double phase = (double)len * step;
         const double t_intra = items * item / (double)(cus - pairs * (2 * p - 3));
         const double fed = t_intra * (double)(p - 1) / (double)p;
+        // The first range is walked by the full scan, the others by passes that write no output and
+        // fetch less, about 0.7 of its time per step: when the scan, not kda_intra, sets the pace
+        // of the first phase, the first range is made shorter by that ratio (measured: 7-9 % on 2
+        // and 4 pairs; a loss where kda_intra is the bound, because the other ranges grow).
+        const double ratio = (phase >= 1.5 * fed) ? 0.7 : 1.0;
+        if (forced >= 3) {
+            if (p <= forced) { parts = p; *first_ratio = ratio; }
+            continue;
+        }
         const double t1 = phase > fed ? phase : fed;
         double t = t1 + 60.0 + 12.0 * (p - 2) + phase;
         if (t_intra + 2 * step > t) t = t_intra + 2 * step;
-        if (t < best) { best = t; parts = p; }
+        if (t < best) { best = t; parts = p; *first_ratio = ratio; }
     }
     return parts;
 }
@@ -1627,7 +1646,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         side = side_stream();
         if (side && (int64_t)streams * 3 > (int64_t)cus) side = nullptr;
     }
-    const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus, g_split) : 1;
+    double first_ratio = 1.0;
+    const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus, g_split, &first_ratio) : 1;
 
     if (side || parts > 1) {
         // the slot flags (overlapped mode), the counters of the time-split scan (they follow the
@@ -1640,7 +1660,11 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     }
     if (parts > 1) {
         // Time-split scan (single segment): one launch, kda_intra beside it in the overlapped mode.
-        const int64_t part_len = (plan.seg_chunks + parts - 1) / parts;
+        // ranges: the first one shorter by the ratio of the step times (full scan : passes without output)
+        const double ratio = (g_split_ratio > 0.0) ? g_split_ratio : first_ratio;
+        int64_t part0_len = (int64_t)((double)plan.seg_chunks * ratio / ((double)(parts - 1) + ratio) + 0.5);
+        if (part0_len < 1) part0_len = 1;
+        const int64_t part_len = (plan.seg_chunks - part0_len + parts - 2) / (parts - 1);
         const size_t pair_states = (size_t)streams * D * D;
         uint32_t *split_flags = reinterpret_cast<uint32_t *>(base + plan.split_offset);
         float *E = reinterpret_cast<float *>(base + plan.split_offset + kSplitFlagBytes);
@@ -1648,7 +1672,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         auto intra = side ? (pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>)
                           : (pro ? kda_intra_kernel<false, true> : kda_intra_kernel<false, false>);
         auto split_k = side ? kda_scan_split_kernel<true> : kda_scan_split_kernel<false>;
-        const dim3 intra_grid_split((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)(parts * part_len));
+        const dim3 intra_grid_split((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)(parts * part_len));   // z: see kda_intra
         if (side) {
             if (hipEventRecord(side->fork, stream) != hipSuccess ||
                 hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
@@ -1656,15 +1680,15 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         } else {
             hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale,
-                               (uint32_t *)nullptr, 0u, raw, 1, 0, ep.gate, gate_ws);
+                               (uint32_t *)nullptr, 0u, raw, 1, 0, 0, ep.gate, gate_ws);
         }
         hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, stream, ws, h0, E,
                            Tm, Bm, hT, cu, o, (int64_t)d->seqlen, (int)d->heads,
-                           plan.seg_chunks, part_len, parts, flags, 1u, status, split_flags, out_bf16);
+                           plan.seg_chunks, part_len, part0_len, parts, flags, 1u, status, split_flags, out_bf16);
         if (side) {
             hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale, flags, 1u, raw,
-                               parts, (int)part_len, (const uint16_t *)nullptr, (uint8_t *)nullptr);
+                               parts, (int)part_len, (int)part0_len, (const uint16_t *)nullptr, (uint8_t *)nullptr);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
@@ -1690,7 +1714,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             auto intra = pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>;
             hipLaunchKernelGGL(intra, intra_grid_overlap,
                                dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
-                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw, 1, 0, ep.gate, gate_ws);
+                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw, 1, 0, 0, ep.gate, gate_ws);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
@@ -1699,7 +1723,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             if (g_phase_mask & 1)
                 hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
                                    (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
-                                   (uint32_t *)nullptr, 0u, raw, 1, 0, ep.gate, gate_ws);
+                                   (uint32_t *)nullptr, 0u, raw, 1, 0, 0, ep.gate, gate_ws);
             auto scan_k = epi ? kda_scan_kernel<false, true> : kda_scan_kernel<false, false>;
             if (g_phase_mask & 2)
                 hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
