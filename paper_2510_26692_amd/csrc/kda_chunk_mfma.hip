@@ -1284,13 +1284,13 @@ __device__ __forceinline__ void kda_fold_slices(float *sE, float *E, const float
     }
 }
 
-template <bool kFlags>
+template <bool kFlags, bool kEpi>
 __global__ __launch_bounds__(512)
 void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, float *E, float *Tm, float *Bm,
                            float *state_final, const int32_t *__restrict__ cu_seqlens, void *__restrict__ o,
                            int64_t T, int H, int64_t seg_chunks, int64_t part_len, int64_t part0_len, int parts,
                            const uint32_t *ready, uint32_t epoch, uint32_t *status, uint32_t *split_flags,
-                           int out_bf16)
+                           EpiParams epi)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1312,15 +1312,19 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
 
     const int64_t st_base = pair_base + 32 * (wave & 3) + (lane & 31);
     const int64_t slot_stride = (int64_t)H * kSlotBytes;
-    const EpiParams no_epi = {nullptr, nullptr, 0.f, out_bf16, nullptr};
+    if (kEpi && threadIdx.x < D)     // RMSNorm weights of the output gate (beyond what the fold uses of the LDS)
+        reinterpret_cast<float *>(lds + scan::kNormW)[threadIdx.x] = epi.norm_w ? epi.norm_w[threadIdx.x] : 1.f;
+    const uint8_t *gate_base = epi.gate_ws;
 
-#define KDA_SCAN_PART(ROLE)                                                                                       \
+    // (the output gate concerns the full scan only; the passes without output ignore it)
+#define KDA_SCAN_PART(ROLE, EPI)                                                                                  \
+    if (EPI) epi.gate_ws = gate_base + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kGateSlotBytes;   \
     if (wave < 4)                                                                                                 \
-        kda_scan_body<0, kFlags, false, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,  \
-                                              len, H, c_begin, c_end, h, flag0, epoch, status, no_epi);           \
+        kda_scan_body<0, kFlags, EPI, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,   \
+                                            len, H, c_begin, c_end, h, flag0, epoch, status, epi);                \
     else                                                                                                          \
-        kda_scan_body<1, kFlags, false, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,  \
-                                              len, H, c_begin, c_end, h, flag0, epoch, status, no_epi)
+        kda_scan_body<1, kFlags, EPI, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,   \
+                                            len, H, c_begin, c_end, h, flag0, epoch, status, epi)
     {   // first phase: the own range, from h0 / the identity / zero
         const float *state_in = (y == 0) ? h0 : nullptr;
         float *state_out = (y == 0) ? E : (kind == kRoleT ? Tm : Bm) + mid * pair_states;
@@ -1330,9 +1334,9 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
         if (c_end > nchunks) c_end = nchunks;
         const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kSlotBytes;
         const uint32_t *flag0 = kFlags ? ready + (int64_t)blockIdx.x * seg_chunks + c_begin : nullptr;
-        if (kind == kRoleFull) { KDA_SCAN_PART(kRoleFull); }
-        else if (kind == kRoleT) { KDA_SCAN_PART(kRoleT); }
-        else { KDA_SCAN_PART(kRoleB); }
+        if (kind == kRoleFull) { KDA_SCAN_PART(kRoleFull, kEpi); }
+        else if (kind == kRoleT) { KDA_SCAN_PART(kRoleT, false); }
+        else { KDA_SCAN_PART(kRoleB, false); }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -1361,7 +1365,7 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
         if (c_end > nchunks) c_end = nchunks;
         const uint8_t *slot0 = ws + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kSlotBytes;
         const uint32_t *flag0 = kFlags ? ready + (int64_t)blockIdx.x * seg_chunks + c_begin : nullptr;
-        KDA_SCAN_PART(kRoleFull);
+        KDA_SCAN_PART(kRoleFull, kEpi);
     }
 #undef KDA_SCAN_PART
 }
@@ -1502,9 +1506,13 @@ static bool reserve_lds()
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_split_kernel<false>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_split_kernel<false, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_split_kernel<true>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_split_kernel<true, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_split_kernel<false, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_split_kernel<true, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess;
     if (!ok) (void)hipGetLastError();
     done[dev] = ok;
@@ -1647,7 +1655,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         if (side && (int64_t)streams * 3 > (int64_t)cus) side = nullptr;
     }
     double first_ratio = 1.0;
-    const int parts = (!epi && g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus, g_split, &first_ratio) : 1;
+    const int parts = (g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus, g_split, &first_ratio) : 1;
 
     if (side || parts > 1) {
         // the slot flags (overlapped mode), the counters of the time-split scan (they follow the
@@ -1671,7 +1679,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         float *Tm = E + kSplitMaxParts * pair_states, *Bm = Tm + kSplitMaxParts * pair_states;
         auto intra = side ? (pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>)
                           : (pro ? kda_intra_kernel<false, true> : kda_intra_kernel<false, false>);
-        auto split_k = side ? kda_scan_split_kernel<true> : kda_scan_split_kernel<false>;
+        auto split_k = side ? (epi ? kda_scan_split_kernel<true, true> : kda_scan_split_kernel<true, false>)
+                            : (epi ? kda_scan_split_kernel<false, true> : kda_scan_split_kernel<false, false>);
         const dim3 intra_grid_split((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)(parts * part_len));   // z: see kda_intra
         if (side) {
             if (hipEventRecord(side->fork, stream) != hipSuccess ||
@@ -1684,11 +1693,11 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         }
         hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, stream, ws, h0, E,
                            Tm, Bm, hT, cu, o, (int64_t)d->seqlen, (int)d->heads,
-                           plan.seg_chunks, part_len, part0_len, parts, flags, 1u, status, split_flags, out_bf16);
+                           plan.seg_chunks, part_len, part0_len, parts, flags, 1u, status, split_flags, ep);
         if (side) {
             hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale, flags, 1u, raw,
-                               parts, (int)part_len, (int)part0_len, (const uint16_t *)nullptr, (uint8_t *)nullptr);
+                               parts, (int)part_len, (int)part0_len, ep.gate, gate_ws);
             if (hipEventRecord(side->join, side->stream) != hipSuccess ||
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));

@@ -163,3 +163,35 @@ def test_decode_output_gate(dtype, tol, d):
     eS = worst_slice_err(S.cpu().numpy(), S_ref, state_slices(N, H))
     print("output gate decode %s: err_o %.2e err_S %.2e" % (dtype, eo, eS))
     assert eo <= tol and eS <= tol
+
+
+@pytest.mark.parametrize("overlap", [1, 0])
+def test_prefill_output_gate_with_the_time_split_scan(overlap):
+    """Few pairs and a long sequence: the sequential kernel cuts the time axis into ranges; the full
+    scans of the ranges apply the output gate, the passes without output ignore it."""
+    import paper_2510_26692_amd as kda
+    H, d, T = 2, 128, 64 * 60 - 11
+    og, w = _out_gate((1, T, H, d), "bf16", 91)
+    x = si.make_tokens(1, T, H, d, d, "bf16", -6.0, 93)
+    names = ("q", "k", "v", "log_alpha", "beta")
+    o_plain, h_ref = oracle.kda_forward(*_np(x, *names), scale=0.5)
+    o_ref = oracle.epilogue.apply(o_plain, si.to_np32(og), w.numpy(), 1e-5)
+    g = {k_: v_.cuda() for k_, v_ in x.items() if isinstance(v_, torch.Tensor)}
+    outs = []
+    try:
+        kda.kda_debug_set_overlap(overlap)
+        for mode in (8, 0):                                  # split for sure / never
+            kda.kda_debug_set_time_split(mode)
+            outs.append(kda.kda_chunk_fwd_fused(*[g[n_] for n_ in names], prologue=False, out_gate=og.cuda(),
+                                                norm_weight=w.cuda(), rms_eps=1e-5, scale=0.5, check=True))
+        torch.cuda.synchronize()
+    finally:
+        kda.kda_debug_set_overlap(1)
+        kda.kda_debug_set_time_split(1)
+    (o, hT), (o2, hT2) = outs
+    eo = worst_slice_err(o.cpu().numpy(), o_ref, o_slices(1, H))
+    eh = worst_slice_err(hT.cpu().numpy(), h_ref, state_slices(1, H))
+    print("output gate + time split overlap=%d: err_o %.2e err_hT %.2e" % (overlap, eo, eh))
+    assert eo <= TOL_GATED_BF16 and eh <= TOL_BF16
+    assert not torch.equal(hT, hT2)                          # the split path really ran: same result, other rounding
+    assert (o - o2).abs().max().item() <= TOL_GATED_BF16 * o2.abs().max().item()
