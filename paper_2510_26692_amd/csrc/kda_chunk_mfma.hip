@@ -1288,9 +1288,9 @@ template <bool kFlags, bool kEpi>
 __global__ __launch_bounds__(512)
 void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, float *E, float *Tm, float *Bm,
                            float *state_final, const int32_t *__restrict__ cu_seqlens, void *__restrict__ o,
-                           int64_t T, int H, int64_t seg_chunks, int64_t part_len, int64_t part0_len, int parts,
-                           const uint32_t *ready, uint32_t epoch, uint32_t *status, uint32_t *split_flags,
-                           EpiParams epi)
+                           int64_t T, int H, int64_t seg_chunks, int64_t seg_index, int64_t part_len,
+                           int64_t part0_len, int parts, const uint32_t *ready, uint32_t epoch, uint32_t *status,
+                           uint32_t *split_flags, EpiParams epi)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1301,7 +1301,11 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
     int64_t tok_base, len;
     if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
     else            { tok_base = (int64_t)n * T; len = T; }
-    const int64_t nchunks = (len + kChunk - 1) / kChunk;
+    // chunk indices below are local to the time segment [cbase, cbase + seg_chunks) of this launch
+    const int64_t cbase = seg_index * seg_chunks;
+    int64_t nchunks = (len + kChunk - 1) / kChunk - cbase;
+    if (nchunks < 0) nchunks = 0;
+    if (nchunks > seg_chunks) nchunks = seg_chunks;
 
     const int y = (int)blockIdx.y;
     const int kind = (y == 0) ? kRoleFull : ((y & 1) ? kRoleT : kRoleB);
@@ -1321,10 +1325,10 @@ void kda_scan_split_kernel(const uint8_t *__restrict__ ws, const float *h0, floa
     if (EPI) epi.gate_ws = gate_base + (((int64_t)n * seg_chunks + c_begin) * H + h) * (int64_t)kGateSlotBytes;   \
     if (wave < 4)                                                                                                 \
         kda_scan_body<0, kFlags, EPI, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,   \
-                                            len, H, c_begin, c_end, h, flag0, epoch, status, epi);                \
+                                            len, H, cbase + c_begin, cbase + c_end, h, flag0, epoch, status, epi); \
     else                                                                                                          \
         kda_scan_body<1, kFlags, EPI, ROLE>(lds, slot0, slot_stride, state_in, state_out, o, st_base, tok_base,   \
-                                            len, H, c_begin, c_end, h, flag0, epoch, status, epi)
+                                            len, H, cbase + c_begin, cbase + c_end, h, flag0, epoch, status, epi)
     {   // first phase: the own range, from h0 / the identity / zero
         const float *state_in = (y == 0) ? h0 : nullptr;
         float *state_out = (y == 0) ? E : (kind == kRoleT ? Tm : Bm) + mid * pair_states;
@@ -1407,8 +1411,8 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
     p.carry_offset = p.slots_offset + (size_t)sc * streams * kSlotBytes;
     p.flags_offset = p.carry_offset + carry;
     p.split_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
-    // counters and states of the time-split scan, when the call qualifies for it (single segment only)
-    const bool split = sc == maxc && streams <= (size_t)kSplitMaxPairs && maxc >= kSplitMinChunks;
+    // counters and states of the time-split scan, when the call qualifies for it
+    const bool split = streams <= (size_t)kSplitMaxPairs && sc >= kSplitMinChunks;
     p.total_bytes = p.split_offset + (split ? kSplitFlagBytes + 3 * (size_t)kSplitMaxParts * carry : 0);
     p.gate_offset = 0;
     if (gate) {
@@ -1430,9 +1434,10 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
 static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forced, double *first_ratio)
 {
     *first_ratio = 1.0;
-    const int64_t maxc = max_chunks_per_seq(d);
+    int64_t maxc = max_chunks_per_seq(d);                    // chunks one launch walks
+    if (maxc > plan.seg_chunks) maxc = plan.seg_chunks;
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
-    if (plan.num_segments != 1 || pairs > kSplitMaxPairs || maxc < kSplitMinChunks || pairs >= cus) return 1;
+    if (pairs > kSplitMaxPairs || maxc < kSplitMinChunks || pairs >= cus) return 1;
     const double step = 2.85, item = 9.5;
     const double items = (double)pairs * (double)maxc;
     const double t_scan = (double)maxc * step, t_intra1 = items * item / (double)(cus - pairs);
@@ -1667,7 +1672,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                            reinterpret_cast<uint32_t *>(first), nfill, 0u, status);
     }
     if (parts > 1) {
-        // Time-split scan (single segment): one launch, kda_intra beside it in the overlapped mode.
+        // Time-split scan: one launch per time segment, kda_intra beside it in the overlapped mode.
         // ranges: the first one shorter by the ratio of the step times (full scan : passes without output)
         const double ratio = (g_split_ratio > 0.0) ? g_split_ratio : first_ratio;
         int64_t part0_len = (int64_t)((double)plan.seg_chunks * ratio / ((double)(parts - 1) + ratio) + 0.5);
@@ -1682,25 +1687,33 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         auto split_k = side ? (epi ? kda_scan_split_kernel<true, true> : kda_scan_split_kernel<true, false>)
                             : (epi ? kda_scan_split_kernel<false, true> : kda_scan_split_kernel<false, false>);
         const dim3 intra_grid_split((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)(parts * part_len));   // z: see kda_intra
-        if (side) {
-            if (hipEventRecord(side->fork, stream) != hipSuccess ||
-                hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
-                return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
-        } else {
-            hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
-                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale,
-                               (uint32_t *)nullptr, 0u, raw, 1, 0, 0, ep.gate, gate_ws);
-        }
-        hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, stream, ws, h0, E,
-                           Tm, Bm, hT, cu, o, (int64_t)d->seqlen, (int)d->heads,
-                           plan.seg_chunks, part_len, part0_len, parts, flags, 1u, status, split_flags, ep);
-        if (side) {
-            hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
-                               (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, (int64_t)0, d->scale, flags, 1u, raw,
-                               parts, (int)part_len, (int)part0_len, ep.gate, gate_ws);
-            if (hipEventRecord(side->join, side->stream) != hipSuccess ||
-                hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
-                return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
+        for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
+            const float *sin = (seg == 0) ? h0 : carry;
+            float *sout = (plan.num_segments > 1 || hT) ? carry : nullptr;
+            const uint32_t epoch = (uint32_t)(seg + 1);
+            if (seg > 0)    // the counters of the ranges start every segment at zero (the extra word: one of them)
+                hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)(kSplitFlagBytes / 4 / 256)), dim3(256), 0, stream,
+                                   split_flags, (int64_t)(kSplitFlagBytes / 4), 0u, split_flags);
+            if (side) {
+                if (hipEventRecord(side->fork, stream) != hipSuccess ||
+                    hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+                    return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
+            } else {
+                hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
+                                   (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
+                                   (uint32_t *)nullptr, 0u, raw, 1, 0, 0, ep.gate, gate_ws);
+            }
+            hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, stream, ws, sin, E,
+                               Tm, Bm, sout, cu, o, (int64_t)d->seqlen, (int)d->heads,
+                               plan.seg_chunks, seg, part_len, part0_len, parts, flags, epoch, status, split_flags, ep);
+            if (side) {
+                hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
+                                   (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw,
+                                   parts, (int)part_len, (int)part0_len, ep.gate, gate_ws);
+                if (hipEventRecord(side->join, side->stream) != hipSuccess ||
+                    hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
+                    return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
+            }
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));

@@ -290,3 +290,32 @@ def test_bf16_zero_tokens_returns_the_initial_state(with_h0):
     torch.cuda.synchronize()
     assert o.numel() == 0
     assert torch.equal(hT, h0 if with_h0 else torch.zeros_like(hT))
+
+
+def test_bf16_time_split_scan_inside_time_segments():
+    """A workspace of 45 % of the full size: the call walks the time axis in three segments, and the
+    sequential kernel of each segment is split into ranges; states are carried from segment to
+    segment.  Checked against the oracle and against the single-segment call."""
+    import paper_2510_26692_amd as kda
+    x = si.make_prefill(2, 64 * 130 + 5, 1, 128, 128, "bf16", -6.0, 304, 0.05)
+    dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+    dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
+    full = kda.kda_chunk_fwd_workspace_size(dims)
+    ws = torch.empty(int(full * 0.45) // 256 * 256, dtype=torch.uint8, device="cuda")
+    try:
+        kda.kda_debug_set_time_split(8)
+        eo, eh = check_prefill(x, TOL_BF16, workspace=ws)
+        o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws,
+                                   check=True)
+        o2, h2 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], check=True)
+        kda.kda_debug_set_time_split(0)
+        o3, h3 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws,
+                                   check=True)
+        torch.cuda.synchronize()
+    finally:
+        kda.kda_debug_set_time_split(1)
+    print("time split in segments: err_o %.2e err_hT %.2e" % (eo, eh))
+    for o_, h_ in ((o2, h2), (o3, h3)):
+        assert (o1 - o_).abs().max().item() <= TOL_BF16 * o_.abs().max().item()
+        assert (h1 - h_).abs().max().item() <= TOL_BF16 * h_.abs().max().item()
+    assert not torch.equal(h1, h3)                            # the segmented call really was split
