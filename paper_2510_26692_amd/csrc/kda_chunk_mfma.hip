@@ -14,6 +14,13 @@
 //             S <- Diag(gamma^C) S + (Gamma^{i->C}.K)^T V_new, with the fp32 state
 //             held in accumulator registers for the whole sequence.
 //
+// With up to a third of the compute units' worth of (sequence, head) pairs the two kernels run
+// at the same time (kda_intra on a helper stream, each slot handed over through a flag); with
+// very few pairs and long sequences kda_scan_split takes the place of kda_scan and cuts the
+// chunk axis into ranges that several workgroups walk side by side (the chunk recurrence is
+// affine in the state).  Optional fused stages (Section 4): the input prologue in kda_intra, the
+// output gate in kda_scan.
+//
 // Matrix-core operands are fp16 (unit roundoff 2^-11), accumulation is fp32.  The
 // raw bf16 inputs convert to fp16 exactly; only derived operands are rounded.
 //
