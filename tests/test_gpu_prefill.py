@@ -319,3 +319,31 @@ def test_bf16_time_split_scan_inside_time_segments():
         assert (o1 - o_).abs().max().item() <= TOL_BF16 * o_.abs().max().item()
         assert (h1 - h_).abs().max().item() <= TOL_BF16 * h_.abs().max().item()
     assert not torch.equal(h1, h3)                            # the segmented call really was split
+
+
+@pytest.mark.parametrize("dtype,tol,d", [("f32", TOL_F32, 64), ("bf16", TOL_BF16, 128)])
+@pytest.mark.parametrize("case", ["no_decay", "no_write", "full_write", "scalar_gate"])
+def test_degenerate_gates(case, dtype, tol, d):
+    """The special cases of Eq. (1): alpha = 1 (the delta rule without decay), beta = 0 (pure decay of
+    the initial state: nothing is written), beta = 1 (every key is overwritten completely) and a
+    decay shared by all channels of a head (the scalar-gate form)."""
+    x = si.make_prefill(2, 3 * 64 + 17, 2, d, d, dtype, -2.0, 700 + len(case), 0.3)
+    if case == "no_decay":
+        x["log_alpha"] = torch.zeros_like(x["log_alpha"])
+    elif case == "no_write":
+        x["beta"] = torch.zeros_like(x["beta"])
+    elif case == "full_write":
+        x["beta"] = torch.ones_like(x["beta"])
+    else:
+        x["log_alpha"] = x["log_alpha"][..., :1].expand_as(x["log_alpha"]).contiguous()
+    eo, eh = check_prefill(x, tol)
+    print("degenerate %s %s: err_o %.2e err_hT %.2e" % (case, dtype, eo, eh))
+    if case == "no_write":
+        # closed form: h_T = Diag(prod alpha) h0, checked here against the GPU result directly
+        import paper_2510_26692_amd as kda
+        dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+        _, hT = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], check=True)
+        G = x["log_alpha"].double().sum(dim=1)                       # [B,H,dk]
+        ref = torch.exp(G)[..., None] * x["h0"].double()
+        err = (hT.cpu().double() - ref).abs().max().item() / ref.abs().max().item()
+        assert err <= tol, err
