@@ -166,7 +166,9 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                       uint8_t *__restrict__ gate_ws)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // (the wave index is the same in all lanes: telling the compiler so turns the per-wave cases
+    // below into scalar branches instead of masked vector code)
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     constexpr int kPolicy = kHandoff ? kCacheDevice : 0;
 
     // Workgroup -> (head, sequence, chunk) straight from the 3-D grid (no divisions).  x = head;
