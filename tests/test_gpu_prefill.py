@@ -347,3 +347,15 @@ def test_degenerate_gates(case, dtype, tol, d):
         ref = torch.exp(G)[..., None] * x["h0"].double()
         err = (hT.cpu().double() - ref).abs().max().item() / ref.abs().max().item()
         assert err <= tol, err
+
+
+def test_bf16_thousands_of_short_packed_sequences():
+    """3 000 packed sequences of 0 to 130 tokens (many shorter than a chunk, some empty): one grid
+    row per sequence in kda_intra, one workgroup per (sequence, head) in kda_scan."""
+    rng = np.random.default_rng(811)
+    lens = rng.integers(0, 131, size=3000)
+    lens[::97] = 0
+    x = si.make_varlen(lens, 2, 128, 128, "bf16", -2.0, 812, 0.05)
+    # (max_seqlen bounds the workspace: without it every sequence is sized as if it held all tokens)
+    eo, eh = check_prefill(x, TOL_BF16, max_seqlen=int(lens.max()))
+    print("bf16 3000 short sequences (%d tokens): err_o %.2e err_hT %.2e" % (int(lens.sum()), eo, eh))
