@@ -194,6 +194,22 @@ def main():
                         "ms_per_step": ms_o16, "tokens_per_s": tokens / (ms_o16 * 1e-3)}
         del o16
 
+    # the scalar-gate special case (one decay per token and head) on the same shape: its own entry point
+    scalar_obj = None
+    if not args.no_breakdown:
+        gh = x["log_alpha"][..., 0].contiguous()
+
+        def prefill_scalar_gate():
+            kda.kda_chunk_fwd_scalar_gate(x["q"], x["k"], x["v"], gh, x["beta"], h0=x["h0"],
+                                          cu_seqlens=x["cu_seqlens"], o=o, hT=hT, workspace=ws, max_seqlen=max_len)
+        for _ in range(args.warmup):
+            prefill_scalar_gate()
+        ms_sg = _time_region(torch, prefill_scalar_gate, args.steps)
+        kda.kda_chunk_fwd_check(dims, ws)
+        scalar_obj = {"what": "kda_chunk_fwd_scalar_gate on the same shape (the decay of channel 0 taken for the whole head)",
+                      "ms_per_step": ms_sg, "tokens_per_s": tokens / (ms_sg * 1e-3)}
+        del gh
+
     # the same prefill on raw projections (fused input prologue), cfg1 shape only
     fused_obj = None
     if name == "cfg1_prefill_bf16" and not args.no_breakdown:
@@ -341,6 +357,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "prefill_bf16_out": bf16_out_obj,
+        "prefill_scalar_gate": scalar_obj,
         "prefill_fused_stages": fused_obj,
         "decode": decode_obj,
         "error_metric": "max|x-ref|/max|ref| per (sequence, head); parity is gated in tests/",

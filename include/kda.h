@@ -188,6 +188,22 @@ kda_status kda_chunk_fwd_fused(const kda_dims *dims, const kda_prologue *prologu
                                void *hip_stream);
 
 /*
+ * kda_chunk_fwd for the scalar-gate special case of Eq. (1) (Section 2.2: alpha_t = a_t I, one
+ * decay per token and head): log_alpha_head is [B,T,H] in in_dtype, everything else as for
+ * kda_chunk_fwd.  The result equals kda_chunk_fwd on that decay repeated over the dk channels; the
+ * per-chunk kernel is cheaper (the decay leaves the matrix-core operands and multiplies the fp32
+ * tiles instead, so no range handling is needed whatever the decay).  Built for KDA_BF16 inputs with
+ * dk == dv == 128; workspace sizes as for kda_chunk_fwd.
+ */
+kda_status kda_chunk_fwd_scalar_gate(const kda_dims *dims,
+                                     const void *q, const void *k, const void *v,
+                                     const void *log_alpha_head, const void *beta,
+                                     const float *h0, const int32_t *cu_seqlens,
+                                     void *o, float *hT,
+                                     void *workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+
+/*
  * Optional check after a bf16 kda_chunk_fwd: waits for `hip_stream` and reads
  * the status word that the call left in `workspace` (same dims, workspace and
  * size as that call).  The sequential kernel of the prefill may run next to
@@ -241,6 +257,13 @@ kda_status kda_recurrent_steps_pooled(const kda_dims *dims,
                                       const void *log_alpha, const void *beta,
                                       float *S_pool, const int32_t *state_indices,
                                       void *o, void *hip_stream);
+
+/* kda_recurrent_steps_pooled with one decay per token and head: log_alpha_head is [N,Tq,H]. */
+kda_status kda_recurrent_steps_pooled_scalar_gate(const kda_dims *dims,
+                                                  const void *q, const void *k, const void *v,
+                                                  const void *log_alpha_head, const void *beta,
+                                                  float *S_pool, const int32_t *state_indices,
+                                                  void *o, void *hip_stream);
 
 /*
  * kda_recurrent_steps_pooled with the fused stages (either may be NULL; see kda_prologue and

@@ -9,7 +9,11 @@ fp64 statement of the same function written from the chunkwise equations of
 Section 3.1, used to pin the recurrence (chunk-size invariance).  `prologue` states the
 input parameterisation of Section 4 (L2Norm, Sigmoid, the decay function) and `epilogue`
 the output gate of the same section (head-wise RMSNorm times a sigmoid gate), in float64.
+`kda_forward_scalar_gate` / `kda_steps_pooled_scalar_gate` are the scalar-gate special case of
+Eq. (1) (Section 2.2, alpha_t = a_t I): the same recurrence on the decay repeated over the channels.
 """
+import numpy as _np
+
 from . import epilogue, prologue  # noqa: F401
 from .recurrence import build, kda_forward, kda_step, kda_steps_pooled, num_threads  # noqa: F401
 
@@ -20,3 +24,18 @@ def kda_forward_raw(q_raw, k_raw, v, gate, beta_logit, eps=1e-6, a_scale=None, d
     this adds is far below every tolerance it is compared under)."""
     q, k, log_alpha, beta = prologue.apply(q_raw, k_raw, gate, beta_logit, eps, a_scale, dt_bias)
     return kda_forward(q, k, v, log_alpha, beta, **kw)
+
+
+def kda_forward_scalar_gate(q, k, v, log_alpha_head, beta, **kw):
+    """Eq. (1) with one decay per (token, head), alpha_t = a_t I (Section 2.2): log_alpha_head is
+    [B,T,H]; it is repeated over the dk channels and handed to the per-channel recurrence."""
+    la = _np.asarray(log_alpha_head)
+    full = _np.ascontiguousarray(_np.broadcast_to(la[..., None], _np.asarray(q).shape))
+    return kda_forward(q, k, v, full, beta, **kw)
+
+
+def kda_steps_pooled_scalar_gate(q, k, v, log_alpha_head, beta, S_pool, state_indices=None, **kw):
+    """kda_steps_pooled with one decay per (token, head): log_alpha_head is [N,Tq,H]."""
+    la = _np.asarray(log_alpha_head)
+    full = _np.ascontiguousarray(_np.broadcast_to(la[..., None], _np.asarray(q).shape))
+    return kda_steps_pooled(q, k, v, full, beta, S_pool, state_indices, **kw)

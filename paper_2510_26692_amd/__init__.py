@@ -9,4 +9,5 @@ any entry point without the built library raises.
 from .kda import (KdaDims, KdaError, KdaEpilogue, KdaPrologue, kda_chunk_fwd, kda_chunk_fwd_check, kda_chunk_fwd_fused,
                   kda_recurrent_steps_fused, kda_debug_set_overlap, kda_debug_set_time_split,  # noqa: F401
                   kda_debug_set_phase_mask, kda_chunk_fwd_min_workspace_size, kda_chunk_fwd_workspace_size, kda_last_error, kda_recurrent_step, kda_recurrent_steps_pooled,
+                  kda_chunk_fwd_scalar_gate, kda_recurrent_steps_pooled_scalar_gate,
                   kda_status_string, kda_version, library_path, load_library)

@@ -24,14 +24,14 @@ kda_status fail(kda_status code, const char *fmt, ...)
 // Kernel-side entry points (one per source file).
 kda_status recurrent_step_dispatch(const kda_dims *, const kda_prologue *, const kda_epilogue *, const void *, const void *,
                                    const void *, const void *, const void *, float *, void *,
-                                   const int32_t *, hipStream_t);
+                                   const int32_t *, bool scalar_gate, hipStream_t);
 int recurrent_max_steps();
 kda_status chunk_f32_dispatch(const kda_dims *, const void *, const void *, const void *,
                               const void *, const void *, const float *, const int32_t *, void *,
                               float *, hipStream_t);
 kda_status chunk_mfma_dispatch(const kda_dims *, const kda_prologue *, const kda_epilogue *, const void *, const void *, const void *,
                                const void *, const void *, const float *, const int32_t *, void *,
-                               float *, void *, size_t, hipStream_t);
+                               float *, void *, size_t, bool scalar_gate, hipStream_t);
 size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal, bool output_gate);
 size_t chunk_mfma_status_offset(const kda_dims *, size_t workspace_bytes);
 
@@ -172,10 +172,12 @@ static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, con
                                  const void *q, const void *k,
                                  const void *v, const void *log_alpha, const void *beta, const float *h0,
                                  const int32_t *cu_seqlens, void *o, float *hT, void *workspace,
-                                 size_t workspace_bytes, void *hip_stream)
+                                 size_t workspace_bytes, void *hip_stream, bool scalar_gate = false)
 {
     kda_status st = check_dims(d, cu_seqlens != nullptr);
     if (st != KDA_OK) return st;
+    if (scalar_gate && !(d->in_dtype == KDA_BF16 && d->dk == 128 && d->dv == 128 && mfma_path(d)))
+        return fail(KDA_ERR_UNSUPPORTED, "the scalar-gate prefill is built for bf16 inputs with dk == dv == 128");
     if ((pro || epi) && !(d->in_dtype == KDA_BF16 && d->dk == 128 && d->dv == 128))
         return fail(KDA_ERR_UNSUPPORTED, "the fused stages are built for bf16 inputs with dk == dv == 128");
     if (epi && (o == epi->gate)) return fail(KDA_ERR_INVALID_ARG, "o must not alias the output gate");
@@ -208,7 +210,7 @@ static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, con
             return fail(KDA_ERR_WORKSPACE, "workspace has %zu bytes, at least %zu needed", workspace_bytes, need);
     }
     return chunk_mfma_dispatch(d, pro, epi, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
-                               workspace_bytes, stream);
+                               workspace_bytes, scalar_gate, stream);
 }
 
 kda_status kda_chunk_fwd(const kda_dims *d, const void *q, const void *k, const void *v,
@@ -219,6 +221,16 @@ kda_status kda_chunk_fwd(const kda_dims *d, const void *q, const void *k, const 
     g_last_error[0] = 0;
     return chunk_fwd_impl(d, nullptr, nullptr, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
                           workspace_bytes, hip_stream);
+}
+
+kda_status kda_chunk_fwd_scalar_gate(const kda_dims *d, const void *q, const void *k, const void *v,
+                                     const void *log_alpha_head, const void *beta, const float *h0,
+                                     const int32_t *cu_seqlens, void *o, float *hT, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream)
+{
+    g_last_error[0] = 0;
+    return chunk_fwd_impl(d, nullptr, nullptr, q, k, v, log_alpha_head, beta, h0, cu_seqlens, o, hT, workspace,
+                          workspace_bytes, hip_stream, true);
 }
 
 kda_status kda_chunk_fwd_fused(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
@@ -270,14 +282,15 @@ kda_status kda_recurrent_step(const kda_dims *d, const void *q, const void *k, c
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(log_alpha) || !aligned16(S) ||
         !aligned16(o) || (reinterpret_cast<uintptr_t>(beta) & 1u))
         return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    return recurrent_step_dispatch(d, nullptr, nullptr, q, k, v, log_alpha, beta, S, o, nullptr,
+    return recurrent_step_dispatch(d, nullptr, nullptr, q, k, v, log_alpha, beta, S, o, nullptr, false,
                                    static_cast<hipStream_t>(hip_stream));
 }
 
 static kda_status steps_pooled_impl(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
                                     const void *q, const void *k,
                                     const void *v, const void *log_alpha, const void *beta, float *S_pool,
-                                    const int32_t *state_indices, void *o, void *hip_stream)
+                                    const int32_t *state_indices, void *o, void *hip_stream,
+                                    bool scalar_gate = false)
 {
     kda_status st = check_dims(d, false);
     if (st != KDA_OK) return st;
@@ -287,11 +300,11 @@ static kda_status steps_pooled_impl(const kda_dims *d, const kda_prologue *pro, 
     if (d->num_seqs == 0 || d->heads == 0) return KDA_OK;
     if (!q || !k || !v || !log_alpha || !beta || !S_pool || !o)
         return fail(KDA_ERR_INVALID_ARG, "q, k, v, log_alpha, beta, S_pool and o must be non-NULL");
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(log_alpha) || !aligned16(S_pool) ||
-        !aligned16(o) || (reinterpret_cast<uintptr_t>(beta) & 1u) ||
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || (!scalar_gate && !aligned16(log_alpha)) || !aligned16(S_pool) ||
+        !aligned16(o) || (reinterpret_cast<uintptr_t>(beta) & 1u) || (reinterpret_cast<uintptr_t>(log_alpha) & 1u) ||
         (reinterpret_cast<uintptr_t>(state_indices) & 3u))
         return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned (state_indices: 4)");
-    return recurrent_step_dispatch(d, pro, epi, q, k, v, log_alpha, beta, S_pool, o, state_indices,
+    return recurrent_step_dispatch(d, pro, epi, q, k, v, log_alpha, beta, S_pool, o, state_indices, scalar_gate,
                                    static_cast<hipStream_t>(hip_stream));
 }
 
@@ -301,6 +314,15 @@ kda_status kda_recurrent_steps_pooled(const kda_dims *d, const void *q, const vo
 {
     g_last_error[0] = 0;
     return steps_pooled_impl(d, nullptr, nullptr, q, k, v, log_alpha, beta, S_pool, state_indices, o, hip_stream);
+}
+
+kda_status kda_recurrent_steps_pooled_scalar_gate(const kda_dims *d, const void *q, const void *k, const void *v,
+                                                  const void *log_alpha_head, const void *beta, float *S_pool,
+                                                  const int32_t *state_indices, void *o, void *hip_stream)
+{
+    g_last_error[0] = 0;
+    return steps_pooled_impl(d, nullptr, nullptr, q, k, v, log_alpha_head, beta, S_pool, state_indices, o, hip_stream,
+                             true);
 }
 
 kda_status kda_recurrent_steps_fused(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,

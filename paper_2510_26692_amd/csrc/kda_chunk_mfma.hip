@@ -138,6 +138,8 @@ template <int kPolicy> __device__ __forceinline__ u32x4 slot_load16(__amdgpu_buf
 // so the decay-scaled operands of the A-matrix products are built in registers.
 // kHandoff: the slot is handed to a kda_scan that runs at the same time (write-through stores and a
 // ready flag); otherwise the stores are ordinary ones and the kernel boundary publishes them.
+// kScalar: log_alpha is [B,T,H], one decay per (token, head) shared by all channels (the scalar-gate
+// special case of Eq. (1), Section 2.2); the decay then leaves the matrix-core operands altogether.
 // kRaw: q, k, log_alpha and beta arrive as the raw projections of Section 4 ("Neural
 // Parameterization") and the kernel applies L2Norm to q and k, Sigmoid to beta and the decay
 // function log alpha = -a_scale[h] softplus(gate + dt_bias[h][c]) itself, in fp32.
@@ -155,7 +157,7 @@ __device__ __forceinline__ float log2_alpha_from_gate(float x, float a)
     return -a * sp;
 }
 
-template <bool kHandoff, bool kRaw>
+template <bool kHandoff, bool kRaw, bool kScalar = false>
 __global__ __launch_bounds__(256, 2)
 void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
                       const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
@@ -232,12 +234,16 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         const u32x4 z = {0, 0, 0, 0};
         const int64_t off = ((tok0 + tok) * H + h) * (int64_t)D + 8 * g;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) graw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(log_alpha + off + 32 * ks) : z;
+        for (int ks = 0; ks < 4; ++ks)
+            graw[ks] = (!kScalar && tok < nv) ? *reinterpret_cast<const u32x4 *>(log_alpha + off + 32 * ks) : z;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) kraw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(k + off + 32 * ks) : z;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qraw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(q + off + 32 * ks) : z;
     }
+    static_assert(!(kRaw && kScalar), "the fused prologue is built for the per-channel gate");
+    float gscalar = 0.f;                                     // kScalar: log alpha of this lane's token
+    if (kScalar && tok < nv) gscalar = bf16_bits_to_float(log_alpha[(tok0 + tok) * H + h]);
     if (tid < kChunk) {
         float b = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
         if (kRaw) b = (tid < nv) ? __builtin_amdgcn_rcpf(1.f + fast_exp2(-b * kLog2e)) : 0.f;   // Sigmoid
@@ -276,6 +282,101 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         invk = (tok < nv) ? __builtin_amdgcn_rsqf(sk + raw.eps) : 0.f;
     }
 
+    f32x4 res_kk[4], res_qk[4];              // A_kk, A_qk tiles (R, I), I = 0..R
+    if constexpr (kScalar) {
+        // ---- scalar gate: A[r][i] = (k_r . k_i) 2^(G_r - G_i), so the tiles are plain K K^T and Q K^T
+        // products of the fp16 copies of k and q (exact: they come from bf16), and the decay, at most
+        // 1 where it is kept, multiplies the fp32 results.  Gamma.K, Gamma.Q and Gamma^{i->C}.K are k and q
+        // times one factor per token.  No sub-chunk split and no exact path are needed.
+        float *sG = reinterpret_cast<float *>(lds + kTab);   // [64] running log2 decay over the chunk
+        float gs = gscalar * kLog2e;
+        gs += row_shr<1>(gs); gs += row_shr<2>(gs); gs += row_shr<4>(gs); gs += row_shr<8>(gs);
+        if (lane == 15) sTot[R] = gs;                        // total of sub-chunk R
+        __syncthreads();                                                           // B1
+        const float t0 = sTot[0], t1 = sTot[1], t2 = sTot[2], t3 = sTot[3];
+        const float total = t0 + t1 + t2 + t3;
+        const float Gc = gs + ((R > 0) ? t0 : 0.f) + ((R > 1) ? t1 : 0.f) + ((R > 2) ? t2 : 0.f);
+        if (g == 0) sG[tok] = Gc;
+        const float gam = fast_exp2(Gc), gam_end = fast_exp2(total - Gc), gam_q = gam * scale;
+        if (R == 0) {   // gamma^C, the same for every channel
+            const float gce = fast_exp2(total);
+            slot_store8<kPolicy>(out, kOffGc + 2 * lane * 4, make_float2(gce, gce));
+        }
+        h8 rowK[4], rowQ[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            float kf[8], qf[8];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                unpack_bf16x2(kraw[ks][w], kf[2 * w], kf[2 * w + 1]);
+                unpack_bf16x2(qraw[ks][w], qf[2 * w], qf[2 * w + 1]);
+            }
+            u32x4 t;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) t[w] = pack_h2(kf[2 * w], kf[2 * w + 1]);
+            rowK[ks] = __builtin_bit_cast(h8, t);
+            // the same k is the column operand of every tile below this sub-chunk
+            if (R < 3) *reinterpret_cast<u32x4 *>(lds + kColS + ((((R + 1) * R / 2 + R) * 4 + ks) * 64 + lane) * 16) = t;
+            if (R < 2) *reinterpret_cast<u32x4 *>(lds + kColS + ((((R + 2) * (R + 1) / 2 + R) * 4 + ks) * 64 + lane) * 16) = t;
+            if (R < 1) *reinterpret_cast<u32x4 *>(lds + kColS + ((((R + 3) * (R + 2) / 2 + R) * 4 + ks) * 64 + lane) * 16) = t;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) t[w] = pack_h2(qf[2 * w], qf[2 * w + 1]);
+            rowQ[ks] = __builtin_bit_cast(h8, t);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) t[w] = pack_h2(kf[2 * w] * gam, kf[2 * w + 1] * gam);
+            *reinterpret_cast<u32x4 *>(lds + kGK + (tok * kLdH + 32 * ks + 8 * g) * 2) = t;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) t[w] = pack_h2(kf[2 * w] * gam_end, kf[2 * w + 1] * gam_end);
+            *reinterpret_cast<u32x4 *>(lds + kKp + (tok * kLdH + 32 * ks + 8 * g) * 2) = t;
+            {   // Gamma.Q to the workspace in MFMA register order (see the per-channel path)
+                const uint32_t a0 = pack_h2(qf[0] * gam_q, qf[1] * gam_q), a1 = pack_h2(qf[2] * gam_q, qf[3] * gam_q);
+                const uint32_t b0 = pack_h2(qf[4] * gam_q, qf[5] * gam_q), b1 = pack_h2(qf[6] * gam_q, qf[7] * gam_q);
+                const bool odd = g & 1;
+                const uint32_t r0 = __shfl_xor(odd ? a0 : b0, 16), r1 = __shfl_xor(odd ? a1 : b1, 16);
+                u32x4 o4;
+                if (odd) { o4[0] = r0; o4[1] = r1; o4[2] = b0; o4[3] = b1; }
+                else     { o4[0] = a0; o4[1] = a1; o4[2] = r0; o4[3] = r1; }
+                slot_store16<kPolicy>(out, kOffQp + frag_rts(tok >> 5, ks, g >> 1) * kFragBytes + ((tok & 31) + 32 * (g & 1)) * 16, o4);
+            }
+        }
+        {
+            f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                akk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowK[ks], rowK[ks], akk, 0, 0, 0);
+                aqk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowQ[ks], rowK[ks], aqk, 0, 0, 0);
+            }
+            res_kk[R] = akk; res_qk[R] = aqk;
+        }
+        __syncthreads();                                                           // B3 (colS, sG visible)
+#pragma unroll
+        for (int I = 0; I < 3; ++I) {
+            if (I < R) {
+                f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const h8 b = *reinterpret_cast<const h8 *>(lds + kColS + (((R * (R - 1) / 2 + I) * 4 + ks) * 64 + lane) * 16);
+                    akk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowK[ks], b, akk, 0, 0, 0);
+                    aqk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowQ[ks], b, aqk, 0, 0, 0);
+                }
+                res_kk[I] = akk; res_qk[I] = aqk;
+            }
+        }
+        // the decay 2^(G_r - G_i) on every kept entry (r >= i; the others are masked below)
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            if (I <= R) {
+                const float gi = sG[16 * I + m];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float dlt = sG[16 * R + 4 * g + j] - gi;
+                    const float f = fast_exp2(dlt < 0.f ? dlt : 0.f);
+                    res_kk[I][j] *= f; res_qk[I][j] *= f;
+                }
+            }
+        }
+        __syncthreads();                                                           // B4 (early aliases dead)
+    } else {
     // ---- G: running sum of log2(alpha) over the 16 tokens of the sub-chunk (lanes of a row) ----
     float G[32];
     f32x4 bias[8];                                           // kRaw: dt_bias of this lane's 32 channels
@@ -477,7 +578,6 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     }
 
     // ---- A_kk, A_qk tiles of sub-chunk row R on the matrix cores (16x16, K = 128) ----
-    f32x4 res_kk[4], res_qk[4];              // index I = 0..R
     {
         f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -555,6 +655,8 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         }
     }
     __syncthreads();                                                               // B4 (early aliases dead)
+
+    }
 
     // ---- L and Tril(A_qk) tiles of row R; fp16 V tile ----
     {
@@ -1512,6 +1614,10 @@ static bool reserve_lds()
                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<false, false, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kda_intra_kernel<true, false, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kIntraLds) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<false, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, scan_lds) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(kda_scan_kernel<true, false>),
@@ -1595,9 +1701,15 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                                const void *q, const void *k,
                                const void *v, const void *log_alpha, const void *beta, const float *h0,
                                const int32_t *cu, void *o, float *hT, void *workspace,
-                               size_t workspace_bytes, hipStream_t stream)
+                               size_t workspace_bytes, bool scalar_gate, hipStream_t stream)
 {
     using namespace mfma;
+    // kda_intra for (slots handed over to a running kda_scan, raw inputs, one decay per head)
+    auto pick_intra = [&](bool handoff) {
+        if (scalar_gate) return handoff ? kda_intra_kernel<true, false, true> : kda_intra_kernel<false, false, true>;
+        if (pro) return handoff ? kda_intra_kernel<true, true> : kda_intra_kernel<false, true>;
+        return handoff ? kda_intra_kernel<true, false> : kda_intra_kernel<false, false>;
+    };
     RawParams raw = {nullptr, nullptr, 0.f};
     if (pro) { raw.a_scale = pro->a_scale; raw.dt_bias = pro->dt_bias; raw.eps = pro->l2norm_eps; }
     const int out_bf16 = d->out_dtype == KDA_BF16;
@@ -1691,8 +1803,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         uint32_t *split_flags = reinterpret_cast<uint32_t *>(base + plan.split_offset);
         float *E = reinterpret_cast<float *>(base + plan.split_offset + kSplitFlagBytes);
         float *Tm = E + kSplitMaxParts * pair_states, *Bm = Tm + kSplitMaxParts * pair_states;
-        auto intra = side ? (pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>)
-                          : (pro ? kda_intra_kernel<false, true> : kda_intra_kernel<false, false>);
+        auto intra = pick_intra(side != nullptr);
         auto split_k = side ? (epi ? kda_scan_split_kernel<true, true> : kda_scan_split_kernel<true, false>)
                             : (epi ? kda_scan_split_kernel<false, true> : kda_scan_split_kernel<false, false>);
         const dim3 intra_grid_split((unsigned)d->heads, (unsigned)d->num_seqs, (unsigned)(parts * part_len));   // z: see kda_intra
@@ -1742,7 +1853,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
                                o, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                flags, epoch, status, ep);
-            auto intra = pro ? kda_intra_kernel<true, true> : kda_intra_kernel<true, false>;
+            auto intra = pick_intra(true);
             hipLaunchKernelGGL(intra, intra_grid_overlap,
                                dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw, 1, 0, 0, ep.gate, gate_ws);
@@ -1750,7 +1861,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                 hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
                 return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
         } else {
-            auto intra = pro ? kda_intra_kernel<false, true> : kda_intra_kernel<false, false>;
+            auto intra = pick_intra(false);
             if (g_phase_mask & 1)
                 hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
                                    (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,

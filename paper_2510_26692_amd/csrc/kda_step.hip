@@ -32,7 +32,7 @@ __global__ __launch_bounds__(DV * 2)
 void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                      const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
                      const Tin *__restrict__ beta, float *__restrict__ S,
-                     void *__restrict__ o, int o_bf16, float scale, int H, int steps,
+                     void *__restrict__ o, int o_bf16, int alpha_per_head, float scale, int H, int steps,
                      const int32_t *__restrict__ indices, const float *__restrict__ a_scale,
                      const float *__restrict__ dt_bias, float l2_eps, const Tin *__restrict__ out_gate,
                      const float *__restrict__ norm_w, float rms_eps)
@@ -65,7 +65,8 @@ void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
         for (int i = tid; i < steps * DK; i += DV * 2) {
             const int t = i / DK, c = i - t * DK;
             const int64_t off = (row0 + (int64_t)t * H) * DK + c;
-            s_alpha[t][c] = fast_exp2(load_as_float(log_alpha + off) * kLog2e);
+            // (alpha_per_head: log_alpha is [N,steps,H], one decay for all channels of a head)
+            s_alpha[t][c] = fast_exp2(load_as_float(log_alpha + (alpha_per_head ? row0 + (int64_t)t * H : off)) * kLog2e);
             s_k[t][c] = load_as_float(k + off);
             s_q[t][c] = load_as_float(q + off);
         }
@@ -187,7 +188,8 @@ void kda_step_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
 template <typename Tin, int DK, int DV>
 static kda_status launch_step(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
                               const void *q, const void *k, const void *v, const void *log_alpha,
-                              const void *beta, float *S, void *o, const int32_t *indices, hipStream_t stream)
+                              const void *beta, float *S, void *o, const int32_t *indices, bool scalar_gate,
+                              hipStream_t stream)
 {
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
     if (pairs == 0) return KDA_OK;
@@ -197,7 +199,7 @@ static kda_status launch_step(const kda_dims *d, const kda_prologue *pro, const 
     hipLaunchKernelGGL(step, dim3((unsigned)pairs), dim3(DV * 2), 0, stream,
                        static_cast<const Tin *>(q), static_cast<const Tin *>(k),
                        static_cast<const Tin *>(v), static_cast<const Tin *>(log_alpha),
-                       static_cast<const Tin *>(beta), S, o, (int)(d->out_dtype == KDA_BF16), d->scale,
+                       static_cast<const Tin *>(beta), S, o, (int)(d->out_dtype == KDA_BF16), (int)scalar_gate, d->scale,
                        (int)d->heads, (int)d->seqlen, indices, pro ? pro->a_scale : nullptr,
                        pro ? pro->dt_bias : nullptr, pro ? pro->l2norm_eps : 0.f,
                        static_cast<const Tin *>(epi ? epi->gate : nullptr), epi ? epi->norm_weight : nullptr,
@@ -211,16 +213,16 @@ int recurrent_max_steps() { return kMaxSteps; }
 
 kda_status recurrent_step_dispatch(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
                                    const void *q, const void *k, const void *v, const void *log_alpha,
-                                   const void *beta, float *S, void *o, const int32_t *indices,
+                                   const void *beta, float *S, void *o, const int32_t *indices, bool scalar_gate,
                                    hipStream_t stream)
 {
     const bool bf = d->in_dtype == KDA_BF16;
     if (d->dk == 128 && d->dv == 128)
-        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, stream)
-                  : launch_step<float, 128, 128>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, stream);
+        return bf ? launch_step<__hip_bfloat16, 128, 128>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, scalar_gate, stream)
+                  : launch_step<float, 128, 128>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, scalar_gate, stream);
     if (d->dk == 64 && d->dv == 64)
-        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, stream)
-                  : launch_step<float, 64, 64>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, stream);
+        return bf ? launch_step<__hip_bfloat16, 64, 64>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, scalar_gate, stream)
+                  : launch_step<float, 64, 64>(d, pro, epi, q, k, v, log_alpha, beta, S, o, indices, scalar_gate, stream);
     return fail(KDA_ERR_UNSUPPORTED, "recurrent step supports dk == dv in {64,128}, got %d x %d",
                 d->dk, d->dv);
 }

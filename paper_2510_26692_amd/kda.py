@@ -88,6 +88,10 @@ def load_library():
     lib.kda_chunk_fwd_fused_workspace_size.argtypes = [dp, ep]
     lib.kda_chunk_fwd_fused_min_workspace_size.restype = sz
     lib.kda_chunk_fwd_fused_min_workspace_size.argtypes = [dp, ep]
+    lib.kda_chunk_fwd_scalar_gate.restype = ctypes.c_int
+    lib.kda_chunk_fwd_scalar_gate.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kda_recurrent_steps_pooled_scalar_gate.restype = ctypes.c_int
+    lib.kda_recurrent_steps_pooled_scalar_gate.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kda_recurrent_steps_fused.restype = ctypes.c_int
     lib.kda_recurrent_steps_fused.argtypes = [dp, pp, ep, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = lib
@@ -223,7 +227,7 @@ def kda_chunk_fwd_fused(q, k, v, gate, beta, prologue=True, l2norm_eps=1e-6, a_s
 
 def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0, o=None,
                   hT=None, want_hT=True, workspace=None, max_seqlen=0, check=False, out_dtype=None,
-                  _fused=None):
+                  _fused=None, _scalar_gate=False):
     """Chunkwise prefill.  q,k,log_alpha [B,T,H,dk]; v [B,T,H,dv]; beta [B,T,H];
     h0 [N,H,dk,dv] fp32 or None; cu_seqlens int32 [N+1] on device or None.
     Returns (o [B,T,H,dv], hT fp32 [N,H,dk,dv] or None); o is fp32 unless out_dtype (or the `o`
@@ -238,8 +242,8 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
         raise ValueError("unsupported input dtype %s" % q.dtype)
     B, T, H, dk = q.shape
     dv = v.shape[-1]
-    if k.shape != q.shape or log_alpha.shape != q.shape or v.shape != (B, T, H, dv) \
-            or beta.shape != (B, T, H):
+    if k.shape != q.shape or log_alpha.shape != ((B, T, H) if _scalar_gate else q.shape) \
+            or v.shape != (B, T, H, dv) or beta.shape != (B, T, H):
         raise ValueError("inconsistent input shapes")
     odt = _out_dtype(o, out_dtype)
     dims = make_chunk_dims(q, v, cu_seqlens, scale, max_seqlen, odt)
@@ -260,7 +264,9 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     tail = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(h0), _ptr(cu_seqlens), _ptr(o),
             _ptr(hT), _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(dev))
-    if _fused is None:
+    if _scalar_gate:
+        st = lib.kda_chunk_fwd_scalar_gate(ctypes.byref(dims), *tail)
+    elif _fused is None:
         st = lib.kda_chunk_fwd(ctypes.byref(dims), *tail)
     else:
         st = lib.kda_chunk_fwd_fused(ctypes.byref(dims), *[None if f is None else ctypes.byref(f) for f in _fused],
@@ -270,6 +276,12 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
     if check:
         kda_chunk_fwd_check(dims, workspace)
     return o, hT
+
+
+def kda_chunk_fwd_scalar_gate(q, k, v, log_alpha_head, beta, **kw):
+    """kda_chunk_fwd with one decay per (token, head): log_alpha_head [B,T,H] (the scalar-gate case
+    of Eq. (1)); other arguments and the result as for kda_chunk_fwd."""
+    return kda_chunk_fwd(q, k, v, log_alpha_head, beta, _scalar_gate=True, **kw)
 
 
 def kda_recurrent_step(q, k, v, log_alpha, beta, S, scale=1.0, o=None, out_dtype=None):
@@ -306,8 +318,13 @@ def kda_recurrent_steps_fused(q, k, v, gate, beta, S_pool, state_indices=None, p
                                       _fused=(pro, _make_epilogue(v, out_gate, norm_weight, rms_eps)), **kw)
 
 
+def kda_recurrent_steps_pooled_scalar_gate(q, k, v, log_alpha_head, beta, S_pool, state_indices=None, **kw):
+    """kda_recurrent_steps_pooled with one decay per (token, head): log_alpha_head [N,Tq,H]."""
+    return kda_recurrent_steps_pooled(q, k, v, log_alpha_head, beta, S_pool, state_indices, _scalar_gate=True, **kw)
+
+
 def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=None, scale=1.0, o=None,
-                               out_dtype=None, _fused=None):
+                               out_dtype=None, _fused=None, _scalar_gate=False):
     """Decode over a state pool.  q,k,log_alpha [N,Tq,H,dk]; v [N,Tq,H,dv]; beta [N,Tq,H];
     S_pool fp32 [P,H,dk,dv], the addressed states updated in place; state_indices int32 [N] on the
     device (negative = skip) or None for 0..N-1.  Returns o [N,Tq,H,dv] (fp32, or bf16 on request as in
@@ -320,7 +337,8 @@ def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=N
         raise ValueError("S_pool must be fp32 [P,H,dk,dv]")
     if q.dtype not in _DTYPE_CODE or not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype):
         raise ValueError("q, k, v, log_alpha, beta must share a supported dtype")
-    if k.shape != q.shape or log_alpha.shape != q.shape or v.shape != (N, Tq, H, dv) or beta.shape != (N, Tq, H):
+    if k.shape != q.shape or log_alpha.shape != ((N, Tq, H) if _scalar_gate else q.shape) \
+            or v.shape != (N, Tq, H, dv) or beta.shape != (N, Tq, H):
         raise ValueError("inconsistent input shapes")
     if state_indices is None:
         if S_pool.shape[0] < N:
@@ -336,7 +354,9 @@ def kda_recurrent_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=N
                    in_dtype=_DTYPE_CODE[q.dtype], out_dtype=_DTYPE_CODE[odt], scale=float(scale), max_seqlen=0)
     tail = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(S_pool), _ptr(state_indices), _ptr(o),
             _stream_ptr(dev))
-    if _fused is None:
+    if _scalar_gate:
+        st = lib.kda_recurrent_steps_pooled_scalar_gate(ctypes.byref(dims), *tail)
+    elif _fused is None:
         st = lib.kda_recurrent_steps_pooled(ctypes.byref(dims), *tail)
     else:
         st = lib.kda_recurrent_steps_fused(ctypes.byref(dims),

@@ -27,7 +27,8 @@ def test_every_declared_symbol_is_exported():
             "kda_version", "kda_debug_set_phase_mask", "kda_debug_set_overlap",
             "kda_chunk_fwd_check", "kda_recurrent_steps_pooled", "kda_chunk_fwd_fused",
             "kda_recurrent_steps_fused", "kda_chunk_fwd_fused_workspace_size",
-            "kda_chunk_fwd_fused_min_workspace_size", "kda_debug_set_time_split"} <= names
+            "kda_chunk_fwd_fused_min_workspace_size", "kda_debug_set_time_split",
+            "kda_chunk_fwd_scalar_gate", "kda_recurrent_steps_pooled_scalar_gate"} <= names
     for n in names:
         assert hasattr(lib, n), n
 

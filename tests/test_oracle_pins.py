@@ -90,6 +90,32 @@ def test_reduces_to_gdn_when_alpha_is_channel_constant():
         np.testing.assert_allclose(hT[0, h], S, rtol=0, atol=1e-12)
 
 
+def test_scalar_gate_entry_equals_the_scalar_recurrence_written_out():
+    """kda_forward_scalar_gate / kda_steps_pooled_scalar_gate against Section 2.2's recurrence with
+    a scalar a_t, written out here with explicit matrices."""
+    rng = np.random.default_rng(121)
+    B, T, H, dk, dv = 2, 17, 2, 5, 4
+    q, k, v, g, b = _inputs(rng, B, T, H, dk, dv)
+    gh = np.ascontiguousarray(g[..., 0])                  # [B,T,H]
+    h0 = rng.standard_normal((B, H, dk, dv))
+    o, hT = oracle.kda_forward_scalar_gate(q, k, v, gh, b, h0=h0, scale=0.7)
+    o_p, pool = oracle.kda_steps_pooled_scalar_gate(q[:, :6], k[:, :6], v[:, :6], gh[:, :6], b[:, :6], h0, scale=0.7)
+    for bi in range(B):
+        for h in range(H):
+            S = h0[bi, h].copy()
+            for t in range(T):
+                kt, vt = k[bi, t, h].astype(np.float64), v[bi, t, h].astype(np.float64)
+                a, bt = np.exp(np.float64(gh[bi, t, h])), np.float64(b[bi, t, h])
+                S = a * (np.eye(dk) - bt * np.outer(kt, kt)) @ S + bt * np.outer(kt, vt)
+                ot = 0.7 * (S.T @ q[bi, t, h].astype(np.float64))
+                np.testing.assert_allclose(o[bi, t, h], ot, rtol=0, atol=1e-12)
+                if t < 6:
+                    np.testing.assert_allclose(o_p[bi, t, h], ot, rtol=0, atol=1e-12)
+                if t == 5:
+                    np.testing.assert_allclose(pool[bi, h], S, rtol=0, atol=1e-12)
+            np.testing.assert_allclose(hT[bi, h], S, rtol=0, atol=1e-12)
+
+
 def test_beta_zero_is_pure_decay_of_h0():
     """Eq. (1) with beta = 0: S_t = Diag(prod alpha) h0, o_t = (Gamma_t . q_t)^T h0."""
     rng = np.random.default_rng(13)
