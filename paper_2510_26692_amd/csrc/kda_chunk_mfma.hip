@@ -75,7 +75,7 @@ constexpr int kTileM = 64 * kLdM * 2;                   // 9216 B
 constexpr int kX = 0;                                   // fp32 (I + L)^-1
 constexpr int kTab = kX;                                //   early alias: per-channel constants, 7 x [4][128] fp32
 constexpr int kFix = kTab + 7 * 2048;                   //   early alias: scratch of the strong-channel fix-up
-constexpr int kL = kX + kTileF;                         // fp32 L = StrictTril(Diag(beta) A_kk)
+constexpr int kL = kX + kTileF;                         // fp32 L = StrictTril(Diag(beta) A_kk), stored transposed
 constexpr int kAq = kL + kTileF;                        // fp16 Tril(A_qk)
 constexpr int kColS = kL;                               //   early alias: column operands [6 tiles][4][64] x 16 B
 constexpr int kV = kL;                                  //   late alias: fp16 V tile
@@ -660,18 +660,23 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     // ---- L and Tril(A_qk) tiles of row R; fp16 V tile ----
     {
-        float *sL = reinterpret_cast<float *>(lds + kL);
+        // (L is kept transposed, sLT[column][row]: a lane's four rows of a column are contiguous, one
+        // 16-byte store per tile, and the substitution below reads a column of L as a row)
+        float *sLT = reinterpret_cast<float *>(lds + kL);
         _Float16 *sAq = reinterpret_cast<_Float16 *>(lds + kAq);
+        const f32x4 beta4 = *reinterpret_cast<const f32x4 *>(sBeta + 16 * R + 4 * g);
 #pragma unroll
         for (int I = 0; I < 4; ++I) {
             const int i = 16 * I + m;                       // column token of this lane
             if (I <= R) {
+                f32x4 lv;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int r = 16 * R + 4 * g + j;
-                    sL[r * kLdF + i] = (i < r) ? sBeta[r] * res_kk[I][j] : 0.f;
+                    lv[j] = (i < r) ? beta4[j] * res_kk[I][j] : 0.f;
                     sAq[r * kLdM + i] = (_Float16)((i <= r) ? res_qk[I][j] * scale : 0.f);
                 }
+                *reinterpret_cast<f32x4 *>(sLT + i * kLdF + 16 * R + 4 * g) = lv;
             } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) sAq[(16 * R + 4 * g + j) * kLdM + i] = (_Float16)0.f;
@@ -693,17 +698,21 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     // ---- UT transform, diagonal 16x16 blocks: column j of (I + L_ww)^-1 per lane ----
     {
-        const float *sL = reinterpret_cast<const float *>(lds + kL);
+        // (column by column: once x[i] is final, the updates of the rows below it are independent
+        // of one another, so the dependent chain is 16 long instead of 120; each x[r] still
+        // receives its terms in the order i = 0, 1, ..)
+        const float *sLT = reinterpret_cast<const float *>(lds + kL);
         float *sX = reinterpret_cast<float *>(lds + kX);
         const int j = lane & 15, w = wave;
         float x[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float s = (r == j) ? 1.f : 0.f;
-            const float *row = sL + (16 * w + r) * kLdF + 16 * w;
+        for (int r = 0; r < 16; ++r) x[r] = (r == j) ? 1.f : 0.f;
 #pragma unroll
-            for (int i = 0; i < r; ++i) s = fmaf(-row[i], x[i], s);
-            x[r] = (r < j) ? 0.f : s;
+        for (int i = 0; i < 15; ++i) {
+            const float *col = sLT + (16 * w + i) * kLdF + 16 * w;      // L[16 w + r][16 w + i], r = 0..15
+            const float xi = x[i];
+#pragma unroll
+            for (int r = i + 1; r < 16; ++r) x[r] = fmaf(-col[r], xi, x[r]);
         }
         if (lane < 16) {
 #pragma unroll
@@ -733,7 +742,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     // ---- UT transform, off-diagonal blocks: X_RI = -X_RR sum_{I<=J<R} L_RJ X_JI (fp32 MFMA) ----
     {
-        const float *sL = reinterpret_cast<const float *>(lds + kL);
+        const float *sLT = reinterpret_cast<const float *>(lds + kL);
         float *sX = reinterpret_cast<float *>(lds + kX);
         for (int Rr = 1; Rr < 4; ++Rr) {
             if (wave < Rr) {
@@ -742,7 +751,7 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
                 for (int J = Ii; J < Rr; ++J) {
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks) {
-                        const float a = sL[(16 * Rr + m) * kLdF + 16 * J + 4 * ks + g];
+                        const float a = sLT[(16 * J + 4 * ks + g) * kLdF + 16 * Rr + m];   // L[16 Rr + m][16 J + 4 ks + g]
                         const float b = sX[(16 * J + 4 * ks + g) * kLdF + 16 * Ii + m];
                         t = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, t, 0, 0, 0);
                     }
