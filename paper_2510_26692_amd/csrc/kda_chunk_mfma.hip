@@ -105,6 +105,21 @@ template <int N> __device__ __forceinline__ float row_shr(float x)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x110 + N, 0xf, 0xf, true));
 }
 
+// Transposing LDS read (ds_read_b64_tr_b16): `block` points at element (row 0, column 0) of a
+// 4 x 16 block of 16-bit values with `ld` values between rows, the same for the 16 lanes of a group
+// (lanes 16 i .. 16 i + 15).  Lane c of the group receives column c of rows 0..3, i.e. the four
+// values an MFMA operand wants in consecutive contraction slots.  (Lane p hands the hardware the
+// address of row p / 4, columns 4 (p % 4) .. + 3; it returns to lane c element c % 4 of the four
+// rows handed in by lanes c / 4, 4 + c / 4, 8 + c / 4, 12 + c / 4.)
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x2 lds_read_tr4(const uint8_t *block, int ld, int lane)
+{
+    const int p = lane & 15;
+    const uint8_t *a = block + ((p >> 2) * ld + 4 * (p & 3)) * 2;
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)a);
+    return __builtin_bit_cast(u32x2, v);
+}
+
 // Workspace slots are written and read through buffer instructions with the device-scope cache
 // policy (sc1): the stores write through the L2 of the writing XCD and the loads do not trust
 // the L2 of the reading XCD, so a slot produced by one workgroup can be consumed by another one
@@ -721,20 +736,16 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
     }
     // ---- copy (Gamma^{i->C}.K)^T out in MFMA register order ----
     {
-        const int x = lane & 31, hh = lane >> 5;
-        const uint16_t *sKp = reinterpret_cast<const uint16_t *>(lds + kKp);
+        // lane (x = lane % 32, hh): channel 32 tau + x, tokens 32 rho + kidx(s, hh, 0..7), which are two
+        // runs of four consecutive tokens: two transposing reads per fragment
+        const int hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int f = wave * 4 + i;                     // Kt frag f = (tau*2 + rho)*2 + s
             const int tau = f >> 2, rho = (f >> 1) & 1, s = f & 1;
-            uint32_t w4[4];
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const int t0 = 32 * rho + kidx(s, hh, e), t1 = 32 * rho + kidx(s, hh, e + 1);
-                w4[e >> 1] = (uint32_t)sKp[t0 * kLdH + 32 * tau + x] |
-                             ((uint32_t)sKp[t1 * kLdH + 32 * tau + x] << 16);
-            }
-            u32x4 o4 = {w4[0], w4[1], w4[2], w4[3]};
+            const uint8_t *blk = lds + kKp + ((32 * rho + kidx(s, hh, 0)) * kLdH + 32 * tau + xb) * 2;
+            const u32x2 lo = lds_read_tr4(blk, kLdH, lane), hi = lds_read_tr4(blk + 8 * kLdH * 2, kLdH, lane);
+            u32x4 o4 = {lo[0], lo[1], hi[0], hi[1]};
             slot_store16<kPolicy>(out, kOffKt + f * kFragBytes + lane * 16, o4);
         }
     }
@@ -817,23 +828,19 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
 
     // ---- W^T = (Gamma.K)^T M^T (wave = d_k tile) and U = M V (wave = d_v tile) ----
     {
-        const int x = lane & 31, hh = lane >> 5;
-        const uint16_t *sGK = reinterpret_cast<const uint16_t *>(lds + kGK);
-        const uint16_t *sV = reinterpret_cast<const uint16_t *>(lds + kV);
+        // operands with the tokens in the contraction slots: lane (x, hh) wants channel 32 wave + x of
+        // the eight tokens 16 s4 + 8 hh + 0..7 of the [token][channel] tiles: two transposing reads each
+        const int x = lane & 31, hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
         h8 mf[2][4], gk[4], vv[4];
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
 #pragma unroll
             for (int rho = 0; rho < 2; ++rho)
                 mf[rho][s4] = *reinterpret_cast<const h8 *>(lds + kM + ((32 * rho + x) * kLdM + 16 * s4 + 8 * hh) * 2);
-            uint32_t wg[4], wv[4];
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const int t0 = 16 * s4 + 8 * hh + e;
-                wg[e >> 1] = (uint32_t)sGK[t0 * kLdH + 32 * wave + x] | ((uint32_t)sGK[(t0 + 1) * kLdH + 32 * wave + x] << 16);
-                wv[e >> 1] = (uint32_t)sV[t0 * kLdH + 32 * wave + x] | ((uint32_t)sV[(t0 + 1) * kLdH + 32 * wave + x] << 16);
-            }
-            u32x4 pg = {wg[0], wg[1], wg[2], wg[3]}, pv = {wv[0], wv[1], wv[2], wv[3]};
+            const int off = ((16 * s4 + 8 * hh) * kLdH + 32 * wave + xb) * 2;
+            const u32x2 g0 = lds_read_tr4(lds + kGK + off, kLdH, lane), g1 = lds_read_tr4(lds + kGK + off + 4 * kLdH * 2, kLdH, lane);
+            const u32x2 v0 = lds_read_tr4(lds + kV + off, kLdH, lane), v1 = lds_read_tr4(lds + kV + off + 4 * kLdH * 2, kLdH, lane);
+            u32x4 pg = {g0[0], g0[1], g1[0], g1[1]}, pv = {v0[0], v0[1], v1[0], v1[1]};
             gk[s4] = __builtin_bit_cast(h8, pg);
             vv[s4] = __builtin_bit_cast(h8, pv);
         }
