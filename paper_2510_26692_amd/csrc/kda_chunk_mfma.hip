@@ -76,7 +76,7 @@ constexpr int kX = 0;                                   // fp32 (I + L)^-1
 constexpr int kTab = kX;                                //   early alias: per-channel constants, 7 x [4][128] fp32
 constexpr int kFix = kTab + 7 * 2048;                   //   early alias: scratch of the strong-channel fix-up
 constexpr int kL = kX + kTileF;                         // fp32 L = StrictTril(Diag(beta) A_kk), stored transposed
-constexpr int kAq = kL + kTileF;                        // fp16 Tril(A_qk)
+constexpr int kAq = kL + kTileF;                        // fp16 Tril(A_qk), stored transposed
 constexpr int kColS = kL;                               //   early alias: column operands [6 tiles][4][64] x 16 B
 constexpr int kV = kL;                                  //   late alias: fp16 V tile
 constexpr int kGK = kAq + kTileM;                       // fp16 Gamma.K
@@ -678,24 +678,26 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
         // (L is kept transposed, sLT[column][row]: a lane's four rows of a column are contiguous, one
         // 16-byte store per tile, and the substitution below reads a column of L as a row)
         float *sLT = reinterpret_cast<float *>(lds + kL);
-        _Float16 *sAq = reinterpret_cast<_Float16 *>(lds + kAq);
+        // (Tril(A_qk) likewise, sAqT[column][row] in fp16: 8-byte stores here, transposing reads below)
+        uint16_t *sAqT = reinterpret_cast<uint16_t *>(lds + kAq);
         const f32x4 beta4 = *reinterpret_cast<const f32x4 *>(sBeta + 16 * R + 4 * g);
 #pragma unroll
         for (int I = 0; I < 4; ++I) {
             const int i = 16 * I + m;                       // column token of this lane
+            u32x2 av = {0u, 0u};
             if (I <= R) {
                 f32x4 lv;
+                float qv[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int r = 16 * R + 4 * g + j;
                     lv[j] = (i < r) ? beta4[j] * res_kk[I][j] : 0.f;
-                    sAq[r * kLdM + i] = (_Float16)((i <= r) ? res_qk[I][j] * scale : 0.f);
+                    qv[j] = (i <= r) ? res_qk[I][j] * scale : 0.f;
                 }
                 *reinterpret_cast<f32x4 *>(sLT + i * kLdF + 16 * R + 4 * g) = lv;
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) sAq[(16 * R + 4 * g + j) * kLdM + i] = (_Float16)0.f;
+                av[0] = pack_h2(qv[0], qv[1]); av[1] = pack_h2(qv[2], qv[3]);
             }
+            *reinterpret_cast<u32x2 *>(sAqT + i * kLdM + 16 * R + 4 * g) = av;   // zeros above the diagonal tiles
         }
     }
     __syncthreads();                                                               // B5
@@ -801,13 +803,14 @@ void kda_intra_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict
             u32x2 w2 = {pack_h2(val[0], val[1]), pack_h2(val[2], val[3])};
             *reinterpret_cast<u32x2 *>(sM + r * kLdM + j0) = w2;
         }
-        const int x = lane & 31, hh = lane >> 5;
+        // lane (x, hh) of fragment (rr, ri, s): row token 32 rr + x, column tokens 32 ri + 16 s + 4 hh + 0..3
+        // and + 8..11, which are rows of the transposed tile
+        const int hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
         for (int idx = wave; idx < 6; idx += 4) {
             const int p = idx >> 1, s = idx & 1;
             const int rr = (p == 0) ? 0 : 1, ri = (p == 2) ? 1 : 0;
-            const int at = ((32 * rr + x) * kLdM + 32 * ri + 16 * s + 4 * hh) * 2;
-            const u32x2 a = *reinterpret_cast<const u32x2 *>(lds + kAq + at);
-            const u32x2 b = *reinterpret_cast<const u32x2 *>(lds + kAq + at + 16);
+            const uint8_t *blk = lds + kAq + ((32 * ri + 16 * s + 4 * hh) * kLdM + 32 * rr + xb) * 2;
+            const u32x2 a = lds_read_tr4(blk, kLdM, lane), b = lds_read_tr4(blk + 8 * kLdM * 2, kLdM, lane);
             u32x4 o4 = {a[0], a[1], b[0], b[1]};
             slot_store16<kPolicy>(out, kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16, o4);
         }
