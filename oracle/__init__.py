@@ -11,11 +11,14 @@ input parameterisation of Section 4 (L2Norm, Sigmoid, the decay function) and `e
 the output gate of the same section (head-wise RMSNorm times a sigmoid gate), in float64.
 `kda_forward_scalar_gate` / `kda_steps_pooled_scalar_gate` are the scalar-gate special case of
 Eq. (1) (Section 2.2, alpha_t = a_t I): the same recurrence on the decay repeated over the channels.
+`kda_backward` is the reverse-mode derivative of that recurrence, token by token (the paper derives no
+backward algorithm; the chain rule on Eq. (1) is the definition), pinned by finite differences of the
+two forward statements.
 """
 import numpy as _np
 
 from . import epilogue, prologue  # noqa: F401
-from .recurrence import build, kda_forward, kda_step, kda_steps_pooled, num_threads  # noqa: F401
+from .recurrence import build, kda_backward, kda_forward, kda_step, kda_steps_pooled, num_threads  # noqa: F401
 
 
 def kda_forward_raw(q_raw, k_raw, v, gate, beta_logit, eps=1e-6, a_scale=None, dt_bias=None, **kw):

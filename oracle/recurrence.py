@@ -43,6 +43,10 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p]
+        lib.kda_oracle_backward.restype = ctypes.c_int
+        lib.kda_oracle_backward.argtypes = [
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int64] + [ctypes.c_void_p] * 7 + [ctypes.c_double] + [ctypes.c_void_p] * 8
         _lib = lib
     return _lib
 
@@ -139,3 +143,45 @@ def kda_steps_pooled(q, k, v, log_alpha, beta, S_pool, state_indices=None, scale
         o[act] = o_a
         pool[idx[act]] = S_a
     return o, pool
+
+
+def kda_backward(q, k, v, log_alpha, beta, do, dhT=None, h0=None, cu_seqlens=None, scale=1.0):
+    """Gradients of sum(o * do) + sum(hT * dhT) with respect to the inputs of `kda_forward`
+    (reverse-mode differentiation of Eq. (1), token by token, in float64).
+
+    do: [B,T,H,dv]; dhT: [N,H,dk,dv] or None (zeros).  Returns a dict with dq, dk, dlog_alpha
+    [B,T,H,dk], dv [B,T,H,dv], dbeta [B,T,H] and dh0 [N,H,dk,dv], float64.  Rows of `do` that
+    belong to no sequence of a packed batch are ignored and their gradients are zero.
+    """
+    q = _f32(q)
+    B, T, H, dk = q.shape
+    k = _f32(k, (B, T, H, dk))
+    log_alpha = _f32(log_alpha, (B, T, H, dk))
+    v = _f32(v)
+    dv = v.shape[-1]
+    beta = _f32(beta, (B, T, H))
+    cu = None
+    if cu_seqlens is not None:
+        cu = np.ascontiguousarray(np.asarray(cu_seqlens), dtype=np.int64)
+        N = cu.shape[0] - 1
+    else:
+        N = B
+    h0d = None if h0 is None else np.ascontiguousarray(np.asarray(h0), dtype=np.float64)
+    if h0d is not None and h0d.shape != (N, H, dk, dv):
+        raise ValueError("bad h0 shape %r" % (h0d.shape,))
+    dod = np.ascontiguousarray(np.asarray(do), dtype=np.float64)
+    if dod.shape != (B, T, H, dv):
+        raise ValueError("bad do shape %r" % (dod.shape,))
+    dhTd = None if dhT is None else np.ascontiguousarray(np.asarray(dhT), dtype=np.float64)
+    if dhTd is not None and dhTd.shape != (N, H, dk, dv):
+        raise ValueError("bad dhT shape %r" % (dhTd.shape,))
+    out = {"dq": np.empty((B, T, H, dk)), "dk": np.empty((B, T, H, dk)),
+           "dv": np.empty((B, T, H, dv)), "dlog_alpha": np.empty((B, T, H, dk)),
+           "dbeta": np.empty((B, T, H)), "dh0": np.empty((N, H, dk, dv))}
+    rc = _load().kda_oracle_backward(B, T, H, dk, dv, N, _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha),
+                                     _ptr(beta), _ptr(h0d), _ptr(cu), float(scale), _ptr(dod),
+                                     _ptr(dhTd), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
+                                     _ptr(out["dlog_alpha"]), _ptr(out["dbeta"]), _ptr(out["dh0"]))
+    if rc != 0:
+        raise ValueError("kda_oracle_backward rejected the call (code %d)" % rc)
+    return out
