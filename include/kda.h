@@ -1,5 +1,5 @@
 /*
- * kda.h -- C ABI of libkda: Kimi Delta Attention (KDA) forward on one MI355X.
+ * kda.h -- C ABI of libkda: Kimi Delta Attention (KDA), forward and backward, on one MI355X.
  *
  * KDA is the gated delta rule of the paper's Section 3, Eq. (1):
  *
@@ -129,6 +129,42 @@ kda_status kda_chunk_fwd(const kda_dims *dims,
                          const void *log_alpha, const void *beta,
                          const float *h0, const int32_t *cu_seqlens,
                          void *o, float *hT,
+                         void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
+
+/*
+ * Backward pass of kda_chunk_fwd: gradients of  sum(o . d_o) + sum(hT . d_hT)  with respect to
+ * every input.  The paper motivates a training kernel (Section 3.1 compares the chunkwise form
+ * with the general DPLR one for exactly that purpose) but derives no backward algorithm; what
+ * is computed here is the chain rule applied to Eq. (1), organised chunk by chunk through the
+ * quantities of Section 3.1 (A_kk, A_qk, the UT transform, the chunk state update), in fp32
+ * throughout, every decay kept as a pairwise difference of cumulative log decays so that it
+ * cannot overflow.
+ *
+ *   q, k, v, log_alpha, beta, h0, cu_seqlens   as for kda_chunk_fwd (in_dtype KDA_F32 or
+ *                              KDA_BF16, dk == dv in {64, 128}; out_dtype is ignored)
+ *   d_o        [B,T,H,dv]      fp32 gradient of o (rows of tokens owned by no sequence are
+ *                              not read)
+ *   d_hT       [N,H,dk,dv]     fp32 gradient of the final states, or NULL for zeros
+ *   dq, dk, dlog_alpha [B,T,H,dk], dv [B,T,H,dv], dbeta [B,T,H]    fp32, written; rows of
+ *                              tokens owned by no sequence are left untouched
+ *   dh0        [N,H,dk,dv]     fp32 gradient of the initial states (equals d_hT for an empty
+ *                              sequence), or NULL if not wanted
+ *   workspace                  at least kda_chunk_bwd_workspace_size(dims) bytes, 256-byte
+ *                              aligned: the state at the start of every chunk and its
+ *                              gradient (2 * dk * dv floats per chunk and head) plus three
+ *                              [tokens, H, dv] arrays and two C x C tiles per chunk and head
+ * No gradient may alias an input or another gradient.  Sequences of more than 65535 * 64
+ * tokens are KDA_ERR_UNSUPPORTED.  Everything runs on `hip_stream`.
+ */
+size_t kda_chunk_bwd_workspace_size(const kda_dims *dims);
+kda_status kda_chunk_bwd(const kda_dims *dims,
+                         const void *q, const void *k, const void *v,
+                         const void *log_alpha, const void *beta,
+                         const float *h0, const int32_t *cu_seqlens,
+                         const float *d_o, const float *d_hT,
+                         float *dq, float *dk, float *dv, float *dlog_alpha, float *dbeta,
+                         float *dh0,
                          void *workspace, size_t workspace_bytes,
                          void *hip_stream);
 

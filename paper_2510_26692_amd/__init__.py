@@ -1,4 +1,4 @@
-"""MI355X-native Kimi Delta Attention (KDA) forward: thin binding over libkda.so.
+"""MI355X-native Kimi Delta Attention (KDA), forward and backward: thin binding over libkda.so.
 
 The package holds the HIP sources (``csrc/``), the in-tree build script and a
 ctypes binding whose functions carry the names of the C entry points in
@@ -9,5 +9,6 @@ any entry point without the built library raises.
 from .kda import (KdaDims, KdaError, KdaEpilogue, KdaPrologue, kda_chunk_fwd, kda_chunk_fwd_check, kda_chunk_fwd_fused,
                   kda_recurrent_steps_fused, kda_debug_set_overlap, kda_debug_set_time_split,  # noqa: F401
                   kda_debug_set_phase_mask, kda_chunk_fwd_min_workspace_size, kda_chunk_fwd_workspace_size, kda_last_error, kda_recurrent_step, kda_recurrent_steps_pooled,
-                  kda_chunk_fwd_scalar_gate, kda_recurrent_steps_pooled_scalar_gate,
+                  kda_chunk_fwd_scalar_gate, kda_recurrent_steps_pooled_scalar_gate, kda_chunk_bwd,
+                  kda_chunk_bwd_workspace_size,
                   kda_status_string, kda_version, library_path, load_library)

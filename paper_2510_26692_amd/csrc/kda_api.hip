@@ -1,6 +1,6 @@
 // C ABI of libkda: argument validation, error strings and dispatch to the
 // kernels.  Nothing here touches tensor data; every step of the path runs in
-// the kernels of kda_step.hip, kda_chunk_f32.hip and kda_chunk_mfma.hip.
+// the kernels of kda_step.hip, kda_chunk_f32.hip, kda_chunk_mfma.hip and kda_chunk_bwd.hip.
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -34,6 +34,11 @@ kda_status chunk_mfma_dispatch(const kda_dims *, const kda_prologue *, const kda
                                float *, void *, size_t, bool scalar_gate, hipStream_t);
 size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal, bool output_gate);
 size_t chunk_mfma_status_offset(const kda_dims *, size_t workspace_bytes);
+size_t chunk_bwd_workspace_size(const kda_dims *);
+kda_status chunk_bwd_dispatch(const kda_dims *, const void *, const void *, const void *, const void *,
+                              const void *, const float *, const int32_t *, const float *, const float *,
+                              float *, float *, float *, float *, float *, float *, void *, size_t,
+                              hipStream_t);
 
 // Diagnostics: which kernels of the matrix-core prefill run (bit 0 kda_intra, bit 1 kda_scan).
 int g_phase_mask = 3;
@@ -148,6 +153,49 @@ size_t kda_chunk_fwd_fused_workspace_size(const kda_dims *d, const kda_epilogue 
 size_t kda_chunk_fwd_fused_min_workspace_size(const kda_dims *d, const kda_epilogue *epi)
 {
     return workspace_size(d, true, epi != nullptr);
+}
+
+size_t kda_chunk_bwd_workspace_size(const kda_dims *d)
+{
+    if (!d || d->chunk != kChunk) return 0;
+    const char saved0 = g_last_error[0];
+    if (check_dims(d, d->num_seqs != d->batch) != KDA_OK) { g_last_error[0] = saved0; return 0; }
+    return chunk_bwd_workspace_size(d);
+}
+
+kda_status kda_chunk_bwd(const kda_dims *d, const void *q, const void *k, const void *v,
+                         const void *log_alpha, const void *beta, const float *h0,
+                         const int32_t *cu_seqlens, const float *d_o, const float *d_hT,
+                         float *dq, float *dk, float *dv, float *dlog_alpha, float *dbeta, float *dh0,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    kda_status st = check_dims(d, cu_seqlens != nullptr);
+    if (st != KDA_OK) return st;
+    if (d->chunk != kChunk) return fail(KDA_ERR_UNSUPPORTED, "chunk must be %d, got %d", kChunk, d->chunk);
+    const bool empty = d->seqlen == 0 || d->heads == 0 || d->batch == 0;
+    if (!empty && (!q || !k || !v || !log_alpha || !beta || !d_o || !dq || !dk || !dv || !dlog_alpha || !dbeta))
+        return fail(KDA_ERR_INVALID_ARG, "inputs, d_o and the five per-token gradients must be non-NULL");
+    const void *ptrs[] = {q, k, v, log_alpha, beta, h0, d_o, d_hT, dq, dk, dv, dlog_alpha, dbeta, dh0};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return fail(KDA_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u)
+        return fail(KDA_ERR_INVALID_ARG, "cu_seqlens must be 4-byte aligned");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u)
+        return fail(KDA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (!empty) {
+        const void *outs[] = {dq, dk, dv, dlog_alpha, dbeta, dh0};
+        const void *ins[] = {q, k, v, log_alpha, beta, h0, d_o, d_hT};
+        for (int a = 0; a < 6; ++a) {
+            if (!outs[a]) continue;
+            for (const void *in : ins)
+                if (outs[a] == in) return fail(KDA_ERR_INVALID_ARG, "a gradient must not alias an input");
+            for (int b = a + 1; b < 6; ++b)
+                if (outs[a] == outs[b]) return fail(KDA_ERR_INVALID_ARG, "gradients must not alias each other");
+        }
+    }
+    if (d->num_seqs == 0 || d->heads == 0) return KDA_OK;
+    return chunk_bwd_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, d_o, d_hT, dq, dk, dv, dlog_alpha,
+                              dbeta, dh0, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 static kda_status check_epilogue(const kda_epilogue *epi)

@@ -1,0 +1,721 @@
+// Chunkwise backward pass of KDA in fp32 (gradients of Section 3, Eq. (1) through the chunkwise
+// form of Section 3.1).  The paper derives no backward algorithm; this one is the chain rule
+// applied to the chunk equations, with every decay kept as a pairwise difference in the log
+// domain (2^(G_r - G_i) with i <= r, 2^(G_r), 2^(G_C - G_r): all at most 1), so that nothing
+// can overflow whatever the decay.
+//
+// Per chunk of C = 64 tokens (G inclusive running sum of log alpha, S0 the state at the chunk's
+// start, beta, k, q, v the chunk's rows):
+//
+//   forward    A_kk[r,i] = sum_d k_r,d k_i,d e^(G_r,d - G_i,d),  A_qk likewise with q_r
+//              L = StrictTril(Diag(beta) A_kk),  T = (I + L)^-1,  M = T Diag(beta)
+//              Kg = Gamma.K,  Qg = Gamma.Q,  Kt = Gamma^{i->C}.K,  P = Tril(A_qk)
+//              Y = V - Kg S0,   Vn = M Y                               ("pseudo"-values)
+//              O = scale (Qg S0 + P Vn),   S1 = Diag(e^(G_C)) S0 + Kt^T Vn
+//
+//   backward   (dO pre-multiplied by scale, dS1 the gradient of the chunk's end state)
+//              dVn = P^T dO + Kt dS1            X = M^T dVn   (= dV)
+//              dS0 = Diag(e^(G_C)) dS1 + Qg^T dO - Kg^T X
+//              dQg = dO S0^T    dKg = -X S0^T    dKt = Vn dS1^T
+//              dP  = Tril(dO Vn^T)               dM  = Tril(dVn Y^T)
+//              dT  = dM Diag(beta)               dbeta_j  = sum_r dM[r,j] T[r,j]
+//              dL  = -StrictTril(T^T dT T^T)     dbeta_r += sum_i dL[r,i] A_kk[r,i]
+//              dA_kk = Diag(beta) dL
+//              dq_r = Gamma_r . dQg_r + sum_{i<=r} dP[r,i] k_i e^(G_r - G_i)
+//              dk_t = Gamma_t . dKg_t + e^(G_C - G_t) . dKt_t
+//                     + sum_{i<t} dA_kk[t,i] k_i e^(G_t - G_i)
+//                     + sum_{r>t} dA_kk[r,t] k_r e^(G_r - G_t) + sum_{r>=t} dP[r,t] q_r e^(G_r - G_t)
+//              dG_t = (every product above that carries e^(+G_t)) - (those that carry e^(-G_t)),
+//              dG_C = e^(G_C) . rowsum(dS1 . S0) + sum_t dKt_t . Kt_t
+//              dlog_alpha_t = sum_{r>=t} dG_r + dG_C
+//
+// Four kernels, all plain fp32 FMAs on LDS tiles (this path is written for correctness and
+// clarity; the matrix cores are not used yet):
+//   kda_bwd_states   one workgroup per (sequence, head, 32 state columns) walks the chunks
+//                    forward and leaves S0 of every chunk, Y and Vn in the workspace
+//   kda_bwd_scan     the same decomposition walks the chunks backward with dS: dVn, dV, the dS1
+//                    of every chunk, dh0  (the columns of S never mix, neither do those of dS)
+//   kda_bwd_products one workgroup per (chunk, head): the products with S0 and dS1 (dQg, dKg,
+//                    dKt, dG_C) folded into dq, dk and dG, and the two C x C products dP, dM
+//   kda_bwd_chain    one workgroup per (chunk, head): the gradient through T and the pairwise
+//                    decay terms, the reverse running sum that turns dG into dlog_alpha, dbeta
+#include "kda_common.h"
+
+namespace kda {
+namespace {
+
+constexpr int kC = kChunk;
+constexpr int kBV = 32;                 // state columns per workgroup of the two scans
+constexpr int kLA = kC + 2;             // row stride of a packed C x C tile
+
+// Slot of chunk c of sequence n among all chunk slots (times H + h gives the workspace index).
+// Packed batches: floor(cu[n] / C) + n + c is strictly increasing over (n, c) and bounded by
+// floor(total / C) + N.
+__device__ __forceinline__ int64_t chunk_slot(const int32_t *cu, int n, int64_t chunks_per_seq, int64_t c)
+{
+    return cu ? (int64_t)(cu[n] / kC) + n + c : (int64_t)n * chunks_per_seq + c;
+}
+
+// Loads one chunk and forms the quantities every backward kernel starts from.  On return
+// (the last statement is a barrier):
+//   sQ, sK [C][D+1]  q and k as given (zero rows past nv)
+//   sG     [C][D+1]  G in log2 units (rows past nv repeat the last valid row)
+//   sA     [C][kLA]  strict lower part [r][i]: T - I;  upper part [i][r+1] for i <= r:
+//                    A_qk[r][i] (kUpperKK false) or A_kk[r][i] (true)
+//   sBeta [C], sGend [D] (G of the last row)
+template <typename Tin, int D, bool kUpperKK>
+__device__ void chunk_setup(const Tin *__restrict__ q, const Tin *__restrict__ k,
+                            const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
+                            int64_t tok0, int nv, int H, int h, float *sQ, float *sK, float *sG,
+                            float *sA, float *sBeta, float *sGend, int tid)
+{
+    constexpr int LD = D + 1;
+    for (int idx = tid; idx < kC * D; idx += 256) {
+        const int r = idx / D, d = idx % D;
+        float fq = 0.f, fk = 0.f, fg = 0.f;
+        if (r < nv) {
+            const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
+            fq = load_as_float(q + off);
+            fk = load_as_float(k + off);
+            fg = load_as_float(log_alpha + off) * kLog2e;
+        }
+        sQ[r * LD + d] = fq; sK[r * LD + d] = fk; sG[r * LD + d] = fg;
+    }
+    if (tid < kC) sBeta[tid] = (tid < nv) ? load_as_float(beta + (tok0 + tid) * H + h) : 0.f;
+    __syncthreads();
+    if (tid < D) {
+        float run = 0.f;
+        for (int r = 0; r < kC; ++r) { run += sG[r * LD + tid]; sG[r * LD + tid] = run; }
+        sGend[tid] = run;
+    }
+    __syncthreads();
+    {
+        const int i = tid & 63;
+        for (int r = tid >> 6; r < kC; r += 4) {
+            if (i <= r) {
+                float akk = 0.f, aqk = 0.f;
+                for (int d = 0; d < D; ++d) {
+                    const float e = fast_exp2(sG[r * LD + d] - sG[i * LD + d]);
+                    const float t = sK[i * LD + d] * e;
+                    akk = fmaf(sK[r * LD + d], t, akk);
+                    aqk = fmaf(sQ[r * LD + d], t, aqk);
+                }
+                if (i < r) sA[r * kLA + i] = sBeta[r] * akk;
+                sA[i * kLA + r + 1] = kUpperKK ? akk : aqk;
+            }
+        }
+    }
+    __syncthreads();
+    // forward substitution, row by row: the strict lower part becomes (I + L)^-1 - I
+    for (int r = 1; r < kC; ++r) {
+        float val = 0.f;
+        const int j = tid;
+        if (j < r) {
+            val = -sA[r * kLA + j];
+            for (int i = j + 1; i < r; ++i) val = fmaf(-sA[r * kLA + i], sA[i * kLA + j], val);
+        }
+        __syncthreads();
+        if (j < r) sA[r * kLA + j] = val;
+        __syncthreads();
+    }
+}
+
+// Strict lower part T - I  ->  M = T Diag(beta), diagonal included.
+__device__ void scale_to_m(float *sA, const float *sBeta, int tid)
+{
+    for (int idx = tid; idx < kC * kC; idx += 256) {
+        const int r = idx >> 6, j = idx & 63;
+        if (j < r) sA[r * kLA + j] *= sBeta[j];
+        else if (j == r) sA[r * kLA + j] = sBeta[j];
+    }
+}
+
+// q, k, G tiles -> Gamma.Q, Gamma^{i->C}.K, Gamma.K (in sQ, sK, sG), as the forward kernel does.
+template <int D>
+__device__ void decay_operands(float *sQ, float *sK, float *sG, const float *sGend, int tid)
+{
+    constexpr int LD = D + 1;
+    for (int idx = tid; idx < kC * D; idx += 256) {
+        const int r = idx / D, d = idx % D;
+        const float G = sG[r * LD + d];
+        const float kk = sK[r * LD + d];
+        const float gam = fast_exp2(G);
+        sQ[r * LD + d] *= gam;
+        sG[r * LD + d] = kk * gam;
+        sK[r * LD + d] = kk * fast_exp2(sGend[d] - G);
+    }
+}
+
+template <int D> constexpr size_t scan_lds_floats()
+{
+    return 3 * kC * (D + 1) + kC * kLA + 3 * kC * kBV + D * kBV + kC + D;
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward walk: S0 of every chunk, Y = V - Kg S0 and Vn = M Y.
+// ------------------------------------------------------------------------------------------
+template <typename Tin, int D>
+__global__ __launch_bounds__(256)
+void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
+                           const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
+                           const Tin *__restrict__ beta, const float *__restrict__ h0,
+                           const int32_t *__restrict__ cu, float *__restrict__ Sc,
+                           float *__restrict__ Yw, float *__restrict__ Vnw, int64_t T, int H,
+                           int64_t chunks_per_seq)
+{
+    constexpr int LD = D + 1;
+    extern __shared__ float smem[];
+    float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;
+    float *sV = sA + kC * kLA, *sVn = sV + kC * kBV, *sX = sVn + kC * kBV;
+    float *sS = sX + kC * kBV, *sBeta = sS + D * kBV, *sGend = sBeta + kC;
+    (void)sX;
+
+    const int n = blockIdx.x, h = blockIdx.y, col0 = blockIdx.z * kBV, tid = threadIdx.x;
+    int64_t tok_base, len;
+    if (cu) { tok_base = cu[n]; len = (int64_t)cu[n + 1] - tok_base; }
+    else    { tok_base = (int64_t)n * T; len = T; }
+    const int64_t state_off = ((int64_t)n * H + h) * (int64_t)(D * D);
+    for (int idx = tid; idx < D * kBV; idx += 256) {
+        const int d = idx / kBV, c = idx % kBV;
+        sS[idx] = h0 ? h0[state_off + (int64_t)d * D + col0 + c] : 0.f;
+    }
+
+    int64_t ci = 0;
+    for (int64_t c0 = 0; c0 < len; c0 += kC, ++ci) {
+        const int nv = (int)((len - c0 < kC) ? (len - c0) : kC);
+        const int64_t tok0 = tok_base + c0;
+        const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
+        __syncthreads();
+        for (int idx = tid; idx < D * kBV; idx += 256) {
+            const int d = idx / kBV, c = idx % kBV;
+            Sc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sS[idx];
+        }
+        for (int idx = tid; idx < kC * kBV; idx += 256) {
+            const int r = idx / kBV, c = idx % kBV;
+            sV[idx] = (r < nv) ? load_as_float(v + ((tok0 + r) * H + h) * (int64_t)D + col0 + c) : 0.f;
+        }
+        chunk_setup<Tin, D, false>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sA, sBeta, sGend, tid);
+        scale_to_m(sA, sBeta, tid);
+        decay_operands<D>(sQ, sK, sG, sGend, tid);
+        __syncthreads();
+        const int c = tid & 31;
+        for (int r = tid >> 5; r < kC; r += 8) {                 // Y = V - Kg S0
+            float acc = 0.f;
+            for (int d = 0; d < D; ++d) acc = fmaf(sG[r * LD + d], sS[d * kBV + c], acc);
+            sV[r * kBV + c] -= acc;
+        }
+        __syncthreads();
+        for (int r = tid >> 5; r < kC; r += 8) {                 // Vn = M Y
+            float acc = 0.f;
+            for (int j = 0; j <= r; ++j) acc = fmaf(sA[r * kLA + j], sV[j * kBV + c], acc);
+            sVn[r * kBV + c] = acc;
+            if (r < nv) {
+                const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + col0 + c;
+                Yw[off] = sV[r * kBV + c];
+                Vnw[off] = acc;
+            }
+        }
+        __syncthreads();
+        for (int d = tid >> 5; d < D; d += 8) {                  // S1 = Diag(e^G_C) S0 + Kt^T Vn
+            float acc = sS[d * kBV + c] * fast_exp2(sGend[d]);
+            for (int j = 0; j < kC; ++j) acc = fmaf(sK[j * LD + d], sVn[j * kBV + c], acc);
+            sS[d * kBV + c] = acc;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward walk with dS: dVn, dV = X, the dS1 of every chunk, dh0.
+// ------------------------------------------------------------------------------------------
+template <typename Tin, int D>
+__global__ __launch_bounds__(256)
+void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
+                         const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
+                         const int32_t *__restrict__ cu, const float *__restrict__ d_o,
+                         const float *__restrict__ d_hT, float *__restrict__ dSc,
+                         float *__restrict__ dVnw, float *__restrict__ dv, float *__restrict__ dh0,
+                         int64_t T, int H, int64_t chunks_per_seq, float scale)
+{
+    constexpr int LD = D + 1;
+    extern __shared__ float smem[];
+    float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;
+    float *sdO = sA + kC * kLA, *sdVn = sdO + kC * kBV, *sX = sdVn + kC * kBV;
+    float *sdS = sX + kC * kBV, *sBeta = sdS + D * kBV, *sGend = sBeta + kC;
+
+    const int n = blockIdx.x, h = blockIdx.y, col0 = blockIdx.z * kBV, tid = threadIdx.x;
+    int64_t tok_base, len;
+    if (cu) { tok_base = cu[n]; len = (int64_t)cu[n + 1] - tok_base; }
+    else    { tok_base = (int64_t)n * T; len = T; }
+    const int64_t state_off = ((int64_t)n * H + h) * (int64_t)(D * D);
+    for (int idx = tid; idx < D * kBV; idx += 256) {
+        const int d = idx / kBV, c = idx % kBV;
+        sdS[idx] = d_hT ? d_hT[state_off + (int64_t)d * D + col0 + c] : 0.f;
+    }
+
+    const int64_t nchunks = (len + kC - 1) / kC;
+    for (int64_t ci = nchunks - 1; ci >= 0; --ci) {
+        const int64_t c0 = ci * kC;
+        const int nv = (int)((len - c0 < kC) ? (len - c0) : kC);
+        const int64_t tok0 = tok_base + c0;
+        const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
+        __syncthreads();
+        for (int idx = tid; idx < D * kBV; idx += 256) {         // dS1 of this chunk
+            const int d = idx / kBV, c = idx % kBV;
+            dSc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sdS[idx];
+        }
+        for (int idx = tid; idx < kC * kBV; idx += 256) {
+            const int r = idx / kBV, c = idx % kBV;
+            sdO[idx] = (r < nv) ? scale * d_o[((tok0 + r) * H + h) * (int64_t)D + col0 + c] : 0.f;
+        }
+        chunk_setup<Tin, D, false>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sA, sBeta, sGend, tid);
+        scale_to_m(sA, sBeta, tid);
+        decay_operands<D>(sQ, sK, sG, sGend, tid);
+        __syncthreads();
+        const int c = tid & 31;
+        for (int i = tid >> 5; i < kC; i += 8) {                 // dVn = P^T dO + Kt dS1
+            float acc = 0.f;
+            for (int r = i; r < kC; ++r) acc = fmaf(sA[i * kLA + r + 1], sdO[r * kBV + c], acc);
+            for (int d = 0; d < D; ++d) acc = fmaf(sK[i * LD + d], sdS[d * kBV + c], acc);
+            sdVn[i * kBV + c] = acc;
+            if (i < nv) dVnw[((tok0 + i) * H + h) * (int64_t)D + col0 + c] = acc;
+        }
+        __syncthreads();
+        for (int j = tid >> 5; j < kC; j += 8) {                 // X = M^T dVn = dV
+            float acc = 0.f;
+            for (int r = j; r < kC; ++r) acc = fmaf(sA[r * kLA + j], sdVn[r * kBV + c], acc);
+            sX[j * kBV + c] = acc;
+            if (j < nv) dv[((tok0 + j) * H + h) * (int64_t)D + col0 + c] = acc;
+        }
+        __syncthreads();
+        for (int d = tid >> 5; d < D; d += 8) {                  // dS0
+            float acc = sdS[d * kBV + c] * fast_exp2(sGend[d]);
+            for (int r = 0; r < kC; ++r) {
+                acc = fmaf(sQ[r * LD + d], sdO[r * kBV + c], acc);
+                acc = fmaf(-sG[r * LD + d], sX[r * kBV + c], acc);
+            }
+            sdS[d * kBV + c] = acc;
+        }
+    }
+    if (dh0) {
+        __syncthreads();
+        for (int idx = tid; idx < D * kBV; idx += 256) {
+            const int d = idx / kBV, c = idx % kBV;
+            dh0[state_off + (int64_t)d * D + col0 + c] = sdS[idx];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Per chunk: products with S0 and dS1, and the two C x C products.
+// ------------------------------------------------------------------------------------------
+template <int D> constexpr size_t products_lds_floats()
+{
+    return (size_t)(D > 2 * kC ? D : 2 * kC) * (D + 1) + 2 * kC * (D + 1) + 2 * D + (256 / D) * D;
+}
+
+// out[r][d] = sum_c sOp[r][c] * sS[d][c] for this thread's column d and rows rg + (256/D) j.
+template <int D, typename Sink>
+__device__ __forceinline__ void times_state_t(const float *sOp, const float *sS, int d, int rg, Sink &&sink)
+{
+    constexpr int LD = D + 1, RG = 256 / D;
+    for (int j0 = 0; j0 < kC / RG; j0 += 4) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < D; ++c) {
+            const float s = sS[d * LD + c];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = fmaf(sOp[(rg + RG * (j0 + u)) * LD + c], s, acc[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sink(rg + RG * (j0 + u), acc[u]);
+    }
+}
+
+// dst[r][i] = sum_c sR[r][c] * sI[i][c] for i <= r (row-major C x C in global memory).
+template <int D>
+__device__ __forceinline__ void lower_product(const float *sR, const float *sI, float *__restrict__ dst, int tid)
+{
+    constexpr int LD = D + 1;
+    const int i = tid & 63;
+    for (int r0 = (tid >> 6) * 16; r0 < (tid >> 6) * 16 + 16; r0 += 4) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < D; ++c) {
+            const float s = sI[i * LD + c];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = fmaf(sR[(r0 + u) * LD + c], s, acc[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) if (i <= r0 + u) dst[(r0 + u) * kC + i] = acc[u];
+    }
+}
+
+template <typename Tin, int D>
+__global__ __launch_bounds__(256)
+void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
+                             const Tin *__restrict__ log_alpha, const int32_t *__restrict__ cu,
+                             const float *__restrict__ d_o, const float *__restrict__ Sc,
+                             const float *__restrict__ dSc, const float *__restrict__ Yw,
+                             const float *__restrict__ Vnw, const float *__restrict__ dVnw,
+                             const float *__restrict__ dv, float *__restrict__ dq,
+                             float *__restrict__ dk, float *__restrict__ dg, float *__restrict__ dgC,
+                             float *__restrict__ Cw, int64_t T, int H, int64_t chunks_per_seq, float scale)
+{
+    constexpr int LD = D + 1, RG = 256 / D;
+    extern __shared__ float smem[];
+    float *sS = smem;                       // [D][LD] S0, later dS1; later two [C][LD] operand tiles
+    float *sOp = sS + (D > 2 * kC ? D : 2 * kC) * LD;   // [C][LD] row operand
+    float *sG = sOp + kC * LD;              // [C][LD] G (log2 units)
+    float *sGend = sG + kC * LD;            // [D]
+    float *sgc = sGend + D;                 // [D]
+    float *sPart = sgc + D;                 // [RG][D]
+
+    const int64_t ci = blockIdx.y;
+    const int n = blockIdx.x, h = blockIdx.z, tid = threadIdx.x;
+    int64_t tok_base, len;
+    if (cu) { tok_base = cu[n]; len = (int64_t)cu[n + 1] - tok_base; }
+    else    { tok_base = (int64_t)n * T; len = T; }
+    const int64_t c0 = ci * kC;
+    if (c0 >= len) return;
+    const int nv = (int)((len - c0 < kC) ? (len - c0) : kC);
+    const int64_t tok0 = tok_base + c0;
+    const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
+    const float *S0 = Sc + slot * (int64_t)(D * D);
+    const float *dS1 = dSc + slot * (int64_t)(D * D);
+    const int d = tid % D, rg = tid / D;
+
+    auto load_rows = [&](float *dst, const float *src, float mul) {      // [C][D] token rows -> LDS
+        for (int idx = tid; idx < kC * D; idx += 256) {
+            const int r = idx / D, c = idx % D;
+            dst[r * LD + c] = (r < nv) ? mul * src[((tok0 + r) * H + h) * (int64_t)D + c] : 0.f;
+        }
+    };
+    auto load_state = [&](const float *src) {
+        for (int idx = tid; idx < D * D; idx += 256) sS[(idx / D) * LD + idx % D] = src[idx];
+    };
+
+    for (int idx = tid; idx < kC * D; idx += 256) {
+        const int r = idx / D, c = idx % D;
+        sG[r * LD + c] = (r < nv) ? load_as_float(log_alpha + ((tok0 + r) * H + h) * (int64_t)D + c) * kLog2e : 0.f;
+    }
+    load_state(S0);
+    load_rows(sOp, d_o, scale);
+    __syncthreads();
+    if (tid < D) {
+        float run = 0.f;
+        for (int r = 0; r < kC; ++r) { run += sG[r * LD + tid]; sG[r * LD + tid] = run; }
+        sGend[tid] = run;
+    }
+    __syncthreads();
+
+    // dQg = dO S0^T:  dq = Gamma . dQg,  dG = dQg . Gamma . q
+    times_state_t<D>(sOp, sS, d, rg, [&](int r, float acc) {
+        if (r < nv) {
+            const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
+            const float t = acc * fast_exp2(sG[r * LD + d]);
+            dq[off] = t;
+            dg[off] = t * load_as_float(q + off);
+        }
+    });
+    __syncthreads();
+    load_rows(sOp, dv, 1.f);                                             // X
+    __syncthreads();
+    // dKg = -X S0^T:  dk = Gamma . dKg,  dG += dKg . Gamma . k
+    times_state_t<D>(sOp, sS, d, rg, [&](int r, float acc) {
+        if (r < nv) {
+            const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
+            const float t = -acc * fast_exp2(sG[r * LD + d]);
+            dk[off] = t;
+            dg[off] += t * load_as_float(k + off);
+        }
+    });
+    __syncthreads();
+    // dG_C (first part) = e^(G_C) . rowsum(dS1 . S0)
+    for (int idx = tid; idx < D * D; idx += 256) sS[(idx / D) * LD + idx % D] *= dS1[idx];
+    __syncthreads();
+    if (tid < D) {
+        float acc = 0.f;
+        for (int c = 0; c < D; ++c) acc += sS[tid * LD + c];
+        sgc[tid] = acc * fast_exp2(sGend[tid]);
+    }
+    __syncthreads();
+    load_state(dS1);
+    load_rows(sOp, Vnw, 1.f);
+    __syncthreads();
+    // dKt = Vn dS1^T:  dk += e^(G_C - G) . dKt,  dG -= dKt . Kt,  dG_C += sum_t dKt . Kt
+    float gc_part = 0.f;
+    times_state_t<D>(sOp, sS, d, rg, [&](int r, float acc) {
+        if (r < nv) {
+            const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
+            const float t = acc * fast_exp2(sGend[d] - sG[r * LD + d]);
+            dk[off] += t;
+            const float tk = t * load_as_float(k + off);
+            dg[off] -= tk;
+            gc_part += tk;
+        }
+    });
+    sPart[rg * D + d] = gc_part;
+    __syncthreads();
+    if (tid < D) {
+        float acc = sgc[tid];
+        for (int g = 0; g < RG; ++g) acc += sPart[g * D + tid];
+        dgC[slot * D + tid] = acc;
+    }
+    // dP = Tril(dO Vn^T), dM = Tril(dVn Y^T): sOp holds Vn; the state area holds two row tiles
+    float *sR = sS, *sI2 = sS + kC * LD;
+    load_rows(sR, d_o, scale);
+    __syncthreads();
+    lower_product<D>(sR, sOp, Cw + slot * (int64_t)(2 * kC * kC), tid);
+    __syncthreads();
+    load_rows(sR, dVnw, 1.f);
+    load_rows(sI2, Yw, 1.f);
+    __syncthreads();
+    lower_product<D>(sR, sI2, Cw + slot * (int64_t)(2 * kC * kC) + kC * kC, tid);
+}
+
+// ------------------------------------------------------------------------------------------
+// Per chunk: gradient through T, pairwise decay terms, dlog_alpha, dbeta.
+// ------------------------------------------------------------------------------------------
+template <int D> constexpr size_t chain_lds_floats()
+{
+    return 3 * kC * (D + 1) + 3 * kC * kLA + 2 * kC + D;
+}
+
+template <typename Tin, int D>
+__global__ __launch_bounds__(256)
+void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
+                          const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
+                          const int32_t *__restrict__ cu, const float *__restrict__ Cw,
+                          const float *__restrict__ dgC, float *__restrict__ dq,
+                          float *__restrict__ dk, float *__restrict__ dla, float *__restrict__ dbeta,
+                          int64_t T, int H, int64_t chunks_per_seq)
+{
+    constexpr int LD = D + 1, RG = 256 / D;
+    extern __shared__ float smem[];
+    float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD;
+    float *sA = sG + kC * LD;               // T - I (strict lower), A_kk (upper, transposed)
+    float *sB = sA + kC * kLA;              // dM -> dT -> dL -> dA_kk (lower), dP (upper, transposed)
+    float *sZ = sB + kC * kLA;              // dT T^T
+    float *sBeta = sZ + kC * kLA, *sdb = sBeta + kC, *sGend = sdb + kC;
+
+    const int64_t ci = blockIdx.y;
+    const int n = blockIdx.x, h = blockIdx.z, tid = threadIdx.x;
+    int64_t tok_base, len;
+    if (cu) { tok_base = cu[n]; len = (int64_t)cu[n + 1] - tok_base; }
+    else    { tok_base = (int64_t)n * T; len = T; }
+    const int64_t c0 = ci * kC;
+    if (c0 >= len) return;
+    const int nv = (int)((len - c0 < kC) ? (len - c0) : kC);
+    const int64_t tok0 = tok_base + c0;
+    const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
+
+    {   // dM (lower, diagonal included) and dP (stored transposed above the diagonal)
+        const float *cP = Cw + slot * (int64_t)(2 * kC * kC), *cM = cP + kC * kC;
+        for (int idx = tid; idx < kC * kC; idx += 256) {
+            const int r = idx >> 6, i = idx & 63;
+            if (i <= r) { sB[r * kLA + i] = cM[idx]; sB[i * kLA + r + 1] = cP[idx]; }
+        }
+    }
+    chunk_setup<Tin, D, true>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sA, sBeta, sGend, tid);
+
+    auto Tm = [&](int r, int j) { return r == j ? 1.f : sA[r * kLA + j]; };   // r >= j
+
+    // dbeta_j = sum_{r>=j} dM[r,j] T[r,j]
+    if (tid < kC) {
+        float acc = 0.f;
+        for (int r = tid; r < kC; ++r) acc = fmaf(sB[r * kLA + tid], Tm(r, tid), acc);
+        sdb[tid] = acc;
+    }
+    __syncthreads();
+    // dT = dM Diag(beta)
+    for (int idx = tid; idx < kC * kC; idx += 256) {
+        const int r = idx >> 6, j = idx & 63;
+        if (j <= r) sB[r * kLA + j] *= sBeta[j];
+    }
+    __syncthreads();
+    // Z[a,i] = sum_{b <= min(a,i)} dT[a,b] T[i,b]
+    {
+        const int i = tid & 63;
+        for (int a = tid >> 6; a < kC; a += 4) {
+            const int m = a < i ? a : i;
+            float acc = 0.f;
+            for (int b = 0; b <= m; ++b) acc = fmaf(sB[a * kLA + b], Tm(i, b), acc);
+            sZ[a * kLA + i] = acc;
+        }
+    }
+    __syncthreads();
+    // dL[r,i] = -sum_{a>=r} T[a,r] Z[a,i]  (i < r), then dbeta_r += sum_i dL A_kk, dA_kk = beta_r dL
+    {
+        const int i = tid & 63;
+        for (int r = tid >> 6; r < kC; r += 4) {
+            if (i < r) {
+                float acc = 0.f;
+                for (int a = r; a < kC; ++a) acc = fmaf(Tm(a, r), sZ[a * kLA + i], acc);
+                sB[r * kLA + i] = -acc;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < kC) {
+        const int r = tid;
+        float acc = sdb[r];
+        for (int i = 0; i < r; ++i) acc = fmaf(sB[r * kLA + i], sA[i * kLA + r + 1], acc);
+        if (r < nv) dbeta[(tok0 + r) * H + h] = acc;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < kC * kC; idx += 256) {
+        const int r = idx >> 6, i = idx & 63;
+        if (i < r) sB[r * kLA + i] *= sBeta[r];
+    }
+    __syncthreads();
+
+    // pairwise decay terms for this thread's channel d and tokens rg + RG j
+    const int d = tid % D, rg = tid / D;
+    float dgt[kC / RG];
+#pragma unroll 1
+    for (int j = 0; j < kC / RG; ++j) {
+        const int t = rg + RG * j;
+        const float Gt = sG[t * LD + d], kt = sK[t * LD + d], qt = sQ[t * LD + d];
+        float a1 = 0.f, a2 = 0.f, b1 = 0.f;
+        for (int i = 0; i < t; ++i) {                            // token t as the row
+            const float kk = sK[i * LD + d] * fast_exp2(Gt - sG[i * LD + d]);
+            a1 = fmaf(sB[t * kLA + i], kk, a1);
+            a2 = fmaf(sB[i * kLA + t + 1], kk, a2);
+        }
+        a2 = fmaf(sB[t * kLA + t + 1], kt, a2);                  // dP[t,t]
+        b1 = sB[t * kLA + t + 1] * qt;
+        for (int r = t + 1; r < kC; ++r) {                       // token t as the column
+            const float e = fast_exp2(sG[r * LD + d] - Gt);
+            b1 = fmaf(fmaf(sB[r * kLA + t], sK[r * LD + d], sB[t * kLA + r + 1] * sQ[r * LD + d]), e, b1);
+        }
+        float g = 0.f;
+        if (t < nv) {
+            const int64_t off = ((tok0 + t) * H + h) * (int64_t)D + d;
+            dq[off] += a2;
+            dk[off] += a1 + b1;
+            g = dla[off] + kt * a1 + qt * a2 - kt * b1;
+        }
+        dgt[j] = g;
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int j = 0; j < kC / RG; ++j) sQ[(rg + RG * j) * LD + d] = dgt[j];
+    __syncthreads();
+    // dlog_alpha_t = sum_{r>=t} dG_r + dG_C
+    if (tid < D) {
+        float run = dgC[slot * D + tid];
+        for (int r = nv - 1; r >= 0; --r) {
+            run += sQ[r * LD + tid];
+            dla[((tok0 + r) * H + h) * (int64_t)D + tid] = run;
+        }
+    }
+}
+
+template <typename F>
+static kda_status reserve(F kern, size_t lds, const char *name)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess)
+        return fail(KDA_ERR_LAUNCH, "%s: cannot reserve %zu B of LDS: %s", name, lds, hipGetErrorString(e));
+    return KDA_OK;
+}
+
+struct BwdPlan {
+    int64_t chunks_per_seq, max_chunks, nslots, ntok;
+    size_t off_S, off_dS, off_Y, off_Vn, off_dVn, off_gC, off_C, total;
+};
+
+static BwdPlan bwd_plan(const kda_dims *d, bool packed)
+{
+    BwdPlan p{};
+    const int64_t D = d->dk;
+    p.chunks_per_seq = (d->seqlen + kC - 1) / kC;
+    const int64_t longest = packed ? ((d->max_seqlen > 0 && d->max_seqlen < d->seqlen) ? d->max_seqlen : d->seqlen)
+                                   : d->seqlen;
+    p.max_chunks = (longest + kC - 1) / kC;
+    const int64_t slots = packed ? d->seqlen / kC + d->num_seqs : (int64_t)d->num_seqs * p.chunks_per_seq;
+    p.nslots = slots * d->heads;
+    p.ntok = (packed ? d->seqlen : (int64_t)d->batch * d->seqlen) * d->heads;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    size_t at = 0;
+    p.off_S = at;   at = up(at + (size_t)p.nslots * D * D * 4);
+    p.off_dS = at;  at = up(at + (size_t)p.nslots * D * D * 4);
+    p.off_Y = at;   at = up(at + (size_t)p.ntok * D * 4);
+    p.off_Vn = at;  at = up(at + (size_t)p.ntok * D * 4);
+    p.off_dVn = at; at = up(at + (size_t)p.ntok * D * 4);
+    p.off_gC = at;  at = up(at + (size_t)p.nslots * D * 4);
+    p.off_C = at;   at = up(at + (size_t)p.nslots * 2 * kC * kC * 4);
+    p.total = at;
+    return p;
+}
+
+template <typename Tin, int D>
+static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q_, const void *k_,
+                             const void *v_, const void *la_, const void *beta_, const float *h0,
+                             const int32_t *cu, const float *d_o, const float *d_hT, float *dq,
+                             float *dk, float *dv, float *dla, float *dbeta, float *dh0, char *ws,
+                             hipStream_t stream)
+{
+    const Tin *q = static_cast<const Tin *>(q_), *k = static_cast<const Tin *>(k_);
+    const Tin *v = static_cast<const Tin *>(v_), *la = static_cast<const Tin *>(la_);
+    const Tin *beta = static_cast<const Tin *>(beta_);
+    float *Sc = reinterpret_cast<float *>(ws + p.off_S), *dSc = reinterpret_cast<float *>(ws + p.off_dS);
+    float *Yw = reinterpret_cast<float *>(ws + p.off_Y), *Vnw = reinterpret_cast<float *>(ws + p.off_Vn);
+    float *dVnw = reinterpret_cast<float *>(ws + p.off_dVn), *gC = reinterpret_cast<float *>(ws + p.off_gC);
+    float *Cw = reinterpret_cast<float *>(ws + p.off_C);
+
+    const size_t lds_scan = scan_lds_floats<D>() * 4, lds_prod = products_lds_floats<D>() * 4,
+                 lds_chain = chain_lds_floats<D>() * 4;
+    kda_status st;
+    if ((st = reserve(kda_bwd_states_kernel<Tin, D>, lds_scan, "kda_bwd_states")) != KDA_OK) return st;
+    if ((st = reserve(kda_bwd_scan_kernel<Tin, D>, lds_scan, "kda_bwd_scan")) != KDA_OK) return st;
+    if ((st = reserve(kda_bwd_products_kernel<Tin, D>, lds_prod, "kda_bwd_products")) != KDA_OK) return st;
+    if ((st = reserve(kda_bwd_chain_kernel<Tin, D>, lds_chain, "kda_bwd_chain")) != KDA_OK) return st;
+
+    const int H = dm->heads;
+    const int64_t T = dm->seqlen;
+    const dim3 gscan((unsigned)dm->num_seqs, (unsigned)H, (unsigned)(D / kBV));
+    hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, q, k, v, la, beta,
+                       h0, cu, Sc, Yw, Vnw, T, H, p.chunks_per_seq);
+    hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, q, k, la, beta, cu,
+                       d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
+    if (p.max_chunks > 0) {
+        const dim3 gchunk((unsigned)dm->num_seqs, (unsigned)p.max_chunks, (unsigned)H);
+        hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, D>), gchunk, dim3(256), lds_prod, stream, q, k, la, cu,
+                           d_o, Sc, dSc, Yw, Vnw, dVnw, dv, dq, dk, dla, gC, Cw, T, H, p.chunks_per_seq,
+                           dm->scale);
+        hipLaunchKernelGGL((kda_bwd_chain_kernel<Tin, D>), gchunk, dim3(256), lds_chain, stream, q, k, la, beta,
+                           cu, Cw, gC, dq, dk, dla, dbeta, T, H, p.chunks_per_seq);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_chunk_bwd: %s", hipGetErrorString(e));
+    return KDA_OK;
+}
+
+}  // namespace
+
+size_t chunk_bwd_workspace_size(const kda_dims *d)
+{
+    return bwd_plan(d, d->num_seqs != d->batch).total;
+}
+
+kda_status chunk_bwd_dispatch(const kda_dims *dm, const void *q, const void *k, const void *v,
+                              const void *log_alpha, const void *beta, const float *h0,
+                              const int32_t *cu, const float *d_o, const float *d_hT, float *dq,
+                              float *dk, float *dv, float *dla, float *dbeta, float *dh0,
+                              void *workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const BwdPlan p = bwd_plan(dm, cu != nullptr);
+    if (p.total > workspace_bytes || (p.total && !workspace))
+        return fail(KDA_ERR_WORKSPACE, "kda_chunk_bwd needs %zu B of workspace, got %zu", p.total, workspace_bytes);
+    if (p.max_chunks > 65535)
+        return fail(KDA_ERR_UNSUPPORTED, "kda_chunk_bwd: sequences longer than %d tokens", 65535 * kC);
+    char *ws = static_cast<char *>(workspace);
+    const bool bf = dm->in_dtype == KDA_BF16;
+#define KDA_BWD(TIN, DD) launch_bwd<TIN, DD>(dm, p, q, k, v, log_alpha, beta, h0, cu, d_o, d_hT, dq, dk, dv, dla, \
+                                             dbeta, dh0, ws, stream)
+    if (dm->dk == 128) return bf ? KDA_BWD(__hip_bfloat16, 128) : KDA_BWD(float, 128);
+    return bf ? KDA_BWD(__hip_bfloat16, 64) : KDA_BWD(float, 64);
+#undef KDA_BWD
+}
+
+}  // namespace kda

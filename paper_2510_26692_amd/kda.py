@@ -71,6 +71,10 @@ def load_library():
     lib.kda_chunk_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kda_chunk_fwd_check.restype = ctypes.c_int
     lib.kda_chunk_fwd_check.argtypes = [dp, vp, sz, vp]
+    lib.kda_chunk_bwd_workspace_size.restype = sz
+    lib.kda_chunk_bwd_workspace_size.argtypes = [dp]
+    lib.kda_chunk_bwd.restype = ctypes.c_int
+    lib.kda_chunk_bwd.argtypes = [dp] + [vp] * 15 + [vp, sz, vp]
     lib.kda_debug_set_phase_mask.restype = None
     lib.kda_debug_set_phase_mask.argtypes = [ctypes.c_int]
     lib.kda_debug_set_overlap.restype = None
@@ -276,6 +280,51 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
     if check:
         kda_chunk_fwd_check(dims, workspace)
     return o, hT
+
+
+def kda_chunk_bwd_workspace_size(dims):
+    return int(load_library().kda_chunk_bwd_workspace_size(ctypes.byref(dims)))
+
+
+def kda_chunk_bwd(q, k, v, log_alpha, beta, do, dhT=None, h0=None, cu_seqlens=None, scale=1.0,
+                  want_dh0=True, workspace=None, max_seqlen=0):
+    """Backward pass of kda_chunk_fwd.  Inputs as there; do fp32 [B,T,H,dv]; dhT fp32 [N,H,dk,dv] or
+    None.  Returns a dict of fp32 tensors dq, dk, dlog_alpha [B,T,H,dk], dv [B,T,H,dv], dbeta [B,T,H]
+    and dh0 [N,H,dk,dv] (None unless want_dh0); rows of tokens that belong to no sequence are zero
+    (this wrapper allocates the gradients zero-filled; the library leaves such rows untouched)."""
+    lib = load_library()
+    dev = _check_dev(q, k, v, log_alpha, beta, do, dhT, h0, cu_seqlens, workspace)
+    if not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype) or q.dtype not in _DTYPE_CODE:
+        raise ValueError("q, k, v, log_alpha, beta must share a supported dtype")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    if k.shape != q.shape or log_alpha.shape != q.shape or v.shape != (B, T, H, dv) or beta.shape != (B, T, H):
+        raise ValueError("inconsistent input shapes")
+    dims = make_chunk_dims(q, v, cu_seqlens, scale, max_seqlen, torch.float32)
+    N = dims.num_seqs
+    if do.dtype != torch.float32 or do.shape != (B, T, H, dv):
+        raise ValueError("do must be fp32 [B,T,H,dv]")
+    for name, t in (("dhT", dhT), ("h0", h0)):
+        if t is not None and (t.dtype != torch.float32 or t.shape != (N, H, dk, dv)):
+            raise ValueError("%s must be fp32 [N,H,dk,dv]" % name)
+    if cu_seqlens is not None and cu_seqlens.dtype != torch.int32:
+        raise ValueError("cu_seqlens must be int32")
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = {"dq": torch.zeros(B, T, H, dk, **f32), "dk": torch.zeros(B, T, H, dk, **f32),
+           "dv": torch.zeros(B, T, H, dv, **f32), "dlog_alpha": torch.zeros(B, T, H, dk, **f32),
+           "dbeta": torch.zeros(B, T, H, **f32),
+           "dh0": torch.empty(N, H, dk, dv, **f32) if want_dh0 else None}
+    if workspace is None:
+        need = kda_chunk_bwd_workspace_size(dims)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev) if need else None
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = lib.kda_chunk_bwd(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta), _ptr(h0),
+                           _ptr(cu_seqlens), _ptr(do), _ptr(dhT), _ptr(out["dq"]), _ptr(out["dk"]),
+                           _ptr(out["dv"]), _ptr(out["dlog_alpha"]), _ptr(out["dbeta"]), _ptr(out["dh0"]),
+                           _ptr(workspace), ctypes.c_size_t(ws_bytes), _stream_ptr(dev))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return out
 
 
 def kda_chunk_fwd_scalar_gate(q, k, v, log_alpha_head, beta, **kw):
