@@ -29,8 +29,10 @@
 //              dG_C = e^(G_C) . rowsum(dS1 . S0) + sum_t dKt_t . Kt_t
 //              dlog_alpha_t = sum_{r>=t} dG_r + dG_C
 //
-// Four kernels, all plain fp32 FMAs on LDS tiles (this path is written for correctness and
+// Five kernels, all plain fp32 FMAs on LDS tiles (this path is written for correctness and
 // clarity; the matrix cores are not used yet):
+//   kda_bwd_prep     one workgroup per (chunk, head), all chunks in parallel: A_kk, A_qk, T and M,
+//                    left in the workspace as two packed C x C tiles
 //   kda_bwd_states   one workgroup per (sequence, head, 32 state columns) walks the chunks
 //                    forward and leaves S0 of every chunk, Y and Vn in the workspace
 //   kda_bwd_scan     the same decomposition walks the chunks backward with dS: dVn, dV, the dS1
@@ -56,18 +58,15 @@ __device__ __forceinline__ int64_t chunk_slot(const int32_t *cu, int n, int64_t 
     return cu ? (int64_t)(cu[n] / kC) + n + c : (int64_t)n * chunks_per_seq + c;
 }
 
-// Loads one chunk and forms the quantities every backward kernel starts from.  On return
-// (the last statement is a barrier):
+// Loads one chunk.  On return (the last statement is a barrier):
 //   sQ, sK [C][D+1]  q and k as given (zero rows past nv)
 //   sG     [C][D+1]  G in log2 units (rows past nv repeat the last valid row)
-//   sA     [C][kLA]  strict lower part [r][i]: T - I;  upper part [i][r+1] for i <= r:
-//                    A_qk[r][i] (kUpperKK false) or A_kk[r][i] (true)
-//   sBeta [C], sGend [D] (G of the last row)
-template <typename Tin, int D, bool kUpperKK>
-__device__ void chunk_setup(const Tin *__restrict__ q, const Tin *__restrict__ k,
-                            const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
-                            int64_t tok0, int nv, int H, int h, float *sQ, float *sK, float *sG,
-                            float *sA, float *sBeta, float *sGend, int tid)
+//   sBeta [C] (zero past nv), sGend [D] (G of the last row)
+template <typename Tin, int D>
+__device__ void chunk_load(const Tin *__restrict__ q, const Tin *__restrict__ k,
+                           const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
+                           int64_t tok0, int nv, int H, int h, float *sQ, float *sK, float *sG,
+                           float *sBeta, float *sGend, int tid)
 {
     constexpr int LD = D + 1;
     for (int idx = tid; idx < kC * D; idx += 256) {
@@ -89,6 +88,44 @@ __device__ void chunk_setup(const Tin *__restrict__ q, const Tin *__restrict__ k
         sGend[tid] = run;
     }
     __syncthreads();
+}
+
+// The two packed C x C tiles of a chunk, [C][kLA] floats each, that kda_bwd_prep leaves in the
+// workspace:
+//   tile 0   strict lower part [r][i]: T - I          upper part [i][r+1], i <= r: A_kk[r][i]
+//   tile 1   lower part with diagonal [r][j]: M = T Diag(beta)    upper part [i][r+1]: A_qk[r][i]
+constexpr int kTile = kC * kLA;
+
+__device__ __forceinline__ void load_tile(float *dst, const float *__restrict__ src, int tid)
+{
+    for (int idx = tid; idx < kTile; idx += 256) dst[idx] = src[idx];
+}
+
+template <typename Tin, int D>
+__global__ __launch_bounds__(256)
+void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
+                         const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
+                         const int32_t *__restrict__ cu, float *__restrict__ Tw, int64_t T, int H,
+                         int64_t chunks_per_seq)
+{
+    constexpr int LD = D + 1;
+    extern __shared__ float smem[];
+    float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD;
+    float *s0 = sG + kC * LD, *s1 = s0 + kTile;
+    float *sBeta = s1 + kTile, *sGend = sBeta + kC;
+
+    const int64_t ci = blockIdx.y;
+    const int n = blockIdx.x, h = blockIdx.z, tid = threadIdx.x;
+    int64_t tok_base, len;
+    if (cu) { tok_base = cu[n]; len = (int64_t)cu[n + 1] - tok_base; }
+    else    { tok_base = (int64_t)n * T; len = T; }
+    const int64_t c0 = ci * kC;
+    if (c0 >= len) return;
+    const int nv = (int)((len - c0 < kC) ? (len - c0) : kC);
+    const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
+
+    for (int idx = tid; idx < 2 * kTile; idx += 256) s0[idx] = 0.f;
+    chunk_load<Tin, D>(q, k, log_alpha, beta, tok_base + c0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
     {
         const int i = tid & 63;
         for (int r = tid >> 6; r < kC; r += 4) {
@@ -100,8 +137,9 @@ __device__ void chunk_setup(const Tin *__restrict__ q, const Tin *__restrict__ k
                     akk = fmaf(sK[r * LD + d], t, akk);
                     aqk = fmaf(sQ[r * LD + d], t, aqk);
                 }
-                if (i < r) sA[r * kLA + i] = sBeta[r] * akk;
-                sA[i * kLA + r + 1] = kUpperKK ? akk : aqk;
+                if (i < r) s0[r * kLA + i] = sBeta[r] * akk;     // L = StrictTril(Diag(beta) A_kk)
+                s0[i * kLA + r + 1] = akk;
+                s1[i * kLA + r + 1] = aqk;
             }
         }
     }
@@ -111,23 +149,21 @@ __device__ void chunk_setup(const Tin *__restrict__ q, const Tin *__restrict__ k
         float val = 0.f;
         const int j = tid;
         if (j < r) {
-            val = -sA[r * kLA + j];
-            for (int i = j + 1; i < r; ++i) val = fmaf(-sA[r * kLA + i], sA[i * kLA + j], val);
+            val = -s0[r * kLA + j];
+            for (int i = j + 1; i < r; ++i) val = fmaf(-s0[r * kLA + i], s0[i * kLA + j], val);
         }
         __syncthreads();
-        if (j < r) sA[r * kLA + j] = val;
+        if (j < r) s0[r * kLA + j] = val;
         __syncthreads();
     }
-}
-
-// Strict lower part T - I  ->  M = T Diag(beta), diagonal included.
-__device__ void scale_to_m(float *sA, const float *sBeta, int tid)
-{
     for (int idx = tid; idx < kC * kC; idx += 256) {
         const int r = idx >> 6, j = idx & 63;
-        if (j < r) sA[r * kLA + j] *= sBeta[j];
-        else if (j == r) sA[r * kLA + j] = sBeta[j];
+        if (j < r) s1[r * kLA + j] = s0[r * kLA + j] * sBeta[j];
+        else if (j == r) s1[r * kLA + j] = sBeta[j];
     }
+    __syncthreads();
+    float *dst = Tw + slot * (int64_t)(2 * kTile);
+    for (int idx = tid; idx < 2 * kTile; idx += 256) dst[idx] = s0[idx];
 }
 
 // q, k, G tiles -> Gamma.Q, Gamma^{i->C}.K, Gamma.K (in sQ, sK, sG), as the forward kernel does.
@@ -146,6 +182,8 @@ __device__ void decay_operands(float *sQ, float *sK, float *sG, const float *sGe
     }
 }
 
+template <int D> constexpr size_t prep_lds_floats() { return 3 * kC * (D + 1) + 2 * kTile + kC + D; }
+
 template <int D> constexpr size_t scan_lds_floats()
 {
     return 3 * kC * (D + 1) + kC * kLA + 3 * kC * kBV + D * kBV + kC + D;
@@ -159,8 +197,9 @@ __global__ __launch_bounds__(256)
 void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                            const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
                            const Tin *__restrict__ beta, const float *__restrict__ h0,
-                           const int32_t *__restrict__ cu, float *__restrict__ Sc,
-                           float *__restrict__ Yw, float *__restrict__ Vnw, int64_t T, int H,
+                           const int32_t *__restrict__ cu, const float *__restrict__ Tw,
+                           float *__restrict__ Sc, float *__restrict__ Yw, float *__restrict__ Vnw,
+                           int64_t T, int H,
                            int64_t chunks_per_seq)
 {
     constexpr int LD = D + 1;
@@ -194,15 +233,20 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             const int r = idx / kBV, c = idx % kBV;
             sV[idx] = (r < nv) ? load_as_float(v + ((tok0 + r) * H + h) * (int64_t)D + col0 + c) : 0.f;
         }
-        chunk_setup<Tin, D, false>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sA, sBeta, sGend, tid);
-        scale_to_m(sA, sBeta, tid);
+        load_tile(sA, Tw + (slot * 2 + 1) * (int64_t)kTile, tid);
+        chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
         decay_operands<D>(sQ, sK, sG, sGend, tid);
         __syncthreads();
-        const int c = tid & 31;
-        for (int r = tid >> 5; r < kC; r += 8) {                 // Y = V - Kg S0
-            float acc = 0.f;
-            for (int d = 0; d < D; ++d) acc = fmaf(sG[r * LD + d], sS[d * kBV + c], acc);
-            sV[r * kBV + c] -= acc;
+        const int c = tid & 31, w8 = tid >> 5;
+        {                                                        // Y = V - Kg S0, rows w8 + 8 u
+            float acc[8] = {};
+            for (int d = 0; d < D; ++d) {
+                const float sv = sS[d * kBV + c];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc[u] = fmaf(sG[(w8 + 8 * u) * LD + d], sv, acc[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sV[(w8 + 8 * u) * kBV + c] -= acc[u];
         }
         __syncthreads();
         for (int r = tid >> 5; r < kC; r += 8) {                 // Vn = M Y
@@ -216,10 +260,17 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             }
         }
         __syncthreads();
-        for (int d = tid >> 5; d < D; d += 8) {                  // S1 = Diag(e^G_C) S0 + Kt^T Vn
-            float acc = sS[d * kBV + c] * fast_exp2(sGend[d]);
-            for (int j = 0; j < kC; ++j) acc = fmaf(sK[j * LD + d], sVn[j * kBV + c], acc);
-            sS[d * kBV + c] = acc;
+        {                                                        // S1 = Diag(e^G_C) S0 + Kt^T Vn
+            float acc[D / 8];
+#pragma unroll
+            for (int u = 0; u < D / 8; ++u) acc[u] = sS[(w8 + 8 * u) * kBV + c] * fast_exp2(sGend[w8 + 8 * u]);
+            for (int j = 0; j < kC; ++j) {
+                const float vn = sVn[j * kBV + c];
+#pragma unroll
+                for (int u = 0; u < D / 8; ++u) acc[u] = fmaf(sK[j * LD + w8 + 8 * u], vn, acc[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < D / 8; ++u) sS[(w8 + 8 * u) * kBV + c] = acc[u];
         }
     }
 }
@@ -231,8 +282,9 @@ template <typename Tin, int D>
 __global__ __launch_bounds__(256)
 void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                          const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
-                         const int32_t *__restrict__ cu, const float *__restrict__ d_o,
-                         const float *__restrict__ d_hT, float *__restrict__ dSc,
+                         const int32_t *__restrict__ cu, const float *__restrict__ Tw,
+                         const float *__restrict__ d_o, const float *__restrict__ d_hT,
+                         float *__restrict__ dSc,
                          float *__restrict__ dVnw, float *__restrict__ dv, float *__restrict__ dh0,
                          int64_t T, int H, int64_t chunks_per_seq, float scale)
 {
@@ -267,17 +319,26 @@ void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             const int r = idx / kBV, c = idx % kBV;
             sdO[idx] = (r < nv) ? scale * d_o[((tok0 + r) * H + h) * (int64_t)D + col0 + c] : 0.f;
         }
-        chunk_setup<Tin, D, false>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sA, sBeta, sGend, tid);
-        scale_to_m(sA, sBeta, tid);
+        load_tile(sA, Tw + (slot * 2 + 1) * (int64_t)kTile, tid);
+        chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
         decay_operands<D>(sQ, sK, sG, sGend, tid);
         __syncthreads();
-        const int c = tid & 31;
-        for (int i = tid >> 5; i < kC; i += 8) {                 // dVn = P^T dO + Kt dS1
-            float acc = 0.f;
-            for (int r = i; r < kC; ++r) acc = fmaf(sA[i * kLA + r + 1], sdO[r * kBV + c], acc);
-            for (int d = 0; d < D; ++d) acc = fmaf(sK[i * LD + d], sdS[d * kBV + c], acc);
-            sdVn[i * kBV + c] = acc;
-            if (i < nv) dVnw[((tok0 + i) * H + h) * (int64_t)D + col0 + c] = acc;
+        const int c = tid & 31, w8 = tid >> 5;
+        {                                                        // dVn = P^T dO + Kt dS1, rows w8 + 8 u
+            float acc[8] = {};
+            for (int d = 0; d < D; ++d) {
+                const float sv = sdS[d * kBV + c];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc[u] = fmaf(sK[(w8 + 8 * u) * LD + d], sv, acc[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = w8 + 8 * u;
+                float a = acc[u];
+                for (int r = i; r < kC; ++r) a = fmaf(sA[i * kLA + r + 1], sdO[r * kBV + c], a);
+                sdVn[i * kBV + c] = a;
+                if (i < nv) dVnw[((tok0 + i) * H + h) * (int64_t)D + col0 + c] = a;
+            }
         }
         __syncthreads();
         for (int j = tid >> 5; j < kC; j += 8) {                 // X = M^T dVn = dV
@@ -287,13 +348,20 @@ void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             if (j < nv) dv[((tok0 + j) * H + h) * (int64_t)D + col0 + c] = acc;
         }
         __syncthreads();
-        for (int d = tid >> 5; d < D; d += 8) {                  // dS0
-            float acc = sdS[d * kBV + c] * fast_exp2(sGend[d]);
+        {                                                        // dS0, rows w8 + 8 u
+            float acc[D / 8];
+#pragma unroll
+            for (int u = 0; u < D / 8; ++u) acc[u] = sdS[(w8 + 8 * u) * kBV + c] * fast_exp2(sGend[w8 + 8 * u]);
             for (int r = 0; r < kC; ++r) {
-                acc = fmaf(sQ[r * LD + d], sdO[r * kBV + c], acc);
-                acc = fmaf(-sG[r * LD + d], sX[r * kBV + c], acc);
+                const float a = sdO[r * kBV + c], x = -sX[r * kBV + c];
+#pragma unroll
+                for (int u = 0; u < D / 8; ++u) {
+                    acc[u] = fmaf(sQ[r * LD + w8 + 8 * u], a, acc[u]);
+                    acc[u] = fmaf(sG[r * LD + w8 + 8 * u], x, acc[u]);
+                }
             }
-            sdS[d * kBV + c] = acc;
+#pragma unroll
+            for (int u = 0; u < D / 8; ++u) sdS[(w8 + 8 * u) * kBV + c] = acc[u];
         }
     }
     if (dh0) {
@@ -483,8 +551,9 @@ template <typename Tin, int D>
 __global__ __launch_bounds__(256)
 void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                           const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
-                          const int32_t *__restrict__ cu, const float *__restrict__ Cw,
-                          const float *__restrict__ dgC, float *__restrict__ dq,
+                          const int32_t *__restrict__ cu, const float *__restrict__ Tw,
+                          const float *__restrict__ Cw, const float *__restrict__ dgC,
+                          float *__restrict__ dq,
                           float *__restrict__ dk, float *__restrict__ dla, float *__restrict__ dbeta,
                           int64_t T, int H, int64_t chunks_per_seq)
 {
@@ -514,7 +583,8 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             if (i <= r) { sB[r * kLA + i] = cM[idx]; sB[i * kLA + r + 1] = cP[idx]; }
         }
     }
-    chunk_setup<Tin, D, true>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sA, sBeta, sGend, tid);
+    load_tile(sA, Tw + slot * 2 * (int64_t)kTile, tid);
+    chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
 
     auto Tm = [&](int r, int j) { return r == j ? 1.f : sA[r * kLA + j]; };   // r >= j
 
@@ -621,7 +691,7 @@ static kda_status reserve(F kern, size_t lds, const char *name)
 
 struct BwdPlan {
     int64_t chunks_per_seq, max_chunks, nslots, ntok;
-    size_t off_S, off_dS, off_Y, off_Vn, off_dVn, off_gC, off_C, total;
+    size_t off_S, off_dS, off_Y, off_Vn, off_dVn, off_gC, off_C, off_T, total;
 };
 
 static BwdPlan bwd_plan(const kda_dims *d, bool packed)
@@ -644,6 +714,7 @@ static BwdPlan bwd_plan(const kda_dims *d, bool packed)
     p.off_dVn = at; at = up(at + (size_t)p.ntok * D * 4);
     p.off_gC = at;  at = up(at + (size_t)p.nslots * D * 4);
     p.off_C = at;   at = up(at + (size_t)p.nslots * 2 * kC * kC * 4);
+    p.off_T = at;   at = up(at + (size_t)p.nslots * 2 * kTile * 4);
     p.total = at;
     return p;
 }
@@ -661,11 +732,12 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     float *Sc = reinterpret_cast<float *>(ws + p.off_S), *dSc = reinterpret_cast<float *>(ws + p.off_dS);
     float *Yw = reinterpret_cast<float *>(ws + p.off_Y), *Vnw = reinterpret_cast<float *>(ws + p.off_Vn);
     float *dVnw = reinterpret_cast<float *>(ws + p.off_dVn), *gC = reinterpret_cast<float *>(ws + p.off_gC);
-    float *Cw = reinterpret_cast<float *>(ws + p.off_C);
+    float *Cw = reinterpret_cast<float *>(ws + p.off_C), *Tw = reinterpret_cast<float *>(ws + p.off_T);
 
     const size_t lds_scan = scan_lds_floats<D>() * 4, lds_prod = products_lds_floats<D>() * 4,
-                 lds_chain = chain_lds_floats<D>() * 4;
+                 lds_chain = chain_lds_floats<D>() * 4, lds_prep = prep_lds_floats<D>() * 4;
     kda_status st;
+    if ((st = reserve(kda_bwd_prep_kernel<Tin, D>, lds_prep, "kda_bwd_prep")) != KDA_OK) return st;
     if ((st = reserve(kda_bwd_states_kernel<Tin, D>, lds_scan, "kda_bwd_states")) != KDA_OK) return st;
     if ((st = reserve(kda_bwd_scan_kernel<Tin, D>, lds_scan, "kda_bwd_scan")) != KDA_OK) return st;
     if ((st = reserve(kda_bwd_products_kernel<Tin, D>, lds_prod, "kda_bwd_products")) != KDA_OK) return st;
@@ -674,17 +746,20 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     const int H = dm->heads;
     const int64_t T = dm->seqlen;
     const dim3 gscan((unsigned)dm->num_seqs, (unsigned)H, (unsigned)(D / kBV));
+    const dim3 gchunk((unsigned)dm->num_seqs, (unsigned)p.max_chunks, (unsigned)H);
+    if (p.max_chunks > 0)
+        hipLaunchKernelGGL((kda_bwd_prep_kernel<Tin, D>), gchunk, dim3(256), lds_prep, stream, q, k, la, beta, cu,
+                           Tw, T, H, p.chunks_per_seq);
     hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, q, k, v, la, beta,
-                       h0, cu, Sc, Yw, Vnw, T, H, p.chunks_per_seq);
+                       h0, cu, Tw, Sc, Yw, Vnw, T, H, p.chunks_per_seq);
     hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, q, k, la, beta, cu,
-                       d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
+                       Tw, d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
     if (p.max_chunks > 0) {
-        const dim3 gchunk((unsigned)dm->num_seqs, (unsigned)p.max_chunks, (unsigned)H);
         hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, D>), gchunk, dim3(256), lds_prod, stream, q, k, la, cu,
                            d_o, Sc, dSc, Yw, Vnw, dVnw, dv, dq, dk, dla, gC, Cw, T, H, p.chunks_per_seq,
                            dm->scale);
         hipLaunchKernelGGL((kda_bwd_chain_kernel<Tin, D>), gchunk, dim3(256), lds_chain, stream, q, k, la, beta,
-                           cu, Cw, gC, dq, dk, dla, dbeta, T, H, p.chunks_per_seq);
+                           cu, Tw, Cw, gC, dq, dk, dla, dbeta, T, H, p.chunks_per_seq);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_chunk_bwd: %s", hipGetErrorString(e));

@@ -92,15 +92,16 @@ def test_backward_parity(case):
 
 def test_backward_strong_decay_stays_finite_and_close():
     """Decays of e^-5 per token and channel and more: every decay is a pairwise difference, so nothing
-    overflows; gradients that the decay wipes out are compared in absolute terms against the
-    tensor's largest entry."""
+    overflows.  The cumulative log decay reaches a few hundred here and is held in fp32, so a decay
+    factor 2^x carries a relative error of about |x| 2^-24 ln 2 (1.2e-5 at |x| = 300), whatever the
+    kernel does afterwards: the bound for this case is 4e-5."""
     x = si.make_prefill(1, 200, 2, 128, 128, "bf16", -2.0, 1210, 0.05)
     x["log_alpha"] = (x["log_alpha"].float() * 40.0).to(torch.bfloat16)
     do, dhT = _grad_inputs(x, 78)
     got, ref, cu = _run(x, do, dhT)
     for name in NAMES:
         assert np.isfinite(got[name]).all()
-        assert rel_err(got[name], ref[name]) <= TOL, name
+        assert rel_err(got[name], ref[name]) <= 4e-5, name
 
 
 def test_backward_packed_leaves_stray_tokens_untouched_and_handles_empty_sequences():
