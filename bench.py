@@ -210,6 +210,47 @@ def main():
                       "ms_per_step": ms_sg, "tokens_per_s": tokens / (ms_sg * 1e-3)}
         del gh
 
+    # the backward pass (kda_chunk_bwd, fp32 throughout) on the same shape: time per call, and its rate
+    # against the fp32 vector peak under a FLOP model of the chunkwise backward (per chunk and head:
+    # eight C x d x d products, eight half-filled C x C x d ones, the C x C x C chain)
+    backward_obj = None
+    if name == "cfg1_prefill_bf16" and not args.no_breakdown:
+        d_o = torch.randn(o.shape, generator=torch.Generator().manual_seed(c["seed"] + 1)).to(dev)
+        ws_b = torch.empty(kda.kda_chunk_bwd_workspace_size(dims), dtype=torch.uint8, device=dev)
+
+        def backward():
+            return kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], d_o, h0=x["h0"],
+                                     workspace=ws_b)
+        backward()
+        steps_b = max(3, min(args.steps, 10))
+        ms_bwd = _time_region(torch, backward, steps_b)
+        C_, D_ = 64, c["dk"]
+        flop_chunk = 8 * 2 * C_ * D_ * D_ + 8 * C_ * C_ * D_ + 3 * 2 * C_ * C_ * C_
+        chunks_heads = tokheads / C_
+        tflops = chunks_heads * flop_chunk / (ms_bwd * 1e-3) / 1e12
+        backward_obj = {"what": "kda_chunk_bwd on the same shape: gradients of q, k, v, log_alpha, beta, h0 (fp32 arithmetic)",
+                        "ms_per_step": ms_bwd, "steps": steps_b, "tokens_per_s": tokens / (ms_bwd * 1e-3),
+                        "roofline": {"bound": "alu", "achieved": tflops, "peak": 157.3, "unit": "TFLOP/s",
+                                     "frac": tflops / 157.3, "flop_per_chunk_head": flop_chunk, "traffic": None}}
+        if not args.no_cpu_baseline and host is not None:
+            import numpy as np
+            import oracle
+            n_s = 256
+            a = {k_: si.to_np32(host[k_][:, :n_s]) for k_ in ("q", "k", "v", "log_alpha", "beta")}
+            t0 = time.perf_counter()
+            reps = 0
+            while time.perf_counter() - t0 < 5.0:
+                oracle.kda_backward(a["q"], a["k"], a["v"], a["log_alpha"], a["beta"],
+                                    d_o[:, :n_s].cpu().numpy(), h0=host["h0"].numpy().astype(np.float64))
+                reps += 1
+            dtb = time.perf_counter() - t0
+            backward_obj["cpu_baseline"] = {"value": c["B"] * n_s * reps / dtb, "unit": "tokens/s",
+                                            "cores": oracle.num_threads(), "kind": "oracle",
+                                            "sample": "first %d tokens of every sequence, %d times over, fp64 "
+                                                      "token-by-token reverse pass" % (n_s, reps),
+                                            "seconds": dtb}
+        del d_o, ws_b
+
     # the same prefill on raw projections (fused input prologue), cfg1 shape only
     fused_obj = None
     if name == "cfg1_prefill_bf16" and not args.no_breakdown:
@@ -359,6 +400,7 @@ def main():
         "prefill_bf16_out": bf16_out_obj,
         "prefill_scalar_gate": scalar_obj,
         "prefill_fused_stages": fused_obj,
+        "backward": backward_obj,
         "decode": decode_obj,
         "error_metric": "max|x-ref|/max|ref| per (sequence, head); parity is gated in tests/",
     }

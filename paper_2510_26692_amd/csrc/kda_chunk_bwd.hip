@@ -29,8 +29,8 @@
 //              dG_C = e^(G_C) . rowsum(dS1 . S0) + sum_t dKt_t . Kt_t
 //              dlog_alpha_t = sum_{r>=t} dG_r + dG_C
 //
-// Five kernels, all plain fp32 FMAs on LDS tiles (this path is written for correctness and
-// clarity; the matrix cores are not used yet):
+// Five kernels in fp32; the dense products of kda_bwd_products run on the matrix cores
+// (v_mfma_f32_32x32x2_f32, fp32 operands), the rest are plain FMAs on LDS tiles:
 //   kda_bwd_prep     one workgroup per (chunk, head), all chunks in parallel: A_kk, A_qk, T and M,
 //                    left in the workspace as two packed C x C tiles
 //   kda_bwd_states   one workgroup per (sequence, head, 32 state columns) walks the chunks
@@ -58,6 +58,60 @@ __device__ __forceinline__ int64_t chunk_slot(const int32_t *cu, int n, int64_t 
     return cu ? (int64_t)(cu[n] / kC) + n + c : (int64_t)n * chunks_per_seq + c;
 }
 
+// ---- global -> LDS copies.  Every copy issues all of a thread's 16-byte loads before it touches
+// LDS, so that their latencies overlap (a load-store-load-store loop pays one memory round trip
+// per iteration).
+
+__device__ __forceinline__ void unpack16(const uint4 &w, const float *, float (&f)[4])
+{
+    f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
+    f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
+}
+__device__ __forceinline__ void unpack16(const uint4 &w, const __hip_bfloat16 *, float (&f)[8])
+{
+    unpack_bf16x2(w.x, f[0], f[1]); unpack_bf16x2(w.y, f[2], f[3]);
+    unpack_bf16x2(w.z, f[4], f[5]); unpack_bf16x2(w.w, f[6], f[7]);
+}
+
+// ROWS x W block of Tin (rows `stride` elements apart, 16-byte aligned) -> dst[r * ld + c] = mul * x,
+// rows r >= nv zero-filled.  ROWS * W * sizeof(Tin) / 16 must be a multiple of 256.
+template <typename Tin, int ROWS, int W>
+__device__ __forceinline__ void rows_to_lds(float *dst, int ld, const Tin *__restrict__ src, int64_t stride,
+                                            int nv, float mul, int tid)
+{
+    constexpr int EPV = 16 / (int)sizeof(Tin), VPR = W / EPV, NV = ROWS * VPR / 256;
+    static_assert(ROWS * VPR % 256 == 0, "block size");
+    uint4 buf[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int vi = tid + 256 * u, r = vi / VPR, cv = vi % VPR;
+        buf[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < nv) buf[u] = *reinterpret_cast<const uint4 *>(src + r * stride + cv * EPV);
+    }
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int vi = tid + 256 * u, r = vi / VPR, cv = vi % VPR;
+        float f[EPV];
+        unpack16(buf[u], src, f);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) dst[r * ld + cv * EPV + e] = mul * f[e];
+    }
+}
+
+// n4 contiguous 16-byte words, global -> LDS (both 16-byte aligned).
+template <int N4>
+__device__ __forceinline__ void copy_to_lds(float *dst, const float *__restrict__ src, int tid)
+{
+    constexpr int NV = (N4 + 255) / 256;
+    uint4 buf[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u)
+        if (tid + 256 * u < N4) buf[u] = reinterpret_cast<const uint4 *>(src)[tid + 256 * u];
+#pragma unroll
+    for (int u = 0; u < NV; ++u)
+        if (tid + 256 * u < N4) reinterpret_cast<uint4 *>(dst)[tid + 256 * u] = buf[u];
+}
+
 // Loads one chunk.  On return (the last statement is a barrier):
 //   sQ, sK [C][D+1]  q and k as given (zero rows past nv)
 //   sG     [C][D+1]  G in log2 units (rows past nv repeat the last valid row)
@@ -69,17 +123,10 @@ __device__ void chunk_load(const Tin *__restrict__ q, const Tin *__restrict__ k,
                            float *sBeta, float *sGend, int tid)
 {
     constexpr int LD = D + 1;
-    for (int idx = tid; idx < kC * D; idx += 256) {
-        const int r = idx / D, d = idx % D;
-        float fq = 0.f, fk = 0.f, fg = 0.f;
-        if (r < nv) {
-            const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
-            fq = load_as_float(q + off);
-            fk = load_as_float(k + off);
-            fg = load_as_float(log_alpha + off) * kLog2e;
-        }
-        sQ[r * LD + d] = fq; sK[r * LD + d] = fk; sG[r * LD + d] = fg;
-    }
+    const int64_t base = (tok0 * H + h) * (int64_t)D, stride = (int64_t)H * D;
+    rows_to_lds<Tin, kC, D>(sQ, LD, q + base, stride, nv, 1.f, tid);
+    rows_to_lds<Tin, kC, D>(sK, LD, k + base, stride, nv, 1.f, tid);
+    rows_to_lds<Tin, kC, D>(sG, LD, log_alpha + base, stride, nv, kLog2e, tid);
     if (tid < kC) sBeta[tid] = (tid < nv) ? load_as_float(beta + (tok0 + tid) * H + h) : 0.f;
     __syncthreads();
     if (tid < D) {
@@ -98,7 +145,7 @@ constexpr int kTile = kC * kLA;
 
 __device__ __forceinline__ void load_tile(float *dst, const float *__restrict__ src, int tid)
 {
-    for (int idx = tid; idx < kTile; idx += 256) dst[idx] = src[idx];
+    copy_to_lds<kTile / 4>(dst, src, tid);
 }
 
 template <typename Tin, int D>
@@ -229,10 +276,7 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             const int d = idx / kBV, c = idx % kBV;
             Sc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sS[idx];
         }
-        for (int idx = tid; idx < kC * kBV; idx += 256) {
-            const int r = idx / kBV, c = idx % kBV;
-            sV[idx] = (r < nv) ? load_as_float(v + ((tok0 + r) * H + h) * (int64_t)D + col0 + c) : 0.f;
-        }
+        rows_to_lds<Tin, kC, kBV>(sV, kBV, v + (tok0 * H + h) * (int64_t)D + col0, (int64_t)H * D, nv, 1.f, tid);
         load_tile(sA, Tw + (slot * 2 + 1) * (int64_t)kTile, tid);
         chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
         decay_operands<D>(sQ, sK, sG, sGend, tid);
@@ -315,10 +359,7 @@ void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             const int d = idx / kBV, c = idx % kBV;
             dSc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sdS[idx];
         }
-        for (int idx = tid; idx < kC * kBV; idx += 256) {
-            const int r = idx / kBV, c = idx % kBV;
-            sdO[idx] = (r < nv) ? scale * d_o[((tok0 + r) * H + h) * (int64_t)D + col0 + c] : 0.f;
-        }
+        rows_to_lds<float, kC, kBV>(sdO, kBV, d_o + (tok0 * H + h) * (int64_t)D + col0, (int64_t)H * D, nv, scale, tid);
         load_tile(sA, Tw + (slot * 2 + 1) * (int64_t)kTile, tid);
         chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
         decay_operands<D>(sQ, sK, sG, sGend, tid);
@@ -381,38 +422,57 @@ template <int D> constexpr size_t products_lds_floats()
     return (size_t)(D > 2 * kC ? D : 2 * kC) * (D + 1) + 2 * kC * (D + 1) + 2 * D + (256 / D) * D;
 }
 
-// out[r][d] = sum_c sOp[r][c] * sS[d][c] for this thread's column d and rows rg + (256/D) j.
-template <int D, typename Sink>
-__device__ __forceinline__ void times_state_t(const float *sOp, const float *sS, int d, int rg, Sink &&sink)
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Row inside a 32 x 32 matrix-core accumulator tile of register j for a lane in half hh (the
+// column is lane % 32).
+__device__ __forceinline__ int acc_row32(int j, int hh) { return 8 * (j >> 2) + 4 * hh + (j & 3); }
+
+// One 32 x 32 tile of  out[r][d] = sum_c sRow[r0 + r][c] * sCol[d0 + d][c]  on the matrix cores in
+// fp32 (v_mfma_f32_32x32x2_f32: lane l feeds row l % 32 of both operands at contraction index
+// k + l / 32).  Both operand tiles are [.][ld] floats in LDS.
+template <int K>
+__device__ __forceinline__ f32x16 tile_rows_times_rows(const float *sRow, const float *sCol, int ld, int lane)
 {
-    constexpr int LD = D + 1, RG = 256 / D;
-    for (int j0 = 0; j0 < kC / RG; j0 += 4) {
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < D; ++c) {
-            const float s = sS[d * LD + c];
+    const float *pa = sRow + (lane & 31) * ld + (lane >> 5);
+    const float *pb = sCol + (lane & 31) * ld + (lane >> 5);
+    f32x16 acc = {};
+#pragma unroll 8
+    for (int k = 0; k < K; k += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[k], pb[k], acc, 0, 0, 0);
+    return acc;
+}
+
+// out[r][d] = sum_c sOp[r][c] * sS[d][c] for all 64 rows and D columns: wave w owns the tiles
+// t = w, w + 4, ... of the (64 / 32) x (D / 32) grid, column block t % (D / 32) -- so a lane sees one
+// column d all along -- and hands every element to sink(r, d, value).
+template <int D, typename Sink>
+__device__ __forceinline__ void times_state_t(const float *sOp, const float *sS, int tid, Sink &&sink)
+{
+    constexpr int LD = D + 1, NB = D / 32;
+    const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5;
+    for (int t = wave; t < 2 * NB; t += 4) {
+        const int d0 = 32 * (t % NB), r0 = 32 * (t / NB);
+        const f32x16 acc = tile_rows_times_rows<D>(sOp + r0 * LD, sS + d0 * LD, LD, lane);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc[u] = fmaf(sOp[(rg + RG * (j0 + u)) * LD + c], s, acc[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) sink(rg + RG * (j0 + u), acc[u]);
+        for (int j = 0; j < 16; ++j) sink(r0 + acc_row32(j, hh), d0 + (lane & 31), acc[j]);
     }
 }
 
-// dst[r][i] = sum_c sR[r][c] * sI[i][c] for i <= r (row-major C x C in global memory).
+// dst[r][i] = sum_c sR[r][c] * sI[i][c] for i <= r (row-major C x C in global memory): the three
+// 32 x 32 tiles on or below the diagonal, one per wave.
 template <int D>
 __device__ __forceinline__ void lower_product(const float *sR, const float *sI, float *__restrict__ dst, int tid)
 {
     constexpr int LD = D + 1;
-    const int i = tid & 63;
-    for (int r0 = (tid >> 6) * 16; r0 < (tid >> 6) * 16 + 16; r0 += 4) {
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < D; ++c) {
-            const float s = sI[i * LD + c];
+    const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5;
+    if (wave < 3) {
+        const int r0 = wave == 0 ? 0 : 32, i0 = wave == 2 ? 32 : 0;
+        const f32x16 acc = tile_rows_times_rows<D>(sR + r0 * LD, sI + i0 * LD, LD, lane);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc[u] = fmaf(sR[(r0 + u) * LD + c], s, acc[u]);
+        for (int j = 0; j < 16; ++j) {
+            const int r = r0 + acc_row32(j, hh), i = i0 + (lane & 31);
+            if (i <= r) dst[r * kC + i] = acc[j];
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) if (i <= r0 + u) dst[(r0 + u) * kC + i] = acc[u];
     }
 }
 
@@ -448,22 +508,16 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
     const float *S0 = Sc + slot * (int64_t)(D * D);
     const float *dS1 = dSc + slot * (int64_t)(D * D);
-    const int d = tid % D, rg = tid / D;
-
+    const int64_t base = (tok0 * H + h) * (int64_t)D, stride = (int64_t)H * D;
     auto load_rows = [&](float *dst, const float *src, float mul) {      // [C][D] token rows -> LDS
-        for (int idx = tid; idx < kC * D; idx += 256) {
-            const int r = idx / D, c = idx % D;
-            dst[r * LD + c] = (r < nv) ? mul * src[((tok0 + r) * H + h) * (int64_t)D + c] : 0.f;
-        }
+        rows_to_lds<float, kC, D>(dst, LD, src + base, stride, nv, mul, tid);
     };
     auto load_state = [&](const float *src) {
-        for (int idx = tid; idx < D * D; idx += 256) sS[(idx / D) * LD + idx % D] = src[idx];
+        rows_to_lds<float, D / 2, D>(sS, LD, src, D, D, 1.f, tid);
+        rows_to_lds<float, D / 2, D>(sS + (D / 2) * LD, LD, src + (D / 2) * D, D, D, 1.f, tid);
     };
 
-    for (int idx = tid; idx < kC * D; idx += 256) {
-        const int r = idx / D, c = idx % D;
-        sG[r * LD + c] = (r < nv) ? load_as_float(log_alpha + ((tok0 + r) * H + h) * (int64_t)D + c) * kLog2e : 0.f;
-    }
+    rows_to_lds<Tin, kC, D>(sG, LD, log_alpha + base, stride, nv, kLog2e, tid);
     load_state(S0);
     load_rows(sOp, d_o, scale);
     __syncthreads();
@@ -475,7 +529,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     __syncthreads();
 
     // dQg = dO S0^T:  dq = Gamma . dQg,  dG = dQg . Gamma . q
-    times_state_t<D>(sOp, sS, d, rg, [&](int r, float acc) {
+    times_state_t<D>(sOp, sS, tid, [&](int r, int d, float acc) {
         if (r < nv) {
             const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
             const float t = acc * fast_exp2(sG[r * LD + d]);
@@ -487,7 +541,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     load_rows(sOp, dv, 1.f);                                             // X
     __syncthreads();
     // dKg = -X S0^T:  dk = Gamma . dKg,  dG += dKg . Gamma . k
-    times_state_t<D>(sOp, sS, d, rg, [&](int r, float acc) {
+    times_state_t<D>(sOp, sS, tid, [&](int r, int d, float acc) {
         if (r < nv) {
             const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
             const float t = -acc * fast_exp2(sG[r * LD + d]);
@@ -497,7 +551,20 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     });
     __syncthreads();
     // dG_C (first part) = e^(G_C) . rowsum(dS1 . S0)
-    for (int idx = tid; idx < D * D; idx += 256) sS[(idx / D) * LD + idx % D] *= dS1[idx];
+    constexpr int kBatch = D * D / 1024 < 8 ? D * D / 1024 : 8;        // 16-byte loads in flight per thread
+#pragma unroll 1
+    for (int part = 0; part < D * D / 4; part += 256 * kBatch) {
+        uint4 buf[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) buf[u] = reinterpret_cast<const uint4 *>(dS1)[part + tid + 256 * u];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int idx = 4 * (part + tid + 256 * u);
+            float *p = sS + (idx / D) * LD + idx % D;
+            p[0] *= __uint_as_float(buf[u].x); p[1] *= __uint_as_float(buf[u].y);
+            p[2] *= __uint_as_float(buf[u].z); p[3] *= __uint_as_float(buf[u].w);
+        }
+    }
     __syncthreads();
     if (tid < D) {
         float acc = 0.f;
@@ -510,7 +577,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     __syncthreads();
     // dKt = Vn dS1^T:  dk += e^(G_C - G) . dKt,  dG -= dKt . Kt,  dG_C += sum_t dKt . Kt
     float gc_part = 0.f;
-    times_state_t<D>(sOp, sS, d, rg, [&](int r, float acc) {
+    times_state_t<D>(sOp, sS, tid, [&](int r, int d, float acc) {
         if (r < nv) {
             const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
             const float t = acc * fast_exp2(sGend[d] - sG[r * LD + d]);
@@ -520,7 +587,10 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
             gc_part += tk;
         }
     });
-    sPart[rg * D + d] = gc_part;
+    {   // a lane's elements all sit in column 32 (wave % (D / 32)) + lane % 32; 256 / D lanes share a column
+        const int wave = tid >> 6, lane = tid & 63;
+        sPart[((lane >> 5) + 2 * (wave / (D / 32))) * D + 32 * (wave % (D / 32)) + (lane & 31)] = gc_part;
+    }
     __syncthreads();
     if (tid < D) {
         float acc = sgc[tid];
