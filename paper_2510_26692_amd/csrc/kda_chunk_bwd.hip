@@ -29,8 +29,9 @@
 //              dG_C = e^(G_C) . rowsum(dS1 . S0) + sum_t dKt_t . Kt_t
 //              dlog_alpha_t = sum_{r>=t} dG_r + dG_C
 //
-// Five kernels in fp32; the dense products of kda_bwd_products run on the matrix cores
-// (v_mfma_f32_32x32x2_f32, fp32 operands), the rest are plain FMAs on LDS tiles:
+// Five kernels in fp32; the dense products of the two scans and of kda_bwd_products run on the
+// matrix cores with fp32 operands (v_mfma_f32_16x16x4_f32, v_mfma_f32_32x32x2_f32), the rest are
+// plain FMAs on LDS tiles:
 //   kda_bwd_prep     one workgroup per (chunk, head), all chunks in parallel: A_kk, A_qk, T and M,
 //                    left in the workspace as two packed C x C tiles
 //   kda_bwd_states   one workgroup per (sequence, head, 32 state columns) walks the chunks
@@ -49,6 +50,8 @@ namespace {
 constexpr int kC = kChunk;
 constexpr int kBV = 32;                 // state columns per workgroup of the two scans
 constexpr int kLA = kC + 2;             // row stride of a packed C x C tile
+constexpr int kTile = kC * kLA;         // floats in one
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // Slot of chunk c of sequence n among all chunk slots (times H + h gives the workspace index).
 // Packed batches: floor(cu[n] / C) + n + c is strictly increasing over (n, c) and bounded by
@@ -73,54 +76,147 @@ __device__ __forceinline__ void unpack16(const uint4 &w, const __hip_bfloat16 *,
     unpack_bf16x2(w.z, f[4], f[5]); unpack_bf16x2(w.w, f[6], f[7]);
 }
 
-// ROWS x W block of Tin (rows `stride` elements apart, 16-byte aligned) -> dst[r * ld + c] = mul * x,
-// rows r >= nv zero-filled.  ROWS * W * sizeof(Tin) / 16 must be a multiple of 256.
+// ROWS x W block of Tin (rows `stride` elements apart, 16-byte aligned): fetch() issues the loads
+// (rows r >= nv read as zero), commit() writes dst[r * ld + c] = mul * x.  ROWS * W * sizeof(Tin) / 16
+// must be a multiple of 256.  Keeping the two apart lets a loop fetch its next block before it works
+// on the current one.
+template <typename Tin, int ROWS, int W>
+struct RowsFetch {
+    static constexpr int EPV = 16 / (int)sizeof(Tin), VPR = W / EPV, NV = ROWS * VPR / 256;
+    static_assert(ROWS * VPR % 256 == 0, "block size");
+    uint4 buf[NV];
+    __device__ __forceinline__ void fetch(const Tin *__restrict__ src, int64_t stride, int nv, int tid)
+    {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int vi = tid + 256 * u, r = vi / VPR, cv = vi % VPR;
+            buf[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (r < nv) buf[u] = *reinterpret_cast<const uint4 *>(src + r * stride + cv * EPV);
+        }
+    }
+    __device__ __forceinline__ void commit(float *dst, int ld, float mul, int tid) const
+    {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int vi = tid + 256 * u, r = vi / VPR, cv = vi % VPR;
+            float f[EPV];
+            unpack16(buf[u], (const Tin *)nullptr, f);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) dst[r * ld + cv * EPV + e] = mul * f[e];
+        }
+    }
+};
+
 template <typename Tin, int ROWS, int W>
 __device__ __forceinline__ void rows_to_lds(float *dst, int ld, const Tin *__restrict__ src, int64_t stride,
                                             int nv, float mul, int tid)
 {
-    constexpr int EPV = 16 / (int)sizeof(Tin), VPR = W / EPV, NV = ROWS * VPR / 256;
-    static_assert(ROWS * VPR % 256 == 0, "block size");
-    uint4 buf[NV];
-#pragma unroll
-    for (int u = 0; u < NV; ++u) {
-        const int vi = tid + 256 * u, r = vi / VPR, cv = vi % VPR;
-        buf[u] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < nv) buf[u] = *reinterpret_cast<const uint4 *>(src + r * stride + cv * EPV);
-    }
-#pragma unroll
-    for (int u = 0; u < NV; ++u) {
-        const int vi = tid + 256 * u, r = vi / VPR, cv = vi % VPR;
-        float f[EPV];
-        unpack16(buf[u], src, f);
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) dst[r * ld + cv * EPV + e] = mul * f[e];
-    }
+    RowsFetch<Tin, ROWS, W> f;
+    f.fetch(src, stride, nv, tid);
+    f.commit(dst, ld, mul, tid);
 }
 
-// n4 contiguous 16-byte words, global -> LDS (both 16-byte aligned).
+// N4 contiguous 16-byte words, global -> LDS (both 16-byte aligned).
+template <int N4>
+struct BlockFetch {
+    static constexpr int NV = (N4 + 255) / 256;
+    uint4 buf[NV];
+    __device__ __forceinline__ void fetch(const float *__restrict__ src, int tid)
+    {
+#pragma unroll
+        for (int u = 0; u < NV; ++u)
+            if (tid + 256 * u < N4) buf[u] = reinterpret_cast<const uint4 *>(src)[tid + 256 * u];
+    }
+    __device__ __forceinline__ void commit(float *dst, int tid) const
+    {
+#pragma unroll
+        for (int u = 0; u < NV; ++u)
+            if (tid + 256 * u < N4) reinterpret_cast<uint4 *>(dst)[tid + 256 * u] = buf[u];
+    }
+};
+
 template <int N4>
 __device__ __forceinline__ void copy_to_lds(float *dst, const float *__restrict__ src, int tid)
 {
-    constexpr int NV = (N4 + 255) / 256;
-    uint4 buf[NV];
-#pragma unroll
-    for (int u = 0; u < NV; ++u)
-        if (tid + 256 * u < N4) buf[u] = reinterpret_cast<const uint4 *>(src)[tid + 256 * u];
-#pragma unroll
-    for (int u = 0; u < NV; ++u)
-        if (tid + 256 * u < N4) reinterpret_cast<uint4 *>(dst)[tid + 256 * u] = buf[u];
+    BlockFetch<N4> f;
+    f.fetch(src, tid);
+    f.commit(dst, tid);
 }
+
+// In place: sG[r][d] <- sum over rows <= r, all 256 threads (256 / D row groups per channel, prefix
+// in registers, the groups' totals through sTot [256 / D][D]); sGend[d] = last row.  Ends with a barrier;
+// the caller has one before.
+template <int D>
+__device__ __forceinline__ void cumsum_rows(float *sG, float *sTot, float *sGend, int tid)
+{
+    constexpr int LD = D + 1, RG = 256 / D, RPT = kC / RG;
+    const int d = tid % D, rg = tid / D;
+    float g[RPT];
+#pragma unroll
+    for (int u = 0; u < RPT; ++u) g[u] = sG[(rg * RPT + u) * LD + d];
+#pragma unroll
+    for (int u = 1; u < RPT; ++u) g[u] += g[u - 1];
+    sTot[rg * D + d] = g[RPT - 1];
+    __syncthreads();
+    float off = 0.f;
+    for (int r2 = 0; r2 < rg; ++r2) off += sTot[r2 * D + d];
+#pragma unroll
+    for (int u = 0; u < RPT; ++u) sG[(rg * RPT + u) * LD + d] = g[u] + off;
+    if (rg == RG - 1) sGend[d] = g[RPT - 1] + off;
+    __syncthreads();
+}
+
+// 16 x 16 fp32 matrix-core tile (v_mfma_f32_16x16x4_f32): with m = lane % 16 and g = lane / 16 a lane
+// feeds A[m][k + g] and B[k + g][m] for every step k of four, and holds D[4 g + j][m] in register j.
+// a(k) and b(k) return this lane's operand element for contraction index k (k + g already applied).
+template <typename FA, typename FB>
+__device__ __forceinline__ f32x4 mma16(int kbeg, int kend, int g, f32x4 acc, FA &&a, FB &&b)
+{
+    for (int k = kbeg; k < kend; k += 4) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a(k + g), b(k + g), acc, 0, 0, 0);
+    return acc;
+}
+
+// Everything a scan step reads from global memory, held in registers between fetch() and commit().
+template <typename Tin, typename Tslice, int D>
+struct StepFetch {
+    RowsFetch<Tin, kC, D> fq, fk, fg;
+    RowsFetch<Tslice, kC, kBV> fs;
+    BlockFetch<kTile / 4> ft;
+    float beta;
+    __device__ __forceinline__ void fetch(const Tin *q, const Tin *k, const Tin *log_alpha, const Tin *beta_,
+                                          const Tslice *slice, const float *tile, int64_t tok0, int nv, int H,
+                                          int h, int col0, int tid)
+    {
+        const int64_t base = (tok0 * H + h) * (int64_t)D, stride = (int64_t)H * D;
+        ft.fetch(tile, tid);
+        fq.fetch(q + base, stride, nv, tid);
+        fk.fetch(k + base, stride, nv, tid);
+        fg.fetch(log_alpha + base, stride, nv, tid);
+        fs.fetch(slice + base + col0, stride, nv, tid);
+        beta = (tid < nv) ? load_as_float(beta_ + (tok0 + tid) * H + h) : 0.f;    // tid < kC rows only
+    }
+    __device__ __forceinline__ void commit(float *sQ, float *sK, float *sG, float *sA, float *sSlice,
+                                           float *sBeta, float slice_mul, int tid) const
+    {
+        constexpr int LD = D + 1;
+        ft.commit(sA, tid);
+        fq.commit(sQ, LD, 1.f, tid);
+        fk.commit(sK, LD, 1.f, tid);
+        fg.commit(sG, LD, kLog2e, tid);
+        fs.commit(sSlice, kBV, slice_mul, tid);
+        if (tid < kC) sBeta[tid] = beta;
+    }
+};
 
 // Loads one chunk.  On return (the last statement is a barrier):
 //   sQ, sK [C][D+1]  q and k as given (zero rows past nv)
 //   sG     [C][D+1]  G in log2 units (rows past nv repeat the last valid row)
-//   sBeta [C] (zero past nv), sGend [D] (G of the last row)
+//   sBeta [C] (zero past nv), sGend [D] (G of the last row); sTot [256] is scratch
 template <typename Tin, int D>
 __device__ void chunk_load(const Tin *__restrict__ q, const Tin *__restrict__ k,
                            const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
                            int64_t tok0, int nv, int H, int h, float *sQ, float *sK, float *sG,
-                           float *sBeta, float *sGend, int tid)
+                           float *sBeta, float *sGend, float *sTot, int tid)
 {
     constexpr int LD = D + 1;
     const int64_t base = (tok0 * H + h) * (int64_t)D, stride = (int64_t)H * D;
@@ -129,19 +225,13 @@ __device__ void chunk_load(const Tin *__restrict__ q, const Tin *__restrict__ k,
     rows_to_lds<Tin, kC, D>(sG, LD, log_alpha + base, stride, nv, kLog2e, tid);
     if (tid < kC) sBeta[tid] = (tid < nv) ? load_as_float(beta + (tok0 + tid) * H + h) : 0.f;
     __syncthreads();
-    if (tid < D) {
-        float run = 0.f;
-        for (int r = 0; r < kC; ++r) { run += sG[r * LD + tid]; sG[r * LD + tid] = run; }
-        sGend[tid] = run;
-    }
-    __syncthreads();
+    cumsum_rows<D>(sG, sTot, sGend, tid);
 }
 
 // The two packed C x C tiles of a chunk, [C][kLA] floats each, that kda_bwd_prep leaves in the
 // workspace:
 //   tile 0   strict lower part [r][i]: T - I          upper part [i][r+1], i <= r: A_kk[r][i]
 //   tile 1   lower part with diagonal [r][j]: M = T Diag(beta)    upper part [i][r+1]: A_qk[r][i]
-constexpr int kTile = kC * kLA;
 
 __device__ __forceinline__ void load_tile(float *dst, const float *__restrict__ src, int tid)
 {
@@ -159,7 +249,7 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD;
     float *s0 = sG + kC * LD, *s1 = s0 + kTile;
-    float *sBeta = s1 + kTile, *sGend = sBeta + kC;
+    float *sBeta = s1 + kTile, *sGend = sBeta + kC, *sTot = sGend + D;
 
     const int64_t ci = blockIdx.y;
     const int n = blockIdx.x, h = blockIdx.z, tid = threadIdx.x;
@@ -172,7 +262,7 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
 
     for (int idx = tid; idx < 2 * kTile; idx += 256) s0[idx] = 0.f;
-    chunk_load<Tin, D>(q, k, log_alpha, beta, tok_base + c0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
+    chunk_load<Tin, D>(q, k, log_alpha, beta, tok_base + c0, nv, H, h, sQ, sK, sG, sBeta, sGend, sTot, tid);
     {
         const int i = tid & 63;
         for (int r = tid >> 6; r < kC; r += 4) {
@@ -229,11 +319,11 @@ __device__ void decay_operands(float *sQ, float *sK, float *sG, const float *sGe
     }
 }
 
-template <int D> constexpr size_t prep_lds_floats() { return 3 * kC * (D + 1) + 2 * kTile + kC + D; }
+template <int D> constexpr size_t prep_lds_floats() { return 3 * kC * (D + 1) + 2 * kTile + kC + D + 256; }
 
 template <int D> constexpr size_t scan_lds_floats()
 {
-    return 3 * kC * (D + 1) + kC * kLA + 3 * kC * kBV + D * kBV + kC + D;
+    return 3 * kC * (D + 1) + kC * kLA + 3 * kC * kBV + D * kBV + kC + D + 256;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -253,7 +343,7 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;
     float *sV = sA + kC * kLA, *sVn = sV + kC * kBV, *sX = sVn + kC * kBV;
-    float *sS = sX + kC * kBV, *sBeta = sS + D * kBV, *sGend = sBeta + kC;
+    float *sS = sX + kC * kBV, *sBeta = sS + D * kBV, *sGend = sBeta + kC, *sTot = sGend + D;
     (void)sX;
 
     const int n = blockIdx.x, h = blockIdx.y, col0 = blockIdx.z * kBV, tid = threadIdx.x;
@@ -266,55 +356,75 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
         sS[idx] = h0 ? h0[state_off + (int64_t)d * D + col0 + c] : 0.f;
     }
 
-    int64_t ci = 0;
-    for (int64_t c0 = 0; c0 < len; c0 += kC, ++ci) {
-        const int nv = (int)((len - c0 < kC) ? (len - c0) : kC);
-        const int64_t tok0 = tok_base + c0;
-        const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
+    const int64_t nchunks = (len + kC - 1) / kC;
+    const int64_t slot_first = chunk_slot(cu, n, chunks_per_seq, 0) * H + h;     // slots of a sequence are H apart
+    auto valid_rows = [&](int64_t ci) { return (int)((len - ci * kC < kC) ? (len - ci * kC) : kC); };
+    StepFetch<Tin, Tin, D> nxt;
+    if (nchunks > 0)
+        nxt.fetch(q, k, log_alpha, beta, v, Tw + ((slot_first) * 2 + 1) * (int64_t)kTile, tok_base, valid_rows(0),
+                  H, h, col0, tid);
+    for (int64_t ci = 0; ci < nchunks; ++ci) {
+        const int nv = valid_rows(ci);
+        const int64_t tok0 = tok_base + ci * kC;
+        const int64_t slot = slot_first + ci * H;
         __syncthreads();
         for (int idx = tid; idx < D * kBV; idx += 256) {
             const int d = idx / kBV, c = idx % kBV;
             Sc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sS[idx];
         }
-        rows_to_lds<Tin, kC, kBV>(sV, kBV, v + (tok0 * H + h) * (int64_t)D + col0, (int64_t)H * D, nv, 1.f, tid);
-        load_tile(sA, Tw + (slot * 2 + 1) * (int64_t)kTile, tid);
-        chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
+        nxt.commit(sQ, sK, sG, sA, sV, sBeta, 1.f, tid);
+        if (ci + 1 < nchunks)                                    // the next chunk's loads fly during this one's work
+            nxt.fetch(q, k, log_alpha, beta, v, Tw + ((slot + H) * 2 + 1) * (int64_t)kTile, tok0 + kC,
+                      valid_rows(ci + 1), H, h, col0, tid);
+        __syncthreads();
+        cumsum_rows<D>(sG, sTot, sGend, tid);
         decay_operands<D>(sQ, sK, sG, sGend, tid);
         __syncthreads();
-        const int c = tid & 31, w8 = tid >> 5;
-        {                                                        // Y = V - Kg S0, rows w8 + 8 u
-            float acc[8] = {};
-            for (int d = 0; d < D; ++d) {
-                const float sv = sS[d * kBV + c];
+        const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
+        const int r0 = 16 * wave;                                // this wave's 16 token rows
+        f32x4 y[2];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc[u] = fmaf(sG[(w8 + 8 * u) * LD + d], sv, acc[u]);
-            }
+        for (int ct = 0; ct < 2; ++ct) {                         // Y = V - Kg S0
+            const f32x4 acc = mma16(0, D, g, f32x4{0.f, 0.f, 0.f, 0.f},
+                                    [&](int k) { return sG[(r0 + m) * LD + k]; },
+                                    [&](int k) { return sS[k * kBV + 16 * ct + m]; });
 #pragma unroll
-            for (int u = 0; u < 8; ++u) sV[(w8 + 8 * u) * kBV + c] -= acc[u];
-        }
-        __syncthreads();
-        for (int r = tid >> 5; r < kC; r += 8) {                 // Vn = M Y
-            float acc = 0.f;
-            for (int j = 0; j <= r; ++j) acc = fmaf(sA[r * kLA + j], sV[j * kBV + c], acc);
-            sVn[r * kBV + c] = acc;
-            if (r < nv) {
-                const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + col0 + c;
-                Yw[off] = sV[r * kBV + c];
-                Vnw[off] = acc;
+            for (int j = 0; j < 4; ++j) {
+                y[ct][j] = sV[(r0 + 4 * g + j) * kBV + 16 * ct + m] - acc[j];
+                sV[(r0 + 4 * g + j) * kBV + 16 * ct + m] = y[ct][j];
             }
         }
         __syncthreads();
-        {                                                        // S1 = Diag(e^G_C) S0 + Kt^T Vn
-            float acc[D / 8];
 #pragma unroll
-            for (int u = 0; u < D / 8; ++u) acc[u] = sS[(w8 + 8 * u) * kBV + c] * fast_exp2(sGend[w8 + 8 * u]);
-            for (int j = 0; j < kC; ++j) {
-                const float vn = sVn[j * kBV + c];
+        for (int ct = 0; ct < 2; ++ct) {                         // Vn = M Y (M lower triangular)
+            const f32x4 acc = mma16(0, r0 + 16, g, f32x4{0.f, 0.f, 0.f, 0.f},
+                                    [&](int k) { return k <= r0 + m ? sA[(r0 + m) * kLA + k] : 0.f; },
+                                    [&](int k) { return sV[k * kBV + 16 * ct + m]; });
 #pragma unroll
-                for (int u = 0; u < D / 8; ++u) acc[u] = fmaf(sK[j * LD + w8 + 8 * u], vn, acc[u]);
+            for (int j = 0; j < 4; ++j) {
+                const int r = r0 + 4 * g + j;
+                sVn[r * kBV + 16 * ct + m] = acc[j];
+                if (r < nv) {
+                    const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + col0 + 16 * ct + m;
+                    Yw[off] = y[ct][j];
+                    Vnw[off] = acc[j];
+                }
             }
+        }
+        __syncthreads();
+        for (int rt = wave * (D / 64); rt < (wave + 1) * (D / 64); ++rt) {       // S1 = Diag(e^G_C) S0 + Kt^T Vn
+            const int d0 = 16 * rt;
 #pragma unroll
-            for (int u = 0; u < D / 8; ++u) sS[(w8 + 8 * u) * kBV + c] = acc[u];
+            for (int ct = 0; ct < 2; ++ct) {
+                f32x4 acc;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[j] = sS[(d0 + 4 * g + j) * kBV + 16 * ct + m] * fast_exp2(sGend[d0 + 4 * g + j]);
+                acc = mma16(0, kC, g, acc, [&](int k) { return sK[k * LD + d0 + m]; },
+                            [&](int k) { return sVn[k * kBV + 16 * ct + m]; });
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sS[(d0 + 4 * g + j) * kBV + 16 * ct + m] = acc[j];
+            }
         }
     }
 }
@@ -336,7 +446,7 @@ void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;
     float *sdO = sA + kC * kLA, *sdVn = sdO + kC * kBV, *sX = sdVn + kC * kBV;
-    float *sdS = sX + kC * kBV, *sBeta = sdS + D * kBV, *sGend = sBeta + kC;
+    float *sdS = sX + kC * kBV, *sBeta = sdS + D * kBV, *sGend = sBeta + kC, *sTot = sGend + D;
 
     const int n = blockIdx.x, h = blockIdx.y, col0 = blockIdx.z * kBV, tid = threadIdx.x;
     int64_t tok_base, len;
@@ -349,60 +459,75 @@ void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     }
 
     const int64_t nchunks = (len + kC - 1) / kC;
+    const int64_t slot_first = chunk_slot(cu, n, chunks_per_seq, 0) * H + h;     // slots of a sequence are H apart
+    auto valid_rows = [&](int64_t ci) { return (int)((len - ci * kC < kC) ? (len - ci * kC) : kC); };
+    StepFetch<Tin, float, D> nxt;
+    if (nchunks > 0)
+        nxt.fetch(q, k, log_alpha, beta, d_o, Tw + ((slot_first + (nchunks - 1) * H) * 2 + 1) * (int64_t)kTile,
+                  tok_base + (nchunks - 1) * kC, valid_rows(nchunks - 1), H, h, col0, tid);
     for (int64_t ci = nchunks - 1; ci >= 0; --ci) {
-        const int64_t c0 = ci * kC;
-        const int nv = (int)((len - c0 < kC) ? (len - c0) : kC);
-        const int64_t tok0 = tok_base + c0;
-        const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
+        const int nv = valid_rows(ci);
+        const int64_t tok0 = tok_base + ci * kC;
+        const int64_t slot = slot_first + ci * H;
         __syncthreads();
         for (int idx = tid; idx < D * kBV; idx += 256) {         // dS1 of this chunk
             const int d = idx / kBV, c = idx % kBV;
             dSc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sdS[idx];
         }
-        rows_to_lds<float, kC, kBV>(sdO, kBV, d_o + (tok0 * H + h) * (int64_t)D + col0, (int64_t)H * D, nv, scale, tid);
-        load_tile(sA, Tw + (slot * 2 + 1) * (int64_t)kTile, tid);
-        chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
+        nxt.commit(sQ, sK, sG, sA, sdO, sBeta, scale, tid);
+        if (ci > 0)                                              // the next chunk's loads fly during this one's work
+            nxt.fetch(q, k, log_alpha, beta, d_o, Tw + ((slot - H) * 2 + 1) * (int64_t)kTile, tok0 - kC, kC,
+                      H, h, col0, tid);
+        __syncthreads();
+        cumsum_rows<D>(sG, sTot, sGend, tid);
         decay_operands<D>(sQ, sK, sG, sGend, tid);
         __syncthreads();
-        const int c = tid & 31, w8 = tid >> 5;
-        {                                                        // dVn = P^T dO + Kt dS1, rows w8 + 8 u
-            float acc[8] = {};
-            for (int d = 0; d < D; ++d) {
-                const float sv = sdS[d * kBV + c];
+        const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
+        const int r0 = 16 * wave;                                // this wave's 16 token rows
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc[u] = fmaf(sK[(w8 + 8 * u) * LD + d], sv, acc[u]);
-            }
+        for (int ct = 0; ct < 2; ++ct) {                         // dVn = Kt dS1 + P^T dO (P lower triangular)
+            f32x4 acc = mma16(0, D, g, f32x4{0.f, 0.f, 0.f, 0.f},
+                              [&](int k) { return sK[(r0 + m) * LD + k]; },
+                              [&](int k) { return sdS[k * kBV + 16 * ct + m]; });
+            acc = mma16(r0, kC, g, acc,
+                        [&](int k) { return k >= r0 + m ? sA[(r0 + m) * kLA + k + 1] : 0.f; },   // P[k][r0 + m]
+                        [&](int k) { return sdO[k * kBV + 16 * ct + m]; });
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = w8 + 8 * u;
-                float a = acc[u];
-                for (int r = i; r < kC; ++r) a = fmaf(sA[i * kLA + r + 1], sdO[r * kBV + c], a);
-                sdVn[i * kBV + c] = a;
-                if (i < nv) dVnw[((tok0 + i) * H + h) * (int64_t)D + col0 + c] = a;
+            for (int j = 0; j < 4; ++j) {
+                const int i = r0 + 4 * g + j;
+                sdVn[i * kBV + 16 * ct + m] = acc[j];
+                if (i < nv) dVnw[((tok0 + i) * H + h) * (int64_t)D + col0 + 16 * ct + m] = acc[j];
             }
         }
         __syncthreads();
-        for (int j = tid >> 5; j < kC; j += 8) {                 // X = M^T dVn = dV
-            float acc = 0.f;
-            for (int r = j; r < kC; ++r) acc = fmaf(sA[r * kLA + j], sdVn[r * kBV + c], acc);
-            sX[j * kBV + c] = acc;
-            if (j < nv) dv[((tok0 + j) * H + h) * (int64_t)D + col0 + c] = acc;
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {                         // X = M^T dVn = dV
+            const f32x4 acc = mma16(r0, kC, g, f32x4{0.f, 0.f, 0.f, 0.f},
+                                    [&](int k) { return k >= r0 + m ? sA[k * kLA + r0 + m] : 0.f; },   // M[k][r0 + m]
+                                    [&](int k) { return sdVn[k * kBV + 16 * ct + m]; });
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = r0 + 4 * g + j;
+                sX[i * kBV + 16 * ct + m] = acc[j];
+                if (i < nv) dv[((tok0 + i) * H + h) * (int64_t)D + col0 + 16 * ct + m] = acc[j];
+            }
         }
         __syncthreads();
-        {                                                        // dS0, rows w8 + 8 u
-            float acc[D / 8];
+        for (int rt = wave * (D / 64); rt < (wave + 1) * (D / 64); ++rt) {       // dS0
+            const int d0 = 16 * rt;
 #pragma unroll
-            for (int u = 0; u < D / 8; ++u) acc[u] = sdS[(w8 + 8 * u) * kBV + c] * fast_exp2(sGend[w8 + 8 * u]);
-            for (int r = 0; r < kC; ++r) {
-                const float a = sdO[r * kBV + c], x = -sX[r * kBV + c];
+            for (int ct = 0; ct < 2; ++ct) {
+                f32x4 acc;
 #pragma unroll
-                for (int u = 0; u < D / 8; ++u) {
-                    acc[u] = fmaf(sQ[r * LD + w8 + 8 * u], a, acc[u]);
-                    acc[u] = fmaf(sG[r * LD + w8 + 8 * u], x, acc[u]);
-                }
+                for (int j = 0; j < 4; ++j)
+                    acc[j] = sdS[(d0 + 4 * g + j) * kBV + 16 * ct + m] * fast_exp2(sGend[d0 + 4 * g + j]);
+                acc = mma16(0, kC, g, acc, [&](int k) { return sQ[k * LD + d0 + m]; },
+                            [&](int k) { return sdO[k * kBV + 16 * ct + m]; });
+                acc = mma16(0, kC, g, acc, [&](int k) { return -sG[k * LD + d0 + m]; },
+                            [&](int k) { return sX[k * kBV + 16 * ct + m]; });
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sdS[(d0 + 4 * g + j) * kBV + 16 * ct + m] = acc[j];
             }
-#pragma unroll
-            for (int u = 0; u < D / 8; ++u) sdS[(w8 + 8 * u) * kBV + c] = acc[u];
         }
     }
     if (dh0) {
@@ -422,7 +547,6 @@ template <int D> constexpr size_t products_lds_floats()
     return (size_t)(D > 2 * kC ? D : 2 * kC) * (D + 1) + 2 * kC * (D + 1) + 2 * D + (256 / D) * D;
 }
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // Row inside a 32 x 32 matrix-core accumulator tile of register j for a lane in half hh (the
 // column is lane % 32).
@@ -521,12 +645,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     load_state(S0);
     load_rows(sOp, d_o, scale);
     __syncthreads();
-    if (tid < D) {
-        float run = 0.f;
-        for (int r = 0; r < kC; ++r) { run += sG[r * LD + tid]; sG[r * LD + tid] = run; }
-        sGend[tid] = run;
-    }
-    __syncthreads();
+    cumsum_rows<D>(sG, sPart, sGend, tid);
 
     // dQg = dO S0^T:  dq = Gamma . dQg,  dG = dQg . Gamma . q
     times_state_t<D>(sOp, sS, tid, [&](int r, int d, float acc) {
@@ -614,7 +733,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
 // ------------------------------------------------------------------------------------------
 template <int D> constexpr size_t chain_lds_floats()
 {
-    return 3 * kC * (D + 1) + 3 * kC * kLA + 2 * kC + D;
+    return 3 * kC * (D + 1) + 3 * kC * kLA + 2 * kC + D + 256;
 }
 
 template <typename Tin, int D>
@@ -633,7 +752,7 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     float *sA = sG + kC * LD;               // T - I (strict lower), A_kk (upper, transposed)
     float *sB = sA + kC * kLA;              // dM -> dT -> dL -> dA_kk (lower), dP (upper, transposed)
     float *sZ = sB + kC * kLA;              // dT T^T
-    float *sBeta = sZ + kC * kLA, *sdb = sBeta + kC, *sGend = sdb + kC;
+    float *sBeta = sZ + kC * kLA, *sdb = sBeta + kC, *sGend = sdb + kC, *sTot = sGend + D;
 
     const int64_t ci = blockIdx.y;
     const int n = blockIdx.x, h = blockIdx.z, tid = threadIdx.x;
@@ -654,7 +773,7 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
         }
     }
     load_tile(sA, Tw + slot * 2 * (int64_t)kTile, tid);
-    chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, tid);
+    chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, sTot, tid);
 
     auto Tm = [&](int r, int j) { return r == j ? 1.f : sA[r * kLA + j]; };   // r >= j
 
