@@ -166,16 +166,6 @@ __device__ __forceinline__ void cumsum_rows(float *sG, float *sTot, float *sGend
     __syncthreads();
 }
 
-// 16 x 16 fp32 matrix-core tile (v_mfma_f32_16x16x4_f32): with m = lane % 16 and g = lane / 16 a lane
-// feeds A[m][k + g] and B[k + g][m] for every step k of four, and holds D[4 g + j][m] in register j.
-// a(k) and b(k) return this lane's operand element for contraction index k (k + g already applied).
-template <typename FA, typename FB>
-__device__ __forceinline__ f32x4 mma16(int kbeg, int kend, int g, f32x4 acc, FA &&a, FB &&b)
-{
-    for (int k = kbeg; k < kend; k += 4) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a(k + g), b(k + g), acc, 0, 0, 0);
-    return acc;
-}
-
 // Everything a scan step reads from global memory, held in registers between fetch() and commit().
 template <typename Tin, typename Tslice, int D>
 struct StepFetch {
@@ -207,6 +197,16 @@ struct StepFetch {
         if (tid < kC) sBeta[tid] = beta;
     }
 };
+
+// 16 x 16 fp32 matrix-core tile (v_mfma_f32_16x16x4_f32): with m = lane % 16 and g = lane / 16 a lane
+// feeds A[m][k + g] and B[k + g][m] for every step k of four, and holds D[4 g + j][m] in register j.
+// a(k) and b(k) return this lane's operand element for contraction index k (k + g already applied).
+template <typename FA, typename FB>
+__device__ __forceinline__ f32x4 mma16(int kbeg, int kend, int g, f32x4 acc, FA &&a, FB &&b)
+{
+    for (int k = kbeg; k < kend; k += 4) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a(k + g), b(k + g), acc, 0, 0, 0);
+    return acc;
+}
 
 // Loads one chunk.  On return (the last statement is a barrier):
 //   sQ, sK [C][D+1]  q and k as given (zero rows past nv)
@@ -263,35 +263,75 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
 
     for (int idx = tid; idx < 2 * kTile; idx += 256) s0[idx] = 0.f;
     chunk_load<Tin, D>(q, k, log_alpha, beta, tok_base + c0, nv, H, h, sQ, sK, sG, sBeta, sGend, sTot, tid);
-    {
-        const int i = tid & 63;
-        for (int r = tid >> 6; r < kC; r += 4) {
-            if (i <= r) {
-                float akk = 0.f, aqk = 0.f;
-                for (int d = 0; d < D; ++d) {
-                    const float e = fast_exp2(sG[r * LD + d] - sG[i * LD + d]);
-                    const float t = sK[i * LD + d] * e;
-                    akk = fmaf(sK[r * LD + d], t, akk);
-                    aqk = fmaf(sQ[r * LD + d], t, aqk);
+    {   // A_kk, A_qk for i <= r, pairwise in the log domain; a thread takes column token i and four rows at a time
+        const int i = tid & 63, wv = tid >> 6;
+        for (int rb = 0; rb < kC; rb += 16) {
+            const int r_[4] = {rb + wv, rb + wv + 4, rb + wv + 8, rb + wv + 12};
+            float akk[4] = {}, aqk[4] = {};
+            for (int d = 0; d < D; ++d) {
+                const float gi = sG[i * LD + d], ki = sK[i * LD + d];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float t = ki * fast_exp2(fminf(sG[r_[u] * LD + d] - gi, 0.f));
+                    akk[u] = fmaf(sK[r_[u] * LD + d], t, akk[u]);
+                    aqk[u] = fmaf(sQ[r_[u] * LD + d], t, aqk[u]);
                 }
-                if (i < r) s0[r * kLA + i] = sBeta[r] * akk;     // L = StrictTril(Diag(beta) A_kk)
-                s0[i * kLA + r + 1] = akk;
-                s1[i * kLA + r + 1] = aqk;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = r_[u];
+                if (i <= r) {
+                    if (i < r) {                                  // L = StrictTril(Diag(beta) A_kk), kept twice:
+                        s0[r * kLA + i] = sBeta[r] * akk[u];      // s0 becomes T - I block by block,
+                        s1[r * kLA + i] = sBeta[r] * akk[u];      // s1 keeps L until M replaces it
+                    }
+                    s0[i * kLA + r + 1] = akk[u];
+                    s1[i * kLA + r + 1] = aqk[u];
+                }
             }
         }
     }
     __syncthreads();
-    // forward substitution, row by row: the strict lower part becomes (I + L)^-1 - I
-    for (int r = 1; r < kC; ++r) {
-        float val = 0.f;
-        const int j = tid;
-        if (j < r) {
-            val = -s0[r * kLA + j];
-            for (int i = j + 1; i < r; ++i) val = fmaf(-s0[r * kLA + i], s0[i * kLA + j], val);
+    // (I + L)^-1 - I in 16 x 16 blocks.  Diagonal blocks: wave w inverts block w, lane m < 16 its column m
+    // (X[r][m] = -L[r][m] - sum_{m < i < r} L[r][i] X[i][m]; a lane reads back only what it wrote itself).
+    {
+        const int wave = tid >> 6, lane = tid & 63, b0 = 16 * wave;
+        if (lane < 16) {
+            for (int r = 1; r < 16; ++r) {
+                float val = 0.f;
+                if (lane < r) {
+                    val = -s1[(b0 + r) * kLA + b0 + lane];
+                    for (int i = lane + 1; i < r; ++i)
+                        val = fmaf(-s1[(b0 + r) * kLA + b0 + i], s0[(b0 + i) * kLA + b0 + lane], val);
+                    s0[(b0 + r) * kLA + b0 + lane] = val;
+                }
+            }
         }
-        __syncthreads();
-        if (j < r) s0[r * kLA + j] = val;
-        __syncthreads();
+    }
+    __syncthreads();
+    // Blocks below the diagonal, one block row at a time (block (R, I) needs the blocks (J, I), I <= J < R):
+    // X_RI = -X_RR (sum_J L_RJ X_JI), X_RR and X_II with their unit diagonals; wave I takes column block I.
+    {
+        const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
+        auto X = [&](int r, int c) { return r == c ? 1.f : (c < r ? s0[r * kLA + c] : 0.f); };
+        for (int R = 1; R < 4; ++R) {
+            if (wave < R) {
+                const int I = wave;
+                const f32x4 t = mma16(16 * I, 16 * R, g, f32x4{0.f, 0.f, 0.f, 0.f},
+                                      [&](int k) { return s1[(16 * R + m) * kLA + k]; },          // L[16 R + m][k]
+                                      [&](int k) { return X(k, 16 * I + m); });
+                // the second product's B operand B[k][m] = t(k, m) sits in register k % 4 of lane group
+                // k / 4: with contraction slot (step ks, group g) standing for k = 4 g + ks, register ks
+                // of this lane is its operand as it stands
+                f32x4 r = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    r = __builtin_amdgcn_mfma_f32_16x16x4f32(X(16 * R + m, 16 * R + 4 * g + ks), t[ks], r, 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) s0[(16 * R + 4 * g + j) * kLA + 16 * I + m] = -r[j];
+            }
+            __syncthreads();
+        }
     }
     for (int idx = tid; idx < kC * kC; idx += 256) {
         const int r = idx >> 6, j = idx & 63;
@@ -790,25 +830,32 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
         if (j <= r) sB[r * kLA + j] *= sBeta[j];
     }
     __syncthreads();
-    // Z[a,i] = sum_{b <= min(a,i)} dT[a,b] T[i,b]
+    // Z[a,i] = sum_{b <= min(a,i)} dT[a,b] T[i,b]: wave w takes the 16 rows a of block w
     {
-        const int i = tid & 63;
-        for (int a = tid >> 6; a < kC; a += 4) {
-            const int m = a < i ? a : i;
-            float acc = 0.f;
-            for (int b = 0; b <= m; ++b) acc = fmaf(sB[a * kLA + b], Tm(i, b), acc);
-            sZ[a * kLA + i] = acc;
+        const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
+        const int a = 16 * wave + m;
+        for (int Ib = 0; Ib < 4; ++Ib) {
+            const int i = 16 * Ib + m;
+            const f32x4 acc = mma16(0, 16 * ((wave < Ib ? wave : Ib) + 1), g, f32x4{0.f, 0.f, 0.f, 0.f},
+                                    [&](int b_) { return b_ <= a ? sB[a * kLA + b_] : 0.f; },
+                                    [&](int b_) { return b_ < i ? sA[i * kLA + b_] : (b_ == i ? 1.f : 0.f); });
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sZ[(16 * wave + 4 * g + j) * kLA + 16 * Ib + m] = acc[j];
         }
     }
     __syncthreads();
     // dL[r,i] = -sum_{a>=r} T[a,r] Z[a,i]  (i < r), then dbeta_r += sum_i dL A_kk, dA_kk = beta_r dL
     {
-        const int i = tid & 63;
-        for (int r = tid >> 6; r < kC; r += 4) {
-            if (i < r) {
-                float acc = 0.f;
-                for (int a = r; a < kC; ++a) acc = fmaf(Tm(a, r), sZ[a * kLA + i], acc);
-                sB[r * kLA + i] = -acc;
+        const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
+        const int r = 16 * wave + m;
+        for (int Ib = 0; Ib <= wave; ++Ib) {
+            const f32x4 acc = mma16(16 * wave, kC, g, f32x4{0.f, 0.f, 0.f, 0.f},
+                                    [&](int a_) { return a_ > r ? sA[a_ * kLA + r] : (a_ == r ? 1.f : 0.f); },
+                                    [&](int a_) { return sZ[a_ * kLA + 16 * Ib + m]; });
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int rr = 16 * wave + 4 * g + j, ii = 16 * Ib + m;
+                if (ii < rr) sB[rr * kLA + ii] = -acc[j];
             }
         }
     }
@@ -826,33 +873,51 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     }
     __syncthreads();
 
-    // pairwise decay terms for this thread's channel d and tokens rg + RG j
+    // pairwise decay terms for this thread's channel d and tokens rg + RG j, four tokens at a time
     const int d = tid % D, rg = tid / D;
     float dgt[kC / RG];
 #pragma unroll 1
-    for (int j = 0; j < kC / RG; ++j) {
-        const int t = rg + RG * j;
-        const float Gt = sG[t * LD + d], kt = sK[t * LD + d], qt = sQ[t * LD + d];
-        float a1 = 0.f, a2 = 0.f, b1 = 0.f;
-        for (int i = 0; i < t; ++i) {                            // token t as the row
-            const float kk = sK[i * LD + d] * fast_exp2(Gt - sG[i * LD + d]);
-            a1 = fmaf(sB[t * kLA + i], kk, a1);
-            a2 = fmaf(sB[i * kLA + t + 1], kk, a2);
+    for (int j0 = 0; j0 < kC / RG; j0 += 4) {
+        int t_[4];
+        float Gt[4], kt[4], qt[4], a1[4] = {}, a2[4] = {}, b1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            t_[u] = rg + RG * (j0 + u);
+            Gt[u] = sG[t_[u] * LD + d]; kt[u] = sK[t_[u] * LD + d]; qt[u] = sQ[t_[u] * LD + d];
         }
-        a2 = fmaf(sB[t * kLA + t + 1], kt, a2);                  // dP[t,t]
-        b1 = sB[t * kLA + t + 1] * qt;
-        for (int r = t + 1; r < kC; ++r) {                       // token t as the column
-            const float e = fast_exp2(sG[r * LD + d] - Gt);
-            b1 = fmaf(fmaf(sB[r * kLA + t], sK[r * LD + d], sB[t * kLA + r + 1] * sQ[r * LD + d]), e, b1);
+        for (int i = 0; i < t_[3]; ++i) {                        // the tokens as rows: columns i < t
+            const float gi = sG[i * LD + d], ki = sK[i * LD + d];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float kk = i < t_[u] ? ki * fast_exp2(Gt[u] - gi) : 0.f;
+                a1[u] = fmaf(sB[t_[u] * kLA + i], kk, a1[u]);
+                a2[u] = fmaf(sB[i * kLA + t_[u] + 1], kk, a2[u]);
+            }
         }
-        float g = 0.f;
-        if (t < nv) {
-            const int64_t off = ((tok0 + t) * H + h) * (int64_t)D + d;
-            dq[off] += a2;
-            dk[off] += a1 + b1;
-            g = dla[off] + kt * a1 + qt * a2 - kt * b1;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a2[u] = fmaf(sB[t_[u] * kLA + t_[u] + 1], kt[u], a2[u]);     // dP[t,t]
+            b1[u] = sB[t_[u] * kLA + t_[u] + 1] * qt[u];
         }
-        dgt[j] = g;
+        for (int r = t_[0] + 1; r < kC; ++r) {                   // the tokens as columns: rows r > t
+            const float gr = sG[r * LD + d], kr = sK[r * LD + d], qr = sQ[r * LD + d];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float e = r > t_[u] ? fast_exp2(gr - Gt[u]) : 0.f;
+                b1[u] = fmaf(fmaf(sB[r * kLA + t_[u]], kr, sB[t_[u] * kLA + r + 1] * qr), e, b1[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float gsum = 0.f;
+            if (t_[u] < nv) {
+                const int64_t off = ((tok0 + t_[u]) * H + h) * (int64_t)D + d;
+                dq[off] += a2[u];
+                dk[off] += a1[u] + b1[u];
+                gsum = dla[off] + kt[u] * a1[u] + qt[u] * a2[u] - kt[u] * b1[u];
+            }
+            dgt[j0 + u] = gsum;
+        }
     }
     __syncthreads();
 #pragma unroll 1
