@@ -151,9 +151,10 @@ kda_status kda_chunk_fwd(const kda_dims *dims,
  *   dh0        [N,H,dk,dv]     fp32 gradient of the initial states (equals d_hT for an empty
  *                              sequence), or NULL if not wanted
  *   workspace                  at least kda_chunk_bwd_workspace_size(dims) bytes, 256-byte
- *                              aligned: the state at the start of every chunk and its
- *                              gradient (2 * dk * dv floats per chunk and head) plus three
- *                              [tokens, H, dv] arrays and two C x C tiles per chunk and head
+ *                              aligned: the state at the start of every chunk and the
+ *                              gradient of the state at its end (2 * dk * dv floats per chunk
+ *                              and head), three [tokens, H, dv] arrays and four C x C tiles
+ *                              per chunk and head; it is not bounded by time segments
  * No gradient may alias an input or another gradient.  Sequences of more than 65535 * 64
  * tokens are KDA_ERR_UNSUPPORTED.  Everything runs on `hip_stream`.
  */
