@@ -194,6 +194,7 @@ kda_status kda_chunk_bwd(const kda_dims *d, const void *q, const void *k, const 
         }
     }
     if (d->num_seqs == 0 || d->heads == 0) return KDA_OK;
+    if (d->seqlen == 0 && !dh0) return KDA_OK;            // no tokens and nobody asks for dh0 = d_hT
     return chunk_bwd_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, d_o, d_hT, dq, dk, dv, dlog_alpha,
                               dbeta, dh0, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }

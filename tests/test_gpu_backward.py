@@ -74,6 +74,7 @@ CASES = {
     "fp32_inputs_d64": lambda: (si.make_prefill(2, 150, 2, 64, 64, "f32", -2.0, 1204, 0.05), 0.125),
     "fp32_inputs_d128": lambda: (si.make_prefill(1, 131, 2, 128, 128, "f32", -1.0, 1205, 0.05), 1.0),
     "packed": lambda: (si.make_varlen([70, 0, 5, 129, 64, 300], 2, 128, 128, "bf16", -2.0, 1206, 0.05), 1.0),
+    "bf16_inputs_d64": lambda: (si.make_prefill(2, 100, 2, 64, 64, "bf16", -2.0, 1208, 0.05), 1.0),
     "slow_decay_long": lambda: (si.make_prefill(1, 64 * 20 + 9, 2, 128, 128, "bf16", -6.0, 1207, 0.05), 1.0),
 }
 
@@ -124,3 +125,24 @@ def test_backward_rejects_bad_calls():
     with pytest.raises(kda.KdaError) as e:
         kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], do, workspace=small)
     assert e.value.status == 3
+
+
+def test_backward_many_short_sequences():
+    """600 packed sequences of 0..70 tokens (the slot of a chunk comes from cu_seqlens alone)."""
+    rng = np.random.default_rng(1213)
+    lens = [int(v) for v in rng.integers(0, 71, size=600)]
+    x = si.make_varlen(lens, 1, 128, 128, "bf16", -2.0, 1213, 0.05)
+    do, dhT = _grad_inputs(x, 80)
+    got, ref, cu = _run(x, do, dhT, max_seqlen=70)
+    for name in NAMES:
+        assert rel_err(got[name], ref[name]) <= TOL, name
+
+
+def test_backward_zero_tokens_and_zero_sequences():
+    import paper_2510_26692_amd as kda
+    z = lambda *shape, dt=torch.bfloat16: torch.zeros(*shape, dtype=dt, device="cuda")
+    out = kda.kda_chunk_bwd(z(2, 0, 3, 128), z(2, 0, 3, 128), z(2, 0, 3, 128), z(2, 0, 3, 128), z(2, 0, 3),
+                            z(2, 0, 3, 128, dt=torch.float32), dhT=torch.ones(2, 3, 128, 128, device="cuda"))
+    torch.cuda.synchronize()
+    assert out["dq"].shape == (2, 0, 3, 128)
+    assert torch.equal(out["dh0"], torch.ones(2, 3, 128, 128, device="cuda"))   # no tokens: dh0 = dhT

@@ -105,6 +105,37 @@ def test_chunk_fwd_rejects_null_misaligned_and_missing_workspace():
                              None, None, 0, None) == 1                             # packed needs B == 1
 
 
+def test_chunk_bwd_workspace_size_and_rejections_without_launching():
+    kda, lib = _lib()
+    d = _dims(kda)                      # B=2? whatever _dims builds: the size follows from its fields
+    D, C = d.dk, 64
+    chunks = d.num_seqs * ((d.seqlen + C - 1) // C) * d.heads
+    tokens = d.batch * d.seqlen * d.heads
+    need = kda.kda_chunk_bwd_workspace_size(d)
+    floats = chunks * (2 * D * D + D + 2 * C * C + 2 * C * (C + 2)) + 3 * tokens * D
+    assert 0 <= need - 4 * floats < 7 * 256              # seven areas, each rounded up to 256 bytes
+    assert kda.kda_chunk_bwd_workspace_size(_dims(kda, dk=96, dv=96)) == 0
+    p = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(16)]
+
+    def call(dims, q=p[0], d_o=p[5], dq=p[6], dk=p[7], ws=None, ws_bytes=0, cu=None):
+        return lib.kda_chunk_bwd(ctypes.byref(dims), q, p[1], p[2], p[3], p[4], None, cu, d_o, None,
+                                 dq, dk, p[8], p[9], p[10], None, ws, ws_bytes, None)
+    assert call(d) == 3                                                   # no workspace
+    assert call(d, ws=ctypes.c_void_p(0x100000), ws_bytes=need - 1) == 3  # too small
+    assert call(d, ws=ctypes.c_void_p(0x100010), ws_bytes=need) == 3      # misaligned
+    assert call(d, q=None) == 1
+    assert call(d, d_o=None) == 1
+    assert call(d, dq=p[0]) == 1                                          # gradient aliases an input
+    assert call(d, dq=p[7]) == 1                                          # two gradients alias
+    assert call(d, q=ctypes.c_void_p(0x1004)) == 1                        # misaligned tensor
+    assert call(_dims(kda, dk=96, dv=96)) == 2
+    assert call(_dims(kda, chunk=32)) == 2
+    assert call(_dims(kda, batch=2, num_seqs=3), cu=p[11]) == 1           # packed needs B == 1
+    too_long = _dims(kda, batch=1, num_seqs=1, seqlen=65536 * 64)
+    assert call(too_long, ws=ctypes.c_void_p(0x100000), ws_bytes=1 << 62) == 2
+    assert call(_dims(kda, seqlen=0)) == 0                                # nothing to do
+
+
 def test_recurrent_step_rejects_bad_calls():
     kda, lib = _lib()
     d = _dims(kda, seqlen=2)
