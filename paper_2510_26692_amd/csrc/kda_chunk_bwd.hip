@@ -885,6 +885,12 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             t_[u] = rg + RG * (j0 + u);
             Gt[u] = sG[t_[u] * LD + d]; kt[u] = sK[t_[u] * LD + d]; qt[u] = sQ[t_[u] * LD + d];
         }
+        float old_q[4], old_k[4], old_g[4];                      // what kda_bwd_products left: fetched now, used below
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t off = ((tok0 + (t_[u] < nv ? t_[u] : 0)) * H + h) * (int64_t)D + d;
+            old_q[u] = dq[off]; old_k[u] = dk[off]; old_g[u] = dla[off];
+        }
         for (int i = 0; i < t_[3]; ++i) {                        // the tokens as rows: columns i < t
             const float gi = sG[i * LD + d], ki = sK[i * LD + d];
 #pragma unroll
@@ -912,9 +918,9 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             float gsum = 0.f;
             if (t_[u] < nv) {
                 const int64_t off = ((tok0 + t_[u]) * H + h) * (int64_t)D + d;
-                dq[off] += a2[u];
-                dk[off] += a1[u] + b1[u];
-                gsum = dla[off] + kt[u] * a1[u] + qt[u] * a2[u] - kt[u] * b1[u];
+                dq[off] = old_q[u] + a2[u];
+                dk[off] = old_k[u] + a1[u] + b1[u];
+                gsum = old_g[u] + kt[u] * a1[u] + qt[u] * a2[u] - kt[u] * b1[u];
             }
             dgt[j0 + u] = gsum;
         }

@@ -146,3 +146,16 @@ def test_backward_zero_tokens_and_zero_sequences():
     torch.cuda.synchronize()
     assert out["dq"].shape == (2, 0, 3, 128)
     assert torch.equal(out["dh0"], torch.ones(2, 3, 128, 128, device="cuda"))   # no tokens: dh0 = dhT
+
+
+def test_backward_cfg1_full_size():
+    """The bench workload itself (B = 4, T = 4096, H = 16, d = 128, bf16 inputs, h0 present): 64 chunks per
+    sequence, every gradient entry against the oracle."""
+    c = si.CONFIGS["cfg1_prefill_bf16"]
+    x = si.make_prefill(c["B"], c["T"], c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"], c["h0_std"])
+    do, dhT = _grad_inputs(x, 81)
+    got, ref, cu = _run(x, do, dhT)
+    errs = _errors(got, ref, cu, c["B"], c["H"])
+    print("cfg1", {k: "%.2e" % v for k, v in errs.items()})
+    for name, e in errs.items():
+        assert e <= TOL, "%s error %.3e exceeds %.1e" % (name, e, TOL)
