@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--no-breakdown", action="store_true",
                     help="skip the extra serial / single-kernel timing passes (keeps a profile of this "
                          "run down to the launches of the timed configuration)")
+    ap.add_argument("--extras", action="store_true",
+                    help="with --serial: still run the extra passes (bf16 outputs, scalar gate, fused stages, "
+                         "backward), every prefill with its kernels one after the other")
     ap.add_argument("--serial", action="store_true",
                     help="run the two prefill kernels one after the other (needed under tools that serialise "
                          "kernels, e.g. rocprofv3 --pmc); implies --no-breakdown")
@@ -82,7 +85,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.serial:
-        args.no_breakdown = True
+        args.no_breakdown = not args.extras
         kda.kda_debug_set_overlap(0)
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -147,7 +150,7 @@ def main():
         kda.kda_debug_set_phase_mask(2)
         ms_scan = _time_region(torch, prefill, args.steps)
         kda.kda_debug_set_phase_mask(3)
-        kda.kda_debug_set_overlap(1)
+        kda.kda_debug_set_overlap(0 if args.serial else 1)
         prefill()
         torch.cuda.synchronize()
 

@@ -607,18 +607,21 @@ __device__ __forceinline__ f32x16 tile_rows_times_rows(const float *sRow, const 
 }
 
 // out[r][d] = sum_c sOp[r][c] * sS[d][c] for all 64 rows and D columns: wave w owns the tiles
-// t = w, w + 4, ... of the (64 / 32) x (D / 32) grid, column block t % (D / 32) -- so a lane sees one
-// column d all along -- and hands every element to sink(r, d, value).
+// t = w, w + 4, ... of the (64 / 32) x (D / 32) grid (D / 64 of them, numbered ti), column block
+// t % (D / 32) -- so a lane sees one column d all along -- and hands every element to
+// sink(ti, j, r, d, value), j the accumulator register.
 template <int D, typename Sink>
 __device__ __forceinline__ void times_state_t(const float *sOp, const float *sS, int tid, Sink &&sink)
 {
     constexpr int LD = D + 1, NB = D / 32;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5;
-    for (int t = wave; t < 2 * NB; t += 4) {
+#pragma unroll
+    for (int ti = 0; ti < D / 64; ++ti) {
+        const int t = wave + 4 * ti;
         const int d0 = 32 * (t % NB), r0 = 32 * (t / NB);
         const f32x16 acc = tile_rows_times_rows<D>(sOp + r0 * LD, sS + d0 * LD, LD, lane);
 #pragma unroll
-        for (int j = 0; j < 16; ++j) sink(r0 + acc_row32(j, hh), d0 + (lane & 31), acc[j]);
+        for (int j = 0; j < 16; ++j) sink(ti, j, r0 + acc_row32(j, hh), d0 + (lane & 31), acc[j]);
     }
 }
 
@@ -687,26 +690,25 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     __syncthreads();
     cumsum_rows<D>(sG, sPart, sGend, tid);
 
+    // The three products below land on the same elements of every lane, so dq, dk and dG stay in
+    // registers until all three are in and are written once.
+    f32x16 gq[D / 64], gk[D / 64], gg[D / 64], kv[D / 64];
     // dQg = dO S0^T:  dq = Gamma . dQg,  dG = dQg . Gamma . q
-    times_state_t<D>(sOp, sS, tid, [&](int r, int d, float acc) {
-        if (r < nv) {
-            const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
-            const float t = acc * fast_exp2(sG[r * LD + d]);
-            dq[off] = t;
-            dg[off] = t * load_as_float(q + off);
-        }
+    times_state_t<D>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
+        const int64_t off = ((tok0 + (r < nv ? r : 0)) * H + h) * (int64_t)D + d;
+        const float t = acc * fast_exp2(sG[r * LD + d]);         // rows past nv: dO is zero there, so is t
+        gq[ti][j] = t;
+        gg[ti][j] = t * load_as_float(q + off);
+        kv[ti][j] = load_as_float(k + off);
     });
     __syncthreads();
     load_rows(sOp, dv, 1.f);                                             // X
     __syncthreads();
     // dKg = -X S0^T:  dk = Gamma . dKg,  dG += dKg . Gamma . k
-    times_state_t<D>(sOp, sS, tid, [&](int r, int d, float acc) {
-        if (r < nv) {
-            const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
-            const float t = -acc * fast_exp2(sG[r * LD + d]);
-            dk[off] = t;
-            dg[off] += t * load_as_float(k + off);
-        }
+    times_state_t<D>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
+        const float t = -acc * fast_exp2(sG[r * LD + d]);
+        gk[ti][j] = t;
+        gg[ti][j] = fmaf(t, kv[ti][j], gg[ti][j]);
     });
     __syncthreads();
     // dG_C (first part) = e^(G_C) . rowsum(dS1 . S0)
@@ -736,14 +738,15 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     __syncthreads();
     // dKt = Vn dS1^T:  dk += e^(G_C - G) . dKt,  dG -= dKt . Kt,  dG_C += sum_t dKt . Kt
     float gc_part = 0.f;
-    times_state_t<D>(sOp, sS, tid, [&](int r, int d, float acc) {
+    times_state_t<D>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
+        const float t = acc * fast_exp2(sGend[d] - sG[r * LD + d]);
+        const float tk = t * kv[ti][j];                          // rows past nv: Vn and k are zero there
+        gc_part += tk;
         if (r < nv) {
             const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + d;
-            const float t = acc * fast_exp2(sGend[d] - sG[r * LD + d]);
-            dk[off] += t;
-            const float tk = t * load_as_float(k + off);
-            dg[off] -= tk;
-            gc_part += tk;
+            dq[off] = gq[ti][j];
+            dk[off] = gk[ti][j] + t;
+            dg[off] = gg[ti][j] - tk;
         }
     });
     {   // a lane's elements all sit in column 32 (wave % (D / 32)) + lane % 32; 256 / D lanes share a column
