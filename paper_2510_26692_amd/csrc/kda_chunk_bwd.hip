@@ -166,35 +166,38 @@ __device__ __forceinline__ void cumsum_rows(float *sG, float *sTot, float *sGend
     __syncthreads();
 }
 
+// The decay-scaled operands of a chunk as kda_bwd_prep leaves them in the workspace: three [C][D] fp32
+// tiles (Gamma.Q, Gamma.K, Gamma^{i->C}.K; rows past the chunk's end are zero) and G_C in log2 units.
+template <int D> constexpr int operand_floats() { return 3 * kC * D + D; }
+
 // Everything a scan step reads from global memory, held in registers between fetch() and commit().
-template <typename Tin, typename Tslice, int D>
+template <typename Tslice, int D, bool kWithQ>
 struct StepFetch {
-    RowsFetch<Tin, kC, D> fq, fk, fg;
+    RowsFetch<float, kC, D> fq, fkg, fkt;
     RowsFetch<Tslice, kC, kBV> fs;
     BlockFetch<kTile / 4> ft;
-    float beta;
-    __device__ __forceinline__ void fetch(const Tin *q, const Tin *k, const Tin *log_alpha, const Tin *beta_,
-                                          const Tslice *slice, const float *tile, int64_t tok0, int nv, int H,
-                                          int h, int col0, int tid)
+    float gend;
+    __device__ __forceinline__ void fetch(const float *ops, const Tslice *slice, const float *tile,
+                                          int64_t tok0, int nv, int H, int h, int col0, int tid)
     {
-        const int64_t base = (tok0 * H + h) * (int64_t)D, stride = (int64_t)H * D;
         ft.fetch(tile, tid);
-        fq.fetch(q + base, stride, nv, tid);
-        fk.fetch(k + base, stride, nv, tid);
-        fg.fetch(log_alpha + base, stride, nv, tid);
-        fs.fetch(slice + base + col0, stride, nv, tid);
-        beta = (tid < nv) ? load_as_float(beta_ + (tok0 + tid) * H + h) : 0.f;    // tid < kC rows only
+        if (kWithQ) fq.fetch(ops, D, kC, tid);
+        fkg.fetch(ops + kC * D, D, kC, tid);
+        fkt.fetch(ops + 2 * kC * D, D, kC, tid);
+        fs.fetch(slice + (tok0 * H + h) * (int64_t)D + col0, (int64_t)H * D, nv, tid);
+        gend = ops[3 * kC * D + tid % D];
     }
+    // sQ <- Gamma.Q (if fetched), sG <- Gamma.K, sK <- Gamma^{i->C}.K, sA <- the M | A_qk tile
     __device__ __forceinline__ void commit(float *sQ, float *sK, float *sG, float *sA, float *sSlice,
-                                           float *sBeta, float slice_mul, int tid) const
+                                           float *sGend, float slice_mul, int tid) const
     {
         constexpr int LD = D + 1;
         ft.commit(sA, tid);
-        fq.commit(sQ, LD, 1.f, tid);
-        fk.commit(sK, LD, 1.f, tid);
-        fg.commit(sG, LD, kLog2e, tid);
+        if (kWithQ) fq.commit(sQ, LD, 1.f, tid);
+        fkg.commit(sG, LD, 1.f, tid);
+        fkt.commit(sK, LD, 1.f, tid);
         fs.commit(sSlice, kBV, slice_mul, tid);
-        if (tid < kC) sBeta[tid] = beta;
+        if (tid < D) sGend[tid] = gend;
     }
 };
 
@@ -228,6 +231,22 @@ __device__ void chunk_load(const Tin *__restrict__ q, const Tin *__restrict__ k,
     cumsum_rows<D>(sG, sTot, sGend, tid);
 }
 
+// q, k, G tiles -> Gamma.Q, Gamma^{i->C}.K, Gamma.K (in sQ, sK, sG), as the forward kernel does.
+template <int D>
+__device__ void decay_operands(float *sQ, float *sK, float *sG, const float *sGend, int tid)
+{
+    constexpr int LD = D + 1;
+    for (int idx = tid; idx < kC * D; idx += 256) {
+        const int r = idx / D, d = idx % D;
+        const float G = sG[r * LD + d];
+        const float kk = sK[r * LD + d];
+        const float gam = fast_exp2(G);
+        sQ[r * LD + d] *= gam;
+        sG[r * LD + d] = kk * gam;
+        sK[r * LD + d] = kk * fast_exp2(sGend[d] - G);
+    }
+}
+
 // The two packed C x C tiles of a chunk, [C][kLA] floats each, that kda_bwd_prep leaves in the
 // workspace:
 //   tile 0   strict lower part [r][i]: T - I          upper part [i][r+1], i <= r: A_kk[r][i]
@@ -242,8 +261,8 @@ template <typename Tin, int D>
 __global__ __launch_bounds__(256)
 void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                          const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
-                         const int32_t *__restrict__ cu, float *__restrict__ Tw, int64_t T, int H,
-                         int64_t chunks_per_seq)
+                         const int32_t *__restrict__ cu, float *__restrict__ Tw, float *__restrict__ Ow,
+                         int64_t T, int H, int64_t chunks_per_seq)
 {
     constexpr int LD = D + 1;
     extern __shared__ float smem[];
@@ -341,29 +360,25 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     __syncthreads();
     float *dst = Tw + slot * (int64_t)(2 * kTile);
     for (int idx = tid; idx < 2 * kTile; idx += 256) dst[idx] = s0[idx];
-}
-
-// q, k, G tiles -> Gamma.Q, Gamma^{i->C}.K, Gamma.K (in sQ, sK, sG), as the forward kernel does.
-template <int D>
-__device__ void decay_operands(float *sQ, float *sK, float *sG, const float *sGend, int tid)
-{
-    constexpr int LD = D + 1;
-    for (int idx = tid; idx < kC * D; idx += 256) {
-        const int r = idx / D, d = idx % D;
-        const float G = sG[r * LD + d];
-        const float kk = sK[r * LD + d];
-        const float gam = fast_exp2(G);
-        sQ[r * LD + d] *= gam;
-        sG[r * LD + d] = kk * gam;
-        sK[r * LD + d] = kk * fast_exp2(sGend[d] - G);
+    // the decay-scaled operands for the two scans
+    decay_operands<D>(sQ, sK, sG, sGend, tid);                   // sQ <- Gamma.Q, sG <- Gamma.K, sK <- Gamma^{i->C}.K
+    __syncthreads();
+    float *ops = Ow + slot * (int64_t)operand_floats<D>();
+    for (int idx = tid; idx < kC * D / 4; idx += 256) {
+        const int r = idx / (D / 4), c = 4 * (idx % (D / 4));
+        const float *pq = sQ + r * LD + c, *pg = sG + r * LD + c, *pk = sK + r * LD + c;
+        reinterpret_cast<float4 *>(ops)[idx] = make_float4(pq[0], pq[1], pq[2], pq[3]);
+        reinterpret_cast<float4 *>(ops + kC * D)[idx] = make_float4(pg[0], pg[1], pg[2], pg[3]);
+        reinterpret_cast<float4 *>(ops + 2 * kC * D)[idx] = make_float4(pk[0], pk[1], pk[2], pk[3]);
     }
+    if (tid < D) ops[3 * kC * D + tid] = sGend[tid];
 }
 
 template <int D> constexpr size_t prep_lds_floats() { return 3 * kC * (D + 1) + 2 * kTile + kC + D + 256; }
 
 template <int D> constexpr size_t scan_lds_floats()
 {
-    return 3 * kC * (D + 1) + kC * kLA + 3 * kC * kBV + D * kBV + kC + D + 256;
+    return 3 * kC * (D + 1) + kC * kLA + 3 * kC * kBV + D * kBV + D;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -371,10 +386,9 @@ template <int D> constexpr size_t scan_lds_floats()
 // ------------------------------------------------------------------------------------------
 template <typename Tin, int D>
 __global__ __launch_bounds__(256)
-void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
-                           const Tin *__restrict__ v, const Tin *__restrict__ log_alpha,
-                           const Tin *__restrict__ beta, const float *__restrict__ h0,
+void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ h0,
                            const int32_t *__restrict__ cu, const float *__restrict__ Tw,
+                           const float *__restrict__ Ow,
                            float *__restrict__ Sc, float *__restrict__ Yw, float *__restrict__ Vnw,
                            int64_t T, int H,
                            int64_t chunks_per_seq)
@@ -383,8 +397,8 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;
     float *sV = sA + kC * kLA, *sVn = sV + kC * kBV, *sX = sVn + kC * kBV;
-    float *sS = sX + kC * kBV, *sBeta = sS + D * kBV, *sGend = sBeta + kC, *sTot = sGend + D;
-    (void)sX;
+    float *sS = sX + kC * kBV, *sGend = sS + D * kBV;
+    (void)sX; (void)sQ;
 
     const int n = blockIdx.x, h = blockIdx.y, col0 = blockIdx.z * kBV, tid = threadIdx.x;
     int64_t tok_base, len;
@@ -399,10 +413,10 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     const int64_t nchunks = (len + kC - 1) / kC;
     const int64_t slot_first = chunk_slot(cu, n, chunks_per_seq, 0) * H + h;     // slots of a sequence are H apart
     auto valid_rows = [&](int64_t ci) { return (int)((len - ci * kC < kC) ? (len - ci * kC) : kC); };
-    StepFetch<Tin, Tin, D> nxt;
+    StepFetch<Tin, D, false> nxt;
     if (nchunks > 0)
-        nxt.fetch(q, k, log_alpha, beta, v, Tw + ((slot_first) * 2 + 1) * (int64_t)kTile, tok_base, valid_rows(0),
-                  H, h, col0, tid);
+        nxt.fetch(Ow + slot_first * (int64_t)operand_floats<D>(), v, Tw + (slot_first * 2 + 1) * (int64_t)kTile,
+                  tok_base, valid_rows(0), H, h, col0, tid);
     for (int64_t ci = 0; ci < nchunks; ++ci) {
         const int nv = valid_rows(ci);
         const int64_t tok0 = tok_base + ci * kC;
@@ -412,13 +426,10 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             const int d = idx / kBV, c = idx % kBV;
             Sc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sS[idx];
         }
-        nxt.commit(sQ, sK, sG, sA, sV, sBeta, 1.f, tid);
+        nxt.commit(sQ, sK, sG, sA, sV, sGend, 1.f, tid);
         if (ci + 1 < nchunks)                                    // the next chunk's loads fly during this one's work
-            nxt.fetch(q, k, log_alpha, beta, v, Tw + ((slot + H) * 2 + 1) * (int64_t)kTile, tok0 + kC,
-                      valid_rows(ci + 1), H, h, col0, tid);
-        __syncthreads();
-        cumsum_rows<D>(sG, sTot, sGend, tid);
-        decay_operands<D>(sQ, sK, sG, sGend, tid);
+            nxt.fetch(Ow + (slot + H) * (int64_t)operand_floats<D>(), v, Tw + ((slot + H) * 2 + 1) * (int64_t)kTile,
+                      tok0 + kC, valid_rows(ci + 1), H, h, col0, tid);
         __syncthreads();
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
         const int r0 = 16 * wave;                                // this wave's 16 token rows
@@ -474,9 +485,8 @@ void kda_bwd_states_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
 // ------------------------------------------------------------------------------------------
 template <typename Tin, int D>
 __global__ __launch_bounds__(256)
-void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
-                         const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
-                         const int32_t *__restrict__ cu, const float *__restrict__ Tw,
+void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict__ Tw,
+                         const float *__restrict__ Ow,
                          const float *__restrict__ d_o, const float *__restrict__ d_hT,
                          float *__restrict__ dSc,
                          float *__restrict__ dVnw, float *__restrict__ dv, float *__restrict__ dh0,
@@ -486,7 +496,7 @@ void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;
     float *sdO = sA + kC * kLA, *sdVn = sdO + kC * kBV, *sX = sdVn + kC * kBV;
-    float *sdS = sX + kC * kBV, *sBeta = sdS + D * kBV, *sGend = sBeta + kC, *sTot = sGend + D;
+    float *sdS = sX + kC * kBV, *sGend = sdS + D * kBV;
 
     const int n = blockIdx.x, h = blockIdx.y, col0 = blockIdx.z * kBV, tid = threadIdx.x;
     int64_t tok_base, len;
@@ -501,9 +511,10 @@ void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     const int64_t nchunks = (len + kC - 1) / kC;
     const int64_t slot_first = chunk_slot(cu, n, chunks_per_seq, 0) * H + h;     // slots of a sequence are H apart
     auto valid_rows = [&](int64_t ci) { return (int)((len - ci * kC < kC) ? (len - ci * kC) : kC); };
-    StepFetch<Tin, float, D> nxt;
+    StepFetch<float, D, true> nxt;
     if (nchunks > 0)
-        nxt.fetch(q, k, log_alpha, beta, d_o, Tw + ((slot_first + (nchunks - 1) * H) * 2 + 1) * (int64_t)kTile,
+        nxt.fetch(Ow + (slot_first + (nchunks - 1) * H) * (int64_t)operand_floats<D>(), d_o,
+                  Tw + ((slot_first + (nchunks - 1) * H) * 2 + 1) * (int64_t)kTile,
                   tok_base + (nchunks - 1) * kC, valid_rows(nchunks - 1), H, h, col0, tid);
     for (int64_t ci = nchunks - 1; ci >= 0; --ci) {
         const int nv = valid_rows(ci);
@@ -514,13 +525,10 @@ void kda_bwd_scan_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             const int d = idx / kBV, c = idx % kBV;
             dSc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sdS[idx];
         }
-        nxt.commit(sQ, sK, sG, sA, sdO, sBeta, scale, tid);
+        nxt.commit(sQ, sK, sG, sA, sdO, sGend, scale, tid);
         if (ci > 0)                                              // the next chunk's loads fly during this one's work
-            nxt.fetch(q, k, log_alpha, beta, d_o, Tw + ((slot - H) * 2 + 1) * (int64_t)kTile, tok0 - kC, kC,
-                      H, h, col0, tid);
-        __syncthreads();
-        cumsum_rows<D>(sG, sTot, sGend, tid);
-        decay_operands<D>(sQ, sK, sG, sGend, tid);
+            nxt.fetch(Ow + (slot - H) * (int64_t)operand_floats<D>(), d_o, Tw + ((slot - H) * 2 + 1) * (int64_t)kTile,
+                      tok0 - kC, kC, H, h, col0, tid);
         __syncthreads();
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
         const int r0 = 16 * wave;                                // this wave's 16 token rows
@@ -954,7 +962,7 @@ static kda_status reserve(F kern, size_t lds, const char *name)
 
 struct BwdPlan {
     int64_t chunks_per_seq, max_chunks, nslots, ntok;
-    size_t off_S, off_dS, off_Y, off_Vn, off_dVn, off_gC, off_C, off_T, total;
+    size_t off_S, off_dS, off_Y, off_Vn, off_dVn, off_gC, off_C, off_T, off_O, total;
 };
 
 static BwdPlan bwd_plan(const kda_dims *d, bool packed)
@@ -978,6 +986,7 @@ static BwdPlan bwd_plan(const kda_dims *d, bool packed)
     p.off_gC = at;  at = up(at + (size_t)p.nslots * D * 4);
     p.off_C = at;   at = up(at + (size_t)p.nslots * 2 * kC * kC * 4);
     p.off_T = at;   at = up(at + (size_t)p.nslots * 2 * kTile * 4);
+    p.off_O = at;   at = up(at + (size_t)p.nslots * (3 * kC * D + D) * 4);
     p.total = at;
     return p;
 }
@@ -996,6 +1005,7 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     float *Yw = reinterpret_cast<float *>(ws + p.off_Y), *Vnw = reinterpret_cast<float *>(ws + p.off_Vn);
     float *dVnw = reinterpret_cast<float *>(ws + p.off_dVn), *gC = reinterpret_cast<float *>(ws + p.off_gC);
     float *Cw = reinterpret_cast<float *>(ws + p.off_C), *Tw = reinterpret_cast<float *>(ws + p.off_T);
+    float *Ow = reinterpret_cast<float *>(ws + p.off_O);
 
     const size_t lds_scan = scan_lds_floats<D>() * 4, lds_prod = products_lds_floats<D>() * 4,
                  lds_chain = chain_lds_floats<D>() * 4, lds_prep = prep_lds_floats<D>() * 4;
@@ -1012,11 +1022,11 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     const dim3 gchunk((unsigned)dm->num_seqs, (unsigned)p.max_chunks, (unsigned)H);
     if (p.max_chunks > 0)
         hipLaunchKernelGGL((kda_bwd_prep_kernel<Tin, D>), gchunk, dim3(256), lds_prep, stream, q, k, la, beta, cu,
-                           Tw, T, H, p.chunks_per_seq);
-    hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, q, k, v, la, beta,
-                       h0, cu, Tw, Sc, Yw, Vnw, T, H, p.chunks_per_seq);
-    hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, q, k, la, beta, cu,
-                       Tw, d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
+                           Tw, Ow, T, H, p.chunks_per_seq);
+    hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, v, h0, cu, Tw, Ow,
+                       Sc, Yw, Vnw, T, H, p.chunks_per_seq);
+    hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, cu, Tw, Ow,
+                       d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
     if (p.max_chunks > 0) {
         hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, D>), gchunk, dim3(256), lds_prod, stream, q, k, la, cu,
                            d_o, Sc, dSc, Yw, Vnw, dVnw, dv, dq, dk, dla, gC, Cw, T, H, p.chunks_per_seq,
