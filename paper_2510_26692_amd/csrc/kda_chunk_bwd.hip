@@ -282,33 +282,54 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
 
     for (int idx = tid; idx < 2 * kTile; idx += 256) s0[idx] = 0.f;
     chunk_load<Tin, D>(q, k, log_alpha, beta, tok_base + c0, nv, H, h, sQ, sK, sG, sBeta, sGend, sTot, tid);
-    {   // A_kk, A_qk for i <= r, pairwise in the log domain; a thread takes column token i and four rows at a time
-        const int i = tid & 63, wv = tid >> 6;
-        for (int rb = 0; rb < kC; rb += 16) {
-            const int r_[4] = {rb + wv, rb + wv + 4, rb + wv + 8, rb + wv + 12};
-            float akk[4] = {}, aqk[4] = {};
-            for (int d = 0; d < D; ++d) {
-                const float gi = sG[i * LD + d], ki = sK[i * LD + d];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float t = ki * fast_exp2(fminf(sG[r_[u] * LD + d] - gi, 0.f));
-                    akk[u] = fmaf(sK[r_[u] * LD + d], t, akk[u]);
-                    aqk[u] = fmaf(sQ[r_[u] * LD + d], t, aqk[u]);
-                }
+    auto put = [&](int r, int i, float akk, float aqk) {         // one entry with i <= r into both tiles
+        if (i < r) {                                             // L = StrictTril(Diag(beta) A_kk), kept twice:
+            s0[r * kLA + i] = sBeta[r] * akk;                    // s0 becomes T - I block by block,
+            s1[r * kLA + i] = sBeta[r] * akk;                    // s1 keeps L until M replaces it
+        }
+        s0[i * kLA + r + 1] = akk;
+        s1[i * kLA + r + 1] = aqk;
+    };
+    // A_kk, A_qk in 16-token blocks.  Below the diagonal (row block R > column block I) the decay splits at
+    // the end of block I, E_I = G of its last token:  e^(G_r - G_i) = e^(G_r - E_I) e^(E_I - G_i), both
+    // factors at most 1, so the block is a plain product of two decay-scaled operands: matrix cores,
+    // one exponential per operand element.  Wave w takes the block pairs w, w + 4 of the list below.
+    {
+        const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
+        for (int pair = wave; pair < 6; pair += 4) {
+            const int R = pair < 3 ? pair + 1 : (pair < 5 ? pair - 1 : 3);        // (1,0) (2,0) (3,0) (2,1) (3,1) (3,2)
+            const int I = pair < 3 ? 0 : (pair < 5 ? 1 : 2);
+            const float *gE = sG + (16 * I + 15) * LD;
+            const float *gr = sG + (16 * R + m) * LD, *gi = sG + (16 * I + m) * LD;
+            const float *kr = sK + (16 * R + m) * LD, *qr = sQ + (16 * R + m) * LD, *ki = sK + (16 * I + m) * LD;
+            f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
+            for (int d = g; d < D; d += 4) {
+                const float e = gE[d];
+                const float f = fast_exp2(gr[d] - e), b_ = ki[d] * fast_exp2(e - gi[d]);
+                akk = __builtin_amdgcn_mfma_f32_16x16x4f32(kr[d] * f, b_, akk, 0, 0, 0);
+                aqk = __builtin_amdgcn_mfma_f32_16x16x4f32(qr[d] * f, b_, aqk, 0, 0, 0);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int r = r_[u];
-                if (i <= r) {
-                    if (i < r) {                                  // L = StrictTril(Diag(beta) A_kk), kept twice:
-                        s0[r * kLA + i] = sBeta[r] * akk[u];      // s0 becomes T - I block by block,
-                        s1[r * kLA + i] = sBeta[r] * akk[u];      // s1 keeps L until M replaces it
-                    }
-                    s0[i * kLA + r + 1] = akk[u];
-                    s1[i * kLA + r + 1] = aqk[u];
-                }
+            for (int j = 0; j < 4; ++j) put(16 * R + 4 * g + j, 16 * I + m, akk[j], aqk[j]);
+        }
+    }
+    // The four diagonal blocks pair by pair in the log domain (the decay inside a block may exceed any
+    // factorisation's range): thread (r, i) of all four blocks at once.
+    {
+        const int rl = tid >> 4, il = tid & 15;
+        float akk[4] = {}, aqk[4] = {};
+        for (int d = 0; d < D; ++d) {
+#pragma unroll
+            for (int b4 = 0; b4 < 4; ++b4) {
+                const int r = 16 * b4 + rl, i = 16 * b4 + il;
+                const float t = sK[i * LD + d] * fast_exp2(fminf(sG[r * LD + d] - sG[i * LD + d], 0.f));
+                akk[b4] = fmaf(sK[r * LD + d], t, akk[b4]);
+                aqk[b4] = fmaf(sQ[r * LD + d], t, aqk[b4]);
             }
         }
+#pragma unroll
+        for (int b4 = 0; b4 < 4; ++b4)
+            if (il <= rl) put(16 * b4 + rl, 16 * b4 + il, akk[b4], aqk[b4]);
     }
     __syncthreads();
     // (I + L)^-1 - I in 16 x 16 blocks.  Diagonal blocks: wave w inverts block w, lane m < 16 its column m
