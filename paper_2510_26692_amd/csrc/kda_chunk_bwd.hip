@@ -905,57 +905,114 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     }
     __syncthreads();
 
-    // pairwise decay terms for this thread's channel d and tokens rg + RG j, four tokens at a time
+    // Decay terms, one 16-token block Bk at a time.  With a1[t] = sum_{i<t} dA_kk[t,i] k_i e^(G_t - G_i),
+    // a2[t] the same with dP (i <= t), b1[t] = sum_{r>t} (dA_kk[r,t] k_r + dP[r,t] q_r) e^(G_r - G_t) (r >= t
+    // for dP):  dq_t += a2,  dk_t += a1 + b1,  dG_t += k_t a1 + q_t a2 - k_t b1.  The parts of the sums
+    // that cross a block boundary split the decay at the end E of the earlier block, e^(G_r - G_i) =
+    // e^(G_r - E) e^(E - G_i) with both factors at most 1, and become block products on the matrix
+    // cores (phase M, results staged in the dead T and Z tiles); the parts inside the block stay pair by
+    // pair (phase P), which is also where everything is combined and written.
     const int d = tid % D, rg = tid / D;
     float dgt[kC / RG];
+    float *stA1 = sA, *stA2 = sA + 16 * D, *stB1 = sZ;           // [16][D] each
 #pragma unroll 1
-    for (int j0 = 0; j0 < kC / RG; j0 += 4) {
-        int t_[4];
-        float Gt[4], kt[4], qt[4], a1[4] = {}, a2[4] = {}, b1[4];
+    for (int Bk = 0; Bk < 4; ++Bk) {
+        {   // ---- phase M: wave w takes the channel tiles dt = w, w + 4, ...
+            const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
+            for (int dt = wave; dt < D / 16; dt += 4) {
+                const int dc = 16 * dt + m;                      // this lane's channel as operand / result column
+                f32x4 o1 = {0.f, 0.f, 0.f, 0.f}, o2 = {0.f, 0.f, 0.f, 0.f};
+                for (int I = 0; I < Bk; ++I) {                   // tokens of block Bk as rows, earlier blocks as columns
+                    const float E = sG[(16 * I + 15) * LD + dc];
+                    f32x4 c1 = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            t_[u] = rg + RG * (j0 + u);
-            Gt[u] = sG[t_[u] * LD + d]; kt[u] = sK[t_[u] * LD + d]; qt[u] = sQ[t_[u] * LD + d];
-        }
-        float old_q[4], old_k[4], old_g[4];                      // what kda_bwd_products left: fetched now, used below
+                    for (int ks = 0; ks < 4; ++ks) {
+                        const int i = 16 * I + 4 * ks + g;
+                        const float bv = sK[i * LD + dc] * fast_exp2(E - sG[i * LD + dc]);
+                        c1 = __builtin_amdgcn_mfma_f32_16x16x4f32(sB[(16 * Bk + m) * kLA + i], bv, c1, 0, 0, 0);
+                        c2 = __builtin_amdgcn_mfma_f32_16x16x4f32(sB[i * kLA + 16 * Bk + m + 1], bv, c2, 0, 0, 0);
+                    }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t off = ((tok0 + (t_[u] < nv ? t_[u] : 0)) * H + h) * (int64_t)D + d;
-            old_q[u] = dq[off]; old_k[u] = dk[off]; old_g[u] = dla[off];
+                    for (int j = 0; j < 4; ++j) {
+                        const float f = fast_exp2(sG[(16 * Bk + 4 * g + j) * LD + dc] - E);
+                        o1[j] = fmaf(f, c1[j], o1[j]);
+                        o2[j] = fmaf(f, c2[j], o2[j]);
+                    }
+                }
+                const float E = sG[(16 * Bk + 15) * LD + dc];
+                f32x4 cb = {0.f, 0.f, 0.f, 0.f};
+                for (int R = Bk + 1; R < 4; ++R) {               // tokens of block Bk as columns, later blocks as rows
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        const int r = 16 * R + 4 * ks + g;
+                        const float f = fast_exp2(sG[r * LD + dc] - E);
+                        cb = __builtin_amdgcn_mfma_f32_16x16x4f32(sB[r * kLA + 16 * Bk + m], sK[r * LD + dc] * f, cb, 0, 0, 0);
+                        cb = __builtin_amdgcn_mfma_f32_16x16x4f32(sB[(16 * Bk + m) * kLA + r + 1], sQ[r * LD + dc] * f, cb, 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int tl = 4 * g + j;
+                    stA1[tl * D + dc] = o1[j];
+                    stA2[tl * D + dc] = o2[j];
+                    stB1[tl * D + dc] = cb[j] * fast_exp2(E - sG[(16 * Bk + tl) * LD + dc]);
+                }
+            }
         }
-        for (int i = 0; i < t_[3]; ++i) {                        // the tokens as rows: columns i < t
-            const float gi = sG[i * LD + d], ki = sK[i * LD + d];
+        __syncthreads();
+        // ---- phase P: this thread's channel d and tokens 16 Bk + rg + RG jj, four at a time
+#pragma unroll 1
+        for (int jj0 = 0; jj0 < 16 / RG; jj0 += 4) {
+            int t_[4];
+            float Gt[4], kt[4], qt[4], a1[4], a2[4], b1[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const float kk = i < t_[u] ? ki * fast_exp2(Gt[u] - gi) : 0.f;
-                a1[u] = fmaf(sB[t_[u] * kLA + i], kk, a1[u]);
-                a2[u] = fmaf(sB[i * kLA + t_[u] + 1], kk, a2[u]);
+                const int tl = rg + RG * (jj0 + u);
+                t_[u] = 16 * Bk + tl;
+                Gt[u] = sG[t_[u] * LD + d]; kt[u] = sK[t_[u] * LD + d]; qt[u] = sQ[t_[u] * LD + d];
+                a1[u] = stA1[tl * D + d]; a2[u] = stA2[tl * D + d]; b1[u] = stB1[tl * D + d];
             }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            a2[u] = fmaf(sB[t_[u] * kLA + t_[u] + 1], kt[u], a2[u]);     // dP[t,t]
-            b1[u] = sB[t_[u] * kLA + t_[u] + 1] * qt[u];
-        }
-        for (int r = t_[0] + 1; r < kC; ++r) {                   // the tokens as columns: rows r > t
-            const float gr = sG[r * LD + d], kr = sK[r * LD + d], qr = sQ[r * LD + d];
+            float old_q[4], old_k[4], old_g[4];                  // what kda_bwd_products left: fetched now, used below
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const float e = r > t_[u] ? fast_exp2(gr - Gt[u]) : 0.f;
-                b1[u] = fmaf(fmaf(sB[r * kLA + t_[u]], kr, sB[t_[u] * kLA + r + 1] * qr), e, b1[u]);
+                const int64_t off = ((tok0 + (t_[u] < nv ? t_[u] : 0)) * H + h) * (int64_t)D + d;
+                old_q[u] = dq[off]; old_k[u] = dk[off]; old_g[u] = dla[off];
             }
-        }
+            for (int i = 16 * Bk; i < t_[3]; ++i) {              // the tokens as rows: columns i < t inside the block
+                const float gi = sG[i * LD + d], ki = sK[i * LD + d];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float gsum = 0.f;
-            if (t_[u] < nv) {
-                const int64_t off = ((tok0 + t_[u]) * H + h) * (int64_t)D + d;
-                dq[off] = old_q[u] + a2[u];
-                dk[off] = old_k[u] + a1[u] + b1[u];
-                gsum = old_g[u] + kt[u] * a1[u] + qt[u] * a2[u] - kt[u] * b1[u];
+                for (int u = 0; u < 4; ++u) {
+                    const float kk = i < t_[u] ? ki * fast_exp2(Gt[u] - gi) : 0.f;
+                    a1[u] = fmaf(sB[t_[u] * kLA + i], kk, a1[u]);
+                    a2[u] = fmaf(sB[i * kLA + t_[u] + 1], kk, a2[u]);
+                }
             }
-            dgt[j0 + u] = gsum;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                a2[u] = fmaf(sB[t_[u] * kLA + t_[u] + 1], kt[u], a2[u]);     // dP[t,t]
+                b1[u] = fmaf(sB[t_[u] * kLA + t_[u] + 1], qt[u], b1[u]);
+            }
+            for (int r = t_[0] + 1; r < 16 * Bk + 16; ++r) {     // the tokens as columns: rows r > t inside the block
+                const float gr = sG[r * LD + d], kr = sK[r * LD + d], qr = sQ[r * LD + d];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float e = r > t_[u] ? fast_exp2(gr - Gt[u]) : 0.f;
+                    b1[u] = fmaf(fmaf(sB[r * kLA + t_[u]], kr, sB[t_[u] * kLA + r + 1] * qr), e, b1[u]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float gsum = 0.f;
+                if (t_[u] < nv) {
+                    const int64_t off = ((tok0 + t_[u]) * H + h) * (int64_t)D + d;
+                    dq[off] = old_q[u] + a2[u];
+                    dk[off] = old_k[u] + a1[u] + b1[u];
+                    gsum = old_g[u] + kt[u] * a1[u] + qt[u] * a2[u] - kt[u] * b1[u];
+                }
+                dgt[(16 * Bk) / RG + jj0 + u] = gsum;
+            }
         }
+        __syncthreads();
     }
     __syncthreads();
 #pragma unroll 1
