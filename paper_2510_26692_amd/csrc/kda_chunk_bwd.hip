@@ -839,9 +839,19 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
 
     {   // dM (lower, diagonal included) and dP (stored transposed above the diagonal)
         const float *cP = Cw + slot * (int64_t)(2 * kC * kC), *cM = cP + kC * kC;
-        for (int idx = tid; idx < kC * kC; idx += 256) {
-            const int r = idx >> 6, i = idx & 63;
-            if (i <= r) { sB[r * kLA + i] = cM[idx]; sB[i * kLA + r + 1] = cP[idx]; }
+        BlockFetch<kC * kC / 4> fp, fm;                          // all loads first (entries above the diagonal were
+        fp.fetch(cP, tid);                                       // never written: read, not used)
+        fm.fetch(cM, tid);
+#pragma unroll
+        for (int u = 0; u < kC * kC / 1024; ++u) {
+            const int idx = 4 * (tid + 256 * u), r = idx >> 6, i0 = idx & 63;
+            const float pv[4] = {__uint_as_float(fp.buf[u].x), __uint_as_float(fp.buf[u].y),
+                                 __uint_as_float(fp.buf[u].z), __uint_as_float(fp.buf[u].w)};
+            const float mv[4] = {__uint_as_float(fm.buf[u].x), __uint_as_float(fm.buf[u].y),
+                                 __uint_as_float(fm.buf[u].z), __uint_as_float(fm.buf[u].w)};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (i0 + e <= r) { sB[r * kLA + i0 + e] = mv[e]; sB[(i0 + e) * kLA + r + 1] = pv[e]; }
         }
     }
     load_tile(sA, Tw + slot * 2 * (int64_t)kTile, tid);
