@@ -204,11 +204,31 @@ struct StepFetch {
 // 16 x 16 fp32 matrix-core tile (v_mfma_f32_16x16x4_f32): with m = lane % 16 and g = lane / 16 a lane
 // feeds A[m][k + g] and B[k + g][m] for every step k of four, and holds D[4 g + j][m] in register j.
 // a(k) and b(k) return this lane's operand element for contraction index k (k + g already applied).
+// kend - kbeg is a multiple of 8 everywhere (block boundaries): two steps per iteration, operands first.
 template <typename FA, typename FB>
 __device__ __forceinline__ f32x4 mma16(int kbeg, int kend, int g, f32x4 acc, FA &&a, FB &&b)
 {
-    for (int k = kbeg; k < kend; k += 4) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a(k + g), b(k + g), acc, 0, 0, 0);
+    for (int k = kbeg + g; k < kend; k += 8) {
+        const float a0 = a(k), b0 = b(k), a1 = a(k + 4), b1 = b(k + 4);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, acc, 0, 0, 0);
+    }
     return acc;
+}
+
+// Two result tiles that share the A operand (the two 16-column halves of a 32-column slice):
+// acc[ct] += A B_ct with b(k, ct).
+template <typename FA, typename FB>
+__device__ __forceinline__ void mma16x2(int kbeg, int kend, int g, f32x4 (&acc)[2], FA &&a, FB &&b)
+{
+    for (int k = kbeg + g; k < kend; k += 8) {
+        const float a0 = a(k), b00 = b(k, 0), b01 = b(k, 1);
+        const float a1 = a(k + 4), b10 = b(k + 4, 0), b11 = b(k + 4, 1);
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b00, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b01, acc[1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b10, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b11, acc[1], 0, 0, 0);
+    }
 }
 
 // Loads one chunk.  On return (the last statement is a barrier):
@@ -454,49 +474,47 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
         __syncthreads();
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
         const int r0 = 16 * wave;                                // this wave's 16 token rows
-        f32x4 y[2];
+        f32x4 y[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        mma16x2(0, D, g, y, [&](int k) { return sG[(r0 + m) * LD + k]; },                  // Kg S0
+                [&](int k, int ct) { return sS[k * kBV + 16 * ct + m]; });
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {                         // Y = V - Kg S0
-            const f32x4 acc = mma16(0, D, g, f32x4{0.f, 0.f, 0.f, 0.f},
-                                    [&](int k) { return sG[(r0 + m) * LD + k]; },
-                                    [&](int k) { return sS[k * kBV + 16 * ct + m]; });
+        for (int ct = 0; ct < 2; ++ct)                           // Y = V - Kg S0
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                y[ct][j] = sV[(r0 + 4 * g + j) * kBV + 16 * ct + m] - acc[j];
+                y[ct][j] = sV[(r0 + 4 * g + j) * kBV + 16 * ct + m] - y[ct][j];
                 sV[(r0 + 4 * g + j) * kBV + 16 * ct + m] = y[ct][j];
             }
-        }
         __syncthreads();
+        f32x4 vn[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        mma16x2(0, r0 + 16, g, vn, [&](int k) { return k <= r0 + m ? sA[(r0 + m) * kLA + k] : 0.f; },   // Vn = M Y
+                [&](int k, int ct) { return sV[k * kBV + 16 * ct + m]; });
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {                         // Vn = M Y (M lower triangular)
-            const f32x4 acc = mma16(0, r0 + 16, g, f32x4{0.f, 0.f, 0.f, 0.f},
-                                    [&](int k) { return k <= r0 + m ? sA[(r0 + m) * kLA + k] : 0.f; },
-                                    [&](int k) { return sV[k * kBV + 16 * ct + m]; });
+        for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int r = r0 + 4 * g + j;
-                sVn[r * kBV + 16 * ct + m] = acc[j];
+                sVn[r * kBV + 16 * ct + m] = vn[ct][j];
                 if (r < nv) {
                     const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + col0 + 16 * ct + m;
                     Yw[off] = y[ct][j];
-                    Vnw[off] = acc[j];
+                    Vnw[off] = vn[ct][j];
                 }
             }
-        }
         __syncthreads();
         for (int rt = wave * (D / 64); rt < (wave + 1) * (D / 64); ++rt) {       // S1 = Diag(e^G_C) S0 + Kt^T Vn
             const int d0 = 16 * rt;
+            f32x4 acc[2];
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
-                f32x4 acc;
+            for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[j] = sS[(d0 + 4 * g + j) * kBV + 16 * ct + m] * fast_exp2(sGend[d0 + 4 * g + j]);
-                acc = mma16(0, kC, g, acc, [&](int k) { return sK[k * LD + d0 + m]; },
-                            [&](int k) { return sVn[k * kBV + 16 * ct + m]; });
+                    acc[ct][j] = sS[(d0 + 4 * g + j) * kBV + 16 * ct + m] * fast_exp2(sGend[d0 + 4 * g + j]);
+            mma16x2(0, kC, g, acc, [&](int k) { return sK[k * LD + d0 + m]; },
+                    [&](int k, int ct) { return sVn[k * kBV + 16 * ct + m]; });
 #pragma unroll
-                for (int j = 0; j < 4; ++j) sS[(d0 + 4 * g + j) * kBV + 16 * ct + m] = acc[j];
-            }
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sS[(d0 + 4 * g + j) * kBV + 16 * ct + m] = acc[ct][j];
         }
     }
 }
@@ -553,50 +571,48 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
         __syncthreads();
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
         const int r0 = 16 * wave;                                // this wave's 16 token rows
+        f32x4 dvn[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};     // dVn = Kt dS1 + P^T dO (P lower triangular)
+        mma16x2(0, D, g, dvn, [&](int k) { return sK[(r0 + m) * LD + k]; },
+                [&](int k, int ct) { return sdS[k * kBV + 16 * ct + m]; });
+        mma16x2(r0, kC, g, dvn, [&](int k) { return k >= r0 + m ? sA[(r0 + m) * kLA + k + 1] : 0.f; },   // P[k][r0 + m]
+                [&](int k, int ct) { return sdO[k * kBV + 16 * ct + m]; });
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {                         // dVn = Kt dS1 + P^T dO (P lower triangular)
-            f32x4 acc = mma16(0, D, g, f32x4{0.f, 0.f, 0.f, 0.f},
-                              [&](int k) { return sK[(r0 + m) * LD + k]; },
-                              [&](int k) { return sdS[k * kBV + 16 * ct + m]; });
-            acc = mma16(r0, kC, g, acc,
-                        [&](int k) { return k >= r0 + m ? sA[(r0 + m) * kLA + k + 1] : 0.f; },   // P[k][r0 + m]
-                        [&](int k) { return sdO[k * kBV + 16 * ct + m]; });
+        for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = r0 + 4 * g + j;
-                sdVn[i * kBV + 16 * ct + m] = acc[j];
-                if (i < nv) dVnw[((tok0 + i) * H + h) * (int64_t)D + col0 + 16 * ct + m] = acc[j];
+                sdVn[i * kBV + 16 * ct + m] = dvn[ct][j];
+                if (i < nv) dVnw[((tok0 + i) * H + h) * (int64_t)D + col0 + 16 * ct + m] = dvn[ct][j];
             }
-        }
         __syncthreads();
+        f32x4 xx[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};      // X = M^T dVn = dV
+        mma16x2(r0, kC, g, xx, [&](int k) { return k >= r0 + m ? sA[k * kLA + r0 + m] : 0.f; },         // M[k][r0 + m]
+                [&](int k, int ct) { return sdVn[k * kBV + 16 * ct + m]; });
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {                         // X = M^T dVn = dV
-            const f32x4 acc = mma16(r0, kC, g, f32x4{0.f, 0.f, 0.f, 0.f},
-                                    [&](int k) { return k >= r0 + m ? sA[k * kLA + r0 + m] : 0.f; },   // M[k][r0 + m]
-                                    [&](int k) { return sdVn[k * kBV + 16 * ct + m]; });
+        for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = r0 + 4 * g + j;
-                sX[i * kBV + 16 * ct + m] = acc[j];
-                if (i < nv) dv[((tok0 + i) * H + h) * (int64_t)D + col0 + 16 * ct + m] = acc[j];
+                sX[i * kBV + 16 * ct + m] = xx[ct][j];
+                if (i < nv) dv[((tok0 + i) * H + h) * (int64_t)D + col0 + 16 * ct + m] = xx[ct][j];
             }
-        }
         __syncthreads();
         for (int rt = wave * (D / 64); rt < (wave + 1) * (D / 64); ++rt) {       // dS0
             const int d0 = 16 * rt;
+            f32x4 acc[2];
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
-                f32x4 acc;
+            for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[j] = sdS[(d0 + 4 * g + j) * kBV + 16 * ct + m] * fast_exp2(sGend[d0 + 4 * g + j]);
-                acc = mma16(0, kC, g, acc, [&](int k) { return sQ[k * LD + d0 + m]; },
-                            [&](int k) { return sdO[k * kBV + 16 * ct + m]; });
-                acc = mma16(0, kC, g, acc, [&](int k) { return -sG[k * LD + d0 + m]; },
-                            [&](int k) { return sX[k * kBV + 16 * ct + m]; });
+                    acc[ct][j] = sdS[(d0 + 4 * g + j) * kBV + 16 * ct + m] * fast_exp2(sGend[d0 + 4 * g + j]);
+            mma16x2(0, kC, g, acc, [&](int k) { return sQ[k * LD + d0 + m]; },
+                    [&](int k, int ct) { return sdO[k * kBV + 16 * ct + m]; });
+            mma16x2(0, kC, g, acc, [&](int k) { return -sG[k * LD + d0 + m]; },
+                    [&](int k, int ct) { return sX[k * kBV + 16 * ct + m]; });
 #pragma unroll
-                for (int j = 0; j < 4; ++j) sdS[(d0 + 4 * g + j) * kBV + 16 * ct + m] = acc[j];
-            }
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sdS[(d0 + 4 * g + j) * kBV + 16 * ct + m] = acc[ct][j];
         }
     }
     if (dh0) {
