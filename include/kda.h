@@ -15,23 +15,32 @@
  *   - All tensor pointers are DEVICE pointers to contiguous row-major arrays,
  *     16-byte aligned.  The caller owns every buffer, including the workspace;
  *     the library allocates no device memory and frees none.  The only state
- *     it keeps is a helper stream with two events per device and host thread,
- *     created by the first bf16 kda_chunk_fwd call that uses them.
+ *     it keeps is a pair of helper streams with four events per device (and up
+ *     to seven idle streams that were tried for the pair), created by the first
+ *     bf16 kda_chunk_fwd call that uses them; that one call synchronises with the
+ *     two new streams once, to check that they run at the same time.
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
- *     NULL = default stream); no host synchronisation happens inside.  Work
- *     that a call puts on the helper stream is ordered after everything queued
+ *     NULL = default stream); no host synchronisation happens inside (but see
+ *     the first call, above).  Work
+ *     that a call puts on the helper streams is ordered after everything queued
  *     on `hip_stream` before the call, and `hip_stream` waits for it before
  *     the call's work counts as complete: to the caller the call behaves as if
  *     everything ran on `hip_stream`.
  *   - Concurrency: calls may be issued from several host threads and on several
  *     streams at once, each with its own workspace (a workspace belongs to one call
- *     until that call has completed).  A bf16 kda_chunk_fwd keeps one compute unit per
- *     (sequence, head) waiting on its producer kernel (up to three eighths of the
- *     device with few pairs), so calls in flight together whose pairs add up to more
- *     than the device has compute units can starve their producers: the waits give up
- *     after about two seconds and kda_chunk_fwd_check reports it.  Run such workloads
- *     with kda_debug_set_overlap(0) (or KDA_PREFILL_OVERLAP=0), which keeps every call
- *     free of waits.
+ *     until that call has completed).  A bf16 kda_chunk_fwd whose two kernels run side
+ *     by side makes one of them wait for the other, and a hardware queue runs its
+ *     kernels in order (a process has few hardware queues for all its streams).  Such
+ *     calls therefore put both kernels on a pair of library streams per device, shared
+ *     by all host threads and checked, when they are created, to run at the same time;
+ *     the calls follow each other there in the order they were issued, so no kernel
+ *     ever waits for one that is queued behind a waiting kernel, whatever streams the
+ *     callers use.  Such a call keeps one compute unit per (sequence, head) waiting on
+ *     its producer kernel (up to three eighths of the device), which other work in
+ *     flight on the device has to live beside; should the producer be starved for about
+ *     two seconds the waiting kernel gives up and kda_chunk_fwd_check reports it.
+ *     kda_debug_set_overlap(0) (or KDA_PREFILL_OVERLAP=0 in the environment) keeps every
+ *     call on the caller's stream and free of waits.
  *   - Element offsets are 64-bit; tensors with more than 2^31 elements are fine.
  *   - Errors: a non-zero kda_status is returned and kda_last_error() holds a
  *     thread-local description.  For KDA_ERR_INVALID_ARG, KDA_ERR_UNSUPPORTED

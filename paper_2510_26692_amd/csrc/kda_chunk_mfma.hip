@@ -38,6 +38,8 @@
 #include <stdlib.h>
 #include <type_traits>
 
+#include <mutex>
+
 #include "kda_common.h"
 #include "kda_mfma_layout.h"
 
@@ -1658,13 +1660,51 @@ static bool reserve_lds()
     return ok;
 }
 
-// Helper stream and events of the overlapped mode, created on first use, one set per device
-// and host thread, never destroyed.
+// Helper streams and events of the overlapped mode, created on first use, one set per device, never
+// destroyed.  Both kernels of an overlapped call run on library streams (kda_scan on `scan`,
+// kda_intra on `intra`) that were seen to run at the same time when they were created; the caller's
+// stream only carries the events around them, so its own hardware queue does not matter.
 struct SideStream {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipStream_t stream = nullptr;           // kda_intra
+    hipStream_t scan_stream = nullptr;      // kda_scan
+    hipEvent_t fork = nullptr, fork_intra = nullptr, join = nullptr, join_scan = nullptr;
     bool tried = false, ok = false;
 };
+
+// A hardware queue runs its kernels in order and a process has few of them for all its streams:
+// two streams on one queue never overlap.  The probe: a one-thread kernel on `a` polls a device word,
+// for a few milliseconds at most, that a kernel on `b` sets.
+__device__ uint32_t g_probe_word[2];        // [0] the word, [1] what the polling kernel saw
+
+__global__ void kda_probe_reset_kernel() { g_probe_word[0] = 0u; g_probe_word[1] = 0u; }
+
+__global__ void kda_probe_set_kernel() { __hip_atomic_store(&g_probe_word[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+__global__ void kda_probe_poll_kernel()
+{
+    uint32_t seen = 0u;
+    for (int it = 0; it < 4000 && !seen; ++it) {            // bounded: about 4 ms
+        seen = __hip_atomic_load(&g_probe_word[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_sleep(32);
+    }
+    g_probe_word[1] = seen;
+}
+
+static bool streams_run_together(hipStream_t a, hipStream_t b)
+{
+    uint32_t seen = 0u;
+    hipLaunchKernelGGL(kda_probe_reset_kernel, dim3(1), dim3(1), 0, a);
+    if (hipStreamSynchronize(a) != hipSuccess) { (void)hipGetLastError(); return false; }
+    hipLaunchKernelGGL(kda_probe_poll_kernel, dim3(1), dim3(1), 0, a);
+    hipLaunchKernelGGL(kda_probe_set_kernel, dim3(1), dim3(1), 0, b);
+    if (hipStreamSynchronize(b) != hipSuccess || hipStreamSynchronize(a) != hipSuccess ||
+        hipMemcpyFromSymbol(&seen, HIP_SYMBOL(g_probe_word), sizeof(seen), sizeof(uint32_t),
+                            hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return seen == 1u;
+}
 
 // Compute units of the current device (cached per device), 0 on failure.
 static int compute_units()
@@ -1681,18 +1721,44 @@ static int compute_units()
     return table[dev];
 }
 
-static SideStream *side_stream()
+// All overlapped calls of a process share one pair of helper streams per device, and a mutex keeps
+// each call's launches together: every kda_scan sits behind the earlier ones on one stream, every
+// kda_intra behind the earlier ones on the other, in the same order, so the kda_intra a kda_scan
+// waits for only has kernels in front of it that wait for nothing.
+struct OverlapGate {
+    std::mutex mu;
+    SideStream side;                        // guarded by mu
+};
+
+static OverlapGate *overlap_gate()
 {
     constexpr int kMaxDevices = 64;
-    static thread_local SideStream table[kMaxDevices];
+    static OverlapGate table[kMaxDevices];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-    SideStream *s = &table[dev];
+    return &table[dev];
+}
+
+// Called with the gate's mutex held.  The first call on a device synchronises with the helper
+// streams (the probe above): not under stream capture, where the overlapped mode is off anyway.
+static SideStream *side_stream(OverlapGate *gate)
+{
+    SideStream *s = &gate->side;
     if (!s->tried) {
         s->tried = true;
-        s->ok = hipStreamCreateWithFlags(&s->stream, hipStreamNonBlocking) == hipSuccess &&
-                hipEventCreateWithFlags(&s->fork, hipEventDisableTiming) == hipSuccess &&
-                hipEventCreateWithFlags(&s->join, hipEventDisableTiming) == hipSuccess;
+        bool ok = hipStreamCreateWithFlags(&s->scan_stream, hipStreamNonBlocking) == hipSuccess &&
+                  hipEventCreateWithFlags(&s->fork, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&s->fork_intra, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&s->join, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&s->join_scan, hipEventDisableTiming) == hipSuccess;
+        // candidates that share the scan stream's queue are kept alive, so that the runtime hands
+        // the next one another queue
+        for (int attempt = 0; ok && attempt < 8 && !s->stream; ++attempt) {
+            hipStream_t cand = nullptr;
+            if (hipStreamCreateWithFlags(&cand, hipStreamNonBlocking) != hipSuccess) break;
+            if (streams_run_together(s->scan_stream, cand)) s->stream = cand;
+        }
+        s->ok = ok && s->stream != nullptr;
         (void)hipGetLastError();
     }
     return s->ok ? s : nullptr;
@@ -1795,10 +1861,32 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     if (hipStreamIsCapturing(stream, &capture) != hipSuccess) { capture = hipStreamCaptureStatusNone; (void)hipGetLastError(); }
     const int cus = compute_units();
     if (cus <= 0) return fail(KDA_ERR_LAUNCH, "cannot query the device");
-    if (g_phase_mask == 3 && g_overlap && capture == hipStreamCaptureStatusNone) {
-        side = side_stream();
-        if (side && (int64_t)streams * 3 > (int64_t)cus) side = nullptr;
+    OverlapGate *gate = nullptr;
+    std::unique_lock<std::mutex> gate_lock;
+    if (g_phase_mask == 3 && g_overlap && capture == hipStreamCaptureStatusNone &&
+        (int64_t)streams * 3 <= (int64_t)cus && (gate = overlap_gate()) != nullptr) {
+        gate_lock = std::unique_lock<std::mutex>(gate->mu);              // held until this call is queued
+        side = side_stream(gate);
+        if (!side) gate_lock.unlock();
     }
+    // kda_scan's stream: the library's in the overlapped mode, else the caller's
+    hipStream_t scan_stream = side ? side->scan_stream : stream;
+    // Both helper streams behind everything queued on the caller's stream -- kda_intra's through
+    // kda_scan's: its release then reaches it a little after kda_scan has been handed to the device,
+    // so kda_scan's workgroups, which need a whole compute unit each, are placed first (if the 4 096
+    // half-unit workgroups of kda_intra fill the device first, kda_scan starts when they are nearly through).
+    auto fork = [&]() {
+        return hipEventRecord(side->fork, stream) == hipSuccess &&
+               hipStreamWaitEvent(side->scan_stream, side->fork, 0) == hipSuccess &&
+               hipEventRecord(side->fork_intra, side->scan_stream) == hipSuccess &&
+               hipStreamWaitEvent(side->stream, side->fork_intra, 0) == hipSuccess;
+    };
+    auto join = [&]() {                      // the caller's stream behind both helper streams
+        return hipEventRecord(side->join, side->stream) == hipSuccess &&
+               hipEventRecord(side->join_scan, side->scan_stream) == hipSuccess &&
+               hipStreamWaitEvent(stream, side->join, 0) == hipSuccess &&
+               hipStreamWaitEvent(stream, side->join_scan, 0) == hipSuccess;
+    };
     double first_ratio = 1.0;
     const int parts = (g_phase_mask == 3 && g_split) ? split_parts(plan, d, cus, g_split, &first_ratio) : 1;
 
@@ -1834,24 +1922,22 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                 hipLaunchKernelGGL(kda_fill_u32_kernel, dim3((unsigned)(kSplitFlagBytes / 4 / 256)), dim3(256), 0, stream,
                                    split_flags, (int64_t)(kSplitFlagBytes / 4), 0u, split_flags);
             if (side) {
-                if (hipEventRecord(side->fork, stream) != hipSuccess ||
-                    hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
-                    return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
+                if (!fork())
+                    return fail(KDA_ERR_LAUNCH, "cannot order the helper streams: %s", hipGetErrorString(hipGetLastError()));
             } else {
                 hipLaunchKernelGGL(intra, intra_grid_serial, dim3(256), kIntraLds, stream, q16, k16, v16, g16, b16, cu, ws,
                                    (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale,
                                    (uint32_t *)nullptr, 0u, raw, 1, 0, 0, ep.gate, gate_ws);
             }
-            hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, stream, ws, sin, E,
+            hipLaunchKernelGGL(split_k, dim3(streams, (unsigned)(2 * parts - 3)), dim3(512), scan_lds, scan_stream, ws, sin, E,
                                Tm, Bm, sout, cu, o, (int64_t)d->seqlen, (int)d->heads,
                                plan.seg_chunks, seg, part_len, part0_len, parts, flags, epoch, status, split_flags, ep);
             if (side) {
                 hipLaunchKernelGGL(intra, intra_grid_split, dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
                                    (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw,
                                    parts, (int)part_len, (int)part0_len, ep.gate, gate_ws);
-                if (hipEventRecord(side->join, side->stream) != hipSuccess ||
-                    hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
-                    return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
+                if (!join())
+                    return fail(KDA_ERR_LAUNCH, "cannot join the helper streams: %s", hipGetErrorString(hipGetLastError()));
             }
         }
         hipError_t e = hipGetLastError();
@@ -1865,20 +1951,18 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
             // kda_intra of this segment may start once everything queued so far on the caller's
             // stream (the inputs' producers, the flag reset, the previous segment's scan) is done
             const uint32_t epoch = (uint32_t)(seg + 1);
-            if (hipEventRecord(side->fork, stream) != hipSuccess ||
-                hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
-                return fail(KDA_ERR_LAUNCH, "cannot order the helper stream: %s", hipGetErrorString(hipGetLastError()));
+            if (!fork())
+                return fail(KDA_ERR_LAUNCH, "cannot order the helper streams: %s", hipGetErrorString(hipGetLastError()));
             auto scan_k = epi ? kda_scan_kernel<true, true> : kda_scan_kernel<true, false>;
-            hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, stream, ws, sin, sout, cu,
+            hipLaunchKernelGGL(scan_k, dim3(streams), dim3(512), scan_lds, scan_stream, ws, sin, sout, cu,
                                o, (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg,
                                flags, epoch, status, ep);
             auto intra = pick_intra(true);
             hipLaunchKernelGGL(intra, intra_grid_overlap,
                                dim3(256), kIntraLds, side->stream, q16, k16, v16, g16, b16, cu, ws,
                                (int64_t)d->seqlen, (int)d->heads, plan.seg_chunks, seg, d->scale, flags, epoch, raw, 1, 0, 0, ep.gate, gate_ws);
-            if (hipEventRecord(side->join, side->stream) != hipSuccess ||
-                hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
-                return fail(KDA_ERR_LAUNCH, "cannot join the helper stream: %s", hipGetErrorString(hipGetLastError()));
+            if (!join())
+                return fail(KDA_ERR_LAUNCH, "cannot join the helper streams: %s", hipGetErrorString(hipGetLastError()));
         } else {
             auto intra = pick_intra(false);
             if (g_phase_mask & 1)

@@ -112,8 +112,8 @@ def test_chunk_bwd_workspace_size_and_rejections_without_launching():
     chunks = d.num_seqs * ((d.seqlen + C - 1) // C) * d.heads
     tokens = d.batch * d.seqlen * d.heads
     need = kda.kda_chunk_bwd_workspace_size(d)
-    floats = chunks * (2 * D * D + D + 2 * C * C + 2 * C * (C + 2)) + 3 * tokens * D
-    assert 0 <= need - 4 * floats < 7 * 256              # seven areas, each rounded up to 256 bytes
+    floats = chunks * (2 * D * D + D + 2 * C * C + 2 * C * (C + 2) + 3 * C * D + D) + 3 * tokens * D
+    assert 0 <= need - 4 * floats < 9 * 256              # nine areas, each rounded up to 256 bytes
     assert kda.kda_chunk_bwd_workspace_size(_dims(kda, dk=96, dv=96)) == 0
     p = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(16)]
 
