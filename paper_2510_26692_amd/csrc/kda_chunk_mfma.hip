@@ -1690,6 +1690,28 @@ __global__ void kda_probe_poll_kernel()
     g_probe_word[1] = seen;
 }
 
+// The same question for a caller's stream against the kda_intra stream, asked without waiting for
+// the caller's stream: the polling kernel goes onto the caller's stream first, then the setting one
+// onto the helper stream (on a shared queue the second cannot run before the first has finished),
+// the answer is copied to pinned host memory behind the polling kernel and read by a later call.
+constexpr int kCallerSlots = 16;
+__device__ uint32_t g_caller_probe[kCallerSlots][2];    // [slot][0] the word, [1] what the polling kernel saw
+
+__global__ void kda_caller_set_kernel(int slot, uint32_t token)
+{
+    __hip_atomic_store(&g_caller_probe[slot][0], token, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ void kda_caller_poll_kernel(int slot, uint32_t token)
+{
+    uint32_t seen = 0u;
+    for (int it = 0; it < 4000 && seen != token; ++it) {    // bounded: about 4 ms
+        seen = __hip_atomic_load(&g_caller_probe[slot][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_sleep(32);
+    }
+    g_caller_probe[slot][1] = seen;
+}
+
 static bool streams_run_together(hipStream_t a, hipStream_t b)
 {
     uint32_t seen = 0u;
@@ -1725,10 +1747,66 @@ static int compute_units()
 // each call's launches together: every kda_scan sits behind the earlier ones on one stream, every
 // kda_intra behind the earlier ones on the other, in the same order, so the kda_intra a kda_scan
 // waits for only has kernels in front of it that wait for nothing.
-struct OverlapGate {
-    std::mutex mu;
-    SideStream side;                        // guarded by mu
+struct CallerStream {                       // what is known about one caller's stream handle
+    hipStream_t handle = nullptr;
+    int state = 0;                          // 0 free, 1 asked, 2 runs beside the kda_intra stream, 3 does not
+    uint32_t token = 0;
+    hipEvent_t answered = nullptr;
 };
+
+struct OverlapGate {
+    std::mutex mu;                          // guards everything below
+    SideStream side;
+    CallerStream callers[kCallerSlots];
+    uint32_t *answers = nullptr;            // pinned host memory, one word per slot
+    uint32_t *probe_words = nullptr;        // device address of g_caller_probe
+    uint32_t next_token = 1;
+    bool tried = false, ok = false;
+    // the last overlapped call: which caller's stream it came down (side.join tells when its kda_intra is over)
+    hipStream_t last_stream = nullptr;
+    bool last_recorded = false;
+};
+
+// Called with the mutex held.  May the caller's stream itself carry kda_scan (no hop through a helper
+// stream in front of it)?  Only once a probe has shown that it runs beside the kda_intra stream;
+// the first calls on a stream answer no and start the probe.
+static bool caller_runs_beside_intra(OverlapGate *g, hipStream_t stream)
+{
+    if (!g->tried) {
+        g->tried = true;
+        void *dev_words = nullptr;
+        g->ok = hipHostMalloc(reinterpret_cast<void **>(&g->answers), kCallerSlots * sizeof(uint32_t), hipHostMallocDefault) == hipSuccess &&
+                hipGetSymbolAddress(&dev_words, HIP_SYMBOL(g_caller_probe)) == hipSuccess;
+        g->probe_words = static_cast<uint32_t *>(dev_words);
+        (void)hipGetLastError();
+    }
+    if (!g->ok) return false;
+    CallerStream *free_slot = nullptr;
+    for (CallerStream &c : g->callers) {
+        if (c.state == 0) { if (!free_slot) free_slot = &c; continue; }
+        if (c.handle != stream) continue;
+        if (c.state == 1 && hipEventQuery(c.answered) == hipSuccess)
+            c.state = (g->answers[&c - g->callers] == c.token) ? 2 : 3;
+        (void)hipGetLastError();
+        return c.state == 2;
+    }
+    if (!free_slot) return false;                            // table full: such streams keep the helper pair
+    CallerStream &c = *free_slot;
+    const int slot = (int)(&c - g->callers);
+    if (!c.answered && hipEventCreateWithFlags(&c.answered, hipEventDisableTiming) != hipSuccess) {
+        c.answered = nullptr; (void)hipGetLastError(); return false;
+    }
+    c.handle = stream;
+    c.token = g->next_token++;
+    hipLaunchKernelGGL(kda_caller_poll_kernel, dim3(1), dim3(1), 0, stream, slot, c.token);
+    hipLaunchKernelGGL(kda_caller_set_kernel, dim3(1), dim3(1), 0, g->side.stream, slot, c.token);
+    const bool queued = hipMemcpyAsync(&g->answers[slot], g->probe_words + 2 * slot + 1, sizeof(uint32_t),
+                                       hipMemcpyDeviceToHost, stream) == hipSuccess &&
+                        hipEventRecord(c.answered, stream) == hipSuccess;
+    c.state = queued ? 1 : 3;
+    (void)hipGetLastError();
+    return false;
+}
 
 static OverlapGate *overlap_gate()
 {
@@ -1863,25 +1941,47 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     if (cus <= 0) return fail(KDA_ERR_LAUNCH, "cannot query the device");
     OverlapGate *gate = nullptr;
     std::unique_lock<std::mutex> gate_lock;
+    bool direct = false;
     if (g_phase_mask == 3 && g_overlap && capture == hipStreamCaptureStatusNone &&
         (int64_t)streams * 3 <= (int64_t)cus && (gate = overlap_gate()) != nullptr) {
         gate_lock = std::unique_lock<std::mutex>(gate->mu);              // held until this call is queued
         side = side_stream(gate);
+        // One overlapped call at a time unless they come down the same caller's stream: each keeps a
+        // compute unit per (sequence, head) waiting, and several of them together could leave their
+        // producers none.
+        // (the last one counts as over once its kda_intra is: its kda_scan then waits for nothing more)
+        if (side && gate->last_recorded && gate->last_stream != stream) {
+            if (hipEventQuery(side->join) != hipSuccess) side = nullptr;
+            (void)hipGetLastError();
+        }
+        if (side) direct = caller_runs_beside_intra(gate, stream);
         if (!side) gate_lock.unlock();
     }
-    // kda_scan's stream: the library's in the overlapped mode, else the caller's
-    hipStream_t scan_stream = side ? side->scan_stream : stream;
+    // kda_scan's stream: the caller's own if it is known to run beside the kda_intra stream (and
+    // when nothing overlaps), else the library's
+    hipStream_t scan_stream = (side && !direct) ? side->scan_stream : stream;
+    auto close_gate = [&]() {                // remember whose overlapped call is in flight
+        if (!side) return;
+        gate->last_recorded = true;
+        gate->last_stream = stream;
+    };
     // Both helper streams behind everything queued on the caller's stream -- kda_intra's through
     // kda_scan's: its release then reaches it a little after kda_scan has been handed to the device,
     // so kda_scan's workgroups, which need a whole compute unit each, are placed first (if the 4 096
     // half-unit workgroups of kda_intra fill the device first, kda_scan starts when they are nearly through).
     auto fork = [&]() {
+        if (direct)                              // kda_scan follows on the caller's stream itself
+            return hipEventRecord(side->fork, stream) == hipSuccess &&
+                   hipStreamWaitEvent(side->stream, side->fork, 0) == hipSuccess;
         return hipEventRecord(side->fork, stream) == hipSuccess &&
                hipStreamWaitEvent(side->scan_stream, side->fork, 0) == hipSuccess &&
                hipEventRecord(side->fork_intra, side->scan_stream) == hipSuccess &&
                hipStreamWaitEvent(side->stream, side->fork_intra, 0) == hipSuccess;
     };
-    auto join = [&]() {                      // the caller's stream behind both helper streams
+    auto join = [&]() {                      // the caller's stream behind the helper streams
+        if (direct)
+            return hipEventRecord(side->join, side->stream) == hipSuccess &&
+                   hipStreamWaitEvent(stream, side->join, 0) == hipSuccess;
         return hipEventRecord(side->join, side->stream) == hipSuccess &&
                hipEventRecord(side->join_scan, side->scan_stream) == hipSuccess &&
                hipStreamWaitEvent(stream, side->join, 0) == hipSuccess &&
@@ -1940,6 +2040,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                     return fail(KDA_ERR_LAUNCH, "cannot join the helper streams: %s", hipGetErrorString(hipGetLastError()));
             }
         }
+        close_gate();
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));
         return KDA_OK;
@@ -1976,6 +2077,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
                                    (const uint32_t *)nullptr, 0u, status, ep);
         }
     }
+    close_gate();
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "prefill kernels: %s", hipGetErrorString(e));
     return KDA_OK;
