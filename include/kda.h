@@ -15,8 +15,9 @@
  *   - All tensor pointers are DEVICE pointers to contiguous row-major arrays,
  *     16-byte aligned.  The caller owns every buffer, including the workspace;
  *     the library allocates no device memory and frees none.  The only state
- *     it keeps is a pair of helper streams with four events per device (and up
- *     to seven idle streams that were tried for the pair), created by the first
+ *     it keeps is a pair of helper streams with four events per device (up to
+ *     seven idle streams that were tried for the pair, 64 bytes of pinned host
+ *     memory and one event per caller stream seen, 16 at most), created by the first
  *     bf16 kda_chunk_fwd call that uses them; that one call synchronises with the
  *     two new streams once, to check that they run at the same time.
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
@@ -33,9 +34,16 @@
  *     kernels in order (a process has few hardware queues for all its streams).  Such
  *     calls therefore put both kernels on a pair of library streams per device, shared
  *     by all host threads and checked, when they are created, to run at the same time;
- *     the calls follow each other there in the order they were issued, so no kernel
- *     ever waits for one that is queued behind a waiting kernel, whatever streams the
- *     callers use.  Such a call keeps one compute unit per (sequence, head) waiting on
+ *     the producer kernels follow each other on one of them in the order the calls were
+ *     issued, and nothing on that stream ever waits.  The waiting kernel moves to the
+ *     caller's own stream (which saves two event hops) once a probe that the library
+ *     queues on that stream, without waiting for it, has shown that the stream runs
+ *     beside the producers' stream.  Calls that come down different streams run side
+ *     by side one at a time: while another stream's call is still producing, a call
+ *     runs its kernels one after the other.  So no kernel ever waits for one that is
+ *     queued behind a waiting kernel, whatever streams the callers use (a stream
+ *     handle that is destroyed and re-created with the same value keeps the old
+ *     answer of the probe).  Such a call keeps one compute unit per (sequence, head) waiting on
  *     its producer kernel (up to three eighths of the device), which other work in
  *     flight on the device has to live beside; should the producer be starved for about
  *     two seconds the waiting kernel gives up and kda_chunk_fwd_check reports it.
