@@ -316,6 +316,31 @@ def test_bf16_two_host_threads_on_their_own_streams():
         assert torch.equal(results[i][0], alone[i][0]) and torch.equal(results[i][1], alone[i][1])
 
 
+def test_bf16_many_caller_streams():
+    """One host thread, 20 different streams in turn (more than the hardware has queues, and more than
+    the library remembers), three calls on each without waiting in between: whichever stream of its
+    own the library pairs a caller's stream with, every result equals the default stream's bit for bit
+    and no wait gives up."""
+    import paper_2510_26692_amd as kda
+    x = si.make_prefill(2, 64 * 12 + 5, 4, 128, 128, "bf16", -2.0, 511, 0.02)
+    d = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+    ref = kda.kda_chunk_fwd(d["q"], d["k"], d["v"], d["log_alpha"], d["beta"], h0=d["h0"], check=True)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(20)]
+    dims = kda.kda.make_chunk_dims(d["q"], d["v"], None, 1.0, 0, torch.float32)
+    outs = []
+    for rep in range(3):
+        for st in streams:
+            with torch.cuda.stream(st):
+                ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
+                o, hT = kda.kda_chunk_fwd(d["q"], d["k"], d["v"], d["log_alpha"], d["beta"], h0=d["h0"], workspace=ws)
+                outs.append((o, hT, ws))
+    torch.cuda.synchronize()
+    for o, hT, ws in outs:
+        kda.kda_chunk_fwd_check(dims, ws)
+        assert torch.equal(o, ref[0]) and torch.equal(hT, ref[1])
+
+
 @pytest.mark.parametrize("with_h0", [True, False])
 def test_bf16_zero_tokens_returns_the_initial_state(with_h0):
     import paper_2510_26692_amd as kda
