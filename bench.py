@@ -27,6 +27,8 @@ MFMA_PEAK_TFLOPS = 2500.0          # dense fp16/bf16 matrix cores
 # scaled by what the same counters read for a 1 GiB copy.  Counter collection serialises kernels, so the
 # prefill figure is that of the two kernels run one after the other (both summed).
 MEASURED_TRAFFIC_BYTES = {"cfg1_prefill_bf16": 1007.3e6, "cfg4_decode_bf16": 1086.6e6}
+# the same for the five kernels of one backward call on the cfg1 shape (profiles/pmc_traffic_bench_backward_cfg1.txt)
+MEASURED_BACKWARD_TRAFFIC_BYTES = 6146.5e6
 
 # Algorithmic work per (token, head) at d_k = d_v = 128, C = 64.
 FLOP_PER_TOKHEAD = 6 * 128 * 128 + 3 * 64 * 128 + 64 * 64        # paper's FLOPs model: 126976

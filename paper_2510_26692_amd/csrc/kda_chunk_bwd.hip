@@ -494,13 +494,13 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
             for (int j = 0; j < 4; ++j) {
                 const int r = r0 + 4 * g + j;
                 sVn[r * kBV + 16 * ct + m] = vn[ct][j];
-                if (r < nv) {
-                    const int64_t off = ((tok0 + r) * H + h) * (int64_t)D + col0 + 16 * ct + m;
-                    Yw[off] = y[ct][j];
-                    Vnw[off] = vn[ct][j];
-                }
             }
         __syncthreads();
+        for (int idx = tid; idx < nv * kBV; idx += 256) {        // whole 128-byte rows of the slice at a time
+            const int64_t off = ((tok0 + idx / kBV) * H + h) * (int64_t)D + col0 + idx % kBV;
+            Yw[off] = sV[idx];
+            Vnw[off] = sVn[idx];
+        }
         for (int rt = wave * (D / 64); rt < (wave + 1) * (D / 64); ++rt) {       // S1 = Diag(e^G_C) S0 + Kt^T Vn
             const int d0 = 16 * rt;
             f32x4 acc[2];
@@ -582,9 +582,10 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
             for (int j = 0; j < 4; ++j) {
                 const int i = r0 + 4 * g + j;
                 sdVn[i * kBV + 16 * ct + m] = dvn[ct][j];
-                if (i < nv) dVnw[((tok0 + i) * H + h) * (int64_t)D + col0 + 16 * ct + m] = dvn[ct][j];
             }
         __syncthreads();
+        for (int idx = tid; idx < nv * kBV; idx += 256)          // whole 128-byte rows of the slice at a time
+            dVnw[((tok0 + idx / kBV) * H + h) * (int64_t)D + col0 + idx % kBV] = sdVn[idx];
         f32x4 xx[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};      // X = M^T dVn = dV
         mma16x2(r0, kC, g, xx, [&](int k) { return k >= r0 + m ? sA[k * kLA + r0 + m] : 0.f; },         // M[k][r0 + m]
                 [&](int k, int ct) { return sdVn[k * kBV + 16 * ct + m]; });
@@ -594,9 +595,10 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
             for (int j = 0; j < 4; ++j) {
                 const int i = r0 + 4 * g + j;
                 sX[i * kBV + 16 * ct + m] = xx[ct][j];
-                if (i < nv) dv[((tok0 + i) * H + h) * (int64_t)D + col0 + 16 * ct + m] = xx[ct][j];
             }
         __syncthreads();
+        for (int idx = tid; idx < nv * kBV; idx += 256)
+            dv[((tok0 + idx / kBV) * H + h) * (int64_t)D + col0 + idx % kBV] = sX[idx];
         for (int rt = wave * (D / 64); rt < (wave + 1) * (D / 64); ++rt) {       // dS0
             const int d0 = 16 * rt;
             f32x4 acc[2];
