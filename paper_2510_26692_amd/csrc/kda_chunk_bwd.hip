@@ -78,18 +78,18 @@ __device__ __forceinline__ void unpack16(const uint4 &w, const __hip_bfloat16 *,
 
 // ROWS x W block of Tin (rows `stride` elements apart, 16-byte aligned): fetch() issues the loads
 // (rows r >= nv read as zero), commit() writes dst[r * ld + c] = mul * x.  ROWS * W * sizeof(Tin) / 16
-// must be a multiple of 256.  Keeping the two apart lets a loop fetch its next block before it works
-// on the current one.
-template <typename Tin, int ROWS, int W>
+// must be a multiple of the NT threads that take part.  Keeping the two apart lets a loop fetch its next
+// block before it works on the current one.
+template <typename Tin, int ROWS, int W, int NT = 256>
 struct RowsFetch {
-    static constexpr int EPV = 16 / (int)sizeof(Tin), VPR = W / EPV, NV = ROWS * VPR / 256;
-    static_assert(ROWS * VPR % 256 == 0, "block size");
+    static constexpr int EPV = 16 / (int)sizeof(Tin), VPR = W / EPV, NV = ROWS * VPR / NT;
+    static_assert(ROWS * VPR % NT == 0, "block size");
     uint4 buf[NV];
     __device__ __forceinline__ void fetch(const Tin *__restrict__ src, int64_t stride, int nv, int tid)
     {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int vi = tid + 256 * u, r = vi / VPR, cv = vi % VPR;
+            const int vi = tid + NT * u, r = vi / VPR, cv = vi % VPR;
             buf[u] = make_uint4(0u, 0u, 0u, 0u);
             if (r < nv) buf[u] = *reinterpret_cast<const uint4 *>(src + r * stride + cv * EPV);
         }
@@ -98,7 +98,7 @@ struct RowsFetch {
     {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int vi = tid + 256 * u, r = vi / VPR, cv = vi % VPR;
+            const int vi = tid + NT * u, r = vi / VPR, cv = vi % VPR;
             float f[EPV];
             unpack16(buf[u], (const Tin *)nullptr, f);
 #pragma unroll
@@ -107,31 +107,31 @@ struct RowsFetch {
     }
 };
 
-template <typename Tin, int ROWS, int W>
+template <typename Tin, int ROWS, int W, int NT = 256>
 __device__ __forceinline__ void rows_to_lds(float *dst, int ld, const Tin *__restrict__ src, int64_t stride,
                                             int nv, float mul, int tid)
 {
-    RowsFetch<Tin, ROWS, W> f;
+    RowsFetch<Tin, ROWS, W, NT> f;
     f.fetch(src, stride, nv, tid);
     f.commit(dst, ld, mul, tid);
 }
 
 // N4 contiguous 16-byte words, global -> LDS (both 16-byte aligned).
-template <int N4>
+template <int N4, int NT = 256>
 struct BlockFetch {
-    static constexpr int NV = (N4 + 255) / 256;
+    static constexpr int NV = (N4 + NT - 1) / NT;
     uint4 buf[NV];
     __device__ __forceinline__ void fetch(const float *__restrict__ src, int tid)
     {
 #pragma unroll
         for (int u = 0; u < NV; ++u)
-            if (tid + 256 * u < N4) buf[u] = reinterpret_cast<const uint4 *>(src)[tid + 256 * u];
+            if (tid + NT * u < N4) buf[u] = reinterpret_cast<const uint4 *>(src)[tid + NT * u];
     }
     __device__ __forceinline__ void commit(float *dst, int tid) const
     {
 #pragma unroll
         for (int u = 0; u < NV; ++u)
-            if (tid + 256 * u < N4) reinterpret_cast<uint4 *>(dst)[tid + 256 * u] = buf[u];
+            if (tid + NT * u < N4) reinterpret_cast<uint4 *>(dst)[tid + NT * u] = buf[u];
     }
 };
 
@@ -143,13 +143,13 @@ __device__ __forceinline__ void copy_to_lds(float *dst, const float *__restrict_
     f.commit(dst, tid);
 }
 
-// In place: sG[r][d] <- sum over rows <= r, all 256 threads (256 / D row groups per channel, prefix
-// in registers, the groups' totals through sTot [256 / D][D]); sGend[d] = last row.  Ends with a barrier;
+// In place: sG[r][d] <- sum over rows <= r, all NT threads (NT / D row groups per channel, prefix
+// in registers, the groups' totals through sTot [NT / D][D]); sGend[d] = last row.  Ends with a barrier;
 // the caller has one before.
-template <int D>
+template <int D, int NT = 256>
 __device__ __forceinline__ void cumsum_rows(float *sG, float *sTot, float *sGend, int tid)
 {
-    constexpr int LD = D + 1, RG = 256 / D, RPT = kC / RG;
+    constexpr int LD = D + 1, RG = NT / D, RPT = kC / RG;
     const int d = tid % D, rg = tid / D;
     float g[RPT];
 #pragma unroll
@@ -629,9 +629,11 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
 // ------------------------------------------------------------------------------------------
 // Per chunk: products with S0 and dS1, and the two C x C products.
 // ------------------------------------------------------------------------------------------
+constexpr int kProductsThreads = 512;
+
 template <int D> constexpr size_t products_lds_floats()
 {
-    return (size_t)(D > 2 * kC ? D : 2 * kC) * (D + 1) + 2 * kC * (D + 1) + 2 * D + (256 / D) * D;
+    return (size_t)(D > 2 * kC ? D : 2 * kC) * (D + 1) + 2 * kC * (D + 1) + 2 * D + kProductsThreads;
 }
 
 
@@ -653,22 +655,24 @@ __device__ __forceinline__ f32x16 tile_rows_times_rows(const float *sRow, const 
     return acc;
 }
 
-// out[r][d] = sum_c sOp[r][c] * sS[d][c] for all 64 rows and D columns: wave w owns the tiles
-// t = w, w + 4, ... of the (64 / 32) x (D / 32) grid (D / 64 of them, numbered ti), column block
+// out[r][d] = sum_c sOp[r][c] * sS[d][c] for all 64 rows and D columns: wave w of NT / 64 owns the
+// tiles t = w, w + NT / 64, ... of the (64 / 32) x (D / 32) grid (numbered ti), column block
 // t % (D / 32) -- so a lane sees one column d all along -- and hands every element to
 // sink(ti, j, r, d, value), j the accumulator register.
-template <int D, typename Sink>
+template <int D, int NT, typename Sink>
 __device__ __forceinline__ void times_state_t(const float *sOp, const float *sS, int tid, Sink &&sink)
 {
-    constexpr int LD = D + 1, NB = D / 32;
+    constexpr int LD = D + 1, NB = D / 32, NW = NT / 64, TPW = (2 * NB + NW - 1) / NW;
     const int wave = tid >> 6, lane = tid & 63, hh = lane >> 5;
 #pragma unroll
-    for (int ti = 0; ti < D / 64; ++ti) {
-        const int t = wave + 4 * ti;
-        const int d0 = 32 * (t % NB), r0 = 32 * (t / NB);
-        const f32x16 acc = tile_rows_times_rows<D>(sOp + r0 * LD, sS + d0 * LD, LD, lane);
+    for (int ti = 0; ti < TPW; ++ti) {
+        const int t = wave + NW * ti;
+        if (t < 2 * NB) {
+            const int d0 = 32 * (t % NB), r0 = 32 * (t / NB);
+            const f32x16 acc = tile_rows_times_rows<D>(sOp + r0 * LD, sS + d0 * LD, LD, lane);
 #pragma unroll
-        for (int j = 0; j < 16; ++j) sink(ti, j, r0 + acc_row32(j, hh), d0 + (lane & 31), acc[j]);
+            for (int j = 0; j < 16; ++j) sink(ti, j, r0 + acc_row32(j, hh), d0 + (lane & 31), acc[j]);
+        }
     }
 }
 
@@ -691,7 +695,7 @@ __device__ __forceinline__ void lower_product(const float *sR, const float *sI, 
 }
 
 template <typename Tin, int D>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(kProductsThreads)
 void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                              const Tin *__restrict__ log_alpha, const int32_t *__restrict__ cu,
                              const float *__restrict__ d_o, const float *__restrict__ Sc,
@@ -701,7 +705,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
                              float *__restrict__ dk, float *__restrict__ dg, float *__restrict__ dgC,
                              float *__restrict__ Cw, int64_t T, int H, int64_t chunks_per_seq, float scale)
 {
-    constexpr int LD = D + 1, RG = 256 / D;
+    constexpr int LD = D + 1, NT = kProductsThreads, RG = NT / D, NB = D / 32, NW = NT / 64;
     extern __shared__ float smem[];
     float *sS = smem;                       // [D][LD] S0, later dS1; later two [C][LD] operand tiles
     float *sOp = sS + (D > 2 * kC ? D : 2 * kC) * LD;   // [C][LD] row operand
@@ -724,24 +728,25 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     const float *dS1 = dSc + slot * (int64_t)(D * D);
     const int64_t base = (tok0 * H + h) * (int64_t)D, stride = (int64_t)H * D;
     auto load_rows = [&](float *dst, const float *src, float mul) {      // [C][D] token rows -> LDS
-        rows_to_lds<float, kC, D>(dst, LD, src + base, stride, nv, mul, tid);
+        rows_to_lds<float, kC, D, NT>(dst, LD, src + base, stride, nv, mul, tid);
     };
     auto load_state = [&](const float *src) {
-        rows_to_lds<float, D / 2, D>(sS, LD, src, D, D, 1.f, tid);
-        rows_to_lds<float, D / 2, D>(sS + (D / 2) * LD, LD, src + (D / 2) * D, D, D, 1.f, tid);
+        rows_to_lds<float, D / 2, D, NT>(sS, LD, src, D, D, 1.f, tid);
+        rows_to_lds<float, D / 2, D, NT>(sS + (D / 2) * LD, LD, src + (D / 2) * D, D, D, 1.f, tid);
     };
 
-    rows_to_lds<Tin, kC, D>(sG, LD, log_alpha + base, stride, nv, kLog2e, tid);
+    rows_to_lds<Tin, kC, D, NT>(sG, LD, log_alpha + base, stride, nv, kLog2e, tid);
     load_state(S0);
     load_rows(sOp, d_o, scale);
     __syncthreads();
-    cumsum_rows<D>(sG, sPart, sGend, tid);
+    cumsum_rows<D, NT>(sG, sPart, sGend, tid);
 
     // The three products below land on the same elements of every lane, so dq, dk and dG stay in
     // registers until all three are in and are written once.
-    f32x16 gq[D / 64], gk[D / 64], gg[D / 64], kv[D / 64];
+    constexpr int TPW = (2 * NB + NW - 1) / NW;               // result tiles per wave
+    f32x16 gq[TPW], gk[TPW], gg[TPW], kv[TPW];
     // dQg = dO S0^T:  dq = Gamma . dQg,  dG = dQg . Gamma . q
-    times_state_t<D>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
+    times_state_t<D, NT>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
         const int64_t off = ((tok0 + (r < nv ? r : 0)) * H + h) * (int64_t)D + d;
         const float t = acc * fast_exp2(sG[r * LD + d]);         // rows past nv: dO is zero there, so is t
         gq[ti][j] = t;
@@ -752,22 +757,22 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     load_rows(sOp, dv, 1.f);                                             // X
     __syncthreads();
     // dKg = -X S0^T:  dk = Gamma . dKg,  dG += dKg . Gamma . k
-    times_state_t<D>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
+    times_state_t<D, NT>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
         const float t = -acc * fast_exp2(sG[r * LD + d]);
         gk[ti][j] = t;
         gg[ti][j] = fmaf(t, kv[ti][j], gg[ti][j]);
     });
     __syncthreads();
     // dG_C (first part) = e^(G_C) . rowsum(dS1 . S0)
-    constexpr int kBatch = D * D / 1024 < 8 ? D * D / 1024 : 8;        // 16-byte loads in flight per thread
+    constexpr int kBatch = D * D / 4 / NT < 8 ? D * D / 4 / NT : 8;     // 16-byte loads in flight per thread
 #pragma unroll 1
-    for (int part = 0; part < D * D / 4; part += 256 * kBatch) {
+    for (int part = 0; part < D * D / 4; part += NT * kBatch) {
         uint4 buf[kBatch];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) buf[u] = reinterpret_cast<const uint4 *>(dS1)[part + tid + 256 * u];
+        for (int u = 0; u < kBatch; ++u) buf[u] = reinterpret_cast<const uint4 *>(dS1)[part + tid + NT * u];
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
-            const int idx = 4 * (part + tid + 256 * u);
+            const int idx = 4 * (part + tid + NT * u);
             float *p = sS + (idx / D) * LD + idx % D;
             p[0] *= __uint_as_float(buf[u].x); p[1] *= __uint_as_float(buf[u].y);
             p[2] *= __uint_as_float(buf[u].z); p[3] *= __uint_as_float(buf[u].w);
@@ -785,7 +790,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     __syncthreads();
     // dKt = Vn dS1^T:  dk += e^(G_C - G) . dKt,  dG -= dKt . Kt,  dG_C += sum_t dKt . Kt
     float gc_part = 0.f;
-    times_state_t<D>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
+    times_state_t<D, NT>(sOp, sS, tid, [&](int ti, int j, int r, int d, float acc) {
         const float t = acc * fast_exp2(sGend[d] - sG[r * LD + d]);
         const float tk = t * kv[ti][j];                          // rows past nv: Vn and k are zero there
         gc_part += tk;
@@ -796,9 +801,9 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
             dg[off] = gg[ti][j] - tk;
         }
     });
-    {   // a lane's elements all sit in column 32 (wave % (D / 32)) + lane % 32; 256 / D lanes share a column
+    {   // a lane's elements all sit in column 32 (wave % NB) + lane % 32; NT / D lanes share a column
         const int wave = tid >> 6, lane = tid & 63;
-        sPart[((lane >> 5) + 2 * (wave / (D / 32))) * D + 32 * (wave % (D / 32)) + (lane & 31)] = gc_part;
+        sPart[((lane >> 5) + 2 * (wave / NB)) * D + 32 * (wave % NB) + (lane & 31)] = gc_part;
     }
     __syncthreads();
     if (tid < D) {
@@ -1134,7 +1139,7 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, cu, Tw, Ow,
                        d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
     if (p.max_chunks > 0) {
-        hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, D>), gchunk, dim3(256), lds_prod, stream, q, k, la, cu,
+        hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, D>), gchunk, dim3(kProductsThreads), lds_prod, stream, q, k, la, cu,
                            d_o, Sc, dSc, Yw, Vnw, dVnw, dv, dq, dk, dla, gC, Cw, T, H, p.chunks_per_seq,
                            dm->scale);
         hipLaunchKernelGGL((kda_bwd_chain_kernel<Tin, D>), gchunk, dim3(256), lds_chain, stream, q, k, la, beta,
