@@ -763,20 +763,18 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
         gg[ti][j] = fmaf(t, kv[ti][j], gg[ti][j]);
     });
     __syncthreads();
-    // dG_C (first part) = e^(G_C) . rowsum(dS1 . S0)
-    constexpr int kBatch = D * D / 4 / NT < 8 ? D * D / 4 / NT : 8;     // 16-byte loads in flight per thread
-#pragma unroll 1
-    for (int part = 0; part < D * D / 4; part += NT * kBatch) {
-        uint4 buf[kBatch];
+    // dG_C (first part) = e^(G_C) . rowsum(dS1 . S0); dS1 is fetched once, multiplied into the S0 tile for
+    // the row sums and kept in registers until it replaces that tile
+    constexpr int kWords = D * D / 4 / NT;                               // 16-byte words of dS1 per thread
+    uint4 ds[kWords];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) buf[u] = reinterpret_cast<const uint4 *>(dS1)[part + tid + NT * u];
+    for (int u = 0; u < kWords; ++u) ds[u] = reinterpret_cast<const uint4 *>(dS1)[tid + NT * u];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int idx = 4 * (part + tid + NT * u);
-            float *p = sS + (idx / D) * LD + idx % D;
-            p[0] *= __uint_as_float(buf[u].x); p[1] *= __uint_as_float(buf[u].y);
-            p[2] *= __uint_as_float(buf[u].z); p[3] *= __uint_as_float(buf[u].w);
-        }
+    for (int u = 0; u < kWords; ++u) {
+        const int idx = 4 * (tid + NT * u);
+        float *p = sS + (idx / D) * LD + idx % D;
+        p[0] *= __uint_as_float(ds[u].x); p[1] *= __uint_as_float(ds[u].y);
+        p[2] *= __uint_as_float(ds[u].z); p[3] *= __uint_as_float(ds[u].w);
     }
     __syncthreads();
     if (tid < D) {
@@ -784,9 +782,15 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
         for (int c = 0; c < D; ++c) acc += sS[tid * LD + c];
         sgc[tid] = acc * fast_exp2(sGend[tid]);
     }
-    __syncthreads();
-    load_state(dS1);
     load_rows(sOp, Vnw, 1.f);
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kWords; ++u) {
+        const int idx = 4 * (tid + NT * u);
+        float *p = sS + (idx / D) * LD + idx % D;
+        p[0] = __uint_as_float(ds[u].x); p[1] = __uint_as_float(ds[u].y);
+        p[2] = __uint_as_float(ds[u].z); p[3] = __uint_as_float(ds[u].w);
+    }
     __syncthreads();
     // dKt = Vn dS1^T:  dk += e^(G_C - G) . dKt,  dG -= dKt . Kt,  dG_C += sum_t dKt . Kt
     float gc_part = 0.f;
