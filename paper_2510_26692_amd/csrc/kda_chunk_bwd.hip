@@ -417,9 +417,14 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
 
 template <int D> constexpr size_t prep_lds_floats() { return 3 * kC * (D + 1) + 2 * kTile + kC + D + 256; }
 
-template <int D> constexpr size_t scan_lds_floats()
+template <int D> constexpr size_t scan_lds_floats()          // kda_bwd_scan
 {
     return 3 * kC * (D + 1) + kC * kLA + 3 * kC * kBV + D * kBV + D;
+}
+
+template <int D> constexpr size_t states_lds_floats()        // kda_bwd_states
+{
+    return 2 * kC * (D + 1) + kC * kLA + 2 * kC * kBV + D * kBV + D;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -436,10 +441,9 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
 {
     constexpr int LD = D + 1;
     extern __shared__ float smem[];
-    float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;
-    float *sV = sA + kC * kLA, *sVn = sV + kC * kBV, *sX = sVn + kC * kBV;
-    float *sS = sX + kC * kBV, *sGend = sS + D * kBV;
-    (void)sX; (void)sQ;
+    float *sK = smem, *sG = sK + kC * LD, *sA = sG + kC * LD;        // Gamma^{i->C}.K, Gamma.K, M | A_qk
+    float *sV = sA + kC * kLA, *sVn = sV + kC * kBV;                 // V slice -> Y, V_new
+    float *sS = sVn + kC * kBV, *sGend = sS + D * kBV;               // state slice, G_C
 
     const int n = blockIdx.x, h = blockIdx.y, col0 = blockIdx.z * kBV, tid = threadIdx.x;
     int64_t tok_base, len;
@@ -467,7 +471,7 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
             const int d = idx / kBV, c = idx % kBV;
             Sc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sS[idx];
         }
-        nxt.commit(sQ, sK, sG, sA, sV, sGend, 1.f, tid);
+        nxt.commit(nullptr, sK, sG, sA, sV, sGend, 1.f, tid);
         if (ci + 1 < nchunks)                                    // the next chunk's loads fly during this one's work
             nxt.fetch(Ow + (slot + H) * (int64_t)operand_floats<D>(), v, Tw + ((slot + H) * 2 + 1) * (int64_t)kTile,
                       tok0 + kC, valid_rows(ci + 1), H, h, col0, tid);
@@ -1122,11 +1126,12 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     float *Cw = reinterpret_cast<float *>(ws + p.off_C), *Tw = reinterpret_cast<float *>(ws + p.off_T);
     float *Ow = reinterpret_cast<float *>(ws + p.off_O);
 
-    const size_t lds_scan = scan_lds_floats<D>() * 4, lds_prod = products_lds_floats<D>() * 4,
+    const size_t lds_scan = scan_lds_floats<D>() * 4, lds_states = states_lds_floats<D>() * 4,
+                 lds_prod = products_lds_floats<D>() * 4,
                  lds_chain = chain_lds_floats<D>() * 4, lds_prep = prep_lds_floats<D>() * 4;
     kda_status st;
     if ((st = reserve(kda_bwd_prep_kernel<Tin, D>, lds_prep, "kda_bwd_prep")) != KDA_OK) return st;
-    if ((st = reserve(kda_bwd_states_kernel<Tin, D>, lds_scan, "kda_bwd_states")) != KDA_OK) return st;
+    if ((st = reserve(kda_bwd_states_kernel<Tin, D>, lds_states, "kda_bwd_states")) != KDA_OK) return st;
     if ((st = reserve(kda_bwd_scan_kernel<Tin, D>, lds_scan, "kda_bwd_scan")) != KDA_OK) return st;
     if ((st = reserve(kda_bwd_products_kernel<Tin, D>, lds_prod, "kda_bwd_products")) != KDA_OK) return st;
     if ((st = reserve(kda_bwd_chain_kernel<Tin, D>, lds_chain, "kda_bwd_chain")) != KDA_OK) return st;
@@ -1138,7 +1143,7 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     if (p.max_chunks > 0)
         hipLaunchKernelGGL((kda_bwd_prep_kernel<Tin, D>), gchunk, dim3(256), lds_prep, stream, q, k, la, beta, cu,
                            Tw, Ow, T, H, p.chunks_per_seq);
-    hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, v, h0, cu, Tw, Ow,
+    hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(256), lds_states, stream, v, h0, cu, Tw, Ow,
                        Sc, Yw, Vnw, T, H, p.chunks_per_seq);
     hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, cu, Tw, Ow,
                        d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
