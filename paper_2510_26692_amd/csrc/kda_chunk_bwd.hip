@@ -234,8 +234,8 @@ __device__ __forceinline__ void mma16x2(int kbeg, int kend, int g, f32x4 (&acc)[
 // Loads one chunk.  On return (the last statement is a barrier):
 //   sQ, sK [C][D+1]  q and k as given (zero rows past nv)
 //   sG     [C][D+1]  G in log2 units (rows past nv repeat the last valid row)
-//   sBeta [C] (zero past nv), sGend [D] (G of the last row); sTot [256] is scratch
-template <typename Tin, int D>
+//   sBeta [C] (zero past nv), sGend [D] (G of the last row); sTot [NT] is scratch
+template <typename Tin, int D, int NT = 256>
 __device__ void chunk_load(const Tin *__restrict__ q, const Tin *__restrict__ k,
                            const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
                            int64_t tok0, int nv, int H, int h, float *sQ, float *sK, float *sG,
@@ -243,12 +243,12 @@ __device__ void chunk_load(const Tin *__restrict__ q, const Tin *__restrict__ k,
 {
     constexpr int LD = D + 1;
     const int64_t base = (tok0 * H + h) * (int64_t)D, stride = (int64_t)H * D;
-    rows_to_lds<Tin, kC, D>(sQ, LD, q + base, stride, nv, 1.f, tid);
-    rows_to_lds<Tin, kC, D>(sK, LD, k + base, stride, nv, 1.f, tid);
-    rows_to_lds<Tin, kC, D>(sG, LD, log_alpha + base, stride, nv, kLog2e, tid);
+    rows_to_lds<Tin, kC, D, NT>(sQ, LD, q + base, stride, nv, 1.f, tid);
+    rows_to_lds<Tin, kC, D, NT>(sK, LD, k + base, stride, nv, 1.f, tid);
+    rows_to_lds<Tin, kC, D, NT>(sG, LD, log_alpha + base, stride, nv, kLog2e, tid);
     if (tid < kC) sBeta[tid] = (tid < nv) ? load_as_float(beta + (tok0 + tid) * H + h) : 0.f;
     __syncthreads();
-    cumsum_rows<D>(sG, sTot, sGend, tid);
+    cumsum_rows<D, NT>(sG, sTot, sGend, tid);
 }
 
 // q, k, G tiles -> Gamma.Q, Gamma^{i->C}.K, Gamma.K (in sQ, sK, sG), as the forward kernel does.
@@ -272,9 +272,12 @@ __device__ void decay_operands(float *sQ, float *sK, float *sG, const float *sGe
 //   tile 0   strict lower part [r][i]: T - I          upper part [i][r+1], i <= r: A_kk[r][i]
 //   tile 1   lower part with diagonal [r][j]: M = T Diag(beta)    upper part [i][r+1]: A_qk[r][i]
 
+template <int NT = 256>
 __device__ __forceinline__ void load_tile(float *dst, const float *__restrict__ src, int tid)
 {
-    copy_to_lds<kTile / 4>(dst, src, tid);
+    BlockFetch<kTile / 4, NT> f;
+    f.fetch(src, tid);
+    f.commit(dst, tid);
 }
 
 template <typename Tin, int D>
@@ -834,13 +837,15 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
 // ------------------------------------------------------------------------------------------
 // Per chunk: gradient through T, pairwise decay terms, dlog_alpha, dbeta.
 // ------------------------------------------------------------------------------------------
+constexpr int kChainThreads = 512;
+
 template <int D> constexpr size_t chain_lds_floats()
 {
-    return 3 * kC * (D + 1) + 3 * kC * kLA + 2 * kC + D + 256;
+    return 3 * kC * (D + 1) + 3 * kC * kLA + 2 * kC + D + kChainThreads;
 }
 
 template <typename Tin, int D>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(kChainThreads)
 void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                           const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
                           const int32_t *__restrict__ cu, const float *__restrict__ Tw,
@@ -849,7 +854,8 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                           float *__restrict__ dk, float *__restrict__ dla, float *__restrict__ dbeta,
                           int64_t T, int H, int64_t chunks_per_seq)
 {
-    constexpr int LD = D + 1, RG = 256 / D;
+    constexpr int LD = D + 1, NT = kChainThreads, NW = NT / 64, RG = NT / D;
+    constexpr int TG = 16 / RG < 4 ? 16 / RG : 4;           // tokens a thread takes together in the pairwise phase
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD;
     float *sA = sG + kC * LD;               // T - I (strict lower), A_kk (upper, transposed)
@@ -870,12 +876,12 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
 
     {   // dM (lower, diagonal included) and dP (stored transposed above the diagonal)
         const float *cP = Cw + slot * (int64_t)(2 * kC * kC), *cM = cP + kC * kC;
-        BlockFetch<kC * kC / 4> fp, fm;                          // all loads first (entries above the diagonal were
+        BlockFetch<kC * kC / 4, NT> fp, fm;                         // all loads first (entries above the diagonal were
         fp.fetch(cP, tid);                                       // never written: read, not used)
         fm.fetch(cM, tid);
 #pragma unroll
-        for (int u = 0; u < kC * kC / 1024; ++u) {
-            const int idx = 4 * (tid + 256 * u), r = idx >> 6, i0 = idx & 63;
+        for (int u = 0; u < kC * kC / 4 / NT; ++u) {
+            const int idx = 4 * (tid + NT * u), r = idx >> 6, i0 = idx & 63;
             const float pv[4] = {__uint_as_float(fp.buf[u].x), __uint_as_float(fp.buf[u].y),
                                  __uint_as_float(fp.buf[u].z), __uint_as_float(fp.buf[u].w)};
             const float mv[4] = {__uint_as_float(fm.buf[u].x), __uint_as_float(fm.buf[u].y),
@@ -885,8 +891,8 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                 if (i0 + e <= r) { sB[r * kLA + i0 + e] = mv[e]; sB[(i0 + e) * kLA + r + 1] = pv[e]; }
         }
     }
-    load_tile(sA, Tw + slot * 2 * (int64_t)kTile, tid);
-    chunk_load<Tin, D>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, sTot, tid);
+    load_tile<NT>(sA, Tw + slot * 2 * (int64_t)kTile, tid);
+    chunk_load<Tin, D, NT>(q, k, log_alpha, beta, tok0, nv, H, h, sQ, sK, sG, sBeta, sGend, sTot, tid);
 
     auto Tm = [&](int r, int j) { return r == j ? 1.f : sA[r * kLA + j]; };   // r >= j
 
@@ -898,36 +904,38 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     }
     __syncthreads();
     // dT = dM Diag(beta)
-    for (int idx = tid; idx < kC * kC; idx += 256) {
+    for (int idx = tid; idx < kC * kC; idx += NT) {
         const int r = idx >> 6, j = idx & 63;
         if (j <= r) sB[r * kLA + j] *= sBeta[j];
     }
     __syncthreads();
-    // Z[a,i] = sum_{b <= min(a,i)} dT[a,b] T[i,b]: wave w takes the 16 rows a of block w
+    // Z[a,i] = sum_{b <= min(a,i)} dT[a,b] T[i,b]: the 16 tiles of 16 x 16 spread over the waves
     {
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
-        const int a = 16 * wave + m;
-        for (int Ib = 0; Ib < 4; ++Ib) {
-            const int i = 16 * Ib + m;
-            const f32x4 acc = mma16(0, 16 * ((wave < Ib ? wave : Ib) + 1), g, f32x4{0.f, 0.f, 0.f, 0.f},
+        for (int tile = wave; tile < 16; tile += NW) {
+            const int Ab = tile & 3, Ib = tile >> 2;
+            const int a = 16 * Ab + m, i = 16 * Ib + m;
+            const f32x4 acc = mma16(0, 16 * ((Ab < Ib ? Ab : Ib) + 1), g, f32x4{0.f, 0.f, 0.f, 0.f},
                                     [&](int b_) { return b_ <= a ? sB[a * kLA + b_] : 0.f; },
                                     [&](int b_) { return b_ < i ? sA[i * kLA + b_] : (b_ == i ? 1.f : 0.f); });
 #pragma unroll
-            for (int j = 0; j < 4; ++j) sZ[(16 * wave + 4 * g + j) * kLA + 16 * Ib + m] = acc[j];
+            for (int j = 0; j < 4; ++j) sZ[(16 * Ab + 4 * g + j) * kLA + 16 * Ib + m] = acc[j];
         }
     }
     __syncthreads();
     // dL[r,i] = -sum_{a>=r} T[a,r] Z[a,i]  (i < r), then dbeta_r += sum_i dL A_kk, dA_kk = beta_r dL
     {
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
-        const int r = 16 * wave + m;
-        for (int Ib = 0; Ib <= wave; ++Ib) {
-            const f32x4 acc = mma16(16 * wave, kC, g, f32x4{0.f, 0.f, 0.f, 0.f},
+        for (int tile = wave; tile < 16; tile += NW) {
+            const int Rb = tile & 3, Ib = tile >> 2;
+            if (Ib > Rb) continue;
+            const int r = 16 * Rb + m;
+            const f32x4 acc = mma16(16 * Rb, kC, g, f32x4{0.f, 0.f, 0.f, 0.f},
                                     [&](int a_) { return a_ > r ? sA[a_ * kLA + r] : (a_ == r ? 1.f : 0.f); },
                                     [&](int a_) { return sZ[a_ * kLA + 16 * Ib + m]; });
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int rr = 16 * wave + 4 * g + j, ii = 16 * Ib + m;
+                const int rr = 16 * Rb + 4 * g + j, ii = 16 * Ib + m;
                 if (ii < rr) sB[rr * kLA + ii] = -acc[j];
             }
         }
@@ -940,7 +948,7 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
         if (r < nv) dbeta[(tok0 + r) * H + h] = acc;
     }
     __syncthreads();
-    for (int idx = tid; idx < kC * kC; idx += 256) {
+    for (int idx = tid; idx < kC * kC; idx += NT) {
         const int r = idx >> 6, i = idx & 63;
         if (i < r) sB[r * kLA + i] *= sBeta[r];
     }
@@ -958,9 +966,9 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     float *stA1 = sA, *stA2 = sA + 16 * D, *stB1 = sZ;           // [16][D] each
 #pragma unroll 1
     for (int Bk = 0; Bk < 4; ++Bk) {
-        {   // ---- phase M: wave w takes the channel tiles dt = w, w + 4, ...
+        {   // ---- phase M: wave w takes the channel tiles dt = w, w + NT / 64, ...
             const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
-            for (int dt = wave; dt < D / 16; dt += 4) {
+            for (int dt = wave; dt < D / 16; dt += NW) {
                 const int dc = 16 * dt + m;                      // this lane's channel as operand / result column
                 f32x4 o1 = {0.f, 0.f, 0.f, 0.f}, o2 = {0.f, 0.f, 0.f, 0.f};
                 for (int I = 0; I < Bk; ++I) {                   // tokens of block Bk as rows, earlier blocks as columns
@@ -1001,48 +1009,48 @@ void kda_bwd_chain_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             }
         }
         __syncthreads();
-        // ---- phase P: this thread's channel d and tokens 16 Bk + rg + RG jj, four at a time
+        // ---- phase P: this thread's channel d and tokens 16 Bk + rg + RG jj, TG at a time
 #pragma unroll 1
-        for (int jj0 = 0; jj0 < 16 / RG; jj0 += 4) {
-            int t_[4];
-            float Gt[4], kt[4], qt[4], a1[4], a2[4], b1[4];
+        for (int jj0 = 0; jj0 < 16 / RG; jj0 += TG) {
+            int t_[TG];
+            float Gt[TG], kt[TG], qt[TG], a1[TG], a2[TG], b1[TG];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < TG; ++u) {
                 const int tl = rg + RG * (jj0 + u);
                 t_[u] = 16 * Bk + tl;
                 Gt[u] = sG[t_[u] * LD + d]; kt[u] = sK[t_[u] * LD + d]; qt[u] = sQ[t_[u] * LD + d];
                 a1[u] = stA1[tl * D + d]; a2[u] = stA2[tl * D + d]; b1[u] = stB1[tl * D + d];
             }
-            float old_q[4], old_k[4], old_g[4];                  // what kda_bwd_products left: fetched now, used below
+            float old_q[TG], old_k[TG], old_g[TG];                  // what kda_bwd_products left: fetched now, used below
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < TG; ++u) {
                 const int64_t off = ((tok0 + (t_[u] < nv ? t_[u] : 0)) * H + h) * (int64_t)D + d;
                 old_q[u] = dq[off]; old_k[u] = dk[off]; old_g[u] = dla[off];
             }
-            for (int i = 16 * Bk; i < t_[3]; ++i) {              // the tokens as rows: columns i < t inside the block
+            for (int i = 16 * Bk; i < t_[TG - 1]; ++i) {              // the tokens as rows: columns i < t inside the block
                 const float gi = sG[i * LD + d], ki = sK[i * LD + d];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < TG; ++u) {
                     const float kk = i < t_[u] ? ki * fast_exp2(Gt[u] - gi) : 0.f;
                     a1[u] = fmaf(sB[t_[u] * kLA + i], kk, a1[u]);
                     a2[u] = fmaf(sB[i * kLA + t_[u] + 1], kk, a2[u]);
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < TG; ++u) {
                 a2[u] = fmaf(sB[t_[u] * kLA + t_[u] + 1], kt[u], a2[u]);     // dP[t,t]
                 b1[u] = fmaf(sB[t_[u] * kLA + t_[u] + 1], qt[u], b1[u]);
             }
             for (int r = t_[0] + 1; r < 16 * Bk + 16; ++r) {     // the tokens as columns: rows r > t inside the block
                 const float gr = sG[r * LD + d], kr = sK[r * LD + d], qr = sQ[r * LD + d];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < TG; ++u) {
                     const float e = r > t_[u] ? fast_exp2(gr - Gt[u]) : 0.f;
                     b1[u] = fmaf(fmaf(sB[r * kLA + t_[u]], kr, sB[t_[u] * kLA + r + 1] * qr), e, b1[u]);
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < TG; ++u) {
                 float gsum = 0.f;
                 if (t_[u] < nv) {
                     const int64_t off = ((tok0 + t_[u]) * H + h) * (int64_t)D + d;
@@ -1151,7 +1159,7 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
         hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, D>), gchunk, dim3(kProductsThreads), lds_prod, stream, q, k, la, cu,
                            d_o, Sc, dSc, Yw, Vnw, dVnw, dv, dq, dk, dla, gC, Cw, T, H, p.chunks_per_seq,
                            dm->scale);
-        hipLaunchKernelGGL((kda_bwd_chain_kernel<Tin, D>), gchunk, dim3(256), lds_chain, stream, q, k, la, beta,
+        hipLaunchKernelGGL((kda_bwd_chain_kernel<Tin, D>), gchunk, dim3(kChainThreads), lds_chain, stream, q, k, la, beta,
                            cu, Tw, Cw, gC, dq, dk, dla, dbeta, T, H, p.chunks_per_seq);
     }
     const hipError_t e = hipGetLastError();
