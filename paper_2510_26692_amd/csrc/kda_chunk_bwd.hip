@@ -252,11 +252,11 @@ __device__ void chunk_load(const Tin *__restrict__ q, const Tin *__restrict__ k,
 }
 
 // q, k, G tiles -> Gamma.Q, Gamma^{i->C}.K, Gamma.K (in sQ, sK, sG), as the forward kernel does.
-template <int D>
+template <int D, int NT = 256>
 __device__ void decay_operands(float *sQ, float *sK, float *sG, const float *sGend, int tid)
 {
     constexpr int LD = D + 1;
-    for (int idx = tid; idx < kC * D; idx += 256) {
+    for (int idx = tid; idx < kC * D; idx += NT) {
         const int r = idx / D, d = idx % D;
         const float G = sG[r * LD + d];
         const float kk = sK[r * LD + d];
@@ -280,14 +280,16 @@ __device__ __forceinline__ void load_tile(float *dst, const float *__restrict__ 
     f.commit(dst, tid);
 }
 
+constexpr int kPrepThreads = 512;
+
 template <typename Tin, int D>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(kPrepThreads)
 void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                          const Tin *__restrict__ log_alpha, const Tin *__restrict__ beta,
                          const int32_t *__restrict__ cu, float *__restrict__ Tw, float *__restrict__ Ow,
                          int64_t T, int H, int64_t chunks_per_seq)
 {
-    constexpr int LD = D + 1;
+    constexpr int LD = D + 1, NT = kPrepThreads, NW = NT / 64;
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD;
     float *s0 = sG + kC * LD, *s1 = s0 + kTile;
@@ -303,8 +305,8 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     const int nv = (int)((len - c0 < kC) ? (len - c0) : kC);
     const int64_t slot = chunk_slot(cu, n, chunks_per_seq, ci) * H + h;
 
-    for (int idx = tid; idx < 2 * kTile; idx += 256) s0[idx] = 0.f;
-    chunk_load<Tin, D>(q, k, log_alpha, beta, tok_base + c0, nv, H, h, sQ, sK, sG, sBeta, sGend, sTot, tid);
+    for (int idx = tid; idx < 2 * kTile; idx += NT) s0[idx] = 0.f;
+    chunk_load<Tin, D, NT>(q, k, log_alpha, beta, tok_base + c0, nv, H, h, sQ, sK, sG, sBeta, sGend, sTot, tid);
     auto put = [&](int r, int i, float akk, float aqk) {         // one entry with i <= r into both tiles
         if (i < r) {                                             // L = StrictTril(Diag(beta) A_kk), kept twice:
             s0[r * kLA + i] = sBeta[r] * akk;                    // s0 becomes T - I block by block,
@@ -316,10 +318,10 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     // A_kk, A_qk in 16-token blocks.  Below the diagonal (row block R > column block I) the decay splits at
     // the end of block I, E_I = G of its last token:  e^(G_r - G_i) = e^(G_r - E_I) e^(E_I - G_i), both
     // factors at most 1, so the block is a plain product of two decay-scaled operands: matrix cores,
-    // one exponential per operand element.  Wave w takes the block pairs w, w + 4 of the list below.
+    // one exponential per operand element.  Wave w takes the block pairs w, w + NT / 64, ... of the list below.
     {
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
-        for (int pair = wave; pair < 6; pair += 4) {
+        for (int pair = wave; pair < 6; pair += NW) {
             const int R = pair < 3 ? pair + 1 : (pair < 5 ? pair - 1 : 3);        // (1,0) (2,0) (3,0) (2,1) (3,1) (3,2)
             const int I = pair < 3 ? 0 : (pair < 5 ? 1 : 2);
             const float *gE = sG + (16 * I + 15) * LD;
@@ -337,29 +339,30 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
         }
     }
     // The four diagonal blocks pair by pair in the log domain (the decay inside a block may exceed any
-    // factorisation's range): thread (r, i) of all four blocks at once.
+    // factorisation's range): 256 threads (r, i) per set of blocks, NT / 256 sets side by side.
     {
-        const int rl = tid >> 4, il = tid & 15;
-        float akk[4] = {}, aqk[4] = {};
+        constexpr int kSets = NT / 256, kPer = 4 / kSets;
+        const int rl = (tid & 255) >> 4, il = tid & 15, first = kPer * (tid >> 8);
+        float akk[kPer] = {}, aqk[kPer] = {};
         for (int d = 0; d < D; ++d) {
 #pragma unroll
-            for (int b4 = 0; b4 < 4; ++b4) {
-                const int r = 16 * b4 + rl, i = 16 * b4 + il;
+            for (int b4 = 0; b4 < kPer; ++b4) {
+                const int r = 16 * (first + b4) + rl, i = 16 * (first + b4) + il;
                 const float t = sK[i * LD + d] * fast_exp2(fminf(sG[r * LD + d] - sG[i * LD + d], 0.f));
                 akk[b4] = fmaf(sK[r * LD + d], t, akk[b4]);
                 aqk[b4] = fmaf(sQ[r * LD + d], t, aqk[b4]);
             }
         }
 #pragma unroll
-        for (int b4 = 0; b4 < 4; ++b4)
-            if (il <= rl) put(16 * b4 + rl, 16 * b4 + il, akk[b4], aqk[b4]);
+        for (int b4 = 0; b4 < kPer; ++b4)
+            if (il <= rl) put(16 * (first + b4) + rl, 16 * (first + b4) + il, akk[b4], aqk[b4]);
     }
     __syncthreads();
     // (I + L)^-1 - I in 16 x 16 blocks.  Diagonal blocks: wave w inverts block w, lane m < 16 its column m
     // (X[r][m] = -L[r][m] - sum_{m < i < r} L[r][i] X[i][m]; a lane reads back only what it wrote itself).
     {
         const int wave = tid >> 6, lane = tid & 63, b0 = 16 * wave;
-        if (lane < 16) {
+        if (wave < 4 && lane < 16) {
             for (int r = 1; r < 16; ++r) {
                 float val = 0.f;
                 if (lane < r) {
@@ -396,19 +399,19 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
             __syncthreads();
         }
     }
-    for (int idx = tid; idx < kC * kC; idx += 256) {
+    for (int idx = tid; idx < kC * kC; idx += NT) {
         const int r = idx >> 6, j = idx & 63;
         if (j < r) s1[r * kLA + j] = s0[r * kLA + j] * sBeta[j];
         else if (j == r) s1[r * kLA + j] = sBeta[j];
     }
     __syncthreads();
     float *dst = Tw + slot * (int64_t)(2 * kTile);
-    for (int idx = tid; idx < 2 * kTile; idx += 256) dst[idx] = s0[idx];
+    for (int idx = tid; idx < 2 * kTile; idx += NT) dst[idx] = s0[idx];
     // the decay-scaled operands for the two scans
-    decay_operands<D>(sQ, sK, sG, sGend, tid);                   // sQ <- Gamma.Q, sG <- Gamma.K, sK <- Gamma^{i->C}.K
+    decay_operands<D, NT>(sQ, sK, sG, sGend, tid);                  // sQ <- Gamma.Q, sG <- Gamma.K, sK <- Gamma^{i->C}.K
     __syncthreads();
     float *ops = Ow + slot * (int64_t)operand_floats<D>();
-    for (int idx = tid; idx < kC * D / 4; idx += 256) {
+    for (int idx = tid; idx < kC * D / 4; idx += NT) {
         const int r = idx / (D / 4), c = 4 * (idx % (D / 4));
         const float *pq = sQ + r * LD + c, *pg = sG + r * LD + c, *pk = sK + r * LD + c;
         reinterpret_cast<float4 *>(ops)[idx] = make_float4(pq[0], pq[1], pq[2], pq[3]);
@@ -418,7 +421,7 @@ void kda_bwd_prep_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
     if (tid < D) ops[3 * kC * D + tid] = sGend[tid];
 }
 
-template <int D> constexpr size_t prep_lds_floats() { return 3 * kC * (D + 1) + 2 * kTile + kC + D + 256; }
+template <int D> constexpr size_t prep_lds_floats() { return 3 * kC * (D + 1) + 2 * kTile + kC + D + kPrepThreads; }
 
 template <int D> constexpr size_t scan_lds_floats()          // kda_bwd_scan
 {
@@ -1149,7 +1152,7 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     const dim3 gscan((unsigned)dm->num_seqs, (unsigned)H, (unsigned)(D / kBV));
     const dim3 gchunk((unsigned)dm->num_seqs, (unsigned)p.max_chunks, (unsigned)H);
     if (p.max_chunks > 0)
-        hipLaunchKernelGGL((kda_bwd_prep_kernel<Tin, D>), gchunk, dim3(256), lds_prep, stream, q, k, la, beta, cu,
+        hipLaunchKernelGGL((kda_bwd_prep_kernel<Tin, D>), gchunk, dim3(kPrepThreads), lds_prep, stream, q, k, la, beta, cu,
                            Tw, Ow, T, H, p.chunks_per_seq);
     hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(256), lds_states, stream, v, h0, cu, Tw, Ow,
                        Sc, Yw, Vnw, T, H, p.chunks_per_seq);
