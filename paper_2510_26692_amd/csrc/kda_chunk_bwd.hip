@@ -78,12 +78,12 @@ __device__ __forceinline__ void unpack16(const uint4 &w, const __hip_bfloat16 *,
 
 // ROWS x W block of Tin (rows `stride` elements apart, 16-byte aligned): fetch() issues the loads
 // (rows r >= nv read as zero), commit() writes dst[r * ld + c] = mul * x.  ROWS * W * sizeof(Tin) / 16
-// must be a multiple of the NT threads that take part.  Keeping the two apart lets a loop fetch its next
+// must be a multiple of the NT threads that take part (or less than NT).  Keeping the two apart lets a loop fetch its next
 // block before it works on the current one.
 template <typename Tin, int ROWS, int W, int NT = 256>
 struct RowsFetch {
-    static constexpr int EPV = 16 / (int)sizeof(Tin), VPR = W / EPV, NV = ROWS * VPR / NT;
-    static_assert(ROWS * VPR % NT == 0, "block size");
+    static constexpr int EPV = 16 / (int)sizeof(Tin), VPR = W / EPV, TOTAL = ROWS * VPR, NV = (TOTAL + NT - 1) / NT;
+    static_assert(TOTAL % NT == 0 || TOTAL < NT, "block size");
     uint4 buf[NV];
     __device__ __forceinline__ void fetch(const Tin *__restrict__ src, int64_t stride, int nv, int tid)
     {
@@ -91,7 +91,7 @@ struct RowsFetch {
         for (int u = 0; u < NV; ++u) {
             const int vi = tid + NT * u, r = vi / VPR, cv = vi % VPR;
             buf[u] = make_uint4(0u, 0u, 0u, 0u);
-            if (r < nv) buf[u] = *reinterpret_cast<const uint4 *>(src + r * stride + cv * EPV);
+            if (vi < TOTAL && r < nv) buf[u] = *reinterpret_cast<const uint4 *>(src + r * stride + cv * EPV);
         }
     }
     __device__ __forceinline__ void commit(float *dst, int ld, float mul, int tid) const
@@ -101,8 +101,10 @@ struct RowsFetch {
             const int vi = tid + NT * u, r = vi / VPR, cv = vi % VPR;
             float f[EPV];
             unpack16(buf[u], (const Tin *)nullptr, f);
+            if (vi < TOTAL) {
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) dst[r * ld + cv * EPV + e] = mul * f[e];
+                for (int e = 0; e < EPV; ++e) dst[r * ld + cv * EPV + e] = mul * f[e];
+            }
         }
     }
 };
@@ -166,6 +168,19 @@ __device__ __forceinline__ void cumsum_rows(float *sG, float *sTot, float *sGend
     __syncthreads();
 }
 
+// How the waves of a scan share a step's result tiles.  Products with token rows (64 x 32 results: four
+// row tiles, two column tiles): with four waves a wave takes a row tile and both columns, with eight one
+// tile.  Products with state rows (D x 32): D / 16 row tiles; a wave takes whole row tiles with both
+// columns when there are enough of them, else one tile.
+constexpr int kScanThreads = 512;
+constexpr int kScanWaves = kScanThreads / 64;
+constexpr int kTokCols = kScanWaves == 4 ? 2 : 1;
+template <int D> struct StateTiles {
+    static constexpr int NRT = D / 16;
+    static constexpr bool kPair = NRT >= kScanWaves;
+    static constexpr int NC = kPair ? 2 : 1, RPW = kPair ? NRT / kScanWaves : 1;
+};
+
 // The decay-scaled operands of a chunk as kda_bwd_prep leaves them in the workspace: three [C][D] fp32
 // tiles (Gamma.Q, Gamma.K, Gamma^{i->C}.K; rows past the chunk's end are zero) and G_C in log2 units.
 template <int D> constexpr int operand_floats() { return 3 * kC * D + D; }
@@ -173,9 +188,9 @@ template <int D> constexpr int operand_floats() { return 3 * kC * D + D; }
 // Everything a scan step reads from global memory, held in registers between fetch() and commit().
 template <typename Tslice, int D, bool kWithQ>
 struct StepFetch {
-    RowsFetch<float, kC, D> fq, fkg, fkt;
-    RowsFetch<Tslice, kC, kBV> fs;
-    BlockFetch<kTile / 4> ft;
+    RowsFetch<float, kC, D, kScanThreads> fq, fkg, fkt;
+    RowsFetch<Tslice, kC, kBV, kScanThreads> fs;
+    BlockFetch<kTile / 4, kScanThreads> ft;
     float gend;
     __device__ __forceinline__ void fetch(const float *ops, const Tslice *slice, const float *tile,
                                           int64_t tok0, int nv, int H, int h, int col0, int tid)
@@ -216,18 +231,20 @@ __device__ __forceinline__ f32x4 mma16(int kbeg, int kend, int g, f32x4 acc, FA 
     return acc;
 }
 
-// Two result tiles that share the A operand (the two 16-column halves of a 32-column slice):
-// acc[ct] += A B_ct with b(k, ct).
-template <typename FA, typename FB>
-__device__ __forceinline__ void mma16x2(int kbeg, int kend, int g, f32x4 (&acc)[2], FA &&a, FB &&b)
+// NCT result tiles that share the A operand (one or both 16-column halves of a 32-column slice):
+// acc[c] += A B_c with b(k, c).
+template <int NCT, typename FA, typename FB>
+__device__ __forceinline__ void mma16t(int kbeg, int kend, int g, f32x4 (&acc)[NCT], FA &&a, FB &&b)
 {
     for (int k = kbeg + g; k < kend; k += 8) {
-        const float a0 = a(k), b00 = b(k, 0), b01 = b(k, 1);
-        const float a1 = a(k + 4), b10 = b(k + 4, 0), b11 = b(k + 4, 1);
-        acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b00, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b01, acc[1], 0, 0, 0);
-        acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b10, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b11, acc[1], 0, 0, 0);
+        const float a0 = a(k), a1 = a(k + 4);
+        float b0[NCT], b1[NCT];
+#pragma unroll
+        for (int c = 0; c < NCT; ++c) { b0[c] = b(k, c); b1[c] = b(k + 4, c); }
+#pragma unroll
+        for (int c = 0; c < NCT; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[c], acc[c], 0, 0, 0);
+#pragma unroll
+        for (int c = 0; c < NCT; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[c], acc[c], 0, 0, 0);
     }
 }
 
@@ -437,7 +454,7 @@ template <int D> constexpr size_t states_lds_floats()        // kda_bwd_states
 // Forward walk: S0 of every chunk, Y = V - Kg S0 and Vn = M Y.
 // ------------------------------------------------------------------------------------------
 template <typename Tin, int D>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(kScanThreads)
 void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ h0,
                            const int32_t *__restrict__ cu, const float *__restrict__ Tw,
                            const float *__restrict__ Ow,
@@ -456,7 +473,7 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
     if (cu) { tok_base = cu[n]; len = (int64_t)cu[n + 1] - tok_base; }
     else    { tok_base = (int64_t)n * T; len = T; }
     const int64_t state_off = ((int64_t)n * H + h) * (int64_t)(D * D);
-    for (int idx = tid; idx < D * kBV; idx += 256) {
+    for (int idx = tid; idx < D * kBV; idx += kScanThreads) {
         const int d = idx / kBV, c = idx % kBV;
         sS[idx] = h0 ? h0[state_off + (int64_t)d * D + col0 + c] : 0.f;
     }
@@ -473,7 +490,7 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
         const int64_t tok0 = tok_base + ci * kC;
         const int64_t slot = slot_first + ci * H;
         __syncthreads();
-        for (int idx = tid; idx < D * kBV; idx += 256) {
+        for (int idx = tid; idx < D * kBV; idx += kScanThreads) {
             const int d = idx / kBV, c = idx % kBV;
             Sc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sS[idx];
         }
@@ -483,48 +500,48 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
                       tok0 + kC, valid_rows(ci + 1), H, h, col0, tid);
         __syncthreads();
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
-        const int r0 = 16 * wave;                                // this wave's 16 token rows
-        f32x4 y[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-        mma16x2(0, D, g, y, [&](int k) { return sG[(r0 + m) * LD + k]; },                  // Kg S0
-                [&](int k, int ct) { return sS[k * kBV + 16 * ct + m]; });
+        const int r0 = 16 * (wave & 3);                          // this wave's 16 token rows ...
+        const int cb = kTokCols == 2 ? 0 : 16 * (wave >> 2);     // ... and first slice column
+        f32x4 y[kTokCols] = {};
+        mma16t<kTokCols>(0, D, g, y, [&](int k) { return sG[(r0 + m) * LD + k]; },                    // Kg S0
+                         [&](int k, int c) { return sS[k * kBV + cb + 16 * c + m]; });
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)                           // Y = V - Kg S0
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                y[ct][j] = sV[(r0 + 4 * g + j) * kBV + 16 * ct + m] - y[ct][j];
-                sV[(r0 + 4 * g + j) * kBV + 16 * ct + m] = y[ct][j];
-            }
-        __syncthreads();
-        f32x4 vn[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-        mma16x2(0, r0 + 16, g, vn, [&](int k) { return k <= r0 + m ? sA[(r0 + m) * kLA + k] : 0.f; },   // Vn = M Y
-                [&](int k, int ct) { return sV[k * kBV + 16 * ct + m]; });
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int c = 0; c < kTokCols; ++c)                       // Y = V - Kg S0
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int r = r0 + 4 * g + j;
-                sVn[r * kBV + 16 * ct + m] = vn[ct][j];
+                y[c][j] = sV[(r0 + 4 * g + j) * kBV + cb + 16 * c + m] - y[c][j];
+                sV[(r0 + 4 * g + j) * kBV + cb + 16 * c + m] = y[c][j];
             }
         __syncthreads();
-        for (int idx = tid; idx < nv * kBV; idx += 256) {        // whole 128-byte rows of the slice at a time
+        f32x4 vn[kTokCols] = {};
+        mma16t<kTokCols>(0, r0 + 16, g, vn, [&](int k) { return k <= r0 + m ? sA[(r0 + m) * kLA + k] : 0.f; },   // Vn = M Y
+                         [&](int k, int c) { return sV[k * kBV + cb + 16 * c + m]; });
+#pragma unroll
+        for (int c = 0; c < kTokCols; ++c)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sVn[(r0 + 4 * g + j) * kBV + cb + 16 * c + m] = vn[c][j];
+        __syncthreads();
+        for (int idx = tid; idx < nv * kBV; idx += kScanThreads) {       // whole 128-byte rows of the slice at a time
             const int64_t off = ((tok0 + idx / kBV) * H + h) * (int64_t)D + col0 + idx % kBV;
             Yw[off] = sV[idx];
             Vnw[off] = sVn[idx];
         }
-        for (int rt = wave * (D / 64); rt < (wave + 1) * (D / 64); ++rt) {       // S1 = Diag(e^G_C) S0 + Kt^T Vn
-            const int d0 = 16 * rt;
-            f32x4 acc[2];
+        using ST = StateTiles<D>;
+        for (int q = 0; q < ST::RPW; ++q) {                              // S1 = Diag(e^G_C) S0 + Kt^T Vn
+            const int d0 = 16 * (ST::kPair ? wave * ST::RPW + q : wave % ST::NRT);
+            const int sb = ST::kPair ? 0 : 16 * (wave / ST::NRT);
+            f32x4 acc[ST::NC];
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct)
+            for (int c = 0; c < ST::NC; ++c)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[ct][j] = sS[(d0 + 4 * g + j) * kBV + 16 * ct + m] * fast_exp2(sGend[d0 + 4 * g + j]);
-            mma16x2(0, kC, g, acc, [&](int k) { return sK[k * LD + d0 + m]; },
-                    [&](int k, int ct) { return sVn[k * kBV + 16 * ct + m]; });
+                    acc[c][j] = sS[(d0 + 4 * g + j) * kBV + sb + 16 * c + m] * fast_exp2(sGend[d0 + 4 * g + j]);
+            mma16t<ST::NC>(0, kC, g, acc, [&](int k) { return sK[k * LD + d0 + m]; },
+                           [&](int k, int c) { return sVn[k * kBV + sb + 16 * c + m]; });
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct)
+            for (int c = 0; c < ST::NC; ++c)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) sS[(d0 + 4 * g + j) * kBV + 16 * ct + m] = acc[ct][j];
+                for (int j = 0; j < 4; ++j) sS[(d0 + 4 * g + j) * kBV + sb + 16 * c + m] = acc[c][j];
         }
     }
 }
@@ -533,7 +550,7 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
 // Backward walk with dS: dVn, dV = X, the dS1 of every chunk, dh0.
 // ------------------------------------------------------------------------------------------
 template <typename Tin, int D>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(kScanThreads)
 void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict__ Tw,
                          const float *__restrict__ Ow,
                          const float *__restrict__ d_o, const float *__restrict__ d_hT,
@@ -552,7 +569,7 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
     if (cu) { tok_base = cu[n]; len = (int64_t)cu[n + 1] - tok_base; }
     else    { tok_base = (int64_t)n * T; len = T; }
     const int64_t state_off = ((int64_t)n * H + h) * (int64_t)(D * D);
-    for (int idx = tid; idx < D * kBV; idx += 256) {
+    for (int idx = tid; idx < D * kBV; idx += kScanThreads) {
         const int d = idx / kBV, c = idx % kBV;
         sdS[idx] = d_hT ? d_hT[state_off + (int64_t)d * D + col0 + c] : 0.f;
     }
@@ -570,7 +587,7 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
         const int64_t tok0 = tok_base + ci * kC;
         const int64_t slot = slot_first + ci * H;
         __syncthreads();
-        for (int idx = tid; idx < D * kBV; idx += 256) {         // dS1 of this chunk
+        for (int idx = tid; idx < D * kBV; idx += kScanThreads) {         // dS1 of this chunk
             const int d = idx / kBV, c = idx % kBV;
             dSc[slot * (int64_t)(D * D) + (int64_t)d * D + col0 + c] = sdS[idx];
         }
@@ -580,56 +597,53 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
                       tok0 - kC, kC, H, h, col0, tid);
         __syncthreads();
         const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
-        const int r0 = 16 * wave;                                // this wave's 16 token rows
-        f32x4 dvn[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};     // dVn = Kt dS1 + P^T dO (P lower triangular)
-        mma16x2(0, D, g, dvn, [&](int k) { return sK[(r0 + m) * LD + k]; },
-                [&](int k, int ct) { return sdS[k * kBV + 16 * ct + m]; });
-        mma16x2(r0, kC, g, dvn, [&](int k) { return k >= r0 + m ? sA[(r0 + m) * kLA + k + 1] : 0.f; },   // P[k][r0 + m]
-                [&](int k, int ct) { return sdO[k * kBV + 16 * ct + m]; });
+        const int r0 = 16 * (wave & 3);                          // this wave's 16 token rows ...
+        const int cb = kTokCols == 2 ? 0 : 16 * (wave >> 2);     // ... and first slice column
+        f32x4 dvn[kTokCols] = {};                                // dVn = Kt dS1 + P^T dO (P lower triangular)
+        mma16t<kTokCols>(0, D, g, dvn, [&](int k) { return sK[(r0 + m) * LD + k]; },
+                         [&](int k, int c) { return sdS[k * kBV + cb + 16 * c + m]; });
+        mma16t<kTokCols>(r0, kC, g, dvn, [&](int k) { return k >= r0 + m ? sA[(r0 + m) * kLA + k + 1] : 0.f; },   // P[k][r0 + m]
+                         [&](int k, int c) { return sdO[k * kBV + cb + 16 * c + m]; });
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int c = 0; c < kTokCols; ++c)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = r0 + 4 * g + j;
-                sdVn[i * kBV + 16 * ct + m] = dvn[ct][j];
-            }
+            for (int j = 0; j < 4; ++j) sdVn[(r0 + 4 * g + j) * kBV + cb + 16 * c + m] = dvn[c][j];
         __syncthreads();
-        for (int idx = tid; idx < nv * kBV; idx += 256)          // whole 128-byte rows of the slice at a time
+        for (int idx = tid; idx < nv * kBV; idx += kScanThreads)         // whole 128-byte rows of the slice at a time
             dVnw[((tok0 + idx / kBV) * H + h) * (int64_t)D + col0 + idx % kBV] = sdVn[idx];
-        f32x4 xx[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};      // X = M^T dVn = dV
-        mma16x2(r0, kC, g, xx, [&](int k) { return k >= r0 + m ? sA[k * kLA + r0 + m] : 0.f; },         // M[k][r0 + m]
-                [&](int k, int ct) { return sdVn[k * kBV + 16 * ct + m]; });
+        f32x4 xx[kTokCols] = {};                                 // X = M^T dVn = dV
+        mma16t<kTokCols>(r0, kC, g, xx, [&](int k) { return k >= r0 + m ? sA[k * kLA + r0 + m] : 0.f; },         // M[k][r0 + m]
+                         [&](int k, int c) { return sdVn[k * kBV + cb + 16 * c + m]; });
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+        for (int c = 0; c < kTokCols; ++c)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = r0 + 4 * g + j;
-                sX[i * kBV + 16 * ct + m] = xx[ct][j];
-            }
+            for (int j = 0; j < 4; ++j) sX[(r0 + 4 * g + j) * kBV + cb + 16 * c + m] = xx[c][j];
         __syncthreads();
-        for (int idx = tid; idx < nv * kBV; idx += 256)
+        for (int idx = tid; idx < nv * kBV; idx += kScanThreads)
             dv[((tok0 + idx / kBV) * H + h) * (int64_t)D + col0 + idx % kBV] = sX[idx];
-        for (int rt = wave * (D / 64); rt < (wave + 1) * (D / 64); ++rt) {       // dS0
-            const int d0 = 16 * rt;
-            f32x4 acc[2];
+        using ST = StateTiles<D>;
+        for (int q = 0; q < ST::RPW; ++q) {                              // dS0
+            const int d0 = 16 * (ST::kPair ? wave * ST::RPW + q : wave % ST::NRT);
+            const int sb = ST::kPair ? 0 : 16 * (wave / ST::NRT);
+            f32x4 acc[ST::NC];
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct)
+            for (int c = 0; c < ST::NC; ++c)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[ct][j] = sdS[(d0 + 4 * g + j) * kBV + 16 * ct + m] * fast_exp2(sGend[d0 + 4 * g + j]);
-            mma16x2(0, kC, g, acc, [&](int k) { return sQ[k * LD + d0 + m]; },
-                    [&](int k, int ct) { return sdO[k * kBV + 16 * ct + m]; });
-            mma16x2(0, kC, g, acc, [&](int k) { return -sG[k * LD + d0 + m]; },
-                    [&](int k, int ct) { return sX[k * kBV + 16 * ct + m]; });
+                    acc[c][j] = sdS[(d0 + 4 * g + j) * kBV + sb + 16 * c + m] * fast_exp2(sGend[d0 + 4 * g + j]);
+            mma16t<ST::NC>(0, kC, g, acc, [&](int k) { return sQ[k * LD + d0 + m]; },
+                           [&](int k, int c) { return sdO[k * kBV + sb + 16 * c + m]; });
+            mma16t<ST::NC>(0, kC, g, acc, [&](int k) { return -sG[k * LD + d0 + m]; },
+                           [&](int k, int c) { return sX[k * kBV + sb + 16 * c + m]; });
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct)
+            for (int c = 0; c < ST::NC; ++c)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) sdS[(d0 + 4 * g + j) * kBV + 16 * ct + m] = acc[ct][j];
+                for (int j = 0; j < 4; ++j) sdS[(d0 + 4 * g + j) * kBV + sb + 16 * c + m] = acc[c][j];
         }
     }
     if (dh0) {
         __syncthreads();
-        for (int idx = tid; idx < D * kBV; idx += 256) {
+        for (int idx = tid; idx < D * kBV; idx += kScanThreads) {
             const int d = idx / kBV, c = idx % kBV;
             dh0[state_off + (int64_t)d * D + col0 + c] = sdS[idx];
         }
@@ -1154,9 +1168,9 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     if (p.max_chunks > 0)
         hipLaunchKernelGGL((kda_bwd_prep_kernel<Tin, D>), gchunk, dim3(kPrepThreads), lds_prep, stream, q, k, la, beta, cu,
                            Tw, Ow, T, H, p.chunks_per_seq);
-    hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(256), lds_states, stream, v, h0, cu, Tw, Ow,
+    hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(kScanThreads), lds_states, stream, v, h0, cu, Tw, Ow,
                        Sc, Yw, Vnw, T, H, p.chunks_per_seq);
-    hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(256), lds_scan, stream, cu, Tw, Ow,
+    hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(kScanThreads), lds_scan, stream, cu, Tw, Ow,
                        d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
     if (p.max_chunks > 0) {
         hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, D>), gchunk, dim3(kProductsThreads), lds_prod, stream, q, k, la, cu,
