@@ -29,19 +29,25 @@
 //              dG_C = e^(G_C) . rowsum(dS1 . S0) + sum_t dKt_t . Kt_t
 //              dlog_alpha_t = sum_{r>=t} dG_r + dG_C
 //
-// Five kernels in fp32; the dense products of the two scans and of kda_bwd_products run on the
-// matrix cores with fp32 operands (v_mfma_f32_16x16x4_f32, v_mfma_f32_32x32x2_f32), the rest are
-// plain FMAs on LDS tiles:
+// Decays that cross a 16-token block are split at the end E of the earlier block,
+// e^(G_r - G_i) = e^(G_r - E) e^(E - G_i) (both factors at most 1 whatever the decay), which turns those
+// parts of A_kk, A_qk and of the gradient sums into block products of decay-scaled operands; only
+// inside a 16 x 16 diagonal block is there one exponential per pair and channel.
+//
+// Five kernels in fp32, 512 threads each (LDS leaves room for one workgroup per compute unit); every
+// dense product runs on the matrix cores with fp32 operands (v_mfma_f32_16x16x4_f32,
+// v_mfma_f32_32x32x2_f32):
 //   kda_bwd_prep     one workgroup per (chunk, head), all chunks in parallel: A_kk, A_qk, T and M,
-//                    left in the workspace as two packed C x C tiles
+//                    left in the workspace as two packed C x C tiles, and the decay-scaled operands
+//                    Gamma.Q, Gamma.K, Gamma^{i->C}.K for the two scans
 //   kda_bwd_states   one workgroup per (sequence, head, 32 state columns) walks the chunks
 //                    forward and leaves S0 of every chunk, Y and Vn in the workspace
 //   kda_bwd_scan     the same decomposition walks the chunks backward with dS: dVn, dV, the dS1
 //                    of every chunk, dh0  (the columns of S never mix, neither do those of dS)
 //   kda_bwd_products one workgroup per (chunk, head): the products with S0 and dS1 (dQg, dKg,
 //                    dKt, dG_C) folded into dq, dk and dG, and the two C x C products dP, dM
-//   kda_bwd_chain    one workgroup per (chunk, head): the gradient through T and the pairwise
-//                    decay terms, the reverse running sum that turns dG into dlog_alpha, dbeta
+//   kda_bwd_chain    one workgroup per (chunk, head): the gradient through T and the decay terms
+//                    of dq, dk, dG, the reverse running sum that turns dG into dlog_alpha, dbeta
 #include "kda_common.h"
 
 namespace kda {
