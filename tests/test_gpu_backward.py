@@ -75,6 +75,7 @@ CASES = {
     "fp32_inputs_d128": lambda: (si.make_prefill(1, 131, 2, 128, 128, "f32", -1.0, 1205, 0.05), 1.0),
     "packed": lambda: (si.make_varlen([70, 0, 5, 129, 64, 300], 2, 128, 128, "bf16", -2.0, 1206, 0.05), 1.0),
     "bf16_inputs_d64": lambda: (si.make_prefill(2, 100, 2, 64, 64, "bf16", -2.0, 1208, 0.05), 1.0),
+    "slow_decay_128_chunks": lambda: (si.make_prefill(1, 64 * 128, 1, 128, 128, "bf16", -6.0, 1209, 0.3), 128 ** -0.5),
     "slow_decay_long": lambda: (si.make_prefill(1, 64 * 20 + 9, 2, 128, 128, "bf16", -6.0, 1207, 0.05), 1.0),
 }
 
