@@ -303,7 +303,7 @@ __device__ __forceinline__ void load_tile(float *dst, const float *__restrict__ 
     f.commit(dst, tid);
 }
 
-constexpr int kPrepThreads = 512;
+constexpr int kPrepThreads = 1024;
 
 template <typename Tin, int D>
 __global__ __launch_bounds__(kPrepThreads)
