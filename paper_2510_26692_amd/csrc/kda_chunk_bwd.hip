@@ -860,7 +860,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
 // ------------------------------------------------------------------------------------------
 // Per chunk: gradient through T, pairwise decay terms, dlog_alpha, dbeta.
 // ------------------------------------------------------------------------------------------
-constexpr int kChainThreads = 512;
+constexpr int kChainThreads = 1024;
 
 template <int D> constexpr size_t chain_lds_floats()
 {
