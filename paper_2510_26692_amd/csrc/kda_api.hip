@@ -35,6 +35,10 @@ kda_status chunk_mfma_dispatch(const kda_dims *, const kda_prologue *, const kda
 size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal, bool output_gate);
 size_t chunk_mfma_status_offset(const kda_dims *, size_t workspace_bytes);
 size_t chunk_bwd_workspace_size(const kda_dims *);
+size_t chunk_f32_fast_workspace_size(const kda_dims *);
+kda_status chunk_f32_fast_dispatch(const kda_dims *, const void *, const void *, const void *, const void *,
+                                   const void *, const float *, const int32_t *, void *, float *, void *,
+                                   hipStream_t);
 kda_status chunk_bwd_dispatch(const kda_dims *, const void *, const void *, const void *, const void *,
                               const void *, const float *, const int32_t *, const float *, const float *,
                               float *, float *, float *, float *, float *, float *, void *, size_t,
@@ -140,7 +144,8 @@ static size_t workspace_size(const kda_dims *d, bool minimal, bool output_gate)
     if (!d || d->chunk != kChunk) return 0;
     const char saved0 = g_last_error[0];
     if (check_dims(d, d->num_seqs != d->batch) != KDA_OK) { g_last_error[0] = saved0; return 0; }
-    if (!mfma_path(d)) return 0;
+    // the fp32 path runs without a workspace (one sequential kernel) and much faster with one
+    if (!mfma_path(d)) return (minimal || d->seqlen == 0) ? 0 : chunk_f32_fast_workspace_size(d);
     return chunk_mfma_workspace_size(d, minimal, output_gate);
 }
 
@@ -247,6 +252,9 @@ static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, con
     if (!mfma_path(d)) {
         if (pro || epi) return fail(KDA_ERR_UNSUPPORTED, "the fused stages need the matrix-core prefill");
         if (d->out_dtype != KDA_F32) return fail(KDA_ERR_UNSUPPORTED, "the fp32 prefill kernel writes fp32 outputs only");
+        const size_t fast = d->seqlen == 0 ? 0 : chunk_f32_fast_workspace_size(d);
+        if (fast > 0 && workspace && workspace_bytes >= fast && !(reinterpret_cast<uintptr_t>(workspace) & 255u))
+            return chunk_f32_fast_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace, stream);
         return chunk_f32_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, stream);
     }
 

@@ -553,6 +553,114 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
+// The forward pass itself from the same pieces (fp32 inputs, or bf16 inputs when the fp32 path is
+// asked for): kda_bwd_prep, then this walk, which is kda_bwd_states plus
+// O = scale (Qg S0 + P Vn) and keeps nothing but o and the final state.
+// ------------------------------------------------------------------------------------------
+template <int D> constexpr size_t fwd_scan_lds_floats()
+{
+    return 3 * kC * (D + 1) + kC * kLA + 2 * kC * kBV + D * kBV + D;
+}
+
+template <typename Tin, int D>
+__global__ __launch_bounds__(kScanThreads)
+void kda_fwd_scan_kernel(const Tin *__restrict__ v, const float *__restrict__ h0,
+                         const int32_t *__restrict__ cu, const float *__restrict__ Tw,
+                         const float *__restrict__ Ow, float *__restrict__ o, float *__restrict__ hT,
+                         int64_t T, int H, int64_t chunks_per_seq, float scale)
+{
+    constexpr int LD = D + 1;
+    extern __shared__ float smem[];
+    float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;   // Gamma.Q, Gamma^{i->C}.K, Gamma.K, M | A_qk
+    float *sV = sA + kC * kLA, *sVn = sV + kC * kBV;                 // V slice -> Y -> O, V_new
+    float *sS = sVn + kC * kBV, *sGend = sS + D * kBV;               // state slice, G_C
+
+    const int n = blockIdx.x, h = blockIdx.y, col0 = blockIdx.z * kBV, tid = threadIdx.x;
+    int64_t tok_base, len;
+    if (cu) { tok_base = cu[n]; len = (int64_t)cu[n + 1] - tok_base; }
+    else    { tok_base = (int64_t)n * T; len = T; }
+    const int64_t state_off = ((int64_t)n * H + h) * (int64_t)(D * D);
+    for (int idx = tid; idx < D * kBV; idx += kScanThreads) {
+        const int d = idx / kBV, c = idx % kBV;
+        sS[idx] = h0 ? h0[state_off + (int64_t)d * D + col0 + c] : 0.f;
+    }
+
+    const int64_t nchunks = (len + kC - 1) / kC;
+    const int64_t slot_first = chunk_slot(cu, n, chunks_per_seq, 0) * H + h;
+    auto valid_rows = [&](int64_t ci) { return (int)((len - ci * kC < kC) ? (len - ci * kC) : kC); };
+    StepFetch<Tin, D, true> nxt;
+    if (nchunks > 0)
+        nxt.fetch(Ow + slot_first * (int64_t)operand_floats<D>(), v, Tw + (slot_first * 2 + 1) * (int64_t)kTile,
+                  tok_base, valid_rows(0), H, h, col0, tid);
+    for (int64_t ci = 0; ci < nchunks; ++ci) {
+        const int nv = valid_rows(ci);
+        const int64_t tok0 = tok_base + ci * kC;
+        const int64_t slot = slot_first + ci * H;
+        __syncthreads();
+        nxt.commit(sQ, sK, sG, sA, sV, sGend, 1.f, tid);
+        if (ci + 1 < nchunks)
+            nxt.fetch(Ow + (slot + H) * (int64_t)operand_floats<D>(), v, Tw + ((slot + H) * 2 + 1) * (int64_t)kTile,
+                      tok0 + kC, valid_rows(ci + 1), H, h, col0, tid);
+        __syncthreads();
+        const int wave = tid >> 6, m = tid & 15, g = (tid >> 4) & 3;
+        const int r0 = 16 * (wave & 3);
+        const int cb = kTokCols == 2 ? 0 : 16 * (wave >> 2);
+        f32x4 y[kTokCols] = {};
+        mma16t<kTokCols>(0, D, g, y, [&](int k) { return sG[(r0 + m) * LD + k]; },                    // Kg S0
+                         [&](int k, int c) { return sS[k * kBV + cb + 16 * c + m]; });
+#pragma unroll
+        for (int c = 0; c < kTokCols; ++c)                       // Y = V - Kg S0
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sV[(r0 + 4 * g + j) * kBV + cb + 16 * c + m] -= y[c][j];
+        __syncthreads();
+        f32x4 vn[kTokCols] = {};
+        mma16t<kTokCols>(0, r0 + 16, g, vn, [&](int k) { return k <= r0 + m ? sA[(r0 + m) * kLA + k] : 0.f; },   // Vn = M Y
+                         [&](int k, int c) { return sV[k * kBV + cb + 16 * c + m]; });
+#pragma unroll
+        for (int c = 0; c < kTokCols; ++c)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sVn[(r0 + 4 * g + j) * kBV + cb + 16 * c + m] = vn[c][j];
+        __syncthreads();
+        f32x4 oo[kTokCols] = {};                                 // O = scale (Qg S0 + P Vn), P lower triangular
+        mma16t<kTokCols>(0, D, g, oo, [&](int k) { return sQ[(r0 + m) * LD + k]; },
+                         [&](int k, int c) { return sS[k * kBV + cb + 16 * c + m]; });
+        mma16t<kTokCols>(0, r0 + 16, g, oo, [&](int k) { return k <= r0 + m ? sA[k * kLA + r0 + m + 1] : 0.f; },   // P[r0 + m][k]
+                         [&](int k, int c) { return sVn[k * kBV + cb + 16 * c + m]; });
+#pragma unroll
+        for (int c = 0; c < kTokCols; ++c)                       // staged in the dead Y tile
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sV[(r0 + 4 * g + j) * kBV + cb + 16 * c + m] = scale * oo[c][j];
+        __syncthreads();
+        for (int idx = tid; idx < nv * kBV; idx += kScanThreads)
+            o[((tok0 + idx / kBV) * H + h) * (int64_t)D + col0 + idx % kBV] = sV[idx];
+        using ST = StateTiles<D>;
+        for (int q = 0; q < ST::RPW; ++q) {                              // S1 = Diag(e^G_C) S0 + Kt^T Vn
+            const int d0 = 16 * (ST::kPair ? wave * ST::RPW + q : wave % ST::NRT);
+            const int sb = ST::kPair ? 0 : 16 * (wave / ST::NRT);
+            f32x4 acc[ST::NC];
+#pragma unroll
+            for (int c = 0; c < ST::NC; ++c)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[c][j] = sS[(d0 + 4 * g + j) * kBV + sb + 16 * c + m] * fast_exp2(sGend[d0 + 4 * g + j]);
+            mma16t<ST::NC>(0, kC, g, acc, [&](int k) { return sK[k * LD + d0 + m]; },
+                           [&](int k, int c) { return sVn[k * kBV + sb + 16 * c + m]; });
+#pragma unroll
+            for (int c = 0; c < ST::NC; ++c)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sS[(d0 + 4 * g + j) * kBV + sb + 16 * c + m] = acc[c][j];
+        }
+    }
+    if (hT) {
+        __syncthreads();
+        for (int idx = tid; idx < D * kBV; idx += kScanThreads) {
+            const int d = idx / kBV, c = idx % kBV;
+            hT[state_off + (int64_t)d * D + col0 + c] = sS[idx];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Backward walk with dS: dVn, dV = X, the dS1 of every chunk, dh0.
 // ------------------------------------------------------------------------------------------
 template <typename Tin, int D>
@@ -1190,6 +1298,44 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     return KDA_OK;
 }
 
+struct FwdPlan { int64_t chunks_per_seq, max_chunks, nslots; size_t off_T, off_O, total; };
+
+static FwdPlan fwd_plan(const kda_dims *d, bool packed)
+{
+    const BwdPlan b = bwd_plan(d, packed);
+    FwdPlan p{};
+    p.chunks_per_seq = b.chunks_per_seq; p.max_chunks = b.max_chunks; p.nslots = b.nslots;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    p.off_T = 0;
+    p.off_O = up((size_t)p.nslots * 2 * kTile * 4);
+    p.total = up(p.off_O + (size_t)p.nslots * (3 * kC * d->dk + d->dk) * 4);
+    return p;
+}
+
+template <typename Tin, int D>
+static kda_status launch_fwd(const kda_dims *dm, const FwdPlan &p, const void *q_, const void *k_, const void *v_,
+                             const void *la_, const void *beta_, const float *h0, const int32_t *cu, float *o,
+                             float *hT, char *ws, hipStream_t stream)
+{
+    float *Tw = reinterpret_cast<float *>(ws + p.off_T), *Ow = reinterpret_cast<float *>(ws + p.off_O);
+    const size_t lds_prep = prep_lds_floats<D>() * 4, lds_scan = fwd_scan_lds_floats<D>() * 4;
+    kda_status st;
+    if ((st = reserve(kda_bwd_prep_kernel<Tin, D>, lds_prep, "kda_bwd_prep")) != KDA_OK) return st;
+    if ((st = reserve(kda_fwd_scan_kernel<Tin, D>, lds_scan, "kda_fwd_scan")) != KDA_OK) return st;
+    const int H = dm->heads;
+    if (p.max_chunks > 0)
+        hipLaunchKernelGGL((kda_bwd_prep_kernel<Tin, D>), dim3((unsigned)dm->num_seqs, (unsigned)p.max_chunks, (unsigned)H),
+                           dim3(kPrepThreads), lds_prep, stream, static_cast<const Tin *>(q_),
+                           static_cast<const Tin *>(k_), static_cast<const Tin *>(la_),
+                           static_cast<const Tin *>(beta_), cu, Tw, Ow, (int64_t)dm->seqlen, H, p.chunks_per_seq);
+    hipLaunchKernelGGL((kda_fwd_scan_kernel<Tin, D>), dim3((unsigned)dm->num_seqs, (unsigned)H, (unsigned)(D / kBV)),
+                       dim3(kScanThreads), lds_scan, stream, static_cast<const Tin *>(v_), h0, cu, Tw, Ow, o, hT,
+                       (int64_t)dm->seqlen, H, p.chunks_per_seq, dm->scale);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "fp32 prefill: %s", hipGetErrorString(e));
+    return KDA_OK;
+}
+
 }  // namespace
 
 size_t chunk_bwd_workspace_size(const kda_dims *d)
@@ -1215,6 +1361,29 @@ kda_status chunk_bwd_dispatch(const kda_dims *dm, const void *q, const void *k, 
     if (dm->dk == 128) return bf ? KDA_BWD(__hip_bfloat16, 128) : KDA_BWD(float, 128);
     return bf ? KDA_BWD(__hip_bfloat16, 64) : KDA_BWD(float, 64);
 #undef KDA_BWD
+}
+
+// The fp32 prefill from kda_bwd_prep and kda_fwd_scan.  Workspace: the two packed tiles and the three
+// operand tiles per (chunk, head).  0 if the shape is outside what the grid can hold (then the
+// single-kernel path of kda_chunk_f32.hip serves).
+size_t chunk_f32_fast_workspace_size(const kda_dims *d)
+{
+    const FwdPlan p = fwd_plan(d, d->num_seqs != d->batch);
+    return p.max_chunks > 65535 ? 0 : p.total;
+}
+
+kda_status chunk_f32_fast_dispatch(const kda_dims *dm, const void *q, const void *k, const void *v,
+                                   const void *log_alpha, const void *beta, const float *h0,
+                                   const int32_t *cu, void *o, float *hT, void *workspace, hipStream_t stream)
+{
+    const FwdPlan p = fwd_plan(dm, cu != nullptr);
+    char *ws = static_cast<char *>(workspace);
+    float *of = static_cast<float *>(o);
+    const bool bf = dm->in_dtype == KDA_BF16;
+#define KDA_FWD(TIN, DD) launch_fwd<TIN, DD>(dm, p, q, k, v, log_alpha, beta, h0, cu, of, hT, ws, stream)
+    if (dm->dk == 128) return bf ? KDA_FWD(__hip_bfloat16, 128) : KDA_FWD(float, 128);
+    return bf ? KDA_FWD(__hip_bfloat16, 64) : KDA_FWD(float, 64);
+#undef KDA_FWD
 }
 
 }  // namespace kda

@@ -1,4 +1,6 @@
-// Chunkwise KDA prefill in fp32 throughout (Section 3.1), used for fp32 inputs.
+// Chunkwise KDA prefill in fp32 throughout (Section 3.1), in one kernel: what fp32 inputs get when the
+// caller brings no workspace (with one, the parallel per-chunk kernel and the matrix-core walk of
+// kda_chunk_bwd.hip run instead).
 //
 // One workgroup walks the chunks of one (sequence, head) for a 32-column slice
 // of the state; every column of S is an independent recurrence, so slices never

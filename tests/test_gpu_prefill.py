@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import synth_inputs as si
-from helpers import check_prefill
+from helpers import check_prefill, rel_err, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -37,6 +37,24 @@ def test_fp32_packed_with_empty_sequence():
     x = si.make_varlen(lens, 2, 64, 64, "f32", -1.0, 9, 0.05)
     eo, eh = check_prefill(x, TOL_F32)
     print("fp32 packed: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp32_both_kernel_paths(d):
+    """With the workspace kda_chunk_fwd_workspace_size asks for, fp32 inputs run the parallel per-chunk
+    kernel and the matrix-core walk; with none, the single sequential kernel.  Both against the oracle,
+    and against each other."""
+    import paper_2510_26692_amd as kda
+    x = si.make_varlen([200, 0, 64, 321, 7], 2, d, d, "f32", -1.0, 23, 0.05)
+    eo, eh = check_prefill(x, TOL_F32, scale=0.5)                            # workspace allocated by the binding
+    eo2, eh2 = check_prefill(x, TOL_F32, scale=0.5, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    print("fp32 d=%d: with workspace %.2e %.2e, without %.2e %.2e" % (d, eo, eh, eo2, eh2))
+    dd = to_device(x)
+    a = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], cu_seqlens=dd["cu_seqlens"])
+    b = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], cu_seqlens=dd["cu_seqlens"],
+                          workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert rel_err(a[0].cpu().numpy(), b[0].cpu().numpy()) < 2e-5
+    assert rel_err(a[1].cpu().numpy(), b[1].cpu().numpy()) < 2e-5
 
 
 def test_fp32_strong_decay():

@@ -62,7 +62,13 @@ def test_workspace_sizes_are_consistent():
     assert 0 <= gated - full - slots * 16384 < 256
     assert kda.kda_chunk_fwd_min_workspace_size(d, output_gate=True) > small
     assert lib.kda_chunk_fwd_fused_workspace_size(ctypes.byref(d), None) == full
-    assert kda.kda_chunk_fwd_workspace_size(_dims(kda, in_dtype=0)) == 0          # fp32 path
+    # fp32 path: two packed C x (C+2) tiles and three C x d operand tiles (+ d) per chunk and head for the
+    # fast kernels, none at all for the single sequential kernel
+    f32 = _dims(kda, in_dtype=0)
+    n_ch = f32.num_seqs * ((f32.seqlen + 63) // 64) * f32.heads
+    want = 4 * n_ch * (2 * 64 * 66 + 3 * 64 * f32.dk + f32.dk)
+    assert 0 <= kda.kda_chunk_fwd_workspace_size(f32) - want < 2 * 256
+    assert kda.kda_chunk_fwd_min_workspace_size(f32) == 0
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, dk=96, dv=96)) == 0        # unsupported
     assert kda.kda_chunk_fwd_workspace_size(_dims(kda, seqlen=0)) == 0
 
