@@ -164,9 +164,10 @@ kda_status kda_chunk_fwd(const kda_dims *dims,
  * cannot overflow.
  *
  *   q, k, v, log_alpha, beta, h0, cu_seqlens   as for kda_chunk_fwd (in_dtype KDA_F32 or
- *                              KDA_BF16, dk == dv in {64, 128}; out_dtype is ignored)
- *   d_o        [B,T,H,dv]      fp32 gradient of o (rows of tokens owned by no sequence are
- *                              not read)
+ *                              KDA_BF16, dk == dv in {64, 128})
+ *   d_o        [B,T,H,dv]      gradient of o in out_dtype, i.e. the dtype o had: fp32, or bf16
+ *                              with bf16 inputs (rows of tokens owned by no sequence are not
+ *                              read)
  *   d_hT       [N,H,dk,dv]     fp32 gradient of the final states, or NULL for zeros
  *   dq, dk, dlog_alpha [B,T,H,dk], dv [B,T,H,dv], dbeta [B,T,H]    fp32, written; rows of
  *                              tokens owned by no sequence are left untouched
@@ -185,7 +186,7 @@ kda_status kda_chunk_bwd(const kda_dims *dims,
                          const void *q, const void *k, const void *v,
                          const void *log_alpha, const void *beta,
                          const float *h0, const int32_t *cu_seqlens,
-                         const float *d_o, const float *d_hT,
+                         const void *d_o, const float *d_hT,
                          float *dq, float *dk, float *dv, float *dlog_alpha, float *dbeta,
                          float *dh0,
                          void *workspace, size_t workspace_bytes,

@@ -40,7 +40,7 @@ kda_status chunk_f32_fast_dispatch(const kda_dims *, const void *, const void *,
                                    const void *, const float *, const int32_t *, void *, float *, void *,
                                    hipStream_t);
 kda_status chunk_bwd_dispatch(const kda_dims *, const void *, const void *, const void *, const void *,
-                              const void *, const float *, const int32_t *, const float *, const float *,
+                              const void *, const float *, const int32_t *, const void *, const float *,
                               float *, float *, float *, float *, float *, float *, void *, size_t,
                               hipStream_t);
 
@@ -170,7 +170,7 @@ size_t kda_chunk_bwd_workspace_size(const kda_dims *d)
 
 kda_status kda_chunk_bwd(const kda_dims *d, const void *q, const void *k, const void *v,
                          const void *log_alpha, const void *beta, const float *h0,
-                         const int32_t *cu_seqlens, const float *d_o, const float *d_hT,
+                         const int32_t *cu_seqlens, const void *d_o, const float *d_hT,
                          float *dq, float *dk, float *dv, float *dlog_alpha, float *dbeta, float *dh0,
                          void *workspace, size_t workspace_bytes, void *hip_stream)
 {

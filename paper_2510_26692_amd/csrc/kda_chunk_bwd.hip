@@ -663,11 +663,11 @@ void kda_fwd_scan_kernel(const Tin *__restrict__ v, const float *__restrict__ h0
 // ------------------------------------------------------------------------------------------
 // Backward walk with dS: dVn, dV = X, the dS1 of every chunk, dh0.
 // ------------------------------------------------------------------------------------------
-template <typename Tin, int D>
+template <typename Tdo, int D>
 __global__ __launch_bounds__(kScanThreads)
 void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict__ Tw,
                          const float *__restrict__ Ow,
-                         const float *__restrict__ d_o, const float *__restrict__ d_hT,
+                         const Tdo *__restrict__ d_o, const float *__restrict__ d_hT,
                          float *__restrict__ dSc,
                          float *__restrict__ dVnw, float *__restrict__ dv, float *__restrict__ dh0,
                          int64_t T, int H, int64_t chunks_per_seq, float scale)
@@ -691,7 +691,7 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
     const int64_t nchunks = (len + kC - 1) / kC;
     const int64_t slot_first = chunk_slot(cu, n, chunks_per_seq, 0) * H + h;     // slots of a sequence are H apart
     auto valid_rows = [&](int64_t ci) { return (int)((len - ci * kC < kC) ? (len - ci * kC) : kC); };
-    StepFetch<float, D, true> nxt;
+    StepFetch<Tdo, D, true> nxt;
     if (nchunks > 0)
         nxt.fetch(Ow + (slot_first + (nchunks - 1) * H) * (int64_t)operand_floats<D>(), d_o,
                   Tw + ((slot_first + (nchunks - 1) * H) * 2 + 1) * (int64_t)kTile,
@@ -832,11 +832,11 @@ __device__ __forceinline__ void lower_product(const float *sR, const float *sI, 
     }
 }
 
-template <typename Tin, int D>
+template <typename Tin, typename Tdo, int D>
 __global__ __launch_bounds__(kProductsThreads)
 void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ k,
                              const Tin *__restrict__ log_alpha, const int32_t *__restrict__ cu,
-                             const float *__restrict__ d_o, const float *__restrict__ Sc,
+                             const Tdo *__restrict__ d_o, const float *__restrict__ Sc,
                              const float *__restrict__ dSc, const float *__restrict__ Yw,
                              const float *__restrict__ Vnw, const float *__restrict__ dVnw,
                              const float *__restrict__ dv, float *__restrict__ dq,
@@ -875,7 +875,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
 
     rows_to_lds<Tin, kC, D, NT>(sG, LD, log_alpha + base, stride, nv, kLog2e, tid);
     load_state(S0);
-    load_rows(sOp, d_o, scale);
+    rows_to_lds<Tdo, kC, D, NT>(sOp, LD, d_o + base, stride, nv, scale, tid);
     __syncthreads();
     cumsum_rows<D, NT>(sG, sPart, sGend, tid);
 
@@ -955,7 +955,7 @@ void kda_bwd_products_kernel(const Tin *__restrict__ q, const Tin *__restrict__ 
     }
     // dP = Tril(dO Vn^T), dM = Tril(dVn Y^T): sOp holds Vn; the state area holds two row tiles
     float *sR = sS, *sI2 = sS + kC * LD;
-    load_rows(sR, d_o, scale);
+    rows_to_lds<Tdo, kC, D, NT>(sR, LD, d_o + base, stride, nv, scale, tid);
     __syncthreads();
     lower_product<D>(sR, sOp, Cw + slot * (int64_t)(2 * kC * kC), tid);
     __syncthreads();
@@ -1249,16 +1249,17 @@ static BwdPlan bwd_plan(const kda_dims *d, bool packed)
     return p;
 }
 
-template <typename Tin, int D>
+template <typename Tin, typename Tdo, int D>
 static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q_, const void *k_,
                              const void *v_, const void *la_, const void *beta_, const float *h0,
-                             const int32_t *cu, const float *d_o, const float *d_hT, float *dq,
+                             const int32_t *cu, const void *d_o_, const float *d_hT, float *dq,
                              float *dk, float *dv, float *dla, float *dbeta, float *dh0, char *ws,
                              hipStream_t stream)
 {
     const Tin *q = static_cast<const Tin *>(q_), *k = static_cast<const Tin *>(k_);
     const Tin *v = static_cast<const Tin *>(v_), *la = static_cast<const Tin *>(la_);
     const Tin *beta = static_cast<const Tin *>(beta_);
+    const Tdo *d_o = static_cast<const Tdo *>(d_o_);
     float *Sc = reinterpret_cast<float *>(ws + p.off_S), *dSc = reinterpret_cast<float *>(ws + p.off_dS);
     float *Yw = reinterpret_cast<float *>(ws + p.off_Y), *Vnw = reinterpret_cast<float *>(ws + p.off_Vn);
     float *dVnw = reinterpret_cast<float *>(ws + p.off_dVn), *gC = reinterpret_cast<float *>(ws + p.off_gC);
@@ -1271,8 +1272,8 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
     kda_status st;
     if ((st = reserve(kda_bwd_prep_kernel<Tin, D>, lds_prep, "kda_bwd_prep")) != KDA_OK) return st;
     if ((st = reserve(kda_bwd_states_kernel<Tin, D>, lds_states, "kda_bwd_states")) != KDA_OK) return st;
-    if ((st = reserve(kda_bwd_scan_kernel<Tin, D>, lds_scan, "kda_bwd_scan")) != KDA_OK) return st;
-    if ((st = reserve(kda_bwd_products_kernel<Tin, D>, lds_prod, "kda_bwd_products")) != KDA_OK) return st;
+    if ((st = reserve(kda_bwd_scan_kernel<Tdo, D>, lds_scan, "kda_bwd_scan")) != KDA_OK) return st;
+    if ((st = reserve(kda_bwd_products_kernel<Tin, Tdo, D>, lds_prod, "kda_bwd_products")) != KDA_OK) return st;
     if ((st = reserve(kda_bwd_chain_kernel<Tin, D>, lds_chain, "kda_bwd_chain")) != KDA_OK) return st;
 
     const int H = dm->heads;
@@ -1284,10 +1285,10 @@ static kda_status launch_bwd(const kda_dims *dm, const BwdPlan &p, const void *q
                            Tw, Ow, T, H, p.chunks_per_seq);
     hipLaunchKernelGGL((kda_bwd_states_kernel<Tin, D>), gscan, dim3(kScanThreads), lds_states, stream, v, h0, cu, Tw, Ow,
                        Sc, Yw, Vnw, T, H, p.chunks_per_seq);
-    hipLaunchKernelGGL((kda_bwd_scan_kernel<Tin, D>), gscan, dim3(kScanThreads), lds_scan, stream, cu, Tw, Ow,
+    hipLaunchKernelGGL((kda_bwd_scan_kernel<Tdo, D>), gscan, dim3(kScanThreads), lds_scan, stream, cu, Tw, Ow,
                        d_o, d_hT, dSc, dVnw, dv, dh0, T, H, p.chunks_per_seq, dm->scale);
     if (p.max_chunks > 0) {
-        hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, D>), gchunk, dim3(kProductsThreads), lds_prod, stream, q, k, la, cu,
+        hipLaunchKernelGGL((kda_bwd_products_kernel<Tin, Tdo, D>), gchunk, dim3(kProductsThreads), lds_prod, stream, q, k, la, cu,
                            d_o, Sc, dSc, Yw, Vnw, dVnw, dv, dq, dk, dla, gC, Cw, T, H, p.chunks_per_seq,
                            dm->scale);
         hipLaunchKernelGGL((kda_bwd_chain_kernel<Tin, D>), gchunk, dim3(kChainThreads), lds_chain, stream, q, k, la, beta,
@@ -1345,7 +1346,7 @@ size_t chunk_bwd_workspace_size(const kda_dims *d)
 
 kda_status chunk_bwd_dispatch(const kda_dims *dm, const void *q, const void *k, const void *v,
                               const void *log_alpha, const void *beta, const float *h0,
-                              const int32_t *cu, const float *d_o, const float *d_hT, float *dq,
+                              const int32_t *cu, const void *d_o, const float *d_hT, float *dq,
                               float *dk, float *dv, float *dla, float *dbeta, float *dh0,
                               void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
@@ -1356,10 +1357,13 @@ kda_status chunk_bwd_dispatch(const kda_dims *dm, const void *q, const void *k, 
         return fail(KDA_ERR_UNSUPPORTED, "kda_chunk_bwd: sequences longer than %d tokens", 65535 * kC);
     char *ws = static_cast<char *>(workspace);
     const bool bf = dm->in_dtype == KDA_BF16;
-#define KDA_BWD(TIN, DD) launch_bwd<TIN, DD>(dm, p, q, k, v, log_alpha, beta, h0, cu, d_o, d_hT, dq, dk, dv, dla, \
-                                             dbeta, dh0, ws, stream)
-    if (dm->dk == 128) return bf ? KDA_BWD(__hip_bfloat16, 128) : KDA_BWD(float, 128);
-    return bf ? KDA_BWD(__hip_bfloat16, 64) : KDA_BWD(float, 64);
+#define KDA_BWD(TIN, TDO, DD) launch_bwd<TIN, TDO, DD>(dm, p, q, k, v, log_alpha, beta, h0, cu, d_o, d_hT, dq, dk, dv, \
+                                                       dla, dbeta, dh0, ws, stream)
+    // d_o has dims->out_dtype: fp32, or bf16 (bf16 inputs only)
+    if (dm->out_dtype == KDA_BF16)
+        return dm->dk == 128 ? KDA_BWD(__hip_bfloat16, __hip_bfloat16, 128) : KDA_BWD(__hip_bfloat16, __hip_bfloat16, 64);
+    if (dm->dk == 128) return bf ? KDA_BWD(__hip_bfloat16, float, 128) : KDA_BWD(float, float, 128);
+    return bf ? KDA_BWD(__hip_bfloat16, float, 64) : KDA_BWD(float, float, 64);
 #undef KDA_BWD
 }
 

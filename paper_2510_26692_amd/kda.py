@@ -288,8 +288,8 @@ def kda_chunk_bwd_workspace_size(dims):
 
 def kda_chunk_bwd(q, k, v, log_alpha, beta, do, dhT=None, h0=None, cu_seqlens=None, scale=1.0,
                   want_dh0=True, workspace=None, max_seqlen=0):
-    """Backward pass of kda_chunk_fwd.  Inputs as there; do fp32 [B,T,H,dv]; dhT fp32 [N,H,dk,dv] or
-    None.  Returns a dict of fp32 tensors dq, dk, dlog_alpha [B,T,H,dk], dv [B,T,H,dv], dbeta [B,T,H]
+    """Backward pass of kda_chunk_fwd.  Inputs as there; do [B,T,H,dv] fp32, or bf16 with bf16 inputs;
+    dhT fp32 [N,H,dk,dv] or None.  Returns a dict of fp32 tensors dq, dk, dlog_alpha [B,T,H,dk], dv [B,T,H,dv], dbeta [B,T,H]
     and dh0 [N,H,dk,dv] (None unless want_dh0); rows of tokens that belong to no sequence are zero
     (this wrapper allocates the gradients zero-filled; the library leaves such rows untouched)."""
     lib = load_library()
@@ -300,10 +300,10 @@ def kda_chunk_bwd(q, k, v, log_alpha, beta, do, dhT=None, h0=None, cu_seqlens=No
     dv = v.shape[-1]
     if k.shape != q.shape or log_alpha.shape != q.shape or v.shape != (B, T, H, dv) or beta.shape != (B, T, H):
         raise ValueError("inconsistent input shapes")
-    dims = make_chunk_dims(q, v, cu_seqlens, scale, max_seqlen, torch.float32)
+    if do.dtype not in _DTYPE_CODE or do.shape != (B, T, H, dv):
+        raise ValueError("do must be fp32 or bf16 [B,T,H,dv]")
+    dims = make_chunk_dims(q, v, cu_seqlens, scale, max_seqlen, do.dtype)        # do has the dtype o had
     N = dims.num_seqs
-    if do.dtype != torch.float32 or do.shape != (B, T, H, dv):
-        raise ValueError("do must be fp32 [B,T,H,dv]")
     for name, t in (("dhT", dhT), ("h0", h0)):
         if t is not None and (t.dtype != torch.float32 or t.shape != (N, H, dk, dv)):
             raise ValueError("%s must be fp32 [N,H,dk,dv]" % name)

@@ -41,7 +41,7 @@ def _run(x, do, dhT, scale=1.0, **kw):
     cu = None if x.get("cu_seqlens") is None else x["cu_seqlens"].cpu().numpy().astype(np.int64)
     h0 = None if x.get("h0") is None else x["h0"].numpy().astype(np.float64)
     ref = oracle.kda_backward(si.to_np32(x["q"]), si.to_np32(x["k"]), si.to_np32(x["v"]),
-                              si.to_np32(x["log_alpha"]), si.to_np32(x["beta"]), do.numpy(),
+                              si.to_np32(x["log_alpha"]), si.to_np32(x["beta"]), do.float().numpy(),
                               dhT=None if dhT is None else dhT.numpy(), h0=h0, cu_seqlens=cu, scale=scale)
     return {n: out[n].cpu().numpy() for n in NAMES}, ref, cu
 
@@ -160,3 +160,15 @@ def test_backward_cfg1_full_size():
     print("cfg1", {k: "%.2e" % v for k, v in errs.items()})
     for name, e in errs.items():
         assert e <= TOL, "%s error %.3e exceeds %.1e" % (name, e, TOL)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_backward_takes_bf16_output_gradients(d):
+    """d_o in bf16 (the dtype o may have with bf16 inputs): widened exactly, so the same bound holds
+    against the oracle fed the same bf16 values."""
+    x = si.make_varlen([150, 3, 64], 2, d, d, "bf16", -2.0, 1214, 0.05)
+    do, dhT = _grad_inputs(x, 82)
+    do = do.to(torch.bfloat16)
+    got, ref, cu = _run(x, do, dhT, scale=d ** -0.5)
+    for name in NAMES:
+        assert rel_err(got[name], ref[name]) <= TOL, name
