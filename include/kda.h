@@ -84,9 +84,10 @@ typedef enum { KDA_F32 = 0, KDA_BF16 = 1 } kda_dtype;
  *   Packed batch       : cu_seqlens != NULL, batch == 1, `seqlen` is the total
  *                        number of packed tokens, sequence n owns tokens
  *                        [cu_seqlens[n], cu_seqlens[n+1]).
- * Supported: dk == dv in {64, 128}, chunk == 64, in_dtype KDA_F32 (any of the
- * two head dims) or KDA_BF16 (head dim 128).  out_dtype KDA_F32 always;
- * KDA_BF16 with in_dtype KDA_BF16 (o is computed in fp32 and rounded to
+ * Supported: dk == dv in {64, 128}, chunk == 64, in_dtype KDA_F32 or KDA_BF16
+ * (bf16 inputs with head dim 64 are processed by the fp32 kernels: exact
+ * widening, fp32 arithmetic, fp32 o).  out_dtype KDA_F32 always; KDA_BF16 with
+ * in_dtype KDA_BF16 and head dim 128 (o is computed in fp32 and rounded to
  * nearest even once, when it is stored; states stay fp32).
  */
 typedef struct {

@@ -106,6 +106,7 @@ static kda_status check_dims(const kda_dims *d, bool packed)
 static bool mfma_path(const kda_dims *d)
 {
     if (d->in_dtype != KDA_BF16) return false;
+    if (d->dk != 128) return false;                     // bf16 inputs with head dim 64 take the fp32 kernels
     const char *force = getenv("KDA_CHUNK_IMPL");       // debugging switch: "f32" forces the
     if (force && strcmp(force, "f32") == 0) return false;  // fp32 kernel for bf16 inputs too
     return true;
@@ -247,11 +248,9 @@ static kda_status chunk_fwd_impl(const kda_dims *d, const kda_prologue *pro, con
     if (d->num_seqs == 0 || d->heads == 0) return KDA_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    if (d->in_dtype == KDA_BF16 && d->dk != 128 && mfma_path(d))
-        return fail(KDA_ERR_UNSUPPORTED, "bf16 prefill is built for dk == dv == 128 only");
     if (!mfma_path(d)) {
         if (pro || epi) return fail(KDA_ERR_UNSUPPORTED, "the fused stages need the matrix-core prefill");
-        if (d->out_dtype != KDA_F32) return fail(KDA_ERR_UNSUPPORTED, "the fp32 prefill kernel writes fp32 outputs only");
+        if (d->out_dtype != KDA_F32) return fail(KDA_ERR_UNSUPPORTED, "the fp32 prefill kernels write fp32 outputs only");
         const size_t fast = d->seqlen == 0 ? 0 : chunk_f32_fast_workspace_size(d);
         if (fast > 0 && workspace && workspace_bytes >= fast && !(reinterpret_cast<uintptr_t>(workspace) & 255u))
             return chunk_f32_fast_dispatch(d, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace, stream);

@@ -57,6 +57,13 @@ def test_fp32_both_kernel_paths(d):
     assert rel_err(a[1].cpu().numpy(), b[1].cpu().numpy()) < 2e-5
 
 
+def test_bf16_inputs_with_head_dim_64_take_the_fp32_kernels():
+    """bf16 values are exact in fp32, so the fp32 tolerance applies."""
+    x = si.make_varlen([130, 64, 0, 9], 3, 64, 64, "bf16", -2.0, 24, 0.05)
+    eo, eh = check_prefill(x, TOL_F32, scale=0.125)
+    print("bf16 inputs, d=64: err_o %.2e err_hT %.2e" % (eo, eh))
+
+
 def test_fp32_strong_decay():
     """log alpha down to about -20 per token: the pairwise log-domain products must
     neither overflow nor lose the surviving terms."""
