@@ -223,9 +223,11 @@ def main():
         d_o = torch.randn(o.shape, generator=torch.Generator().manual_seed(c["seed"] + 1)).to(dev)
         ws_b = torch.empty(kda.kda_chunk_bwd_workspace_size(dims), dtype=torch.uint8, device=dev)
 
+        grads = kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], d_o, h0=x["h0"], workspace=ws_b)
+
         def backward():
             return kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], d_o, h0=x["h0"],
-                                     workspace=ws_b)
+                                     workspace=ws_b, out=grads)
         backward()
         steps_b = max(3, min(args.steps, 10))
         ms_bwd = _time_region(torch, backward, steps_b)
@@ -254,7 +256,7 @@ def main():
                                             "sample": "first %d tokens of every sequence, %d times over, fp64 "
                                                       "token-by-token reverse pass" % (n_s, reps),
                                             "seconds": dtb}
-        del d_o, ws_b
+        del d_o, ws_b, grads
 
     # the same prefill on raw projections (fused input prologue), cfg1 shape only
     fused_obj = None

@@ -287,11 +287,12 @@ def kda_chunk_bwd_workspace_size(dims):
 
 
 def kda_chunk_bwd(q, k, v, log_alpha, beta, do, dhT=None, h0=None, cu_seqlens=None, scale=1.0,
-                  want_dh0=True, workspace=None, max_seqlen=0):
+                  want_dh0=True, workspace=None, max_seqlen=0, out=None):
     """Backward pass of kda_chunk_fwd.  Inputs as there; do [B,T,H,dv] fp32, or bf16 with bf16 inputs;
     dhT fp32 [N,H,dk,dv] or None.  Returns a dict of fp32 tensors dq, dk, dlog_alpha [B,T,H,dk], dv [B,T,H,dv], dbeta [B,T,H]
     and dh0 [N,H,dk,dv] (None unless want_dh0); rows of tokens that belong to no sequence are zero
-    (this wrapper allocates the gradients zero-filled; the library leaves such rows untouched)."""
+    (this wrapper allocates the gradients zero-filled; the library leaves such rows untouched).  `out`:
+    the dict an earlier call returned, to be written in place instead of allocating."""
     lib = load_library()
     dev = _check_dev(q, k, v, log_alpha, beta, do, dhT, h0, cu_seqlens, workspace)
     if not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype) or q.dtype not in _DTYPE_CODE:
@@ -310,10 +311,19 @@ def kda_chunk_bwd(q, k, v, log_alpha, beta, do, dhT=None, h0=None, cu_seqlens=No
     if cu_seqlens is not None and cu_seqlens.dtype != torch.int32:
         raise ValueError("cu_seqlens must be int32")
     f32 = dict(dtype=torch.float32, device=dev)
-    out = {"dq": torch.zeros(B, T, H, dk, **f32), "dk": torch.zeros(B, T, H, dk, **f32),
-           "dv": torch.zeros(B, T, H, dv, **f32), "dlog_alpha": torch.zeros(B, T, H, dk, **f32),
-           "dbeta": torch.zeros(B, T, H, **f32),
-           "dh0": torch.empty(N, H, dk, dv, **f32) if want_dh0 else None}
+    shapes = {"dq": (B, T, H, dk), "dk": (B, T, H, dk), "dv": (B, T, H, dv), "dlog_alpha": (B, T, H, dk),
+              "dbeta": (B, T, H), "dh0": (N, H, dk, dv)}
+    if out is None:
+        out = {n_: torch.zeros(*sh, **f32) for n_, sh in shapes.items() if n_ != "dh0"}
+        out["dh0"] = torch.empty(*shapes["dh0"], **f32) if want_dh0 else None
+    else:                                   # the dict of an earlier call with the same shapes, written in place
+        for n_, sh in shapes.items():
+            t = out.get(n_)
+            if t is None and n_ == "dh0":
+                continue
+            if t is None or t.dtype != torch.float32 or tuple(t.shape) != sh or not t.is_contiguous():
+                raise ValueError("out[%r] must be a contiguous fp32 tensor of shape %r" % (n_, sh))
+        _check_dev(q, *[t for t in out.values() if t is not None])
     if workspace is None:
         need = kda_chunk_bwd_workspace_size(dims)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev) if need else None

@@ -198,3 +198,21 @@ def test_backward_cfg2_packed_full_size_sampled_heads():
         got = got[:, heads] if name == "dh0" else got[:, :, heads]
         e = rel_err(got, ref[name])
         assert e <= TOL, "%s error %.3e exceeds %.1e" % (name, e, TOL)
+
+
+def test_backward_binding_reuses_the_output_tensors_it_is_given():
+    import paper_2510_26692_amd as kda
+    x = to_device(si.make_prefill(1, 130, 2, 128, 128, "bf16", -2.0, 1215, 0.05))
+    do = torch.randn(1, 130, 2, 128, device="cuda")
+    first = kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], do, h0=x["h0"])
+    keep = {n: t.clone() for n, t in first.items()}
+    ptrs = {n: t.data_ptr() for n, t in first.items()}
+    for t in first.values():
+        t.fill_(7.0)
+    again = kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], do, h0=x["h0"], out=first)
+    torch.cuda.synchronize()
+    for n in NAMES:
+        assert again[n].data_ptr() == ptrs[n] and torch.equal(again[n], keep[n]), n
+    with pytest.raises(ValueError):
+        kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], do, h0=x["h0"],
+                          out={**first, "dq": first["dq"][:, :64]})
