@@ -108,8 +108,15 @@ struct RowsFetch {
             float f[EPV];
             unpack16(buf[u], (const Tin *)nullptr, f);
             if (vi < TOTAL) {
+                float *p = dst + r * ld + cv * EPV;
+                if ((ld & 3) == 0) {                     // rows 16-byte aligned: whole 16-byte stores (dst is)
 #pragma unroll
-                for (int e = 0; e < EPV; ++e) dst[r * ld + cv * EPV + e] = mul * f[e];
+                    for (int e = 0; e < EPV; e += 4)
+                        *reinterpret_cast<float4 *>(p + e) = make_float4(mul * f[e], mul * f[e + 1], mul * f[e + 2], mul * f[e + 3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) p[e] = mul * f[e];
+                }
             }
         }
     }
@@ -212,7 +219,7 @@ struct StepFetch {
     __device__ __forceinline__ void commit(float *sQ, float *sK, float *sG, float *sA, float *sSlice,
                                            float *sGend, float slice_mul, int tid) const
     {
-        constexpr int LD = D + 1;
+        constexpr int LD = D + 4;           // as in the scan kernels
         ft.commit(sA, tid);
         if (kWithQ) fq.commit(sQ, LD, 1.f, tid);
         fkg.commit(sG, LD, 1.f, tid);
@@ -448,12 +455,12 @@ template <int D> constexpr size_t prep_lds_floats() { return 3 * kC * (D + 1) + 
 
 template <int D> constexpr size_t scan_lds_floats()          // kda_bwd_scan
 {
-    return 3 * kC * (D + 1) + kC * kLA + 3 * kC * kBV + D * kBV + D;
+    return 3 * kC * (D + 4) + kC * kLA + 3 * kC * kBV + D * kBV + D;
 }
 
 template <int D> constexpr size_t states_lds_floats()        // kda_bwd_states
 {
-    return 2 * kC * (D + 1) + kC * kLA + 2 * kC * kBV + D * kBV + D;
+    return 2 * kC * (D + 4) + kC * kLA + 2 * kC * kBV + D * kBV + D;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -468,7 +475,7 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
                            int64_t T, int H,
                            int64_t chunks_per_seq)
 {
-    constexpr int LD = D + 1;
+    constexpr int LD = D + 4;          // rows 16-byte aligned: the operand tiles are written 16 bytes at a time
     extern __shared__ float smem[];
     float *sK = smem, *sG = sK + kC * LD, *sA = sG + kC * LD;        // Gamma^{i->C}.K, Gamma.K, M | A_qk
     float *sV = sA + kC * kLA, *sVn = sV + kC * kBV;                 // V slice -> Y, V_new
@@ -559,7 +566,7 @@ void kda_bwd_states_kernel(const Tin *__restrict__ v, const float *__restrict__ 
 // ------------------------------------------------------------------------------------------
 template <int D> constexpr size_t fwd_scan_lds_floats()
 {
-    return 3 * kC * (D + 1) + kC * kLA + 2 * kC * kBV + D * kBV + D;
+    return 3 * kC * (D + 4) + kC * kLA + 2 * kC * kBV + D * kBV + D;
 }
 
 template <typename Tin, int D>
@@ -569,7 +576,7 @@ void kda_fwd_scan_kernel(const Tin *__restrict__ v, const float *__restrict__ h0
                          const float *__restrict__ Ow, float *__restrict__ o, float *__restrict__ hT,
                          int64_t T, int H, int64_t chunks_per_seq, float scale)
 {
-    constexpr int LD = D + 1;
+    constexpr int LD = D + 4;          // rows 16-byte aligned: the operand tiles are written 16 bytes at a time
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;   // Gamma.Q, Gamma^{i->C}.K, Gamma.K, M | A_qk
     float *sV = sA + kC * kLA, *sVn = sV + kC * kBV;                 // V slice -> Y -> O, V_new
@@ -672,7 +679,7 @@ void kda_bwd_scan_kernel(const int32_t *__restrict__ cu, const float *__restrict
                          float *__restrict__ dVnw, float *__restrict__ dv, float *__restrict__ dh0,
                          int64_t T, int H, int64_t chunks_per_seq, float scale)
 {
-    constexpr int LD = D + 1;
+    constexpr int LD = D + 4;          // rows 16-byte aligned: the operand tiles are written 16 bytes at a time
     extern __shared__ float smem[];
     float *sQ = smem, *sK = sQ + kC * LD, *sG = sK + kC * LD, *sA = sG + kC * LD;
     float *sdO = sA + kC * kLA, *sdVn = sdO + kC * kBV, *sX = sdVn + kC * kBV;
