@@ -176,3 +176,65 @@ def test_packed_batch_equals_separate_calls_and_stray_tokens_get_zero():
         assert np.abs(gr[name][:, int(cu[-1]):]).max() == 0.0
     # an empty sequence hands its final-state gradient straight to its initial state
     np.testing.assert_array_equal(gr["dh0"][1], dhT[1])
+
+
+def test_planted_mistakes_in_a_reverse_pass_are_caught_by_the_finite_difference_pin():
+    """Sanity of the pins themselves: a numpy reverse pass with one plausible mistake at a time (a dropped
+    term, a wrong sign, a missing decay, the undecayed state, the old state in place of the new one) is compared with central differences of the chunkwise forward exactly as the first pin does;
+    the faithful version passes at 2e-7, every planted version misses some gradient by more than 1e-3."""
+    rng = np.random.default_rng(107)
+    T, dk, dv = 9, 3, 4
+    q, k, v, g, b = (x[0, :, 0].astype(np.float64) for x in _inputs(rng, 1, T, 1, dk, dv))
+    S0 = rng.standard_normal((dk, dv))
+    do = rng.standard_normal((T, dv))
+    dST = rng.standard_normal((dk, dv))
+
+    def reverse(mistake=None):
+        states = [S0]
+        for t in range(T):
+            Sp = np.exp(g[t])[:, None] * states[-1]
+            states.append(Sp + b[t] * np.outer(k[t], v[t] - Sp.T @ k[t]))
+        D = dST.copy()
+        out = {n: np.zeros_like(x) for n, x in (("dq", q), ("dk", k), ("dv", v), ("dlog_alpha", g), ("dbeta", b))}
+        for t in range(T - 1, -1, -1):
+            a = np.exp(g[t])[:, None]
+            Sp = a * states[t]
+            u = v[t] - Sp.T @ k[t]
+            St = states[t] if mistake == "old_state_in_dq" else states[t + 1]
+            D = D + np.outer(q[t], do[t])
+            out["dq"][t] = St @ do[t]
+            out["dbeta"][t] = k[t] @ D @ u
+            du = b[t] * (D.T @ k[t])
+            out["dv"][t] = du
+            corr = 0.0 if mistake == "dropped_correction_in_dk" else Sp @ du
+            out["dk"][t] = b[t] * (D @ u) + (corr if mistake == "wrong_sign_in_dk" else -corr)
+            Dp = D if mistake == "dropped_rank_one_in_dS" else D - np.outer(k[t], du)
+            out["dlog_alpha"][t] = (Dp * (states[t] if mistake == "undecayed_state_in_dlog_alpha" else Sp)).sum(axis=1)
+            D = Dp if mistake == "no_decay_of_dS" else a * Dp
+        out["dh0"] = D
+        return out
+
+    def loss(args):
+        o, hT = kda_chunkwise(*[x[None, :, None] for x in args[:5]], h0=args[5][None, None], C=4)
+        return float((o[0, :, 0] * do).sum() + (hT[0, 0] * dST).sum())
+
+    base = [q, k, v, g, b, S0]
+    h = 1e-6
+    numeric = {}
+    for which, name in enumerate(NAMES):
+        num = np.zeros_like(base[which])
+        for idx in np.ndindex(*base[which].shape):
+            plus = [x.copy() for x in base]
+            minus = [x.copy() for x in base]
+            plus[which][idx] += h
+            minus[which][idx] -= h
+            num[idx] = (loss(plus) - loss(minus)) / (2 * h)
+        numeric[name] = num
+
+    def worst(grads):
+        return max(np.abs(grads[n] - numeric[n]).max() / np.abs(numeric[n]).max() for n in NAMES)
+
+    assert worst(reverse()) < 2e-7
+    for mistake in ("old_state_in_dq", "dropped_correction_in_dk", "wrong_sign_in_dk", "dropped_rank_one_in_dS",
+                    "undecayed_state_in_dlog_alpha", "no_decay_of_dS"):
+        assert worst(reverse(mistake)) > 1e-3, mistake
