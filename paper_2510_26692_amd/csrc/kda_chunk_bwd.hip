@@ -1346,9 +1346,14 @@ static kda_status launch_fwd(const kda_dims *dm, const FwdPlan &p, const void *q
 
 }  // namespace
 
+// The size entry points do not see cu_seqlens.  A batch of one row may or may not come with it, and the
+// packed layout (one extra slot per sequence) is the larger of the two, so a single row is sized as packed:
+// whatever the dispatcher then lays out fits.
+static bool sized_as_packed(const kda_dims *d) { return d->num_seqs != d->batch || d->batch == 1; }
+
 size_t chunk_bwd_workspace_size(const kda_dims *d)
 {
-    return bwd_plan(d, d->num_seqs != d->batch).total;
+    return bwd_plan(d, sized_as_packed(d)).total;
 }
 
 kda_status chunk_bwd_dispatch(const kda_dims *dm, const void *q, const void *k, const void *v,
@@ -1358,8 +1363,10 @@ kda_status chunk_bwd_dispatch(const kda_dims *dm, const void *q, const void *k, 
                               void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
     const BwdPlan p = bwd_plan(dm, cu != nullptr);
-    if (p.total > workspace_bytes || (p.total && !workspace))
-        return fail(KDA_ERR_WORKSPACE, "kda_chunk_bwd needs %zu B of workspace, got %zu", p.total, workspace_bytes);
+    // (the size the library reports is the requirement, even where this call's own layout is smaller)
+    const size_t need = chunk_bwd_workspace_size(dm) > p.total ? chunk_bwd_workspace_size(dm) : p.total;
+    if (need > workspace_bytes || (need && !workspace))
+        return fail(KDA_ERR_WORKSPACE, "kda_chunk_bwd needs %zu B of workspace, got %zu", need, workspace_bytes);
     if (p.max_chunks > 65535)
         return fail(KDA_ERR_UNSUPPORTED, "kda_chunk_bwd: sequences longer than %d tokens", 65535 * kC);
     char *ws = static_cast<char *>(workspace);
@@ -1379,7 +1386,7 @@ kda_status chunk_bwd_dispatch(const kda_dims *dm, const void *q, const void *k, 
 // single-kernel path of kda_chunk_f32.hip serves).
 size_t chunk_f32_fast_workspace_size(const kda_dims *d)
 {
-    const FwdPlan p = fwd_plan(d, d->num_seqs != d->batch);
+    const FwdPlan p = fwd_plan(d, sized_as_packed(d));
     return p.max_chunks > 65535 ? 0 : p.total;
 }
 

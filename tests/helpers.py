@@ -50,13 +50,61 @@ def to_device(d, dev="cuda"):
     return {k: (v.to(dev) if isinstance(v, torch.Tensor) else v) for k, v in d.items()}
 
 
+GUARD_BYTES = 4096
+GUARD_FILL = 0xA5
+
+
+class Guarded:
+    """A device tensor carved out of a larger byte buffer, with GUARD_BYTES of a known pattern on
+    both sides: a kernel that writes past either end of the tensor changes the pattern."""
+
+    def __init__(self, shape, dtype, device="cuda", fill=None):
+        numel = 1
+        for s_ in shape:
+            numel *= int(s_)
+        nbytes = numel * torch.empty((), dtype=dtype).element_size()
+        self.body = (nbytes + 255) // 256 * 256
+        self.nbytes = nbytes
+        self.raw = torch.full((2 * GUARD_BYTES + self.body,), GUARD_FILL, dtype=torch.uint8, device=device)
+        self.tensor = self.raw[GUARD_BYTES:GUARD_BYTES + nbytes].view(dtype).view(*shape)
+        if fill is not None:
+            self.tensor.fill_(fill)
+
+    def assert_untouched(self, what):
+        torch.cuda.synchronize()
+        front = self.raw[:GUARD_BYTES]
+        back = self.raw[GUARD_BYTES + self.nbytes:]
+        assert bool((front == GUARD_FILL).all()), "bytes in front of %s were overwritten" % what
+        assert bool((back == GUARD_FILL).all()), "bytes behind %s were overwritten" % what
+
+
 def check_prefill(d, tol, scale=1.0, **kw):
-    """GPU chunk forward vs oracle on the same tensors; returns (err_o, err_hT)."""
+    """GPU chunk forward vs oracle on the same tensors; returns (err_o, err_hT).  o, hT and (unless the
+    caller brings one) the workspace sit between guard regions that must come back untouched."""
     import paper_2510_26692_amd as kda
     dd = to_device(d)
+    B, T, H, _ = d["q"].shape
+    dv = d["v"].shape[-1]
+    N = B if dd.get("cu_seqlens") is None else dd["cu_seqlens"].numel() - 1
+    guards = {}
+    if "o" not in kw:
+        guards["o"] = Guarded((B, T, H, dv), kw.get("out_dtype") or torch.float32, fill=0)
+        kw["o"] = guards["o"].tensor
+    if "hT" not in kw and kw.get("want_hT", True):
+        guards["hT"] = Guarded((N, H, d["q"].shape[-1], dv), torch.float32)
+        kw["hT"] = guards["hT"].tensor
+    if "workspace" not in kw:
+        dims = kda.kda.make_chunk_dims(dd["q"], dd["v"], dd.get("cu_seqlens"), scale, kw.get("max_seqlen", 0),
+                                       kw["o"].dtype)
+        need = kda.kda_chunk_fwd_workspace_size(dims)
+        if need:
+            guards["workspace"] = Guarded((need,), torch.uint8)
+            kw["workspace"] = guards["workspace"].tensor
     o, hT = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"],
                               h0=dd.get("h0"), cu_seqlens=dd.get("cu_seqlens"), scale=scale, check=True, **kw)
     torch.cuda.synchronize()
+    for name, g in guards.items():
+        g.assert_untouched(name)
     o_ref, hT_ref = oracle_prefill(d, scale)
     B, T, H, _ = d["q"].shape
     cu = None if d.get("cu_seqlens") is None else d["cu_seqlens"].cpu().numpy()

@@ -74,6 +74,10 @@ CASES = {
     "fp32_inputs_d64": lambda: (si.make_prefill(2, 150, 2, 64, 64, "f32", -2.0, 1204, 0.05), 0.125),
     "fp32_inputs_d128": lambda: (si.make_prefill(1, 131, 2, 128, 128, "f32", -1.0, 1205, 0.05), 1.0),
     "packed": lambda: (si.make_varlen([70, 0, 5, 129, 64, 300], 2, 128, 128, "bf16", -2.0, 1206, 0.05), 1.0),
+    # one row that arrives as a packed batch of one sequence (cu_seqlens = [0, T]), T a multiple of the chunk or
+    # not: the packed slot layout has one slot more than the plain one, and the workspace is sized for it
+    "packed_single_128": lambda: (si.make_varlen([128], 2, 128, 128, "bf16", -2.0, 1211, 0.05), 1.0),
+    "packed_single_130_f32": lambda: (si.make_varlen([130], 2, 64, 64, "f32", -1.0, 1212, 0.05), 0.5),
     "bf16_inputs_d64": lambda: (si.make_prefill(2, 100, 2, 64, 64, "bf16", -2.0, 1208, 0.05), 1.0),
     "slow_decay_128_chunks": lambda: (si.make_prefill(1, 64 * 128, 1, 128, 128, "bf16", -6.0, 1209, 0.3), 128 ** -0.5),
     "slow_decay_long": lambda: (si.make_prefill(1, 64 * 20 + 9, 2, 128, 128, "bf16", -6.0, 1207, 0.05), 1.0),

@@ -39,6 +39,17 @@ def test_fp32_packed_with_empty_sequence():
     print("fp32 packed: err_o %.2e err_hT %.2e" % (eo, eh))
 
 
+@pytest.mark.parametrize("T", [64, 128, 130])
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp32_single_sequence_as_packed_batch(T, d):
+    """One row given as a packed batch of one sequence (cu_seqlens = [0, T]).  The packed slot layout
+    holds floor(T / 64) + 1 slots where the plain one holds ceil(T / 64); the workspace the library
+    asks for covers it (check_prefill puts guard regions around the workspace, o and h_T)."""
+    x = si.make_varlen([T], 2, d, d, "f32", -1.0, 40 + T + d, 0.05)
+    eo, eh = check_prefill(x, TOL_F32)
+    print("fp32 packed single T=%d d=%d: err_o %.2e err_hT %.2e" % (T, d, eo, eh))
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_fp32_both_kernel_paths(d):
     """With the workspace kda_chunk_fwd_workspace_size asks for, fp32 inputs run the parallel per-chunk

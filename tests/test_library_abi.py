@@ -64,8 +64,9 @@ def test_workspace_sizes_are_consistent():
     assert lib.kda_chunk_fwd_fused_workspace_size(ctypes.byref(d), None) == full
     # fp32 path: two packed C x (C+2) tiles and three C x d operand tiles (+ d) per chunk and head for the
     # fast kernels, none at all for the single sequential kernel
+    # (a single row may arrive with cu_seqlens: it is sized for the packed layout, one more slot per sequence)
     f32 = _dims(kda, in_dtype=0)
-    n_ch = f32.num_seqs * ((f32.seqlen + 63) // 64) * f32.heads
+    n_ch = (f32.seqlen // 64 + f32.num_seqs) * f32.heads
     want = 4 * n_ch * (2 * 64 * 66 + 3 * 64 * f32.dk + f32.dk)
     assert 0 <= kda.kda_chunk_fwd_workspace_size(f32) - want < 2 * 256
     assert kda.kda_chunk_fwd_min_workspace_size(f32) == 0
@@ -113,13 +114,30 @@ def test_chunk_fwd_rejects_null_misaligned_and_missing_workspace():
 
 def test_chunk_bwd_workspace_size_and_rejections_without_launching():
     kda, lib = _lib()
-    d = _dims(kda)                      # B=2? whatever _dims builds: the size follows from its fields
+    d = _dims(kda, batch=2, num_seqs=2)
     D, C = d.dk, 64
+
+    def floats_for(chunks, tokens):
+        return chunks * (2 * D * D + D + 2 * C * C + 2 * C * (C + 2) + 3 * C * D + D) + 3 * tokens * D
     chunks = d.num_seqs * ((d.seqlen + C - 1) // C) * d.heads
     tokens = d.batch * d.seqlen * d.heads
     need = kda.kda_chunk_bwd_workspace_size(d)
-    floats = chunks * (2 * D * D + D + 2 * C * C + 2 * C * (C + 2) + 3 * C * D + D) + 3 * tokens * D
-    assert 0 <= need - 4 * floats < 9 * 256              # nine areas, each rounded up to 256 bytes
+    assert 0 <= need - 4 * floats_for(chunks, tokens) < 9 * 256      # nine areas, each rounded up to 256 bytes
+    # The size entry points never see cu_seqlens.  One row (B = N = 1) may be a packed batch of one
+    # sequence, whose chunks are laid out at floor(T / C) + N slots, so it is sized for that layout:
+    # the plan of either dispatch then fits what the library asked for.
+    for T in (64, 128, 130, 4096):
+        one = _dims(kda, seqlen=T)
+        packed_slots = (T // C + 1) * one.heads
+        plain_slots = ((T + C - 1) // C) * one.heads
+        assert packed_slots >= plain_slots
+        got = kda.kda_chunk_bwd_workspace_size(one)
+        assert 0 <= got - 4 * floats_for(packed_slots, T * one.heads) < 9 * 256, T
+        f32 = _dims(kda, seqlen=T, in_dtype=0)
+        want = 4 * packed_slots * (2 * C * (C + 2) + 3 * C * D + D)
+        assert 0 <= kda.kda_chunk_fwd_workspace_size(f32) - want < 2 * 256, T
+    d = _dims(kda)
+    need = kda.kda_chunk_bwd_workspace_size(d)
     assert kda.kda_chunk_bwd_workspace_size(_dims(kda, dk=96, dv=96)) == 0
     p = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(16)]
 
