@@ -1,18 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the KDA hot path on one MI355X.
 
-A "step" is one pass of the hot path over one batch of synthetic input: the
-chunkwise prefill (kda_chunk_fwd) on the bf16 prefill workload, and one decode
-step (kda_recurrent_step) over the decode workload's state pool.  The two are
-timed in separate regions of K steps each, inputs resident in HBM, bracketed
-by device synchronisation and measured with HIP events on the launch stream.
-`value` is prefill tokens/s; the decode figures are in the `decode` object.
+A "step" is one pass of the hot path over one batch of synthetic input.  The headline is the
+chunkwise prefill (kda_chunk_fwd) on the largest single-GPU workload, the 2^20-token long-context
+prefill (cfg3_long_bf16): `value` is its tokens/s, timed over K steps with the inputs resident in
+HBM, bracketed by device synchronisation and measured with HIP events on the launch stream.  The
+other bf16 prefill workloads (cfg1, cfg2) and the decode workload (cfg4: one kda_recurrent_step
+over the 512 MiB state pool) are timed the same way and reported as sub-objects, each with its own
+`roofline` and `cpu_baseline`.
 
 Prints ONE JSON line.  Runs on one GPU only.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -23,26 +25,29 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0          # dense fp16/bf16 matrix cores
 
-# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (profiles/pmc_traffic_bench_cfg1_cfg4.txt),
-# scaled by what the same counters read for a 1 GiB copy.  Counter collection serialises kernels, so the
-# prefill figure is that of the two kernels run one after the other (both summed).
-MEASURED_TRAFFIC_BYTES = {"cfg1_prefill_bf16": 1007.3e6, "cfg4_decode_bf16": 1086.6e6}
-# the same for the five kernels of one backward call on the cfg1 shape (profiles/pmc_traffic_bench_backward_cfg1.txt)
-MEASURED_BACKWARD_TRAFFIC_BYTES = 6146.5e6
-
 # Algorithmic work per (token, head) at d_k = d_v = 128, C = 64.
 FLOP_PER_TOKHEAD = 6 * 128 * 128 + 3 * 64 * 128 + 64 * 64        # paper's FLOPs model: 126976
 BYTES_PER_TOKHEAD = (3 * 128 + 128) * 2 + 2 + 128 * 4            # q,k,log_alpha,v,beta bf16 + o fp32: 1538
 
+HEADLINE = "cfg3_long_bf16"
+PREFILL_WORKLOADS = ("cfg3_long_bf16", "cfg1_prefill_bf16", "cfg2_varlen_bf16")
 
-def _events(torch):
-    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the workload's call, from the rocprofv3 counter summary committed
+    under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain copy of
+    known size; the file states the command).  Returns (bytes or None, file name or None)."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None, None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return (float(m.group(1)) if m else None), os.path.relpath(path, ROOT)
 
 
 def _time_region(torch, fn, steps):
     """Time `steps` calls of fn() with HIP events on the current stream; returns ms per call."""
     torch.cuda.synchronize()
-    a, b = _events(torch)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     for _ in range(steps):
         fn()
@@ -51,26 +56,268 @@ def _time_region(torch, fn, steps):
     return a.elapsed_time(b) / steps
 
 
+def make_workload(torch, si, name, dev):
+    """Device tensors of one prefill workload: (x, tokens, max_len, config description)."""
+    c = si.CONFIGS[name]
+    if name == "cfg1_prefill_bf16":
+        host = si.make_prefill(c["B"], c["T"], c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"], c["h0_std"])
+        x = {k_: (v_.to(dev) if isinstance(v_, torch.Tensor) else v_) for k_, v_ in host.items()}
+        return x, c["B"] * c["T"], 0, {"workload": name, "B": c["B"], "T": c["T"], "H": c["H"], "dk": c["dk"],
+                                      "dv": c["dv"], "chunk": 64}
+    if name == "cfg2_varlen_bf16":
+        lens = si.varlen_lengths(c["N"], c["len_lo"], c["len_hi"], c["seed"])
+        host = si.make_varlen(lens, c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"], c["h0_std"])
+        x = {k_: (v_.to(dev) if isinstance(v_, torch.Tensor) else v_) for k_, v_ in host.items()}
+        return x, int(lens.sum()), int(lens.max()), {"workload": name, "num_seqs": c["N"], "total_tokens": int(lens.sum()),
+                                                      "H": c["H"], "dk": c["dk"], "dv": c["dv"], "chunk": 64}
+    if name == "cfg3_long_bf16":
+        x = si.make_long_on_device(c["T"], c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"], dev)
+        x["h0"] = None
+        x["cu_seqlens"] = None
+        return x, c["T"], 0, {"workload": name, "B": 1, "T": c["T"], "H": c["H"], "dk": c["dk"], "dv": c["dv"],
+                              "chunk": 64}
+    raise SystemExit("unknown workload " + name)
+
+
+def run_prefill(torch, si, kda, name, steps, warmup, dev, cpu_seconds, breakdown):
+    """Times kda_chunk_fwd on one workload; returns the result object (ms, tokens/s, roofline, cpu_baseline)."""
+    c = si.CONFIGS[name]
+    x, tokens, max_len, desc = make_workload(torch, si, name, dev)
+    H = c["H"]
+    tokheads = tokens * H
+    dims = kda.kda.make_chunk_dims(x["q"], x["v"], x["cu_seqlens"], 1.0, max_len)
+    ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device=dev)
+    o = torch.empty(x["q"].shape[0], x["q"].shape[1], H, c["dv"], dtype=torch.float32, device=dev)
+    hT = torch.empty(dims.num_seqs, H, c["dk"], c["dv"], dtype=torch.float32, device=dev)
+
+    def prefill():
+        kda.kda_chunk_fwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], h0=x["h0"],
+                          cu_seqlens=x["cu_seqlens"], o=o, hT=hT, workspace=ws, max_seqlen=max_len)
+
+    for _ in range(warmup):
+        prefill()
+    ms = _time_region(torch, prefill, steps)
+    kda.kda_chunk_fwd_check(dims, ws)            # raises if the call reported a failed wait: outputs would be invalid
+
+    alg_bytes = tokheads * BYTES_PER_TOKHEAD + 2 * dims.num_seqs * H * 128 * 128 * 4
+    traffic, traffic_file = measured_traffic(name)
+    kernels = kda.kda_chunk_fwd_kernel_names(dims, ws) if hasattr(kda, "kda_chunk_fwd_kernel_names") else None
+    roofline = {
+        # the call's kernels run side by side from the first to the last microsecond of the call, so the
+        # duration of the dominant one is the call's own (HIP events on the launch stream around K calls)
+        "kernel": kernels or "kda_chunk_fwd (its kernels run side by side for the length of the call)",
+        "bound": "hbm",
+        "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": traffic, "traffic_source": traffic_file,
+        "ms_kernel": ms,
+        "algorithmic_bytes": alg_bytes,
+        "mfma_frac_model_flops": tokheads * FLOP_PER_TOKHEAD / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+        "model_tflops": tokheads * FLOP_PER_TOKHEAD / (ms * 1e-3) / 1e12,
+    }
+    res = {"metric": "KDA prefill tokens/s", "value": tokens / (ms * 1e-3), "unit": "tokens/s",
+           "ms_per_step": ms, "steps": steps, "warmup": warmup, "config": desc,
+           "tokheads_per_s": tokheads / (ms * 1e-3), "workspace_bytes": int(ws.numel()), "roofline": roofline}
+    if breakdown:
+        res["breakdown"] = breakdown(kda, torch, prefill, steps)
+
+    if cpu_seconds > 0:
+        import oracle
+        # bounded sample: a prefix of every (sequence, head), sized so the fp64 recurrence runs for seconds
+        n_s = min(16384 if name == HEADLINE else 4096, x["q"].shape[1])
+        if x["cu_seqlens"] is None:
+            a = {k_: si.to_np32(x[k_][:, :n_s]) for k_ in ("q", "k", "v", "log_alpha", "beta")}
+            sample_tokens = x["q"].shape[0] * n_s
+            what = "first %d tokens of every sequence" % n_s
+            kw = {}
+        else:
+            import numpy as np
+            a = {k_: si.to_np32(x[k_]) for k_ in ("q", "k", "v", "log_alpha", "beta")}
+            sample_tokens = tokens
+            what = "the whole packed batch"
+            kw = {"cu_seqlens": x["cu_seqlens"].cpu().numpy().astype(np.int64)}
+        reps, dt = 0, 0.0
+        t0 = time.perf_counter()
+        while dt < cpu_seconds and reps < 50:
+            oracle.kda_forward(a["q"], a["k"], a["v"], a["log_alpha"], a["beta"], want_hT=False, **kw)
+            reps += 1
+            dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": sample_tokens * reps / dt, "unit": "tokens/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": "%s of %s (x %d heads), %d time(s) over, fp64 per-token recurrence"
+                                         % (what, name, H, reps),
+                               "seconds": dt}
+    del x, ws, o, hT
+    torch.cuda.empty_cache()
+    return res
+
+
+def run_decode(torch, si, kda, steps, warmup, dev, cpu_baseline):
+    d4 = si.CONFIGS["cfg4_decode_bf16"]
+    N4, H4, dk4, dv4 = d4["N"], d4["H"], d4["dk"], d4["dv"]
+    S = si.make_state(N4, H4, dk4, dv4, d4["state_std"], d4["seed"]).to(dev)
+    tok_host = si.make_decode_tokens(N4, H4, dk4, dv4, d4["dtype"], d4["mu"], d4["seed"], 0)
+    tk = {k_: v_.to(dev) for k_, v_ in tok_host.items()}
+    o4 = torch.empty(N4, H4, dv4, dtype=torch.float32, device=dev)
+
+    def decode():
+        kda.kda_recurrent_step(tk["q"], tk["k"], tk["v"], tk["log_alpha"], tk["beta"], S, o=o4)
+
+    for _ in range(warmup):
+        decode()
+    ms_decode = _time_region(torch, decode, steps)
+    dec_bytes = 2 * N4 * H4 * dk4 * dv4 * 4 + N4 * H4 * ((3 * dk4 + dv4) * 2 + 2) + N4 * H4 * dv4 * 4
+    traffic, traffic_file = measured_traffic("cfg4_decode_bf16")
+    obj = {
+        "metric": "decode-step state GB/s", "value": dec_bytes / (ms_decode * 1e-3) / 1e9, "unit": "GB/s",
+        "ms_per_step": ms_decode, "steps": steps,
+        "config": {"workload": "cfg4_decode_bf16", "num_seqs": N4, "H": H4, "dk": dk4, "dv": dv4,
+                   "state_bytes": N4 * H4 * dk4 * dv4 * 4},
+        "roofline": {"kernel": "kda_step_kernel", "bound": "hbm",
+                     "achieved": dec_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dec_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": traffic, "traffic_source": traffic_file, "ms_kernel": ms_decode,
+                     "algorithmic_bytes": dec_bytes},
+    }
+
+    # pooled multi-token decode: the same 256 x 32 states addressed through a permuted index array,
+    # four tokens per sequence and call (state traffic is paid once per call, not once per token)
+    Tq = 4
+    perm = torch.randperm(N4, generator=torch.Generator().manual_seed(d4["seed"])).to(torch.int32).to(dev)
+    mt_host = [si.make_decode_tokens(N4, H4, dk4, dv4, d4["dtype"], d4["mu"], d4["seed"], 1 + t) for t in range(Tq)]
+    mt = {k_: torch.stack([t_[k_] for t_ in mt_host], dim=1).contiguous().to(dev) for k_ in mt_host[0]}
+    o4m = torch.empty(N4, Tq, H4, dv4, dtype=torch.float32, device=dev)
+
+    def decode_pooled():
+        kda.kda_recurrent_steps_pooled(mt["q"], mt["k"], mt["v"], mt["log_alpha"], mt["beta"], S, perm, o=o4m)
+
+    for _ in range(warmup):
+        decode_pooled()
+    ms_pooled = _time_region(torch, decode_pooled, steps)
+    pooled_bytes = 2 * N4 * H4 * dk4 * dv4 * 4 + Tq * (N4 * H4 * ((3 * dk4 + dv4) * 2 + 2) + N4 * H4 * dv4 * 4)
+    obj["pooled_multi_token"] = {
+        "tokens_per_call": Tq, "ms_per_call": ms_pooled,
+        "decode_tokens_per_s": N4 * Tq / (ms_pooled * 1e-3),
+        "single_token_decode_tokens_per_s": N4 / (ms_decode * 1e-3),
+        "achieved_GBps": pooled_bytes / (ms_pooled * 1e-3) / 1e9,
+        "hbm_frac": pooled_bytes / (ms_pooled * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    }
+
+    # what a plain device-to-device copy reaches on this GPU (bytes read + written per second)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ms_copy = _time_region(torch, lambda: dst.copy_(src), 10)
+    copy_gbs = 2 * src.numel() / (ms_copy * 1e-3) / 1e9
+    del src, dst
+    obj["roofline"]["measured_copy_GBps"] = copy_gbs
+    obj["roofline"]["frac_of_measured_copy"] = obj["value"] / copy_gbs
+
+    if cpu_baseline:
+        import numpy as np
+        import oracle
+        Sh = S.cpu().numpy().astype(np.float64)
+        args = [si.to_np32(tok_host[n_]) for n_ in ("q", "k", "v", "log_alpha", "beta")]
+        reps, dt = 0, 0.0
+        t0 = time.perf_counter()
+        while dt < 5.0 and reps < 50:
+            oracle.kda_step(*args, Sh)
+            reps += 1
+            dt = time.perf_counter() - t0
+        obj["cpu_baseline"] = {"value": dec_bytes * reps / dt / 1e9, "unit": "GB/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "one decode step over the whole cfg4 state pool, %d time(s) over, fp64" % reps,
+                               "seconds": dt}
+    del S
+    torch.cuda.empty_cache()
+    return obj
+
+
+def run_extras(torch, si, kda, steps, warmup, dev, cpu_baseline):
+    """Other entry points on the cfg1 shape: bf16 outputs, scalar gate, fused stages, backward."""
+    name = "cfg1_prefill_bf16"
+    c = si.CONFIGS[name]
+    x, tokens, _, _ = make_workload(torch, si, name, dev)
+    H = c["H"]
+    tokheads = tokens * H
+    dims = kda.kda.make_chunk_dims(x["q"], x["v"], None, 1.0, 0)
+    ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device=dev)
+    o = torch.empty(c["B"], c["T"], H, c["dv"], dtype=torch.float32, device=dev)
+    hT = torch.empty(c["B"], H, c["dk"], c["dv"], dtype=torch.float32, device=dev)
+    out = {}
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        ms = _time_region(torch, fn, steps)
+        return {"ms_per_step": ms, "tokens_per_s": tokens / (ms * 1e-3)}
+
+    o16 = torch.empty(o.shape, dtype=torch.bfloat16, device=dev)
+    out["prefill_bf16_out"] = dict(what="cfg1 shape, out_dtype bf16 (o rounded once at the store)", **timed(
+        lambda: kda.kda_chunk_fwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], h0=x["h0"], o=o16, hT=hT, workspace=ws)))
+    del o16
+    gh = x["log_alpha"][..., 0].contiguous()
+    out["prefill_scalar_gate"] = dict(what="kda_chunk_fwd_scalar_gate on the cfg1 shape (the decay of channel 0 taken for the whole head)", **timed(
+        lambda: kda.kda_chunk_fwd_scalar_gate(x["q"], x["k"], x["v"], gh, x["beta"], h0=x["h0"], o=o, hT=hT, workspace=ws)))
+    del gh
+
+    rawx = si.make_raw_tokens(c["B"], c["T"], H, c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"])
+    rx = {k_: v_.to(dev) for k_, v_ in rawx.items()}
+    fused = {"what": "kda_chunk_fwd_fused on the cfg1 shape: (a) input prologue (L2Norm(q), L2Norm(k), Sigmoid(beta), decay "
+                     "function) inside the per-chunk kernel; (b) plus the output gate Sigmoid(g) * RMSNorm(o) inside the "
+                     "sequential kernel"}
+    fused["prologue"] = timed(lambda: kda.kda_chunk_fwd_fused(rx["q_raw"], rx["k_raw"], rx["v"], rx["gate"], rx["beta_logit"],
+                                                              h0=x["h0"], o=o, hT=hT, workspace=ws))
+    og = torch.randn(c["B"], c["T"], H, c["dv"], generator=torch.Generator().manual_seed(c["seed"])).to(torch.bfloat16).to(dev)
+    nw = torch.ones(c["dv"], dtype=torch.float32, device=dev)
+    ws_g = torch.empty(kda.kda_chunk_fwd_workspace_size(dims, output_gate=True), dtype=torch.uint8, device=dev)
+    fused["prologue_and_output_gate"] = timed(lambda: kda.kda_chunk_fwd_fused(
+        rx["q_raw"], rx["k_raw"], rx["v"], rx["gate"], rx["beta_logit"], out_gate=og, norm_weight=nw, h0=x["h0"], o=o, hT=hT,
+        workspace=ws_g))
+    out["prefill_fused_stages"] = fused
+    del ws_g, og, rx
+
+    # the backward pass (kda_chunk_bwd, fp32 throughout): time per call, and its rate against the fp32 vector
+    # peak under a FLOP model of the chunkwise backward (per chunk and head: eight C x d x d products, eight
+    # half-filled C x C x d ones, the C x C x C chain)
+    d_o = torch.randn(o.shape, generator=torch.Generator().manual_seed(c["seed"] + 1)).to(dev)
+    ws_b = torch.empty(kda.kda_chunk_bwd_workspace_size(dims), dtype=torch.uint8, device=dev)
+    grads = kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], d_o, h0=x["h0"], workspace=ws_b)
+
+    def backward():
+        return kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], d_o, h0=x["h0"], workspace=ws_b, out=grads)
+    backward()
+    steps_b = max(3, min(steps, 10))
+    ms_bwd = _time_region(torch, backward, steps_b)
+    C_, D_ = 64, c["dk"]
+    flop_chunk = 8 * 2 * C_ * D_ * D_ + 8 * C_ * C_ * D_ + 3 * 2 * C_ * C_ * C_
+    tflops = tokheads / C_ * flop_chunk / (ms_bwd * 1e-3) / 1e12
+    traffic, traffic_file = measured_traffic("backward_cfg1")
+    out["backward"] = {"what": "kda_chunk_bwd on the cfg1 shape: gradients of q, k, v, log_alpha, beta, h0 (fp32 arithmetic)",
+                       "ms_per_step": ms_bwd, "steps": steps_b, "tokens_per_s": tokens / (ms_bwd * 1e-3),
+                       "roofline": {"bound": "alu", "achieved": tflops, "peak": 157.3, "unit": "TFLOP/s",
+                                    "frac": tflops / 157.3, "flop_per_chunk_head": flop_chunk, "traffic": traffic,
+                                    "traffic_source": traffic_file}}
+    del d_o, ws_b, grads, x, ws, o, hT
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-breakdown", action="store_true",
-                    help="skip the extra serial / single-kernel timing passes (keeps a profile of this "
-                         "run down to the launches of the timed configuration)")
     ap.add_argument("--extras", action="store_true",
-                    help="with --serial: still run the extra passes (bf16 outputs, scalar gate, fused stages, "
-                         "backward), every prefill with its kernels one after the other")
-    ap.add_argument("--serial", action="store_true",
-                    help="run the two prefill kernels one after the other (needed under tools that serialise "
-                         "kernels, e.g. rocprofv3 --pmc); implies --no-breakdown")
+                    help="also time the other entry points on the cfg1 shape (bf16 outputs, scalar gate, fused "
+                         "stages, backward)")
+    ap.add_argument("--only", default=None,
+                    help="time just this workload (cfg1_prefill_bf16, cfg2_varlen_bf16, cfg3_long_bf16 or "
+                         "cfg4_decode_bf16), with no CPU baseline: what a profiler run wants")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run a plain 1 GiB device copy three times, so that a byte counter collected over "
                          "this run can be scaled by what it reads for a transfer of known size")
-    ap.add_argument("--workload", default="cfg1_prefill_bf16",
-                    help="prefill workload: cfg1_prefill_bf16 (default), cfg2_varlen_bf16, cfg3_long_bf16")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
@@ -86,9 +333,6 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    if args.serial:
-        args.no_breakdown = not args.extras
-        kda.kda_debug_set_overlap(0)
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -97,318 +341,34 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ------------------------------------------------------------------ prefill workload
-    name = args.workload
-    c = si.CONFIGS[name]
-    if name == "cfg1_prefill_bf16":
-        host = si.make_prefill(c["B"], c["T"], c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"],
-                               c["h0_std"])
-        x = {k_: (v_.to(dev) if isinstance(v_, torch.Tensor) else v_) for k_, v_ in host.items()}
-        tokens = c["B"] * c["T"]
-        desc = {"workload": name, "B": c["B"], "T": c["T"], "H": c["H"], "dk": c["dk"], "dv": c["dv"],
-                "chunk": 64}
-    elif name == "cfg2_varlen_bf16":
-        lens = si.varlen_lengths(c["N"], c["len_lo"], c["len_hi"], c["seed"])
-        host = si.make_varlen(lens, c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"], c["h0_std"])
-        x = {k_: (v_.to(dev) if isinstance(v_, torch.Tensor) else v_) for k_, v_ in host.items()}
-        tokens = int(lens.sum())
-        desc = {"workload": name, "num_seqs": c["N"], "total_tokens": tokens, "H": c["H"], "dk": c["dk"],
-                "dv": c["dv"], "chunk": 64}
-    elif name == "cfg3_long_bf16":
-        host = None
-        x = si.make_long_on_device(c["T"], c["H"], c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"], dev)
-        x["h0"] = None
-        x["cu_seqlens"] = None
-        tokens = c["T"]
-        desc = {"workload": name, "B": 1, "T": c["T"], "H": c["H"], "dk": c["dk"], "dv": c["dv"], "chunk": 64}
-    else:
-        raise SystemExit("unknown workload " + name)
-    H = c["H"]
-    tokheads = tokens * H
+    cpu = not args.no_cpu_baseline and args.only is None
+    results = {}
+    for name in PREFILL_WORKLOADS:
+        if args.only not in (None, name):
+            continue
+        # the small workloads take well under a millisecond per step: more steps for a steady figure
+        steps = args.steps if name == HEADLINE else max(args.steps, 50)
+        warmup = args.warmup if name == HEADLINE else max(args.warmup, 10)
+        results[name] = run_prefill(torch, si, kda, name, steps, warmup, dev, 10.0 if cpu else 0.0, None)
+    decode_obj = None
+    if args.only in (None, "cfg4_decode_bf16"):
+        decode_obj = run_decode(torch, si, kda, max(args.steps, 50), max(args.warmup, 10), dev, cpu)
+    extras = run_extras(torch, si, kda, max(args.steps, 50), max(args.warmup, 10), dev, cpu) if args.extras else None
 
-    max_len = int(lens.max()) if name == "cfg2_varlen_bf16" else 0
-    dims = kda.kda.make_chunk_dims(x["q"], x["v"], x["cu_seqlens"], 1.0, max_len)
-    ws_bytes = kda.kda_chunk_fwd_workspace_size(dims)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    o = torch.empty(x["q"].shape[0], x["q"].shape[1], H, c["dv"], dtype=torch.float32, device=dev)
-    hT = torch.empty(dims.num_seqs, H, c["dk"], c["dv"], dtype=torch.float32, device=dev)
-
-    def prefill():
-        kda.kda_chunk_fwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], h0=x["h0"],
-                          cu_seqlens=x["cu_seqlens"], o=o, hT=hT, workspace=ws, max_seqlen=max_len)
-
-    for _ in range(args.warmup):
-        prefill()
-    ms_prefill = _time_region(torch, prefill, args.steps)
-    kda.kda_chunk_fwd_check(dims, ws)            # raises if the sequential kernel ever gave up waiting for a slot
-    # The same call with its two kernels strictly one after the other, and each kernel alone
-    # (switching one off also switches the overlap off): per-kernel durations.
-    ms_serial = ms_intra = ms_scan = None
-    if not args.no_breakdown:
-        kda.kda_debug_set_overlap(0)
-        ms_serial = _time_region(torch, prefill, args.steps)
-        kda.kda_debug_set_phase_mask(1)
-        ms_intra = _time_region(torch, prefill, args.steps)
-        kda.kda_debug_set_phase_mask(2)
-        ms_scan = _time_region(torch, prefill, args.steps)
-        kda.kda_debug_set_phase_mask(3)
-        kda.kda_debug_set_overlap(0 if args.serial else 1)
-        prefill()
-        torch.cuda.synchronize()
-
-    tok_per_s = tokens / (ms_prefill * 1e-3)
-    alg_bytes = tokheads * BYTES_PER_TOKHEAD + 2 * dims.num_seqs * H * 128 * 128 * 4
-    streams = dims.num_seqs * H
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    # the library's own rule for running the kernels side by side
-    overlapped = 4 * streams <= 3 * cus and not args.serial
-    if overlapped or ms_scan is None:
-        # kda_scan is launched first and retires last: its duration is the call's, up to the flag
-        # reset (a few microseconds) and the launch gaps, which the event pair also brackets
-        dom_name, dom_ms = "kda_scan_kernel (kda_intra_kernel runs beside it)", ms_prefill
-    else:
-        dom_name, dom_ms = ("kda_scan_kernel", ms_scan) if ms_scan >= ms_intra else ("kda_intra_kernel", ms_intra)
-    roofline = {
-        "kernel": dom_name, "bound": "hbm",
-        "achieved": alg_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": alg_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get(name),
-        "ms_kernel": dom_ms,
-        "algorithmic_bytes": alg_bytes,
-        "kernels_ms_alone": {"kda_intra_kernel": ms_intra, "kda_scan_kernel": ms_scan, "both_serial": ms_serial},
-        "whole_call": {
-            "hbm_frac": alg_bytes / (ms_prefill * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "mfma_frac_model_flops": tokheads * FLOP_PER_TOKHEAD / (ms_prefill * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
-            "model_tflops": tokheads * FLOP_PER_TOKHEAD / (ms_prefill * 1e-3) / 1e12,
-        },
-    }
-
-    # the same prefill with o stored as bf16 (the headline keeps fp32 o, which parity is stated on)
-    bf16_out_obj = None
-    if not args.no_breakdown:
-        o16 = torch.empty(o.shape, dtype=torch.bfloat16, device=dev)
-
-        def prefill_bf16_out():
-            kda.kda_chunk_fwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], h0=x["h0"],
-                              cu_seqlens=x["cu_seqlens"], o=o16, hT=hT, workspace=ws, max_seqlen=max_len)
-        for _ in range(args.warmup):
-            prefill_bf16_out()
-        ms_o16 = _time_region(torch, prefill_bf16_out, args.steps)
-        kda.kda_chunk_fwd_check(dims, ws)
-        bf16_out_obj = {"what": "same workload, out_dtype bf16 (o rounded once at the store)",
-                        "ms_per_step": ms_o16, "tokens_per_s": tokens / (ms_o16 * 1e-3)}
-        del o16
-
-    # the scalar-gate special case (one decay per token and head) on the same shape: its own entry point
-    scalar_obj = None
-    if not args.no_breakdown:
-        gh = x["log_alpha"][..., 0].contiguous()
-
-        def prefill_scalar_gate():
-            kda.kda_chunk_fwd_scalar_gate(x["q"], x["k"], x["v"], gh, x["beta"], h0=x["h0"],
-                                          cu_seqlens=x["cu_seqlens"], o=o, hT=hT, workspace=ws, max_seqlen=max_len)
-        for _ in range(args.warmup):
-            prefill_scalar_gate()
-        ms_sg = _time_region(torch, prefill_scalar_gate, args.steps)
-        kda.kda_chunk_fwd_check(dims, ws)
-        scalar_obj = {"what": "kda_chunk_fwd_scalar_gate on the same shape (the decay of channel 0 taken for the whole head)",
-                      "ms_per_step": ms_sg, "tokens_per_s": tokens / (ms_sg * 1e-3)}
-        del gh
-
-    # the backward pass (kda_chunk_bwd, fp32 throughout) on the same shape: time per call, and its rate
-    # against the fp32 vector peak under a FLOP model of the chunkwise backward (per chunk and head:
-    # eight C x d x d products, eight half-filled C x C x d ones, the C x C x C chain)
-    backward_obj = None
-    if name == "cfg1_prefill_bf16" and not args.no_breakdown:
-        d_o = torch.randn(o.shape, generator=torch.Generator().manual_seed(c["seed"] + 1)).to(dev)
-        ws_b = torch.empty(kda.kda_chunk_bwd_workspace_size(dims), dtype=torch.uint8, device=dev)
-
-        grads = kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], d_o, h0=x["h0"], workspace=ws_b)
-
-        def backward():
-            return kda.kda_chunk_bwd(x["q"], x["k"], x["v"], x["log_alpha"], x["beta"], d_o, h0=x["h0"],
-                                     workspace=ws_b, out=grads)
-        backward()
-        steps_b = max(3, min(args.steps, 10))
-        ms_bwd = _time_region(torch, backward, steps_b)
-        C_, D_ = 64, c["dk"]
-        flop_chunk = 8 * 2 * C_ * D_ * D_ + 8 * C_ * C_ * D_ + 3 * 2 * C_ * C_ * C_
-        chunks_heads = tokheads / C_
-        tflops = chunks_heads * flop_chunk / (ms_bwd * 1e-3) / 1e12
-        backward_obj = {"what": "kda_chunk_bwd on the same shape: gradients of q, k, v, log_alpha, beta, h0 (fp32 arithmetic)",
-                        "ms_per_step": ms_bwd, "steps": steps_b, "tokens_per_s": tokens / (ms_bwd * 1e-3),
-                        "roofline": {"bound": "alu", "achieved": tflops, "peak": 157.3, "unit": "TFLOP/s",
-                                     "frac": tflops / 157.3, "flop_per_chunk_head": flop_chunk, "traffic": None}}
-        if not args.no_cpu_baseline and host is not None:
-            import numpy as np
-            import oracle
-            n_s = 256
-            a = {k_: si.to_np32(host[k_][:, :n_s]) for k_ in ("q", "k", "v", "log_alpha", "beta")}
-            t0 = time.perf_counter()
-            reps = 0
-            while time.perf_counter() - t0 < 5.0:
-                oracle.kda_backward(a["q"], a["k"], a["v"], a["log_alpha"], a["beta"],
-                                    d_o[:, :n_s].cpu().numpy(), h0=host["h0"].numpy().astype(np.float64))
-                reps += 1
-            dtb = time.perf_counter() - t0
-            backward_obj["cpu_baseline"] = {"value": c["B"] * n_s * reps / dtb, "unit": "tokens/s",
-                                            "cores": oracle.num_threads(), "kind": "oracle",
-                                            "sample": "first %d tokens of every sequence, %d times over, fp64 "
-                                                      "token-by-token reverse pass" % (n_s, reps),
-                                            "seconds": dtb}
-        del d_o, ws_b, grads
-
-    # the same prefill on raw projections (fused input prologue), cfg1 shape only
-    fused_obj = None
-    if name == "cfg1_prefill_bf16" and not args.no_breakdown:
-        rawx = si.make_raw_tokens(c["B"], c["T"], H, c["dk"], c["dv"], c["dtype"], c["mu"], c["seed"])
-        rx = {k_: v_.to(dev) for k_, v_ in rawx.items()}
-
-        def prefill_fused():
-            # a_scale = 1, dt_bias = 0: the decays then follow the workload's own recipe, -softplus(N(mu, 1))
-            kda.kda_chunk_fwd_fused(rx["q_raw"], rx["k_raw"], rx["v"], rx["gate"], rx["beta_logit"],
-                                    h0=x["h0"], o=o, hT=hT, workspace=ws)
-        for _ in range(args.warmup):
-            prefill_fused()
-        ms_fused = _time_region(torch, prefill_fused, args.steps)
-        kda.kda_chunk_fwd_check(dims, ws)
-        og = torch.randn(c["B"], c["T"], H, c["dv"], generator=torch.Generator().manual_seed(c["seed"])).to(torch.bfloat16).to(dev)
-        nw = torch.ones(c["dv"], dtype=torch.float32, device=dev)
-
-        # (with the output gate the workspace also holds the re-laid gate logits)
-        ws_g = torch.empty(kda.kda_chunk_fwd_workspace_size(dims, output_gate=True), dtype=torch.uint8, device=dev)
-
-        def prefill_fused_both():
-            kda.kda_chunk_fwd_fused(rx["q_raw"], rx["k_raw"], rx["v"], rx["gate"], rx["beta_logit"],
-                                    out_gate=og, norm_weight=nw, h0=x["h0"], o=o, hT=hT, workspace=ws_g)
-        for _ in range(args.warmup):
-            prefill_fused_both()
-        ms_both = _time_region(torch, prefill_fused_both, args.steps)
-        kda.kda_chunk_fwd_check(dims, ws_g)
-        del ws_g
-        fused_obj = {"what": "kda_chunk_fwd_fused on the cfg1 shape: (a) input prologue (L2Norm(q), L2Norm(k), "
-                             "Sigmoid(beta), decay function) inside the per-chunk kernel; (b) plus the output gate "
-                             "Sigmoid(g) * RMSNorm(o) inside the sequential kernel",
-                     "prologue": {"ms_per_step": ms_fused, "tokens_per_s": tokens / (ms_fused * 1e-3)},
-                     "prologue_and_output_gate": {"ms_per_step": ms_both, "tokens_per_s": tokens / (ms_both * 1e-3)}}
-        del og
-        del rx
-
-    # ------------------------------------------------------------------ decode workload
-    d4 = si.CONFIGS["cfg4_decode_bf16"]
-    N4, H4, dk4, dv4 = d4["N"], d4["H"], d4["dk"], d4["dv"]
-    del ws
-    S = si.make_state(N4, H4, dk4, dv4, d4["state_std"], d4["seed"]).to(dev)
-    tok_host = si.make_decode_tokens(N4, H4, dk4, dv4, d4["dtype"], d4["mu"], d4["seed"], 0)
-    tk = {k_: v_.to(dev) for k_, v_ in tok_host.items()}
-    o4 = torch.empty(N4, H4, dv4, dtype=torch.float32, device=dev)
-
-    def decode():
-        kda.kda_recurrent_step(tk["q"], tk["k"], tk["v"], tk["log_alpha"], tk["beta"], S, o=o4)
-
-    for _ in range(args.warmup):
-        decode()
-    ms_decode = _time_region(torch, decode, args.steps)
-    dec_bytes = 2 * N4 * H4 * dk4 * dv4 * 4 + N4 * H4 * ((3 * dk4 + dv4) * 2 + 2) + N4 * H4 * dv4 * 4
-    decode_obj = {
-        "metric": "decode-step state GB/s", "value": dec_bytes / (ms_decode * 1e-3) / 1e9, "unit": "GB/s",
-        "ms_per_step": ms_decode, "steps": args.steps,
-        "config": {"workload": "cfg4_decode_bf16", "num_seqs": N4, "H": H4, "dk": dk4, "dv": dv4,
-                   "state_bytes": N4 * H4 * dk4 * dv4 * 4},
-        "roofline": {"kernel": "kda_step_kernel", "bound": "hbm",
-                     "achieved": dec_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": dec_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get("cfg4_decode_bf16"),
-                     "algorithmic_bytes": dec_bytes},
-    }
-
-    # pooled multi-token decode: the same 256 x 32 states addressed through a permuted index array,
-    # four tokens per sequence and call (state traffic is paid once per call, not once per token)
-    Tq = 4
-    perm = torch.randperm(N4, generator=torch.Generator().manual_seed(d4["seed"])).to(torch.int32).to(dev)
-    mt_host = [si.make_decode_tokens(N4, H4, dk4, dv4, d4["dtype"], d4["mu"], d4["seed"], 1 + t) for t in range(Tq)]
-    mt = {k_: torch.stack([t_[k_] for t_ in mt_host], dim=1).contiguous().to(dev) for k_ in mt_host[0]}
-    o4m = torch.empty(N4, Tq, H4, dv4, dtype=torch.float32, device=dev)
-
-    def decode_pooled():
-        kda.kda_recurrent_steps_pooled(mt["q"], mt["k"], mt["v"], mt["log_alpha"], mt["beta"], S, perm, o=o4m)
-
-    for _ in range(args.warmup):
-        decode_pooled()
-    ms_pooled = _time_region(torch, decode_pooled, args.steps)
-    pooled_bytes = 2 * N4 * H4 * dk4 * dv4 * 4 + Tq * (N4 * H4 * ((3 * dk4 + dv4) * 2 + 2) + N4 * H4 * dv4 * 4)
-    decode_obj["pooled_multi_token"] = {
-        "tokens_per_call": Tq, "ms_per_call": ms_pooled,
-        "decode_tokens_per_s": N4 * Tq / (ms_pooled * 1e-3),
-        "single_token_decode_tokens_per_s": N4 / (ms_decode * 1e-3),
-        "achieved_GBps": pooled_bytes / (ms_pooled * 1e-3) / 1e9,
-        "hbm_frac": pooled_bytes / (ms_pooled * 1e-3) / 1e9 / HBM_PEAK_GBS,
-    }
-
-    # what a plain device-to-device copy reaches on this GPU (bytes read + written per second)
-    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    dst = torch.empty_like(src)
-    dst.copy_(src)
-    ms_copy = _time_region(torch, lambda: dst.copy_(src), 10)
-    copy_gbs = 2 * src.numel() / (ms_copy * 1e-3) / 1e9
-    del src, dst
-    decode_obj["roofline"]["measured_copy_GBps"] = copy_gbs
-    decode_obj["roofline"]["frac_of_measured_copy"] = decode_obj["value"] / copy_gbs
-
-    # ------------------------------------------------------------------ CPU baseline (oracle)
-    cpu = None
-    if not args.no_cpu_baseline:
-        import numpy as np
-        import oracle
-        if host is not None and name == "cfg1_prefill_bf16":
-            a = {k_: si.to_np32(host[k_]) for k_ in ("q", "k", "v", "log_alpha", "beta")}
-            h0 = host["h0"].numpy().astype(np.float64)
-            # the whole workload, repeated until about ten seconds of CPU work have gone by
-            reps, dt = 0, 0.0
-            t0 = time.perf_counter()
-            while dt < 10.0 and reps < 200:
-                oracle.kda_forward(a["q"], a["k"], a["v"], a["log_alpha"], a["beta"], h0=h0)
-                reps += 1
-                dt = time.perf_counter() - t0
-            sample_tokens = tokens * reps
-            sample = "whole %s workload (%d tokens x %d heads) %d times over, fp64 per-token recurrence" % (
-                name, tokens, H, reps)
-        else:
-            # bounded sample: the first 4096 tokens of every head
-            n_s = min(4096, tokens)
-            a = {k_: si.to_np32(x[k_][:, :n_s]) for k_ in ("q", "k", "v", "log_alpha", "beta")}
-            t0 = time.perf_counter()
-            oracle.kda_forward(a["q"], a["k"], a["v"], a["log_alpha"], a["beta"])
-            dt = time.perf_counter() - t0
-            sample_tokens = n_s
-            sample = "first %d tokens of %s x %d heads, fp64 per-token recurrence" % (n_s, name, H)
-        cpu = {"value": sample_tokens / dt, "unit": "tokens/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": sample, "seconds": dt}
-        Sh = S.cpu().numpy().astype(np.float64)
-        t0 = time.perf_counter()
-        oracle.kda_step(si.to_np32(tok_host["q"]), si.to_np32(tok_host["k"]), si.to_np32(tok_host["v"]),
-                        si.to_np32(tok_host["log_alpha"]), si.to_np32(tok_host["beta"]), Sh)
-        dt4 = time.perf_counter() - t0
-        decode_obj["cpu_baseline"] = {"value": dec_bytes / dt4 / 1e9, "unit": "GB/s",
-                                      "cores": oracle.num_threads(), "kind": "oracle",
-                                      "sample": "one decode step over the whole cfg4 state pool, fp64",
-                                      "seconds": dt4}
-
+    head = results.get(HEADLINE) or next(iter(results.values()), None) or decode_obj
     out = {
-        "metric": "KDA prefill tokens/s", "value": tok_per_s, "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_prefill,
+        "metric": head["metric"], "value": head["value"], "unit": head["unit"],
+        "n_gpus": 1, "steps": head["steps"], "warmup": head.get("warmup", args.warmup), "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 matrix-core operands (bf16 inputs), f32 accumulate/state",
         "data": "synthetic",
-        "config": desc,
-        "tokheads_per_s": tokheads / (ms_prefill * 1e-3),
-        "roofline": roofline,
-        "cpu_baseline": cpu,
-        "prefill_bf16_out": bf16_out_obj,
-        "prefill_scalar_gate": scalar_obj,
-        "prefill_fused_stages": fused_obj,
-        "backward": backward_obj,
-        "decode": decode_obj,
+        "config": head["config"],
+        "roofline": head["roofline"],
+        "cpu_baseline": head.get("cpu_baseline"),
+        "tokheads_per_s": head.get("tokheads_per_s"),
+        "workloads": {n_: r_ for n_, r_ in results.items() if r_ is not head},
+        "decode": decode_obj if decode_obj is not head else None,
+        "extras": extras,
         "error_metric": "max|x-ref|/max|ref| per (sequence, head); parity is gated in tests/",
     }
     print(json.dumps(out))
