@@ -71,6 +71,14 @@ static double split_ratio_default()
     return (r >= 0.2 && r <= 1.0) ? r : 0.0;
 }
 double g_split_ratio = split_ratio_default();
+static int fused_default()
+{
+    const char *e = getenv("KDA_PREFILL_FUSED");
+    return (e && e[0] == '0' && e[1] == 0) ? 0 : 1;
+}
+int g_fused = fused_default();
+int g_producers = 1;
+uint64_t g_wait_limit = 200000000ull;     // two seconds
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -123,6 +131,10 @@ const char *kda_version(void) { return "kda-gfx950 0.1"; }
 void kda_debug_set_phase_mask(int mask) { g_phase_mask = mask & 3; }
 
 void kda_debug_set_overlap(int enabled) { g_overlap = enabled ? 1 : 0; }
+
+void kda_debug_set_producers(int enabled) { g_producers = enabled ? 1 : 0; }
+
+void kda_debug_set_wait_limit(unsigned long long ticks) { g_wait_limit = ticks; }
 
 void kda_debug_set_time_split(int mode) { g_split = mode < 0 ? 0 : mode; }
 

@@ -1,0 +1,55 @@
+// Launch interface of the one-kernel prefill (kda_prefill_fused.hip).
+#pragma once
+#include "kda_intra.h"
+
+namespace kda {
+namespace mfma {
+
+// (sequence, head) pairs per batch of the grid: the scan workgroups of a batch wait for the per-chunk
+// workgroups behind them, and about two batches' worth of them are resident at a time, each on half a
+// compute unit.
+constexpr int kMaxBatchPairs = 64;
+
+// Time-split scan (kda_scan4_split.h): workspace areas and the cut of the chunk axis.
+struct SplitArgs {
+    float *E, *Tm, *Bm;          // [kSplitMaxParts][pairs][128][128] fp32 each
+    uint32_t *flags;             // 24 counters per pair
+    int64_t part_len, part0_len;
+    int parts;                   // 1: no time split
+};
+
+struct FusedArgs {
+    const uint16_t *q, *k, *v, *log_alpha, *beta;
+    const int32_t *cu;              // cu_seqlens or NULL
+    const float *state_in;          // [N,H,dk,dv] or NULL (= zeros)
+    float *state_out;               // [N,H,dk,dv] or NULL
+    void *o;
+    uint8_t *ws;                    // first slot of the segment
+    uint32_t *ready;                // one flag per slot
+    uint32_t *status;
+    int64_t T;                      // tokens per batch row (fixed-length batches)
+    int64_t pairs;                  // num_seqs * heads
+    int64_t seg_chunks, seg_index;  // chunk indices per time segment, and which segment this launch works on
+    int64_t launch_chunks;          // chunk indices this launch covers (<= seg_chunks)
+    uint64_t wait_limit;            // ticks of the 100 MHz wall clock a scan workgroup waits for one slot
+    int H, nb;
+    float scale;
+    uint32_t epoch;                 // value of a raised flag
+    int producers;                  // 0: the per-chunk role does nothing (a diagnostic: every wait of the scan role then runs out)
+    RawParams raw;
+    SplitArgs split;
+};
+
+struct FusedLaunch {
+    FusedArgs args;
+    bool raw, scalar_gate, out_bf16;
+    bool reset_flags;               // clear num_flags words at args.ready and the status word first
+    int64_t num_flags;
+    bool reset_split;               // clear the counters of the time-split scan first (segments after the first)
+};
+
+int fused_batch_pairs(int64_t pairs);
+kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream);
+
+}  // namespace mfma
+}  // namespace kda

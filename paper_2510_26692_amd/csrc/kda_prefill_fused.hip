@@ -1,0 +1,181 @@
+// One launch for the whole matrix-core prefill (Section 3.1) of a time segment: the per-chunk
+// stage and the sequential stage are two ROLES of one kernel, chosen by workgroup index.
+//
+// Both roles are workgroups of 256 threads with 80 KiB of LDS, so any two of them share a
+// compute unit.  The grid is laid out in batches of `nb` (sequence, head) pairs:
+//
+//     [ nb scan workgroups ][ nb x chunks per-chunk workgroups, chunk index first ]  [ next batch ] ...
+//
+// Workgroups are dispatched in index order.  A scan workgroup walks the chunks of its pair and
+// takes each slot when the per-chunk workgroup that produces it has raised the slot's flag; the
+// per-chunk workgroups wait for nothing.  Every producer a scan workgroup depends on follows it
+// in the grid within its own batch, a batch holds at most kMaxBatchPairs scan workgroups, and
+// the scan workgroups of the next batch start only when the per-chunk workgroups of this one
+// have all been placed: at no time do waiting workgroups hold more than a fraction of the
+// device, whatever the number of pairs, so the producers always find room and every wait ends.
+// (The wait is bounded anyway: see kda_scan4.h.)
+//
+// No stream, event or host synchronisation is involved, so the call can be captured into a graph,
+// and tools that run one kernel at a time see a single kernel.
+#include "kda_prefill_fused.h"
+
+#include "kda_scan4.h"
+#include "kda_scan4_split.h"
+
+namespace kda {
+namespace mfma {
+
+static_assert(kIntraLds <= scan4::kLds, "both roles run in the LDS of the larger one");
+
+template <bool kRaw, bool kScalar, bool kOutBf16>
+__global__ __launch_bounds__(256, 2)
+void kda_prefill_kernel(const FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    if (a.split.parts > 1) {
+        // ---- time-split layout (few pairs): [pairs x (2 parts - 3) scan workgroups][per-chunk workgroups] ----
+        const int nsw = 2 * a.split.parts - 3;
+        const int64_t bid = blockIdx.x, nscan = a.pairs * nsw;
+        if (bid < nscan) {
+            const int y = (int)(bid / a.pairs);
+            const int64_t pair = bid - (int64_t)y * a.pairs;
+            const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
+            int64_t tok_base, len;
+            if (a.cu) { tok_base = a.cu[n]; len = (int64_t)a.cu[n + 1] - tok_base; }
+            else      { tok_base = (int64_t)n * a.T; len = a.T; }
+            const int64_t cbase = a.seg_index * a.seg_chunks;
+            int64_t nchunks = (len + kChunk - 1) / kChunk - cbase;
+            if (nchunks < 0) nchunks = 0;
+            if (nchunks > a.seg_chunks) nchunks = a.seg_chunks;
+            scan4::split_role<kOutBf16>(lds, a.split, a.ws + pair * a.seg_chunks * (int64_t)kSlotBytes, a.ready + pair * a.seg_chunks,
+                                        a.state_in, a.state_out, a.o, pair, a.pairs, y, tok_base, len, a.H, h, cbase, nchunks,
+                                        a.epoch, a.status, a.wait_limit);
+            return;
+        }
+        if (!a.producers) return;
+        // The first phase of the scan walks all ranges but the last side by side, so the chunk order
+        // interleaves those and lets the last range follow.
+        const int64_t i = bid - nscan;
+        const int64_t z = i / a.pairs, pair = i - z * a.pairs;
+        const int64_t first = a.split.parts - 1, part_len = a.split.part_len, part0_len = a.split.part0_len;
+        int64_t cl;
+        if (z < first * part_len) {
+            const int64_t rr = z % first, j = z / first;
+            if (rr == 0 && j >= part0_len) return;                   // the first range is the shorter one
+            cl = (rr == 0) ? j : part0_len + (rr - 1) * part_len + j;
+        } else {
+            cl = part0_len + (first - 1) * part_len + (z - first * part_len);
+        }
+        const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
+        kda_intra_chunk<true, kRaw, kScalar>(lds, a.q, a.k, a.v, a.log_alpha, a.beta, a.cu, a.ws, a.T, a.H, a.seg_chunks,
+                                             a.seg_index, a.scale, a.ready, a.epoch, a.raw, nullptr, nullptr, h, n, cl);
+        return;
+    }
+    const int64_t per_batch = (int64_t)a.nb * (1 + a.launch_chunks);
+    const int64_t bid = blockIdx.x;
+    const int64_t b = bid / per_batch, r = bid - b * per_batch;
+    if (r < a.nb) {
+        // ---- sequential role: one (sequence, head) ----
+        const int64_t pair = b * a.nb + r;
+        if (pair >= a.pairs) return;
+        const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
+        int64_t tok_base, len;
+        if (a.cu) { tok_base = a.cu[n]; len = (int64_t)a.cu[n + 1] - tok_base; }
+        else      { tok_base = (int64_t)n * a.T; len = a.T; }
+        const int64_t nchunks = (len + kChunk - 1) / kChunk;
+        const int64_t c_begin = a.seg_index * a.seg_chunks;
+        const int64_t c_end = (nchunks < c_begin + a.seg_chunks) ? nchunks : c_begin + a.seg_chunks;
+        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        const int64_t st_base = pair * (int64_t)(D * D) + 32 * wave + (lane & 31);
+        const uint8_t *slot0 = a.ws + pair * a.seg_chunks * (int64_t)kSlotBytes;
+        scan4::kda_scan4_body<true, kOutBf16>(lds, slot0, (int64_t)kSlotBytes, a.state_in, a.state_out, a.o, st_base,
+                                              tok_base, len, a.H, c_begin, c_end, h, a.ready + pair * a.seg_chunks, a.epoch,
+                                              a.status, a.wait_limit);
+    } else {
+        // ---- per-chunk role: one (chunk, sequence, head), chunk index first ----
+        if (!a.producers) return;
+        const int64_t i = r - a.nb;
+        const int64_t cl = i / a.nb, pl = i - cl * a.nb;
+        const int64_t pair = b * a.nb + pl;
+        if (pair >= a.pairs) return;
+        const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
+        kda_intra_chunk<true, kRaw, kScalar>(lds, a.q, a.k, a.v, a.log_alpha, a.beta, a.cu, a.ws, a.T, a.H, a.seg_chunks,
+                                             a.seg_index, a.scale, a.ready, a.epoch, a.raw, nullptr, nullptr, h, n, cl);
+    }
+}
+
+__global__ void kda_fused_fill_kernel(uint32_t *p, int64_t n, uint32_t value, uint32_t *one_more)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+    if (i == 0) *one_more = value;
+}
+
+template <bool kRaw, bool kScalar, bool kOutBf16>
+static bool reserve_one()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kda_prefill_kernel<kRaw, kScalar, kOutBf16>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, scan4::kLds) == hipSuccess;
+}
+
+static bool reserve_fused_lds()
+{
+    constexpr int kMaxDevices = 64;
+    static bool done[kMaxDevices];                          // same outcome from every thread
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+    if (done[dev]) return true;
+    const bool ok = reserve_one<false, false, false>() && reserve_one<false, false, true>() &&
+                    reserve_one<true, false, false>() && reserve_one<true, false, true>() &&
+                    reserve_one<false, true, false>() && reserve_one<false, true, true>();
+    if (!ok) (void)hipGetLastError();
+    done[dev] = ok;
+    return ok;
+}
+
+int fused_batch_pairs(int64_t pairs)
+{
+    return (int)(pairs < kMaxBatchPairs ? pairs : kMaxBatchPairs);
+}
+
+kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
+{
+    if (!reserve_fused_lds())
+        return fail(KDA_ERR_LAUNCH, "cannot reserve %d bytes of LDS for the prefill kernel", scan4::kLds);
+    FusedArgs a = L.args;
+    a.nb = fused_batch_pairs(a.pairs);
+    int64_t blocks;
+    if (a.split.parts > 1) {
+        blocks = a.pairs * (int64_t)(2 * a.split.parts - 3) + a.pairs * (int64_t)a.split.parts * a.split.part_len;
+    } else {
+        const int64_t nbatches = (a.pairs + a.nb - 1) / a.nb;
+        blocks = nbatches * (int64_t)a.nb * (1 + a.launch_chunks);
+    }
+    if (blocks > 0x7fffffffLL)
+        return fail(KDA_ERR_UNSUPPORTED, "%lld workgroups in one launch: use a smaller workspace (shorter time segments)",
+                    (long long)blocks);
+    if (L.reset_split)
+        hipLaunchKernelGGL(kda_fused_fill_kernel, dim3((unsigned)(kSplitFlagBytes / 4 / 256)), dim3(256), 0, stream,
+                           a.split.flags, (int64_t)(kSplitFlagBytes / 4), 0u, a.split.flags);
+    // the slot flags and the status word start every call at zero (a kernel, not a memset: the call may be captured)
+    if (L.reset_flags)
+        hipLaunchKernelGGL(kda_fused_fill_kernel, dim3((unsigned)((L.num_flags + 255) / 256 + 1)), dim3(256), 0, stream,
+                           a.ready, L.num_flags, 0u, a.status);
+    auto kern = L.scalar_gate ? (L.out_bf16 ? kda_prefill_kernel<false, true, true> : kda_prefill_kernel<false, true, false>)
+                : L.raw ? (L.out_bf16 ? kda_prefill_kernel<true, false, true> : kda_prefill_kernel<true, false, false>)
+                        : (L.out_bf16 ? kda_prefill_kernel<false, false, true> : kda_prefill_kernel<false, false, false>);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), scan4::kLds, stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_prefill_kernel: %s", hipGetErrorString(e));
+    return KDA_OK;
+}
+
+}  // namespace mfma
+}  // namespace kda
+
+#ifdef KDA_SCAN4_TRACE
+extern "C" int kda_debug_read_trace(unsigned long long *out)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(kda::mfma::scan4::g_trace), sizeof(unsigned long long) * 64 * 8, 0, hipMemcpyDeviceToHost);
+}
+#endif
