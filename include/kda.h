@@ -13,42 +13,26 @@
  *
  * Conventions shared by every call
  *   - All tensor pointers are DEVICE pointers to contiguous row-major arrays,
- *     16-byte aligned.  The caller owns every buffer, including the workspace;
- *     the library allocates no device memory and frees none.  The only state
- *     it keeps is a pair of helper streams with four events per device (up to
- *     seven idle streams that were tried for the pair, 64 bytes of pinned host
- *     memory and one event per caller stream seen, 16 at most), created by the first
- *     bf16 kda_chunk_fwd call that uses them; that one call synchronises with the
- *     two new streams once, to check that they run at the same time.
+ *     16-byte aligned.  The caller owns every buffer, including the workspace.
+ *     The library allocates nothing, frees nothing, creates no stream or event
+ *     and keeps no state between calls (beyond per-device caches of constant
+ *     device attributes).
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
- *     NULL = default stream); no host synchronisation happens inside (but see
- *     the first call, above).  Work
- *     that a call puts on the helper streams is ordered after everything queued
- *     on `hip_stream` before the call, and `hip_stream` waits for it before
- *     the call's work counts as complete: to the caller the call behaves as if
- *     everything ran on `hip_stream`.
+ *     NULL = default stream): every kernel of a call is launched on that stream,
+ *     no host synchronisation happens inside (kda_chunk_fwd_check, which exists to
+ *     wait, aside), and a call may be captured into a graph.
  *   - Concurrency: calls may be issued from several host threads and on several
  *     streams at once, each with its own workspace (a workspace belongs to one call
- *     until that call has completed).  A bf16 kda_chunk_fwd whose two kernels run side
- *     by side makes one of them wait for the other, and a hardware queue runs its
- *     kernels in order (a process has few hardware queues for all its streams).  Such
- *     calls therefore put both kernels on a pair of library streams per device, shared
- *     by all host threads and checked, when they are created, to run at the same time;
- *     the producer kernels follow each other on one of them in the order the calls were
- *     issued, and nothing on that stream ever waits.  The waiting kernel moves to the
- *     caller's own stream (which saves two event hops) once a probe that the library
- *     queues on that stream, without waiting for it, has shown that the stream runs
- *     beside the producers' stream.  Calls that come down different streams run side
- *     by side one at a time: while another stream's call is still producing, a call
- *     runs its kernels one after the other.  So no kernel ever waits for one that is
- *     queued behind a waiting kernel, whatever streams the callers use (a stream
- *     handle that is destroyed and re-created with the same value keeps the old
- *     answer of the probe).  Such a call keeps one compute unit per (sequence, head) waiting on
- *     its producer kernel (up to three eighths of the device), which other work in
- *     flight on the device has to live beside; should the producer be starved for about
- *     two seconds the waiting kernel gives up and kda_chunk_fwd_check reports it.
- *     kda_debug_set_overlap(0) (or KDA_PREFILL_OVERLAP=0 in the environment) keeps every
- *     call on the caller's stream and free of waits.
+ *     until that call has completed).  The bf16 prefill runs its per-chunk stage and
+ *     its sequential stage as workgroups of ONE kernel: the sequential workgroups (one
+ *     per (sequence, head), each on half a compute unit, at most about 130 of them
+ *     resident at a time) wait for the slots that the per-chunk workgroups behind them
+ *     in the same grid produce.  The producers wait for nothing and are dispatched as
+ *     soon as any half compute unit is free, so every wait ends; each wait is bounded
+ *     all the same (about two seconds).  Should other work on the device starve the
+ *     producers that long, the waiting workgroup gives up: the call's later outputs for
+ *     that (sequence, head) and its final state are NaN, never stale data, and
+ *     kda_chunk_fwd_check reports it.
  *   - Element offsets are 64-bit; tensors with more than 2^31 elements are fine.
  *   - Errors: a non-zero kda_status is returned and kda_last_error() holds a
  *     thread-local description.  For KDA_ERR_INVALID_ARG, KDA_ERR_UNSUPPORTED
@@ -144,8 +128,13 @@ size_t kda_chunk_fwd_min_workspace_size(const kda_dims *dims);
  * o must not alias any input.  Arithmetic: KDA_F32 inputs are processed in fp32
  * throughout; KDA_BF16 inputs use fp16 matrix-core operands with fp32
  * accumulation, fp32 cumulative decay and an fp32 state.  Domain of the KDA_BF16
- * path: entries of q and k within +-3.9 (the paper's q and k are L2-normalised,
- * Section 4), and states and values small enough for fp16 (below 65504).
+ * path: |k_t| <= 4 and entries of q within +-3.9 (the paper's q and k are
+ * L2-normalised, Section 4), and states, values and pseudo-values small enough for
+ * fp16 (below 65504 in magnitude).  bf16 inputs convert to fp16 exactly while their magnitude is
+ * zero or within [2^-14, 65504]; smaller ones lose bits or flush, larger ones
+ * become infinite.  Beyond the domain an fp16 operand overflows to infinity and
+ * the affected outputs and states come back as Inf or NaN; kda_chunk_fwd_check
+ * reports a key beyond the domain and a state that is not finite.
  */
 kda_status kda_chunk_fwd(const kda_dims *dims,
                          const void *q, const void *k, const void *v,
@@ -267,11 +256,13 @@ kda_status kda_chunk_fwd_scalar_gate(const kda_dims *dims,
 /*
  * Optional check after a bf16 kda_chunk_fwd: waits for `hip_stream` and reads
  * the status word that the call left in `workspace` (same dims, workspace and
- * size as that call).  The sequential kernel of the prefill may run next to
- * the per-chunk kernel and then waits, for a bounded time, for each workspace
- * slot; if such a wait ever ran out, the outputs of the call are invalid and
- * this returns KDA_ERR_LAUNCH.  KDA_OK otherwise (also for calls that keep no
- * status word).
+ * size as that call).  The sequential workgroups of the prefill wait, for a
+ * bounded time, for each workspace slot; if such a wait ever ran out, the call
+ * has written NaN to o from that point of the (sequence, head) on and to its
+ * final state, and this returns KDA_ERR_LAUNCH.  If a state of the call ended
+ * up not finite (an fp16 operand overflowed) or a key was beyond the domain
+ * stated at kda_chunk_fwd it returns KDA_ERR_INVALID_ARG.  KDA_OK otherwise (also for
+ * calls that keep no status word: fp32 inputs, and calls with the output gate).
  */
 kda_status kda_chunk_fwd_check(const kda_dims *dims, const void *workspace, size_t workspace_bytes,
                                void *hip_stream);
@@ -342,44 +333,6 @@ const char *kda_status_string(kda_status status);
 
 /* Detail of the last error raised on the calling thread ("" if none). */
 const char *kda_last_error(void);
-
-/*
- * Diagnostics for per-kernel timing only: selects which kernels of the
- * matrix-core prefill run on later kda_chunk_fwd calls (bit 0: the per-chunk
- * kernel, bit 1: the sequential scan; default 3).  With a bit cleared the
- * outputs of that call are incomplete and the two kernels never overlap.
- * Process-wide, not thread-safe.
- */
-void kda_debug_set_phase_mask(int mask);
-
-/*
- * Diagnostics: 0 makes the matrix-core prefill run its two kernels strictly one
- * after the other on `hip_stream`; 1 (default) lets them overlap when there are
- * few enough (sequence, head) pairs.  Results are identical either way.
- * KDA_PREFILL_OVERLAP=0 in the environment sets the default to 0.  Use 0 under
- * tools that run kernels strictly one at a time (hardware-counter collection):
- * there the sequential kernel would wait for slots that cannot be produced
- * until it has given up (bounded, about two seconds; see kda_chunk_fwd_check).
- * Calls made while `hip_stream` is being captured into a graph never overlap.
- * Process-wide, not thread-safe.
- */
-void kda_debug_set_overlap(int enabled);
-
-/*
- * Diagnostics: 0 keeps the sequential kernel of the matrix-core prefill to one workgroup per
- * (sequence, head); 1 (default) lets calls with few pairs and long sequences cut the chunk axis into
- * ranges that several workgroups walk at the same time (the chunk recurrence is affine in the state,
- * S_out = T S_in + B, so a range's T and B can be formed before its initial state is known).  Results
- * agree within rounding, not bit for bit.  The workgroups of such a launch wait for one another
- * (first the ranges' transitions, then the folded states), again for a bounded time that
- * kda_chunk_fwd_check reports; they all fit the device at once, so every wait ends, also under
- * tools that run one kernel at a time.  With 1 the library estimates whether, and into how many
- * ranges, a call is worth splitting; a value of 3..8 takes that many ranges whatever the estimate
- * says (still lowered to what the device and the sequence length allow; calls with fewer than 24
- * chunks are never split).  KDA_PREFILL_TIME_SPLIT=0 in the environment sets the default to 0.
- * Process-wide, not thread-safe.
- */
-void kda_debug_set_time_split(int mode);
 
 /* Library version string, e.g. "kda-gfx950 0.1". */
 const char *kda_version(void);

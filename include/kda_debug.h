@@ -1,0 +1,52 @@
+/*
+ * libkda diagnostics: switches and queries for tests and measurement, not part of the product
+ * interface of kda.h.  The switches are process-wide and read at the start of each call; they are
+ * not synchronised with calls made from other threads at the same time.
+ */
+#ifndef KDA_DEBUG_H_
+#define KDA_DEBUG_H_
+
+#include "kda.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * 0 keeps the sequential stage of the matrix-core prefill to one workgroup per (sequence, head);
+ * 1 (default) lets calls with few pairs and long sequences cut the chunk axis into ranges that
+ * several workgroups walk at the same time (the chunk recurrence of Section 3.1 is affine in the
+ * state, S_out = T S_in + B, so a range's T and B can be formed before its initial state is known).
+ * Results agree within rounding, not bit for bit.  With 1 the library estimates whether, and into
+ * how many ranges, a call is worth splitting; a value of 3..8 takes that many ranges whatever the
+ * estimate says (still lowered to what the device and the sequence length allow; calls with fewer
+ * than 24 chunks, more than 42 pairs or the output gate are never split).
+ * KDA_PREFILL_TIME_SPLIT=0 in the environment sets the default to 0.
+ */
+void kda_debug_set_time_split(int mode);
+
+/*
+ * Fault injection for the bounded waits of the matrix-core prefill, driven from the host so that
+ * every kernel still runs to its end.  kda_debug_set_producers(0) makes the per-chunk workgroups of
+ * later calls return at once: no slot is ever produced, so every wait of the sequential stage runs
+ * out after kda_debug_set_wait_limit(ticks) ticks of the 100 MHz device wall clock (default
+ * 200 000 000 = two seconds; 0 = give up at the first look).  Such a call still returns KDA_OK,
+ * writes NaN to o and h_T (see kda_chunk_fwd) and leaves the status word that kda_chunk_fwd_check
+ * reports.  kda_debug_set_producers(1) restores normal operation.
+ */
+void kda_debug_set_producers(int enabled);
+void kda_debug_set_wait_limit(unsigned long long ticks);
+
+/*
+ * What kda_chunk_fwd (output_gate = 0) or kda_chunk_fwd_fused with an output gate (1) would do with
+ * a workspace of `workspace_bytes` on the current device: out[0] chunk indices per time segment,
+ * out[1] time segments, out[2] ranges of the time-split scan (1 = not split), out[3] chunks in the
+ * first range of a segment, out[4] chunks in each of the others.  Launches nothing.
+ */
+kda_status kda_debug_chunk_fwd_plan(const kda_dims *dims, size_t workspace_bytes, int output_gate,
+                                    int64_t out[5]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KDA_DEBUG_H_ */

@@ -1,12 +1,13 @@
 // C ABI of libkda: argument validation, error strings and dispatch to the
 // kernels.  Nothing here touches tensor data; every step of the path runs in
-// the kernels of kda_step.hip, kda_chunk_f32.hip, kda_chunk_mfma.hip and kda_chunk_bwd.hip.
+// the kernels of kda_step.hip, kda_chunk_f32.hip, kda_prefill_fused.hip, kda_prefill_gated.hip and kda_chunk_bwd.hip.
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
 #include "kda_common.h"
+#include "kda_debug.h"
 
 namespace kda {
 
@@ -34,6 +35,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *, const kda_prologue *, const kda
                                float *, void *, size_t, bool scalar_gate, hipStream_t);
 size_t chunk_mfma_workspace_size(const kda_dims *, bool minimal, bool output_gate);
 size_t chunk_mfma_status_offset(const kda_dims *, size_t workspace_bytes);
+kda_status chunk_mfma_plan(const kda_dims *, size_t workspace_bytes, bool gate, int64_t out[5]);
 size_t chunk_bwd_workspace_size(const kda_dims *);
 size_t chunk_f32_fast_workspace_size(const kda_dims *);
 kda_status chunk_f32_fast_dispatch(const kda_dims *, const void *, const void *, const void *, const void *,
@@ -44,18 +46,9 @@ kda_status chunk_bwd_dispatch(const kda_dims *, const void *, const void *, cons
                               float *, float *, float *, float *, float *, float *, void *, size_t,
                               hipStream_t);
 
-// Diagnostics: which kernels of the matrix-core prefill run (bit 0 kda_intra, bit 1 kda_scan).
-int g_phase_mask = 3;
-// 0 keeps kda_intra and kda_scan strictly one after the other (kda_debug_set_overlap, or
-// KDA_PREFILL_OVERLAP=0 in the environment when the library is loaded).
-static int overlap_default()
-{
-    const char *e = getenv("KDA_PREFILL_OVERLAP");
-    return (e && e[0] == '0' && e[1] == 0) ? 0 : 1;
-}
-int g_overlap = overlap_default();
-// 0 keeps the sequential kernel to one workgroup per (sequence, head) whatever the shape
-// (kda_debug_set_time_split, or KDA_PREFILL_TIME_SPLIT=0 in the environment).
+// Diagnostics switches (kda_debug.h): process-wide, read at the start of a call.
+// 0 keeps the sequential stage of the matrix-core prefill to one workgroup per (sequence, head) whatever
+// the shape (kda_debug_set_time_split, or KDA_PREFILL_TIME_SPLIT=0 in the environment).
 static int split_default()
 {
     const char *e = getenv("KDA_PREFILL_TIME_SPLIT");
@@ -71,14 +64,8 @@ static double split_ratio_default()
     return (r >= 0.2 && r <= 1.0) ? r : 0.0;
 }
 double g_split_ratio = split_ratio_default();
-static int fused_default()
-{
-    const char *e = getenv("KDA_PREFILL_FUSED");
-    return (e && e[0] == '0' && e[1] == 0) ? 0 : 1;
-}
-int g_fused = fused_default();
-int g_producers = 1;
-uint64_t g_wait_limit = 200000000ull;     // two seconds
+int g_producers = 1;                      // 0: the per-chunk role of the one-kernel prefill does nothing
+uint64_t g_wait_limit = 200000000ull;     // ticks of the 100 MHz wall clock a scan workgroup waits for a slot: two seconds
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -128,15 +115,23 @@ extern "C" {
 
 const char *kda_version(void) { return "kda-gfx950 0.1"; }
 
-void kda_debug_set_phase_mask(int mask) { g_phase_mask = mask & 3; }
-
-void kda_debug_set_overlap(int enabled) { g_overlap = enabled ? 1 : 0; }
-
 void kda_debug_set_producers(int enabled) { g_producers = enabled ? 1 : 0; }
 
 void kda_debug_set_wait_limit(unsigned long long ticks) { g_wait_limit = ticks; }
 
 void kda_debug_set_time_split(int mode) { g_split = mode < 0 ? 0 : mode; }
+
+kda_status kda_debug_chunk_fwd_plan(const kda_dims *d, size_t workspace_bytes, int output_gate, int64_t out[5])
+{
+    g_last_error[0] = 0;
+    if (!d || !out) return fail(KDA_ERR_INVALID_ARG, "dims or out is NULL");
+    if (d->chunk != kChunk) return fail(KDA_ERR_UNSUPPORTED, "chunk must be %d, got %d", kChunk, d->chunk);
+    const kda_status st = check_dims(d, d->num_seqs != d->batch);
+    if (st != KDA_OK) return st;
+    if (!mfma_path(d)) return fail(KDA_ERR_UNSUPPORTED, "only the matrix-core prefill (bf16 inputs, dk = dv = 128) has a plan");
+    if (d->seqlen == 0 || d->num_seqs == 0 || d->heads == 0) { out[0] = out[1] = out[3] = out[4] = 0; out[2] = 1; return KDA_OK; }
+    return chunk_mfma_plan(d, workspace_bytes, output_gate != 0, out);
+}
 
 const char *kda_last_error(void) { return g_last_error; }
 
@@ -329,9 +324,15 @@ kda_status kda_chunk_fwd_check(const kda_dims *d, const void *workspace, size_t 
     e = hipMemcpy(&word, static_cast<const uint8_t *>(workspace) + chunk_mfma_status_offset(d, workspace_bytes),
                   sizeof(word), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "status read: %s", hipGetErrorString(e));
-    if (word != 0)
-        return fail(KDA_ERR_LAUNCH, "kda_scan gave up waiting for a workspace slot (status %u): outputs are invalid",
-                    word);
+    if (word & 1u)
+        return fail(KDA_ERR_LAUNCH, "the sequential stage gave up waiting for a workspace slot (status %u): o is NaN from "
+                    "that point of each affected (sequence, head) on, and so is its final state", word);
+    if (word & 4u)
+        return fail(KDA_ERR_INVALID_ARG, "a key outside the domain of the fp16 matrix-core operands (status %u): |k_t|^2 > 16 "
+                    "for some token; the results may be inaccurate or not finite", word);
+    if (word & 2u)
+        return fail(KDA_ERR_INVALID_ARG, "a state left the range of the fp16 matrix-core operands (status %u): inputs outside "
+                    "the documented domain; the affected outputs are Inf or NaN", word);
     return KDA_OK;
 }
 

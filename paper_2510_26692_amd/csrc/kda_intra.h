@@ -33,6 +33,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+constexpr float kMaxKeyNorm2 = 16.0f;  // |k_t|^2 up to which the fp16 operands are safe (entries then stay below 4)
 constexpr float kStrongLog2 = 24.0f;   // sub-chunk decay below 2^-24 leaves the fast operands
 constexpr float kRowScale = 4.0f;      // keeps small row operands out of the fp16 subnormals
 constexpr float kRowShift = 2.0f;      // log2(kRowScale)
@@ -150,6 +151,8 @@ __device__ __forceinline__ float log2_alpha_from_gate(float x, float a)
 
 // Workgroup of 256 threads (four waves), kIntraLds bytes of LDS at `lds`; (h, n, cl): head, sequence and
 // chunk index inside the time segment.  Every thread of the workgroup must make the call (barriers inside).
+// status (may be NULL): bit 2 is raised when a key of the chunk has |k_t|^2 > kMaxKeyNorm2, beyond which the fp16
+// operands may overflow and the UT transform loses accuracy (the paper's keys are L2-normalised, Section 4).
 template <bool kHandoff, bool kRaw, bool kScalar = false>
 __device__ __forceinline__
 void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
@@ -157,7 +160,8 @@ void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_
                      const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
                      uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
                      int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch, RawParams raw,
-                     const uint16_t *__restrict__ out_gate, uint8_t *__restrict__ gate_ws, int h, int n, int64_t cl)
+                     const uint16_t *__restrict__ out_gate, uint8_t *__restrict__ gate_ws, int h, int n, int64_t cl,
+                     uint32_t *status = nullptr)
 {
     // (the wave index is the same in all lanes: telling the compiler so turns the per-wave cases
     // below into scalar branches instead of masked vector code)
@@ -317,6 +321,14 @@ void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_
             for (int ks = 0; ks < 4; ++ks) {
                 akk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowK[ks], rowK[ks], akk, 0, 0, 0);
                 aqk = __builtin_amdgcn_mfma_f32_16x16x32_f16(rowQ[ks], rowK[ks], aqk, 0, 0, 0);
+            }
+            // the diagonal of the diagonal tile is |k_t|^2: the domain check of the keys costs a few compares
+            if (status) {
+                bool bad = false;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bad |= (4 * g + j == m) && !(akk[j] <= kMaxKeyNorm2);
+                if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0)
+                    __hip_atomic_fetch_or(status, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             res_kk[R] = akk; res_qk[R] = aqk;
         }
@@ -608,6 +620,14 @@ void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 }
             }
+        }
+        // the diagonal of the diagonal tile is |k_t|^2: the domain check of the keys costs a few compares
+        if (status) {
+            bool bad = false;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bad |= (4 * g + j == m) && !(akk[j] <= kMaxKeyNorm2);
+            if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0)
+                __hip_atomic_fetch_or(status, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         res_kk[R] = akk; res_qk[R] = aqk;
     }

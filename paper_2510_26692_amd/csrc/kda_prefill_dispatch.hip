@@ -1,0 +1,293 @@
+// Host side of the matrix-core prefill (bf16 inputs, d_k = d_v = 128, C = 64): workspace plan, the
+// decision whether to cut the chunk axis into ranges, and the launches.  No kernel lives here; the
+// device code is in kda_prefill_fused.hip (every call but those with the output gate) and
+// kda_prefill_gated.hip.
+//
+// Nothing is allocated, no stream or event is created and the host never waits: a call is one or
+// two launches per time segment on the caller's stream (plus a small fill kernel for the flags).
+#include <stdlib.h>
+
+#include "kda_prefill_fused.h"
+#include "kda_prefill_gated.h"
+
+namespace kda {
+
+extern int g_split;            // diagnostics switches owned by kda_api.hip (see kda_debug.h)
+extern double g_split_ratio;
+extern int g_producers;
+extern uint64_t g_wait_limit;
+
+namespace mfma {
+
+__global__ void kda_zero_words_kernel(uint32_t *p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+static int64_t max_chunks_per_seq(const kda_dims *d)
+{
+    int64_t longest = d->seqlen;
+    if (d->num_seqs != d->batch || d->batch == 1) {           // packed (or a single row)
+        if (d->max_seqlen > 0 && d->max_seqlen < longest) longest = d->max_seqlen;
+    }
+    return (longest + kChunk - 1) / kChunk;
+}
+
+static size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workspace: [status word, 256 B][slots of one segment, pair by pair][state carry][ready flags, one per slot]
+// [time-split counters and states][staged gate logits]; the last two only when the call can use them.
+static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
+{
+    SegPlan p;
+    const int64_t maxc = max_chunks_per_seq(d);
+    const size_t streams = (size_t)d->num_seqs * d->heads;
+    const size_t carry = streams * D * D * sizeof(float);
+    p.seg_chunks = sc;
+    p.num_segments = (maxc + sc - 1) / sc;
+    p.status_offset = 0;                                  // the same place whatever the segment size
+    p.slots_offset = 256;
+    p.carry_offset = p.slots_offset + (size_t)sc * streams * kSlotBytes;
+    p.flags_offset = p.carry_offset + carry;
+    p.split_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
+    // counters and states of the time-split scan, when the call qualifies for it
+    const bool split = !gate && streams <= (size_t)kSplitMaxPairs && sc >= kSplitMinChunks;
+    p.total_bytes = p.split_offset + (split ? kSplitFlagBytes + 3 * (size_t)kSplitMaxParts * carry : 0);
+    p.gate_offset = 0;
+    if (gate) {
+        p.gate_offset = round_up(p.total_bytes, 256);
+        p.total_bytes = p.gate_offset + (size_t)sc * streams * kGateSlotBytes;
+    }
+    return p;
+}
+
+// Number of ranges for the time-split scan (1 = plain scan).  Every workgroup of either stage takes
+// half a compute unit; a split launch keeps 2 parts - 3 such slots per pair busy with the scan, at
+// most three eighths of all slots, so that the per-chunk stage, the larger half of the work, keeps
+// the rest.  Among the admissible numbers the one with the smallest estimated duration is taken,
+// the plain scan included.  The estimate (microseconds, measured on MI355X with both stages sharing
+// the compute units): a step of the scan 3.0, a chunk of the per-chunk stage 17 on one slot, the
+// fold and the extra start-up of a split launch 60 + 12 per middle range.  The first phase needs
+// the first parts - 1 ranges produced, the last range one more phase after everything before it.
+// forced = 3..8: the largest admissible number up to `forced`, whatever the estimate says.
+static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forced, double *first_ratio)
+{
+    *first_ratio = 1.0;
+    int64_t maxc = max_chunks_per_seq(d);                    // chunks one launch walks
+    if (maxc > plan.seg_chunks) maxc = plan.seg_chunks;
+    const int64_t pairs = (int64_t)d->num_seqs * d->heads;
+    const int64_t slots = 2 * (int64_t)cus;
+    if (pairs > kSplitMaxPairs || maxc < kSplitMinChunks || pairs >= slots) return 1;
+    const double step = 3.0, item = 17.0;
+    const double items = (double)pairs * (double)maxc;
+    const double t_scan = (double)maxc * step, t_intra1 = items * item / (double)(slots - pairs);
+    double best = t_scan > t_intra1 ? t_scan : t_intra1;
+    int parts = 1;
+    for (int p = 3; p <= kSplitMaxParts; ++p) {
+        const int64_t len = (maxc + p - 1) / p;
+        if (pairs * (2 * p - 3) * 8 > slots * 3 || len < 8) continue;
+        const double phase = (double)len * step;
+        const double t_intra = items * item / (double)(slots - pairs * (2 * p - 3));
+        const double fed = t_intra * (double)(p - 1) / (double)p;
+        // The first range is walked by the full scan, the others by passes that write no output and
+        // fetch less, about 0.7 of its time per step: when the scan, not the per-chunk stage, sets the
+        // pace of the first phase, the first range is made shorter by that ratio.
+        const double ratio = (phase >= 1.5 * fed) ? 0.7 : 1.0;
+        if (forced >= 3) {
+            if (p <= forced) { parts = p; *first_ratio = ratio; }
+            continue;
+        }
+        const double t1 = phase > fed ? phase : fed;
+        double t = t1 + 60.0 + 12.0 * (p - 2) + phase;
+        if (t_intra + 2 * step > t) t = t_intra + 2 * step;
+        if (t < best) { best = t; parts = p; *first_ratio = ratio; }
+    }
+    return parts;
+}
+
+// The plan with the most chunk indices per segment that fits `workspace_bytes` (full: no limit).
+static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full, bool gate)
+{
+    const int64_t maxc = max_chunks_per_seq(d);
+    int64_t sc = maxc < 1 ? 1 : maxc;
+    if (sc > 65535) sc = 65535;                               // grid dimension limit of the gated path
+    if (!full) {
+        const size_t streams = (size_t)d->num_seqs * d->heads;
+        const size_t per_chunk_index = streams * (kSlotBytes + sizeof(uint32_t) + (gate ? kGateSlotBytes : 0));
+        const size_t fixed = plan_with(d, 1, gate).total_bytes - per_chunk_index;
+        const size_t avail = workspace_bytes > fixed ? workspace_bytes - fixed : 0;
+        const int64_t fit = per_chunk_index ? (int64_t)(avail / per_chunk_index) : sc;
+        if (fit < sc) sc = fit;
+        if (sc < 1) sc = 1;
+        while (sc > 1 && plan_with(d, sc, gate).total_bytes > workspace_bytes) --sc;   // rounding of the flag area, time-split area
+    }
+    return plan_with(d, sc, gate);
+}
+
+// Compute units of the current device (cached per device), 0 on failure.
+static int compute_units()
+{
+    constexpr int kMaxDevices = 64;
+    static int table[kMaxDevices];                          // 0 = not asked yet; same value from every thread
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    if (table[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { n = 0; (void)hipGetLastError(); }
+        table[dev] = n;
+    }
+    return table[dev];
+}
+
+}  // namespace mfma
+
+size_t chunk_mfma_workspace_size(const kda_dims *d, bool minimal, bool gate)
+{
+    if (d->num_seqs == 0 || d->heads == 0 || d->seqlen == 0) return 0;
+    if (minimal) {
+        // four chunk indices per segment keep the launches from being pure overhead
+        const int64_t maxc = mfma::max_chunks_per_seq(d);
+        return mfma::plan_with(d, maxc < 4 ? maxc : 4, gate).total_bytes;
+    }
+    return mfma::make_plan(d, 0, true, gate).total_bytes;
+}
+
+size_t chunk_mfma_status_offset(const kda_dims *d, size_t workspace_bytes)
+{
+    return mfma::make_plan(d, workspace_bytes, false, false).status_offset;
+}
+
+// What a call with this workspace would do: out[0] chunk indices per time segment, [1] time segments,
+// [2] ranges of the time-split scan (1: none), [3] length of the first range, [4] of the others (chunks).
+kda_status chunk_mfma_plan(const kda_dims *d, size_t workspace_bytes, bool gate, int64_t out[5])
+{
+    using namespace mfma;
+    const SegPlan plan = make_plan(d, workspace_bytes, false, gate);
+    if (plan.total_bytes > workspace_bytes) return fail(KDA_ERR_WORKSPACE, "workspace too small for any plan");
+    const int cus = compute_units();
+    if (cus <= 0) return fail(KDA_ERR_LAUNCH, "cannot query the device");
+    double ratio = 1.0;
+    const int parts = (g_split && !gate) ? split_parts(plan, d, cus, g_split, &ratio) : 1;
+    if (g_split_ratio > 0.0) ratio = g_split_ratio;
+    out[0] = plan.seg_chunks; out[1] = plan.num_segments; out[2] = parts; out[3] = 0; out[4] = 0;
+    if (parts > 1) {
+        int64_t part0_len = (int64_t)((double)plan.seg_chunks * ratio / ((double)(parts - 1) + ratio) + 0.5);
+        if (part0_len < 1) part0_len = 1;
+        out[3] = part0_len;
+        out[4] = (plan.seg_chunks - part0_len + parts - 2) / (parts - 1);
+    }
+    return KDA_OK;
+}
+
+kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const kda_epilogue *epi,
+                               const void *q, const void *k,
+                               const void *v, const void *log_alpha, const void *beta, const float *h0,
+                               const int32_t *cu, void *o, float *hT, void *workspace,
+                               size_t workspace_bytes, bool scalar_gate, hipStream_t stream)
+{
+    using namespace mfma;
+    RawParams raw = {nullptr, nullptr, 0.f};
+    if (pro) { raw.a_scale = pro->a_scale; raw.dt_bias = pro->dt_bias; raw.eps = pro->l2norm_eps; }
+    const bool out_bf16 = d->out_dtype == KDA_BF16;
+    if (d->seqlen == 0) {
+        // nothing to scan: the final state is the initial one
+        if (hT && hT != h0) {
+            const size_t bytes = (size_t)d->num_seqs * d->heads * D * D * sizeof(float);
+            hipError_t e = hipSuccess;
+            if (h0) {
+                e = hipMemcpyAsync(hT, h0, bytes, hipMemcpyDeviceToDevice, stream);
+            } else {
+                // (a fill kernel rather than a memset: the call may be captured into a graph)
+                const int64_t words = (int64_t)(bytes / 4);
+                hipLaunchKernelGGL(kda_zero_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream,
+                                   reinterpret_cast<uint32_t *>(hT), words);
+                e = hipGetLastError();
+            }
+            if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "state copy: %s", hipGetErrorString(e));
+        }
+        return KDA_OK;
+    }
+    const SegPlan plan = make_plan(d, workspace_bytes, false, epi != nullptr);
+    if (plan.total_bytes > workspace_bytes)
+        return fail(KDA_ERR_WORKSPACE, "workspace has %zu bytes, segment plan needs %zu", workspace_bytes,
+                    plan.total_bytes);
+    if (d->num_seqs > 65535)
+        return fail(KDA_ERR_UNSUPPORTED, "more than 65535 sequences in one call: %d", d->num_seqs);
+    if ((int64_t)d->num_seqs * d->heads > 0x7fffffffLL)
+        return fail(KDA_ERR_UNSUPPORTED, "num_seqs * heads exceeds 2^31 - 1");
+    const int cus = compute_units();
+    if (cus <= 0) return fail(KDA_ERR_LAUNCH, "cannot query the device");
+
+    uint8_t *base = static_cast<uint8_t *>(workspace);
+    uint8_t *ws = base + plan.slots_offset;
+    float *carry = hT ? hT : reinterpret_cast<float *>(base + plan.carry_offset);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(base + plan.flags_offset);
+    uint32_t *status = reinterpret_cast<uint32_t *>(base + plan.status_offset);
+    const uint16_t *q16 = static_cast<const uint16_t *>(q), *k16 = static_cast<const uint16_t *>(k),
+                   *v16 = static_cast<const uint16_t *>(v), *g16 = static_cast<const uint16_t *>(log_alpha),
+                   *b16 = static_cast<const uint16_t *>(beta);
+    const int64_t streams = (int64_t)d->num_seqs * d->heads;
+    const int64_t maxc = max_chunks_per_seq(d);
+
+    if (epi) {
+        // the output gate: two kernels per segment, one after the other
+        for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
+            GatedLaunch L{};
+            L.q = q16; L.k = k16; L.v = v16; L.log_alpha = g16; L.beta = b16; L.cu = cu;
+            L.state_in = (seg == 0) ? h0 : carry;
+            L.state_out = (plan.num_segments > 1 || hT) ? carry : nullptr;
+            L.o = o; L.ws = ws; L.gate_ws = base + plan.gate_offset; L.status = status;
+            L.gate = static_cast<const uint16_t *>(epi->gate); L.norm_w = epi->norm_weight; L.rms_eps = epi->rms_eps;
+            L.scale = d->scale; L.T = d->seqlen; L.seg_chunks = plan.seg_chunks; L.seg_index = seg;
+            const int64_t left = maxc - seg * plan.seg_chunks;
+            L.launch_chunks = left < plan.seg_chunks ? left : plan.seg_chunks;
+            L.H = d->heads; L.num_seqs = d->num_seqs; L.raw_inputs = pro != nullptr; L.out_bf16 = out_bf16; L.raw = raw;
+            const kda_status st = launch_prefill_gated(L, stream);
+            if (st != KDA_OK) return st;
+        }
+        return KDA_OK;
+    }
+
+    // One launch per time segment, both stages as roles of one kernel.
+    double ratio = 1.0;
+    const int parts = g_split ? split_parts(plan, d, cus, g_split, &ratio) : 1;
+    if (g_split_ratio > 0.0) ratio = g_split_ratio;
+    int64_t part0_len = 0, part_len = 0;
+    if (parts > 1) {
+        // ranges: the first one shorter by the ratio of the step times (full scan : passes without output)
+        part0_len = (int64_t)((double)plan.seg_chunks * ratio / ((double)(parts - 1) + ratio) + 0.5);
+        if (part0_len < 1) part0_len = 1;
+        part_len = (plan.seg_chunks - part0_len + parts - 2) / (parts - 1);
+    }
+    const size_t pair_states = (size_t)streams * D * D;
+    for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
+        FusedLaunch L{};
+        FusedArgs &a = L.args;
+        a.q = q16; a.k = k16; a.v = v16; a.log_alpha = g16; a.beta = b16; a.cu = cu;
+        a.state_in = (seg == 0) ? h0 : carry;
+        a.state_out = (plan.num_segments > 1 || hT) ? carry : nullptr;
+        a.o = o; a.ws = ws; a.ready = flags; a.status = status;
+        a.T = d->seqlen; a.pairs = streams; a.seg_chunks = plan.seg_chunks; a.seg_index = seg;
+        const int64_t left = maxc - seg * plan.seg_chunks;
+        a.launch_chunks = left < plan.seg_chunks ? left : plan.seg_chunks;
+        a.wait_limit = g_wait_limit; a.H = d->heads; a.scale = d->scale; a.epoch = (uint32_t)(seg + 1);
+        a.producers = g_producers; a.raw = raw;
+        a.split.parts = parts; a.split.part_len = part_len; a.split.part0_len = part0_len;
+        a.split.flags = reinterpret_cast<uint32_t *>(base + plan.split_offset);
+        a.split.E = reinterpret_cast<float *>(base + plan.split_offset + kSplitFlagBytes);
+        a.split.Tm = a.split.E + kSplitMaxParts * pair_states;
+        a.split.Bm = a.split.Tm + kSplitMaxParts * pair_states;
+        L.raw = pro != nullptr; L.scalar_gate = scalar_gate; L.out_bf16 = out_bf16;
+        L.reset_flags = seg == 0;
+        // (the counters of the time-split scan follow the slot flags: one fill clears both)
+        L.num_flags = parts > 1 ? (int64_t)((plan.split_offset + kSplitFlagBytes - plan.flags_offset) / 4)
+                                : (int64_t)plan.seg_chunks * streams;
+        L.reset_split = parts > 1 && seg > 0;
+        const kda_status st = launch_prefill_fused(L, stream);
+        if (st != KDA_OK) return st;
+    }
+    return KDA_OK;
+}
+
+}  // namespace kda

@@ -68,7 +68,7 @@ void kda_prefill_kernel(const FusedArgs a)
         }
         const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
         kda_intra_chunk<true, kRaw, kScalar>(lds, a.q, a.k, a.v, a.log_alpha, a.beta, a.cu, a.ws, a.T, a.H, a.seg_chunks,
-                                             a.seg_index, a.scale, a.ready, a.epoch, a.raw, nullptr, nullptr, h, n, cl);
+                                             a.seg_index, a.scale, a.ready, a.epoch, a.raw, nullptr, nullptr, h, n, cl, a.status);
         return;
     }
     const int64_t per_batch = (int64_t)a.nb * (1 + a.launch_chunks);
@@ -100,7 +100,7 @@ void kda_prefill_kernel(const FusedArgs a)
         if (pair >= a.pairs) return;
         const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
         kda_intra_chunk<true, kRaw, kScalar>(lds, a.q, a.k, a.v, a.log_alpha, a.beta, a.cu, a.ws, a.T, a.H, a.seg_chunks,
-                                             a.seg_index, a.scale, a.ready, a.epoch, a.raw, nullptr, nullptr, h, n, cl);
+                                             a.seg_index, a.scale, a.ready, a.epoch, a.raw, nullptr, nullptr, h, n, cl, a.status);
     }
 }
 

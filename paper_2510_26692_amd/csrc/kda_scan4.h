@@ -244,7 +244,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
         };
         auto poison = [&]() __attribute__((always_inline)) {
             gave_up = true;
-            if (lane == 0) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) __hip_atomic_fetch_or(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const float bad = __builtin_nanf("");
 #pragma unroll
             for (int t = 0; t < 4; ++t)
@@ -489,6 +489,17 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
         wait_vm<0>();
     }
 
+    // A state that is not finite at the end of the pass means that an fp16 operand overflowed on the way
+    // (values outside the documented domain) or that a wait ran out: recorded as bit 1 of the status word.
+    {
+        bool bad = false;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) bad |= !(__builtin_fabsf(S[t][j]) < __builtin_inff());
+        if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0)
+            __hip_atomic_fetch_or(status, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (state_out && (state_out != state_in || c_begin < c_end)) {
 #pragma unroll
         for (int t = 0; t < 4; ++t)

@@ -156,7 +156,7 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
         if (workers == 8)      ok = fold_slices<1>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 16 * w, parts, workers, pf, wait_limit);
         else if (workers == 4) ok = fold_slices<2>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 32 * w, parts, workers, pf, wait_limit);
         else                   ok = fold_slices<4>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 64 * w, parts, workers, pf, wait_limit);
-        if (!ok && threadIdx.x == 0) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!ok && threadIdx.x == 0) __hip_atomic_fetch_or(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (kind == kRoleB) return;
     {   // second phase: the scan of a range whose initial state is now known
@@ -165,7 +165,7 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
         float *state_out = (y == 0) ? state_final : nullptr;
         if (threadIdx.x == 0) {
             const bool ok = wait_flag(pf + part - 1, (uint32_t)workers, wait_limit);
-            if (!ok) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!ok) __hip_atomic_fetch_or(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             second_ok = ok;
         }
         __syncthreads();

@@ -75,10 +75,13 @@ def load_library():
     lib.kda_chunk_bwd_workspace_size.argtypes = [dp]
     lib.kda_chunk_bwd.restype = ctypes.c_int
     lib.kda_chunk_bwd.argtypes = [dp] + [vp] * 15 + [vp, sz, vp]
-    lib.kda_debug_set_phase_mask.restype = None
-    lib.kda_debug_set_phase_mask.argtypes = [ctypes.c_int]
-    lib.kda_debug_set_overlap.restype = None
-    lib.kda_debug_set_overlap.argtypes = [ctypes.c_int]
+    lib.kda_debug_set_producers.restype = None
+    lib.kda_debug_set_producers.argtypes = [ctypes.c_int]
+    lib.kda_debug_set_wait_limit.restype = None
+    lib.kda_debug_set_wait_limit.argtypes = [ctypes.c_ulonglong]
+    lib.kda_debug_chunk_fwd_plan.restype = ctypes.c_int
+    lib.kda_debug_chunk_fwd_plan.argtypes = [ctypes.POINTER(KdaDims), ctypes.c_size_t, ctypes.c_int,
+                                             ctypes.POINTER(ctypes.c_int64)]
     lib.kda_debug_set_time_split.restype = None
     lib.kda_debug_set_time_split.argtypes = [ctypes.c_int]
     lib.kda_recurrent_step.restype = ctypes.c_int
@@ -110,12 +113,25 @@ def kda_last_error():
     return load_library().kda_last_error().decode()
 
 
-def kda_debug_set_phase_mask(mask):
-    load_library().kda_debug_set_phase_mask(int(mask))
+def kda_debug_set_producers(enabled):
+    """Fault injection (kda_debug.h): 0 makes the per-chunk workgroups of later prefill calls do nothing."""
+    load_library().kda_debug_set_producers(int(bool(enabled)))
 
 
-def kda_debug_set_overlap(enabled):
-    load_library().kda_debug_set_overlap(int(bool(enabled)))
+def kda_debug_set_wait_limit(ticks):
+    """Ticks of the 100 MHz device clock a sequential workgroup waits for one slot (default 200 000 000)."""
+    load_library().kda_debug_set_wait_limit(int(ticks))
+
+
+def kda_debug_chunk_fwd_plan(dims, workspace_bytes, output_gate=False):
+    """(chunk indices per time segment, time segments, ranges of the time-split scan, chunks in the first
+    range, chunks in each other range) for a kda_chunk_fwd call with this workspace size."""
+    out = (ctypes.c_int64 * 5)()
+    st = load_library().kda_debug_chunk_fwd_plan(ctypes.byref(dims), ctypes.c_size_t(int(workspace_bytes)),
+                                                 int(bool(output_gate)), out)
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return tuple(int(x) for x in out)
 
 
 def kda_debug_set_time_split(mode):

@@ -147,38 +147,108 @@ def test_bf16_segmented_workspace_matches_single_segment():
     assert ei.value.status == 3
 
 
-def test_bf16_overlapped_kernels_match_the_serial_order():
-    """With few (sequence, head) pairs the sequential kernel runs next to the per-chunk kernel and
-    picks up each workspace slot when its flag goes up.  The arithmetic is the same, so the
-    results must equal, bit for bit, those of the strictly serial order, also when the workspace
-    still holds the slots and flags of an earlier call with other inputs, or garbage."""
+def test_bf16_results_do_not_depend_on_what_the_workspace_held():
+    """The sequential workgroups pick up each workspace slot when its flag goes up.  The flags are cleared
+    by a kernel of the call itself, so slots and flags of an earlier call with other inputs, or garbage,
+    must not matter: repeated calls give the same bits, and they match the oracle."""
     import paper_2510_26692_amd as kda
     ws = None
+    for seed, fill in ((21, 0xFF), (22, None), (23, 0x01)):
+        x = si.make_prefill(3, 1500, 4, 128, 128, "bf16", -2.0, seed, 0.02)
+        dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+        dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
+        if ws is None:
+            ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
+        if fill is not None:
+            ws.fill_(fill)
+        o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                                   workspace=ws, check=True)
+        o1, h1 = o1.clone(), h1.clone()
+        o2, h2 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                                   workspace=ws, check=True)
+        assert torch.equal(o1, o2) and torch.equal(h1, h2), seed
+        check_prefill(x, TOL_BF16, workspace=ws)
+
+
+def test_bf16_wait_that_runs_out_poisons_the_outputs_and_is_reported():
+    """Failure handling of the bounded waits, forced from the host: with the per-chunk workgroups switched
+    off no slot is ever produced, and with a wait limit of zero every sequential workgroup gives up at its
+    first look.  Every kernel still runs to its end.  The call must not hand back stale or partial data:
+    o and h_T are NaN, and kda_chunk_fwd_check reports the failure.  The next ordinary call is unaffected."""
+    import paper_2510_26692_amd as kda
+    x = si.make_prefill(2, 300, 3, 128, 128, "bf16", -2.0, 61, 0.02)
+    dd = to_device(x)
+    dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
+    ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
+    good_o, good_h = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws,
+                                       check=True)
+    good_o, good_h = good_o.clone(), good_h.clone()
+    for split in (1, 8):                                     # the plain scan, and (T long enough) the time-split one
+        xs = x if split == 1 else si.make_prefill(1, 64 * 40, 2, 128, 128, "bf16", -2.0, 62, 0.02)
+        ds = to_device(xs)
+        dims_s = kda.kda.make_chunk_dims(ds["q"], ds["v"])
+        ws_s = torch.empty(kda.kda_chunk_fwd_workspace_size(dims_s), dtype=torch.uint8, device="cuda")
+        try:
+            kda.kda_debug_set_time_split(split)
+            kda.kda_debug_set_producers(0)
+            kda.kda_debug_set_wait_limit(0)
+            o, hT = kda.kda_chunk_fwd(ds["q"], ds["k"], ds["v"], ds["log_alpha"], ds["beta"], h0=ds["h0"], workspace=ws_s)
+            torch.cuda.synchronize()
+            assert torch.isnan(o).all() and torch.isnan(hT).all()
+            with pytest.raises(kda.KdaError) as ei:
+                kda.kda_chunk_fwd_check(dims_s, ws_s)
+            assert ei.value.status == 4 and "gave up" in str(ei.value)
+        finally:
+            kda.kda_debug_set_producers(1)
+            kda.kda_debug_set_wait_limit(200000000)
+            kda.kda_debug_set_time_split(1)
+    o, hT = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws, check=True)
+    assert torch.equal(o, good_o) and torch.equal(hT, good_h)
+
+
+@pytest.mark.parametrize("case", ["v_1e3", "v_1e5", "k_unnormalised"])
+def test_bf16_values_at_and_beyond_the_fp16_domain(case):
+    """The matrix-core operands are fp16.  |v| of 1e3 stays inside their range and must simply be right;
+    |v| of 1e5 and keys with entries far above 3.9 leave it: the call must then either still match the
+    oracle or report the state that overflowed (kda_chunk_fwd_check), never hand back finite wrong numbers
+    without a word."""
+    import paper_2510_26692_amd as kda
+    x = si.make_prefill(1, 256, 2, 128, 128, "bf16", -2.0, 71, 0.02)
+    if case == "v_1e3":
+        x["v"] = (x["v"].float() * 1e3).to(torch.bfloat16)
+    elif case == "v_1e5":
+        x["v"] = (x["v"].float() * 1e5).to(torch.bfloat16)
+    else:
+        x["k"] = (x["k"].float() * 60.0).to(torch.bfloat16)          # entries up to ~20, |k| ~ 60
+        x["beta"] = (x["beta"].float() * 1e-4).to(torch.bfloat16)    # keeps beta |k|^2 < 2, so the oracle itself stays bounded
+    if case == "v_1e3":
+        eo, eh = check_prefill(x, TOL_BF16)
+        print("|v| ~ 1e3: err_o %.2e err_hT %.2e" % (eo, eh))
+        return
+    dd = to_device(x)
+    dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
+    ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
+    o, hT = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws)
+    torch.cuda.synchronize()
+    reported = False
     try:
-        for seed, fill in ((21, 0xFF), (22, None), (23, 0x01)):
-            x = si.make_prefill(3, 1500, 4, 128, 128, "bf16", -2.0, seed, 0.02)
-            dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
-            dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
-            if ws is None:
-                ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
-            if fill is not None:
-                ws.fill_(fill)
-            kda.kda_debug_set_overlap(1)
-            o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
-                                       workspace=ws, check=True)
-            o1, h1 = o1.clone(), h1.clone()
-            kda.kda_debug_set_overlap(0)
-            o2, h2 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
-                                       workspace=ws, check=True)
-            assert torch.equal(o1, o2) and torch.equal(h1, h2), seed
-    finally:
-        kda.kda_debug_set_overlap(1)
+        kda.kda_chunk_fwd_check(dims, ws)
+    except kda.KdaError as e:
+        reported = True
+        assert e.status == 1 and "fp16" in str(e), str(e)
+    if not reported:
+        from helpers import oracle_prefill, worst_slice_err, o_slices, state_slices
+        o_ref, h_ref = oracle_prefill(x)
+        assert np.isfinite(o.cpu().numpy()).all()
+        assert worst_slice_err(o.cpu().numpy(), o_ref, o_slices(1, 2)) <= TOL_BF16
+        assert worst_slice_err(hT.cpu().numpy(), h_ref, state_slices(1, 2)) <= TOL_BF16
+    print(case, "reported" if reported else "within tolerance")
 
 
 def test_bf16_prefill_inside_a_captured_graph_replays_correctly():
-    """A caller may capture kda_chunk_fwd into a graph.  The call then keeps its two kernels on
-    the captured stream, one after the other (no helper stream, no waiting on flags).  Every
-    replay, with eager work in between, must reproduce the eager result bit for bit."""
+    """A caller may capture kda_chunk_fwd into a graph: the call is a fill kernel and one kernel whose
+    workgroups hand slots to one another, all on the captured stream.  Every replay, with eager work in
+    between, must reproduce the eager result bit for bit."""
     import paper_2510_26692_amd as kda
     x = si.make_prefill(2, 700, 4, 128, 128, "bf16", -2.0, 51, 0.02)
     dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
@@ -276,9 +346,8 @@ def test_bf16_decay_ladder_across_the_exact_path_threshold():
     print("bf16 decay ladder: err_o %.2e err_hT %.2e" % (eo, eh))
 
 
-@pytest.mark.parametrize("overlap", [1, 0])
 @pytest.mark.parametrize("case", ["three_ranges", "eight_ranges", "packed_ragged"])
-def test_bf16_time_split_scan(case, overlap):
+def test_bf16_time_split_scan(case):
     """Few (sequence, head) pairs and long sequences: the sequential kernel cuts the chunk axis into
     ranges that several workgroups walk side by side (transition and offset of a range first, the
     true states after a fold).  Checked against the oracle, and against the plain scan, with which
@@ -293,7 +362,6 @@ def test_bf16_time_split_scan(case, overlap):
     else:
         x = si.make_varlen(np.array([64 * 130, 3001, 100, 0]), 1, 128, 128, "bf16", -2.0, 303, 0.05)
     try:
-        kda.kda_debug_set_overlap(overlap)
         kda.kda_debug_set_time_split(8)                      # split for sure, into as many ranges as fit
         eo, eh = check_prefill(x, TOL_BF16)
         dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
@@ -305,12 +373,11 @@ def test_bf16_time_split_scan(case, overlap):
         torch.cuda.synchronize()
         d_o = (o1 - o2).abs().max().item() / o2.abs().max().item()
         d_h = (h1 - h2).abs().max().item() / h2.abs().max().item()
-        print("time split %s overlap=%d: err_o %.2e err_hT %.2e; vs plain scan %.2e / %.2e" % (case, overlap, eo, eh, d_o, d_h))
+        print("time split %s: err_o %.2e err_hT %.2e; vs plain scan %.2e / %.2e" % (case, eo, eh, d_o, d_h))
         assert d_o <= TOL_BF16 and d_h <= TOL_BF16
         if case != "packed_ragged":
             assert not torch.equal(h1, h2)                    # the split path really ran: same result, other rounding
     finally:
-        kda.kda_debug_set_overlap(1)
         kda.kda_debug_set_time_split(1)
 
 

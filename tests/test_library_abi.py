@@ -19,18 +19,37 @@ def _lib():
 
 def test_every_declared_symbol_is_exported():
     kda, lib = _lib()
-    header = open(os.path.join(ROOT, "include", "kda.h")).read()
+    header = open(os.path.join(ROOT, "include", "kda.h")).read() + open(os.path.join(ROOT, "include", "kda_debug.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(kda_[a-z_0-9]+)\s*\(", header))
     assert {"kda_chunk_fwd", "kda_recurrent_step", "kda_chunk_fwd_workspace_size",
             "kda_chunk_fwd_min_workspace_size", "kda_status_string", "kda_last_error",
-            "kda_version", "kda_debug_set_phase_mask", "kda_debug_set_overlap",
+            "kda_version", "kda_debug_set_producers", "kda_debug_set_wait_limit", "kda_debug_chunk_fwd_plan",
             "kda_chunk_fwd_check", "kda_recurrent_steps_pooled", "kda_chunk_fwd_fused",
             "kda_recurrent_steps_fused", "kda_chunk_fwd_fused_workspace_size",
             "kda_chunk_fwd_fused_min_workspace_size", "kda_debug_set_time_split",
             "kda_chunk_fwd_scalar_gate", "kda_recurrent_steps_pooled_scalar_gate"} <= names
     for n in names:
         assert hasattr(lib, n), n
+
+
+def test_library_imports_no_allocating_or_stream_creating_runtime_call():
+    """The boundary's conventions, checked on the built library itself: it allocates nothing, creates no
+    stream or event and registers no host memory, so none of those runtime entry points may even be
+    imported.  The only calls that wait for the device are hipStreamSynchronize and the blocking hipMemcpy
+    of kda_chunk_fwd_check, which exists to wait."""
+    import subprocess
+    kda, _ = _lib()
+    out = subprocess.run(["nm", "-D", "--undefined-only", kda.library_path()], check=True, capture_output=True, text=True).stdout
+    imported = {ln.split()[-1].split("@")[0] for ln in out.splitlines() if ln.strip()}
+    hip = {n for n in imported if n.startswith("hip")}
+    assert "hipLaunchKernel" in hip
+    banned = [n for n in hip if re.search(r"Malloc|Free|StreamCreate|EventCreate|HostRegister|HostAlloc|DeviceSynchronize|"
+                                          r"EventSynchronize|Graph|MemPool|ModuleLoad", n)]
+    assert not banned, banned
+    assert hip <= {"hipLaunchKernel", "hipGetDevice", "hipDeviceGetAttribute", "hipFuncSetAttribute", "hipGetLastError",
+                   "hipGetErrorString", "hipMemcpyAsync", "hipMemcpy", "hipStreamSynchronize", "hipGetSymbolAddress",
+                   "hipPeekAtLastError"}, hip
 
 
 def test_dims_struct_layout_matches_header():
