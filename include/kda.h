@@ -145,6 +145,26 @@ kda_status kda_chunk_fwd(const kda_dims *dims,
                          void *hip_stream);
 
 /*
+ * kda_chunk_fwd for callers that cannot allocate device memory and have no workspace to bring: code
+ * under graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a
+ * static device array inside the library, kda_static_scratch_size() bytes (64 MiB) per GPU that the
+ * library runs on, held until the process ends.  Everything else (arguments, results, arithmetic) is
+ * that of kda_chunk_fwd given a workspace of that size: long inputs are walked in time segments with
+ * the state carried between them.  The call allocates nothing and frees nothing.  A call whose
+ * smallest workspace (kda_chunk_fwd_min_workspace_size) exceeds the array is refused with
+ * KDA_ERR_WORKSPACE and launches nothing: at dk = dv = 128 that is beyond about 190 (sequence, head)
+ * pairs per call.  All calls on one GPU share that GPU's array, which keeps the last call's contents
+ * (each call clears what it needs at zero itself): calls that overlap in time on one GPU, from any
+ * stream or thread, race on it and must not be made.  kda_chunk_fwd_check does not apply.
+ */
+size_t kda_static_scratch_size(void);
+kda_status kda_chunk_fwd_static_scratch(const kda_dims *dims,
+                                        const void *q, const void *k, const void *v,
+                                        const void *log_alpha, const void *beta,
+                                        const float *h0, const int32_t *cu_seqlens,
+                                        void *o, float *hT, void *hip_stream);
+
+/*
  * Backward pass of kda_chunk_fwd: gradients of  sum(o . d_o) + sum(hT . d_hT)  with respect to
  * every input.  The paper motivates a training kernel (Section 3.1 compares the chunkwise form
  * with the general DPLR one for exactly that purpose) but derives no backward algorithm; what

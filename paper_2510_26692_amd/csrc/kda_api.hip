@@ -67,6 +67,35 @@ double g_split_ratio = split_ratio_default();
 int g_producers = 1;                      // 0: the per-chunk role of the one-kernel prefill does nothing
 uint64_t g_wait_limit = 200000000ull;     // ticks of the 100 MHz wall clock a scan workgroup waits for a slot: two seconds
 
+// Scratch of the entry point that allocates nothing (kda_chunk_fwd_static_scratch): each device the
+// library runs on holds its own copy of this array, at its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device (the array's name is a host-side stand-in, not a
+// device address): asked once per device, with that device current, and kept.
+static kda_status static_scratch_ptr(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static void *table[kMaxDevices];                        // same value from every thread
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return fail(KDA_ERR_LAUNCH, "cannot tell the current device");
+    }
+    if (!table[dev]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return fail(KDA_ERR_LAUNCH, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        }
+        table[dev] = ptr;
+    }
+    *out = table[dev];
+    return KDA_OK;
+}
+
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Checks shared by both entry points.  Returns KDA_OK or the failure code.
@@ -284,6 +313,28 @@ kda_status kda_chunk_fwd(const kda_dims *d, const void *q, const void *k, const 
     g_last_error[0] = 0;
     return chunk_fwd_impl(d, nullptr, nullptr, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, workspace,
                           workspace_bytes, hip_stream);
+}
+
+size_t kda_static_scratch_size(void) { return kStaticScratchBytes; }
+
+kda_status kda_chunk_fwd_static_scratch(const kda_dims *d, const void *q, const void *k, const void *v,
+                                        const void *log_alpha, const void *beta, const float *h0,
+                                        const int32_t *cu_seqlens, void *o, float *hT, void *hip_stream)
+{
+    g_last_error[0] = 0;
+    kda_status st = check_dims(d, cu_seqlens != nullptr);
+    if (st != KDA_OK) return st;
+    if (d->chunk != kChunk) return fail(KDA_ERR_UNSUPPORTED, "chunk must be %d, got %d", kChunk, d->chunk);
+    // the smallest workspace the call can run with must fit the array (KDA_F32 inputs need none at all)
+    const size_t need = mfma_path(d) ? chunk_mfma_workspace_size(d, true, false) : 0;
+    if (need > kStaticScratchBytes)
+        return fail(KDA_ERR_WORKSPACE, "this call needs at least %zu bytes of scratch, the static array holds %zu: fewer "
+                    "sequences or heads per call", need, kStaticScratchBytes);
+    void *ptr = nullptr;
+    st = static_scratch_ptr(&ptr);
+    if (st != KDA_OK) return st;
+    return chunk_fwd_impl(d, nullptr, nullptr, q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT, ptr, kStaticScratchBytes,
+                          hip_stream);
 }
 
 kda_status kda_chunk_fwd_scalar_gate(const kda_dims *d, const void *q, const void *k, const void *v,

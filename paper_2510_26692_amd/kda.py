@@ -75,6 +75,10 @@ def load_library():
     lib.kda_chunk_bwd_workspace_size.argtypes = [dp]
     lib.kda_chunk_bwd.restype = ctypes.c_int
     lib.kda_chunk_bwd.argtypes = [dp] + [vp] * 15 + [vp, sz, vp]
+    lib.kda_static_scratch_size.restype = ctypes.c_size_t
+    lib.kda_static_scratch_size.argtypes = []
+    lib.kda_chunk_fwd_static_scratch.restype = ctypes.c_int
+    lib.kda_chunk_fwd_static_scratch.argtypes = [ctypes.POINTER(KdaDims)] + [ctypes.c_void_p] * 10
     lib.kda_debug_set_producers.restype = None
     lib.kda_debug_set_producers.argtypes = [ctypes.c_int]
     lib.kda_debug_set_wait_limit.restype = None
@@ -295,6 +299,34 @@ def kda_chunk_fwd(q, k, v, log_alpha, beta, h0=None, cu_seqlens=None, scale=1.0,
         raise KdaError(st, kda_last_error())
     if check:
         kda_chunk_fwd_check(dims, workspace)
+    return o, hT
+
+
+def kda_static_scratch_size():
+    return int(load_library().kda_static_scratch_size())
+
+
+def kda_chunk_fwd_static_scratch(q, k, v, log_alpha, beta, o, hT=None, h0=None, cu_seqlens=None, scale=1.0, max_seqlen=0):
+    """kda_chunk_fwd on the library's static scratch array: nothing is allocated, so `o` (and `hT`, if the
+    final states are wanted) must be passed in.  Returns (o, hT)."""
+    lib = load_library()
+    dev = _check_dev(q, k, v, log_alpha, beta, h0, cu_seqlens, o, hT)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    if not (q.dtype == k.dtype == v.dtype == log_alpha.dtype == beta.dtype) or q.dtype not in _DTYPE_CODE:
+        raise ValueError("q, k, v, log_alpha, beta must share a supported dtype")
+    if k.shape != q.shape or log_alpha.shape != q.shape or v.shape != (B, T, H, dv) or beta.shape != (B, T, H) \
+            or o.shape != (B, T, H, dv) or o.dtype not in _DTYPE_CODE:
+        raise ValueError("inconsistent shapes")
+    dims = make_chunk_dims(q, v, cu_seqlens, scale, max_seqlen, o.dtype)
+    N = dims.num_seqs
+    for name, t in (("hT", hT), ("h0", h0)):
+        if t is not None and (t.dtype != torch.float32 or t.shape != (N, H, dk, dv)):
+            raise ValueError("%s must be fp32 [N,H,dk,dv]" % name)
+    st = lib.kda_chunk_fwd_static_scratch(ctypes.byref(dims), _ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(beta),
+                                          _ptr(h0), _ptr(cu_seqlens), _ptr(o), _ptr(hT), _stream_ptr(dev))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
     return o, hT
 
 
