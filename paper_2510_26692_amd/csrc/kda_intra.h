@@ -122,6 +122,30 @@ template <int kPolicy> __device__ __forceinline__ u32x4 slot_load16(__amdgpu_buf
     return __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, kPolicy);
 }
 
+// Input rows are read through a descriptor that covers exactly the bytes that may be read: the hardware
+// returns zeros for an offset beyond it (a padding token of a ragged chunk).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rows_resource(const void *base, int bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 rows_load16(__amdgpu_buffer_rsrc_t rs, int off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+}
+__device__ __forceinline__ uint16_t rows_load2(__amdgpu_buffer_rsrc_t rs, int off)
+{
+    return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, off, 0, 0);
+}
+
+// A value that is the same in every lane of the wave, moved to scalar registers.
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ int64_t uni64(int64_t x)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)x);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)x >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // ----------------------------------------------------------------------------------
 // kda_intra
 // ----------------------------------------------------------------------------------
@@ -149,45 +173,349 @@ __device__ __forceinline__ float log2_alpha_from_gate(float x, float a)
     return -a * sp;
 }
 
-// Workgroup of 256 threads (four waves), kIntraLds bytes of LDS at `lds`; (h, n, cl): head, sequence and
-// chunk index inside the time segment.  Every thread of the workgroup must make the call (barriers inside).
-// status (may be NULL): bit 2 is raised when a key of the chunk has |k_t|^2 > kMaxKeyNorm2, beyond which the fp16
+// What the per-chunk stage reads and writes, the same for every chunk of a launch.
+struct IntraArgs {
+    const uint16_t *q, *k, *v, *log_alpha, *beta;    // bf16 inputs (log_alpha: [B,T,H,128], or [B,T,H] with kScalar)
+    const int32_t *cu_seqlens;                       // NULL: sequences of T tokens
+    uint8_t *ws;                                     // slots
+    int64_t T;
+    int H;
+    int64_t seg_chunks, seg_index;                   // time segment: chunk indices seg_index * seg_chunks + [0, seg_chunks)
+    float scale;
+    uint32_t *ready;                                 // kHandoff: one flag per slot
+    uint32_t epoch;                                  //           value of a raised flag
+    RawParams raw;
+    const uint16_t *out_gate;                        // fused output gate: logits [B,T,H,128] or NULL
+    uint8_t *gate_ws;                                //                    their slots
+    uint32_t *status;                                // may be NULL
+};
+// One chunk of one (sequence, head): cl is the chunk index inside the time segment; cl < 0: nothing to do.
+struct IntraItem {
+    int h, n;
+    int64_t cl;
+};
+
+// Workgroup of 256 threads (four waves), kIntraLds bytes of LDS at `lds`.  The workgroup works through the items
+// item_at(0), .., item_at(count - 1) one after the other; the inputs of an item are fetched while the item before
+// it is still being computed, so only the first fetch of a workgroup is waited for in full.  item_at must
+// return the same item in every thread.  Every thread of the workgroup must make the call (barriers inside).
+// status: bit 2 is raised when a key of the chunk has |k_t|^2 > kMaxKeyNorm2, beyond which the fp16
 // operands may overflow and the UT transform loses accuracy (the paper's keys are L2-normalised, Section 4).
-template <bool kHandoff, bool kRaw, bool kScalar = false>
+template <bool kHandoff, bool kRaw, bool kScalar, typename ItemAt>
 __device__ __forceinline__
-void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_t *__restrict__ k,
-                     const uint16_t *__restrict__ v, const uint16_t *__restrict__ log_alpha,
-                     const uint16_t *__restrict__ beta, const int32_t *__restrict__ cu_seqlens,
-                     uint8_t *__restrict__ ws, int64_t T, int H, int64_t seg_chunks,
-                     int64_t seg_index, float scale, uint32_t *ready, uint32_t epoch, RawParams raw,
-                     const uint16_t *__restrict__ out_gate, uint8_t *__restrict__ gate_ws, int h, int n, int64_t cl,
-                     uint32_t *status = nullptr)
+void kda_intra_items(uint8_t *lds, const IntraArgs &A, int count, ItemAt item_at)
 {
     // (the wave index is the same in all lanes: telling the compiler so turns the per-wave cases
     // below into scalar branches instead of masked vector code)
-    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     constexpr int kPolicy = kHandoff ? kCacheDevice : 0;
-    if (cl >= seg_chunks) return;
-    // slots are laid out pair by pair, a pair's chunks one after the other: the sequential stage then
-    // walks one contiguous range of memory per (sequence, head)
-    const int64_t slot = ((int64_t)n * H + h) * seg_chunks + cl;
-    const int64_t ci = seg_index * seg_chunks + cl;
-    int64_t tok_base, len;
-    if (cu_seqlens) { tok_base = cu_seqlens[n]; len = (int64_t)cu_seqlens[n + 1] - tok_base; }
-    else            { tok_base = (int64_t)n * T; len = T; }
-    if (ci * kChunk >= len) return;                      // uniform for the workgroup
-    const int nv = (int)((len - ci * kChunk < kChunk) ? (len - ci * kChunk) : kChunk);
-    const int64_t tok0 = tok_base + ci * kChunk;
-    const __amdgpu_buffer_rsrc_t out = slot_resource(ws + slot * (int64_t)kSlotBytes);
+    const uint16_t *__restrict__ q = A.q, *__restrict__ k = A.k, *__restrict__ v = A.v;
+    const uint16_t *__restrict__ log_alpha = A.log_alpha, *__restrict__ beta = A.beta, *__restrict__ out_gate = A.out_gate;
+    uint8_t *__restrict__ ws = A.ws, *__restrict__ gate_ws = A.gate_ws;
+    const int H = A.H;
+    const int64_t seg_chunks = A.seg_chunks;
+    const float scale = A.scale;
+    const RawParams raw = A.raw;
+    uint32_t *status = A.status;
+    const int row_pitch = H * D * 2;                          // bytes between consecutive tokens of an input
 
+    // Where an item's data is: slots are laid out pair by pair, a pair's chunks one after the other (the
+    // sequential stage then walks one contiguous range of memory per (sequence, head)).  row0: this head's row
+    // of the chunk's first token in the [token][head][128] inputs; row_bytes: from there to the end of the
+    // last valid token's row; head_bytes: the same for the [token][head] inputs.  An item that does not exist
+    // (no such chunk in the segment or the sequence) has valid = false and row_bytes = head_bytes = 0.
+    struct Loc {
+        bool valid;
+        int h, nv, row_bytes, head_bytes;
+        int64_t slot, tok0, row0;
+    };
+    auto locate = [&](const IntraItem it) __attribute__((always_inline)) {
+        Loc L;
+        L.valid = false; L.h = it.h; L.nv = 0; L.row_bytes = 0; L.head_bytes = 0;
+        L.slot = 0; L.tok0 = 0; L.row0 = 0;
+        if (it.cl >= 0 && it.cl < seg_chunks) {
+            const int64_t ci = A.seg_index * seg_chunks + it.cl;
+            int64_t tok_base, len;
+            if (A.cu_seqlens) { tok_base = A.cu_seqlens[it.n]; len = (int64_t)A.cu_seqlens[it.n + 1] - tok_base; }
+            else              { tok_base = (int64_t)it.n * A.T; len = A.T; }
+            if (ci * kChunk < len) {
+                L.valid = true;
+                L.nv = (int)((len - ci * kChunk < kChunk) ? (len - ci * kChunk) : kChunk);
+                L.slot = ((int64_t)it.n * H + it.h) * seg_chunks + it.cl;
+                L.tok0 = tok_base + ci * kChunk;
+                L.row0 = (L.tok0 * H + it.h) * (int64_t)D;
+                L.row_bytes = (L.nv - 1) * row_pitch + D * 2;
+                L.head_bytes = ((L.nv - 1) * H + 1) * 2;
+            }
+        }
+        // (the same in every lane: kept in scalar registers)
+        L.h = uni(L.h); L.nv = uni(L.nv); L.row_bytes = uni(L.row_bytes); L.head_bytes = uni(L.head_bytes);
+        L.slot = uni64(L.slot); L.tok0 = uni64(L.tok0); L.row0 = uni64(L.row0);
+        L.valid = uni((int)L.valid) != 0;
+        return L;
+    };
+    // The inputs the first phases need, 16 bytes (8 channels) per ks and tensor, all through descriptors that
+    // end with the chunk's last valid token: a token beyond it (and every token of an item that does not
+    // exist) reads as zeros, with no branch around a load and nothing for a load to wait for.
+    // (log_alpha first: the running sum waits for it, k and q are needed later)
+    u32x4 kraw[4], qraw[4], graw[4];
+    uint32_t beta_raw = 0, gscalar_raw = 0;                  // beta of token tid % 64; kScalar: log alpha of this lane's token
+    auto fetch = [&](const Loc &L, const int tid) __attribute__((always_inline)) {
+        const int tok = (tid & 63 & 15) + 16 * (tid >> 6), g = (tid & 63) >> 4;
+        const int off = tok * row_pitch + 16 * g;
+        const __amdgpu_buffer_rsrc_t rg = rows_resource(log_alpha + L.row0, kScalar ? 0 : L.row_bytes);
+        const __amdgpu_buffer_rsrc_t rk = rows_resource(k + L.row0, L.row_bytes), rq = rows_resource(q + L.row0, L.row_bytes);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) graw[ks] = rows_load16(rg, off + 64 * ks);
+        if (kScalar) gscalar_raw = rows_load2(rows_resource(log_alpha + (L.tok0 * H + L.h), L.head_bytes), tok * H * 2);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) kraw[ks] = rows_load16(rk, off + 64 * ks);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) qraw[ks] = rows_load16(rq, off + 64 * ks);
+        beta_raw = rows_load2(rows_resource(beta + (L.tok0 * H + L.h), L.head_bytes), (tid & 63) * H * 2);
+    };
+
+    // Each item is computed in two halves, and the loop is rotated by one half: a pass fetches the inputs of
+    // its item, finishes the item before it (which does not touch them) and then computes the first half of
+    // its own, so a fetch has the second half of an item, a third of the whole, to arrive, and no register
+    // holds fetched data from one pass of the loop to the next.  Between its halves an item lives in LDS and
+    // in the A_kk and A_qk tiles (R, I), I = 0..R, of this wave.
+    f32x4 res_kk[4], res_qk[4];
+    Loc prev = locate(IntraItem{0, 0, -1}), cur = locate(item_at(0));
+    for (int item = 0; item <= count; ++item) {
+    // (the thread index is made opaque once per pass: what is derived from it, addresses above all, is then
+    // computed where it is used instead of being carried in registers across the whole loop)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int R = wave, m = lane & 15, g = lane >> 4;
+    const int tok = 16 * R + m;
+    fetch(cur, tid);                                         // (nothing is read for an item that does not exist)
     float *sTot = reinterpret_cast<float *>(lds + kTot);
     float *sBeta = reinterpret_cast<float *>(lds + kBeta);
     uint32_t *sStrong = reinterpret_cast<uint32_t *>(lds + kStrong);
     float *sTab = reinterpret_cast<float *>(lds + kTab);     // [7][4][128]: P, E, Tinv, iA, iB, shifted total, row shift
 
-    const int R = wave, m = lane & 15, g = lane >> 4;
-    const int tok = 16 * R + m;
 
+    if (prev.valid) {                                        // ---- second half of the item before ----
+    const int h = prev.h, nv = prev.nv, row_bytes = prev.row_bytes;
+    const int64_t slot = prev.slot, row0 = prev.row0;
+    const __amdgpu_buffer_rsrc_t out = slot_resource(ws + slot * (int64_t)kSlotBytes);
+    (void)h;
+    // ---- L and Tril(A_qk) tiles of row R; fp16 V tile ----
+    {
+        // (L is kept transposed, sLT[column][row]: a lane's four rows of a column are contiguous, one
+        // 16-byte store per tile, and the substitution below reads a column of L as a row)
+        float *sLT = reinterpret_cast<float *>(lds + kL);
+        // (Tril(A_qk) likewise, sAqT[column][row] in fp16: 8-byte stores here, transposing reads below)
+        uint16_t *sAqT = reinterpret_cast<uint16_t *>(lds + kAq);
+        const f32x4 beta4 = *reinterpret_cast<const f32x4 *>(sBeta + 16 * R + 4 * g);
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            const int i = 16 * I + m;                       // column token of this lane
+            u32x2 av = {0u, 0u};
+            if (I <= R) {
+                f32x4 lv;
+                float qv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 16 * R + 4 * g + j;
+                    lv[j] = (i < r) ? beta4[j] * res_kk[I][j] : 0.f;
+                    qv[j] = (i <= r) ? res_qk[I][j] * scale : 0.f;
+                }
+                *reinterpret_cast<f32x4 *>(sLT + i * kLdF + 16 * R + 4 * g) = lv;
+                av[0] = pack_h2(qv[0], qv[1]); av[1] = pack_h2(qv[2], qv[3]);
+            }
+            *reinterpret_cast<u32x2 *>(sAqT + i * kLdM + 16 * R + 4 * g) = av;   // zeros above the diagonal tiles
+        }
+    }
+    __syncthreads();                                                               // B5
+
+    // V is fetched now; its latency hides behind the UT transform
+    u32x4 vraw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+        vraw[i] = rows_load16(rows_resource(v + row0, row_bytes), tokv * row_pitch + 16 * cg);
+    }
+
+    // ---- UT transform, diagonal 16x16 blocks: column j of (I + L_ww)^-1 per lane ----
+    {
+        // (column by column: once x[i] is final, the updates of the rows below it are independent
+        // of one another, so the dependent chain is 16 long instead of 120; each x[r] still
+        // receives its terms in the order i = 0, 1, ..)
+        const float *sLT = reinterpret_cast<const float *>(lds + kL);
+        float *sX = reinterpret_cast<float *>(lds + kX);
+        const int j = lane & 15, w = wave;
+        float x[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) x[r] = (r == j) ? 1.f : 0.f;
+#pragma unroll
+        for (int i = 0; i < 15; ++i) {
+            const float *col = sLT + (16 * w + i) * kLdF + 16 * w;      // L[16 w + r][16 w + i], r = 0..15
+            const float xi = x[i];
+#pragma unroll
+            for (int r = i + 1; r < 16; ++r) x[r] = fmaf(-col[r], xi, x[r]);
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sX[(16 * w + r) * kLdF + 16 * w + j] = x[r];
+        }
+    }
+    // ---- copy (Gamma^{i->C}.K)^T out in MFMA register order ----
+    {
+        // lane (x = lane % 32, hh): channel 32 tau + x, tokens 32 rho + kidx(s, hh, 0..7), which are two
+        // runs of four consecutive tokens: two transposing reads per fragment
+        const int hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int f = wave * 4 + i;                     // Kt frag f = (tau*2 + rho)*2 + s
+            const int tau = f >> 2, rho = (f >> 1) & 1, s = f & 1;
+            const uint8_t *blk = lds + kKp + ((32 * rho + kidx(s, hh, 0)) * kLdH + 32 * tau + xb) * 2;
+            const u32x2 lo = lds_read_tr4(blk, kLdH, lane), hi = lds_read_tr4(blk + 8 * kLdH * 2, kLdH, lane);
+            u32x4 o4 = {lo[0], lo[1], hi[0], hi[1]};
+            slot_store16<kPolicy>(out, kOffKt + f * kFragBytes + lane * 16, o4);
+        }
+    }
+    __syncthreads();                                                               // B6
+
+    // ---- UT transform, off-diagonal blocks: X_RI = -X_RR sum_{I<=J<R} L_RJ X_JI (fp32 MFMA) ----
+    {
+        const float *sLT = reinterpret_cast<const float *>(lds + kL);
+        float *sX = reinterpret_cast<float *>(lds + kX);
+        for (int Rr = 1; Rr < 4; ++Rr) {
+            if (wave < Rr) {
+                const int Ii = wave;
+                f32x4 t = {0.f, 0.f, 0.f, 0.f};
+                for (int J = Ii; J < Rr; ++J) {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        const float a = sLT[(16 * J + 4 * ks + g) * kLdF + 16 * Rr + m];   // L[16 Rr + m][16 J + 4 ks + g]
+                        const float b = sX[(16 * J + 4 * ks + g) * kLdF + 16 * Ii + m];
+                        t = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, t, 0, 0, 0);
+                    }
+                }
+                // second product with contraction slot (ks, g) standing for index 4 g + ks, so
+                // that register ks of the accumulator t is the B operand as it stands
+                f32x4 r = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const float a = sX[(16 * Rr + m) * kLdF + 16 * Rr + 4 * g + ks];
+                    r = __builtin_amdgcn_mfma_f32_16x16x4f32(a, t[ks], r, 0, 0, 0);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sX[(16 * Rr + 4 * g + j) * kLdF + 16 * Ii + m] = -r[j];
+            }
+            __syncthreads();                                                       // B7
+        }
+    }
+    // ---- M = X Diag(beta) as fp16 (over the dead K' tile); Tril(A_qk) out; V tile (over L) ----
+    {
+        const float *sX = reinterpret_cast<const float *>(lds + kX);
+        _Float16 *sM = reinterpret_cast<_Float16 *>(lds + kM);
+        // four consecutive columns per thread and pass: 16-byte reads, 8-byte writes
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int idx = tid + 256 * pass, r = idx >> 4, j0 = 4 * (idx & 15);
+            const f32x4 xr = *reinterpret_cast<const f32x4 *>(sX + r * kLdF + j0);
+            const f32x4 br = *reinterpret_cast<const f32x4 *>(sBeta + j0);
+            float val[4];
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                const int j = j0 + z;
+                val[z] = (j < r) ? xr[z] * br[z] : ((j == r) ? br[z] : 0.f);
+            }
+            u32x2 w2 = {pack_h2(val[0], val[1]), pack_h2(val[2], val[3])};
+            *reinterpret_cast<u32x2 *>(sM + r * kLdM + j0) = w2;
+        }
+        // lane (x, hh) of fragment (rr, ri, s): row token 32 rr + x, column tokens 32 ri + 16 s + 4 hh + 0..3
+        // and + 8..11, which are rows of the transposed tile
+        const int hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
+        for (int idx = wave; idx < 6; idx += 4) {
+            const int p = idx >> 1, s = idx & 1;
+            const int rr = (p == 0) ? 0 : 1, ri = (p == 2) ? 1 : 0;
+            const uint8_t *blk = lds + kAq + ((32 * ri + 16 * s + 4 * hh) * kLdM + 32 * rr + xb) * 2;
+            const u32x2 a = lds_read_tr4(blk, kLdM, lane), b = lds_read_tr4(blk + 8 * kLdM * 2, kLdM, lane);
+            u32x4 o4 = {a[0], a[1], b[0], b[1]};
+            slot_store16<kPolicy>(out, kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16, o4);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+            u32x4 y;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float a, b;
+                unpack_bf16x2(vraw[i][w], a, b);
+                y[w] = pack_h2(a, b);
+            }
+            *reinterpret_cast<u32x4 *>(lds + kV + (tokv * kLdH + 8 * cg) * 2) = y;
+        }
+    }
+    __syncthreads();                                                               // B8
+
+    // ---- W^T = (Gamma.K)^T M^T (wave = d_k tile) and U = M V (wave = d_v tile) ----
+    {
+        // operands with the tokens in the contraction slots: lane (x, hh) wants channel 32 wave + x of
+        // the eight tokens 16 s4 + 8 hh + 0..7 of the [token][channel] tiles: two transposing reads each
+        const int x = lane & 31, hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
+        h8 mf[2][4], gk[4], vv[4];
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+            for (int rho = 0; rho < 2; ++rho)
+                mf[rho][s4] = *reinterpret_cast<const h8 *>(lds + kM + ((32 * rho + x) * kLdM + 16 * s4 + 8 * hh) * 2);
+            const int off = ((16 * s4 + 8 * hh) * kLdH + 32 * wave + xb) * 2;
+            const u32x2 g0 = lds_read_tr4(lds + kGK + off, kLdH, lane), g1 = lds_read_tr4(lds + kGK + off + 4 * kLdH * 2, kLdH, lane);
+            const u32x2 v0 = lds_read_tr4(lds + kV + off, kLdH, lane), v1 = lds_read_tr4(lds + kV + off + 4 * kLdH * 2, kLdH, lane);
+            u32x4 pg = {g0[0], g0[1], g1[0], g1[1]}, pv = {v0[0], v0[1], v1[0], v1[1]};
+            gk[s4] = __builtin_bit_cast(h8, pg);
+            vv[s4] = __builtin_bit_cast(h8, pv);
+        }
+#pragma unroll
+        for (int rho = 0; rho < 2; ++rho) {
+            f32x16 wt = {0.f}, u = {0.f};
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                if (s4 < 2 * (rho + 1)) {            // M is lower triangular: tokens j <= r only
+                    wt = __builtin_amdgcn_mfma_f32_32x32x16_f16(gk[s4], mf[rho][s4], wt, 0, 0, 0);
+                    u = __builtin_amdgcn_mfma_f32_32x32x16_f16(mf[rho][s4], vv[s4], u, 0, 0, 0);
+                }
+            }
+            // -W: registers 8s..8s+7 of a lane are its 8 contraction slots of K-step s
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                u32x4 o4;
+#pragma unroll
+                for (int z = 0; z < 4; ++z) o4[z] = pack_h2(-wt[8 * s + 2 * z], -wt[8 * s + 2 * z + 1]);
+                slot_store16<kPolicy>(out, kOffWn + frag_rts(rho, wave, s) * kFragBytes + lane * 16, o4);
+            }
+#pragma unroll
+            for (int j2 = 0; j2 < 2; ++j2) {            // U as fp16: kda_scan rounds V_new = U - W S to fp16 anyway
+                u32x4 o4;
+#pragma unroll
+                for (int z = 0; z < 4; ++z) o4[z] = pack_h2(u[8 * j2 + 2 * z], u[8 * j2 + 2 * z + 1]);
+                slot_store16<kPolicy>(out, kOffU + (rho * 4 + wave) * kUTileBytes + (j2 * 64 + lane) * 16, o4);
+            }
+        }
+    }
+    if (kHandoff) {
+        // Hand the finished slot to kda_scan.  Every store to the slot is a write-through store;
+        // each wave waits until all of its stores have completed (vmcnt(0): a workgroup barrier
+        // alone does not wait for global stores), so after the barrier the slot is in place,
+        // device-wide, and one lane raises its flag.
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
+        __syncthreads();
+        if (tid == 0)
+            __hip_atomic_store(A.ready + slot, A.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (cur.valid) {
+        __syncthreads();                                     // the tiles in LDS are free for the next item
+    }
+    }
+
+    if (cur.valid) {                                         // ---- first half of this pass's item ----
+    const int h = cur.h, nv = cur.nv, row_bytes = cur.row_bytes;
+    const int64_t slot = cur.slot, row0 = cur.row0;
+    const __amdgpu_buffer_rsrc_t out = slot_resource(ws + slot * (int64_t)kSlotBytes);
     // ---- output gate (fused epilogue): the chunk's gate logits are re-laid into the accumulator
     // order of the sequential kernel, which reads them like any other part of the slot.  The loads
     // go out first and the stores follow the kernel's own loads, so the copy hides in their latency.
@@ -196,32 +524,16 @@ void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
-            u32x4 x = {0, 0, 0, 0};
-            if (tokv < nv)
-                x = *reinterpret_cast<const u32x4 *>(out_gate + ((tok0 + tokv) * H + h) * (int64_t)D + 8 * cg);
-            ograw[i] = x;
+            ograw[i] = rows_load16(rows_resource(out_gate + row0, row_bytes), tokv * row_pitch + 16 * cg);
         }
     }
 
-    // ---- loads: 16 bytes (8 channels) per ks and tensor ----
-    // (log_alpha first: the running sum below waits for it, k and q are not needed before B2)
-    u32x4 kraw[4], qraw[4], graw[4];
-    {
-        const u32x4 z = {0, 0, 0, 0};
-        const int64_t off = ((tok0 + tok) * H + h) * (int64_t)D + 8 * g;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            graw[ks] = (!kScalar && tok < nv) ? *reinterpret_cast<const u32x4 *>(log_alpha + off + 32 * ks) : z;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) kraw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(k + off + 32 * ks) : z;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qraw[ks] = (tok < nv) ? *reinterpret_cast<const u32x4 *>(q + off + 32 * ks) : z;
-    }
+    // ---- this item's inputs were fetched while the item before it was computed ----
+    const float gscalar = bf16_bits_to_float((uint16_t)gscalar_raw);    // kScalar: log alpha of this lane's token
+    const float beta_tok = bf16_bits_to_float((uint16_t)beta_raw);      // beta of token tid (threads 0..63)
     static_assert(!(kRaw && kScalar), "the fused prologue is built for the per-channel gate");
-    float gscalar = 0.f;                                     // kScalar: log alpha of this lane's token
-    if (kScalar && tok < nv) gscalar = bf16_bits_to_float(log_alpha[(tok0 + tok) * H + h]);
     if (tid < kChunk) {
-        float b = (tid < nv) ? bf16_bits_to_float(beta[(tok0 + tid) * H + h]) : 0.f;
+        float b = beta_tok;
         if (kRaw) b = (tid < nv) ? __builtin_amdgcn_rcpf(1.f + fast_exp2(-b * kLog2e)) : 0.f;   // Sigmoid
         sBeta[tid] = b;
     }
@@ -258,7 +570,6 @@ void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_
         invk = (tok < nv) ? __builtin_amdgcn_rsqf(sk + raw.eps) : 0.f;
     }
 
-    f32x4 res_kk[4], res_qk[4];              // A_kk, A_qk tiles (R, I), I = 0..R
     if constexpr (kScalar) {
         // ---- scalar gate: A[r][i] = (k_r . k_i) 2^(G_r - G_i), so the tiles are plain K K^T and Q K^T
         // products of the fp16 copies of k and q (exact: they come from bf16), and the decay, at most
@@ -560,7 +871,6 @@ void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_
             slot_store16<kPolicy>(out, kOffQp + frag_rts(tok >> 5, ks, g >> 1) * kFragBytes + ((tok & 31) + 32 * (g & 1)) * 16, o4);
         }
     }
-
     // ---- A_kk, A_qk tiles of sub-chunk row R on the matrix cores (16x16, K = 128) ----
     {
         f32x4 akk = {0.f, 0.f, 0.f, 0.f}, aqk = {0.f, 0.f, 0.f, 0.f};
@@ -587,12 +897,11 @@ void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_
                     float Ge = G[ks * 8];
 #pragma unroll
                     for (int z = 1; z < 8; ++z) Ge = (e == z) ? G[ks * 8 + z] : Ge;
-                    uint32_t kw = kraw[ks][0], qw = qraw[ks][0];
-#pragma unroll
-                    for (int z = 1; z < 4; ++z) {
-                        kw = ((e >> 1) == z) ? kraw[ks][z] : kw;
-                        qw = ((e >> 1) == z) ? qraw[ks][z] : qw;
-                    }
+                    // (k and q of the slot are read again: keeping the raw inputs in registers up to here for
+                    // the sake of this rare path would cost the common one 24 registers at its tightest point)
+                    const int woff = tok * row_pitch + 16 * g + 64 * ks + 4 * (e >> 1);
+                    const uint32_t kw = __builtin_amdgcn_raw_buffer_load_b32(rows_resource(k + row0, row_bytes), woff, 0, 0);
+                    const uint32_t qw = __builtin_amdgcn_raw_buffer_load_b32(rows_resource(q + row0, row_bytes), woff, 0, 0);
                     const float kfe = invk * ((e & 1) ? __uint_as_float(kw & 0xffff0000u) : __uint_as_float(kw << 16));
                     const float qfe = invq * ((e & 1) ? __uint_as_float(qw & 0xffff0000u) : __uint_as_float(qw << 16));
                     const int sl = ks * 8 + e;
@@ -650,217 +959,9 @@ void kda_intra_chunk(uint8_t *lds, const uint16_t *__restrict__ q, const uint16_
 
     }
 
-    // ---- L and Tril(A_qk) tiles of row R; fp16 V tile ----
-    {
-        // (L is kept transposed, sLT[column][row]: a lane's four rows of a column are contiguous, one
-        // 16-byte store per tile, and the substitution below reads a column of L as a row)
-        float *sLT = reinterpret_cast<float *>(lds + kL);
-        // (Tril(A_qk) likewise, sAqT[column][row] in fp16: 8-byte stores here, transposing reads below)
-        uint16_t *sAqT = reinterpret_cast<uint16_t *>(lds + kAq);
-        const f32x4 beta4 = *reinterpret_cast<const f32x4 *>(sBeta + 16 * R + 4 * g);
-#pragma unroll
-        for (int I = 0; I < 4; ++I) {
-            const int i = 16 * I + m;                       // column token of this lane
-            u32x2 av = {0u, 0u};
-            if (I <= R) {
-                f32x4 lv;
-                float qv[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int r = 16 * R + 4 * g + j;
-                    lv[j] = (i < r) ? beta4[j] * res_kk[I][j] : 0.f;
-                    qv[j] = (i <= r) ? res_qk[I][j] * scale : 0.f;
-                }
-                *reinterpret_cast<f32x4 *>(sLT + i * kLdF + 16 * R + 4 * g) = lv;
-                av[0] = pack_h2(qv[0], qv[1]); av[1] = pack_h2(qv[2], qv[3]);
-            }
-            *reinterpret_cast<u32x2 *>(sAqT + i * kLdM + 16 * R + 4 * g) = av;   // zeros above the diagonal tiles
-        }
     }
-    __syncthreads();                                                               // B5
-
-    // V is fetched now; its latency hides behind the UT transform
-    u32x4 vraw[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
-        u32x4 x = {0, 0, 0, 0};
-        if (tokv < nv)
-            x = *reinterpret_cast<const u32x4 *>(v + ((tok0 + tokv) * H + h) * (int64_t)D + 8 * cg);
-        vraw[i] = x;
-    }
-
-    // ---- UT transform, diagonal 16x16 blocks: column j of (I + L_ww)^-1 per lane ----
-    {
-        // (column by column: once x[i] is final, the updates of the rows below it are independent
-        // of one another, so the dependent chain is 16 long instead of 120; each x[r] still
-        // receives its terms in the order i = 0, 1, ..)
-        const float *sLT = reinterpret_cast<const float *>(lds + kL);
-        float *sX = reinterpret_cast<float *>(lds + kX);
-        const int j = lane & 15, w = wave;
-        float x[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) x[r] = (r == j) ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < 15; ++i) {
-            const float *col = sLT + (16 * w + i) * kLdF + 16 * w;      // L[16 w + r][16 w + i], r = 0..15
-            const float xi = x[i];
-#pragma unroll
-            for (int r = i + 1; r < 16; ++r) x[r] = fmaf(-col[r], xi, x[r]);
-        }
-        if (lane < 16) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sX[(16 * w + r) * kLdF + 16 * w + j] = x[r];
-        }
-    }
-    // ---- copy (Gamma^{i->C}.K)^T out in MFMA register order ----
-    {
-        // lane (x = lane % 32, hh): channel 32 tau + x, tokens 32 rho + kidx(s, hh, 0..7), which are two
-        // runs of four consecutive tokens: two transposing reads per fragment
-        const int hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int f = wave * 4 + i;                     // Kt frag f = (tau*2 + rho)*2 + s
-            const int tau = f >> 2, rho = (f >> 1) & 1, s = f & 1;
-            const uint8_t *blk = lds + kKp + ((32 * rho + kidx(s, hh, 0)) * kLdH + 32 * tau + xb) * 2;
-            const u32x2 lo = lds_read_tr4(blk, kLdH, lane), hi = lds_read_tr4(blk + 8 * kLdH * 2, kLdH, lane);
-            u32x4 o4 = {lo[0], lo[1], hi[0], hi[1]};
-            slot_store16<kPolicy>(out, kOffKt + f * kFragBytes + lane * 16, o4);
-        }
-    }
-    __syncthreads();                                                               // B6
-
-    // ---- UT transform, off-diagonal blocks: X_RI = -X_RR sum_{I<=J<R} L_RJ X_JI (fp32 MFMA) ----
-    {
-        const float *sLT = reinterpret_cast<const float *>(lds + kL);
-        float *sX = reinterpret_cast<float *>(lds + kX);
-        for (int Rr = 1; Rr < 4; ++Rr) {
-            if (wave < Rr) {
-                const int Ii = wave;
-                f32x4 t = {0.f, 0.f, 0.f, 0.f};
-                for (int J = Ii; J < Rr; ++J) {
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) {
-                        const float a = sLT[(16 * J + 4 * ks + g) * kLdF + 16 * Rr + m];   // L[16 Rr + m][16 J + 4 ks + g]
-                        const float b = sX[(16 * J + 4 * ks + g) * kLdF + 16 * Ii + m];
-                        t = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, t, 0, 0, 0);
-                    }
-                }
-                // second product with contraction slot (ks, g) standing for index 4 g + ks, so
-                // that register ks of the accumulator t is the B operand as it stands
-                f32x4 r = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const float a = sX[(16 * Rr + m) * kLdF + 16 * Rr + 4 * g + ks];
-                    r = __builtin_amdgcn_mfma_f32_16x16x4f32(a, t[ks], r, 0, 0, 0);
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) sX[(16 * Rr + 4 * g + j) * kLdF + 16 * Ii + m] = -r[j];
-            }
-            __syncthreads();                                                       // B7
-        }
-    }
-
-    // ---- M = X Diag(beta) as fp16 (over the dead K' tile); Tril(A_qk) out; V tile (over L) ----
-    {
-        const float *sX = reinterpret_cast<const float *>(lds + kX);
-        _Float16 *sM = reinterpret_cast<_Float16 *>(lds + kM);
-        // four consecutive columns per thread and pass: 16-byte reads, 8-byte writes
-#pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
-            const int idx = tid + 256 * pass, r = idx >> 4, j0 = 4 * (idx & 15);
-            const f32x4 xr = *reinterpret_cast<const f32x4 *>(sX + r * kLdF + j0);
-            const f32x4 br = *reinterpret_cast<const f32x4 *>(sBeta + j0);
-            float val[4];
-#pragma unroll
-            for (int z = 0; z < 4; ++z) {
-                const int j = j0 + z;
-                val[z] = (j < r) ? xr[z] * br[z] : ((j == r) ? br[z] : 0.f);
-            }
-            u32x2 w2 = {pack_h2(val[0], val[1]), pack_h2(val[2], val[3])};
-            *reinterpret_cast<u32x2 *>(sM + r * kLdM + j0) = w2;
-        }
-        // lane (x, hh) of fragment (rr, ri, s): row token 32 rr + x, column tokens 32 ri + 16 s + 4 hh + 0..3
-        // and + 8..11, which are rows of the transposed tile
-        const int hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
-        for (int idx = wave; idx < 6; idx += 4) {
-            const int p = idx >> 1, s = idx & 1;
-            const int rr = (p == 0) ? 0 : 1, ri = (p == 2) ? 1 : 0;
-            const uint8_t *blk = lds + kAq + ((32 * ri + 16 * s + 4 * hh) * kLdM + 32 * rr + xb) * 2;
-            const u32x2 a = lds_read_tr4(blk, kLdM, lane), b = lds_read_tr4(blk + 8 * kLdM * 2, kLdM, lane);
-            u32x4 o4 = {a[0], a[1], b[0], b[1]};
-            slot_store16<kPolicy>(out, kOffAqk + frag_aqk(rr, ri, s) * kFragBytes + lane * 16, o4);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
-            u32x4 y;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                float a, b;
-                unpack_bf16x2(vraw[i][w], a, b);
-                y[w] = pack_h2(a, b);
-            }
-            *reinterpret_cast<u32x4 *>(lds + kV + (tokv * kLdH + 8 * cg) * 2) = y;
-        }
-    }
-    __syncthreads();                                                               // B8
-
-    // ---- W^T = (Gamma.K)^T M^T (wave = d_k tile) and U = M V (wave = d_v tile) ----
-    {
-        // operands with the tokens in the contraction slots: lane (x, hh) wants channel 32 wave + x of
-        // the eight tokens 16 s4 + 8 hh + 0..7 of the [token][channel] tiles: two transposing reads each
-        const int x = lane & 31, hh = lane >> 5, xb = 16 * ((lane >> 4) & 1);
-        h8 mf[2][4], gk[4], vv[4];
-#pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-#pragma unroll
-            for (int rho = 0; rho < 2; ++rho)
-                mf[rho][s4] = *reinterpret_cast<const h8 *>(lds + kM + ((32 * rho + x) * kLdM + 16 * s4 + 8 * hh) * 2);
-            const int off = ((16 * s4 + 8 * hh) * kLdH + 32 * wave + xb) * 2;
-            const u32x2 g0 = lds_read_tr4(lds + kGK + off, kLdH, lane), g1 = lds_read_tr4(lds + kGK + off + 4 * kLdH * 2, kLdH, lane);
-            const u32x2 v0 = lds_read_tr4(lds + kV + off, kLdH, lane), v1 = lds_read_tr4(lds + kV + off + 4 * kLdH * 2, kLdH, lane);
-            u32x4 pg = {g0[0], g0[1], g1[0], g1[1]}, pv = {v0[0], v0[1], v1[0], v1[1]};
-            gk[s4] = __builtin_bit_cast(h8, pg);
-            vv[s4] = __builtin_bit_cast(h8, pv);
-        }
-#pragma unroll
-        for (int rho = 0; rho < 2; ++rho) {
-            f32x16 wt = {0.f}, u = {0.f};
-#pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4) {
-                if (s4 < 2 * (rho + 1)) {            // M is lower triangular: tokens j <= r only
-                    wt = __builtin_amdgcn_mfma_f32_32x32x16_f16(gk[s4], mf[rho][s4], wt, 0, 0, 0);
-                    u = __builtin_amdgcn_mfma_f32_32x32x16_f16(mf[rho][s4], vv[s4], u, 0, 0, 0);
-                }
-            }
-            // -W: registers 8s..8s+7 of a lane are its 8 contraction slots of K-step s
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                u32x4 o4;
-#pragma unroll
-                for (int z = 0; z < 4; ++z) o4[z] = pack_h2(-wt[8 * s + 2 * z], -wt[8 * s + 2 * z + 1]);
-                slot_store16<kPolicy>(out, kOffWn + frag_rts(rho, wave, s) * kFragBytes + lane * 16, o4);
-            }
-#pragma unroll
-            for (int j2 = 0; j2 < 2; ++j2) {            // U as fp16: kda_scan rounds V_new = U - W S to fp16 anyway
-                u32x4 o4;
-#pragma unroll
-                for (int z = 0; z < 4; ++z) o4[z] = pack_h2(u[8 * j2 + 2 * z], u[8 * j2 + 2 * z + 1]);
-                slot_store16<kPolicy>(out, kOffU + (rho * 4 + wave) * kUTileBytes + (j2 * 64 + lane) * 16, o4);
-            }
-        }
-    }
-    if (kHandoff) {
-        // Hand the finished slot to kda_scan.  Every store to the slot is a write-through store;
-        // each wave waits until all of its stores have completed (vmcnt(0): a workgroup barrier
-        // alone does not wait for global stores), so after the barrier the slot is in place,
-        // device-wide, and one lane raises its flag.
-        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
-        __syncthreads();
-        if (tid == 0)
-            __hip_atomic_store(ready + ((int64_t)n * H + h) * seg_chunks + cl, epoch, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+    prev = cur;
+    cur = (item + 1 < count) ? locate(item_at(item + 1)) : locate(IntraItem{0, 0, -1});
     }
 }
 

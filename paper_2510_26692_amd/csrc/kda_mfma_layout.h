@@ -67,6 +67,7 @@ constexpr int kSplitMaxParts = 8;
 constexpr int kSplitMaxPairs = 42;
 constexpr int kSplitMinChunks = 24;
 constexpr size_t kSplitFlagBytes = 4096;     // 24 u32 counters per pair, ahead of the states
+static_assert((size_t)kSplitMaxPairs * 24 * 4 <= kSplitFlagBytes, "every pair's counters must fit the area");
 
 // Geometry of one launch pair: `seg_chunks` chunk indices of every sequence.
 struct SegPlan {

@@ -284,6 +284,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         L.num_flags = parts > 1 ? (int64_t)((plan.split_offset + kSplitFlagBytes - plan.flags_offset) / 4)
                                 : (int64_t)plan.seg_chunks * streams;
         L.reset_split = parts > 1 && seg > 0;
+        L.compute_units = cus;
         const kda_status st = launch_prefill_fused(L, stream);
         if (st != KDA_OK) return st;
     }

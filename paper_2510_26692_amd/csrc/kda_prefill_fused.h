@@ -10,6 +10,9 @@ namespace mfma {
 // compute unit.
 constexpr int kMaxBatchPairs = 64;
 
+// Chunks one workgroup of the per-chunk role works through (the fetch of each hides behind the one before).
+constexpr int kItemsPerWorkgroup = 4;
+
 // Time-split scan (kda_scan4_split.h): workspace areas and the cut of the chunk axis.
 struct SplitArgs {
     float *E, *Tm, *Bm;          // [kSplitMaxParts][pairs][128][128] fp32 each
@@ -36,6 +39,7 @@ struct FusedArgs {
     float scale;
     uint32_t epoch;                 // value of a raised flag
     int producers;                  // 0: the per-chunk role does nothing (a diagnostic: every wait of the scan role then runs out)
+    int per_wg, window;             // per-chunk role: chunks per workgroup, and workgroups that share a run of window * per_wg chunks
     RawParams raw;
     SplitArgs split;
 };
@@ -46,6 +50,7 @@ struct FusedLaunch {
     bool reset_flags;               // clear num_flags words at args.ready and the status word first
     int64_t num_flags;
     bool reset_split;               // clear the counters of the time-split scan first (segments after the first)
+    int compute_units;              // of the device the launch goes to
 };
 
 int fused_batch_pairs(int64_t pairs);

@@ -27,6 +27,28 @@ namespace mfma {
 
 static_assert(kIntraLds <= scan4::kLds, "both roles run in the LDS of the larger one");
 
+// The per-chunk role works through its items (chunk, sequence, head) in the order the scan role wants them,
+// per_wg items per workgroup.  `window` consecutive workgroups share a run of window * per_wg items and
+// take them in per_wg passes, workgroup r the items r, window + r, 2 window + r, .. of the run: as long as a
+// window's workgroups are resident together (the host sizes it for that), the items are finished in nearly the
+// order of their index, as they would be with one item per workgroup.
+__host__ __device__ inline int64_t intra_workgroups(int64_t items, int per_wg, int window)
+{
+    const int64_t run = (int64_t)window * per_wg;
+    const int64_t full = items / run, rest = items - full * run;
+    return full * window + (rest < window ? rest : window);
+}
+__device__ __forceinline__ int64_t item_index(int64_t wg, int t, int per_wg, int window)
+{
+    const int64_t w = wg / window, r = wg - w * window;
+    return w * window * per_wg + (int64_t)t * window + r;
+}
+__device__ __forceinline__ IntraArgs intra_args(const FusedArgs &a)
+{
+    return IntraArgs{a.q, a.k, a.v, a.log_alpha, a.beta, a.cu, a.ws, a.T, a.H, a.seg_chunks, a.seg_index, a.scale,
+                     a.ready, a.epoch, a.raw, nullptr, nullptr, a.status};
+}
+
 template <bool kRaw, bool kScalar, bool kOutBf16>
 __global__ __launch_bounds__(256, 2)
 void kda_prefill_kernel(const FusedArgs a)
@@ -55,23 +77,28 @@ void kda_prefill_kernel(const FusedArgs a)
         if (!a.producers) return;
         // The first phase of the scan walks all ranges but the last side by side, so the chunk order
         // interleaves those and lets the last range follow.
-        const int64_t i = bid - nscan;
-        const int64_t z = i / a.pairs, pair = i - z * a.pairs;
         const int64_t first = a.split.parts - 1, part_len = a.split.part_len, part0_len = a.split.part0_len;
-        int64_t cl;
-        if (z < first * part_len) {
-            const int64_t rr = z % first, j = z / first;
-            if (rr == 0 && j >= part0_len) return;                   // the first range is the shorter one
-            cl = (rr == 0) ? j : part0_len + (rr - 1) * part_len + j;
-        } else {
-            cl = part0_len + (first - 1) * part_len + (z - first * part_len);
-        }
-        const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
-        kda_intra_chunk<true, kRaw, kScalar>(lds, a.q, a.k, a.v, a.log_alpha, a.beta, a.cu, a.ws, a.T, a.H, a.seg_chunks,
-                                             a.seg_index, a.scale, a.ready, a.epoch, a.raw, nullptr, nullptr, h, n, cl, a.status);
+        const int64_t total = a.pairs * (int64_t)a.split.parts * part_len;
+        kda_intra_items<true, kRaw, kScalar>(lds, intra_args(a), a.per_wg, [&](int t) __attribute__((always_inline)) {
+            const int64_t i = item_index(bid - nscan, t, a.per_wg, a.window);
+            IntraItem it = {0, 0, -1};
+            if (i >= total) return it;
+            const int64_t z = i / a.pairs, pair = i - z * a.pairs;
+            int64_t cl;
+            if (z < first * part_len) {
+                const int64_t rr = z % first, j = z / first;
+                if (rr == 0 && j >= part0_len) return it;                // the first range is the shorter one
+                cl = (rr == 0) ? j : part0_len + (rr - 1) * part_len + j;
+            } else {
+                cl = part0_len + (first - 1) * part_len + (z - first * part_len);
+            }
+            it.n = (int)(pair / a.H); it.h = (int)(pair - (int64_t)it.n * a.H); it.cl = cl;
+            return it;
+        });
         return;
     }
-    const int64_t per_batch = (int64_t)a.nb * (1 + a.launch_chunks);
+    const int64_t batch_items = (int64_t)a.nb * a.launch_chunks;
+    const int64_t per_batch = a.nb + intra_workgroups(batch_items, a.per_wg, a.window);
     const int64_t bid = blockIdx.x;
     const int64_t b = bid / per_batch, r = bid - b * per_batch;
     if (r < a.nb) {
@@ -92,15 +119,17 @@ void kda_prefill_kernel(const FusedArgs a)
                                               tok_base, len, a.H, c_begin, c_end, h, a.ready + pair * a.seg_chunks, a.epoch,
                                               a.status, a.wait_limit);
     } else {
-        // ---- per-chunk role: one (chunk, sequence, head), chunk index first ----
+        // ---- per-chunk role: per_wg (chunk, sequence, head) items of this batch, chunk index first ----
         if (!a.producers) return;
-        const int64_t i = r - a.nb;
-        const int64_t cl = i / a.nb, pl = i - cl * a.nb;
-        const int64_t pair = b * a.nb + pl;
-        if (pair >= a.pairs) return;
-        const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
-        kda_intra_chunk<true, kRaw, kScalar>(lds, a.q, a.k, a.v, a.log_alpha, a.beta, a.cu, a.ws, a.T, a.H, a.seg_chunks,
-                                             a.seg_index, a.scale, a.ready, a.epoch, a.raw, nullptr, nullptr, h, n, cl, a.status);
+        kda_intra_items<true, kRaw, kScalar>(lds, intra_args(a), a.per_wg, [&](int t) __attribute__((always_inline)) {
+            const int64_t i = item_index(r - a.nb, t, a.per_wg, a.window);
+            IntraItem it = {0, 0, -1};
+            if (i >= batch_items) return it;
+            const int64_t cl = i / a.nb, pair = b * a.nb + (i - cl * a.nb);
+            if (pair >= a.pairs) return it;
+            it.n = (int)(pair / a.H); it.h = (int)(pair - (int64_t)it.n * a.H); it.cl = cl;
+            return it;
+        });
     }
 }
 
@@ -145,11 +174,19 @@ kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
     FusedArgs a = L.args;
     a.nb = fused_batch_pairs(a.pairs);
     int64_t blocks;
+    // chunks per workgroup of the per-chunk role, and the workgroups of that role expected to be resident
+    // together: two per compute unit, less the scan workgroups beside them (two batches' worth, or all of them)
+    const int slots = 2 * L.compute_units;
+    a.per_wg = kItemsPerWorkgroup;
     if (a.split.parts > 1) {
-        blocks = a.pairs * (int64_t)(2 * a.split.parts - 3) + a.pairs * (int64_t)a.split.parts * a.split.part_len;
+        const int64_t nscan = a.pairs * (int64_t)(2 * a.split.parts - 3);
+        a.window = (int)(slots - nscan > 64 ? slots - nscan : 64);
+        blocks = nscan + intra_workgroups(a.pairs * (int64_t)a.split.parts * a.split.part_len, a.per_wg, a.window);
     } else {
         const int64_t nbatches = (a.pairs + a.nb - 1) / a.nb;
-        blocks = nbatches * (int64_t)a.nb * (1 + a.launch_chunks);
+        const int64_t beside = nbatches > 1 ? 2 * a.nb : a.nb;
+        a.window = (int)(slots - beside > 64 ? slots - beside : 64);
+        blocks = nbatches * (a.nb + intra_workgroups((int64_t)a.nb * a.launch_chunks, a.per_wg, a.window));
     }
     if (blocks > 0x7fffffffLL)
         return fail(KDA_ERR_UNSUPPORTED, "%lld workgroups in one launch: use a smaller workspace (shorter time segments)",

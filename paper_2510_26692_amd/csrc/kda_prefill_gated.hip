@@ -25,9 +25,11 @@ void kda_intra_gate_kernel(const uint16_t *__restrict__ q, const uint16_t *__res
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     // x = head, y = chunk, z = sequence: consecutive workgroups read neighbouring tokens
-    kda_intra_chunk<false, kRaw, false>(lds, q, k, v, log_alpha, beta, cu_seqlens, ws, T, H, seg_chunks, seg_index, scale,
-                                        nullptr, 0u, raw, out_gate, gate_ws, (int)blockIdx.x, (int)blockIdx.z,
-                                        (int64_t)blockIdx.y);
+    const IntraArgs A = {q, k, v, log_alpha, beta, cu_seqlens, ws, T, H, seg_chunks, seg_index, scale, nullptr, 0u, raw,
+                         out_gate, gate_ws, nullptr};
+    kda_intra_items<false, kRaw, false>(lds, A, 1, [&](int) __attribute__((always_inline)) {
+        return IntraItem{(int)blockIdx.x, (int)blockIdx.z, (int64_t)blockIdx.y};
+    });
 }
 
 static bool reserve_gated_lds()

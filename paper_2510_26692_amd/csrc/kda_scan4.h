@@ -195,6 +195,9 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const int c = __builtin_amdgcn_readfirstlane(tid >> 6);       // the wave: column slice of S, V_new, O
+    // The chain of steps is the critical path of the whole prefill, the per-chunk workgroups that share the
+    // compute unit are throughput work: the waves of this role go first where both want to issue.
+    __builtin_amdgcn_s_setprio(3);
     const int x = lane & 31, hh = lane >> 5;
     const uint32_t lane16 = (uint32_t)lane * 16;
     constexpr bool kFull = kRole == kRoleFull;
