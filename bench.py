@@ -79,7 +79,7 @@ def make_workload(torch, si, name, dev):
     raise SystemExit("unknown workload " + name)
 
 
-def run_prefill(torch, si, kda, name, steps, warmup, dev, cpu_seconds, breakdown):
+def run_prefill(torch, si, kda, name, steps, warmup, dev, cpu_seconds):
     """Times kda_chunk_fwd on one workload; returns the result object (ms, tokens/s, roofline, cpu_baseline)."""
     c = si.CONFIGS[name]
     x, tokens, max_len, desc = make_workload(torch, si, name, dev)
@@ -101,11 +101,10 @@ def run_prefill(torch, si, kda, name, steps, warmup, dev, cpu_seconds, breakdown
 
     alg_bytes = tokheads * BYTES_PER_TOKHEAD + 2 * dims.num_seqs * H * 128 * 128 * 4
     traffic, traffic_file = measured_traffic(name)
-    kernels = kda.kda_chunk_fwd_kernel_names(dims, ws) if hasattr(kda, "kda_chunk_fwd_kernel_names") else None
     roofline = {
-        # the call's kernels run side by side from the first to the last microsecond of the call, so the
-        # duration of the dominant one is the call's own (HIP events on the launch stream around K calls)
-        "kernel": kernels or "kda_chunk_fwd (its kernels run side by side for the length of the call)",
+        # one kernel per call (both stages are roles of kda_prefill_kernel), so the kernel's duration is the
+        # call's own (HIP events on the launch stream around K calls)
+        "kernel": "kda_prefill_kernel",
         "bound": "hbm",
         "achieved": alg_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -118,8 +117,6 @@ def run_prefill(torch, si, kda, name, steps, warmup, dev, cpu_seconds, breakdown
     res = {"metric": "KDA prefill tokens/s", "value": tokens / (ms * 1e-3), "unit": "tokens/s",
            "ms_per_step": ms, "steps": steps, "warmup": warmup, "config": desc,
            "tokheads_per_s": tokheads / (ms * 1e-3), "workspace_bytes": int(ws.numel()), "roofline": roofline}
-    if breakdown:
-        res["breakdown"] = breakdown(kda, torch, prefill, steps)
 
     if cpu_seconds > 0:
         import oracle
@@ -212,6 +209,18 @@ def run_decode(torch, si, kda, steps, warmup, dev, cpu_baseline):
     del src, dst
     obj["roofline"]["measured_copy_GBps"] = copy_gbs
     obj["roofline"]["frac_of_measured_copy"] = obj["value"] / copy_gbs
+
+    # what this device streams with the simplest kernels: 512 MiB (the size of the state pool) read only, written
+    # only, and read-modified-written in place, which is the traffic of the decode step
+    buf = torch.empty(N4 * H4 * dk4 * dv4, dtype=torch.float32, device=dev)
+    rates = {}
+    for mode, name in ((0, "read_only"), (1, "write_only"), (2, "read_modify_write_in_place")):
+        kda.kda_debug_stream_probe(mode, buf)
+        ms = _time_region(torch, lambda: kda.kda_debug_stream_probe(mode, buf), 20)
+        rates[name + "_GBps"] = (2 if mode == 2 else 1) * buf.numel() * 4 / (ms * 1e-3) / 1e9
+    del buf
+    obj["roofline"]["measured_stream"] = rates
+    obj["roofline"]["frac_of_measured_read_modify_write"] = obj["value"] / rates["read_modify_write_in_place_GBps"]
 
     if cpu_baseline:
         import numpy as np
@@ -349,13 +358,21 @@ def main():
         # the small workloads take well under a millisecond per step: more steps for a steady figure
         steps = args.steps if name == HEADLINE else max(args.steps, 50)
         warmup = args.warmup if name == HEADLINE else max(args.warmup, 10)
-        results[name] = run_prefill(torch, si, kda, name, steps, warmup, dev, 10.0 if cpu else 0.0, None)
+        results[name] = run_prefill(torch, si, kda, name, steps, warmup, dev, 10.0 if cpu else 0.0)
     decode_obj = None
     if args.only in (None, "cfg4_decode_bf16"):
         decode_obj = run_decode(torch, si, kda, max(args.steps, 50), max(args.warmup, 10), dev, cpu)
     extras = run_extras(torch, si, kda, max(args.steps, 50), max(args.warmup, 10), dev, cpu) if args.extras else None
 
     head = results.get(HEADLINE) or next(iter(results.values()), None) or decode_obj
+    if args.only is None:
+        # what the matrix cores of this device deliver on the prefill's own instruction, beside the data-sheet peak
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        wgs = 8 * torch.cuda.get_device_properties(0).multi_processor_count
+        flops = kda.kda_debug_mfma_probe(sink, wgs, 2000)
+        ms_mfma = _time_region(torch, lambda: kda.kda_debug_mfma_probe(sink, wgs, 2000), 5)
+        head["roofline"]["measured_mfma_f16_TFLOPs"] = flops / (ms_mfma * 1e-3) / 1e12
+        head["roofline"]["mfma_peak_TFLOPs"] = MFMA_PEAK_TFLOPS
     out = {
         "metric": head["metric"], "value": head["value"], "unit": head["unit"],
         "n_gpus": 1, "steps": head["steps"], "warmup": head.get("warmup", args.warmup), "ms_per_step": head["ms_per_step"],

@@ -46,6 +46,23 @@ void kda_debug_set_wait_limit(unsigned long long ticks);
 kda_status kda_debug_chunk_fwd_plan(const kda_dims *dims, size_t workspace_bytes, int output_gate,
                                     int64_t out[5]);
 
+/*
+ * The device's own rates, for reading a roofline fraction against what this device delivers beside its
+ * data-sheet peak.  Both launch one kernel on `hip_stream` and return at once; the caller times them.
+ *
+ * kda_debug_stream_probe: streams `bytes` (a multiple of 65 536, the size of one decode state) of the
+ * device buffer `buffer` (16-byte aligned, overwritten) in tiles of 64 KiB, one workgroup of 256 threads per
+ * tile, sixteen 16-byte accesses per thread: mode 0 reads only, 1 writes only, 2 reads, modifies and writes in
+ * place, which is the traffic of kda_recurrent_step.
+ *
+ * kda_debug_mfma_probe: `workgroups` workgroups of four waves; every wave issues 16 * iters matrix products
+ * 32x32x16 (f16 operands, fp32 accumulation, the instruction of the prefill kernels) on four independent
+ * accumulators.  *flops (may be NULL) receives the floating-point operations of the launch; sink: one float of
+ * device memory (never written in practice).
+ */
+kda_status kda_debug_stream_probe(int mode, float *buffer, size_t bytes, void *hip_stream);
+kda_status kda_debug_mfma_probe(float *sink, int workgroups, int iters, double *flops, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -86,6 +86,10 @@ def load_library():
     lib.kda_debug_chunk_fwd_plan.restype = ctypes.c_int
     lib.kda_debug_chunk_fwd_plan.argtypes = [ctypes.POINTER(KdaDims), ctypes.c_size_t, ctypes.c_int,
                                              ctypes.POINTER(ctypes.c_int64)]
+    lib.kda_debug_stream_probe.restype = ctypes.c_int
+    lib.kda_debug_stream_probe.argtypes = [ctypes.c_int, vp, sz, vp]
+    lib.kda_debug_mfma_probe.restype = ctypes.c_int
+    lib.kda_debug_mfma_probe.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     lib.kda_debug_set_time_split.restype = None
     lib.kda_debug_set_time_split.argtypes = [ctypes.c_int]
     lib.kda_recurrent_step.restype = ctypes.c_int
@@ -136,6 +140,28 @@ def kda_debug_chunk_fwd_plan(dims, workspace_bytes, output_gate=False):
     if st != 0:
         raise KdaError(st, kda_last_error())
     return tuple(int(x) for x in out)
+
+
+def kda_debug_stream_probe(mode, buffer):
+    """One streaming pass over the fp32 device tensor `buffer` (a multiple of 65536 bytes, overwritten) on the
+    current stream: mode 0 reads, 1 writes, 2 reads, modifies and writes in place.  Returns the bytes of the buffer."""
+    _check_dev(buffer)
+    assert buffer.dtype == torch.float32 and buffer.is_contiguous()
+    nbytes = buffer.numel() * 4
+    st = load_library().kda_debug_stream_probe(int(mode), _ptr(buffer), ctypes.c_size_t(nbytes), _stream_ptr(buffer.device))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return nbytes
+
+
+def kda_debug_mfma_probe(sink, workgroups, iters):
+    """One launch of the matrix-core probe on the current stream; returns its floating-point operations."""
+    _check_dev(sink)
+    flops = ctypes.c_double(0.0)
+    st = load_library().kda_debug_mfma_probe(_ptr(sink), int(workgroups), int(iters), ctypes.byref(flops), _stream_ptr(sink.device))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return flops.value
 
 
 def kda_debug_set_time_split(mode):
