@@ -61,6 +61,15 @@ kda_status kda_debug_chunk_fwd_plan(const kda_dims *dims, size_t workspace_bytes
  * device memory (never written in practice).
  */
 kda_status kda_debug_stream_probe(int mode, float *buffer, size_t bytes, void *hip_stream);
+/*
+ * kda_debug_prefill_traffic_probe: the data movement of the two-stage matrix-core prefill and nothing else.  `buffer`
+ * (device, 16-byte aligned, overwritten) holds bytes / 172 032 items of [64 KiB in][72 KiB slot][32 KiB out]; one
+ * workgroup per item reads its input, writes its slot, reads the slot of the item half the buffer away (written by
+ * another workgroup of the launch or an earlier one) and writes its output: 240 KiB through the memory system per
+ * item, which is what kda_chunk_fwd moves per chunk and head with bf16 inputs and fp32 o.  *moved (may be NULL)
+ * receives the bytes the launch moves.  The time of a launch is the floor of a prefill of that many chunks.
+ */
+kda_status kda_debug_prefill_traffic_probe(void *buffer, size_t bytes, size_t *moved, void *hip_stream);
 kda_status kda_debug_mfma_probe(float *sink, int workgroups, int iters, double *flops, void *hip_stream);
 
 #ifdef __cplusplus

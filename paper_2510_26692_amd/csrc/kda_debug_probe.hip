@@ -30,6 +30,29 @@ __global__ __launch_bounds__(256) void kda_stream_probe_kernel(float *buf, float
     }
 }
 
+// mode 3: the data movement of the two-stage prefill and nothing else.  Item i (one chunk of one head) reads 64 KiB of
+// streamed input, writes a 72 KiB slot, reads the slot of another item (written by another workgroup) and writes
+// 32 KiB of streamed output: 240 KiB through the memory system per item, as kda_prefill_kernel moves per chunk with
+// bf16 inputs and fp32 o.  The buffer holds `items` records of 168 KiB: [64 KiB in][72 KiB slot][32 KiB out].
+constexpr int kItemIn = 65536, kItemSlot = 73728, kItemOut = 32768, kItemBytes = kItemIn + kItemSlot + kItemOut;
+__global__ __launch_bounds__(256) void kda_prefill_traffic_probe_kernel(uint8_t *buf, unsigned items, float a)
+{
+    const unsigned i = blockIdx.x, j = (i + items / 2) % items;
+    const f32x4 *in = reinterpret_cast<const f32x4 *>(buf + (size_t)i * kItemBytes) + threadIdx.x;
+    f32x4 *slot = reinterpret_cast<f32x4 *>(buf + (size_t)i * kItemBytes + kItemIn) + threadIdx.x;
+    const f32x4 *other = reinterpret_cast<const f32x4 *>(buf + (size_t)j * kItemBytes + kItemIn) + threadIdx.x;
+    f32x4 *out = reinterpret_cast<f32x4 *>(buf + (size_t)i * kItemBytes + kItemIn + kItemSlot) + threadIdx.x;
+    f32x4 acc = {a, a, a, a};
+#pragma unroll
+    for (int m = 0; m < kItemIn / 4096; ++m) acc += __builtin_nontemporal_load(in + m * 256);
+#pragma unroll
+    for (int m = 0; m < kItemSlot / 4096; ++m) __builtin_nontemporal_store(acc, slot + m * 256);
+#pragma unroll
+    for (int m = 0; m < kItemSlot / 4096; ++m) acc += __builtin_nontemporal_load(other + m * 256);
+#pragma unroll
+    for (int m = 0; m < kItemOut / 4096; ++m) __builtin_nontemporal_store(acc, out + m * 256);
+}
+
 // Every wave issues 16 * iters products 32x32x16 (f16 in, fp32 out) on four independent accumulators.
 __global__ __launch_bounds__(256) void kda_mfma_probe_kernel(float *sink, int iters)
 {
@@ -70,6 +93,20 @@ extern "C" kda_status kda_debug_stream_probe(int mode, float *buffer, size_t byt
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, stream, buffer, 0.5f);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_stream_probe_kernel: %s", hipGetErrorString(e));
+    return KDA_OK;
+}
+
+extern "C" kda_status kda_debug_prefill_traffic_probe(void *buffer, size_t bytes, size_t *moved, void *hip_stream)
+{
+    if (!buffer || bytes < 2 * (size_t)kItemBytes || bytes % kItemBytes != 0 || (reinterpret_cast<uintptr_t>(buffer) & 15u))
+        return fail(KDA_ERR_INVALID_ARG, "buffer must be 16-byte aligned and a multiple (at least two) of %d bytes long", kItemBytes);
+    const size_t items = bytes / kItemBytes;
+    if (items > 0x7fffffffu) return fail(KDA_ERR_INVALID_ARG, "buffer too large");
+    hipLaunchKernelGGL(kda_prefill_traffic_probe_kernel, dim3((unsigned)items), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<uint8_t *>(buffer), (unsigned)items, 0.5f);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "kda_prefill_traffic_probe_kernel: %s", hipGetErrorString(e));
+    if (moved) *moved = items * (size_t)(kItemIn + 2 * kItemSlot + kItemOut);
     return KDA_OK;
 }
 

@@ -45,15 +45,6 @@ constexpr int kRoleFull = 0, kRoleT = 1, kRoleB = 2;
 
 namespace scan4 {
 
-#ifndef KDA_STORE_AUX
-#define KDA_STORE_AUX 0
-#endif
-#ifdef KDA_SCAN4_TRACE
-__device__ unsigned long long g_trace[64 * 8];
-#define KDA_TS(slot) do { if (blockIdx.x == KDA_TRACE_BLOCK && threadIdx.x == 0 && rel >= 8 && rel < 72) g_trace[(rel - 8) * 8 + (slot)] = wall_clock64(); } while (0)
-#else
-#define KDA_TS(slot) do { } while (0)
-#endif
 
 constexpr int kBig = 16 * kFragBytes;                       // W, Gamma.Q or K^T of one chunk
 constexpr int kSmall = 8 * kFragBytes;                      // Tril(A_qk), gamma^C (and the first bytes of U, unused)
@@ -98,9 +89,6 @@ __device__ __forceinline__ void dma2(uint32_t m0, uint32_t voff, const uint8_t *
 // One LDS-direct load of 16 bytes per lane: LDS byte m0 + 16 L <- src[voff(L)].
 __device__ __forceinline__ void dma1(uint32_t m0, uint32_t voff, const uint8_t *src)
 {
-#ifdef KDA_DBG_NOVMEM
-    return;
-#endif
     asm volatile("s_mov_b32 m0, %0\n\t"
                  "s_nop 0\n\t"
                  "global_load_lds_dwordx4 %1, %2 sc1"
@@ -108,9 +96,6 @@ __device__ __forceinline__ void dma1(uint32_t m0, uint32_t voff, const uint8_t *
 }
 __device__ __forceinline__ void load1(u32x4 &a, uint32_t voff, const uint8_t *src)
 {
-#ifdef KDA_DBG_NOVMEM
-    return;
-#endif
     asm volatile("global_load_dwordx4 %0, %1, %2 sc1" : "=&v"(a) : "v"(voff), "s"(src) : "memory");
 }
 // lane i of each quad of four lanes receives the value of lane kSel[i] of the quad
@@ -173,11 +158,6 @@ __device__ __noinline__ bool wait_flag(const uint32_t *flag, uint32_t epoch, uin
         __builtin_amdgcn_s_sleep(8);
     }
 }
-
-// Output parameters of the scan (the fused output gate is not part of this path).
-struct Out {
-    void *o;                 // [B,T,H,dv], fp32 or bf16
-};
 
 // One pass over the chunks [c_begin, c_end) of one (sequence, head): 256 threads, kLds bytes at `lds`.
 //   slot0, slot_stride   the slot of chunk c_begin and the byte distance to the next chunk's
@@ -291,10 +271,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
         take_u();
 
         const uint32_t o_rstride = (uint32_t)H * D * (kOutBf16 ? 2 : 4);   // bytes between consecutive tokens of o
-#ifndef KDA_LA
-#define KDA_LA 4
-#endif
-        constexpr int LA = KDA_LA, RING = KDA_LA + 2;
+        constexpr int LA = 4, RING = LA + 2;                     // operand fragments read ahead of the product that uses them
         // Vector-memory instructions are handed to the memory pipe one at a time between the matrix
         // products (a burst of them stalls the wave at issue, and the products behind it), in this order:
         //   phase V  the flag of the step after next, then W, the small piece and U of the next step   (G1)
@@ -321,7 +298,6 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
             }
             const uint32_t *flag2 = kFlags ? flag_of(rel + 2) : nullptr;
             __builtin_amdgcn_sched_barrier(0);
-            KDA_TS(0);
 
             // ---- phase V: V_new[P] = U[P] + (-W)(P, tau, s) S(tau, s), slot i: P = i % 2, (tau, s) = i / 2 ----
             h8 Sb[8];                                            // fp16 copy of S as it enters the step: (tau, s) -> Sb[2 tau + s]
@@ -358,10 +334,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
                 for (int s = 0; s < 2; ++s)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) Vb[P][s][e] = (_Float16)av[P][8 * s + e];
-
-            KDA_TS(1);
             phase_barrier<G3 + G4 + G1>();                       // Gamma.Q (and the small piece) of this step
-            KDA_TS(2);
 
             // ---- phase O: O^T[P] = S^T (Gamma.Q)(P)^T + V_new^T Tril(A_qk)(P, rho)^T; between the products the
             // state is scaled, S <- Diag(gamma^C) S (the products read the fp16 copy taken in phase V) ----
@@ -445,10 +418,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
             // bf16: store qq of tile P: token 32 P + x, columns 32 c + 8 (qq + 2 hh) + 0..7
             const uint32_t ol = kOutBf16 ? (uint32_t)x * o_rstride + (uint32_t)(32 * c + 16 * hh) * 2
                                          : (uint32_t)(x & ~3) * o_rstride + (uint32_t)(32 * c + 8 * (x & 3) + 4 * hh) * 4;
-
-            KDA_TS(3);
             phase_barrier<G1 + G2 + G3>();                       // K^T of this step
-            KDA_TS(4);
 
             // ---- phase S: S += (Gamma^{i->C}.K)^T V_new (S is already scaled), slot i: tau = i % 4, (rho, s) = i / 4.
             // Slots 0..3 also issue K^T of the next step and turn output tile 0 into store order, 4..7 store it
@@ -469,11 +439,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
                         constexpr int P = (i - 4) / 4, k = (i - 4) % 4;
                         if constexpr (k < kStores / 2) {
                             const uint32_t off = ol + (uint32_t)(32 * P) * o_rstride + (kOutBf16 ? (uint32_t)k * 16 : (uint32_t)k * o_rstride);
-#ifdef KDA_DBG_NOVMEM
-                            asm volatile("" :: "v"(ot[P][k]), "v"(off));
-#else
                             __builtin_amdgcn_raw_buffer_store_b128(ot[P][k], orsrc, (int)off, 0, 0);
-#endif
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -481,9 +447,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
             }
 
             // ---- the next step's W and U are here: take U, note whether the flag read in phase V was up ----
-            KDA_TS(5);
             phase_barrier<G2 + G3 + G4>();
-            KDA_TS(6);
             take_u();
             if (kFlags) next_ok = (uint32_t)__builtin_amdgcn_readfirstlane((int)seen) == epoch;
         }

@@ -88,6 +88,8 @@ def load_library():
                                              ctypes.POINTER(ctypes.c_int64)]
     lib.kda_debug_stream_probe.restype = ctypes.c_int
     lib.kda_debug_stream_probe.argtypes = [ctypes.c_int, vp, sz, vp]
+    lib.kda_debug_prefill_traffic_probe.restype = ctypes.c_int
+    lib.kda_debug_prefill_traffic_probe.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_size_t), vp]
     lib.kda_debug_mfma_probe.restype = ctypes.c_int
     lib.kda_debug_mfma_probe.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     lib.kda_debug_set_time_split.restype = None
@@ -152,6 +154,19 @@ def kda_debug_stream_probe(mode, buffer):
     if st != 0:
         raise KdaError(st, kda_last_error())
     return nbytes
+
+
+def kda_debug_prefill_traffic_probe(buffer):
+    """One launch of the prefill traffic probe over the uint8 device tensor `buffer` (a multiple of 172032 bytes,
+    overwritten) on the current stream; returns (items, bytes moved)."""
+    _check_dev(buffer)
+    nbytes = buffer.numel() * buffer.element_size()
+    moved = ctypes.c_size_t(0)
+    st = load_library().kda_debug_prefill_traffic_probe(_ptr(buffer), ctypes.c_size_t(nbytes), ctypes.byref(moved),
+                                                        _stream_ptr(buffer.device))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return nbytes // 172032, int(moved.value)
 
 
 def kda_debug_mfma_probe(sink, workgroups, iters):
