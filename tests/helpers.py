@@ -37,6 +37,33 @@ def state_slices(N, H):
     return [(n, h) for n in range(N) for h in range(H)]
 
 
+def gated_error_ratio(o_gated, o_plain_ref, gate, weight, eps, slices, tol):
+    """Largest |o_gated - ref| / bound over all elements of the output gate's result.
+
+    The stated tolerance is on o as the recurrence produces it: |o - o_ref| <= tol * max|o_ref| over a
+    (sequence, head).  The gate (Section 4) then divides token t by r_t = sqrt(mean_j o_tj^2 + eps) and scales
+    column j by w_j Sigmoid(g_tj).  To first order an error delta in o_t moves o_tj / r_t by
+    delta_j / r_t - o_tj (o_t . delta) / (d r_t^3), at most |delta|_inf (1 + |o_tj| / r_t) / r_t
+    (since |o_t|_1 <= d r_t), so the same tolerance carried through the gate is, per element,
+
+        bound_tj = tol * max|o_ref| * (1 + |o_tj| / r_t) / r_t * |w_j| Sigmoid(g_tj).
+
+    A token whose o is small next to the largest of its sequence carries the error at that larger relative size;
+    the bound follows it, which one number for the whole tensor cannot."""
+    o_plain_ref = np.asarray(o_plain_ref, dtype=np.float64)
+    g = np.asarray(gate, dtype=np.float64)
+    w = np.ones(o_plain_ref.shape[-1]) if weight is None else np.asarray(weight, dtype=np.float64)
+    ref = o_plain_ref / np.sqrt(np.mean(o_plain_ref ** 2, axis=-1, keepdims=True) + eps) * w / (1.0 + np.exp(-g))
+    worst = 0.0
+    for sl in slices:
+        op = o_plain_ref[sl]                                   # [tokens, dv]
+        r = np.sqrt(np.mean(op ** 2, axis=-1, keepdims=True) + eps)
+        bound = tol * np.abs(op).max() * (1.0 + np.abs(op) / r) / r * np.abs(w) / (1.0 + np.exp(-g[sl]))
+        err = np.abs(np.asarray(o_gated[sl], dtype=np.float64) - ref[sl])
+        worst = max(worst, float((err / np.maximum(bound, 1e-300)).max()))
+    return worst
+
+
 def oracle_prefill(d, scale=1.0):
     """Run the fp64 oracle on a dict produced by synth_inputs (any device)."""
     cu = None if d.get("cu_seqlens") is None else d["cu_seqlens"].cpu().numpy().astype(np.int64)

@@ -12,10 +12,22 @@ from helpers import o_slices, oracle_prefill, to_device, worst_slice_err
 
 pytestmark = pytest.mark.gpu
 
-# 2e-3 (bf16 inputs, fp32 outputs) plus the unit roundoff of bf16: 8 significant bits, so rounding
-# to nearest moves a value in [2^e, 2^(e+1)) by at most 2^(e-8), i.e. by at most 2^-8 max|ref| for
-# values no larger than max|ref|.
-TOL_BF16_OUT = 2e-3 + 2.0 ** -8
+# The stated 2e-3 is on the fp32 output.  Rounding to bf16 (8 significant bits, round to nearest even) moves a value
+# x by at most 2^-8 |x| (half a unit in the last place, the unit being at most 2^-7 |x|), so element by element
+#     |o_bf16 - o_ref| <= tol + 2^-8 (|o_ref| + tol),     tol = 2e-3 max|o_ref| of the (sequence, head):
+# the allowance for the rounding follows each element's own size instead of the largest one's.
+TOL_BF16 = 2e-3
+
+
+def bf16_out_excess(o16, o_ref, slices):
+    """Largest |o16 - ref| / (tol + 2^-8 (|ref| + tol)) over all elements; at most 1 when within the bound."""
+    worst = 0.0
+    for sl in slices:
+        ref = np.asarray(o_ref[sl], dtype=np.float64)
+        tol = TOL_BF16 * np.abs(ref).max()
+        bound = tol + 2.0 ** -8 * (np.abs(ref) + tol)
+        worst = max(worst, float((np.abs(np.asarray(o16[sl], dtype=np.float64) - ref) / bound).max()))
+    return worst
 
 
 def _prefill_both(x, **kw):
@@ -53,8 +65,9 @@ def test_prefill_bf16_output_is_the_rounded_fp32_output(case):
     B, T, H, _ = x["q"].shape
     cu = None if x.get("cu_seqlens") is None else x["cu_seqlens"].cpu().numpy()
     eo = worst_slice_err(o16.float().cpu().numpy(), o_ref, o_slices(B, H, cu))
-    print("bf16 output %s: err_o %.2e" % (case, eo))
-    assert eo <= TOL_BF16_OUT
+    excess = bf16_out_excess(o16.float().cpu().numpy(), o_ref, o_slices(B, H, cu))
+    print("bf16 output %s: err_o %.2e, error / element-wise bound %.3f" % (case, eo, excess))
+    assert excess <= 1.0
 
 
 def test_prefill_bf16_output_with_the_output_gate():
@@ -103,8 +116,9 @@ def test_decode_bf16_output_is_the_rounded_fp32_output(Tq):
     o_np = outs[0][0].float().cpu().numpy().reshape(N, Tq, H, d)
     err = max(np.max(np.abs(o_np[n, :, h] - o_ref[n, :, h])) / np.max(np.abs(o_ref[n, :, h]))
               for n in range(N) for h in range(H))
-    print("bf16 decode output Tq=%d: err_o %.2e" % (Tq, err))
-    assert err <= TOL_BF16_OUT
+    excess = bf16_out_excess(o_np, o_ref, [(n, slice(None), h) for n in range(N) for h in range(H)])
+    print("bf16 decode output Tq=%d: err_o %.2e, error / element-wise bound %.3f" % (Tq, err, excess))
+    assert excess <= 1.0
 
 
 def test_bf16_output_needs_bf16_inputs():

@@ -7,18 +7,17 @@ import torch
 
 import oracle
 import synth_inputs as si
-from helpers import o_slices, rel_err, state_slices, worst_slice_err
+from helpers import gated_error_ratio, o_slices, rel_err, state_slices, worst_slice_err
 
 pytestmark = pytest.mark.gpu
 
 TOL_BF16 = 2e-3   # stated tolerance for bf16 inputs
 TOL_F32 = 1e-5
-# After the output gate every token's o is divided by its own RMS, so what the metric sees is the
-# error of o relative to that token's magnitude, not to the largest o of the sequence: tokens whose
-# o is small (weak state, cancelling terms) carry the absolute error of the fp16 operand roundings
-# (unit roundoff 2^-11 = 4.9e-4 on each of the three factors of a term) at full relative size.
-# 20 unit roundoffs are allowed; measured 1e-3 ... 3e-3.
-TOL_GATED_BF16 = 1e-2
+# After the output gate every token's o is divided by its own RMS, so a single max-relative number over the
+# tensor no longer measures what the stated tolerance is about: the gated tests check every element against
+# the stated 2e-3 carried through the gate (helpers.gated_error_ratio, at most 1), and the plain metric, which
+# tokens with a small o dominate, against the stated figure itself (measured 6e-4 ... 1.1e-3).
+TOL_GATED_BF16 = 2e-3
 
 
 def _np(d, *names):
@@ -139,8 +138,9 @@ def test_prefill_output_gate(prologue):
     o_ref = oracle.epilogue.apply(o_plain, si.to_np32(og), w.numpy(), 1e-5)
     eo = worst_slice_err(o.cpu().numpy(), o_ref, o_slices(1, H, cu.numpy()))
     eh = worst_slice_err(hT.cpu().numpy(), h_ref, state_slices(len(lens), H))
-    print("output gate prefill prologue=%s: err_o %.2e err_hT %.2e" % (prologue, eo, eh))
-    assert eo <= TOL_GATED_BF16 and eh <= TOL_BF16
+    ratio = gated_error_ratio(o.cpu().numpy(), o_plain, si.to_np32(og), w.numpy(), 1e-5, o_slices(1, H, cu.numpy()), TOL_BF16)
+    print("output gate prefill prologue=%s: err_o %.2e err_hT %.2e, error / carried tolerance %.3f" % (prologue, eo, eh, ratio))
+    assert ratio <= 1.0 and eo <= TOL_GATED_BF16 and eh <= TOL_BF16
 
 
 @pytest.mark.parametrize("dtype,tol,d", [("f32", TOL_F32, 64), ("bf16", TOL_BF16, 128)])
@@ -188,6 +188,7 @@ def test_prefill_output_gate_on_a_long_sequence_with_few_pairs():
     (o, hT), (o2, hT2) = outs
     eo = worst_slice_err(o.cpu().numpy(), o_ref, o_slices(1, H))
     eh = worst_slice_err(hT.cpu().numpy(), h_ref, state_slices(1, H))
-    print("output gate, long sequence: err_o %.2e err_hT %.2e" % (eo, eh))
-    assert eo <= TOL_GATED_BF16 and eh <= TOL_BF16
+    ratio = gated_error_ratio(o.cpu().numpy(), o_plain, si.to_np32(og), w.numpy(), 1e-5, o_slices(1, H), TOL_BF16)
+    print("output gate, long sequence: err_o %.2e err_hT %.2e, error / carried tolerance %.3f" % (eo, eh, ratio))
+    assert ratio <= 1.0 and eo <= TOL_GATED_BF16 and eh <= TOL_BF16
     assert torch.equal(hT, hT2) and torch.equal(o, o2)
