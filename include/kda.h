@@ -223,9 +223,12 @@ typedef struct {
  * Fused output gate (Section 4): with a kda_epilogue the kernels replace each o (one vector of
  * dv values per token and head) by
  *     o <- Sigmoid(gate) * o / sqrt(mean_j o_j^2 + rms_eps) * norm_weight
- * in fp32 before they store it (`scale` is applied to o first).  The paper gives neither the
- * epsilon nor the shape of the learned RMSNorm weight: one vector of dv values shared by all
- * heads is taken (NULL = ones).  The gate's and the output's projections stay with the caller.
+ * in fp32 before they store it (`scale` is applied to o first; the prefill carries the factor
+ * norm_weight * Sigmoid(gate) from its per-chunk stage to its sequential stage as fp16, the decode
+ * kernel evaluates it in fp32).  The paper gives neither the epsilon nor the shape of the learned
+ * RMSNorm weight: one vector of dv values shared by all heads is taken (NULL = ones).  The gate's
+ * and the output's projections stay with the caller.  With the gate, few pairs and long sequences
+ * are not cut into time ranges (one sequential workgroup per pair).
  */
 typedef struct {
     float        rms_eps;      /* >= 0                                                       */
@@ -235,8 +238,8 @@ typedef struct {
 
 /*
  * Workspace sizes for kda_chunk_fwd_fused: as kda_chunk_fwd_workspace_size and
- * kda_chunk_fwd_min_workspace_size, plus, when `epilogue` is not NULL, room for the gate logits that
- * the per-chunk kernel re-lays for the sequential kernel (16 KiB per chunk and head held at once).
+ * kda_chunk_fwd_min_workspace_size, plus, when `epilogue` is not NULL, room for the gate factors that
+ * the per-chunk stage leaves for the sequential stage (16 KiB per chunk and head held at once).
  * With epilogue == NULL they equal the plain functions.  A fused call whose workspace is smaller
  * than the first figure still runs, in more segments.
  */

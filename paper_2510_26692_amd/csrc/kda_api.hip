@@ -1,6 +1,6 @@
 // C ABI of libkda: argument validation, error strings and dispatch to the
 // kernels.  Nothing here touches tensor data; every step of the path runs in
-// the kernels of kda_step.hip, kda_chunk_f32.hip, kda_prefill_fused.hip, kda_prefill_gated.hip and kda_chunk_bwd.hip.
+// the kernels of kda_step.hip, kda_chunk_f32.hip, kda_prefill_fused.hip and kda_chunk_bwd.hip.
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>

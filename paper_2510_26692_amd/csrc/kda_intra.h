@@ -186,7 +186,8 @@ struct IntraArgs {
     uint32_t epoch;                                  //           value of a raised flag
     RawParams raw;
     const uint16_t *out_gate;                        // fused output gate: logits [B,T,H,128] or NULL
-    uint8_t *gate_ws;                                //                    their slots
+    uint8_t *gate_ws;                                //   slots of the gate factors w_j Sigmoid(g_tj), fp16, kGateSlotBytes each
+    const float *gate_norm_w;                        //   RMSNorm weights [128] or NULL (= ones)
     uint32_t *status;                                // may be NULL
 };
 // One chunk of one (sequence, head): cl is the chunk index inside the time segment; cl < 0: nothing to do.
@@ -301,6 +302,47 @@ void kda_intra_items(uint8_t *lds, const IntraArgs &A, int count, ItemAt item_at
     const int64_t slot = prev.slot, row0 = prev.row0;
     const __amdgpu_buffer_rsrc_t out = slot_resource(ws + slot * (int64_t)kSlotBytes);
     (void)h;
+    // ---- output gate (fused epilogue): the chunk's gate factors go out in the accumulator order of the
+    // sequential stage, which reads them like any other part of the slot.  Done first thing in the second half
+    // of the chunk, where few registers are in use, and fenced off from the scheduler so that it stays there.
+    if (out_gate) {
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 ograw[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+            ograw[i] = rows_load16(rows_resource(out_gate + row0, row_bytes), tokv * row_pitch + 16 * cg);
+        }
+        // piece (token, 8 columns 8 cg ..) = column group q = cg % 4 of tile (token / 32, cg / 4): its
+        // first four columns belong to lane (token % 32, hh = 0), the other four to lane (.., hh = 1)
+        const __amdgpu_buffer_rsrc_t gout = __builtin_amdgcn_make_buffer_rsrc(
+            gate_ws + slot * (int64_t)kGateSlotBytes, 0, kGateSlotBytes, 0x00020000);
+        float gate_w[8];                                     // RMSNorm weights of this thread's 8 columns (the same in all four pieces)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gate_w[e] = A.gate_norm_w ? A.gate_norm_w[8 * (tid & 15) + e] : 1.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
+            const int base = ((tokv >> 5) * 4 + (cg >> 2)) * kGateTileBytes + ((cg & 3) >> 1) * 1024 + (tokv & 31) * 16 +
+                             (cg & 1) * 8;
+            // what leaves is the factor the gate multiplies the normalised o by, w_j Sigmoid(g_tj), as fp16 (it lies
+            // in (0, |w_j|); the 2^-11 of its rounding is a quarter of the tolerance and comes off the sequential
+            // stage's critical path, which would otherwise evaluate 32 exponentials per lane and chunk)
+            uint32_t f[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float g0, g1;
+                unpack_bf16x2(ograw[i][w], g0, g1);
+                f[w] = pack_h2(gate_w[2 * w] * __builtin_amdgcn_rcpf(1.f + fast_exp2(-g0 * kLog2e)),
+                               gate_w[2 * w + 1] * __builtin_amdgcn_rcpf(1.f + fast_exp2(-g1 * kLog2e)));
+            }
+            const u32x2 lo = {f[0], f[1]}, hi = {f[2], f[3]};
+            slot_store8<kPolicy>(gout, base, lo);
+            slot_store8<kPolicy>(gout, base + 32 * 16, hi);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
     // ---- L and Tril(A_qk) tiles of row R; fp16 V tile ----
     {
         // (L is kept transposed, sLT[column][row]: a lane's four rows of a column are contiguous, one
@@ -516,18 +558,6 @@ void kda_intra_items(uint8_t *lds, const IntraArgs &A, int count, ItemAt item_at
     const int h = cur.h, nv = cur.nv, row_bytes = cur.row_bytes;
     const int64_t slot = cur.slot, row0 = cur.row0;
     const __amdgpu_buffer_rsrc_t out = slot_resource(ws + slot * (int64_t)kSlotBytes);
-    // ---- output gate (fused epilogue): the chunk's gate logits are re-laid into the accumulator
-    // order of the sequential kernel, which reads them like any other part of the slot.  The loads
-    // go out first and the stores follow the kernel's own loads, so the copy hides in their latency.
-    u32x4 ograw[4];
-    if (out_gate) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
-            ograw[i] = rows_load16(rows_resource(out_gate + row0, row_bytes), tokv * row_pitch + 16 * cg);
-        }
-    }
-
     // ---- this item's inputs were fetched while the item before it was computed ----
     const float gscalar = bf16_bits_to_float((uint16_t)gscalar_raw);    // kScalar: log alpha of this lane's token
     const float beta_tok = bf16_bits_to_float((uint16_t)beta_raw);      // beta of token tid (threads 0..63)
@@ -536,21 +566,6 @@ void kda_intra_items(uint8_t *lds, const IntraArgs &A, int count, ItemAt item_at
         float b = beta_tok;
         if (kRaw) b = (tid < nv) ? __builtin_amdgcn_rcpf(1.f + fast_exp2(-b * kLog2e)) : 0.f;   // Sigmoid
         sBeta[tid] = b;
-    }
-    if (out_gate) {
-        // piece (token, 8 columns 8 cg ..) = column group q = cg % 4 of tile (token / 32, cg / 4): its
-        // first four columns belong to lane (token % 32, hh = 0), the other four to lane (.., hh = 1)
-        const __amdgpu_buffer_rsrc_t gout = __builtin_amdgcn_make_buffer_rsrc(
-            gate_ws + slot * (int64_t)kGateSlotBytes, 0, kGateSlotBytes, 0x00020000);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int u = tid + 256 * i, tokv = u >> 4, cg = u & 15;
-            const int base = ((tokv >> 5) * 4 + (cg >> 2)) * kGateTileBytes + ((cg & 3) >> 1) * 1024 + (tokv & 31) * 16 +
-                             (cg & 1) * 8;
-            const u32x2 lo = {ograw[i][0], ograw[i][1]}, hi = {ograw[i][2], ograw[i][3]};
-            slot_store8<kPolicy>(gout, base, lo);
-            slot_store8<kPolicy>(gout, base + 32 * 16, hi);
-        }
     }
     // kRaw: 1 / |q|, 1 / |k| of this lane's token (the four lanes g = 0..3 of a token hold 32 channels each)
     float invq = 1.f, invk = 1.f;

@@ -1,14 +1,12 @@
 // Host side of the matrix-core prefill (bf16 inputs, d_k = d_v = 128, C = 64): workspace plan, the
 // decision whether to cut the chunk axis into ranges, and the launches.  No kernel lives here; the
-// device code is in kda_prefill_fused.hip (every call but those with the output gate) and
-// kda_prefill_gated.hip.
+// device code is in kda_prefill_fused.hip.
 //
-// Nothing is allocated, no stream or event is created and the host never waits: a call is one or
-// two launches per time segment on the caller's stream (plus a small fill kernel for the flags).
+// Nothing is allocated, no stream or event is created and the host never waits: a call is one launch
+// per time segment on the caller's stream (plus a small fill kernel for the flags).
 #include <stdlib.h>
 
 #include "kda_prefill_fused.h"
-#include "kda_prefill_gated.h"
 
 namespace kda {
 
@@ -111,7 +109,7 @@ static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full, b
 {
     const int64_t maxc = max_chunks_per_seq(d);
     int64_t sc = maxc < 1 ? 1 : maxc;
-    if (sc > 65535) sc = 65535;                               // grid dimension limit of the gated path
+    if (sc > 65535) sc = 65535;                               // a segment holds at most 65 535 chunk indices (4.2 M tokens)
     if (!full) {
         const size_t streams = (size_t)d->num_seqs * d->heads;
         const size_t per_chunk_index = streams * (kSlotBytes + sizeof(uint32_t) + (gate ? kGateSlotBytes : 0));
@@ -230,28 +228,9 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     const int64_t streams = (int64_t)d->num_seqs * d->heads;
     const int64_t maxc = max_chunks_per_seq(d);
 
-    if (epi) {
-        // the output gate: two kernels per segment, one after the other
-        for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
-            GatedLaunch L{};
-            L.q = q16; L.k = k16; L.v = v16; L.log_alpha = g16; L.beta = b16; L.cu = cu;
-            L.state_in = (seg == 0) ? h0 : carry;
-            L.state_out = (plan.num_segments > 1 || hT) ? carry : nullptr;
-            L.o = o; L.ws = ws; L.gate_ws = base + plan.gate_offset; L.status = status;
-            L.gate = static_cast<const uint16_t *>(epi->gate); L.norm_w = epi->norm_weight; L.rms_eps = epi->rms_eps;
-            L.scale = d->scale; L.T = d->seqlen; L.seg_chunks = plan.seg_chunks; L.seg_index = seg;
-            const int64_t left = maxc - seg * plan.seg_chunks;
-            L.launch_chunks = left < plan.seg_chunks ? left : plan.seg_chunks;
-            L.H = d->heads; L.num_seqs = d->num_seqs; L.raw_inputs = pro != nullptr; L.out_bf16 = out_bf16; L.raw = raw;
-            const kda_status st = launch_prefill_gated(L, stream);
-            if (st != KDA_OK) return st;
-        }
-        return KDA_OK;
-    }
-
     // One launch per time segment, both stages as roles of one kernel.
     double ratio = 1.0;
-    const int parts = g_split ? split_parts(plan, d, cus, g_split, &ratio) : 1;
+    const int parts = (g_split && !epi) ? split_parts(plan, d, cus, g_split, &ratio) : 1;
     if (g_split_ratio > 0.0) ratio = g_split_ratio;
     int64_t part0_len = 0, part_len = 0;
     if (parts > 1) {
@@ -278,7 +257,11 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         a.split.E = reinterpret_cast<float *>(base + plan.split_offset + kSplitFlagBytes);
         a.split.Tm = a.split.E + kSplitMaxParts * pair_states;
         a.split.Bm = a.split.Tm + kSplitMaxParts * pair_states;
-        L.raw = pro != nullptr; L.scalar_gate = scalar_gate; L.out_bf16 = out_bf16;
+        L.raw = pro != nullptr; L.scalar_gate = scalar_gate; L.out_bf16 = out_bf16; L.gate = epi != nullptr;
+        if (epi) {
+            a.out_gate = static_cast<const uint16_t *>(epi->gate); a.gate_ws = base + plan.gate_offset;
+            a.norm_w = epi->norm_weight; a.rms_eps = epi->rms_eps;
+        }
         L.reset_flags = seg == 0;
         // (the counters of the time-split scan follow the slot flags: one fill clears both)
         L.num_flags = parts > 1 ? (int64_t)((plan.split_offset + kSplitFlagBytes - plan.flags_offset) / 4)

@@ -42,11 +42,16 @@ struct FusedArgs {
     int per_wg, window;             // per-chunk role: chunks per workgroup, and workgroups that share a run of window * per_wg chunks
     RawParams raw;
     SplitArgs split;
+    // output gate of Section 4 (kGate kernels only): o <- Sigmoid(g) * RMSNorm(o) * w
+    const uint16_t *out_gate;       // gate logits [B,T,H,dv] bf16
+    uint8_t *gate_ws;               // the same re-laid by the per-chunk role, kGateSlotBytes per slot
+    const float *norm_w;            // [dv] or NULL (= ones)
+    float rms_eps;
 };
 
 struct FusedLaunch {
     FusedArgs args;
-    bool raw, scalar_gate, out_bf16;
+    bool raw, scalar_gate, out_bf16, gate;
     bool reset_flags;               // clear num_flags words at args.ready and the status word first
     int64_t num_flags;
     bool reset_split;               // clear the counters of the time-split scan first (segments after the first)

@@ -16,7 +16,8 @@
 // (The wait is bounded anyway: see kda_scan4.h.)
 //
 // No stream, event or host synchronisation is involved, so the call can be captured into a graph,
-// and tools that run one kernel at a time see a single kernel.
+// and tools that run one kernel at a time see a single kernel.  The fused output gate of Section 4
+// (o <- Sigmoid(g) * RMSNorm(o) * w) is a variant of the same kernel.
 #include "kda_prefill_fused.h"
 
 #include "kda_scan4.h"
@@ -43,18 +44,22 @@ __device__ __forceinline__ int64_t item_index(int64_t wg, int t, int per_wg, int
     const int64_t w = wg / window, r = wg - w * window;
     return w * window * per_wg + (int64_t)t * window + r;
 }
-__device__ __forceinline__ IntraArgs intra_args(const FusedArgs &a)
+template <bool kGate> __device__ __forceinline__ IntraArgs intra_args(const FusedArgs &a)
 {
     return IntraArgs{a.q, a.k, a.v, a.log_alpha, a.beta, a.cu, a.ws, a.T, a.H, a.seg_chunks, a.seg_index, a.scale,
-                     a.ready, a.epoch, a.raw, nullptr, nullptr, a.status};
+                     a.ready, a.epoch, a.raw, kGate ? a.out_gate : nullptr, kGate ? a.gate_ws : nullptr,
+                     kGate ? a.norm_w : nullptr, a.status};
 }
 
-template <bool kRaw, bool kScalar, bool kOutBf16>
+// kGate: the output gate of Section 4; the per-chunk role leaves the chunk's gate factors beside its slot and the
+// scan role normalises O and applies them in registers (never together with the time split or the scalar gate).
+template <bool kRaw, bool kScalar, bool kOutBf16, bool kGate = false>
 __global__ __launch_bounds__(256, 2)
 void kda_prefill_kernel(const FusedArgs a)
 {
+    static_assert(!(kGate && kScalar), "no output gate on the scalar-gate entry point");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    if (a.split.parts > 1) {
+    if (!kGate && a.split.parts > 1) {
         // ---- time-split layout (few pairs): [pairs x (2 parts - 3) scan workgroups][per-chunk workgroups] ----
         const int nsw = 2 * a.split.parts - 3;
         const int64_t bid = blockIdx.x, nscan = a.pairs * nsw;
@@ -79,7 +84,7 @@ void kda_prefill_kernel(const FusedArgs a)
         // interleaves those and lets the last range follow.
         const int64_t first = a.split.parts - 1, part_len = a.split.part_len, part0_len = a.split.part0_len;
         const int64_t total = a.pairs * (int64_t)a.split.parts * part_len;
-        kda_intra_items<true, kRaw, kScalar>(lds, intra_args(a), a.per_wg, [&](int t) __attribute__((always_inline)) {
+        kda_intra_items<true, kRaw, kScalar>(lds, intra_args<kGate>(a), a.per_wg, [&](int t) __attribute__((always_inline)) {
             const int64_t i = item_index(bid - nscan, t, a.per_wg, a.window);
             IntraItem it = {0, 0, -1};
             if (i >= total) return it;
@@ -115,13 +120,15 @@ void kda_prefill_kernel(const FusedArgs a)
         const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
         const int64_t st_base = pair * (int64_t)(D * D) + 32 * wave + (lane & 31);
         const uint8_t *slot0 = a.ws + pair * a.seg_chunks * (int64_t)kSlotBytes;
-        scan4::kda_scan4_body<true, kOutBf16>(lds, slot0, (int64_t)kSlotBytes, a.state_in, a.state_out, a.o, st_base,
-                                              tok_base, len, a.H, c_begin, c_end, h, a.ready + pair * a.seg_chunks, a.epoch,
-                                              a.status, a.wait_limit);
+        const scan4::GateParams gate = {kGate ? a.gate_ws + pair * a.seg_chunks * (int64_t)kGateSlotBytes : nullptr, a.rms_eps};
+        scan4::kda_scan4_body<true, kOutBf16, kRoleFull, kGate>(lds, slot0, (int64_t)kSlotBytes, a.state_in, a.state_out,
+                                                                a.o, st_base, tok_base, len, a.H, c_begin, c_end, h,
+                                                                a.ready + pair * a.seg_chunks, a.epoch, a.status,
+                                                                a.wait_limit, false, gate);
     } else {
         // ---- per-chunk role: per_wg (chunk, sequence, head) items of this batch, chunk index first ----
         if (!a.producers) return;
-        kda_intra_items<true, kRaw, kScalar>(lds, intra_args(a), a.per_wg, [&](int t) __attribute__((always_inline)) {
+        kda_intra_items<true, kRaw, kScalar>(lds, intra_args<kGate>(a), a.per_wg, [&](int t) __attribute__((always_inline)) {
             const int64_t i = item_index(r - a.nb, t, a.per_wg, a.window);
             IntraItem it = {0, 0, -1};
             if (i >= batch_items) return it;
@@ -140,10 +147,10 @@ __global__ void kda_fused_fill_kernel(uint32_t *p, int64_t n, uint32_t value, ui
     if (i == 0) *one_more = value;
 }
 
-template <bool kRaw, bool kScalar, bool kOutBf16>
+template <bool kRaw, bool kScalar, bool kOutBf16, bool kGate = false>
 static bool reserve_one()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(kda_prefill_kernel<kRaw, kScalar, kOutBf16>),
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kda_prefill_kernel<kRaw, kScalar, kOutBf16, kGate>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, scan4::kLds) == hipSuccess;
 }
 
@@ -156,7 +163,9 @@ static bool reserve_fused_lds()
     if (done[dev]) return true;
     const bool ok = reserve_one<false, false, false>() && reserve_one<false, false, true>() &&
                     reserve_one<true, false, false>() && reserve_one<true, false, true>() &&
-                    reserve_one<false, true, false>() && reserve_one<false, true, true>();
+                    reserve_one<false, true, false>() && reserve_one<false, true, true>() &&
+                    reserve_one<false, false, false, true>() && reserve_one<false, false, true, true>() &&
+                    reserve_one<true, false, false, true>() && reserve_one<true, false, true, true>();
     if (!ok) (void)hipGetLastError();
     done[dev] = ok;
     return ok;
@@ -198,7 +207,11 @@ kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
     if (L.reset_flags)
         hipLaunchKernelGGL(kda_fused_fill_kernel, dim3((unsigned)((L.num_flags + 255) / 256 + 1)), dim3(256), 0, stream,
                            a.ready, L.num_flags, 0u, a.status);
-    auto kern = L.scalar_gate ? (L.out_bf16 ? kda_prefill_kernel<false, true, true> : kda_prefill_kernel<false, true, false>)
+    if (L.gate && (L.scalar_gate || a.split.parts > 1))
+        return fail(KDA_ERR_UNSUPPORTED, "the output gate runs neither with the scalar gate nor with the time split");
+    auto kern = L.gate ? (L.raw ? (L.out_bf16 ? kda_prefill_kernel<true, false, true, true> : kda_prefill_kernel<true, false, false, true>)
+                                : (L.out_bf16 ? kda_prefill_kernel<false, false, true, true> : kda_prefill_kernel<false, false, false, true>))
+                : L.scalar_gate ? (L.out_bf16 ? kda_prefill_kernel<false, true, true> : kda_prefill_kernel<false, true, false>)
                 : L.raw ? (L.out_bf16 ? kda_prefill_kernel<true, false, true> : kda_prefill_kernel<true, false, false>)
                         : (L.out_bf16 ? kda_prefill_kernel<false, false, true> : kda_prefill_kernel<false, false, false>);
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), scan4::kLds, stream, a);

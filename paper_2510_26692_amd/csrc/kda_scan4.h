@@ -50,6 +50,10 @@ constexpr int kBig = 16 * kFragBytes;                       // W, Gamma.Q or K^T
 constexpr int kSmall = 8 * kFragBytes;                      // Tril(A_qk), gamma^C (and the first bytes of U, unused)
 constexpr int kSmallRegions = 4 * kBig;                     // byte offset of the two small regions
 constexpr int kLds = kSmallRegions + 2 * kSmall;            // 81920
+// The tail of a small region, behind Tril(A_qk) and gamma^C, receives bytes nobody reads; while its step is being
+// worked on it carries the partial mean squares of the output gate: [token tile][wave][32 tokens] fp32.
+constexpr int kGateRed = kOffGc - kOffAqk + D * 4;          // 6656
+static_assert(kGateRed + 2 * 4 * 32 * 4 <= kSmall, "the partial sums fit the tail of the small region");
 static_assert(kOffQp == kBig && kOffKt == 2 * kBig && kOffAqk == 3 * kBig, "pieces follow the slot layout");
 static_assert(kOffAqk + kSmall <= kSlotBytes && kOffGc + D * 4 <= kOffAqk + kSmall, "the small piece stays inside the slot");
 static_assert(kLds <= 80 * 1024, "two workgroups must fit a compute unit");
@@ -166,13 +170,24 @@ __device__ __noinline__ bool wait_flag(const uint32_t *flag, uint32_t epoch, uin
 //   poisoned             start from NaN instead of state_in (the caller could not obtain the initial state)
 //   status               word that records a wait that ran out (the state is then poisoned with NaN, so
 //                        every later output of this (sequence, head) and its final state are NaN)
-template <bool kFlags, bool kOutBf16, int kRole = kRoleFull>
+//   kGate, gate           the output gate of Section 4 applied to O before it is stored:
+//                        o <- Sigmoid(g) * RMSNorm(o) * w, the mean square taken over the d_v values of a token
+//                        (the four waves of the workgroup); gate.factors: w_j Sigmoid(g_tj) as fp16 in accumulator
+//                        order, as the per-chunk role leaves them, kGateSlotBytes per chunk, this pair's first
+//                        chunk of the pass
+struct GateParams {
+    const uint8_t *factors;
+    float eps;
+};
+template <bool kFlags, bool kOutBf16, int kRole = kRoleFull, bool kGate = false>
 __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
                                                const float *state_in, float *state_out, void *o, int64_t st_base,
                                                int64_t tok_base, int64_t len, int H, int64_t c_begin, int64_t c_end,
                                                int h, const uint32_t *ready, uint32_t epoch, uint32_t *status,
-                                               uint64_t wait_limit, bool poisoned = false)
+                                               uint64_t wait_limit, bool poisoned = false,
+                                               const GateParams gate = GateParams{nullptr, 0.f})
 {
+    static_assert(!kGate || kRole == kRoleFull, "only a pass that writes outputs has a gate to apply");
     const int tid = threadIdx.x, lane = tid & 63;
     const int c = __builtin_amdgcn_readfirstlane(tid >> 6);       // the wave: column slice of S, V_new, O
     // The chain of steps is the critical path of the whole prefill, the per-chunk workgroups that share the
@@ -185,6 +200,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
     // vector-memory instructions per step, in issue order (see the loop)
     constexpr int nFlag = kFlags ? 1 : 0, nW = 4, nA = 2, nU = (kRole != kRoleT) ? 4 : 0;
     constexpr int nQ = kFull ? 4 : 0, nSt = kFull ? (kOutBf16 ? 4 : 8) : 0, nK = 4;
+    constexpr int G0 = kGate ? 4 : 0;                             // the step's own gate factors, first thing in phase V
     constexpr int G1 = nFlag + nW + nA + nU, G2 = nQ, G3 = nSt, G4 = nK;
 
     // own state tiles in accumulator order: S[t][j] = S(dk = 32 t + acc_row(j, hh), dv = 32 c + x)
@@ -205,7 +221,12 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
         // this wave's share of a piece: fragments 4 c .. 4 c + 3 of a big one, 2 c, 2 c + 1 of a small one
         const uint32_t voff_big = lane16 + (uint32_t)c * 4096, voff_small = lane16 + (uint32_t)c * 2048;
         const uint32_t voff_u = lane16 + (uint32_t)c * kUTileBytes;
+        // gate factors of this wave: tiles (P, c), P = 0, 1, two 16-byte units per lane and tile
+        const uint32_t voff_g = lane16 + (uint32_t)c * kGateTileBytes;
         bool gave_up = false;
+        auto gate_of = [&](int64_t rel) __attribute__((always_inline)) {       // clamped past the end
+            return gate.factors + ((rel < nsteps) ? rel : nsteps - 1) * (int64_t)kGateSlotBytes;
+        };
 
         auto slot_of = [&](int64_t rel) __attribute__((always_inline)) {       // clamped past the end
             return slot0 + ((rel < nsteps) ? rel : nsteps - 1) * slot_stride;
@@ -274,7 +295,8 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
         constexpr int LA = 4, RING = LA + 2;                     // operand fragments read ahead of the product that uses them
         // Vector-memory instructions are handed to the memory pipe one at a time between the matrix
         // products (a burst of them stalls the wave at issue, and the products behind it), in this order:
-        //   phase V  the flag of the step after next, then W, the small piece and U of the next step   (G1)
+        //   phase V  (gate: the factors of this step, G0,) the flag of the step after next, then W, the small piece and
+        //            U of the next step                                                                 (G1)
         //   phase O  Gamma.Q of the next step                                                          (G2)
         //   phase S  K^T of the next step (G4), then this step's output stores                         (G3)
         constexpr int kStores = nSt;
@@ -288,6 +310,9 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
             const uint8_t *ldsA = lds + kSmallRegions + sm * kSmall + lane16;
             const float *gc = reinterpret_cast<const float *>(lds + kSmallRegions + sm * kSmall + (kOffGc - kOffAqk)) + 4 * hh;
             const uint8_t *nxt = slot_of(rel + 1);
+            const uint8_t *gate_cur = kGate ? gate_of(rel) : nullptr;
+            u32x4 gr[4];                                         // kGate: gate factors of tiles (0, c), (1, c), two 16-byte units each
+            float *red = reinterpret_cast<float *>(lds + kSmallRegions + sm * kSmall + kGateRed);   // kGate: partial mean squares
             const uint32_t m0W = lds0 + (uint32_t)rN * kBig + (uint32_t)c * 4096;      // W of the next step
             const uint32_t m0Q = lds0 + (uint32_t)rW * kBig + (uint32_t)c * 4096;      // Gamma.Q of the next step (over this step's W)
             const uint32_t m0K = lds0 + (uint32_t)rQ * kBig + (uint32_t)c * 4096;      // K^T of the next step (over this step's Gamma.Q)
@@ -315,13 +340,15 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
                         for (int e = 0; e < 8; ++e) Sb[i / 2][e] = (_Float16)S[tau][8 * s + e];
                     }
                     av[P] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ring[i % RING], Sb[i / 2], av[P], 0, 0, 0);
-                    // G1, one instruction per slot
-                    if constexpr (i == 0) { if (kFlags) load_word(seen, 0u, flag2); }
-                    else if constexpr (i >= 1 && i <= 4) dma1(m0W + (i - 1) * 1024, voff_big, nxt + kOffWn + (i - 1) * 1024);
-                    else if constexpr (i >= 5 && i <= 6) dma1(m0A + (i - 5) * 1024, voff_small, nxt + kOffAqk + (i - 5) * 1024);
-                    else if constexpr (i >= 7 && i <= 10) {
+                    // G0 (this step's gate factors), then G1, one instruction per slot
+                    constexpr int j = i - G0;
+                    if constexpr (i < G0) load1(gr[i], voff_g, gate_cur + (i / 2) * 4 * kGateTileBytes + (i % 2) * 1024);
+                    else if constexpr (j == 0) { if (kFlags) load_word(seen, 0u, flag2); }
+                    else if constexpr (j >= 1 && j <= 4) dma1(m0W + (j - 1) * 1024, voff_big, nxt + kOffWn + (j - 1) * 1024);
+                    else if constexpr (j >= 5 && j <= 6) dma1(m0A + (j - 5) * 1024, voff_small, nxt + kOffAqk + (j - 5) * 1024);
+                    else if constexpr (j >= 7 && j <= 10) {
                         if (kRole != kRoleT)
-                            load1(ur[i - 7], voff_u, nxt + kOffU + ((i - 7) / 2) * 4 * kUTileBytes + ((i - 7) % 2) * 1024);
+                            load1(ur[j - 7], voff_u, nxt + kOffU + ((j - 7) / 2) * 4 * kUTileBytes + ((j - 7) % 2) * 1024);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 });
@@ -334,7 +361,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
                 for (int s = 0; s < 2; ++s)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) Vb[P][s][e] = (_Float16)av[P][8 * s + e];
-            phase_barrier<G3 + G4 + G1>();                       // Gamma.Q (and the small piece) of this step
+            phase_barrier<G3 + G4 + G0 + G1>();                  // Gamma.Q (and the small piece) of this step
 
             // ---- phase O: O^T[P] = S^T (Gamma.Q)(P)^T + V_new^T Tril(A_qk)(P, rho)^T; between the products the
             // state is scaled, S <- Diag(gamma^C) S (the products read the fp16 copy taken in phase V) ----
@@ -371,6 +398,37 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
 #pragma unroll
                 for (int i = 0; i < 16; ++i) scale_state(i / 4, i % 4);
             }
+            if (kGate) {
+                // A token's 128 outputs sit in two lanes of each of the four waves: lane-local sum of squares, the
+                // two lanes by a swap, the four waves through the unused tail of this step's small region (the
+                // barrier that ends the phase publishes it).
+#pragma unroll
+                for (int P = 0; P < 2; ++P) {
+                    float ssq = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) ssq = fmaf(ao[P][j], ao[P][j], ssq);
+                    ssq += __shfl_xor(ssq, 32);
+                    if (hh == 0) red[(P * 4 + c) * 32 + x] = ssq;
+                }
+            }
+            // O <- Sigmoid(g) * RMSNorm(O) * w on tile P, in place (phase S, before the tile is turned for the stores)
+            auto apply_gate = [&](const int P) __attribute__((always_inline)) {
+                const float tot = red[(P * 4 + 0) * 32 + x] + red[(P * 4 + 1) * 32 + x] + red[(P * 4 + 2) * 32 + x] +
+                                  red[(P * 4 + 3) * 32 + x];
+                const float rstd = __builtin_amdgcn_rsqf(tot * (1.0f / D) + gate.eps);
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int wd = 0; wd < 4; ++wd) {
+                        // word wd of unit `half`: columns 32 c + 8 q4 + 4 hh + 2 w, + 1 with q4 = 2 half + wd / 2, w = wd % 2
+                        // (through a scalar: a bit cast applied to a vector element directly reads element 0)
+                        const uint32_t w2 = gr[2 * P + half][wd];
+                        const h2 pr = __builtin_bit_cast(h2, w2);
+                        const int idx = 4 * (2 * half + (wd >> 1)) + 2 * (wd & 1);
+                        ao[P][idx] *= rstd * (float)pr[0];
+                        ao[P][idx + 1] *= rstd * (float)pr[1];
+                    }
+            };
             // O^T accumulator: lane (token 32 P + x, hh), registers 4 q .. 4 q + 3 = columns 32 c + 8 q + 4 hh + 0..3:
             // a token's 128 bytes of this wave's columns sit in two lanes, 16 bytes per register group.  Stored
             // that way, one instruction touches 32 cache lines and every line is written four times over; the
@@ -418,7 +476,9 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
             // bf16: store qq of tile P: token 32 P + x, columns 32 c + 8 (qq + 2 hh) + 0..7
             const uint32_t ol = kOutBf16 ? (uint32_t)x * o_rstride + (uint32_t)(32 * c + 16 * hh) * 2
                                          : (uint32_t)(x & ~3) * o_rstride + (uint32_t)(32 * c + 8 * (x & 3) + 4 * hh) * 4;
-            phase_barrier<G1 + G2 + G3>();                       // K^T of this step
+            // K^T of this step; with the gate also its factors, which were issued after the stores of the step before:
+            // those stores are then waited for as well
+            phase_barrier<kGate ? G1 + G2 : G1 + G2 + G3>();
 
             // ---- phase S: S += (Gamma^{i->C}.K)^T V_new (S is already scaled), slot i: tau = i % 4, (rho, s) = i / 4.
             // Slots 0..3 also issue K^T of the next step and turn output tile 0 into store order, 4..7 store it
@@ -434,6 +494,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
                     if constexpr (i + LA < 16) ring[(i + LA) % RING] = frag(i + LA);
                     S[tau] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ring[i % RING], Vb[rho][s], S[tau], 0, 0, 0);
                     if constexpr (i < 4) dma1(m0K + i * 1024, voff_big, nxt + kOffKt + i * 1024);      // G4
+                    if constexpr (kGate && (i == 0 || i == 4)) apply_gate(i / 4);
                     if constexpr (kFull && i < 8) prepare_out(i / 4, i % 4);
                     if constexpr (kFull && i >= 4 && i < 12) {                                          // G3
                         constexpr int P = (i - 4) / 4, k = (i - 4) % 4;
