@@ -410,6 +410,8 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
                     ssq += __shfl_xor(ssq, 32);
                     if (hh == 0) red[(P * 4 + c) * 32 + x] = ssq;
                 }
+                // (the barrier below waits for vector memory only: the LDS stores above are waited for here)
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
             // O <- Sigmoid(g) * RMSNorm(O) * w on tile P, in place (phase S, before the tile is turned for the stores)
             auto apply_gate = [&](const int P) __attribute__((always_inline)) {
