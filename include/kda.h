@@ -227,8 +227,7 @@ typedef struct {
  * norm_weight * Sigmoid(gate) from its per-chunk stage to its sequential stage as fp16, the decode
  * kernel evaluates it in fp32).  The paper gives neither the epsilon nor the shape of the learned
  * RMSNorm weight: one vector of dv values shared by all heads is taken (NULL = ones).  The gate's
- * and the output's projections stay with the caller.  With the gate, few pairs and long sequences
- * are not cut into time ranges (one sequential workgroup per pair).
+ * and the output's projections stay with the caller.
  */
 typedef struct {
     float        rms_eps;      /* >= 0                                                       */
@@ -285,7 +284,7 @@ kda_status kda_chunk_fwd_scalar_gate(const kda_dims *dims,
  * final state, and this returns KDA_ERR_LAUNCH.  If a state of the call ended
  * up not finite (an fp16 operand overflowed) or a key was beyond the domain
  * stated at kda_chunk_fwd it returns KDA_ERR_INVALID_ARG.  KDA_OK otherwise (also for
- * calls that keep no status word: fp32 inputs, and calls with the output gate).
+ * calls that keep no status word: fp32 inputs).
  */
 kda_status kda_chunk_fwd_check(const kda_dims *dims, const void *workspace, size_t workspace_bytes,
                                void *hip_stream);

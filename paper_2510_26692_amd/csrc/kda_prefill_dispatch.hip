@@ -50,7 +50,7 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
     p.flags_offset = p.carry_offset + carry;
     p.split_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
     // counters and states of the time-split scan, when the call qualifies for it
-    const bool split = !gate && streams <= (size_t)kSplitMaxPairs && sc >= kSplitMinChunks;
+    const bool split = streams <= (size_t)kSplitMaxPairs && sc >= kSplitMinChunks;
     p.total_bytes = p.split_offset + (split ? kSplitFlagBytes + 3 * (size_t)kSplitMaxParts * carry : 0);
     p.gate_offset = 0;
     if (gate) {
@@ -166,7 +166,7 @@ kda_status chunk_mfma_plan(const kda_dims *d, size_t workspace_bytes, bool gate,
     const int cus = compute_units();
     if (cus <= 0) return fail(KDA_ERR_LAUNCH, "cannot query the device");
     double ratio = 1.0;
-    const int parts = (g_split && !gate) ? split_parts(plan, d, cus, g_split, &ratio) : 1;
+    const int parts = g_split ? split_parts(plan, d, cus, g_split, &ratio) : 1;
     if (g_split_ratio > 0.0) ratio = g_split_ratio;
     out[0] = plan.seg_chunks; out[1] = plan.num_segments; out[2] = parts; out[3] = 0; out[4] = 0;
     if (parts > 1) {
@@ -230,7 +230,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
 
     // One launch per time segment, both stages as roles of one kernel.
     double ratio = 1.0;
-    const int parts = (g_split && !epi) ? split_parts(plan, d, cus, g_split, &ratio) : 1;
+    const int parts = g_split ? split_parts(plan, d, cus, g_split, &ratio) : 1;
     if (g_split_ratio > 0.0) ratio = g_split_ratio;
     int64_t part0_len = 0, part_len = 0;
     if (parts > 1) {

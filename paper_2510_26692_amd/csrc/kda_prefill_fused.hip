@@ -52,14 +52,14 @@ template <bool kGate> __device__ __forceinline__ IntraArgs intra_args(const Fuse
 }
 
 // kGate: the output gate of Section 4; the per-chunk role leaves the chunk's gate factors beside its slot and the
-// scan role normalises O and applies them in registers (never together with the time split or the scalar gate).
+// scan role normalises O and applies them in registers (not offered on the scalar-gate entry point).
 template <bool kRaw, bool kScalar, bool kOutBf16, bool kGate = false>
 __global__ __launch_bounds__(256, 2)
 void kda_prefill_kernel(const FusedArgs a)
 {
     static_assert(!(kGate && kScalar), "no output gate on the scalar-gate entry point");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    if (!kGate && a.split.parts > 1) {
+    if (a.split.parts > 1) {
         // ---- time-split layout (few pairs): [pairs x (2 parts - 3) scan workgroups][per-chunk workgroups] ----
         const int nsw = 2 * a.split.parts - 3;
         const int64_t bid = blockIdx.x, nscan = a.pairs * nsw;
@@ -74,9 +74,11 @@ void kda_prefill_kernel(const FusedArgs a)
             int64_t nchunks = (len + kChunk - 1) / kChunk - cbase;
             if (nchunks < 0) nchunks = 0;
             if (nchunks > a.seg_chunks) nchunks = a.seg_chunks;
-            scan4::split_role<kOutBf16>(lds, a.split, a.ws + pair * a.seg_chunks * (int64_t)kSlotBytes, a.ready + pair * a.seg_chunks,
-                                        a.state_in, a.state_out, a.o, pair, a.pairs, y, tok_base, len, a.H, h, cbase, nchunks,
-                                        a.epoch, a.status, a.wait_limit);
+            scan4::split_role<kOutBf16, kGate>(lds, a.split, a.ws + pair * a.seg_chunks * (int64_t)kSlotBytes,
+                                               a.ready + pair * a.seg_chunks, a.state_in, a.state_out, a.o, pair, a.pairs, y,
+                                               tok_base, len, a.H, h, cbase, nchunks, a.epoch, a.status, a.wait_limit,
+                                               kGate ? a.gate_ws + pair * a.seg_chunks * (int64_t)kGateSlotBytes : nullptr,
+                                               a.rms_eps);
             return;
         }
         if (!a.producers) return;
@@ -207,8 +209,8 @@ kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
     if (L.reset_flags)
         hipLaunchKernelGGL(kda_fused_fill_kernel, dim3((unsigned)((L.num_flags + 255) / 256 + 1)), dim3(256), 0, stream,
                            a.ready, L.num_flags, 0u, a.status);
-    if (L.gate && (L.scalar_gate || a.split.parts > 1))
-        return fail(KDA_ERR_UNSUPPORTED, "the output gate runs neither with the scalar gate nor with the time split");
+    if (L.gate && L.scalar_gate)
+        return fail(KDA_ERR_UNSUPPORTED, "the scalar-gate entry point has no output gate");
     auto kern = L.gate ? (L.raw ? (L.out_bf16 ? kda_prefill_kernel<true, false, true, true> : kda_prefill_kernel<true, false, false, true>)
                                 : (L.out_bf16 ? kda_prefill_kernel<false, false, true, true> : kda_prefill_kernel<false, false, false, true>))
                 : L.scalar_gate ? (L.out_bf16 ? kda_prefill_kernel<false, true, true> : kda_prefill_kernel<false, true, false>)

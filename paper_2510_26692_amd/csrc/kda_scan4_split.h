@@ -112,11 +112,14 @@ __device__ __forceinline__ bool fold_slices(float *sE, float *E, const float *Tm
 // One workgroup (256 threads) of the time-split scan: pair `pair` (sequence n, head h), role index y in
 // [0, 2 parts - 3).  nchunks: chunk indices of this pair inside the launch's time segment; ws_pair / ready_pair:
 // the pair's first slot and flag in the segment; cbase: the segment's first chunk index in the sequence.
-template <bool kOutBf16>
+// kGate: the passes that write outputs apply the output gate; gate_pair: the pair's first slot of gate factors, eps: of
+// the RMSNorm (see kda_scan4_body).
+template <bool kOutBf16, bool kGate = false>
 __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, const uint8_t *ws_pair, const uint32_t *ready_pair,
                                            const float *h0, float *state_final, void *o, int64_t pair, int64_t pairs, int y,
                                            int64_t tok_base, int64_t len, int H, int h, int64_t cbase, int64_t nchunks,
-                                           uint32_t epoch, uint32_t *status, uint64_t wait_limit)
+                                           uint32_t epoch, uint32_t *status, uint64_t wait_limit,
+                                           const uint8_t *gate_pair = nullptr, float gate_eps = 0.f)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int parts = sp.parts;
@@ -139,7 +142,11 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
         int64_t c_end = c_begin + ((mid == 0) ? sp.part0_len : sp.part_len);
         if (c_begin > nchunks) c_begin = nchunks;
         if (c_end > nchunks) c_end = nchunks;
-        if (kind == kRoleFull) KDA_SCAN4_PART(kRoleFull);
+        if (kind == kRoleFull)
+            kda_scan4_body<true, kOutBf16, kRoleFull, kGate>(
+                lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, state_in, state_out, o, st_base, tok_base,
+                len, H, cbase + c_begin, cbase + c_end, h, ready_pair + c_begin, epoch, status, wait_limit, false,
+                GateParams{kGate ? gate_pair + c_begin * (int64_t)kGateSlotBytes : nullptr, gate_eps});
         else if (kind == kRoleT) KDA_SCAN4_PART(kRoleT);
         else KDA_SCAN4_PART(kRoleB);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
@@ -176,9 +183,10 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
         // (if the range's initial state never arrived, the scan starts from NaN: see kda_scan4_body's `poisoned`)
         const bool poisoned = second_ok == 0;
         if (poisoned) state_in = nullptr;
-        kda_scan4_body<true, kOutBf16, kRoleFull>(lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, state_in,
-                                                  state_out, o, st_base, tok_base, len, H, cbase + c_begin, cbase + c_end, h,
-                                                  ready_pair + c_begin, epoch, status, wait_limit, poisoned);
+        kda_scan4_body<true, kOutBf16, kRoleFull, kGate>(
+            lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, state_in, state_out, o, st_base, tok_base, len, H,
+            cbase + c_begin, cbase + c_end, h, ready_pair + c_begin, epoch, status, wait_limit, poisoned,
+            GateParams{kGate ? gate_pair + c_begin * (int64_t)kGateSlotBytes : nullptr, gate_eps});
     }
 #undef KDA_SCAN4_PART
 }
