@@ -656,7 +656,10 @@ void kda_intra_items(uint8_t *lds, const IntraArgs &A, int count, ItemAt item_at
                 if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0)
                     __hip_atomic_fetch_or(status, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            res_kk[R] = akk; res_qk[R] = aqk;
+            // (written through constant indices: an array indexed by the wave number would be placed in scratch memory)
+#pragma unroll
+            for (int I = 0; I < 4; ++I)
+                if (I == R) { res_kk[I] = akk; res_qk[I] = aqk; }
         }
         __syncthreads();                                                           // B3 (colS, sG visible)
 #pragma unroll
@@ -953,7 +956,10 @@ void kda_intra_items(uint8_t *lds, const IntraArgs &A, int count, ItemAt item_at
             if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0)
                 __hip_atomic_fetch_or(status, 4u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        res_kk[R] = akk; res_qk[R] = aqk;
+        // (written through constant indices: an array indexed by the wave number would be placed in scratch memory)
+#pragma unroll
+            for (int I = 0; I < 4; ++I)
+                if (I == R) { res_kk[I] = akk; res_qk[I] = aqk; }
     }
     __syncthreads();                                                               // B3 (colS visible)
 #pragma unroll
