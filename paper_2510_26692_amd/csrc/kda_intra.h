@@ -912,9 +912,18 @@ void kda_intra_items(uint8_t *lds, const IntraArgs &A, int count, ItemAt item_at
                 while (bits) {
                     const int e = __builtin_ctz(bits);
                     bits &= bits - 1;
-                    float Ge = G[ks * 8];
-#pragma unroll
-                    for (int z = 1; z < 8; ++z) Ge = (e == z) ? G[ks * 8 + z] : Ge;
+                    // (the running sum of the slot's channel is formed again from the input: holding all 32 sums up to here
+                    // for the sake of this rare path would keep them in registers across the operand loop, the tightest
+                    // point of the kernel; only differences of it are used, so the row shift is not needed)
+                    float Ge = bf16_bits_to_float(rows_load2(rows_resource(log_alpha + row0, row_bytes),
+                                                             tok * row_pitch + 16 * g + 64 * ks + 2 * e));
+                    if (kRaw) {
+                        const float be = raw.dt_bias ? raw.dt_bias[h * D + 32 * ks + 8 * g + e] : 0.f;
+                        Ge = (tok < nv) ? log2_alpha_from_gate(Ge + be, a_scale) : 0.f;
+                    } else {
+                        Ge *= kLog2e;
+                    }
+                    Ge += row_shr<1>(Ge); Ge += row_shr<2>(Ge); Ge += row_shr<4>(Ge); Ge += row_shr<8>(Ge);
                     // (k and q of the slot are read again: keeping the raw inputs in registers up to here for
                     // the sake of this rare path would cost the common one 24 registers at its tightest point)
                     const int woff = tok * row_pitch + 16 * g + 64 * ks + 4 * (e >> 1);

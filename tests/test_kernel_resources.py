@@ -29,11 +29,10 @@ def test_report_covers_the_kernels_of_the_hot_path(resources):
     assert _kernels(resources, "kda_step_kernel") and _kernels(resources, "kda_fused_fill_kernel")
 
 
-def test_prefill_kernels_of_the_bench_workloads_use_no_scratch(resources):
-    # template arguments <kRaw, kScalar, kOutBf16, kGate>: everything but the raw-input variants
-    plain = _kernels(resources, "kda_prefill_kernelILb0E")
-    assert len(plain) == 6
-    for name, r in plain.items():
+def test_prefill_kernels_use_no_scratch_outside_the_gated_variants(resources):
+    # template arguments <kRaw, kScalar, kOutBf16, kGate>
+    every = _kernels(resources, "kda_prefill_kernel")
+    for name, r in every.items():
         gate = name.endswith("Lb1EEEvNS0_9FusedArgsE")
         assert r["VGPRs"] <= 256 and r["Occupancy [waves/SIMD]"] >= 2, (name, r)
         if not gate:
