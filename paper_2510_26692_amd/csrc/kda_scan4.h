@@ -398,25 +398,32 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
 #pragma unroll
                 for (int i = 0; i < 16; ++i) scale_state(i / 4, i % 4);
             }
+            // (the lane number is formed afresh where the gate needs it: carried in a register across the loop it was
+            // the one value too many, and its reload from scratch memory waited for every load in flight, once per step)
+            auto lane_now = [&]() __attribute__((always_inline)) {
+                return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+            };
             if (kGate) {
                 // A token's 128 outputs sit in two lanes of each of the four waves: lane-local sum of squares, the
                 // two lanes by a swap, the four waves through the unused tail of this step's small region (the
                 // barrier that ends the phase publishes it).
+                const int ln = lane_now();
 #pragma unroll
                 for (int P = 0; P < 2; ++P) {
                     float ssq = 0.f;
 #pragma unroll
                     for (int j = 0; j < 16; ++j) ssq = fmaf(ao[P][j], ao[P][j], ssq);
                     ssq += __shfl_xor(ssq, 32);
-                    if (hh == 0) red[(P * 4 + c) * 32 + x] = ssq;
+                    if (ln < 32) red[(P * 4 + c) * 32 + ln] = ssq;
                 }
                 // (the barrier below waits for vector memory only: the LDS stores above are waited for here)
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
             // O <- Sigmoid(g) * RMSNorm(O) * w on tile P, in place (phase S, before the tile is turned for the stores)
             auto apply_gate = [&](const int P) __attribute__((always_inline)) {
-                const float tot = red[(P * 4 + 0) * 32 + x] + red[(P * 4 + 1) * 32 + x] + red[(P * 4 + 2) * 32 + x] +
-                                  red[(P * 4 + 3) * 32 + x];
+                const int xl = lane_now() & 31;
+                const float tot = red[(P * 4 + 0) * 32 + xl] + red[(P * 4 + 1) * 32 + xl] + red[(P * 4 + 2) * 32 + xl] +
+                                  red[(P * 4 + 3) * 32 + xl];
                 const float rstd = __builtin_amdgcn_rsqf(tot * (1.0f / D) + gate.eps);
 #pragma unroll
                 for (int half = 0; half < 2; ++half)
