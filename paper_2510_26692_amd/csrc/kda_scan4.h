@@ -312,7 +312,7 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
             const uint8_t *nxt = slot_of(rel + 1);
             const uint8_t *gate_cur = kGate ? gate_of(rel) : nullptr;
             u32x4 gr[4];                                         // kGate: gate factors of tiles (0, c), (1, c), two 16-byte units each
-            float *red = reinterpret_cast<float *>(lds + kSmallRegions + sm * kSmall + kGateRed);   // kGate: partial mean squares
+            float *red = reinterpret_cast<float *>(lds + kSmallRegions + sm * kSmall + kGateRed);   // idle tail of the small region: kGate's partial mean squares, kRoleT's flags
             const uint32_t m0W = lds0 + (uint32_t)rN * kBig + (uint32_t)c * 4096;      // W of the next step
             const uint32_t m0Q = lds0 + (uint32_t)rW * kBig + (uint32_t)c * 4096;      // Gamma.Q of the next step (over this step's W)
             const uint32_t m0K = lds0 + (uint32_t)rQ * kBig + (uint32_t)c * 4096;      // K^T of the next step (over this step's Gamma.Q)
@@ -516,10 +516,34 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
                 });
             }
 
+            // kRoleT, every eighth step: has this wave's slice of the transition vanished, bit for bit?  Decay takes a
+            // range's transition to exact zero within a few chunks (S is scaled by gamma^C every step and what the
+            // products add is formed from it), and zero stays zero under every further step, so the rest of the range
+            // need not be walked.  Every wave still loads its share of the operands for the others, so the four
+            // waves leave together: flags through the idle tail of this step's small region.
+            const bool probe = kRole == kRoleT && (rel & 7) == 7;
+            if (probe) {
+                uint32_t bits = 0;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) bits |= __float_as_uint(S[t][j]);
+                const bool zero = __builtin_amdgcn_ballot_w64((bits & 0x7fffffffu) != 0) == 0;
+                if (lane == 0) reinterpret_cast<uint32_t *>(red)[c] = zero ? 1u : 0u;
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+
             // ---- the next step's W and U are here: take U, note whether the flag read in phase V was up ----
             phase_barrier<G2 + G3 + G4>();
             take_u();
             if (kFlags) next_ok = (uint32_t)__builtin_amdgcn_readfirstlane((int)seen) == epoch;
+            if (probe) {
+                const uint32_t *zf = reinterpret_cast<const uint32_t *>(red);
+                const bool all_zero = (zf[0] & zf[1] & zf[2] & zf[3]) != 0;
+                // (nobody's next loads may land on the flags before everybody has read them)
+                __builtin_amdgcn_s_barrier();
+                if (all_zero) break;                             // the same answer in every thread of the workgroup
+            }
         }
         // the loads issued for a step that does not exist (clamped to the last slot) must not land after the
         // workgroup has given its LDS back
