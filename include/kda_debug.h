@@ -15,8 +15,12 @@ extern "C" {
 /*
  * 0 keeps the sequential stage of the matrix-core prefill to one workgroup per (sequence, head);
  * 1 (default) lets calls with few pairs and long sequences cut the chunk axis into ranges that
- * several workgroups walk at the same time (the chunk recurrence of Section 3.1 is affine in the
- * state, S_out = T S_in + B, so a range's T and B can be formed before its initial state is known).
+ * several workgroups walk at the same time.  The chunk recurrence of Section 3.1 is affine in the
+ * state, S_out = T S_in + B, and decay makes T vanish: where the transition of the last 32 chunks of
+ * a range is exactly zero in fp32, the state at the range's end is the offset of those chunks alone
+ * and the next range starts after 32 steps (the short way).  A (sequence, head) for which some range
+ * fails that test forms T and B of whole ranges and chains the range states through them (the
+ * general way: two ranges' time instead of one).
  * Results agree within rounding, not bit for bit.  With 1 the library estimates whether, and into
  * how many ranges, a call is worth splitting; a value of 3..8 takes that many ranges whatever the
  * estimate says (still lowered to what the device and the sequence length allow; calls with fewer
@@ -45,6 +49,15 @@ void kda_debug_set_wait_limit(unsigned long long ticks);
  */
 kda_status kda_debug_chunk_fwd_plan(const kda_dims *dims, size_t workspace_bytes, int output_gate,
                                     int64_t out[5]);
+
+/*
+ * The raw status word that a bf16 prefill call left in `workspace` (same dims, workspace and size as
+ * that call), after waiting for `hip_stream`.  Bits 1, 2, 4: the failures kda_chunk_fwd_check reports.
+ * Bits 256 and 512 report, for a call whose scan was split into ranges, that some (sequence, head)
+ * of any of its time segments took the short way (256) / the general way (512); no failure.
+ */
+kda_status kda_debug_chunk_fwd_status(const kda_dims *dims, const void *workspace, size_t workspace_bytes,
+                                      void *hip_stream, unsigned *word);
 
 /*
  * The device's own rates, for reading a roofline fraction against what this device delivers beside its

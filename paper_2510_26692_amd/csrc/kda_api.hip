@@ -64,6 +64,15 @@ static double split_ratio_default()
     return (r >= 0.2 && r <= 1.0) ? r : 0.0;
 }
 double g_split_ratio = split_ratio_default();
+// development switch: chunks at a range's end that the time-split scan tests for a vanished transition
+// (-1 = chosen per call, 0 = not tried)
+static int split_tail_default()
+{
+    const char *e = getenv("KDA_PREFILL_SPLIT_TAIL");
+    const int t = e ? atoi(e) : -1;
+    return (e && t >= 0 && t <= 4096) ? t : -1;
+}
+int g_split_tail = split_tail_default();
 int g_producers = 1;                      // 0: the per-chunk role of the one-kernel prefill does nothing
 uint64_t g_wait_limit = 200000000ull;     // ticks of the 100 MHz wall clock a scan workgroup waits for a slot: two seconds
 
@@ -384,6 +393,25 @@ kda_status kda_chunk_fwd_check(const kda_dims *d, const void *workspace, size_t 
     if (word & 2u)
         return fail(KDA_ERR_INVALID_ARG, "a state left the range of the fp16 matrix-core operands (status %u): inputs outside "
                     "the documented domain; the affected outputs are Inf or NaN", word);
+    return KDA_OK;
+}
+
+kda_status kda_debug_chunk_fwd_status(const kda_dims *d, const void *workspace, size_t workspace_bytes,
+                                      void *hip_stream, unsigned *word)
+{
+    g_last_error[0] = 0;
+    if (!d || !workspace || !word) return fail(KDA_ERR_INVALID_ARG, "dims, workspace or word is NULL");
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "stream: %s", hipGetErrorString(e));
+    if (d->chunk != kChunk || check_dims(d, d->num_seqs != d->batch) != KDA_OK) return KDA_ERR_INVALID_ARG;
+    if (!mfma_path(d) || chunk_mfma_workspace_size(d, true, false) == 0 ||
+        workspace_bytes < chunk_mfma_workspace_size(d, true, false))
+        return fail(KDA_ERR_UNSUPPORTED, "this call keeps no status word");
+    uint32_t w = 0;
+    e = hipMemcpy(&w, static_cast<const uint8_t *>(workspace) + chunk_mfma_status_offset(d, workspace_bytes), sizeof(w),
+                  hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "status read: %s", hipGetErrorString(e));
+    *word = w;
     return KDA_OK;
 }
 

@@ -66,8 +66,10 @@ constexpr int frag_aqk(int rr, int ri, int s) { return (rr + ri) * 2 + s; }   //
 constexpr int kSplitMaxParts = 8;
 constexpr int kSplitMaxPairs = 42;
 constexpr int kSplitMinChunks = 24;
-constexpr size_t kSplitFlagBytes = 4096;     // 24 u32 counters per pair, ahead of the states
-static_assert((size_t)kSplitMaxPairs * 24 * 4 <= kSplitFlagBytes, "every pair's counters must fit the area");
+constexpr int kSplitTail = 32;               // chunks at a range's end over which its transition is expected to vanish
+constexpr int kSplitMinTail = 16;            // ranges shorter than this do not try
+constexpr size_t kSplitFlagBytes = 8192;     // 32 u32 words per pair, ahead of the states
+static_assert((size_t)kSplitMaxPairs * 32 * 4 <= kSplitFlagBytes, "every pair's words must fit the area");
 
 // Geometry of one launch pair: `seg_chunks` chunk indices of every sequence.
 struct SegPlan {

@@ -12,6 +12,7 @@ namespace kda {
 
 extern int g_split;            // diagnostics switches owned by kda_api.hip (see kda_debug.h)
 extern double g_split_ratio;
+extern int g_split_tail;
 extern int g_producers;
 extern uint64_t g_wait_limit;
 
@@ -60,48 +61,81 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
     return p;
 }
 
-// Number of ranges for the time-split scan (1 = plain scan).  Every workgroup of either stage takes
-// half a compute unit; a split launch keeps 2 parts - 3 such slots per pair busy with the scan, at
-// most three eighths of all slots, so that the per-chunk stage, the larger half of the work, keeps
-// the rest.  Among the admissible numbers the one with the smallest estimated duration is taken,
-// the plain scan included.  The estimate (microseconds, measured on MI355X with both stages sharing
-// the compute units): a step of the scan 3.0, a chunk of the per-chunk stage 17 on one slot, the
-// fold and the extra start-up of a split launch 60 + 12 per middle range.  The first phase needs
-// the first parts - 1 ranges produced, the last range one more phase after everything before it.
+// How the time-split scan cuts a segment's chunk axis: parts = 1 means the plain scan.
+struct SplitCut {
+    int parts;
+    int64_t part0_len, part_len;   // chunk indices of the first range and of each other one
+    int64_t tail;                  // chunks at a range's end tested for a vanished transition; 0: not tried
+};
+
+// Every workgroup of either stage takes half a compute unit; a split launch starts 2 parts - 1 scan
+// workgroups per pair, at most half of all slots, of which `parts` per pair stay for the length of a
+// range on the short way (the others leave after the tail of one), at most three eighths of all
+// slots, so that the per-chunk stage, the larger half of the work, keeps the rest.  Among the
+// admissible numbers of ranges the one with the smallest estimated duration is taken, the plain scan
+// included.  The estimates are in microseconds, fitted to measurements on MI355X with both stages
+// sharing the compute units; a step of the scan takes 3.0.
+//   Ranges of at least kSplitMinTail chunks try the short way: the tails (half a range, within
+// kSplitMinTail .. kSplitTail chunks) are produced and walked first, then all ranges go side by side.
+// With all slots busy a chunk of the per-chunk stage costs 21.2 on one slot, and a scan workgroup,
+// which mostly waits, takes a quarter of a slot from that stage.  The per-chunk stage sets the pace as
+// long as the chain of scan steps stays under half its time; a longer chain falls behind now and then
+// and finishes up to a quarter later (fitted), and a chain longer than that is the duration.  Half the
+// time the tails take to produce comes on top.  (The host cannot know whether the data lets the
+// transitions vanish; the estimate assumes it does.)
+//   Shorter ranges leave no room for a transition to vanish and take the general way at once: two
+// phases, the first range shorter by the ratio of a pass that writes no output to the full scan (0.7)
+// when the scan, not the per-chunk stage, sets the pace of the first phase; a chunk of the per-chunk
+// stage 17 on one slot of a device that is not full, the fold and the extra start-up 60 + 12 per
+// middle range.
 // forced = 3..8: the largest admissible number up to `forced`, whatever the estimate says.
-static int split_parts(const SegPlan &plan, const kda_dims *d, int cus, int forced, double *first_ratio)
+static SplitCut split_cut(const SegPlan &plan, const kda_dims *d, int cus, int forced)
 {
-    *first_ratio = 1.0;
+    SplitCut cut = {1, 0, 0, 0};
     int64_t maxc = max_chunks_per_seq(d);                    // chunks one launch walks
     if (maxc > plan.seg_chunks) maxc = plan.seg_chunks;
     const int64_t pairs = (int64_t)d->num_seqs * d->heads;
     const int64_t slots = 2 * (int64_t)cus;
-    if (pairs > kSplitMaxPairs || maxc < kSplitMinChunks || pairs >= slots) return 1;
-    const double step = 3.0, item = 17.0;
+    if (pairs > kSplitMaxPairs || maxc < kSplitMinChunks || pairs >= slots) return cut;
+    const double step = 3.0, item = 17.0, item_full = 21.2;
     const double items = (double)pairs * (double)maxc;
     const double t_scan = (double)maxc * step, t_intra1 = items * item / (double)(slots - pairs);
-    double best = t_scan > t_intra1 ? t_scan : t_intra1;
-    int parts = 1;
+    double best = t_scan > t_intra1 ? t_scan : t_intra1, ratio = 1.0;
     for (int p = 3; p <= kSplitMaxParts; ++p) {
         const int64_t len = (maxc + p - 1) / p;
-        if (pairs * (2 * p - 3) * 8 > slots * 3 || len < 8) continue;
+        if (pairs * (2 * p - 1) * 2 > slots || pairs * p * 8 > slots * 3 || len < 8) continue;
+        const bool try_short = len >= kSplitMinTail;
+        int64_t tail = 0;
         const double phase = (double)len * step;
-        const double t_intra = items * item / (double)(slots - pairs * (2 * p - 3));
-        const double fed = t_intra * (double)(p - 1) / (double)p;
-        // The first range is walked by the full scan, the others by passes that write no output and
-        // fetch less, about 0.7 of its time per step: when the scan, not the per-chunk stage, sets the
-        // pace of the first phase, the first range is made shorter by that ratio.
-        const double ratio = (phase >= 1.5 * fed) ? 0.7 : 1.0;
-        if (forced >= 3) {
-            if (p <= forced) { parts = p; *first_ratio = ratio; }
-            continue;
+        double t, r = 1.0;
+        if (try_short) {
+            tail = len / 2 < kSplitMinTail ? kSplitMinTail : len / 2 > kSplitTail ? kSplitTail : len / 2;
+            const double t_tails = (double)(p - 1) * (double)tail * (double)pairs * item_full / (double)(slots - pairs * (2 * p - 1));
+            const double t_intra = items * item_full / ((double)slots - 0.25 * (double)(pairs * p));
+            const double chain = t_tails + (double)tail * step + phase;
+            double behind = chain / t_intra - 0.5;
+            behind = behind < 0.0 ? 0.0 : behind > 0.5 ? 0.5 : behind;
+            const double paced = t_intra * (1.0 + 0.5 * behind);
+            t = (chain > paced ? chain : paced) + 0.5 * t_tails;
+        } else {
+            const double t_intra = items * item / (double)(slots - pairs * (2 * p - 1));
+            const double fed = t_intra * (double)(p - 1) / (double)p;
+            r = (phase >= 1.5 * fed) ? 0.7 : 1.0;
+            t = (phase > fed ? phase : fed) + 60.0 + 12.0 * (p - 2) + phase;
+            if (t_intra + 2 * step > t) t = t_intra + 2 * step;
         }
-        const double t1 = phase > fed ? phase : fed;
-        double t = t1 + 60.0 + 12.0 * (p - 2) + phase;
-        if (t_intra + 2 * step > t) t = t_intra + 2 * step;
-        if (t < best) { best = t; parts = p; *first_ratio = ratio; }
+        if (forced >= 3 ? p <= forced : t < best) { best = t; cut.parts = p; ratio = r; cut.tail = tail; }
     }
-    return parts;
+    if (cut.parts > 1) {
+        if (g_split_ratio > 0.0) ratio = g_split_ratio;
+        cut.part0_len = (int64_t)((double)plan.seg_chunks * ratio / ((double)(cut.parts - 1) + ratio) + 0.5);
+        if (cut.part0_len < 1) cut.part0_len = 1;
+        cut.part_len = (plan.seg_chunks - cut.part0_len + cut.parts - 2) / (cut.parts - 1);
+        if (g_split_tail >= 0) cut.tail = g_split_tail;
+        if (cut.tail > cut.part0_len) cut.tail = cut.part0_len;
+        if (cut.tail > cut.part_len) cut.tail = cut.part_len;
+    }
+    return cut;
 }
 
 // The plan with the most chunk indices per segment that fits `workspace_bytes` (full: no limit).
@@ -165,16 +199,8 @@ kda_status chunk_mfma_plan(const kda_dims *d, size_t workspace_bytes, bool gate,
     if (plan.total_bytes > workspace_bytes) return fail(KDA_ERR_WORKSPACE, "workspace too small for any plan");
     const int cus = compute_units();
     if (cus <= 0) return fail(KDA_ERR_LAUNCH, "cannot query the device");
-    double ratio = 1.0;
-    const int parts = g_split ? split_parts(plan, d, cus, g_split, &ratio) : 1;
-    if (g_split_ratio > 0.0) ratio = g_split_ratio;
-    out[0] = plan.seg_chunks; out[1] = plan.num_segments; out[2] = parts; out[3] = 0; out[4] = 0;
-    if (parts > 1) {
-        int64_t part0_len = (int64_t)((double)plan.seg_chunks * ratio / ((double)(parts - 1) + ratio) + 0.5);
-        if (part0_len < 1) part0_len = 1;
-        out[3] = part0_len;
-        out[4] = (plan.seg_chunks - part0_len + parts - 2) / (parts - 1);
-    }
+    const SplitCut cut = g_split ? split_cut(plan, d, cus, g_split) : SplitCut{1, 0, 0, 0};
+    out[0] = plan.seg_chunks; out[1] = plan.num_segments; out[2] = cut.parts; out[3] = cut.part0_len; out[4] = cut.part_len;
     return KDA_OK;
 }
 
@@ -229,16 +255,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
     const int64_t maxc = max_chunks_per_seq(d);
 
     // One launch per time segment, both stages as roles of one kernel.
-    double ratio = 1.0;
-    const int parts = g_split ? split_parts(plan, d, cus, g_split, &ratio) : 1;
-    if (g_split_ratio > 0.0) ratio = g_split_ratio;
-    int64_t part0_len = 0, part_len = 0;
-    if (parts > 1) {
-        // ranges: the first one shorter by the ratio of the step times (full scan : passes without output)
-        part0_len = (int64_t)((double)plan.seg_chunks * ratio / ((double)(parts - 1) + ratio) + 0.5);
-        if (part0_len < 1) part0_len = 1;
-        part_len = (plan.seg_chunks - part0_len + parts - 2) / (parts - 1);
-    }
+    const SplitCut cut = g_split ? split_cut(plan, d, cus, g_split) : SplitCut{1, 0, 0, 0};
+    const int parts = cut.parts;
     const size_t pair_states = (size_t)streams * D * D;
     for (int64_t seg = 0; seg < plan.num_segments; ++seg) {
         FusedLaunch L{};
@@ -252,7 +270,7 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         a.launch_chunks = left < plan.seg_chunks ? left : plan.seg_chunks;
         a.wait_limit = g_wait_limit; a.H = d->heads; a.scale = d->scale; a.epoch = (uint32_t)(seg + 1);
         a.producers = g_producers; a.raw = raw;
-        a.split.parts = parts; a.split.part_len = part_len; a.split.part0_len = part0_len;
+        a.split.parts = parts; a.split.part_len = cut.part_len; a.split.part0_len = cut.part0_len; a.split.tail = cut.tail;
         a.split.flags = reinterpret_cast<uint32_t *>(base + plan.split_offset);
         a.split.E = reinterpret_cast<float *>(base + plan.split_offset + kSplitFlagBytes);
         a.split.Tm = a.split.E + kSplitMaxParts * pair_states;

@@ -60,8 +60,8 @@ void kda_prefill_kernel(const FusedArgs a)
     static_assert(!(kGate && kScalar), "no output gate on the scalar-gate entry point");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     if (a.split.parts > 1) {
-        // ---- time-split layout (few pairs): [pairs x (2 parts - 3) scan workgroups][per-chunk workgroups] ----
-        const int nsw = 2 * a.split.parts - 3;
+        // ---- time-split layout (few pairs): [pairs x (2 parts - 1) scan workgroups][per-chunk workgroups] ----
+        const int nsw = 2 * a.split.parts - 1;
         const int64_t bid = blockIdx.x, nscan = a.pairs * nsw;
         if (bid < nscan) {
             const int y = (int)(bid / a.pairs);
@@ -82,22 +82,26 @@ void kda_prefill_kernel(const FusedArgs a)
             return;
         }
         if (!a.producers) return;
-        // The first phase of the scan walks all ranges but the last side by side, so the chunk order
-        // interleaves those and lets the last range follow.
-        const int64_t first = a.split.parts - 1, part_len = a.split.part_len, part0_len = a.split.part0_len;
-        const int64_t total = a.pairs * (int64_t)a.split.parts * part_len;
+        // The scan wants the tails of all ranges but the last first (what starts the other ranges comes from
+        // them), then walks all ranges side by side: the chunk order is the tails, interleaved, and then the
+        // ranges, interleaved, from their starts (a tail's chunks are not produced twice).
+        const int64_t parts = a.split.parts, part_len = a.split.part_len, part0_len = a.split.part0_len, tail = a.split.tail;
+        const int64_t tails = (parts - 1) * tail;
+        const int64_t total = a.pairs * (tails + parts * part_len);
         kda_intra_items<true, kRaw, kScalar>(lds, intra_args<kGate>(a), a.per_wg, [&](int t) __attribute__((always_inline)) {
             const int64_t i = item_index(bid - nscan, t, a.per_wg, a.window);
             IntraItem it = {0, 0, -1};
             if (i >= total) return it;
             const int64_t z = i / a.pairs, pair = i - z * a.pairs;
             int64_t cl;
-            if (z < first * part_len) {
-                const int64_t rr = z % first, j = z / first;
-                if (rr == 0 && j >= part0_len) return it;                // the first range is the shorter one
-                cl = (rr == 0) ? j : part0_len + (rr - 1) * part_len + j;
+            if (z < tails) {
+                const int64_t rr = z % (parts - 1), j = z / (parts - 1);
+                cl = part0_len + rr * part_len - tail + j;                // the end of range rr, less the tail
             } else {
-                cl = part0_len + (first - 1) * part_len + (z - first * part_len);
+                const int64_t zz = z - tails, rr = zz % parts, j = zz / parts;
+                const int64_t rlen = (rr == 0) ? part0_len : part_len;
+                if (j >= ((rr == parts - 1) ? rlen : rlen - tail)) return it;
+                cl = ((rr == 0) ? 0 : part0_len + (rr - 1) * part_len) + j;
             }
             it.n = (int)(pair / a.H); it.h = (int)(pair - (int64_t)it.n * a.H); it.cl = cl;
             return it;
@@ -190,9 +194,10 @@ kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
     const int slots = 2 * L.compute_units;
     a.per_wg = kItemsPerWorkgroup;
     if (a.split.parts > 1) {
-        const int64_t nscan = a.pairs * (int64_t)(2 * a.split.parts - 3);
+        const int64_t nscan = a.pairs * (int64_t)(2 * a.split.parts - 1);
         a.window = (int)(slots - nscan > 64 ? slots - nscan : 64);
-        blocks = nscan + intra_workgroups(a.pairs * (int64_t)a.split.parts * a.split.part_len, a.per_wg, a.window);
+        const int64_t items = a.pairs * ((a.split.parts - 1) * a.split.tail + (int64_t)a.split.parts * a.split.part_len);
+        blocks = nscan + intra_workgroups(items, a.per_wg, a.window);
     } else {
         const int64_t nbatches = (a.pairs + a.nb - 1) / a.nb;
         const int64_t beside = nbatches > 1 ? 2 * a.nb : a.nb;

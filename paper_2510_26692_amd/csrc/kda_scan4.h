@@ -41,6 +41,7 @@ namespace mfma {
 //   kRoleT      the d_k x d_k transition of the range: starts from the identity, drops U (the
 //               recurrence is affine in the state: S_out = T S_in + B), writes no output
 //   kRoleB      the offset of the range: starts from zero, keeps U, writes no output
+// A kRoleT pass returns whether the transition it ended with is exactly zero (every other pass: false).
 constexpr int kRoleFull = 0, kRoleT = 1, kRoleB = 2;
 
 namespace scan4 {
@@ -180,7 +181,7 @@ struct GateParams {
     float eps;
 };
 template <bool kFlags, bool kOutBf16, int kRole = kRoleFull, bool kGate = false>
-__device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
+__device__ __forceinline__ bool kda_scan4_body(uint8_t *lds, const uint8_t *slot0, int64_t slot_stride,
                                                const float *state_in, float *state_out, void *o, int64_t st_base,
                                                int64_t tok_base, int64_t len, int H, int64_t c_begin, int64_t c_end,
                                                int h, const uint32_t *ready, uint32_t epoch, uint32_t *status,
@@ -568,6 +569,23 @@ __device__ __forceinline__ void kda_scan4_body(uint8_t *lds, const uint8_t *slot
             for (int j = 0; j < 16; ++j)
                 state_out[st_base + (int64_t)(32 * t + acc_row(j, hh)) * D] = S[t][j];
     }
+    bool vanished = false;
+    if (kRole == kRoleT) {
+        // the transition as it stands at the end of the pass, whichever way the loop was left: all four slices zero?
+        uint32_t bits = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) bits |= __float_as_uint(S[t][j]);
+        const bool zero = __builtin_amdgcn_ballot_w64((bits & 0x7fffffffu) != 0) == 0;
+        volatile uint32_t *zf = reinterpret_cast<volatile uint32_t *>(lds);
+        __syncthreads();                                         // nobody reads operands from the LDS any more
+        if (lane == 0) zf[c] = zero ? 1u : 0u;
+        __syncthreads();
+        vanished = (zf[0] & zf[1] & zf[2] & zf[3]) != 0;
+        __syncthreads();                                         // the words are free again
+    }
+    return vanished;
 }
 
 }  // namespace scan4

@@ -1,21 +1,38 @@
 // Time-split scan for few (sequence, head) pairs and long sequences, built from the four-wave scan
-// (kda_scan4.h).  The chunk recurrence is affine in the state (Section 3.1: S_out = T S_in + B with T
-// the product of the per-chunk transitions), so the chunk axis is cut into `parts` ranges, the first
-// of `part0_len` chunk indices and the others of `part_len`, and 2 parts - 3 workgroups work on one
-// pair side by side:
-//   y = 0          scans range 0 from the initial state (outputs and all) and leaves its final state
-//                  in E[0]; later it scans the last range from E[parts - 2] and delivers the final state.
-//   y = 2 p - 1    computes the transition T_p of range p = 1 .. parts - 2; later it scans range p
-//                  from E[p - 1].
-//   y = 2 p        computes the offset B_p of range p.
-// Between the phases, workgroups y = 1 .. workers form E[p] = T_p E[p-1] + B_p for p = 1 .. parts - 2,
-// each on its own slice of the d_v columns (the columns do not interact).  Results travel through
-// the workspace (E, Tm, Bm: arrays of [pairs][128][128] fp32 states, one per range) under per-pair
-// counters: pf[p] = slices of E[p] that are complete (E[0]: set to `workers` at once), pf[8 + p] /
-// pf[16 + p] = T_p / B_p complete.  Every producer makes its stores visible with a device-scope
-// release before it raises the counter, every consumer follows its (bounded) wait with a
-// device-scope acquire.  No first-phase work waits for anything but its slots, all these workgroups
-// sit at the front of the grid and take well under half the device, so every wait ends.
+// (kda_scan4.h).  The chunk axis is cut into `parts` ranges, the first of `part0_len` chunk indices and
+// the others of `part_len`, and the ranges of one pair are scanned side by side, each by a workgroup of
+// its own.  What a range needs is the state at its start, E[p] = the state at the end of range p.
+//
+// The short way.  The chunk recurrence is affine in the state (Section 3.1: S_out = T S_in + B, T the
+// product of the per-chunk transitions), and every step scales the state by the chunk's decay, so over
+// enough chunks T vanishes: in fp32, bit for bit.  Where the transition of the last `tail` chunks of
+// range p is exactly zero, the state at the end of the range does not depend on the state the range
+// started from, and E[p] is the offset B of those chunks alone: `tail` steps from a zero state instead
+// of the whole range.  Per pair, 2 parts - 1 workgroups:
+//   y = 0          scans range 0 from the initial state (outputs and all) and leaves its final state in E[0].
+//   y = 2 p + 1    forms the transition of the tail of range p, p = 0 .. parts - 2, and publishes the verdict:
+//                  V[p] = 2 (zero) or 1 (not zero).  Then it scans range p + 1 from the offset of that tail;
+//                  the last range delivers the final state.
+//   y = 2 p + 2    forms the offset of the tail of range p (Bm[p]) and leaves.
+// All ranges are under way after about `tail` steps, and the chain is one range long.
+//
+// The general way, for a pair in which some verdict is 1 (slow decay, or a sequence that ends before
+// its ranges do): as soon as the verdicts are in, the same workgroups form the whole-range transitions and
+// offsets and chain the range states through them,
+//   y = 2 p + 1    T_p of range p = 1 .. parts - 2 into Tm[p]; later it scans range p from E[p - 1]
+//                  (p = 0: nothing first, later the last range from E[parts - 2] and the final state),
+//   y = 2 p + 2    B_p of range p = 1 .. parts - 2 into Bm[p],
+//   y = 1 .. workers   then form E[p] = T_p E[p-1] + B_p for p = 1 .. parts - 2, each on its own slice of
+//                  the d_v columns (the columns do not interact).
+// which takes two ranges' time instead of one.
+//
+// Results travel through the workspace (E, Tm, Bm: arrays of [pairs][128][128] fp32 states, one per
+// range) under per-pair words: pf[p] = slices of E[p] that are complete (E[0]: set to `workers` at
+// once), pf[8 + p] = T_p complete, pf[16 + p] = 1 when the tail's offset is in Bm[p], 2 when B_p is,
+// pf[24 + p] = V[p].  Every producer makes its stores visible with a device-scope release before it
+// raises a word, every consumer follows its (bounded) wait with a device-scope acquire.  No first
+// pass waits for anything but its slots, all these workgroups sit at the front of the grid and take
+// well under half the device, so every wait ends.
 #pragma once
 #include "kda_prefill_fused.h"
 #include "kda_scan4.h"
@@ -24,16 +41,28 @@ namespace kda {
 namespace mfma {
 namespace scan4 {
 
-constexpr int kSplitFlagsPerPair = 24;
-
+constexpr int kSplitFlagsPerPair = 32;
+static_assert((size_t)kSplitMaxPairs * kSplitFlagsPerPair * 4 <= kSplitFlagBytes, "every pair's words must fit the area");
 
 __device__ __forceinline__ int split_workers(int parts) { return (parts - 2 >= 4) ? 8 : (parts - 2 >= 2) ? 4 : 2; }
 
+// Waits until *flag is not zero and returns it; 0 after `limit` ticks of the 100 MHz wall clock.
+__device__ __noinline__ uint32_t wait_nonzero(const uint32_t *flag, uint64_t limit)
+{
+    const uint64_t t0 = wall_clock64();
+    for (;;) {
+        const uint32_t v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (v != 0) return v;
+        if (wall_clock64() - t0 >= limit) return 0;
+        __builtin_amdgcn_s_sleep(8);
+    }
+}
+
 // E[p][:, col0 .. col0 + 16 CW) for p = 1 .. parts - 2, in fp32, by one 256-thread workgroup.
 // Thread (ty, tx) owns rows 8 ty .. 8 ty + 7 and columns col0 + CW tx .. + CW - 1; the current
-// slice of E sits in LDS.  All T_p and B_p are awaited first (they finish before E[0] does) and
-// pulled into this die's L2; after that the chain crosses no fence: E[0] is read and E[p] written
-// with device-scope accesses.  Returns false if a wait ran out.
+// slice of E sits in LDS.  All T_p and B_p are awaited first (they are done at about the time E[0]
+// is) and pulled into this die's L2; after that the chain crosses no fence: E[0] is read and E[p]
+// written with device-scope accesses.  Returns false if a wait ran out.
 template <int CW>
 __device__ __forceinline__ bool fold_slices(float *sE, float *E, const float *Tm, const float *Bm, int64_t pair_states,
                                             int64_t pair_base, int col0, int parts, int workers, uint32_t *pf,
@@ -46,7 +75,7 @@ __device__ __forceinline__ bool fold_slices(float *sE, float *E, const float *Tm
     if (tid == 0) {
         bool ok = true;
         for (int p = 1; p <= parts - 2 && ok; ++p)
-            ok = wait_flag(pf + 8 + p, 1u, wait_limit) && wait_flag(pf + 16 + p, 1u, wait_limit);
+            ok = wait_flag(pf + 8 + p, 1u, wait_limit) && wait_flag(pf + 16 + p, 2u, wait_limit);
         ok_word = ok;
     }
     __syncthreads();
@@ -110,7 +139,7 @@ __device__ __forceinline__ bool fold_slices(float *sE, float *E, const float *Tm
 }
 
 // One workgroup (256 threads) of the time-split scan: pair `pair` (sequence n, head h), role index y in
-// [0, 2 parts - 3).  nchunks: chunk indices of this pair inside the launch's time segment; ws_pair / ready_pair:
+// [0, 2 parts - 1).  nchunks: chunk indices of this pair inside the launch's time segment; ws_pair / ready_pair:
 // the pair's first slot and flag in the segment; cbase: the segment's first chunk index in the sequence.
 // kGate: the passes that write outputs apply the output gate; gate_pair: the pair's first slot of gate factors, eps: of
 // the RMSNorm (see kda_scan4_body).
@@ -124,71 +153,152 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int parts = sp.parts;
     const int64_t pair_states = pairs * (int64_t)(D * D), pair_base = pair * (int64_t)(D * D);
-    const int kind = (y == 0) ? kRoleFull : ((y & 1) ? kRoleT : kRoleB);
-    const int mid = (y + 1) / 2;                              // the range of the first phase
     const int workers = split_workers(parts);
     uint32_t *pf = sp.flags + pair * kSplitFlagsPerPair;
     const int64_t st_base = pair_base + 32 * wave + (lane & 31);
-    volatile int &second_ok = *reinterpret_cast<volatile int *>(lds + kLds - 16);
+    // (a word at the very end of the workgroup's LDS, past everything the scan's first loads touch)
+    volatile int &word = *reinterpret_cast<volatile int *>(lds + kLds - 16);
+    auto clip = [&](int64_t c) __attribute__((always_inline)) { return c < nchunks ? c : nchunks; };
+    auto begin_of = [&](int r) __attribute__((always_inline)) { return r == 0 ? (int64_t)0 : sp.part0_len + (r - 1) * sp.part_len; };
+    auto end_of = [&](int r) __attribute__((always_inline)) { return sp.part0_len + r * sp.part_len; };
+    auto give_up = [&]() __attribute__((always_inline)) {
+        __hip_atomic_fetch_or(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
 
-#define KDA_SCAN4_PART(ROLE)                                                                                        \
-    kda_scan4_body<true, kOutBf16, ROLE>(lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, state_in, \
-                                         state_out, o, st_base, tok_base, len, H, cbase + c_begin, cbase + c_end, h,  \
-                                         ready_pair + c_begin, epoch, status, wait_limit)
-    {   // first phase: the own range, from the initial state / the identity / zero
-        const float *state_in = (y == 0) ? h0 : nullptr;
-        float *state_out = (y == 0) ? sp.E : (kind == kRoleT ? sp.Tm : sp.Bm) + mid * pair_states;
-        int64_t c_begin = (mid == 0) ? 0 : sp.part0_len + (mid - 1) * sp.part_len;
-        int64_t c_end = c_begin + ((mid == 0) ? sp.part0_len : sp.part_len);
-        if (c_begin > nchunks) c_begin = nchunks;
-        if (c_end > nchunks) c_end = nchunks;
-        if (kind == kRoleFull)
-            kda_scan4_body<true, kOutBf16, kRoleFull, kGate>(
-                lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, state_in, state_out, o, st_base, tok_base,
-                len, H, cbase + c_begin, cbase + c_end, h, ready_pair + c_begin, epoch, status, wait_limit, false,
-                GateParams{kGate ? gate_pair + c_begin * (int64_t)kGateSlotBytes : nullptr, gate_eps});
-        else if (kind == kRoleT) KDA_SCAN4_PART(kRoleT);
-        else KDA_SCAN4_PART(kRoleB);
+    // the scan of one range (outputs and all); every workgroup that scans comes through this one call
+    int range;                       // the range to scan
+    const float *state_in;           // its initial state
+    bool poisoned = false;           // .. which never arrived
+    if (y == 0) {
+        range = 0; state_in = h0;
+    } else {
+        const int p = (y - 1) >> 1;                               // the boundary: end of range p
+        const bool is_t = (y & 1) != 0;
+        // ---- the tail of range p: transition (is it zero?) / offset; tail = 0: the host saw no point in trying ----
+        int64_t c_begin = 0, c_end = 0;
+        bool general = sp.tail == 0;
+        if (general && y == 1 && threadIdx.x == 0) __hip_atomic_fetch_or(status, 512u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma nounroll
+        for (int pass = general ? 1 : 0; pass < 2; ++pass) {
+            if (pass == 0) {
+                c_end = end_of(p); c_begin = c_end - sp.tail;    // (tail <= every range's length)
+            } else {
+                if (p == 0) break;
+                c_begin = begin_of(p); c_end = end_of(p);
+            }
+            c_begin = clip(c_begin); c_end = clip(c_end);
+            // pass 0: the tail; pass 1 (general way, middle ranges only): the whole range
+            float *state_out = is_t ? (pass ? sp.Tm + p * pair_states : nullptr) : sp.Bm + p * pair_states;
+            bool vanished = false;
+            if (is_t)
+                vanished = kda_scan4_body<true, kOutBf16, kRoleT>(
+                    lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, nullptr, state_out, o, st_base, tok_base,
+                    len, H, cbase + c_begin, cbase + c_end, h, ready_pair + c_begin, epoch, status, wait_limit);
+            else
+                kda_scan4_body<true, kOutBf16, kRoleB>(
+                    lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, nullptr, state_out, o, st_base, tok_base,
+                    len, H, cbase + c_begin, cbase + c_end, h, ready_pair + c_begin, epoch, status, wait_limit);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __syncthreads();
+            if (pass == 1) {
+                if (threadIdx.x == 0)
+                    __hip_atomic_store(is_t ? pf + 8 + p : pf + 16 + p, is_t ? 1u : 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            if (threadIdx.x == 0) {
+                __hip_atomic_store(is_t ? pf + 24 + p : pf + 16 + p, is_t ? (vanished ? 2u : 1u) : 1u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                // the verdicts of all boundaries of the pair: every workgroup of the pair takes the same way
+                bool all_zero = true;
+                for (int b = 0; b <= parts - 2; ++b) {
+                    const uint32_t v = wait_nonzero(pf + 24 + b, wait_limit);
+                    if (v == 0) give_up();                        // (never seen: the general way then runs into its own waits)
+                    all_zero = all_zero && v == 2u;
+                }
+                word = all_zero ? 0 : 1;
+                // (for tests and measurement: which way pairs took, in two bits of the status word that report no failure)
+                if (y == 1) __hip_atomic_fetch_or(status, all_zero ? 256u : 512u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();
+            general = uni(word) != 0;                            // (the same in every lane: branches and addresses stay scalar)
+            __syncthreads();
+            if (!general) break;
+        }
+        if (!general) {
+            if (!is_t) return;
+            // the short way: range p + 1 starts from the offset of the tail of range p
+            if (threadIdx.x == 0) {
+                const bool ok = wait_flag(pf + 16 + p, 1u, wait_limit);
+                if (!ok) give_up();
+                word = ok;
+            }
+            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            poisoned = uni(word) == 0;
+            range = p + 1; state_in = sp.Bm + p * pair_states;
+        } else {
+            if (y <= workers) {
+                float *sE = reinterpret_cast<float *>(lds);
+                const int w = y - 1;
+                bool ok;
+                if (workers == 8)      ok = fold_slices<1>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 16 * w, parts, workers, pf, wait_limit);
+                else if (workers == 4) ok = fold_slices<2>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 32 * w, parts, workers, pf, wait_limit);
+                else                   ok = fold_slices<4>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 64 * w, parts, workers, pf, wait_limit);
+                if (!ok && threadIdx.x == 0) give_up();
+                __syncthreads();
+            }
+            if (!is_t) return;
+            // the general way: range p from E[p - 1]; the workgroup of boundary 0 takes the last range
+            range = (p == 0) ? parts - 1 : p;
+            if (threadIdx.x == 0) {
+                const bool ok = wait_flag(pf + range - 1, (uint32_t)workers, wait_limit);
+                if (!ok) give_up();
+                word = ok;
+            }
+            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            poisoned = uni(word) == 0;
+            state_in = sp.E + (range - 1) * pair_states;
+        }
+        __syncthreads();
+    }
+
+    // (if the range's initial state never arrived, the scan starts from NaN: see kda_scan4_body's `poisoned`)
+    if (poisoned) state_in = nullptr;
+    // The last range delivers the final state.  Where that is the array the initial state was read from (a later time
+    // segment of a call), the workgroup of range 0 may not have read it yet: the state then rests in E[parts - 1]
+    // until that workgroup is done.
+    const bool last = range == parts - 1;
+    const bool detour = last && state_final != nullptr && state_final == h0;
+    float *state_out = (range == 0) ? sp.E : last ? (detour ? sp.E + (int64_t)(parts - 1) * pair_states : state_final) : nullptr;
+    const int64_t c_begin = clip(begin_of(range)), c_end = clip(end_of(range));
+    kda_scan4_body<true, kOutBf16, kRoleFull, kGate>(
+        lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, state_in, state_out, o, st_base, tok_base, len, H,
+        cbase + c_begin, cbase + c_end, h, ready_pair + c_begin, epoch, status, wait_limit, poisoned,
+        GateParams{kGate ? gate_pair + c_begin * (int64_t)kGateSlotBytes : nullptr, gate_eps});
+    if (range == 0) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         __syncthreads();
+        if (threadIdx.x == 0) __hip_atomic_store(pf, (uint32_t)workers, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (detour) {
+        __syncthreads();
         if (threadIdx.x == 0) {
-            uint32_t *f = (kind == kRoleFull) ? pf : (kind == kRoleT) ? pf + 8 + mid : pf + 16 + mid;
-            __hip_atomic_store(f, (kind == kRoleFull) ? (uint32_t)workers : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    if (y >= 1 && y <= workers) {
-        float *sE = reinterpret_cast<float *>(lds);
-        const int w = y - 1;
-        bool ok;
-        if (workers == 8)      ok = fold_slices<1>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 16 * w, parts, workers, pf, wait_limit);
-        else if (workers == 4) ok = fold_slices<2>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 32 * w, parts, workers, pf, wait_limit);
-        else                   ok = fold_slices<4>(sE, sp.E, sp.Tm, sp.Bm, pair_states, pair_base, 64 * w, parts, workers, pf, wait_limit);
-        if (!ok && threadIdx.x == 0) __hip_atomic_fetch_or(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (kind == kRoleB) return;
-    {   // second phase: the scan of a range whose initial state is now known
-        const int part = (y == 0) ? parts - 1 : mid;
-        const float *state_in = sp.E + (part - 1) * pair_states;
-        float *state_out = (y == 0) ? state_final : nullptr;
-        if (threadIdx.x == 0) {
-            const bool ok = wait_flag(pf + part - 1, (uint32_t)workers, wait_limit);
-            if (!ok) __hip_atomic_fetch_or(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            second_ok = ok;
+            const bool ok = wait_flag(pf, (uint32_t)workers, wait_limit);
+            if (!ok) give_up();
+            word = ok;
         }
         __syncthreads();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        int64_t c_begin = sp.part0_len + (part - 1) * sp.part_len, c_end = c_begin + sp.part_len;   // part >= 1 here
-        if (c_begin > nchunks) c_begin = nchunks;
-        if (c_end > nchunks) c_end = nchunks;
-        // (if the range's initial state never arrived, the scan starts from NaN: see kda_scan4_body's `poisoned`)
-        const bool poisoned = second_ok == 0;
-        if (poisoned) state_in = nullptr;
-        kda_scan4_body<true, kOutBf16, kRoleFull, kGate>(
-            lds, ws_pair + c_begin * (int64_t)kSlotBytes, (int64_t)kSlotBytes, state_in, state_out, o, st_base, tok_base, len, H,
-            cbase + c_begin, cbase + c_end, h, ready_pair + c_begin, epoch, status, wait_limit, poisoned,
-            GateParams{kGate ? gate_pair + c_begin * (int64_t)kGateSlotBytes : nullptr, gate_eps});
+        const bool ok = uni(word) != 0;
+        // (every thread moves the elements it has just written itself)
+        const float *from = sp.E + (int64_t)(parts - 1) * pair_states;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int64_t at = st_base + (int64_t)(32 * t + acc_row(j, lane >> 5)) * D;
+                state_final[at] = ok ? from[at] : __builtin_nanf("");
+            }
     }
-#undef KDA_SCAN4_PART
 }
 
 }  // namespace scan4

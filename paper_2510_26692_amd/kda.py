@@ -86,6 +86,8 @@ def load_library():
     lib.kda_debug_chunk_fwd_plan.restype = ctypes.c_int
     lib.kda_debug_chunk_fwd_plan.argtypes = [ctypes.POINTER(KdaDims), ctypes.c_size_t, ctypes.c_int,
                                              ctypes.POINTER(ctypes.c_int64)]
+    lib.kda_debug_chunk_fwd_status.restype = ctypes.c_int
+    lib.kda_debug_chunk_fwd_status.argtypes = [ctypes.POINTER(KdaDims), vp, sz, vp, ctypes.POINTER(ctypes.c_uint)]
     lib.kda_debug_stream_probe.restype = ctypes.c_int
     lib.kda_debug_stream_probe.argtypes = [ctypes.c_int, vp, sz, vp]
     lib.kda_debug_prefill_traffic_probe.restype = ctypes.c_int
@@ -142,6 +144,18 @@ def kda_debug_chunk_fwd_plan(dims, workspace_bytes, output_gate=False):
     if st != 0:
         raise KdaError(st, kda_last_error())
     return tuple(int(x) for x in out)
+
+
+def kda_debug_chunk_fwd_status(dims, workspace):
+    """The raw status word the bf16 prefill call that used `workspace` with `dims` left behind (waits for the
+    current stream): bits 1, 2, 4 failures, 256 / 512 the way the time-split scan took (kda_debug.h)."""
+    word = ctypes.c_uint(0)
+    st = load_library().kda_debug_chunk_fwd_status(ctypes.byref(dims), _ptr(workspace),
+                                                   ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                                   _stream_ptr(workspace.device), ctypes.byref(word))
+    if st != 0:
+        raise KdaError(st, kda_last_error())
+    return int(word.value)
 
 
 def kda_debug_stream_probe(mode, buffer):

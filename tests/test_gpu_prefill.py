@@ -346,40 +346,62 @@ def test_bf16_decay_ladder_across_the_exact_path_threshold():
     print("bf16 decay ladder: err_o %.2e err_hT %.2e" % (eo, eh))
 
 
-@pytest.mark.parametrize("case", ["three_ranges", "eight_ranges", "packed_ragged", "vanishing_transition"])
+SHORT_WAY, GENERAL_WAY = 256, 512                           # bits of the status word: the way pairs of a time-split call took
+
+
+@pytest.mark.parametrize("case", ["three_ranges", "eight_ranges", "packed_ragged", "vanishing_transition",
+                                  "vanishing_short_ranges", "mixed_ways"])
 def test_bf16_time_split_scan(case):
     """Few (sequence, head) pairs and long sequences: the sequential kernel cuts the chunk axis into
-    ranges that several workgroups walk side by side (transition and offset of a range first, the
-    true states after a fold).  Checked against the oracle, and against the plain scan, with which
-    it must agree to rounding."""
+    ranges that several workgroups walk side by side.  Where the transition of every range's last chunks
+    is exactly zero, the ranges start from the offsets of those chunks (the short way); otherwise
+    transition and offset of whole ranges are formed first and the true states after a fold (the general
+    way).  Checked against the oracle, and against the plain scan, with which it must agree to rounding;
+    the status word says which way was taken."""
     import paper_2510_26692_amd as kda
     # mu = -6: log alpha around -0.0025 per token, so a range's transition matrix is far from zero
-    # and the fold of the ranges matters; mu = -2: the state is forgotten within a range, and with ranges of 50
-    # chunks (vanishing_transition) the workgroups that form the transitions find them exactly zero and leave early
+    # and the fold of the ranges matters; mu = -2: the state is forgotten within a dozen chunks
+    mode, want = 8, GENERAL_WAY
     if case == "three_ranges":
         x = si.make_prefill(1, 64 * 60 - 11, 2, 128, 128, "bf16", -6.0, 301, 0.05)
     elif case == "eight_ranges":
         x = si.make_prefill(2, 64 * 130 + 5, 1, 128, 128, "bf16", -6.0, 302, 0.05)
-    elif case == "vanishing_transition":
+    elif case == "vanishing_transition":                      # four ranges of 50 chunks, tails of 32
         x = si.make_prefill(1, 64 * 200 + 9, 2, 128, 128, "bf16", -2.0, 304, 0.05)
-    else:
+        mode, want = 4, SHORT_WAY
+    elif case == "vanishing_short_ranges":                    # five ranges of 20 chunks: the tail is the whole range
+        x = si.make_prefill(1, 64 * 100 - 3, 3, 128, 128, "bf16", -2.0, 305, 0.05)
+        mode, want = 5, SHORT_WAY
+    elif case == "mixed_ways":                                # one head forgets, the other does not
+        x = si.make_prefill(1, 64 * 120 + 1, 2, 128, 128, "bf16", -2.0, 306, 0.05)
+        slow = si.make_prefill(1, 64 * 120 + 1, 2, 128, 128, "bf16", -6.0, 307, 0.05)
+        x["log_alpha"][:, :, 1] = slow["log_alpha"][:, :, 1]
+        mode, want = 3, SHORT_WAY | GENERAL_WAY
+    else:                                                     # sequences that end before their ranges do
         x = si.make_varlen(np.array([64 * 130, 3001, 100, 0]), 1, 128, 128, "bf16", -2.0, 303, 0.05)
     try:
-        kda.kda_debug_set_time_split(4 if case == "vanishing_transition" else 8)   # split for sure
+        kda.kda_debug_set_time_split(mode)                    # split for sure
         eo, eh = check_prefill(x, TOL_BF16)
         dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
+        dims = kda.kda.make_chunk_dims(dd["q"], dd["v"], dd["cu_seqlens"])
+        ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
         o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
-                                   cu_seqlens=dd["cu_seqlens"], check=True)
+                                   cu_seqlens=dd["cu_seqlens"], workspace=ws, check=True)
+        status = kda.kda_debug_chunk_fwd_status(dims, ws)
         kda.kda_debug_set_time_split(0)
         o2, h2 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
-                                   cu_seqlens=dd["cu_seqlens"], check=True)
+                                   cu_seqlens=dd["cu_seqlens"], workspace=ws, check=True)
+        status_plain = kda.kda_debug_chunk_fwd_status(dims, ws)
         torch.cuda.synchronize()
         d_o = (o1 - o2).abs().max().item() / o2.abs().max().item()
         d_h = (h1 - h2).abs().max().item() / h2.abs().max().item()
-        print("time split %s: err_o %.2e err_hT %.2e; vs plain scan %.2e / %.2e" % (case, eo, eh, d_o, d_h))
+        print("time split %s: err_o %.2e err_hT %.2e; vs plain scan %.2e / %.2e; status %#x" % (case, eo, eh, d_o, d_h, status))
         assert d_o <= TOL_BF16 and d_h <= TOL_BF16
-        if case in ("three_ranges", "eight_ranges"):
-            assert not torch.equal(h1, h2)                    # the split path really ran: same result, other rounding
+        assert status_plain == 0
+        if case == "packed_ragged":
+            assert status & GENERAL_WAY and status & ~(SHORT_WAY | GENERAL_WAY) == 0
+        else:
+            assert status == want
     finally:
         kda.kda_debug_set_time_split(1)
 
@@ -460,21 +482,28 @@ def test_bf16_zero_tokens_returns_the_initial_state(with_h0):
     assert torch.equal(hT, h0 if with_h0 else torch.zeros_like(hT))
 
 
-def test_bf16_time_split_scan_inside_time_segments():
+@pytest.mark.parametrize("mu,mode", [(-6.0, 8), (-2.0, 3)])
+def test_bf16_time_split_scan_inside_time_segments(mu, mode):
     """A workspace of 45 % of the full size: the call walks the time axis in three segments, and the
     sequential kernel of each segment is split into ranges; states are carried from segment to
-    segment.  Checked against the oracle and against the single-segment call."""
+    segment (a segment's final state goes to the array its initial state is read from).  Slow decay takes
+    the general way in every segment; with fast decay and three ranges the segments take the short way (a last
+    segment that ends before its ranges do would take the general one).  Checked against the oracle and
+    against the single-segment call."""
     import paper_2510_26692_amd as kda
-    x = si.make_prefill(2, 64 * 130 + 5, 1, 128, 128, "bf16", -6.0, 304, 0.05)
+    x = si.make_prefill(2, 64 * 130 + 5, 1, 128, 128, "bf16", mu, 304, 0.05)
     dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
     dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
     full = kda.kda_chunk_fwd_workspace_size(dims)
     ws = torch.empty(int(full * 0.45) // 256 * 256, dtype=torch.uint8, device="cuda")
     try:
-        kda.kda_debug_set_time_split(8)
+        kda.kda_debug_set_time_split(mode)
+        plan = kda.kda_debug_chunk_fwd_plan(dims, ws.numel())
+        assert plan[1] == 3 and 3 <= plan[2] <= mode
         eo, eh = check_prefill(x, TOL_BF16, workspace=ws)
         o1, h1 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws,
                                    check=True)
+        status = kda.kda_debug_chunk_fwd_status(dims, ws)
         o2, h2 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], check=True)
         kda.kda_debug_set_time_split(0)
         o3, h3 = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws,
@@ -482,11 +511,11 @@ def test_bf16_time_split_scan_inside_time_segments():
         torch.cuda.synchronize()
     finally:
         kda.kda_debug_set_time_split(1)
-    print("time split in segments: err_o %.2e err_hT %.2e" % (eo, eh))
+    print("time split in segments (mu %.0f): err_o %.2e err_hT %.2e status %#x" % (mu, eo, eh, status))
     for o_, h_ in ((o2, h2), (o3, h3)):
         assert (o1 - o_).abs().max().item() <= TOL_BF16 * o_.abs().max().item()
         assert (h1 - h_).abs().max().item() <= TOL_BF16 * h_.abs().max().item()
-    assert not torch.equal(h1, h3)                            # the segmented call really was split
+    assert status == GENERAL_WAY if mu == -6.0 else status in (SHORT_WAY, SHORT_WAY | GENERAL_WAY)
 
 
 @pytest.mark.parametrize("dtype,tol,d", [("f32", TOL_F32, 64), ("bf16", TOL_BF16, 128)])

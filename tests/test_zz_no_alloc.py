@@ -1,5 +1,7 @@
 """kda_chunk_fwd_static_scratch: the entry point that allocates nothing (its workspace is a static device
 array inside the library) against kda_chunk_fwd on the same inputs, through the C ABI."""
+import gc
+
 import numpy as np
 import pytest
 import torch
@@ -19,6 +21,7 @@ def _both(x, **kw):
     o_ref, h_ref = kda.kda_chunk_fwd(*args, h0=dd.get("h0"), cu_seqlens=dd.get("cu_seqlens"), check=True, **kw)
     o = torch.full_like(o_ref, float("nan"))
     hT = torch.full_like(h_ref, float("nan"))
+    gc.collect()                                             # (garbage of earlier tests must not be freed in between)
     before = torch.cuda.memory_allocated()
     kda.kda_chunk_fwd_static_scratch(*args, o, hT=hT, h0=dd.get("h0"), cu_seqlens=dd.get("cu_seqlens"), **kw)
     torch.cuda.synchronize()
