@@ -373,20 +373,22 @@ def main():
         ms_mfma = _time_region(torch, lambda: kda.kda_debug_mfma_probe(sink, wgs, 2000), 5)
         head["roofline"]["measured_mfma_f16_TFLOPs"] = flops / (ms_mfma * 1e-3) / 1e12
         head["roofline"]["mfma_peak_TFLOPs"] = MFMA_PEAK_TFLOPS
-        # the floor the two-stage design sets itself: its own data movement per (chunk, head) and nothing else
-        # (64 KiB in, a 72 KiB slot written and read back, 32 KiB out), on 65 536 items (the item count of a
-        # prefill of 2^17 tokens x 32 heads)
+        # the data movement of the two-stage design per (chunk, head) and nothing else (64 KiB in, a 72 KiB slot
+        # written and read back, 32 KiB out), by a plain kernel on 65 536 items (the item count of a prefill of
+        # 2^17 tokens x 32 heads): the level a prefill that is bound by its own traffic is read against
         tbuf = torch.empty(65536 * 172032, dtype=torch.uint8, device=dev)
         items, moved = kda.kda_debug_prefill_traffic_probe(tbuf)
         ms_t = _time_region(torch, lambda: kda.kda_debug_prefill_traffic_probe(tbuf), 5)
         del tbuf
         ns_item = ms_t * 1e6 / items
-        head["roofline"]["two_stage_traffic_floor"] = {
+        head["roofline"]["two_stage_traffic_probe"] = {
             "ns_per_chunk_head": ns_item, "moved_GBps": moved / (ms_t * 1e-3) / 1e9,
             "bytes_per_chunk_head": moved // items}
         for r_ in results.values():
             chunk_heads = r_["tokheads_per_s"] * r_["ms_per_step"] * 1e-3 / 64.0
-            r_["roofline"]["frac_of_two_stage_traffic_floor"] = ns_item * chunk_heads * 1e-6 / r_["ms_per_step"]
+            r_["roofline"]["probe_time_over_kernel_time"] = ns_item * chunk_heads * 1e-6 / r_["ms_per_step"]
+            if r_["roofline"].get("traffic"):
+                r_["roofline"]["moved_GBps"] = r_["roofline"]["traffic"] / (r_["ms_per_step"] * 1e-3) / 1e9
     out = {
         "metric": head["metric"], "value": head["value"], "unit": head["unit"],
         "n_gpus": 1, "steps": head["steps"], "warmup": head.get("warmup", args.warmup), "ms_per_step": head["ms_per_step"],
