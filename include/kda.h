@@ -25,13 +25,16 @@
  *     streams at once, each with its own workspace (a workspace belongs to one call
  *     until that call has completed).  The bf16 prefill runs its per-chunk stage and
  *     its sequential stage as workgroups of ONE kernel: the sequential workgroups (one
- *     per (sequence, head), each on half a compute unit, at most about 130 of them
- *     resident at a time) wait for the slots that the per-chunk workgroups behind them
+ *     per (sequence, head), or a few for calls with few pairs and long sequences, each
+ *     on half a compute unit, never more than half of the device's such places at a
+ *     time) wait for the slots that the per-chunk workgroups behind them
  *     in the same grid produce.  The producers wait for nothing and are dispatched as
  *     soon as any half compute unit is free, so every wait ends; each wait is bounded
  *     all the same (about two seconds).  Should other work on the device starve the
- *     producers that long, the waiting workgroup gives up: the call's later outputs for
- *     that (sequence, head) and its final state are NaN, never stale data, and
+ *     producers that long, the waiting workgroup gives up: the outputs it had still
+ *     to write for that (sequence, head), to the end of the sequence (a call that scans
+ *     ranges of a long sequence side by side: at least to the end of the range), and the
+ *     final state if the stretch reaches it, are NaN, never stale data, and
  *     kda_chunk_fwd_check reports it.
  *   - Element offsets are 64-bit; tensors with more than 2^31 elements are fine.
  *   - Errors: a non-zero kda_status is returned and kda_last_error() holds a
@@ -280,8 +283,8 @@ kda_status kda_chunk_fwd_scalar_gate(const kda_dims *dims,
  * the status word that the call left in `workspace` (same dims, workspace and
  * size as that call).  The sequential workgroups of the prefill wait, for a
  * bounded time, for each workspace slot; if such a wait ever ran out, the call
- * has written NaN to o from that point of the (sequence, head) on and to its
- * final state, and this returns KDA_ERR_LAUNCH.  If a state of the call ended
+ * has written NaN to o from that point of the (sequence, head) on (see the
+ * conventions above) and this returns KDA_ERR_LAUNCH.  If a state of the call ended
  * up not finite (an fp16 operand overflowed) or a key was beyond the domain
  * stated at kda_chunk_fwd it returns KDA_ERR_INVALID_ARG.  KDA_OK otherwise (also for
  * calls that keep no status word: fp32 inputs).

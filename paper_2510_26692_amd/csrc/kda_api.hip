@@ -386,7 +386,7 @@ kda_status kda_chunk_fwd_check(const kda_dims *d, const void *workspace, size_t 
     if (e != hipSuccess) return fail(KDA_ERR_LAUNCH, "status read: %s", hipGetErrorString(e));
     if (word & 1u)
         return fail(KDA_ERR_LAUNCH, "the sequential stage gave up waiting for a workspace slot (status %u): o is NaN from "
-                    "that point of each affected (sequence, head) on, and so is its final state", word);
+                    "that point of each affected (sequence, head) on, and so is a final state computed from there", word);
     if (word & 4u)
         return fail(KDA_ERR_INVALID_ARG, "a key outside the domain of the fp16 matrix-core operands (status %u): |k_t|^2 > 16 "
                     "for some token; the results may be inaccurate or not finite", word);

@@ -170,7 +170,7 @@ __device__ __noinline__ bool wait_flag(const uint32_t *flag, uint32_t epoch, uin
 //   st_base              element offset of this lane's column in the [d_k][d_v] states: pair * D * D + 32 c + x
 //   poisoned             start from NaN instead of state_in (the caller could not obtain the initial state)
 //   status               word that records a wait that ran out (the state is then poisoned with NaN, so
-//                        every later output of this (sequence, head) and its final state are NaN)
+//                        every later output of this pass and its final state are NaN)
 //   kGate, gate           the output gate of Section 4 applied to O before it is stored:
 //                        o <- Sigmoid(g) * RMSNorm(o) * w, the mean square taken over the d_v values of a token
 //                        (the four waves of the workgroup); gate.factors: w_j Sigmoid(g_tj) as fp16 in accumulator

@@ -273,26 +273,26 @@ def test_bf16_prefill_inside_a_captured_graph_replays_correctly():
         assert torch.equal(o2, o_ref)
 
 
-def test_bf16_time_split_prefill_inside_a_captured_graph():
+@pytest.mark.parametrize("mu,mode,way", [(-6.0, 8, 512), (-2.0, 3, 256)])
+def test_bf16_time_split_prefill_inside_a_captured_graph(mu, mode, way):
     """The same for a call whose sequential kernel is split into ranges: its workgroups wait for one
-    another inside the one launch, and the counters they use are cleared by a kernel of the graph, so
-    a workspace full of garbage before each replay must not matter."""
+    another inside the one launch, and the words they use are cleared by a kernel of the graph, so
+    a workspace full of garbage before each replay must not matter.  Once on the general way of the
+    split (slow decay) and once on the short one; the status word says which was taken."""
     import paper_2510_26692_amd as kda
     T = 64 * 60 - 11
-    x = si.make_prefill(1, T, 2, 128, 128, "bf16", -6.0, 52, 0.05)
+    x = si.make_prefill(1, T, 2, 128, 128, "bf16", mu, 52, 0.05)
     dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
     dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
     ws = torch.empty(kda.kda_chunk_fwd_workspace_size(dims), dtype=torch.uint8, device="cuda")
     o = torch.empty(1, T, 2, 128, device="cuda")
     hT = torch.empty(1, 2, 128, 128, device="cuda")
     try:
-        kda.kda_debug_set_time_split(8)
-        o_ref, h_ref = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], check=True)
-        kda.kda_debug_set_time_split(0)
-        _, h_plain = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], check=True)
-        kda.kda_debug_set_time_split(8)
+        kda.kda_debug_set_time_split(mode)
+        o_ref, h_ref = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws,
+                                         check=True)
+        assert kda.kda_debug_chunk_fwd_status(dims, ws) == way   # the reference really took the split path, this way
         torch.cuda.synchronize()
-        assert not torch.equal(h_ref, h_plain)               # the reference really took the split path
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], o=o, hT=hT,
@@ -304,6 +304,7 @@ def test_bf16_time_split_prefill_inside_a_captured_graph():
             torch.cuda.synchronize()
             assert torch.equal(o, o_ref) and torch.equal(hT, h_ref), rep
             kda.kda_chunk_fwd_check(dims, ws)
+            assert kda.kda_debug_chunk_fwd_status(dims, ws) == way
             o2, _ = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"])
             assert torch.equal(o2, o_ref)
     finally:
