@@ -309,7 +309,16 @@ __device__ __forceinline__ bool kda_scan4_body(uint8_t *lds, const uint8_t *slot
             const int sm = (int)(rel & 1);
             const uint8_t *ldsW = lds + rW * kBig + lane16, *ldsQ = lds + rQ * kBig + lane16, *ldsK = lds + rK * kBig + lane16;
             const uint8_t *ldsA = lds + kSmallRegions + sm * kSmall + lane16;
-            const float *gc = reinterpret_cast<const float *>(lds + kSmallRegions + sm * kSmall + (kOffGc - kOffAqk)) + 4 * hh;
+            // (kGate: what depends on the lane number is formed afresh in every step: carried in registers across the loop
+            // these were the values too many, and a reload from scratch memory waits for every load in flight, once per
+            // step; a volatile statement, or the compiler forms them once ahead of the loop all the same)
+            auto lane_now = [&]() __attribute__((always_inline)) {
+                int l;
+                asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+                return l;
+            };
+            const int hh_step = kGate ? (lane_now() >> 5) : hh;
+            const float *gc = reinterpret_cast<const float *>(lds + kSmallRegions + sm * kSmall + (kOffGc - kOffAqk)) + 4 * hh_step;
             const uint8_t *nxt = slot_of(rel + 1);
             const uint8_t *gate_cur = kGate ? gate_of(rel) : nullptr;
             u32x4 gr[4];                                         // kGate: gate factors of tiles (0, c), (1, c), two 16-byte units each
@@ -399,11 +408,6 @@ __device__ __forceinline__ bool kda_scan4_body(uint8_t *lds, const uint8_t *slot
 #pragma unroll
                 for (int i = 0; i < 16; ++i) scale_state(i / 4, i % 4);
             }
-            // (the lane number is formed afresh where the gate needs it: carried in a register across the loop it was
-            // the one value too many, and its reload from scratch memory waited for every load in flight, once per step)
-            auto lane_now = [&]() __attribute__((always_inline)) {
-                return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-            };
             if (kGate) {
                 // A token's 128 outputs sit in two lanes of each of the four waves: lane-local sum of squares, the
                 // two lanes by a swap, the four waves through the unused tail of this step's small region (the

@@ -58,6 +58,18 @@ __device__ __noinline__ uint32_t wait_nonzero(const uint32_t *flag, uint64_t lim
     }
 }
 
+// NaN into the outputs of head h for the tokens [t_begin, t_end) of a sequence (clipped to its length): by 256 threads.
+template <bool kOutBf16>
+__device__ __forceinline__ void fill_nan(void *o, int64_t tok_base, int64_t len, int H, int h, int64_t t_begin, int64_t t_end)
+{
+    if (t_end > len) t_end = len;
+    for (int64_t i = t_begin * D + threadIdx.x; i < t_end * D; i += 256) {
+        const int64_t at = ((tok_base + i / D) * H + h) * (int64_t)D + i % D;
+        if (kOutBf16) static_cast<uint16_t *>(o)[at] = 0x7fc0u;
+        else          static_cast<float *>(o)[at] = __builtin_nanf("");
+    }
+}
+
 // E[p][:, col0 .. col0 + 16 CW) for p = 1 .. parts - 2, in fp32, by one 256-thread workgroup.
 // Thread (ty, tx) owns rows 8 ty .. 8 ty + 7 and columns col0 + CW tx .. + CW - 1; the current
 // slice of E sits in LDS.  All T_p and B_p are awaited first (they are done at about the time E[0]
@@ -176,10 +188,10 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
         const bool is_t = (y & 1) != 0;
         // ---- the tail of range p: transition (is it zero?) / offset; tail = 0: the host saw no point in trying ----
         int64_t c_begin = 0, c_end = 0;
-        bool general = sp.tail == 0;
-        if (general && y == 1 && threadIdx.x == 0) __hip_atomic_fetch_or(status, 512u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int way = sp.tail == 0 ? 1 : 0;                          // 0: short, 1: general, 2: unknown
+        if (way == 1 && y == 1 && threadIdx.x == 0) __hip_atomic_fetch_or(status, 512u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma nounroll
-        for (int pass = general ? 1 : 0; pass < 2; ++pass) {
+        for (int pass = way; pass < 2; ++pass) {
             if (pass == 0) {
                 c_end = end_of(p); c_begin = c_end - sp.tail;    // (tail <= every range's length)
             } else {
@@ -208,23 +220,36 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
             if (threadIdx.x == 0) {
                 __hip_atomic_store(is_t ? pf + 24 + p : pf + 16 + p, is_t ? (vanished ? 2u : 1u) : 1u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
-                // the verdicts of all boundaries of the pair: every workgroup of the pair takes the same way
-                bool all_zero = true;
+                // The verdicts of all boundaries of the pair: they are written once, so all workgroups of the pair
+                // that get to read them take the same way; one that does not (a wait ran out) takes neither.
+                bool all_zero = true, all_seen = true;
                 for (int b = 0; b <= parts - 2; ++b) {
                     const uint32_t v = wait_nonzero(pf + 24 + b, wait_limit);
-                    if (v == 0) give_up();                        // (never seen: the general way then runs into its own waits)
+                    all_seen = all_seen && v != 0;
                     all_zero = all_zero && v == 2u;
                 }
-                word = all_zero ? 0 : 1;
+                if (!all_seen) give_up();
+                word = !all_seen ? 2 : all_zero ? 0 : 1;
                 // (for tests and measurement: which way pairs took, in two bits of the status word that report no failure)
-                if (y == 1) __hip_atomic_fetch_or(status, all_zero ? 256u : 512u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (y == 1 && all_seen) __hip_atomic_fetch_or(status, all_zero ? 256u : 512u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             __syncthreads();
-            general = uni(word) != 0;                            // (the same in every lane: branches and addresses stay scalar)
+            way = uni(word);                                     // (the same in every lane: branches and addresses stay scalar)
             __syncthreads();
-            if (!general) break;
+            if (way != 1) break;
         }
-        if (!general) {
+        if (way == 2) {
+            // Neither way can be taken.  Whatever this workgroup would have scanned on either is written as NaN (a
+            // workgroup of the pair that did read the verdicts may write the true values over some of it: the
+            // failure is in the status word, and no output keeps what the caller's buffer held before).
+            if (!is_t) return;
+            const int other = (p == 0) ? parts - 1 : p;
+            fill_nan<kOutBf16>(o, tok_base, len, H, h, (cbase + clip(begin_of(p + 1))) * kChunk, (cbase + clip(end_of(p + 1))) * kChunk);
+            fill_nan<kOutBf16>(o, tok_base, len, H, h, (cbase + clip(begin_of(other))) * kChunk, (cbase + clip(end_of(other))) * kChunk);
+            if ((p + 1 == parts - 1 || other == parts - 1) && state_final != nullptr)
+                for (int i = threadIdx.x; i < D * D; i += 256) state_final[pair_base + i] = __builtin_nanf("");
+            return;
+        } else if (way == 0) {
             if (!is_t) return;
             // the short way: range p + 1 starts from the offset of the tail of range p
             if (threadIdx.x == 0) {

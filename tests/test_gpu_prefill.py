@@ -183,8 +183,9 @@ def test_bf16_wait_that_runs_out_poisons_the_outputs_and_is_reported():
     good_o, good_h = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], workspace=ws,
                                        check=True)
     good_o, good_h = good_o.clone(), good_h.clone()
-    for split in (1, 8):                                     # the plain scan, and (T long enough) the time-split one
-        xs = x if split == 1 else si.make_prefill(1, 64 * 40, 2, 128, 128, "bf16", -2.0, 62, 0.02)
+    # the plain scan, and (T long enough) the time-split one: ranges too short to try the short way, and ranges that try it
+    for split in (1, 8, 3):
+        xs = x if split == 1 else si.make_prefill(1, 64 * (40 if split == 8 else 60), 2, 128, 128, "bf16", -2.0, 62, 0.02)
         ds = to_device(xs)
         dims_s = kda.kda.make_chunk_dims(ds["q"], ds["v"])
         ws_s = torch.empty(kda.kda_chunk_fwd_workspace_size(dims_s), dtype=torch.uint8, device="cuda")
