@@ -165,20 +165,23 @@ def test_decode_output_gate(dtype, tol, d):
     assert eo <= tol and eS <= tol
 
 
-def test_prefill_output_gate_on_a_long_sequence_with_few_pairs():
+@pytest.mark.parametrize("mu,split", [(-6.0, 8), (-2.0, 3)])
+def test_prefill_output_gate_on_a_long_sequence_with_few_pairs(mu, split):
     """Few pairs and a long sequence: the time axis is cut into ranges walked side by side, and the passes that
-    write outputs apply the gate; against the oracle, and against the same call with the split switched off."""
+    write outputs apply the gate; against the oracle, and against the same call with the split switched off.
+    Slow decay in many short ranges (range states through the fold), and fast decay in three ranges that start
+    from the tails of the ranges before them."""
     import paper_2510_26692_amd as kda
     H, d, T = 2, 128, 64 * 60 - 11
     og, w = _out_gate((1, T, H, d), "bf16", 91)
-    x = si.make_tokens(1, T, H, d, d, "bf16", -6.0, 93)
+    x = si.make_tokens(1, T, H, d, d, "bf16", mu, 93)
     names = ("q", "k", "v", "log_alpha", "beta")
     o_plain, h_ref = oracle.kda_forward(*_np(x, *names), scale=0.5)
     o_ref = oracle.epilogue.apply(o_plain, si.to_np32(og), w.numpy(), 1e-5)
     g = {k_: v_.cuda() for k_, v_ in x.items() if isinstance(v_, torch.Tensor)}
     outs, parts = [], []
     try:
-        for mode in (8, 0):
+        for mode in (split, 0):
             kda.kda_debug_set_time_split(mode)
             dims = kda.kda.make_chunk_dims(g["q"], g["v"], None, 0.5, 0)
             parts.append(kda.kda_debug_chunk_fwd_plan(dims, 1 << 40, True)[2])
