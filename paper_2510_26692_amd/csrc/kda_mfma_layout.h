@@ -62,14 +62,27 @@ constexpr int frag_trs(int t, int r, int s) { return (t * 2 + r) * 2 + s; }   //
 constexpr int frag_aqk(int rr, int ri, int s) { return (rr + ri) * 2 + s; }   // (0,0) (1,0) (1,1)
 
 // Time-split scan: at most this many ranges per sequence, offered to calls with at most this many
-// (sequence, head) pairs whose longest sequence has at least kSplitMinChunks chunks.
-constexpr int kSplitMaxParts = 8;
+// (sequence, head) pairs whose longest sequence has at least kSplitMinChunks chunks.  The more pairs, the
+// fewer ranges: 2 ranges - 1 scan workgroups per pair must start side by side on half of a device's
+// workgroup slots (512 on MI355X).  split_parts_cap is that limit; it also sizes the state arrays in the
+// workspace, so it depends on the number of pairs and on the chunk indices of a time segment alone.
+constexpr int kSplitMaxParts = 32;
 constexpr int kSplitMaxPairs = 42;
 constexpr int kSplitMinChunks = 24;
+constexpr int split_parts_cap(long long pairs, long long chunks)
+{
+    long long p = pairs > 0 ? (256 / pairs + 1) / 2 : kSplitMaxParts;
+    if (p > chunks / 7 + 1) p = chunks / 7 + 1;               // (a range has at least 8 chunks)
+    return p > kSplitMaxParts ? kSplitMaxParts : p < 3 ? 3 : (int)p;
+}
+static_assert(split_parts_cap(1, 1 << 20) == 32 && split_parts_cap(4, 1 << 20) == 32 && split_parts_cap(8, 1 << 20) == 16 &&
+              split_parts_cap(16, 1 << 20) == 8 && split_parts_cap(32, 1 << 20) == 4 && split_parts_cap(42, 1 << 20) == 3 &&
+              split_parts_cap(2, 64) == 10, "ranges offered by number of pairs and chunks");
 constexpr int kSplitTail = 32;               // chunks at a range's end over which its transition is expected to vanish
 constexpr int kSplitMinTail = 16;            // ranges shorter than this do not try
-constexpr size_t kSplitFlagBytes = 8192;     // 32 u32 words per pair, ahead of the states
-static_assert((size_t)kSplitMaxPairs * 32 * 4 <= kSplitFlagBytes, "every pair's words must fit the area");
+constexpr int kSplitFlagsPerPair = 4 * kSplitMaxParts;      // u32 words per pair, ahead of the states
+constexpr size_t kSplitFlagBytes = (size_t)kSplitMaxPairs * kSplitFlagsPerPair * 4;
+static_assert(kSplitFlagBytes % 1024 == 0, "the area is cleared in blocks of 256 words and keeps what follows aligned");
 
 // Geometry of one launch pair: `seg_chunks` chunk indices of every sequence.
 struct SegPlan {
@@ -80,7 +93,7 @@ struct SegPlan {
     size_t flags_offset;     // one u32 "slot ready" flag per (sequence, head, chunk of the segment)
     size_t status_offset;    // u32 set by kda_scan when a bounded wait for a flag ran out
     size_t gate_offset;      // staged gate logits, kGateSlotBytes per slot (0: no output gate)
-    size_t split_offset;     // time-split scan: kSplitFlagBytes of counters, then E, T, B, each [kSplitMaxParts][pairs][128][128] fp32
+    size_t split_offset;     // time-split scan: kSplitFlagBytes of counters, then E, T, B, each [split_parts_cap(pairs, seg_chunks)][pairs][128][128] fp32
     size_t total_bytes;
 };
 

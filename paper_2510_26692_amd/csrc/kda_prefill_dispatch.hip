@@ -52,7 +52,7 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
     p.split_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
     // counters and states of the time-split scan, when the call qualifies for it
     const bool split = streams <= (size_t)kSplitMaxPairs && sc >= kSplitMinChunks;
-    p.total_bytes = p.split_offset + (split ? kSplitFlagBytes + 3 * (size_t)kSplitMaxParts * carry : 0);
+    p.total_bytes = p.split_offset + (split ? kSplitFlagBytes + 3 * (size_t)split_parts_cap((long long)streams, sc) * carry : 0);
     p.gate_offset = 0;
     if (gate) {
         p.gate_offset = round_up(p.total_bytes, 256);
@@ -88,7 +88,7 @@ struct SplitCut {
 // when the scan, not the per-chunk stage, sets the pace of the first phase; a chunk of the per-chunk
 // stage 17 on one slot of a device that is not full, the fold and the extra start-up 60 + 12 per
 // middle range.
-// forced = 3..8: the largest admissible number up to `forced`, whatever the estimate says.
+// forced = 3..32: the largest admissible number up to `forced`, whatever the estimate says.
 static SplitCut split_cut(const SegPlan &plan, const kda_dims *d, int cus, int forced)
 {
     SplitCut cut = {1, 0, 0, 0};
@@ -101,7 +101,7 @@ static SplitCut split_cut(const SegPlan &plan, const kda_dims *d, int cus, int f
     const double items = (double)pairs * (double)maxc;
     const double t_scan = (double)maxc * step, t_intra1 = items * item / (double)(slots - pairs);
     double best = t_scan > t_intra1 ? t_scan : t_intra1, ratio = 1.0;
-    for (int p = 3; p <= kSplitMaxParts; ++p) {
+    for (int p = 3; p <= split_parts_cap(pairs, plan.seg_chunks); ++p) {
         const int64_t len = (maxc + p - 1) / p;
         if (pairs * (2 * p - 1) * 2 > slots || pairs * p * 8 > slots * 3 || len < 8) continue;
         const bool try_short = len >= kSplitMinTail;
@@ -273,8 +273,8 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         a.split.parts = parts; a.split.part_len = cut.part_len; a.split.part0_len = cut.part0_len; a.split.tail = cut.tail;
         a.split.flags = reinterpret_cast<uint32_t *>(base + plan.split_offset);
         a.split.E = reinterpret_cast<float *>(base + plan.split_offset + kSplitFlagBytes);
-        a.split.Tm = a.split.E + kSplitMaxParts * pair_states;
-        a.split.Bm = a.split.Tm + kSplitMaxParts * pair_states;
+        a.split.Tm = a.split.E + split_parts_cap((long long)streams, plan.seg_chunks) * pair_states;
+        a.split.Bm = a.split.Tm + split_parts_cap((long long)streams, plan.seg_chunks) * pair_states;
         L.raw = pro != nullptr; L.scalar_gate = scalar_gate; L.out_bf16 = out_bf16; L.gate = epi != nullptr;
         if (epi) {
             a.out_gate = static_cast<const uint16_t *>(epi->gate); a.gate_ws = base + plan.gate_offset;

@@ -15,8 +15,8 @@ constexpr int kItemsPerWorkgroup = 4;
 
 // Time-split scan (kda_scan4_split.h): workspace areas and the cut of the chunk axis.
 struct SplitArgs {
-    float *E, *Tm, *Bm;          // [kSplitMaxParts][pairs][128][128] fp32 each
-    uint32_t *flags;             // 32 words per pair
+    float *E, *Tm, *Bm;          // [split_parts_cap(pairs, seg_chunks)][pairs][128][128] fp32 each
+    uint32_t *flags;             // kSplitFlagsPerPair words per pair
     int64_t part_len, part0_len; // chunk indices of the first range and of every other one
     int64_t tail;                // chunks at the end of a range whose transition is tested for zero (<= both lengths)
     int parts;                   // 1: no time split

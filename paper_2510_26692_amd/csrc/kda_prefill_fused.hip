@@ -64,8 +64,14 @@ void kda_prefill_kernel(const FusedArgs a)
         const int nsw = 2 * a.split.parts - 1;
         const int64_t bid = blockIdx.x, nscan = a.pairs * nsw;
         if (bid < nscan) {
-            const int y = (int)(bid / a.pairs);
-            const int64_t pair = bid - (int64_t)y * a.pairs;
+            // The workgroups that stay for the length of a range (role 0 and the odd roles) come first, the ones that
+            // leave after a tail (the even roles from 2 on) behind them: workgroups are handed to the dies and their
+            // shader engines in turn, and role-major order would put all that stay on half of them when there are
+            // four or eight pairs (with four pairs, every odd role on dies 4..7).
+            const int64_t nstay = a.pairs * a.split.parts;
+            const int64_t g = (bid < nstay) ? bid / a.pairs : (bid - nstay) / a.pairs;
+            const int64_t pair = (bid < nstay) ? bid - g * a.pairs : bid - nstay - g * a.pairs;
+            const int y = (bid < nstay) ? (g == 0 ? 0 : (int)(2 * g - 1)) : (int)(2 * g + 2);
             const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
             int64_t tok_base, len;
             if (a.cu) { tok_base = a.cu[n]; len = (int64_t)a.cu[n + 1] - tok_base; }

@@ -28,8 +28,8 @@
 //
 // Results travel through the workspace (E, Tm, Bm: arrays of [pairs][128][128] fp32 states, one per
 // range) under per-pair words: pf[p] = slices of E[p] that are complete (E[0]: set to `workers` at
-// once), pf[8 + p] = T_p complete, pf[16 + p] = 1 when the tail's offset is in Bm[p], 2 when B_p is,
-// pf[24 + p] = V[p].  Every producer makes its stores visible with a device-scope release before it
+// once), pf[kPfT + p] = T_p complete, pf[kPfB + p] = 1 when the tail's offset is in Bm[p], 2 when B_p
+// is, pf[kPfV + p] = V[p].  Every producer makes its stores visible with a device-scope release before it
 // raises a word, every consumer follows its (bounded) wait with a device-scope acquire.  No first
 // pass waits for anything but its slots, all these workgroups sit at the front of the grid and take
 // well under half the device, so every wait ends.
@@ -41,8 +41,8 @@ namespace kda {
 namespace mfma {
 namespace scan4 {
 
-constexpr int kSplitFlagsPerPair = 32;
-static_assert((size_t)kSplitMaxPairs * kSplitFlagsPerPair * 4 <= kSplitFlagBytes, "every pair's words must fit the area");
+// per-pair words: four groups of kSplitMaxParts
+constexpr int kPfT = kSplitMaxParts, kPfB = 2 * kSplitMaxParts, kPfV = 3 * kSplitMaxParts;
 
 __device__ __forceinline__ int split_workers(int parts) { return (parts - 2 >= 4) ? 8 : (parts - 2 >= 2) ? 4 : 2; }
 
@@ -87,7 +87,7 @@ __device__ __forceinline__ bool fold_slices(float *sE, float *E, const float *Tm
     if (tid == 0) {
         bool ok = true;
         for (int p = 1; p <= parts - 2 && ok; ++p)
-            ok = wait_flag(pf + 8 + p, 1u, wait_limit) && wait_flag(pf + 16 + p, 2u, wait_limit);
+            ok = wait_flag(pf + kPfT + p, 1u, wait_limit) && wait_flag(pf + kPfB + p, 2u, wait_limit);
         ok_word = ok;
     }
     __syncthreads();
@@ -214,17 +214,17 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
             __syncthreads();
             if (pass == 1) {
                 if (threadIdx.x == 0)
-                    __hip_atomic_store(is_t ? pf + 8 + p : pf + 16 + p, is_t ? 1u : 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(is_t ? pf + kPfT + p : pf + kPfB + p, is_t ? 1u : 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
             if (threadIdx.x == 0) {
-                __hip_atomic_store(is_t ? pf + 24 + p : pf + 16 + p, is_t ? (vanished ? 2u : 1u) : 1u, __ATOMIC_RELAXED,
+                __hip_atomic_store(is_t ? pf + kPfV + p : pf + kPfB + p, is_t ? (vanished ? 2u : 1u) : 1u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
                 // The verdicts of all boundaries of the pair: they are written once, so all workgroups of the pair
                 // that get to read them take the same way; one that does not (a wait ran out) takes neither.
                 bool all_zero = true, all_seen = true;
                 for (int b = 0; b <= parts - 2; ++b) {
-                    const uint32_t v = wait_nonzero(pf + 24 + b, wait_limit);
+                    const uint32_t v = wait_nonzero(pf + kPfV + b, wait_limit);
                     all_seen = all_seen && v != 0;
                     all_zero = all_zero && v == 2u;
                 }
@@ -253,7 +253,7 @@ __device__ __forceinline__ void split_role(uint8_t *lds, const SplitArgs &sp, co
             if (!is_t) return;
             // the short way: range p + 1 starts from the offset of the tail of range p
             if (threadIdx.x == 0) {
-                const bool ok = wait_flag(pf + 16 + p, 1u, wait_limit);
+                const bool ok = wait_flag(pf + kPfB + p, 1u, wait_limit);
                 if (!ok) give_up();
                 word = ok;
             }

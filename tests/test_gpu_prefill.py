@@ -352,7 +352,7 @@ SHORT_WAY, GENERAL_WAY = 256, 512                           # bits of the status
 
 
 @pytest.mark.parametrize("case", ["three_ranges", "eight_ranges", "packed_ragged", "vanishing_transition",
-                                  "vanishing_short_ranges", "mixed_ways"])
+                                  "vanishing_short_ranges", "mixed_ways", "twenty_ranges_short", "twenty_ranges_general"])
 def test_bf16_time_split_scan(case):
     """Few (sequence, head) pairs and long sequences: the sequential kernel cuts the chunk axis into
     ranges that several workgroups walk side by side.  Where the transition of every range's last chunks
@@ -374,6 +374,10 @@ def test_bf16_time_split_scan(case):
     elif case == "vanishing_short_ranges":                    # five ranges of 20 chunks: the tail is the whole range
         x = si.make_prefill(1, 64 * 100 - 3, 3, 128, 128, "bf16", -2.0, 305, 0.05)
         mode, want = 5, SHORT_WAY
+    elif case.startswith("twenty_ranges"):                    # one pair, 400 chunks: the fold runs through 18 middle ranges
+        short = case.endswith("short")
+        x = si.make_prefill(1, 64 * 400 - 30, 1, 128, 128, "bf16", -2.0 if short else -6.0, 308, 0.05)
+        mode, want = 20, SHORT_WAY if short else GENERAL_WAY
     elif case == "mixed_ways":                                # one head forgets, the other does not
         x = si.make_prefill(1, 64 * 120 + 1, 2, 128, 128, "bf16", -2.0, 306, 0.05)
         slow = si.make_prefill(1, 64 * 120 + 1, 2, 128, 128, "bf16", -6.0, 307, 0.05)
@@ -486,7 +490,7 @@ def test_bf16_zero_tokens_returns_the_initial_state(with_h0):
 
 @pytest.mark.parametrize("mu,mode", [(-6.0, 8), (-2.0, 3)])
 def test_bf16_time_split_scan_inside_time_segments(mu, mode):
-    """A workspace of 45 % of the full size: the call walks the time axis in three segments, and the
+    """A workspace of about half the full size: the call walks the time axis in three segments, and the
     sequential kernel of each segment is split into ranges; states are carried from segment to
     segment (a segment's final state goes to the array its initial state is read from).  Slow decay takes
     the general way in every segment; with fast decay and three ranges the segments take the short way (a last
@@ -497,9 +501,12 @@ def test_bf16_time_split_scan_inside_time_segments(mu, mode):
     dd = {k_: (v_.cuda() if isinstance(v_, torch.Tensor) else v_) for k_, v_ in x.items()}
     dims = kda.kda.make_chunk_dims(dd["q"], dd["v"])
     full = kda.kda_chunk_fwd_workspace_size(dims)
-    ws = torch.empty(int(full * 0.45) // 256 * 256, dtype=torch.uint8, device="cuda")
     try:
         kda.kda_debug_set_time_split(mode)
+        # the largest workspace, in steps of 5 % of the full one, that makes the call take three segments
+        size = next(s_ for s_ in (int(full * f / 100) // 256 * 256 for f in range(95, 20, -5))
+                    if kda.kda_debug_chunk_fwd_plan(dims, s_)[1] == 3)
+        ws = torch.empty(size, dtype=torch.uint8, device="cuda")
         plan = kda.kda_debug_chunk_fwd_plan(dims, ws.numel())
         assert plan[1] == 3 and 3 <= plan[2] <= mode
         eo, eh = check_prefill(x, TOL_BF16, workspace=ws)
