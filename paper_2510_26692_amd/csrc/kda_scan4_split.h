@@ -24,7 +24,10 @@
 //   y = 2 p + 2    B_p of range p = 1 .. parts - 2 into Bm[p],
 //   y = 1 .. workers   then form E[p] = T_p E[p-1] + B_p for p = 1 .. parts - 2, each on its own slice of
 //                  the d_v columns (the columns do not interact).
-// which takes two ranges' time instead of one.
+// which takes two ranges' time instead of one.  With tail = 0 (ranges too short for a transition to vanish)
+// the tails are not tried and every pair goes this way at once.  A workgroup that cannot read the pair's verdicts
+// (a bounded wait ran out) takes neither way: it reports the failure and writes NaN over the outputs it would
+// have scanned on either.
 //
 // Results travel through the workspace (E, Tm, Bm: arrays of [pairs][128][128] fp32 states, one per
 // range) under per-pair words: pf[p] = slices of E[p] that are complete (E[0]: set to `workers` at
@@ -32,7 +35,7 @@
 // is, pf[kPfV + p] = V[p].  Every producer makes its stores visible with a device-scope release before it
 // raises a word, every consumer follows its (bounded) wait with a device-scope acquire.  No first
 // pass waits for anything but its slots, all these workgroups sit at the front of the grid and take
-// well under half the device, so every wait ends.
+// at most half the device, so every wait ends.
 #pragma once
 #include "kda_prefill_fused.h"
 #include "kda_scan4.h"
