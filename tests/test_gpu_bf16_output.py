@@ -42,20 +42,22 @@ def _prefill_both(x, **kw):
     return o16, h16, o32, h32
 
 
-@pytest.mark.parametrize("case", ["ragged", "packed", "time_split", "many_pairs"])
+@pytest.mark.parametrize("case", ["ragged", "packed", "time_split", "time_split_short_way", "many_pairs"])
 def test_prefill_bf16_output_is_the_rounded_fp32_output(case):
     import paper_2510_26692_amd as kda
     if case == "ragged":
         x = si.make_prefill(2, 200 + 37, 4, 128, 128, "bf16", -2.0, 401, 0.02)
     elif case == "packed":
         x = si.make_varlen([70, 0, 5, 129, 64, 300], 3, 128, 128, "bf16", -2.0, 402, 0.05)
-    elif case == "time_split":
+    elif case == "time_split":                               # slow decay, short ranges: range states through the fold
         x = si.make_prefill(1, 64 * 60 - 11, 2, 128, 128, "bf16", -6.0, 403, 0.05)
+    elif case == "time_split_short_way":                     # fast decay, three ranges that start from the tails before them
+        x = si.make_prefill(1, 64 * 60 - 11, 2, 128, 128, "bf16", -2.0, 405, 0.05)
     else:
         x = si.make_prefill(10, 150, 8, 128, 128, "bf16", -2.0, 404, 0.02)     # 80 pairs: more than one batch of the grid
     try:
-        if case == "time_split":
-            kda.kda_debug_set_time_split(8)                  # split for sure
+        if case.startswith("time_split"):
+            kda.kda_debug_set_time_split(8 if case == "time_split" else 3)   # split for sure
         o16, h16, o32, h32 = _prefill_both(x)
     finally:
         kda.kda_debug_set_time_split(1)

@@ -42,7 +42,7 @@ def _check(x, **kw):
     return o, hT, eo, eh
 
 
-@pytest.mark.parametrize("case", ["ragged", "packed", "strong_decay", "no_decay", "long_split"])
+@pytest.mark.parametrize("case", ["ragged", "packed", "strong_decay", "no_decay", "long_split", "long_split_short_way"])
 def test_prefill_scalar_gate(case):
     import paper_2510_26692_amd as kda
     if case == "ragged":
@@ -55,12 +55,14 @@ def test_prefill_scalar_gate(case):
     elif case == "no_decay":
         x = si.make_prefill(1, 257, 2, 128, 128, "bf16", -2.0, 904, 0.3)
         x["log_alpha"] = torch.zeros_like(x["log_alpha"])
-    else:
+    elif case == "long_split":                               # slow decay, short ranges: range states through the fold
         x = si.make_prefill(1, 64 * 60 - 11, 2, 128, 128, "bf16", -6.0, 905, 0.05)
+    else:                                                    # fast decay, three ranges that start from the tails before them
+        x = si.make_prefill(1, 64 * 60 - 11, 2, 128, 128, "bf16", -2.0, 906, 0.05)
     x = _scalar_problem(x)
     try:
-        if case == "long_split":
-            kda.kda_debug_set_time_split(8)
+        if case.startswith("long_split"):
+            kda.kda_debug_set_time_split(8 if case == "long_split" else 3)
         o, hT, eo, eh = _check(x)
         # the per-channel entry point on the repeated decay computes the same function
         dd = to_device(x)
