@@ -352,7 +352,8 @@ SHORT_WAY, GENERAL_WAY = 256, 512                           # bits of the status
 
 
 @pytest.mark.parametrize("case", ["three_ranges", "eight_ranges", "packed_ragged", "vanishing_transition",
-                                  "vanishing_short_ranges", "mixed_ways", "twenty_ranges_short", "twenty_ranges_general"])
+                                  "vanishing_short_ranges", "mixed_ways", "twenty_ranges_short", "twenty_ranges_general",
+                                  "forty_eight_pairs"])
 def test_bf16_time_split_scan(case):
     """Few (sequence, head) pairs and long sequences: the sequential kernel cuts the chunk axis into
     ranges that several workgroups walk side by side.  Where the transition of every range's last chunks
@@ -378,6 +379,9 @@ def test_bf16_time_split_scan(case):
         short = case.endswith("short")
         x = si.make_prefill(1, 64 * 400 - 30, 1, 128, 128, "bf16", -2.0 if short else -6.0, 308, 0.05)
         mode, want = 20, SHORT_WAY if short else GENERAL_WAY
+    elif case == "forty_eight_pairs":                         # the most pairs the split is offered to: three ranges
+        x = si.make_prefill(3, 64 * 60 - 7, 16, 128, 128, "bf16", -2.0, 309, 0.05)
+        mode, want = 3, SHORT_WAY
     elif case == "mixed_ways":                                # one head forgets, the other does not
         x = si.make_prefill(1, 64 * 120 + 1, 2, 128, 128, "bf16", -2.0, 306, 0.05)
         slow = si.make_prefill(1, 64 * 120 + 1, 2, 128, 128, "bf16", -6.0, 307, 0.05)
