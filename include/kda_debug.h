@@ -22,9 +22,9 @@ extern "C" {
  * fails that test forms T and B of whole ranges and chains the range states through them (the
  * general way: two ranges' time instead of one).
  * Results agree within rounding, not bit for bit.  With 1 the library estimates whether, and into
- * how many ranges, a call is worth splitting; a value of 3..32 takes that many ranges whatever the
+ * how many ranges, a call is worth splitting; a value of 2..32 takes that many ranges whatever the
  * estimate says (still lowered to what the device and the sequence length allow; calls with fewer
- * than 24 chunks or more than 48 pairs are never split).
+ * than 24 chunks or more than 64 pairs are never split).
  * KDA_PREFILL_TIME_SPLIT=0 in the environment sets the default to 0.
  */
 void kda_debug_set_time_split(int mode);

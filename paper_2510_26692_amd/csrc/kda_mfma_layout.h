@@ -67,16 +67,16 @@ constexpr int frag_aqk(int rr, int ri, int s) { return (rr + ri) * 2 + s; }   //
 // workgroup slots (512 on MI355X).  split_parts_cap is that limit; it also sizes the state arrays in the
 // workspace, so it depends on the number of pairs and on the chunk indices of a time segment alone.
 constexpr int kSplitMaxParts = 32;
-constexpr int kSplitMaxPairs = 48;
+constexpr int kSplitMaxPairs = 64;
 constexpr int kSplitMinChunks = 24;
 constexpr int split_parts_cap(long long pairs, long long chunks)
 {
     long long p = pairs > 0 ? (256 / pairs + 1) / 2 : kSplitMaxParts;
     if (p > chunks / 7 + 1) p = chunks / 7 + 1;               // (a range has at least 8 chunks)
-    return p > kSplitMaxParts ? kSplitMaxParts : p < 3 ? 3 : (int)p;
+    return p > kSplitMaxParts ? kSplitMaxParts : p < 2 ? 2 : (int)p;
 }
 static_assert(split_parts_cap(1, 1 << 20) == 32 && split_parts_cap(4, 1 << 20) == 32 && split_parts_cap(8, 1 << 20) == 16 &&
-              split_parts_cap(16, 1 << 20) == 8 && split_parts_cap(32, 1 << 20) == 4 && split_parts_cap(48, 1 << 20) == 3 &&
+              split_parts_cap(16, 1 << 20) == 8 && split_parts_cap(32, 1 << 20) == 4 && split_parts_cap(48, 1 << 20) == 3 && split_parts_cap(64, 1 << 20) == 2 &&
               split_parts_cap(2, 64) == 10, "ranges offered by number of pairs and chunks");
 constexpr int kSplitTail = 32;               // chunks at a range's end over which its transition is expected to vanish
 constexpr int kSplitMinTail = 16;            // ranges shorter than this do not try

@@ -74,7 +74,9 @@ struct SplitCut {
 // slots, so that the per-chunk stage, the larger half of the work, keeps the rest.  Among the
 // admissible numbers of ranges the one with the smallest estimated duration is taken, the plain scan
 // included.  The estimates are in microseconds, fitted to measurements on MI355X with both stages
-// sharing the compute units; a step of the scan takes 3.0.
+// sharing the compute units; a step of the scan takes 3.0.  (Two ranges are offered up to 64 pairs: what
+// they buy there is not a shorter chain but twice the scan workgroups, whose steps, not the per-chunk
+// stage, pace a long call of 64 pairs.)
 //   Ranges of at least kSplitMinTail chunks try the short way: the tails (half a range, within
 // kSplitMinTail .. kSplitTail chunks) are produced and walked first, then all ranges go side by side.
 // With all slots busy a chunk of the per-chunk stage costs 21.2 on one slot, and a scan workgroup,
@@ -88,7 +90,7 @@ struct SplitCut {
 // when the scan, not the per-chunk stage, sets the pace of the first phase; a chunk of the per-chunk
 // stage 17 on one slot of a device that is not full, the fold and the extra start-up 60 + 12 per
 // middle range.
-// forced = 3..32: the largest admissible number up to `forced`, whatever the estimate says.
+// forced = 2..32: the largest admissible number up to `forced`, whatever the estimate says.
 static SplitCut split_cut(const SegPlan &plan, const kda_dims *d, int cus, int forced)
 {
     SplitCut cut = {1, 0, 0, 0};
@@ -99,12 +101,17 @@ static SplitCut split_cut(const SegPlan &plan, const kda_dims *d, int cus, int f
     if (pairs > kSplitMaxPairs || maxc < kSplitMinChunks || pairs >= slots) return cut;
     const double step = 3.0, item = 17.0, item_full = 21.2;
     const double items = (double)pairs * (double)maxc;
+    // the plain scan: the chain of one pair, the per-chunk stage beside the scan workgroups, or what all scan
+    // workgroups together get done (with 64 of them on a busy device a step takes 3.6)
     const double t_scan = (double)maxc * step, t_intra1 = items * item / (double)(slots - pairs);
+    const double t_steps = items * (pairs >= 64 ? 3.6 : step) / (double)pairs;
     double best = t_scan > t_intra1 ? t_scan : t_intra1, ratio = 1.0;
-    for (int p = 3; p <= split_parts_cap(pairs, plan.seg_chunks); ++p) {
+    if (t_steps > best) best = t_steps;
+    for (int p = 2; p <= split_parts_cap(pairs, plan.seg_chunks); ++p) {
         const int64_t len = (maxc + p - 1) / p;
         if (pairs * (2 * p - 1) * 2 > slots || pairs * p * 8 > slots * 3 || len < 8) continue;
         const bool try_short = len >= kSplitMinTail;
+        if (p == 2 && !try_short) continue;                  // two ranges on the general way are the plain scan, later
         int64_t tail = 0;
         const double phase = (double)len * step;
         double t, r = 1.0;
@@ -124,7 +131,7 @@ static SplitCut split_cut(const SegPlan &plan, const kda_dims *d, int cus, int f
             t = (phase > fed ? phase : fed) + 60.0 + 12.0 * (p - 2) + phase;
             if (t_intra + 2 * step > t) t = t_intra + 2 * step;
         }
-        if (forced >= 3 ? p <= forced : t < best) { best = t; cut.parts = p; ratio = r; cut.tail = tail; }
+        if (forced >= 2 ? p <= forced : t < best) { best = t; cut.parts = p; ratio = r; cut.tail = tail; }
     }
     if (cut.parts > 1) {
         if (g_split_ratio > 0.0) ratio = g_split_ratio;
@@ -150,9 +157,12 @@ static SegPlan make_plan(const kda_dims *d, size_t workspace_bytes, bool full, b
         const size_t fixed = plan_with(d, 1, gate).total_bytes - per_chunk_index;
         const size_t avail = workspace_bytes > fixed ? workspace_bytes - fixed : 0;
         const int64_t fit = per_chunk_index ? (int64_t)(avail / per_chunk_index) : sc;
+        const int64_t most = sc;
         if (fit < sc) sc = fit;
         if (sc < 1) sc = 1;
-        while (sc > 1 && plan_with(d, sc, gate).total_bytes > workspace_bytes) --sc;   // rounding of the flag area, time-split area
+        // the estimate ignores the rounding of the flag area and the time-split area: settle on the exact sizes
+        while (sc > 1 && plan_with(d, sc, gate).total_bytes > workspace_bytes) --sc;
+        while (sc < most && plan_with(d, sc + 1, gate).total_bytes <= workspace_bytes) ++sc;
     }
     return plan_with(d, sc, gate);
 }

@@ -7,8 +7,10 @@ namespace mfma {
 
 // (sequence, head) pairs per batch of the grid: the scan workgroups of a batch wait for the per-chunk
 // workgroups behind them, and about two batches' worth of them are resident at a time, each on half a
-// compute unit.
-constexpr int kMaxBatchPairs = 64;
+// compute unit.  128 scan workgroups in flight is where an MI355X does best (64 cannot take the slots as fast
+// as the per-chunk role makes them, 256 leave that role too little of the device); a device with fewer compute
+// units gets batches of a quarter of its workgroup slots, so that two batches never take more than half.
+constexpr int kMaxBatchPairs = 128;
 
 // Chunks one workgroup of the per-chunk role works through (the fetch of each hides behind the one before).
 constexpr int kItemsPerWorkgroup = 4;
@@ -59,7 +61,7 @@ struct FusedLaunch {
     int compute_units;              // of the device the launch goes to
 };
 
-int fused_batch_pairs(int64_t pairs);
+int fused_batch_pairs(int64_t pairs, int compute_units);
 kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream);
 
 }  // namespace mfma

@@ -183,9 +183,12 @@ static bool reserve_fused_lds()
     return ok;
 }
 
-int fused_batch_pairs(int64_t pairs)
+int fused_batch_pairs(int64_t pairs, int compute_units)
 {
-    return (int)(pairs < kMaxBatchPairs ? pairs : kMaxBatchPairs);
+    int most = compute_units / 2;                             // a quarter of the two slots per compute unit
+    if (most > kMaxBatchPairs) most = kMaxBatchPairs;
+    if (most < 1) most = 1;
+    return (int)(pairs < most ? pairs : most);
 }
 
 kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
@@ -193,7 +196,7 @@ kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
     if (!reserve_fused_lds())
         return fail(KDA_ERR_LAUNCH, "cannot reserve %d bytes of LDS for the prefill kernel", scan4::kLds);
     FusedArgs a = L.args;
-    a.nb = fused_batch_pairs(a.pairs);
+    a.nb = fused_batch_pairs(a.pairs, L.compute_units);
     int64_t blocks;
     // chunks per workgroup of the per-chunk role, and the workgroups of that role expected to be resident
     // together: two per compute unit, less the scan workgroups beside them (two batches' worth, or all of them)

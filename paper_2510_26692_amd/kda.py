@@ -194,7 +194,7 @@ def kda_debug_mfma_probe(sink, workgroups, iters):
 
 
 def kda_debug_set_time_split(mode):
-    """0 = off, 1 = on (the library estimates whether and how far to split), 3..32 = that many ranges
+    """0 = off, 1 = on (the library estimates whether and how far to split), 2..32 = that many ranges
     (at most) whatever the estimate says."""
     load_library().kda_debug_set_time_split(int(mode))
 

@@ -353,7 +353,7 @@ SHORT_WAY, GENERAL_WAY = 256, 512                           # bits of the status
 
 @pytest.mark.parametrize("case", ["three_ranges", "eight_ranges", "packed_ragged", "vanishing_transition",
                                   "vanishing_short_ranges", "mixed_ways", "twenty_ranges_short", "twenty_ranges_general",
-                                  "forty_eight_pairs"])
+                                  "forty_eight_pairs", "sixty_four_pairs_two_ranges"])
 def test_bf16_time_split_scan(case):
     """Few (sequence, head) pairs and long sequences: the sequential kernel cuts the chunk axis into
     ranges that several workgroups walk side by side.  Where the transition of every range's last chunks
@@ -379,9 +379,12 @@ def test_bf16_time_split_scan(case):
         short = case.endswith("short")
         x = si.make_prefill(1, 64 * 400 - 30, 1, 128, 128, "bf16", -2.0 if short else -6.0, 308, 0.05)
         mode, want = 20, SHORT_WAY if short else GENERAL_WAY
-    elif case == "forty_eight_pairs":                         # the most pairs the split is offered to: three ranges
+    elif case == "forty_eight_pairs":                         # the most pairs that get three ranges
         x = si.make_prefill(3, 64 * 60 - 7, 16, 128, 128, "bf16", -2.0, 309, 0.05)
         mode, want = 3, SHORT_WAY
+    elif case == "sixty_four_pairs_two_ranges":               # the most pairs the split is offered to
+        x = si.make_prefill(4, 64 * 40 + 21, 16, 128, 128, "bf16", -2.0, 310, 0.05)
+        mode, want = 2, SHORT_WAY
     elif case == "mixed_ways":                                # one head forgets, the other does not
         x = si.make_prefill(1, 64 * 120 + 1, 2, 128, 128, "bf16", -2.0, 306, 0.05)
         slow = si.make_prefill(1, 64 * 120 + 1, 2, 128, 128, "bf16", -6.0, 307, 0.05)
@@ -414,6 +417,21 @@ def test_bf16_time_split_scan(case):
             assert status == want
     finally:
         kda.kda_debug_set_time_split(1)
+
+
+@pytest.mark.parametrize("B,T,H", [(6, 16384, 16), (10, 150, 8), (3, 64 * 60, 16), (1, 64 * 300, 5), (4, 4096, 16),
+                                   (7, 777, 3)])
+def test_bf16_workspace_of_the_advertised_size_is_one_time_segment(B, T, H):
+    """kda_chunk_fwd_workspace_size is the size at which a call needs no time segments: the plan for exactly that
+    many bytes must be a single segment, for pair counts whose flag area needs rounding and with or without the
+    area of the time-split scan (plans only, nothing is launched)."""
+    import paper_2510_26692_amd as kda
+    dims = kda.kda.KdaDims(batch=B, seqlen=T, heads=H, dk=128, dv=128, chunk=64, num_seqs=B, in_dtype=1, out_dtype=0,
+                           scale=1.0, max_seqlen=0)
+    full = kda.kda_chunk_fwd_workspace_size(dims)
+    plan = kda.kda_debug_chunk_fwd_plan(dims, full)
+    assert plan[0] == (T + 63) // 64 and plan[1] == 1, plan
+    assert kda.kda_debug_chunk_fwd_plan(dims, full - 256)[1] == 2
 
 
 def test_bf16_two_host_threads_on_their_own_streams():
