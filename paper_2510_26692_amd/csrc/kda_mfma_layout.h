@@ -78,6 +78,10 @@ constexpr int split_parts_cap(long long pairs, long long chunks)
 static_assert(split_parts_cap(1, 1 << 20) == 32 && split_parts_cap(4, 1 << 20) == 32 && split_parts_cap(8, 1 << 20) == 16 &&
               split_parts_cap(16, 1 << 20) == 8 && split_parts_cap(32, 1 << 20) == 4 && split_parts_cap(48, 1 << 20) == 3 && split_parts_cap(64, 1 << 20) == 2 &&
               split_parts_cap(2, 64) == 10, "ranges offered by number of pairs and chunks");
+// Packed calls with several batches of pairs and at most this many sequences take their sequences longest first
+// (kda_prefill_fused.hip); the order sits behind the status word.
+constexpr int kMaxOrderedSeqs = 256;
+constexpr size_t kStatusAreaBytes = 256 + (size_t)kMaxOrderedSeqs * 4;
 constexpr int kSplitTail = 32;               // chunks at a range's end over which its transition is expected to vanish
 constexpr int kSplitMinTail = 16;            // ranges shorter than this do not try
 constexpr int kSplitFlagsPerPair = 4 * kSplitMaxParts;      // u32 words per pair, ahead of the states

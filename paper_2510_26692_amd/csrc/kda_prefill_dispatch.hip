@@ -35,7 +35,7 @@ static int64_t max_chunks_per_seq(const kda_dims *d)
 
 static size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Workspace: [status word, 256 B][slots of one segment, pair by pair][state carry][ready flags, one per slot]
+// Workspace: [status word, 256 B; sequence order, 1 KiB][slots of one segment, pair by pair][state carry][ready flags, one per slot]
 // [time-split counters and states][staged gate logits]; the last two only when the call can use them.
 static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
 {
@@ -46,7 +46,7 @@ static SegPlan plan_with(const kda_dims *d, int64_t sc, bool gate)
     p.seg_chunks = sc;
     p.num_segments = (maxc + sc - 1) / sc;
     p.status_offset = 0;                                  // the same place whatever the segment size
-    p.slots_offset = 256;
+    p.slots_offset = kStatusAreaBytes;
     p.carry_offset = p.slots_offset + (size_t)sc * streams * kSlotBytes;
     p.flags_offset = p.carry_offset + carry;
     p.split_offset = round_up(p.flags_offset + (size_t)sc * streams * sizeof(uint32_t), 256);
@@ -280,6 +280,12 @@ kda_status chunk_mfma_dispatch(const kda_dims *d, const kda_prologue *pro, const
         a.launch_chunks = left < plan.seg_chunks ? left : plan.seg_chunks;
         a.wait_limit = g_wait_limit; a.H = d->heads; a.scale = d->scale; a.epoch = (uint32_t)(seg + 1);
         a.producers = g_producers; a.raw = raw;
+        // packed sequences in more than one batch of pairs: longest first
+        const bool ordered = cu != nullptr && parts == 1 && d->num_seqs > 1 && d->num_seqs <= kMaxOrderedSeqs &&
+                             streams > fused_batch_pairs(streams, cus);
+        a.order = ordered ? reinterpret_cast<const int32_t *>(base + 256) : nullptr;
+        L.order_out = (ordered && seg == 0) ? reinterpret_cast<int32_t *>(base + 256) : nullptr;
+        L.num_seqs = (int)d->num_seqs;
         a.split.parts = parts; a.split.part_len = cut.part_len; a.split.part0_len = cut.part0_len; a.split.tail = cut.tail;
         a.split.flags = reinterpret_cast<uint32_t *>(base + plan.split_offset);
         a.split.E = reinterpret_cast<float *>(base + plan.split_offset + kSplitFlagBytes);

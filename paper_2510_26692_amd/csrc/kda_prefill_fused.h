@@ -27,6 +27,7 @@ struct SplitArgs {
 struct FusedArgs {
     const uint16_t *q, *k, *v, *log_alpha, *beta;
     const int32_t *cu;              // cu_seqlens or NULL
+    const int32_t *order;           // packed calls in several batches: the sequences, longest first (NULL: as they come)
     const float *state_in;          // [N,H,dk,dv] or NULL (= zeros)
     float *state_out;               // [N,H,dk,dv] or NULL
     void *o;
@@ -57,6 +58,8 @@ struct FusedLaunch {
     bool raw, scalar_gate, out_bf16, gate;
     bool reset_flags;               // clear num_flags words at args.ready and the status word first
     int64_t num_flags;
+    int32_t *order_out;             // the first launch of such a call writes the order here (num_seqs entries), else NULL
+    int num_seqs;
     bool reset_split;               // clear the counters of the time-split scan first (segments after the first)
     int compute_units;              // of the device the launch goes to
 };

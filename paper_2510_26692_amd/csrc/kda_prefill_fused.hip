@@ -118,11 +118,16 @@ void kda_prefill_kernel(const FusedArgs a)
     const int64_t per_batch = a.nb + intra_workgroups(batch_items, a.per_wg, a.window);
     const int64_t bid = blockIdx.x;
     const int64_t b = bid / per_batch, r = bid - b * per_batch;
+    // A batch is a.nb consecutive places; place p is head p % H of the sequence a.order[p / H] (packed calls whose
+    // sequences are taken longest first: sequences of like length share a batch, and the batch the grid ends with
+    // has the short chains) or of sequence p / H.
     if (r < a.nb) {
         // ---- sequential role: one (sequence, head) ----
-        const int64_t pair = b * a.nb + r;
-        if (pair >= a.pairs) return;
-        const int n = (int)(pair / a.H), h = (int)(pair - (int64_t)n * a.H);
+        const int64_t place = b * a.nb + r;
+        if (place >= a.pairs) return;
+        const int64_t seq = place / a.H;
+        const int n = a.order ? a.order[seq] : (int)seq, h = (int)(place - seq * a.H);
+        const int64_t pair = (int64_t)n * a.H + h;
         int64_t tok_base, len;
         if (a.cu) { tok_base = a.cu[n]; len = (int64_t)a.cu[n + 1] - tok_base; }
         else      { tok_base = (int64_t)n * a.T; len = a.T; }
@@ -144,12 +149,27 @@ void kda_prefill_kernel(const FusedArgs a)
             const int64_t i = item_index(r - a.nb, t, a.per_wg, a.window);
             IntraItem it = {0, 0, -1};
             if (i >= batch_items) return it;
-            const int64_t cl = i / a.nb, pair = b * a.nb + (i - cl * a.nb);
-            if (pair >= a.pairs) return it;
-            it.n = (int)(pair / a.H); it.h = (int)(pair - (int64_t)it.n * a.H); it.cl = cl;
+            const int64_t cl = i / a.nb, place = b * a.nb + (i - cl * a.nb);
+            if (place >= a.pairs) return it;
+            const int64_t seq = place / a.H;
+            it.n = a.order ? a.order[seq] : (int)seq; it.h = (int)(place - seq * a.H); it.cl = cl;
             return it;
         });
     }
+}
+
+// order[rank] = n with the sequences ranked by length, longest first (equal lengths: by index): one workgroup of
+// kMaxOrderedSeqs threads, num_seqs <= kMaxOrderedSeqs.
+__global__ void kda_seq_order_kernel(const int32_t *cu, int num_seqs, int32_t *order)
+{
+    __shared__ int32_t len[kMaxOrderedSeqs];
+    const int n = threadIdx.x;
+    if (n < num_seqs) len[n] = cu[n + 1] - cu[n];
+    __syncthreads();
+    if (n >= num_seqs) return;
+    int rank = 0;
+    for (int m = 0; m < num_seqs; ++m) rank += (len[m] > len[n] || (len[m] == len[n] && m < n)) ? 1 : 0;
+    order[rank] = n;
 }
 
 __global__ void kda_fused_fill_kernel(uint32_t *p, int64_t n, uint32_t value, uint32_t *one_more)
@@ -223,6 +243,8 @@ kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
     if (L.reset_flags)
         hipLaunchKernelGGL(kda_fused_fill_kernel, dim3((unsigned)((L.num_flags + 255) / 256 + 1)), dim3(256), 0, stream,
                            a.ready, L.num_flags, 0u, a.status);
+    if (L.order_out)
+        hipLaunchKernelGGL(kda_seq_order_kernel, dim3(1), dim3(kMaxOrderedSeqs), 0, stream, a.cu, L.num_seqs, L.order_out);
     if (L.gate && L.scalar_gate)
         return fail(KDA_ERR_UNSUPPORTED, "the scalar-gate entry point has no output gate");
     auto kern = L.gate ? (L.raw ? (L.out_bf16 ? kda_prefill_kernel<true, false, true, true> : kda_prefill_kernel<true, false, false, true>)

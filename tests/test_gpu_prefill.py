@@ -105,6 +105,36 @@ def test_bf16_packed_with_empty_sequence():
     print("bf16 packed: err_o %.2e err_hT %.2e" % (eo, eh))
 
 
+def test_bf16_packed_in_several_batches_of_pairs_takes_the_longest_sequences_first():
+    """320 (sequence, head) pairs: more than one batch of the sequential role, so the library ranks the sequences by
+    length (ties, empty sequences and a one-token sequence among them) and lays the batches out longest first.
+    Results per sequence must not depend on that: against the oracle, and bit for bit against each sequence run
+    alone; also in two time segments."""
+    import paper_2510_26692_amd as kda
+    lens = [300, 0, 64, 700, 64, 1, 129, 500, 0, 257]
+    x = si.make_varlen(lens, 32, 128, 128, "bf16", -2.0, 11, 0.05)
+    eo, eh = check_prefill(x, TOL_BF16)
+    print("bf16 packed, three batches: err_o %.2e err_hT %.2e" % (eo, eh))
+    dd = to_device(x)
+    o, hT = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"], cu_seqlens=dd["cu_seqlens"],
+                              check=True)
+    dims = kda.kda.make_chunk_dims(dd["q"], dd["v"], dd["cu_seqlens"])
+    ws = torch.empty(int(kda.kda_chunk_fwd_workspace_size(dims) * 0.6) // 256 * 256, dtype=torch.uint8, device="cuda")
+    assert kda.kda_debug_chunk_fwd_plan(dims, ws.numel())[1] == 2
+    o_seg, h_seg = kda.kda_chunk_fwd(dd["q"], dd["k"], dd["v"], dd["log_alpha"], dd["beta"], h0=dd["h0"],
+                                     cu_seqlens=dd["cu_seqlens"], workspace=ws, check=True)
+    assert torch.equal(o_seg, o) and torch.equal(h_seg, hT)
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    for n, ln in enumerate(lens):
+        if ln == 0:
+            continue
+        sl = slice(int(cu[n]), int(cu[n + 1]))
+        o1, h1 = kda.kda_chunk_fwd(dd["q"][:, sl].contiguous(), dd["k"][:, sl].contiguous(), dd["v"][:, sl].contiguous(),
+                                   dd["log_alpha"][:, sl].contiguous(), dd["beta"][:, sl].contiguous(),
+                                   h0=dd["h0"][n:n + 1].contiguous(), check=True)
+        assert torch.equal(o1, o[:, sl]) and torch.equal(h1[0], hT[n]), n
+
+
 def test_bf16_strong_decay_takes_the_exact_subchunk_path():
     """Gates far stronger than the fast operands allow (sub-chunk decay below 2^-11 on
     most channels, log alpha down to about -20 per token)."""
