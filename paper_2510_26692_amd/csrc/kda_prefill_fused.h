@@ -58,7 +58,7 @@ struct FusedLaunch {
     bool raw, scalar_gate, out_bf16, gate;
     bool reset_flags;               // clear num_flags words at args.ready and the status word first
     int64_t num_flags;
-    int32_t *order_out;             // the first launch of such a call writes the order here (num_seqs entries), else NULL
+    int32_t *order_out;             // the first launch of such a call (the one that resets the flags) writes the order here, else NULL
     int num_seqs;
     bool reset_split;               // clear the counters of the time-split scan first (segments after the first)
     int compute_units;              // of the device the launch goes to

@@ -27,6 +27,7 @@ namespace kda {
 namespace mfma {
 
 static_assert(kIntraLds <= scan4::kLds, "both roles run in the LDS of the larger one");
+static_assert(kMaxOrderedSeqs == 256, "the fill kernel ranks one sequence per thread of its first workgroup");
 
 // The per-chunk role works through its items (chunk, sequence, head) in the order the scan role wants them,
 // per_wg items per workgroup.  `window` consecutive workgroups share a run of window * per_wg items and
@@ -158,25 +159,24 @@ void kda_prefill_kernel(const FusedArgs a)
     }
 }
 
-// order[rank] = n with the sequences ranked by length, longest first (equal lengths: by index): one workgroup of
-// kMaxOrderedSeqs threads, num_seqs <= kMaxOrderedSeqs.
-__global__ void kda_seq_order_kernel(const int32_t *cu, int num_seqs, int32_t *order)
-{
-    __shared__ int32_t len[kMaxOrderedSeqs];
-    const int n = threadIdx.x;
-    if (n < num_seqs) len[n] = cu[n + 1] - cu[n];
-    __syncthreads();
-    if (n >= num_seqs) return;
-    int rank = 0;
-    for (int m = 0; m < num_seqs; ++m) rank += (len[m] > len[n] || (len[m] == len[n] && m < n)) ? 1 : 0;
-    order[rank] = n;
-}
-
-__global__ void kda_fused_fill_kernel(uint32_t *p, int64_t n, uint32_t value, uint32_t *one_more)
+// Clears n words at p and the word at one_more.  Its first workgroup also ranks the sequences of a packed call by
+// length when `order` is given: order[rank] = n, longest first (equal lengths: by index), num_seqs <= kMaxOrderedSeqs
+// = the 256 threads of the workgroup.
+__global__ void kda_fused_fill_kernel(uint32_t *p, int64_t n, uint32_t value, uint32_t *one_more, const int32_t *cu,
+                                      int num_seqs, int32_t *order)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = value;
     if (i == 0) *one_more = value;
+    if (order == nullptr || blockIdx.x != 0) return;
+    __shared__ int32_t len[kMaxOrderedSeqs];
+    const int s = threadIdx.x;
+    if (s < num_seqs) len[s] = cu[s + 1] - cu[s];
+    __syncthreads();
+    if (s >= num_seqs) return;
+    int rank = 0;
+    for (int m = 0; m < num_seqs; ++m) rank += (len[m] > len[s] || (len[m] == len[s] && m < s)) ? 1 : 0;
+    order[rank] = s;
 }
 
 template <bool kRaw, bool kScalar, bool kOutBf16, bool kGate = false>
@@ -238,13 +238,11 @@ kda_status launch_prefill_fused(const FusedLaunch &L, hipStream_t stream)
                     (long long)blocks);
     if (L.reset_split)
         hipLaunchKernelGGL(kda_fused_fill_kernel, dim3((unsigned)(kSplitFlagBytes / 4 / 256)), dim3(256), 0, stream,
-                           a.split.flags, (int64_t)(kSplitFlagBytes / 4), 0u, a.split.flags);
+                           a.split.flags, (int64_t)(kSplitFlagBytes / 4), 0u, a.split.flags, nullptr, 0, nullptr);
     // the slot flags and the status word start every call at zero (a kernel, not a memset: the call may be captured)
     if (L.reset_flags)
         hipLaunchKernelGGL(kda_fused_fill_kernel, dim3((unsigned)((L.num_flags + 255) / 256 + 1)), dim3(256), 0, stream,
-                           a.ready, L.num_flags, 0u, a.status);
-    if (L.order_out)
-        hipLaunchKernelGGL(kda_seq_order_kernel, dim3(1), dim3(kMaxOrderedSeqs), 0, stream, a.cu, L.num_seqs, L.order_out);
+                           a.ready, L.num_flags, 0u, a.status, a.cu, L.num_seqs, L.order_out);
     if (L.gate && L.scalar_gate)
         return fail(KDA_ERR_UNSUPPORTED, "the scalar-gate entry point has no output gate");
     auto kern = L.gate ? (L.raw ? (L.out_bf16 ? kda_prefill_kernel<true, false, true, true> : kda_prefill_kernel<true, false, false, true>)
